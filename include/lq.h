@@ -1,0 +1,197 @@
+/*
+ * lq - star-schema joins as foreign-key indicator products, fused with model
+ * prediction, and relational aggregates as linear algebra, for AMD gfx950.
+ *
+ * The calls follow "Accelerating Machine Learning Queries with Linear Algebra
+ * Query Processing" (SSDBM 2023).  Notation (Table 1 of the paper): n fact
+ * rows (the paper's i), K dimension tables, D_k of r_k rows and c_k columns,
+ * c_f feature columns owned by the fact table, k = c_f + sum c_k the joined
+ * width, L (here W[0]) the first linear operator of the model with l outputs,
+ * I_k in {0,1}^(n x r_k) the row-mapping matrix of dimension k.
+ *
+ * Conventions shared by every call
+ *   - Every `data` / array pointer is a DEVICE pointer unless the comment says
+ *     host.  Descriptor structs and the small pointer arrays inside them live
+ *     on the host.  All matrices are row-major with leading dimension `ld` in
+ *     elements (ld >= cols).
+ *   - I_k is never stored as a matrix: because a fact row matches exactly one
+ *     row of each dimension (Section 2.3.3: one 1 per materialised row),
+ *     I_k is the int32 column fks[k][i] in [0, r_k), already mapped from key
+ *     values to 0-based dimension row numbers.
+ *   - The library owns no memory.  Inputs are read-only, outputs and
+ *     workspaces are caller-allocated, and nothing is kept between calls.
+ *   - Calls validate on the host, enqueue kernels on `hip_stream` (a
+ *     hipStream_t passed as void*, NULL = the default stream) and return
+ *     without waiting; outputs are valid once the stream has been
+ *     synchronised.  Calls on one stream run in order.
+ *   - Return value: LQ_OK or an lq_status; on an error nothing has been
+ *     enqueued and lq_last_error() (thread-local, host) describes it.  No C++
+ *     exception crosses this boundary.
+ *   - With LQ_CHECK_FKS a call first verifies on the device that every foreign
+ *     key is in range, waits for that check, and returns LQ_ERR_FK_RANGE
+ *     without touching the outputs if one is not.  Without the flag, keys are
+ *     trusted (referential integrity of the star schema, Section 3.1) and an
+ *     out-of-range key is undefined behaviour.
+ */
+#ifndef LQ_H_
+#define LQ_H_
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef enum {
+  LQ_OK = 0,
+  LQ_ERR_NULL = 1,        /* a required pointer is NULL */
+  LQ_ERR_SHAPE = 2,       /* sizes do not fit together */
+  LQ_ERR_DTYPE = 3,       /* unsupported element type or mix of types */
+  LQ_ERR_WORKSPACE = 4,   /* workspace missing, misaligned or too small */
+  LQ_ERR_FK_RANGE = 5,    /* LQ_CHECK_FKS found a key outside its table */
+  LQ_ERR_UNSUPPORTED = 6, /* valid request this build cannot run */
+  LQ_ERR_HIP = 7          /* the HIP runtime reported an error */
+} lq_status;
+
+typedef enum { LQ_F32 = 0, LQ_BF16 = 1 } lq_dtype;
+
+/* flags */
+#define LQ_CHECK_FKS 1u
+/* Testing aid for lq_fused_join_predict: run the shape-agnostic kernel even where a
+ * specialised one exists, so that the two can be compared. */
+#define LQ_FORCE_GENERIC 0x100u
+
+/* which_call values of lq_workspace_bytes */
+#define LQ_CALL_FUSED 1
+#define LQ_CALL_MATERIALIZED 2
+
+#define LQ_MAX_DIMS 8
+#define LQ_MAX_LAYERS 8
+#define LQ_MAX_MEASURES 4
+
+/* A row-major matrix on the device. */
+typedef struct {
+  void*   data;   /* device; may be NULL only when rows*cols == 0 */
+  int64_t rows;
+  int32_t cols;
+  int64_t ld;     /* elements between consecutive rows, >= cols */
+  int32_t dtype;  /* lq_dtype */
+} lq_mat;
+
+/* The star schema after key mapping (Section 3.1: fact table A, dimensions B, C, D). */
+typedef struct {
+  int64_t               n_fact; /* n */
+  lq_mat                fact;   /* X_f [n x c_f]; cols == 0 allowed (data ignored) */
+  int32_t               n_dims; /* K in 0..LQ_MAX_DIMS */
+  const lq_mat*         dims;   /* host array of K descriptors, D_k [r_k x c_k] */
+  const int32_t* const* fks;    /* host array of K device pointers, fks[k] has n int32 */
+} lq_star;
+
+/*
+ * The model: a linear operator (n_layers == 1) or a ReLU MLP.
+ * W[0] is [(c_f + sum c_k) x l_1]; its rows are ordered like the columns of the
+ * joined table T: fact columns first, then dimension 0, 1, ... (the column
+ * mapping matrices M_k of Section 2.1 place D_k's columns side by side, so
+ * M_k L is simply a block of c_k consecutive rows of L).
+ * W[j] is [l_j x l_(j+1)].  ReLU follows every layer but the last.
+ * bias[j] is NULL or l_(j+1) elements of W[j]'s dtype, added once after the sum.
+ * All of fact, dims and W share one dtype (f32 or bf16).
+ */
+typedef struct {
+  int32_t            n_layers; /* 1..LQ_MAX_LAYERS */
+  const lq_mat*      W;        /* host array of n_layers descriptors */
+  const void* const* bias;     /* host array of n_layers device pointers, or NULL */
+} lq_model;
+
+/*
+ * Pre-fusion stage (the underlined terms of Eq. 1): P_k = D_k M_k L, i.e.
+ * D_k times rows [c_f + c_0 + .. + c_(k-1), +c_k) of W[0], accumulated in fp32.
+ *   P  host array of K descriptors; P[k] must be preallocated [r_k x l_1] with
+ *      dtype f32 (any model dtype) or bf16 (bf16 models only; rounded once to
+ *      nearest-even on store).
+ * Needs no workspace.  Run it again whenever a dimension table or W[0] changes.
+ */
+int lq_project_dims(const lq_star* star, const lq_model* model, lq_mat* P, void* hip_stream);
+
+/*
+ * Join-computation stage (last line of Eq. 1) with the rest of the model fused in:
+ *   z_i = x_i W[0][0:c_f, :] + sum_k P_k[fks[k][i], :] + bias[0]
+ *   y_i = z_i for a linear operator; otherwise ReLU and the remaining layers are
+ *   applied to z_i in registers/LDS (a non-linearity that follows a reduction
+ *   cannot be pushed below the sum - the argument Section 3.3.2 makes for the
+ *   tree's final comparison).  The joined table is never formed.
+ *   P   as produced by lq_project_dims (f32 or bf16)
+ *   Y   [n x l_out], dtype f32 or bf16 (bf16 only for bf16 models), overwritten
+ *   ws  workspace of lq_workspace_bytes(LQ_CALL_FUSED, ..) bytes, 256-byte
+ *       aligned; only used with LQ_CHECK_FKS (may be NULL otherwise)
+ * star->dims may be NULL here: only n_dims, fks and the row counts in P are used.
+ */
+int lq_fused_join_predict(const lq_star* star, const lq_model* model, const lq_mat* P,
+                          lq_mat* Y, void* ws, size_t ws_bytes, uint32_t flags,
+                          void* hip_stream);
+
+/*
+ * The non-fused pipeline the paper compares against (first two lines of Eq. 1):
+ * T = X_f M_f + sum_k I_k D_k M_k is written to memory chunk by chunk, then the
+ * model is applied to T by dense matrix products.
+ *   ws  holds the chunk of T ([chunk_rows x k], model dtype); ws_bytes decides
+ *       chunk_rows (lq_workspace_bytes(LQ_CALL_MATERIALIZED, .., chunk_rows)
+ *       gives the size for a wanted chunk; at least one 256-row chunk is needed).
+ */
+int lq_materialized_join_predict(const lq_star* star, const lq_model* model, lq_mat* Y,
+                                 void* ws, size_t ws_bytes, uint32_t flags, void* hip_stream);
+
+/*
+ * A filtered star join with GROUP BY and SUM as linear algebra (Sections 2.2-2.4):
+ *   s_i = fact_mask[i] * prod_k dim_mask[k][fks[k][i]]     (selection vectors pushed through I_k)
+ *   g_i = mixed-radix number of (dim_code[k][fks[k][i]] : k grouping), last grouping
+ *         dimension fastest                                 (group-mapping matrix of Section 2.4)
+ *   sums[m][g] = sum_i s_i [g_i == g] measures[m][i],  counts[g] = sum_i s_i [g_i == g]
+ * All integer, exact: int32 measures, int64 accumulation.
+ *   fks        host array of K device pointers; a key < 0 means "no match" and drops
+ *              the row (inner join, Section 2.3.2); keys >= dim_rows[k] are undefined
+ *              behaviour unless LQ_CHECK_FKS
+ *   dim_rows   host array of K row counts
+ *   dim_mask   host array of K device pointers (uint8 [r_k], 0 = filtered out) or NULL
+ *              entries / NULL array for "no predicate"
+ *   dim_code   host array of K device pointers (int32 [r_k] in [0, group_card[k])) or
+ *              NULL entries / NULL array for dimensions that do not group
+ *   group_card host array of K cardinalities (ignored where dim_code[k] is NULL);
+ *              G = product over grouping dimensions, G * (n_measures + 1) <= 8192
+ *   fact_mask  uint8 [n] or NULL
+ *   measures   host array of n_measures (1..LQ_MAX_MEASURES) device pointers, int32 [n]
+ *   sums       int64 [n_measures x G], overwritten;  counts int64 [G] or NULL
+ *   ws         lq_groupby_workspace_bytes(..) bytes, 256-byte aligned
+ * A code outside [0, group_card[k]) on a surviving row is undefined behaviour.
+ */
+int lq_masked_groupby_sum(int64_t n_fact, int32_t n_dims, const int32_t* const* fks,
+                          const int64_t* dim_rows, const uint8_t* const* dim_mask,
+                          const int32_t* const* dim_code, const int32_t* group_card,
+                          const uint8_t* fact_mask, int32_t n_measures,
+                          const int32_t* const* measures, int64_t* sums, int64_t* counts,
+                          void* ws, size_t ws_bytes, uint32_t flags, void* hip_stream);
+
+/* Workspace sizes in bytes (host-only computations, 0 on invalid arguments). */
+size_t lq_workspace_bytes(int which_call, const lq_star* star, const lq_model* model,
+                          int64_t chunk_rows);
+size_t lq_groupby_workspace_bytes(int32_t n_dims, const int64_t* dim_rows,
+                                  const int32_t* group_card, int32_t n_measures);
+
+/*
+ * Plain device-to-device copy of `bytes` bytes (16-byte aligned pointers, bytes a
+ * multiple of 16) by a grid-stride kernel.  Not part of the method: it is the
+ * yardstick the benchmarks use for "what a pure stream reaches on this GPU".
+ */
+int lq_stream_copy(void* dst, const void* src, size_t bytes, void* hip_stream);
+
+/* Description of the last error on this host thread ("" if none). */
+const char* lq_last_error(void);
+
+/* Library version string. */
+const char* lq_version(void);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* LQ_H_ */

@@ -1,0 +1,13 @@
+"""lq on MI355X: fused star-join + model prediction and linear-algebra group-by.
+
+All computation happens in the HIP library ``liblq.so`` (built in-tree by
+``paper_2306_08367_amd.build``); this package only marshals torch tensors
+into its C interface.  There is no fallback: without the library, importing
+``binding`` raises.
+"""
+from .binding import (  # noqa: F401
+    LQ_CHECK_FKS, LQ_FORCE_GENERIC, LQError, lib_path, lq_fused_join_predict,
+    lq_groupby_workspace_bytes, lq_last_error, lq_masked_groupby_sum,
+    lq_materialized_join_predict, lq_project_dims, lq_stream_copy, lq_version,
+    lq_workspace_bytes,
+)

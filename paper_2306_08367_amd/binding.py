@@ -1,0 +1,312 @@
+"""ctypes binding of liblq.so: same names as the C entry points, argument marshalling only.
+
+torch is used for device memory (inputs, outputs, workspaces) and for the current
+stream handle; every arithmetic step runs inside the library's kernels.
+"""
+from __future__ import annotations
+
+import ctypes
+import os
+from typing import List, Optional, Sequence
+
+import torch
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+_LIB_PATH = os.path.join(_HERE, "liblq.so")
+
+LQ_OK = 0
+LQ_CHECK_FKS = 1
+LQ_FORCE_GENERIC = 0x100
+LQ_CALL_FUSED = 1
+LQ_CALL_MATERIALIZED = 2
+LQ_F32, LQ_BF16 = 0, 1
+_STATUS = {1: "LQ_ERR_NULL", 2: "LQ_ERR_SHAPE", 3: "LQ_ERR_DTYPE", 4: "LQ_ERR_WORKSPACE",
+           5: "LQ_ERR_FK_RANGE", 6: "LQ_ERR_UNSUPPORTED", 7: "LQ_ERR_HIP"}
+
+
+class LQError(RuntimeError):
+    def __init__(self, code: int, msg: str):
+        super().__init__(f"{_STATUS.get(code, code)}: {msg}")
+        self.code = code
+        self.status = _STATUS.get(code, str(code))
+
+
+class lq_mat(ctypes.Structure):
+    _fields_ = [("data", ctypes.c_void_p), ("rows", ctypes.c_int64), ("cols", ctypes.c_int32),
+                ("ld", ctypes.c_int64), ("dtype", ctypes.c_int32)]
+
+
+class lq_star(ctypes.Structure):
+    _fields_ = [("n_fact", ctypes.c_int64), ("fact", lq_mat), ("n_dims", ctypes.c_int32),
+                ("dims", ctypes.POINTER(lq_mat)), ("fks", ctypes.POINTER(ctypes.c_void_p))]
+
+
+class lq_model(ctypes.Structure):
+    _fields_ = [("n_layers", ctypes.c_int32), ("W", ctypes.POINTER(lq_mat)),
+                ("bias", ctypes.POINTER(ctypes.c_void_p))]
+
+
+def lib_path() -> str:
+    return _LIB_PATH
+
+
+def _load():
+    if not os.path.exists(_LIB_PATH):
+        raise ImportError(
+            f"{_LIB_PATH} is missing: build it with `python -m paper_2306_08367_amd.build` "
+            "(there is no CPU or PyTorch fallback)")
+    lib = ctypes.CDLL(_LIB_PATH)
+    vp, i64, i32, u32, sz = ctypes.c_void_p, ctypes.c_int64, ctypes.c_int32, ctypes.c_uint32, ctypes.c_size_t
+    pm, ps, pmod = ctypes.POINTER(lq_mat), ctypes.POINTER(lq_star), ctypes.POINTER(lq_model)
+    lib.lq_project_dims.argtypes = [ps, pmod, pm, vp]
+    lib.lq_fused_join_predict.argtypes = [ps, pmod, pm, pm, vp, sz, u32, vp]
+    lib.lq_materialized_join_predict.argtypes = [ps, pmod, pm, vp, sz, u32, vp]
+    lib.lq_masked_groupby_sum.argtypes = [i64, i32, ctypes.POINTER(vp), ctypes.POINTER(i64),
+                                          ctypes.POINTER(vp), ctypes.POINTER(vp),
+                                          ctypes.POINTER(i32), vp, i32, ctypes.POINTER(vp), vp, vp,
+                                          vp, sz, u32, vp]
+    lib.lq_workspace_bytes.argtypes = [ctypes.c_int, ps, pmod, i64]
+    lib.lq_workspace_bytes.restype = sz
+    lib.lq_groupby_workspace_bytes.argtypes = [i32, ctypes.POINTER(i64), ctypes.POINTER(i32), i32]
+    lib.lq_groupby_workspace_bytes.restype = sz
+    lib.lq_stream_copy.argtypes = [vp, vp, sz, vp]
+    lib.lq_last_error.restype = ctypes.c_char_p
+    lib.lq_version.restype = ctypes.c_char_p
+    for f in ("lq_project_dims", "lq_fused_join_predict", "lq_materialized_join_predict",
+              "lq_masked_groupby_sum", "lq_stream_copy"):
+        getattr(lib, f).restype = ctypes.c_int
+    return lib
+
+
+_lib = _load()
+
+
+def lq_last_error() -> str:
+    return _lib.lq_last_error().decode()
+
+
+def lq_version() -> str:
+    return _lib.lq_version().decode()
+
+
+def _check(rc: int):
+    if rc != LQ_OK:
+        raise LQError(rc, lq_last_error())
+
+
+def _dtype_code(t: torch.Tensor) -> int:
+    if t.dtype == torch.float32:
+        return LQ_F32
+    if t.dtype == torch.bfloat16:
+        return LQ_BF16
+    raise TypeError(f"unsupported dtype {t.dtype} (float32 or bfloat16)")
+
+
+def _mat(t: Optional[torch.Tensor], rows: int = 0, cols: int = 0, dtype: int = LQ_F32) -> lq_mat:
+    if t is None:
+        return lq_mat(None, rows, cols, max(cols, 1), dtype)
+    if t.dim() != 2:
+        raise ValueError("matrices are 2-D tensors")
+    if t.shape[1] > 1 and t.stride(1) != 1:
+        raise ValueError("matrix columns must be contiguous (row-major)")
+    ld = t.stride(0) if t.shape[0] > 1 else max(int(t.shape[1]), 1)
+    if t.shape[0] > 1 and ld < t.shape[1]:
+        raise ValueError("row stride smaller than the row")
+    return lq_mat(t.data_ptr() if t.numel() else None, int(t.shape[0]), int(t.shape[1]), int(ld),
+                  _dtype_code(t))
+
+
+def _mat_array(ts: Sequence[torch.Tensor]):
+    arr = (lq_mat * max(1, len(ts)))()
+    for j, t in enumerate(ts):
+        arr[j] = _mat(t)
+    return arr
+
+
+def _ptr_array(ts: Sequence[Optional[torch.Tensor]]):
+    arr = (ctypes.c_void_p * max(1, len(ts)))()
+    for j, t in enumerate(ts):
+        arr[j] = None if t is None else t.data_ptr()
+    return arr
+
+
+def _stream(stream) -> Optional[int]:
+    if stream is None:
+        stream = torch.cuda.current_stream()
+    return int(stream.cuda_stream) or None
+
+
+def _expect(t: torch.Tensor, dtype, what: str):
+    if t.dtype != dtype:
+        raise TypeError(f"{what} must be {dtype}, got {t.dtype}")
+    if not t.is_cuda:
+        raise ValueError(f"{what} must live on the GPU")
+    if t.dim() == 1 and t.numel() > 1 and t.stride(0) != 1:
+        raise ValueError(f"{what} must be contiguous")
+
+
+class _Star:
+    """Keeps the ctypes arrays of a star schema alive for the duration of a call."""
+
+    def __init__(self, n: int, X, dims, fks, n_dims: Optional[int] = None):
+        self.keep = [X, dims, fks]
+        K = len(fks) if n_dims is None else n_dims
+        for f in fks:
+            _expect(f, torch.int32, "foreign-key column")
+        self.dims_arr = _mat_array(dims) if dims is not None else None
+        self.fks_arr = _ptr_array(fks)
+        fact = _mat(X) if X is not None else _mat(None, n, 0)
+        self.c = lq_star(n, fact, K,
+                         self.dims_arr if dims is not None else ctypes.POINTER(lq_mat)(),
+                         self.fks_arr)
+
+
+class _Model:
+    def __init__(self, weights, biases):
+        self.keep = [weights, biases]
+        self.W = _mat_array(weights)
+        self.b = _ptr_array(biases if biases is not None else [None] * len(weights))
+        self.c = lq_model(len(weights), self.W, self.b)
+
+
+def _n_of(X, fks) -> int:
+    if X is not None:
+        return int(X.shape[0])
+    if fks:
+        return int(fks[0].shape[0])
+    raise ValueError("need fact columns or at least one foreign-key column")
+
+
+def lq_project_dims(dims: Sequence[torch.Tensor], W0: torch.Tensor, c_f: int,
+                    P: Optional[List[torch.Tensor]] = None, p_dtype: Optional[torch.dtype] = None,
+                    stream=None) -> List[torch.Tensor]:
+    """P_k = D_k times its rows of W0 (pre-fusion stage).  Allocates P unless given."""
+    if P is None:
+        pd = p_dtype or torch.float32
+        P = [torch.empty((d.shape[0], W0.shape[1]), dtype=pd, device=d.device) for d in dims]
+    fact = lq_mat(None, 0, int(c_f), max(int(c_f), 1), _dtype_code(W0))
+    dims_arr = _mat_array(dims)
+    star = lq_star(0, fact, len(dims), dims_arr, _ptr_array([None] * len(dims)))
+    model = _Model([W0], None)
+    P_arr = _mat_array(P)
+    _check(_lib.lq_project_dims(ctypes.byref(star), ctypes.byref(model.c), P_arr, _stream(stream)))
+    return P
+
+
+def lq_fused_join_predict(X: Optional[torch.Tensor], fks: Sequence[torch.Tensor],
+                          P: Sequence[torch.Tensor], weights: Sequence[torch.Tensor],
+                          biases: Optional[Sequence[Optional[torch.Tensor]]] = None,
+                          Y: Optional[torch.Tensor] = None, y_dtype: Optional[torch.dtype] = None,
+                          flags: int = 0, ws: Optional[torch.Tensor] = None, stream=None) -> torch.Tensor:
+    """Y = MLP(x W_f + sum_k P_k[fk_k]) without forming the joined table."""
+    n = _n_of(X, fks)
+    dev = weights[0].device
+    if Y is None:
+        Y = torch.empty((n, weights[-1].shape[1]), dtype=y_dtype or weights[0].dtype, device=dev)
+    if ws is None and (flags & LQ_CHECK_FKS):
+        ws = torch.empty(256, dtype=torch.uint8, device=dev)
+    star = _Star(n, X, None, fks)
+    model = _Model(weights, biases)
+    P_arr = _mat_array(P)
+    Ym = _mat(Y)
+    _check(_lib.lq_fused_join_predict(ctypes.byref(star.c), ctypes.byref(model.c), P_arr,
+                                      ctypes.byref(Ym), None if ws is None else ws.data_ptr(),
+                                      0 if ws is None else ws.numel() * ws.element_size(),
+                                      flags, _stream(stream)))
+    return Y
+
+
+def lq_workspace_bytes(which_call: int, k: int, weights: Sequence[torch.Tensor], chunk_rows: int) -> int:
+    model = _Model(weights, None)
+    star = lq_star(0, lq_mat(None, 0, 0, 1, _dtype_code(weights[0])), 0, ctypes.POINTER(lq_mat)(),
+                   _ptr_array([]))
+    return int(_lib.lq_workspace_bytes(which_call, ctypes.byref(star), ctypes.byref(model.c), chunk_rows))
+
+
+def lq_materialized_join_predict(X: Optional[torch.Tensor], dims: Sequence[torch.Tensor],
+                                 fks: Sequence[torch.Tensor], weights: Sequence[torch.Tensor],
+                                 biases: Optional[Sequence[Optional[torch.Tensor]]] = None,
+                                 Y: Optional[torch.Tensor] = None, y_dtype: Optional[torch.dtype] = None,
+                                 ws: Optional[torch.Tensor] = None, chunk_rows: Optional[int] = None,
+                                 flags: int = 0, stream=None) -> torch.Tensor:
+    """The non-fused pipeline: write T chunk by chunk, then run the model on it layer by layer."""
+    n = _n_of(X, fks)
+    dev = weights[0].device
+    if Y is None:
+        Y = torch.empty((n, weights[-1].shape[1]), dtype=y_dtype or weights[0].dtype, device=dev)
+    if ws is None:
+        rows = chunk_rows or min(max(n, 256), 1 << 22)
+        nbytes = lq_workspace_bytes(LQ_CALL_MATERIALIZED, int(weights[0].shape[0]), weights, rows)
+        ws = torch.empty(nbytes, dtype=torch.uint8, device=dev)
+    star = _Star(n, X, dims, fks)
+    model = _Model(weights, biases)
+    Ym = _mat(Y)
+    _check(_lib.lq_materialized_join_predict(ctypes.byref(star.c), ctypes.byref(model.c),
+                                             ctypes.byref(Ym), ws.data_ptr(),
+                                             ws.numel() * ws.element_size(), flags, _stream(stream)))
+    return Y
+
+
+def lq_groupby_workspace_bytes(dim_rows: Sequence[int], group_card: Sequence[int], n_measures: int) -> int:
+    K = len(dim_rows)
+    rows = (ctypes.c_int64 * max(1, K))(*[int(r) for r in dim_rows])
+    card = (ctypes.c_int32 * max(1, K))(*[int(c) for c in group_card])
+    return int(_lib.lq_groupby_workspace_bytes(K, rows, card, n_measures))
+
+
+def lq_masked_groupby_sum(fks: Sequence[torch.Tensor], dim_rows: Sequence[int],
+                          dim_mask: Optional[Sequence[Optional[torch.Tensor]]],
+                          dim_code: Optional[Sequence[Optional[torch.Tensor]]],
+                          group_card: Sequence[int], fact_mask: Optional[torch.Tensor],
+                          measures: Sequence[torch.Tensor], sums: Optional[torch.Tensor] = None,
+                          counts: Optional[torch.Tensor] = None, want_counts: bool = True,
+                          ws: Optional[torch.Tensor] = None, flags: int = 0, stream=None):
+    """Filtered star join + GROUP BY + SUM/COUNT.  Returns (sums [M x G] int64, counts [G] int64 or None)."""
+    K = len(fks)
+    n = int(measures[0].shape[0])
+    dev = measures[0].device
+    for f in fks:
+        _expect(f, torch.int32, "foreign-key column")
+        if f.shape[0] != n:
+            raise ValueError("foreign-key column length differs from the measures")
+    for m in measures:
+        _expect(m, torch.int32, "measure column")
+    masks = list(dim_mask) if dim_mask is not None else [None] * K
+    codes = list(dim_code) if dim_code is not None else [None] * K
+    for k in range(K):
+        if masks[k] is not None:
+            _expect(masks[k], torch.uint8, "dimension mask")
+            if masks[k].shape[0] != dim_rows[k]:
+                raise ValueError("mask length differs from dim_rows")
+        if codes[k] is not None:
+            _expect(codes[k], torch.int32, "dimension group code")
+            if codes[k].shape[0] != dim_rows[k]:
+                raise ValueError("code length differs from dim_rows")
+    if fact_mask is not None:
+        _expect(fact_mask, torch.uint8, "fact mask")
+    G = 1
+    for k in range(K):
+        if codes[k] is not None:
+            G *= int(group_card[k])
+    if sums is None:
+        sums = torch.empty((len(measures), G), dtype=torch.int64, device=dev)
+    if counts is None and want_counts:
+        counts = torch.empty((G,), dtype=torch.int64, device=dev)
+    if ws is None:
+        ws = torch.empty(lq_groupby_workspace_bytes(dim_rows, group_card, len(measures)),
+                         dtype=torch.uint8, device=dev)
+    rows = (ctypes.c_int64 * max(1, K))(*[int(r) for r in dim_rows])
+    card = (ctypes.c_int32 * max(1, K))(*[int(c) for c in group_card])
+    _check(_lib.lq_masked_groupby_sum(
+        n, K, _ptr_array(fks), rows, _ptr_array(masks), _ptr_array(codes), card,
+        None if fact_mask is None else fact_mask.data_ptr(), len(measures), _ptr_array(measures),
+        sums.data_ptr(), None if counts is None else counts.data_ptr(), ws.data_ptr(),
+        ws.numel() * ws.element_size(), flags, _stream(stream)))
+    return sums, counts
+
+
+def lq_stream_copy(dst: torch.Tensor, src: torch.Tensor, stream=None) -> None:
+    nbytes = src.numel() * src.element_size()
+    if dst.numel() * dst.element_size() < nbytes:
+        raise ValueError("destination smaller than source")
+    _check(_lib.lq_stream_copy(dst.data_ptr(), src.data_ptr(), nbytes, _stream(stream)))

@@ -1,0 +1,309 @@
+// Join-computation stage with the model fused in (last line of Eq. 1):
+//   z_i = x_i W_f + sum_k P_k[fk_k[i], :] + b_1,  then ReLU / later layers.
+// The joined table is never formed; each fact row gathers one l_1-wide row from
+// every projected dimension table and adds them up.
+//
+// Two kernels live here:
+//   fused_vec_kernel      - the fast path.  A fact row is owned by a group of LPR
+//                           adjacent lanes, each holding VEC consecutive hidden
+//                           columns, so every gather is one 16-byte (or 4-byte)
+//                           load per lane and a row of P_k is read as one
+//                           contiguous run by its lane group.  W_f, b_1 and the
+//                           lane's slice of W_2 sit in registers.
+//   fused_generic_kernel  - any shape: a workgroup stages R rows of z in LDS and
+//                           walks the remaining layers there.
+#include "lq_common.h"
+
+namespace lq {
+namespace {
+
+// ------------------------------------------------------------------ generic ------------
+
+constexpr int GEN_THREADS = 256;
+
+__global__ __launch_bounds__(GEN_THREADS) void fused_generic_kernel(PredictArgs a, int R, int maxw) {
+  extern __shared__ float lds[];
+  float* cur = lds;
+  float* nxt = lds + static_cast<size_t>(R) * maxw;
+  const int tid = threadIdx.x;
+  const int l1 = a.wout[0];
+  const int64_t n_tiles = (a.n + R - 1) / R;
+  for (int64_t tile = blockIdx.x; tile < n_tiles; tile += gridDim.x) {
+    const int64_t base = tile * R;
+    const int rows = static_cast<int>(min(static_cast<int64_t>(R), a.n - base));
+    const bool last0 = a.n_layers == 1;
+    for (int idx = tid; idx < rows * l1; idx += GEN_THREADS) {
+      const int r = idx / l1, j = idx - r * l1;
+      const int64_t row = base + r;
+      float acc = 0.f;
+      for (int q = 0; q < a.c_f; ++q)
+        acc += load_as_f32(a.X, row * a.ldx + q, a.x_dtype) *
+               load_as_f32(a.W[0], static_cast<int64_t>(q) * a.ldw[0] + j, a.x_dtype);
+      for (int k = 0; k < a.K; ++k)
+        acc += load_as_f32(a.P[k], static_cast<int64_t>(a.fk[k][row]) * a.ldp[k] + j, a.p_dtype);
+      if (a.bias[0]) acc += load_as_f32(a.bias[0], j, a.x_dtype);
+      if (last0) store_from_f32(a.Y, row * a.ldy + j, a.y_dtype, acc);
+      else cur[r * maxw + j] = fmaxf(acc, 0.f);
+    }
+    for (int layer = 1; layer < a.n_layers; ++layer) {
+      __syncthreads();
+      const int win = a.win[layer], wout = a.wout[layer];
+      const bool last = layer == a.n_layers - 1;
+      for (int idx = tid; idx < rows * wout; idx += GEN_THREADS) {
+        const int r = idx / wout, o = idx - r * wout;
+        float acc = 0.f;
+        for (int q = 0; q < win; ++q)
+          acc += cur[r * maxw + q] *
+                 load_as_f32(a.W[layer], static_cast<int64_t>(q) * a.ldw[layer] + o, a.x_dtype);
+        if (a.bias[layer]) acc += load_as_f32(a.bias[layer], o, a.x_dtype);
+        if (last) store_from_f32(a.Y, (base + r) * a.ldy + o, a.y_dtype, acc);
+        else nxt[r * maxw + o] = fmaxf(acc, 0.f);
+      }
+      float* t = cur; cur = nxt; nxt = t;
+    }
+    __syncthreads();
+  }
+}
+
+int launch_generic(const PredictArgs& a, hipStream_t s) {
+  int maxw = 1;
+  for (int j = 0; j + 1 < a.n_layers; ++j) maxw = std::max(maxw, a.wout[j]);
+  int R = 16;
+  while (R > 1 && static_cast<size_t>(2) * R * maxw * sizeof(float) > 64 * 1024) R >>= 1;
+  const size_t lds = static_cast<size_t>(2) * R * maxw * sizeof(float);
+  if (lds > 64 * 1024)
+    return fail(LQ_ERR_UNSUPPORTED, "hidden width %d is too wide for the generic kernel", maxw);
+  const int64_t n_tiles = (a.n + R - 1) / R;
+  const int64_t blocks = std::min<int64_t>(n_tiles, static_cast<int64_t>(num_cus()) * 8);
+  if (blocks <= 0) return LQ_OK;
+  hipLaunchKernelGGL(fused_generic_kernel, dim3(static_cast<unsigned>(blocks)), dim3(GEN_THREADS),
+                     lds, s, a, R, maxw);
+  LQ_LAUNCH_CHECK("fused_generic_kernel");
+  return LQ_OK;
+}
+
+// ------------------------------------------------------------------ vectorised ----------
+
+// VEC consecutive elements of type T as one load.
+template <typename T, int VEC> struct Chunk;
+template <> struct Chunk<float, 4> {
+  static __device__ __forceinline__ void load(const float* p, float (&v)[4]) {
+    const float4 t = *reinterpret_cast<const float4*>(p);
+    v[0] = t.x; v[1] = t.y; v[2] = t.z; v[3] = t.w;
+  }
+  static __device__ __forceinline__ void store(float* p, const float (&v)[4]) {
+    *reinterpret_cast<float4*>(p) = make_float4(v[0], v[1], v[2], v[3]);
+  }
+};
+template <> struct Chunk<float, 1> {
+  static __device__ __forceinline__ void load(const float* p, float (&v)[1]) { v[0] = *p; }
+  static __device__ __forceinline__ void store(float* p, const float (&v)[1]) { *p = v[0]; }
+};
+template <> struct Chunk<bf16_t, 8> {
+  static __device__ __forceinline__ void load(const bf16_t* p, float (&v)[8]) {
+    const uint4 t = *reinterpret_cast<const uint4*>(p);
+    const uint32_t w[4] = {t.x, t.y, t.z, t.w};
+#pragma unroll
+    for (int q = 0; q < 4; ++q) {
+      v[2 * q] = __uint_as_float(w[q] << 16);
+      v[2 * q + 1] = __uint_as_float(w[q] & 0xffff0000u);
+    }
+  }
+  static __device__ __forceinline__ void store(bf16_t* p, const float (&v)[8]) {
+    uint32_t w[4];
+#pragma unroll
+    for (int q = 0; q < 4; ++q)
+      w[q] = static_cast<uint32_t>(f32_to_bf16(v[2 * q])) |
+             (static_cast<uint32_t>(f32_to_bf16(v[2 * q + 1])) << 16);
+    *reinterpret_cast<uint4*>(p) = make_uint4(w[0], w[1], w[2], w[3]);
+  }
+};
+template <> struct Chunk<bf16_t, 1> {
+  static __device__ __forceinline__ void load(const bf16_t* p, float (&v)[1]) { v[0] = bf16_to_f32(*p); }
+  static __device__ __forceinline__ void store(bf16_t* p, const float (&v)[1]) { *p = f32_to_bf16(v[0]); }
+};
+
+constexpr int VEC_THREADS = 256;
+
+// TX: dtype of X / W / bias, TP: dtype of P, TY: dtype of Y.
+// LPR lanes per fact row (power of two, <= 64), VEC hidden columns per lane: l_1 == LPR * VEC.
+// CF: compile-time c_f.  NL: 1 (linear) or 2 (ReLU then W_2 with L2 outputs).
+template <typename TX, typename TP, typename TY, int VEC, int LPR, int CF, int NL, int L2>
+__global__ __launch_bounds__(VEC_THREADS) void fused_vec_kernel(PredictArgs a) {
+  constexpr int RPW = 64 / LPR;                 // fact rows per wavefront pass
+  constexpr int RPB = RPW * (VEC_THREADS / 64); // per workgroup pass
+  const int tid = threadIdx.x;
+  const int sub = tid / LPR;                    // which row of the workgroup pass
+  const int c = tid % LPR;                      // which VEC-wide column slice
+  const int col0 = c * VEC;
+
+  const TX* __restrict__ X = static_cast<const TX*>(a.X);
+  const TX* __restrict__ W0 = static_cast<const TX*>(a.W[0]);
+
+  float wf[CF > 0 ? CF : 1][VEC];
+#pragma unroll
+  for (int q = 0; q < CF; ++q)
+#pragma unroll
+    for (int v = 0; v < VEC; ++v) wf[q][v] = Elem<TX>::load(W0 + static_cast<int64_t>(q) * a.ldw[0] + col0 + v);
+  float b1[VEC];
+#pragma unroll
+  for (int v = 0; v < VEC; ++v)
+    b1[v] = a.bias[0] ? Elem<TX>::load(static_cast<const TX*>(a.bias[0]) + col0 + v) : 0.f;
+
+  float w2[NL == 2 ? VEC : 1][NL == 2 ? L2 : 1];
+  float b2[NL == 2 ? L2 : 1];
+  if (NL == 2) {
+    const TX* __restrict__ W1 = static_cast<const TX*>(a.W[1]);
+#pragma unroll
+    for (int v = 0; v < VEC; ++v)
+#pragma unroll
+      for (int o = 0; o < L2; ++o)
+        w2[v][o] = Elem<TX>::load(W1 + static_cast<int64_t>(col0 + v) * a.ldw[1] + o);
+#pragma unroll
+    for (int o = 0; o < L2; ++o)
+      b2[o] = a.bias[1] ? Elem<TX>::load(static_cast<const TX*>(a.bias[1]) + o) : 0.f;
+  }
+
+  const int64_t n_pass = (a.n + RPB - 1) / RPB;
+  for (int64_t pass = blockIdx.x; pass < n_pass; pass += gridDim.x) {
+    const int64_t row = pass * RPB + sub;
+    const bool live = row < a.n;
+    const int64_t rr = live ? row : a.n - 1;    // dead lanes redo the last row, store nothing
+
+    float z[VEC];
+#pragma unroll
+    for (int v = 0; v < VEC; ++v) z[v] = b1[v];
+    if (CF > 0) {
+      const TX* xr = X + rr * a.ldx;
+#pragma unroll
+      for (int q = 0; q < CF; ++q) {
+        const float xq = Elem<TX>::load(xr + q);
+#pragma unroll
+        for (int v = 0; v < VEC; ++v) z[v] = fmaf(xq, wf[q][v], z[v]);
+      }
+    }
+    for (int k = 0; k < a.K; ++k) {
+      const int64_t j = a.fk[k][rr];
+      float p[VEC];
+      Chunk<TP, VEC>::load(static_cast<const TP*>(a.P[k]) + j * a.ldp[k] + col0, p);
+#pragma unroll
+      for (int v = 0; v < VEC; ++v) z[v] += p[v];
+    }
+
+    if (NL == 1) {
+      if (live) Chunk<TY, VEC>::store(static_cast<TY*>(a.Y) + row * a.ldy + col0, z);
+    } else {
+      float y[L2];
+#pragma unroll
+      for (int o = 0; o < L2; ++o) y[o] = 0.f;
+#pragma unroll
+      for (int v = 0; v < VEC; ++v) {
+        const float h = fmaxf(z[v], 0.f);
+#pragma unroll
+        for (int o = 0; o < L2; ++o) y[o] = fmaf(h, w2[v][o], y[o]);
+      }
+#pragma unroll
+      for (int m = 1; m < LPR; m <<= 1)
+#pragma unroll
+        for (int o = 0; o < L2; ++o) y[o] += __shfl_xor(y[o], m, 64);
+      if (live && c == 0) {
+        TY* yr = static_cast<TY*>(a.Y) + row * a.ldy;
+#pragma unroll
+        for (int o = 0; o < L2; ++o) Elem<TY>::store(yr + o, y[o] + b2[o]);
+      }
+    }
+  }
+}
+
+template <typename TX, typename TP, typename TY, int VEC, int LPR, int CF, int NL, int L2>
+int launch_vec_inst(const PredictArgs& a, hipStream_t s) {
+  constexpr int RPB = (64 / LPR) * (VEC_THREADS / 64);
+  const int64_t n_pass = (a.n + RPB - 1) / RPB;
+  const int64_t blocks = std::min<int64_t>(n_pass, static_cast<int64_t>(num_cus()) * 8);
+  if (blocks <= 0) return LQ_OK;
+  hipLaunchKernelGGL((fused_vec_kernel<TX, TP, TY, VEC, LPR, CF, NL, L2>),
+                     dim3(static_cast<unsigned>(blocks)), dim3(VEC_THREADS), 0, s, a);
+  LQ_LAUNCH_CHECK("fused_vec_kernel");
+  return LQ_OK;
+}
+
+// Run-time -> compile-time dispatch.  Returns -1 when no instantiation fits.
+template <typename TX, typename TP, typename TY, int VEC, int LPR, int CF>
+int pick_layers(const PredictArgs& a, hipStream_t s) {
+  if (a.n_layers == 1) return launch_vec_inst<TX, TP, TY, VEC, LPR, CF, 1, 1>(a, s);
+  if (a.n_layers == 2) {
+    switch (a.wout[1]) {
+      case 1: return launch_vec_inst<TX, TP, TY, VEC, LPR, CF, 2, 1>(a, s);
+      case 2: return launch_vec_inst<TX, TP, TY, VEC, LPR, CF, 2, 2>(a, s);
+      case 4: return launch_vec_inst<TX, TP, TY, VEC, LPR, CF, 2, 4>(a, s);
+      default: return -1;
+    }
+  }
+  return -1;
+}
+
+template <typename TX, typename TP, typename TY, int VEC, int LPR>
+int pick_cf(const PredictArgs& a, hipStream_t s) {
+  switch (a.c_f) {
+    case 0: return pick_layers<TX, TP, TY, VEC, LPR, 0>(a, s);
+    case 4: return pick_layers<TX, TP, TY, VEC, LPR, 4>(a, s);
+    case 8: return pick_layers<TX, TP, TY, VEC, LPR, 8>(a, s);
+    default: return -1;
+  }
+}
+
+template <typename TX, typename TP, typename TY, int VEC>
+int pick_lpr(const PredictArgs& a, hipStream_t s) {
+  const int l1 = a.wout[0];
+  if (l1 % VEC) return -1;
+  switch (l1 / VEC) {
+    case 1: return pick_cf<TX, TP, TY, VEC, 1>(a, s);
+    case 2: return pick_cf<TX, TP, TY, VEC, 2>(a, s);
+    case 4: return pick_cf<TX, TP, TY, VEC, 4>(a, s);
+    case 8: return pick_cf<TX, TP, TY, VEC, 8>(a, s);
+    case 16: return pick_cf<TX, TP, TY, VEC, 16>(a, s);
+    case 32: return pick_cf<TX, TP, TY, VEC, 32>(a, s);
+    case 64: return pick_cf<TX, TP, TY, VEC, 64>(a, s);
+    default: return -1;
+  }
+}
+
+// Are 16-byte chunk accesses to P and Y legal?
+bool chunks_aligned(const PredictArgs& a, int vec_p, int vec_y) {
+  const size_t ps = dtype_size(a.p_dtype), ys = dtype_size(a.y_dtype);
+  for (int k = 0; k < a.K; ++k)
+    if (!aligned(a.P[k], vec_p * ps) || a.ldp[k] % vec_p) return false;
+  if (a.n_layers == 1 && (!aligned(a.Y, vec_y * ys) || a.ldy % vec_y)) return false;
+  return true;
+}
+
+int try_vec(const PredictArgs& a, hipStream_t s) {
+  const int l1 = a.wout[0];
+  if (a.x_dtype == LQ_F32 && a.p_dtype == LQ_F32 && a.y_dtype == LQ_F32) {
+    if (l1 % 4 == 0 && chunks_aligned(a, 4, 4)) return pick_lpr<float, float, float, 4>(a, s);
+    if (l1 == 1) return pick_cf<float, float, float, 1, 1>(a, s);
+    return -1;
+  }
+  if (a.x_dtype == LQ_BF16 && a.p_dtype == LQ_BF16 && a.y_dtype == LQ_BF16) {
+    if (l1 % 8 == 0 && chunks_aligned(a, 8, 8)) return pick_lpr<bf16_t, bf16_t, bf16_t, 8>(a, s);
+    return -1;
+  }
+  return -1;
+}
+
+}  // namespace
+
+int launch_fused(const PredictArgs& a, hipStream_t s) {
+  if (a.n == 0) return LQ_OK;
+  const int rc = try_vec(a, s);
+  if (rc >= 0) return rc;
+  return launch_generic(a, s);
+}
+
+// The generic kernel alone (used to cross-check the fast path from the tests via a flag).
+int launch_fused_generic(const PredictArgs& a, hipStream_t s) {
+  if (a.n == 0) return LQ_OK;
+  return launch_generic(a, s);
+}
+
+}  // namespace lq

@@ -1,0 +1,125 @@
+// Materialisation of the joined table (first line of Eq. 1, T = X_f M_f + sum_k I_k D_k M_k),
+// foreign-key validation, and the plain stream-copy yardstick.
+#include "lq_common.h"
+
+namespace lq {
+namespace {
+
+struct MatArgs {
+  int64_t row0, rows;
+  const void* X; int64_t ldx; int32_t c_f;
+  int32_t K;
+  const void* D[LQ_MAX_DIMS]; int64_t ldd[LQ_MAX_DIMS]; int32_t c[LQ_MAX_DIMS];
+  int32_t off[LQ_MAX_DIMS];          // first column of dimension k in T
+  const int32_t* fk[LQ_MAX_DIMS];
+  void* T; int64_t ldt; int32_t kw;  // joined width
+};
+
+// One thread per (row, column) of the chunk, columns fastest: the writes to T are
+// fully coalesced and the reads of one dimension row are contiguous across lanes.
+template <typename E>
+__global__ __launch_bounds__(256) void materialize_kernel(MatArgs a) {
+  const int64_t total = a.rows * a.kw;
+  const int64_t stride = static_cast<int64_t>(gridDim.x) * blockDim.x;
+  for (int64_t idx = static_cast<int64_t>(blockIdx.x) * blockDim.x + threadIdx.x; idx < total;
+       idx += stride) {
+    const int64_t r = idx / a.kw;
+    const int col = static_cast<int>(idx - r * a.kw);
+    const int64_t row = a.row0 + r;
+    E v;
+    if (col < a.c_f) {
+      v = static_cast<const E*>(a.X)[row * a.ldx + col];
+    } else {
+      int k = 0;
+#pragma unroll
+      for (int q = 1; q < LQ_MAX_DIMS; ++q)
+        if (q < a.K && col >= a.off[q]) k = q;
+      const int64_t j = a.fk[k][row];
+      v = static_cast<const E*>(a.D[k])[j * a.ldd[k] + (col - a.off[k])];
+    }
+    static_cast<E*>(a.T)[r * a.ldt + col] = v;
+  }
+}
+
+struct CheckArgs {
+  int64_t n; int32_t K;
+  const int32_t* fk[LQ_MAX_DIMS];
+  int64_t rows[LQ_MAX_DIMS];
+  int negative_ok;
+};
+
+__global__ __launch_bounds__(256) void check_fks_kernel(CheckArgs a, int32_t* flag) {
+  const int64_t stride = static_cast<int64_t>(gridDim.x) * blockDim.x;
+  int bad = 0;
+  for (int64_t i = static_cast<int64_t>(blockIdx.x) * blockDim.x + threadIdx.x; i < a.n; i += stride)
+    for (int k = 0; k < a.K; ++k) {
+      const int64_t j = a.fk[k][i];
+      if (j >= a.rows[k] || (j < 0 && !a.negative_ok)) bad = 1;
+    }
+  if (bad) atomicOr(flag, 1);
+}
+
+__global__ __launch_bounds__(256) void zero_flag_kernel(int32_t* flag) {
+  if (threadIdx.x == 0 && blockIdx.x == 0) *flag = 0;
+}
+
+__global__ __launch_bounds__(256) void copy_kernel(uint4* __restrict__ dst,
+                                                   const uint4* __restrict__ src, int64_t n16) {
+  const int64_t stride = static_cast<int64_t>(gridDim.x) * blockDim.x;
+  for (int64_t i = static_cast<int64_t>(blockIdx.x) * blockDim.x + threadIdx.x; i < n16; i += stride)
+    dst[i] = src[i];
+}
+
+}  // namespace
+
+int launch_materialize(const lq_star& star, void* T, int64_t ldt, int64_t row0, int64_t rows,
+                       hipStream_t s) {
+  MatArgs a{};
+  a.row0 = row0; a.rows = rows;
+  a.X = star.fact.data; a.ldx = star.fact.ld; a.c_f = star.fact.cols;
+  a.K = star.n_dims;
+  int32_t off = a.c_f;
+  for (int k = 0; k < a.K; ++k) {
+    a.D[k] = star.dims[k].data; a.ldd[k] = star.dims[k].ld; a.c[k] = star.dims[k].cols;
+    a.off[k] = off; off += a.c[k];
+    a.fk[k] = star.fks[k];
+  }
+  a.T = T; a.ldt = ldt; a.kw = off;
+  const int64_t total = rows * off;
+  if (total <= 0) return LQ_OK;
+  const int64_t blocks = std::min<int64_t>((total + 255) / 256, static_cast<int64_t>(num_cus()) * 16);
+  const int32_t dt = a.c_f > 0 ? star.fact.dtype : star.dims[0].dtype;
+  if (dt == LQ_BF16)
+    hipLaunchKernelGGL(materialize_kernel<uint16_t>, dim3(static_cast<unsigned>(blocks)), dim3(256), 0, s, a);
+  else
+    hipLaunchKernelGGL(materialize_kernel<float>, dim3(static_cast<unsigned>(blocks)), dim3(256), 0, s, a);
+  LQ_LAUNCH_CHECK("materialize_kernel");
+  return LQ_OK;
+}
+
+int launch_check_fks(int64_t n, int32_t K, const int32_t* const* fks, const int64_t* rows,
+                     bool negative_ok, int32_t* d_flag, hipStream_t s) {
+  CheckArgs a{};
+  a.n = n; a.K = K; a.negative_ok = negative_ok ? 1 : 0;
+  for (int k = 0; k < K; ++k) { a.fk[k] = fks[k]; a.rows[k] = rows[k]; }
+  hipLaunchKernelGGL(zero_flag_kernel, dim3(1), dim3(64), 0, s, d_flag);
+  LQ_LAUNCH_CHECK("zero_flag_kernel");
+  if (n > 0 && K > 0) {
+    const int64_t blocks = std::min<int64_t>((n + 255) / 256, static_cast<int64_t>(num_cus()) * 8);
+    hipLaunchKernelGGL(check_fks_kernel, dim3(static_cast<unsigned>(blocks)), dim3(256), 0, s, a, d_flag);
+    LQ_LAUNCH_CHECK("check_fks_kernel");
+  }
+  return LQ_OK;
+}
+
+int launch_copy(void* dst, const void* src, size_t bytes, hipStream_t s) {
+  const int64_t n16 = static_cast<int64_t>(bytes / 16);
+  if (n16 == 0) return LQ_OK;
+  const int64_t blocks = std::min<int64_t>((n16 + 255) / 256, static_cast<int64_t>(num_cus()) * 16);
+  hipLaunchKernelGGL(copy_kernel, dim3(static_cast<unsigned>(blocks)), dim3(256), 0, s,
+                     static_cast<uint4*>(dst), static_cast<const uint4*>(src), n16);
+  LQ_LAUNCH_CHECK("copy_kernel");
+  return LQ_OK;
+}
+
+}  // namespace lq

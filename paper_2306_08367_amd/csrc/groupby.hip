@@ -1,0 +1,312 @@
+// Filtered star join + GROUP BY + SUM/COUNT as linear algebra (Sections 2.2-2.4).
+//
+// The selection vectors of the dimensions are pushed through the row-mapping matrices
+// (s_i = prod_k mask_k[fk_k[i]]) and the group-mapping matrix is applied row by row
+// (g_i = mixed-radix number of code_k[fk_k[i]]); neither matrix is ever built.
+//
+// Two launches per call:
+//   1. pack_kernel   - folds mask and code of every dimension into one compact side table
+//                      per dimension (a bitmap for mask-only dimensions, one byte or one
+//                      16-bit word "code, or all-ones if filtered out" for grouping
+//                      dimensions) and zeroes the outputs.
+//   2. scan_kernel   - streams the fact columns once.  The side tables sit in LDS when they
+//                      fit (they are read through L2 otherwise); survivors add into int64
+//                      accumulators in LDS, which each workgroup flushes to the global result
+//                      with 64-bit atomics at the end.  Integer addition commutes, so the
+//                      result is exact and independent of scheduling.
+#include "lq_common.h"
+
+namespace lq {
+namespace {
+
+enum DimKind : int32_t { DK_NONE = 0, DK_BITMAP = 1, DK_BYTE = 2, DK_U16 = 3 };
+
+struct GbDim {
+  const int32_t* fk;
+  const uint8_t* mask;   // raw, may be NULL
+  const int32_t* code;   // raw, may be NULL
+  int64_t rows;
+  int32_t kind;
+  int32_t card;          // 1 when not grouping
+  uint32_t off;          // byte offset of the packed table (16-byte aligned)
+  uint32_t bytes;        // packed size, multiple of 16
+};
+
+struct GbArgs {
+  int64_t n;
+  int32_t K;
+  GbDim d[LQ_MAX_DIMS];
+  const uint8_t* fact_mask;
+  int32_t M;
+  const int32_t* meas[LQ_MAX_MEASURES];
+  unsigned long long* sums;    // [M x G]
+  unsigned long long* counts;  // [G] or NULL
+  int32_t G;
+  uint8_t* packed;             // workspace: all packed tables
+  uint32_t packed_bytes;
+};
+
+// ---------------------------------------------------------------- pack ------------------
+
+__global__ __launch_bounds__(256) void pack_kernel(GbArgs a) {
+  const int64_t gtid = static_cast<int64_t>(blockIdx.x) * blockDim.x + threadIdx.x;
+  const int64_t gstride = static_cast<int64_t>(gridDim.x) * blockDim.x;
+  for (int64_t i = gtid; i < static_cast<int64_t>(a.M) * a.G; i += gstride) a.sums[i] = 0ull;
+  if (a.counts)
+    for (int64_t i = gtid; i < a.G; i += gstride) a.counts[i] = 0ull;
+  for (int k = 0; k < a.K; ++k) {
+    const GbDim& d = a.d[k];
+    if (d.kind == DK_BITMAP) {
+      uint32_t* out = reinterpret_cast<uint32_t*>(a.packed + d.off);
+      const int64_t words = d.bytes / 4;
+      for (int64_t w = gtid; w < words; w += gstride) {
+        uint32_t bits = 0;
+        const int64_t j0 = w * 32;
+        for (int b = 0; b < 32; ++b)
+          if (j0 + b < d.rows && d.mask[j0 + b]) bits |= 1u << b;
+        out[w] = bits;
+      }
+    } else if (d.kind == DK_BYTE) {
+      uint8_t* out = a.packed + d.off;
+      for (int64_t j = gtid; j < d.bytes; j += gstride) {
+        uint8_t v = 0xff;
+        if (j < d.rows && (!d.mask || d.mask[j])) v = d.code ? static_cast<uint8_t>(d.code[j]) : 0;
+        out[j] = v;
+      }
+    } else if (d.kind == DK_U16) {
+      uint16_t* out = reinterpret_cast<uint16_t*>(a.packed + d.off);
+      for (int64_t j = gtid; j < d.bytes / 2; j += gstride) {
+        uint16_t v = 0xffff;
+        if (j < d.rows && (!d.mask || d.mask[j])) v = static_cast<uint16_t>(d.code[j]);
+        out[j] = v;
+      }
+    }
+  }
+}
+
+// ---------------------------------------------------------------- scan ------------------
+
+constexpr int SCAN_THREADS = 1024;
+
+// One fact row: returns the group number, or -1 when the row is filtered out.
+template <bool LDS_TABLES>
+__device__ __forceinline__ int32_t classify(const GbArgs& a, const uint8_t* tab, const int32_t* fk) {
+  bool alive = true;
+  int32_t g = 0;
+#pragma unroll
+  for (int k = 0; k < LQ_MAX_DIMS; ++k) {
+    if (k >= a.K) break;
+    const GbDim& d = a.d[k];
+    const int32_t j = fk[k];
+    alive = alive && j >= 0;
+    const uint32_t jj = j < 0 ? 0u : static_cast<uint32_t>(j);   // keep the lookup in bounds
+    const uint8_t* t = tab + d.off;
+    if (d.kind == DK_BITMAP) {
+      const uint32_t w = reinterpret_cast<const uint32_t*>(t)[jj >> 5];
+      alive = alive && ((w >> (jj & 31)) & 1u);
+    } else if (d.kind == DK_BYTE) {
+      const uint32_t v = t[jj];
+      alive = alive && v != 0xffu;
+      g = g * d.card + static_cast<int32_t>(v);
+    } else if (d.kind == DK_U16) {
+      const uint32_t v = reinterpret_cast<const uint16_t*>(t)[jj];
+      alive = alive && v != 0xffffu;
+      g = g * d.card + static_cast<int32_t>(v);
+    }
+  }
+  return alive ? g : -1;
+}
+
+template <bool LDS_TABLES, int VEC>
+__global__ __launch_bounds__(SCAN_THREADS) void scan_kernel(GbArgs a) {
+  extern __shared__ __align__(16) uint8_t smem[];
+  // layout: accumulators [(M+1) x G] int64, then (LDS_TABLES) the packed tables
+  unsigned long long* acc = reinterpret_cast<unsigned long long*>(smem);
+  const int n_acc = (a.M + 1) * a.G;
+  uint8_t* tab_lds = smem + round_up(static_cast<size_t>(n_acc) * 8, 16);
+  const int tid = threadIdx.x;
+
+  for (int i = tid; i < n_acc; i += SCAN_THREADS) acc[i] = 0ull;
+  if (LDS_TABLES) {
+    const uint4* src = reinterpret_cast<const uint4*>(a.packed);
+    uint4* dst = reinterpret_cast<uint4*>(tab_lds);
+    for (uint32_t i = tid; i < a.packed_bytes / 16; i += SCAN_THREADS) dst[i] = src[i];
+  }
+  __syncthreads();
+  const uint8_t* tab = LDS_TABLES ? tab_lds : a.packed;
+
+  const int64_t n_vec = a.n / VEC;   // full VEC-row groups; the tail is done by workgroup 0
+  const int64_t gstride = static_cast<int64_t>(gridDim.x) * SCAN_THREADS;
+  for (int64_t v = static_cast<int64_t>(blockIdx.x) * SCAN_THREADS + tid; v < n_vec; v += gstride) {
+    int32_t fk[VEC][LQ_MAX_DIMS];
+    uint32_t fm = 0x01010101u;
+    if constexpr (VEC == 4) {
+#pragma unroll
+      for (int k = 0; k < LQ_MAX_DIMS; ++k) {
+        if (k >= a.K) break;
+        const int4 t = reinterpret_cast<const int4*>(a.d[k].fk)[v];
+        fk[0][k] = t.x; fk[1][k] = t.y; fk[2][k] = t.z; fk[3][k] = t.w;
+      }
+      if (a.fact_mask) fm = reinterpret_cast<const uint32_t*>(a.fact_mask)[v];
+    } else {
+#pragma unroll
+      for (int k = 0; k < LQ_MAX_DIMS; ++k) {
+        if (k >= a.K) break;
+        fk[0][k] = a.d[k].fk[v];
+      }
+      if (a.fact_mask) fm = a.fact_mask[v];
+    }
+    int32_t g[VEC];
+    bool any = false;
+#pragma unroll
+    for (int r = 0; r < VEC; ++r) {
+      g[r] = classify<LDS_TABLES>(a, tab, fk[r]);
+      if (((fm >> (8 * r)) & 0xffu) == 0) g[r] = -1;
+      any = any || g[r] >= 0;
+    }
+    if (any) {
+#pragma unroll
+      for (int m = 0; m < LQ_MAX_MEASURES; ++m) {
+        if (m >= a.M) break;
+        int32_t val[VEC];
+        if constexpr (VEC == 4) {
+          const int4 t = reinterpret_cast<const int4*>(a.meas[m])[v];
+          val[0] = t.x; val[1] = t.y; val[2] = t.z; val[3] = t.w;
+        } else {
+          val[0] = a.meas[m][v];
+        }
+#pragma unroll
+        for (int r = 0; r < VEC; ++r)
+          if (g[r] >= 0)
+            atomicAdd(&acc[m * a.G + g[r]],
+                      static_cast<unsigned long long>(static_cast<long long>(val[r])));
+      }
+#pragma unroll
+      for (int r = 0; r < VEC; ++r)
+        if (g[r] >= 0) atomicAdd(&acc[a.M * a.G + g[r]], 1ull);
+    }
+  }
+  // ragged tail (n % VEC rows)
+  if (VEC > 1 && blockIdx.x == 0) {
+    const int64_t i = n_vec * VEC + tid;
+    if (i < a.n) {
+      int32_t fk1[LQ_MAX_DIMS];
+#pragma unroll
+      for (int k = 0; k < LQ_MAX_DIMS; ++k) {
+        if (k >= a.K) break;
+        fk1[k] = a.d[k].fk[i];
+      }
+      int32_t g = classify<LDS_TABLES>(a, tab, fk1);
+      if (a.fact_mask && a.fact_mask[i] == 0) g = -1;
+      if (g >= 0) {
+        for (int m = 0; m < a.M; ++m)
+          atomicAdd(&acc[m * a.G + g],
+                    static_cast<unsigned long long>(static_cast<long long>(a.meas[m][i])));
+        atomicAdd(&acc[a.M * a.G + g], 1ull);
+      }
+    }
+  }
+  __syncthreads();
+  for (int i = tid; i < n_acc; i += SCAN_THREADS) {
+    const unsigned long long v = acc[i];
+    if (v == 0ull) continue;
+    if (i < a.M * a.G) atomicAdd(&a.sums[i], v);
+    else if (a.counts) atomicAdd(&a.counts[i - a.M * a.G], v);
+  }
+}
+
+constexpr size_t LDS_BUDGET = 160 * 1024 - 1024;   // gfx950 workgroups may use the whole 160 KB
+
+// Fills kind / off / bytes of every dimension; returns the packed size.
+size_t plan_tables(int32_t K, const int64_t* rows, const uint8_t* const* mask,
+                   const int32_t* const* code, const int32_t* card, GbDim* d) {
+  size_t off = 0;
+  for (int k = 0; k < K; ++k) {
+    const bool has_mask = mask && mask[k];
+    const bool has_code = code && code[k];
+    const int64_t r = rows[k];
+    size_t bytes = 0;
+    int32_t kind = DK_NONE;
+    if (has_code) {
+      if (card[k] <= 255) { kind = DK_BYTE; bytes = static_cast<size_t>(r); }
+      else { kind = DK_U16; bytes = static_cast<size_t>(r) * 2; }
+    } else if (has_mask) {
+      kind = DK_BITMAP; bytes = static_cast<size_t>((r + 31) / 32) * 4;
+    }
+    bytes = round_up(bytes, 16);
+    if (d) {
+      d[k].kind = kind; d[k].off = static_cast<uint32_t>(off); d[k].bytes = static_cast<uint32_t>(bytes);
+    }
+    off += bytes;
+  }
+  return off;
+}
+
+}  // namespace
+
+size_t groupby_ws_bytes(int32_t K, const int64_t* rows) {
+  // Upper bound that does not depend on which dimensions carry masks or codes:
+  // two bytes per dimension row, each table rounded to 16 bytes.
+  size_t t = 0;
+  for (int k = 0; k < K; ++k) t += round_up(static_cast<size_t>(rows[k]) * 2, 16);
+  return round_up(t, 256) + 256;
+}
+
+int launch_groupby(int64_t n, int32_t K, const int32_t* const* fks, const int64_t* rows,
+                   const uint8_t* const* mask, const int32_t* const* code, const int32_t* card,
+                   const uint8_t* fact_mask, int32_t M, const int32_t* const* meas, int64_t* sums,
+                   int64_t* counts, int32_t G, void* ws, hipStream_t s) {
+  GbArgs a{};
+  a.n = n; a.K = K; a.fact_mask = fact_mask; a.M = M; a.G = G;
+  a.sums = reinterpret_cast<unsigned long long*>(sums);
+  a.counts = reinterpret_cast<unsigned long long*>(counts);
+  a.packed = static_cast<uint8_t*>(ws);
+  bool vec_ok = aligned(fact_mask, 4);
+  for (int k = 0; k < K; ++k) {
+    a.d[k].fk = fks[k];
+    a.d[k].mask = mask ? mask[k] : nullptr;
+    a.d[k].code = code ? code[k] : nullptr;
+    a.d[k].rows = rows[k];
+    a.d[k].card = (code && code[k]) ? card[k] : 1;
+    vec_ok = vec_ok && aligned(fks[k], 16);
+  }
+  for (int m = 0; m < M; ++m) { a.meas[m] = meas[m]; vec_ok = vec_ok && aligned(meas[m], 16); }
+  const size_t packed = plan_tables(K, rows, mask, code, card, a.d);
+  if (packed > 0xffffffffull) return fail(LQ_ERR_UNSUPPORTED, "group-by: dimension side tables exceed 4 GiB");
+  a.packed_bytes = static_cast<uint32_t>(packed);
+
+  const int cus = num_cus();
+  {
+    size_t work = static_cast<size_t>(M + 1) * G;
+    for (int k = 0; k < K; ++k) work = std::max(work, static_cast<size_t>(a.d[k].bytes));
+    const int64_t blocks = std::min<int64_t>(static_cast<int64_t>((work + 255) / 256) , cus * 4);
+    hipLaunchKernelGGL(pack_kernel, dim3(static_cast<unsigned>(std::max<int64_t>(blocks, 1))), dim3(256), 0, s, a);
+    LQ_LAUNCH_CHECK("pack_kernel");
+  }
+  if (n == 0) return LQ_OK;
+
+  const size_t acc_bytes = round_up(static_cast<size_t>(M + 1) * G * 8, 16);
+  const bool lds_tables = acc_bytes + packed <= LDS_BUDGET;
+  const size_t lds = acc_bytes + (lds_tables ? packed : 0);
+  // Workgroups per CU the LDS footprint allows (at most two 1024-thread workgroups fit a CU).
+  const int per_cu = lds * 2 <= 160 * 1024 ? 2 : 1;
+  const int vec = vec_ok ? 4 : 1;
+  const int64_t want = (n / vec + SCAN_THREADS - 1) / SCAN_THREADS;
+  const unsigned blocks = static_cast<unsigned>(std::max<int64_t>(1, std::min<int64_t>(want, static_cast<int64_t>(cus) * per_cu)));
+
+#define LQ_SCAN(LT, V)                                                                        \
+  do {                                                                                        \
+    if (lds > 64 * 1024)                                                                      \
+      LQ_HIP_TRY(hipFuncSetAttribute(reinterpret_cast<const void*>(&scan_kernel<LT, V>),      \
+                                     hipFuncAttributeMaxDynamicSharedMemorySize,              \
+                                     static_cast<int>(lds)));                                 \
+    hipLaunchKernelGGL((scan_kernel<LT, V>), dim3(blocks), dim3(SCAN_THREADS), lds, s, a);    \
+  } while (0)
+  if (lds_tables) { if (vec == 4) LQ_SCAN(true, 4); else LQ_SCAN(true, 1); }
+  else            { if (vec == 4) LQ_SCAN(false, 4); else LQ_SCAN(false, 1); }
+#undef LQ_SCAN
+  LQ_LAUNCH_CHECK("scan_kernel");
+  return LQ_OK;
+}
+
+}  // namespace lq

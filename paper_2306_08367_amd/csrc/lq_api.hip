@@ -1,0 +1,379 @@
+// The C boundary of liblq: argument validation, error reporting and dispatch.
+// Every entry point validates on the host, enqueues on the caller's stream and returns.
+#include <string.h>
+
+#include "lq_common.h"
+
+namespace lq {
+
+static thread_local char g_err[512] = "";
+
+int fail(int code, const char* fmt, ...) {
+  va_list ap;
+  va_start(ap, fmt);
+  vsnprintf(g_err, sizeof(g_err), fmt, ap);
+  va_end(ap);
+  return code;
+}
+void clear_error() { g_err[0] = 0; }
+
+int num_cus() {
+  static int cached[64] = {0};
+  int dev = 0;
+  if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= 64) return 256;
+  if (cached[dev] == 0) {
+    int v = 0;
+    if (hipDeviceGetAttribute(&v, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess || v <= 0) v = 256;
+    cached[dev] = v;
+  }
+  return cached[dev];
+}
+
+int launch_gemm(const void* A, int64_t lda, const void* B, int64_t ldb, void* C, int64_t ldc,
+                const void* bias, int64_t M, int32_t N, int32_t Kd, int relu, int32_t in_dtype,
+                int32_t out_dtype, hipStream_t s);
+int launch_fused_generic(const PredictArgs& a, hipStream_t s);
+int launch_groupby(int64_t n, int32_t K, const int32_t* const* fks, const int64_t* rows,
+                   const uint8_t* const* mask, const int32_t* const* code, const int32_t* card,
+                   const uint8_t* fact_mask, int32_t M, const int32_t* const* meas, int64_t* sums,
+                   int64_t* counts, int32_t G, void* ws, hipStream_t s);
+size_t groupby_ws_bytes(int32_t K, const int64_t* rows);
+
+namespace {
+
+int check_mat(const lq_mat& m, const char* what, bool need_data) {
+  if (m.rows < 0 || m.cols < 0) return fail(LQ_ERR_SHAPE, "%s: negative size", what);
+  if (!dtype_ok(m.dtype)) return fail(LQ_ERR_DTYPE, "%s: unknown dtype %d", what, m.dtype);
+  if (m.rows > 0 && m.cols > 0) {
+    if (m.ld < m.cols) return fail(LQ_ERR_SHAPE, "%s: ld %lld < cols %d", what, (long long)m.ld, m.cols);
+    if (need_data && !m.data) return fail(LQ_ERR_NULL, "%s: data is NULL", what);
+    if (m.data && !aligned(m.data, dtype_size(m.dtype)))
+      return fail(LQ_ERR_SHAPE, "%s: data is not aligned to its element size", what);
+  }
+  return LQ_OK;
+}
+
+// Validates star + model (+ optional P) and works out the common dtype and the joined width.
+struct Checked {
+  int32_t dtype = LQ_F32;
+  int32_t kw = 0;      // joined width k
+  int32_t l1 = 0, l_out = 0;
+};
+
+int check_star_model(const lq_star* star, const lq_model* model, bool need_dims, Checked* out) {
+  if (!star || !model) return fail(LQ_ERR_NULL, "star or model is NULL");
+  if (star->n_fact < 0) return fail(LQ_ERR_SHAPE, "n_fact < 0");
+  if (star->n_dims < 0 || star->n_dims > LQ_MAX_DIMS)
+    return fail(LQ_ERR_SHAPE, "n_dims %d outside 0..%d", star->n_dims, LQ_MAX_DIMS);
+  if (model->n_layers < 1 || model->n_layers > LQ_MAX_LAYERS)
+    return fail(LQ_ERR_SHAPE, "n_layers %d outside 1..%d", model->n_layers, LQ_MAX_LAYERS);
+  if (!model->W) return fail(LQ_ERR_NULL, "model->W is NULL");
+  if (star->n_dims > 0 && !star->fks) return fail(LQ_ERR_NULL, "star->fks is NULL");
+  if (star->n_dims > 0 && need_dims && !star->dims) return fail(LQ_ERR_NULL, "star->dims is NULL");
+
+  const int32_t dt = model->W[0].dtype;
+  int rc = LQ_OK;
+  int32_t kw = 0;
+  if (star->fact.cols > 0) {
+    if ((rc = check_mat(star->fact, "fact", star->n_fact > 0))) return rc;
+    if (star->fact.rows != star->n_fact) return fail(LQ_ERR_SHAPE, "fact.rows != n_fact");
+    if (star->fact.dtype != dt) return fail(LQ_ERR_DTYPE, "fact and W[0] differ in dtype");
+    kw = star->fact.cols;
+  } else if (star->fact.cols < 0) {
+    return fail(LQ_ERR_SHAPE, "fact.cols < 0");
+  }
+  for (int k = 0; k < star->n_dims; ++k) {
+    if (star->n_fact > 0 && !star->fks[k]) return fail(LQ_ERR_NULL, "fks[%d] is NULL", k);
+    if (star->fks[k] && !aligned(star->fks[k], 4)) return fail(LQ_ERR_SHAPE, "fks[%d] is not 4-byte aligned", k);
+    if (need_dims || star->dims) {
+      char name[32];
+      snprintf(name, sizeof(name), "dims[%d]", k);
+      if ((rc = check_mat(star->dims[k], name, true))) return rc;
+      if (star->dims[k].dtype != dt) return fail(LQ_ERR_DTYPE, "%s and W[0] differ in dtype", name);
+      if (star->dims[k].rows < 1 && star->n_fact > 0) return fail(LQ_ERR_SHAPE, "%s has no rows", name);
+      kw += star->dims[k].cols;
+    }
+  }
+  for (int j = 0; j < model->n_layers; ++j) {
+    char name[32];
+    snprintf(name, sizeof(name), "W[%d]", j);
+    if ((rc = check_mat(model->W[j], name, true))) return rc;
+    if (model->W[j].dtype != dt) return fail(LQ_ERR_DTYPE, "all layers must share one dtype");
+    if (model->W[j].cols < 1) return fail(LQ_ERR_SHAPE, "%s has no columns", name);
+    if (j > 0 && model->W[j].rows != model->W[j - 1].cols)
+      return fail(LQ_ERR_SHAPE, "%s has %lld rows but the previous layer has %d outputs", name,
+                  (long long)model->W[j].rows, model->W[j - 1].cols);
+    if (model->bias && model->bias[j] && !aligned(model->bias[j], dtype_size(dt)))
+      return fail(LQ_ERR_SHAPE, "bias[%d] is misaligned", j);
+  }
+  if ((need_dims || star->dims || star->n_dims == 0) && model->W[0].rows != kw)
+    return fail(LQ_ERR_SHAPE, "W[0] has %lld rows but the joined width is %d",
+                (long long)model->W[0].rows, kw);
+  out->dtype = dt;
+  out->kw = static_cast<int32_t>(model->W[0].rows);
+  out->l1 = model->W[0].cols;
+  out->l_out = model->W[model->n_layers - 1].cols;
+  return LQ_OK;
+}
+
+int check_Y(const lq_mat* Y, int64_t n, int32_t l_out, int32_t model_dtype) {
+  if (!Y) return fail(LQ_ERR_NULL, "Y is NULL");
+  int rc = check_mat(*Y, "Y", n > 0);
+  if (rc) return rc;
+  if (Y->rows != n || Y->cols != l_out)
+    return fail(LQ_ERR_SHAPE, "Y is %lld x %d, expected %lld x %d", (long long)Y->rows, Y->cols,
+                (long long)n, l_out);
+  if (Y->dtype == LQ_BF16 && model_dtype != LQ_BF16)
+    return fail(LQ_ERR_DTYPE, "bf16 output needs a bf16 model");
+  return LQ_OK;
+}
+
+void fill_layers(PredictArgs* a, const lq_model* model) {
+  a->n_layers = model->n_layers;
+  for (int j = 0; j < model->n_layers; ++j) {
+    a->W[j] = model->W[j].data;
+    a->ldw[j] = model->W[j].ld;
+    a->win[j] = static_cast<int32_t>(model->W[j].rows);
+    a->wout[j] = model->W[j].cols;
+    a->bias[j] = model->bias ? model->bias[j] : nullptr;
+  }
+}
+
+// Synchronous range check of the foreign keys; ws must hold one int32.
+int run_fk_check(int64_t n, int32_t K, const int32_t* const* fks, const int64_t* rows,
+                 bool negative_ok, void* ws, size_t ws_bytes, hipStream_t s) {
+  if (!ws || ws_bytes < 256 || !aligned(ws, 256))
+    return fail(LQ_ERR_WORKSPACE, "LQ_CHECK_FKS needs a 256-byte aligned workspace of >= 256 bytes");
+  int32_t* flag = static_cast<int32_t*>(ws);
+  int rc = launch_check_fks(n, K, fks, rows, negative_ok, flag, s);
+  if (rc) return rc;
+  int32_t h = 0;
+  LQ_HIP_TRY(hipMemcpyAsync(&h, flag, sizeof(h), hipMemcpyDeviceToHost, s));
+  LQ_HIP_TRY(hipStreamSynchronize(s));
+  if (h) return fail(LQ_ERR_FK_RANGE, "a foreign key lies outside its dimension table");
+  return LQ_OK;
+}
+
+constexpr uint32_t FLAG_FORCE_GENERIC = 0x100u;   // testing aid, see lq_fused_join_predict
+
+}  // namespace
+}  // namespace lq
+
+using namespace lq;
+
+extern "C" {
+
+const char* lq_last_error(void) { return g_err; }
+const char* lq_version(void) { return "lq 0.1 (gfx950)"; }
+
+int lq_project_dims(const lq_star* star, const lq_model* model, lq_mat* P, void* hip_stream) {
+  clear_error();
+  Checked c;
+  int rc = check_star_model(star, model, true, &c);
+  if (rc) return rc;
+  if (star->n_dims > 0 && !P) return fail(LQ_ERR_NULL, "P is NULL");
+  for (int k = 0; k < star->n_dims; ++k) {
+    char name[32];
+    snprintf(name, sizeof(name), "P[%d]", k);
+    if ((rc = check_mat(P[k], name, true))) return rc;
+    if (P[k].rows != star->dims[k].rows || P[k].cols != c.l1)
+      return fail(LQ_ERR_SHAPE, "%s is %lld x %d, expected %lld x %d", name, (long long)P[k].rows,
+                  P[k].cols, (long long)star->dims[k].rows, c.l1);
+    if (P[k].dtype == LQ_BF16 && c.dtype != LQ_BF16)
+      return fail(LQ_ERR_DTYPE, "%s: bf16 projected tables need a bf16 model", name);
+  }
+  hipStream_t s = static_cast<hipStream_t>(hip_stream);
+  int32_t off = star->fact.cols > 0 ? star->fact.cols : 0;
+  for (int k = 0; k < star->n_dims; ++k) {
+    if ((rc = launch_project_dims(star->dims[k], model->W[0], off, P[k], s))) return rc;
+    off += star->dims[k].cols;
+  }
+  return LQ_OK;
+}
+
+int lq_fused_join_predict(const lq_star* star, const lq_model* model, const lq_mat* P, lq_mat* Y,
+                          void* ws, size_t ws_bytes, uint32_t flags, void* hip_stream) {
+  clear_error();
+  Checked c;
+  int rc = check_star_model(star, model, false, &c);
+  if (rc) return rc;
+  if (star->n_dims > 0 && !P) return fail(LQ_ERR_NULL, "P is NULL");
+  if ((rc = check_Y(Y, star->n_fact, c.l_out, c.dtype))) return rc;
+  PredictArgs a{};
+  a.n = star->n_fact;
+  a.c_f = star->fact.cols > 0 ? star->fact.cols : 0;
+  a.X = a.c_f ? star->fact.data : nullptr;
+  a.ldx = star->fact.ld;
+  a.K = star->n_dims;
+  int64_t rows[LQ_MAX_DIMS];
+  for (int k = 0; k < a.K; ++k) {
+    char name[32];
+    snprintf(name, sizeof(name), "P[%d]", k);
+    if ((rc = check_mat(P[k], name, true))) return rc;
+    if (P[k].cols != c.l1 || P[k].rows < 1)
+      return fail(LQ_ERR_SHAPE, "%s is %lld x %d, expected r_k x %d", name, (long long)P[k].rows,
+                  P[k].cols, c.l1);
+    if (P[k].dtype != P[0].dtype) return fail(LQ_ERR_DTYPE, "projected tables differ in dtype");
+    if (P[k].dtype == LQ_BF16 && c.dtype != LQ_BF16)
+      return fail(LQ_ERR_DTYPE, "%s: bf16 projected tables need a bf16 model", name);
+    if (star->dims) {
+      if (star->dims[k].rows != P[k].rows)
+        return fail(LQ_ERR_SHAPE, "%s has %lld rows, dims[%d] has %lld", name, (long long)P[k].rows, k,
+                    (long long)star->dims[k].rows);
+    }
+    a.P[k] = P[k].data;
+    a.ldp[k] = P[k].ld;
+    a.fk[k] = star->fks[k];
+    rows[k] = P[k].rows;
+  }
+  if (!star->dims && a.K > 0 && model->W[0].rows < a.c_f)
+    return fail(LQ_ERR_SHAPE, "W[0] has fewer rows than the fact table has columns");
+  fill_layers(&a, model);
+  a.Y = Y->data; a.ldy = Y->ld;
+  a.x_dtype = c.dtype;
+  a.p_dtype = a.K ? P[0].dtype : c.dtype;
+  a.y_dtype = Y->dtype;
+  hipStream_t s = static_cast<hipStream_t>(hip_stream);
+  if ((flags & LQ_CHECK_FKS) && a.K > 0 && a.n > 0)
+    if ((rc = run_fk_check(a.n, a.K, star->fks, rows, false, ws, ws_bytes, s))) return rc;
+  if (flags & FLAG_FORCE_GENERIC) return launch_fused_generic(a, s);
+  return launch_fused(a, s);
+}
+
+size_t lq_workspace_bytes(int which_call, const lq_star* star, const lq_model* model,
+                          int64_t chunk_rows) {
+  if (which_call == LQ_CALL_FUSED) return 256;
+  if (which_call != LQ_CALL_MATERIALIZED || !star || !model || !model->W || chunk_rows < 1) return 0;
+  if (model->n_layers < 1 || model->n_layers > LQ_MAX_LAYERS) return 0;
+  const size_t es = dtype_size(model->W[0].dtype);
+  size_t widest = 0;
+  for (int j = 0; j + 1 < model->n_layers; ++j)
+    widest = std::max(widest, static_cast<size_t>(model->W[j].cols));
+  const size_t rows = round_up(static_cast<size_t>(chunk_rows), 256);
+  const size_t t_bytes = round_up(rows * static_cast<size_t>(model->W[0].rows) * es, 256);
+  const size_t act_bytes = round_up(rows * widest * es, 256);
+  return 256 + t_bytes + 2 * act_bytes;
+}
+
+int lq_materialized_join_predict(const lq_star* star, const lq_model* model, lq_mat* Y, void* ws,
+                                 size_t ws_bytes, uint32_t flags, void* hip_stream) {
+  clear_error();
+  Checked c;
+  int rc = check_star_model(star, model, true, &c);
+  if (rc) return rc;
+  if ((rc = check_Y(Y, star->n_fact, c.l_out, c.dtype))) return rc;
+  if (star->n_fact == 0) return LQ_OK;
+  if (!ws || !aligned(ws, 256)) return fail(LQ_ERR_WORKSPACE, "workspace is NULL or not 256-byte aligned");
+  // Largest chunk (multiple of 256 rows) whose buffers fit.
+  const size_t per256 = lq_workspace_bytes(LQ_CALL_MATERIALIZED, star, model, 256) - 256;
+  if (ws_bytes < 256 + per256)
+    return fail(LQ_ERR_WORKSPACE, "workspace of %zu bytes cannot hold one 256-row chunk (%zu needed)",
+                ws_bytes, 256 + per256);
+  int64_t chunk = static_cast<int64_t>((ws_bytes - 256) / per256) * 256;
+  while (chunk > 256 && lq_workspace_bytes(LQ_CALL_MATERIALIZED, star, model, chunk) > ws_bytes) chunk -= 256;
+  chunk = std::min<int64_t>(chunk, static_cast<int64_t>(round_up(static_cast<size_t>(star->n_fact), 256)));
+
+  hipStream_t s = static_cast<hipStream_t>(hip_stream);
+  int64_t rows[LQ_MAX_DIMS];
+  for (int k = 0; k < star->n_dims; ++k) rows[k] = star->dims[k].rows;
+  if ((flags & LQ_CHECK_FKS) && star->n_dims > 0)
+    if ((rc = run_fk_check(star->n_fact, star->n_dims, star->fks, rows, false, ws, ws_bytes, s))) return rc;
+
+  const size_t es = dtype_size(c.dtype);
+  size_t widest = 0;
+  for (int j = 0; j + 1 < model->n_layers; ++j) widest = std::max(widest, static_cast<size_t>(model->W[j].cols));
+  char* base = static_cast<char*>(ws) + 256;
+  void* T = base;
+  const size_t t_bytes = round_up(static_cast<size_t>(chunk) * c.kw * es, 256);
+  const size_t act_bytes = round_up(static_cast<size_t>(chunk) * widest * es, 256);
+  void* act[2] = {base + t_bytes, base + t_bytes + act_bytes};
+
+  for (int64_t r0 = 0; r0 < star->n_fact; r0 += chunk) {
+    const int64_t m = std::min<int64_t>(chunk, star->n_fact - r0);
+    if ((rc = launch_materialize(*star, T, c.kw, r0, m, s))) return rc;
+    const void* in = T;
+    int64_t ldin = c.kw;
+    for (int j = 0; j < model->n_layers; ++j) {
+      const bool last = j == model->n_layers - 1;
+      void* out = last ? static_cast<void*>(static_cast<char*>(Y->data) +
+                                            static_cast<size_t>(r0) * Y->ld * dtype_size(Y->dtype))
+                       : act[j & 1];
+      const int64_t ldout = last ? Y->ld : model->W[j].cols;
+      rc = launch_gemm(in, ldin, model->W[j].data, model->W[j].ld, out, ldout,
+                       model->bias ? model->bias[j] : nullptr, m, model->W[j].cols,
+                       static_cast<int32_t>(model->W[j].rows), last ? 0 : 1, c.dtype,
+                       last ? Y->dtype : c.dtype, s);
+      if (rc) return rc;
+      in = out;
+      ldin = ldout;
+    }
+  }
+  return LQ_OK;
+}
+
+size_t lq_groupby_workspace_bytes(int32_t n_dims, const int64_t* dim_rows, const int32_t* group_card,
+                                  int32_t n_measures) {
+  (void)group_card; (void)n_measures;
+  if (n_dims < 0 || n_dims > LQ_MAX_DIMS || (n_dims > 0 && !dim_rows)) return 0;
+  for (int k = 0; k < n_dims; ++k)
+    if (dim_rows[k] < 0) return 0;
+  return groupby_ws_bytes(n_dims, dim_rows);
+}
+
+int lq_masked_groupby_sum(int64_t n_fact, int32_t n_dims, const int32_t* const* fks,
+                          const int64_t* dim_rows, const uint8_t* const* dim_mask,
+                          const int32_t* const* dim_code, const int32_t* group_card,
+                          const uint8_t* fact_mask, int32_t n_measures,
+                          const int32_t* const* measures, int64_t* sums, int64_t* counts, void* ws,
+                          size_t ws_bytes, uint32_t flags, void* hip_stream) {
+  clear_error();
+  if (n_fact < 0) return fail(LQ_ERR_SHAPE, "n_fact < 0");
+  if (n_dims < 0 || n_dims > LQ_MAX_DIMS) return fail(LQ_ERR_SHAPE, "n_dims %d outside 0..%d", n_dims, LQ_MAX_DIMS);
+  if (n_measures < 1 || n_measures > LQ_MAX_MEASURES)
+    return fail(LQ_ERR_SHAPE, "n_measures %d outside 1..%d", n_measures, LQ_MAX_MEASURES);
+  if (n_dims > 0 && (!fks || !dim_rows)) return fail(LQ_ERR_NULL, "fks or dim_rows is NULL");
+  if (!measures || !sums) return fail(LQ_ERR_NULL, "measures or sums is NULL");
+  if (!aligned(sums, 8) || !aligned(counts, 8)) return fail(LQ_ERR_SHAPE, "sums / counts are not 8-byte aligned");
+  int64_t G = 1;
+  for (int k = 0; k < n_dims; ++k) {
+    if (n_fact > 0 && !fks[k]) return fail(LQ_ERR_NULL, "fks[%d] is NULL", k);
+    if (!aligned(fks[k], 4)) return fail(LQ_ERR_SHAPE, "fks[%d] is not 4-byte aligned", k);
+    if (dim_rows[k] < 0 || dim_rows[k] > 0x7fffffffLL) return fail(LQ_ERR_SHAPE, "dim_rows[%d] out of range", k);
+    if (dim_code && dim_code[k]) {
+      if (!group_card) return fail(LQ_ERR_NULL, "group_card is NULL");
+      if (group_card[k] < 1 || group_card[k] > 65535)
+        return fail(LQ_ERR_SHAPE, "group_card[%d] = %d outside 1..65535", k, group_card[k]);
+      if (!aligned(dim_code[k], 4)) return fail(LQ_ERR_SHAPE, "dim_code[%d] is not 4-byte aligned", k);
+      G *= group_card[k];
+      if (G > 8192) return fail(LQ_ERR_UNSUPPORTED, "more than 8192 groups");
+    }
+    if (dim_rows[k] == 0 && n_fact > 0 && ((dim_code && dim_code[k]) || (dim_mask && dim_mask[k])))
+      return fail(LQ_ERR_SHAPE, "dimension %d has no rows", k);
+  }
+  if (G * (n_measures + 1) > 8192)
+    return fail(LQ_ERR_UNSUPPORTED, "groups x (measures + 1) = %lld exceeds 8192", (long long)(G * (n_measures + 1)));
+  for (int m = 0; m < n_measures; ++m) {
+    if (n_fact > 0 && !measures[m]) return fail(LQ_ERR_NULL, "measures[%d] is NULL", m);
+    if (!aligned(measures[m], 4)) return fail(LQ_ERR_SHAPE, "measures[%d] is not 4-byte aligned", m);
+  }
+  const size_t need = lq_groupby_workspace_bytes(n_dims, dim_rows, group_card, n_measures);
+  if (!ws || !aligned(ws, 256) || ws_bytes < need)
+    return fail(LQ_ERR_WORKSPACE, "group-by needs a 256-byte aligned workspace of %zu bytes", need);
+  hipStream_t s = static_cast<hipStream_t>(hip_stream);
+  int rc;
+  if ((flags & LQ_CHECK_FKS) && n_dims > 0 && n_fact > 0)
+    if ((rc = run_fk_check(n_fact, n_dims, fks, dim_rows, true, ws, ws_bytes, s))) return rc;
+  return launch_groupby(n_fact, n_dims, fks, dim_rows, dim_mask, dim_code, group_card, fact_mask,
+                        n_measures, measures, sums, counts, static_cast<int32_t>(G), ws, s);
+}
+
+int lq_stream_copy(void* dst, const void* src, size_t bytes, void* hip_stream) {
+  clear_error();
+  if (bytes == 0) return LQ_OK;
+  if (!dst || !src) return fail(LQ_ERR_NULL, "dst or src is NULL");
+  if (!aligned(dst, 16) || !aligned(src, 16) || bytes % 16)
+    return fail(LQ_ERR_SHAPE, "stream copy needs 16-byte aligned pointers and size");
+  return launch_copy(dst, src, bytes, static_cast<hipStream_t>(hip_stream));
+}
+
+}  // extern "C"

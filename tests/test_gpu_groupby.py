@@ -1,0 +1,154 @@
+"""GPU parity of the masked star-join group-by against the int64 oracle: bit-exact."""
+import numpy as np
+import pytest
+import torch
+
+from oracle import lq_oracle as O
+from tests.helpers import cpu_list, to_dev
+from workloads import star as WL
+
+pytestmark = pytest.mark.gpu
+
+
+@pytest.fixture(scope="module")
+def lq():
+    import paper_2306_08367_amd as lq
+    return lq
+
+
+def _oracle(w, nthreads=8):
+    return O.groupby_sum(cpu_list(w.fks), w.dim_rows, cpu_list(w.dim_mask), cpu_list(w.dim_code),
+                         w.group_card, None if w.fact_mask is None else w.fact_mask.cpu(),
+                         cpu_list(w.measures), nthreads=nthreads)
+
+
+def _gpu(lq, w, **kw):
+    sums, counts = lq.lq_masked_groupby_sum(w.fks, w.dim_rows, w.dim_mask, w.dim_code, w.group_card,
+                                            w.fact_mask, w.measures, **kw)
+    torch.cuda.synchronize()
+    return sums.cpu().numpy(), None if counts is None else counts.cpu().numpy()
+
+
+def _check(lq, w, **kw):
+    ws, wc = _oracle(w)
+    w = to_dev(w)
+    s, c = _gpu(lq, w, **kw)
+    np.testing.assert_array_equal(s, ws)
+    np.testing.assert_array_equal(c, wc)
+    return w, ws, wc
+
+
+def _random_groupby(seed, n, rows, card, n_measures=2, fact_mask=True, neg=False, sel=(0.8, 0.5, 0.6)):
+    r = np.random.default_rng(seed)
+    K = len(rows)
+    fks = [torch.from_numpy(r.integers(0, a, size=n).astype(np.int32)) for a in rows]
+    if neg:
+        fks[K - 1][torch.from_numpy(r.integers(0, n, size=max(1, n // 50)))] = -1
+    codes = [torch.from_numpy(r.integers(0, card[k], size=rows[k]).astype(np.int32)) if card[k] > 1 else None
+             for k in range(K)]
+    masks = [None] + [torch.from_numpy((r.random(rows[k]) < sel[(k - 1) % len(sel)]).astype(np.uint8))
+                      for k in range(1, K)]
+    meas = [torch.from_numpy(r.integers(-100_000, 100_001, size=n).astype(np.int32)) for _ in range(n_measures)]
+    fm = torch.from_numpy((r.random(n) < 0.9).astype(np.uint8)) if fact_mask else None
+    return WL.GroupByWorkload("rand", n, fks, list(rows), masks, codes, list(card), fm, meas)
+
+
+def test_config3_both_variants_full_size(lq):
+    for variant in ("A", "B"):
+        w = WL.c3_groupby(variant=variant)
+        w, ws, wc = _check(lq, w)
+        populated = int((wc > 0).sum())
+        assert populated == (175 if variant == "A" else 35)
+        frac = wc.sum() / w.n
+        assert (0.015 < frac < 0.035) if variant == "A" else (0.002 < frac < 0.02)
+        # twice more: integer atomics make the result independent of scheduling
+        for _ in range(2):
+            s, c = _gpu(lq, w)
+            np.testing.assert_array_equal(s, ws)
+            np.testing.assert_array_equal(c, wc)
+
+
+def test_config3_two_measures(lq):
+    _check(lq, WL.c3_groupby(n=1_000_003, n_measures=2))
+
+
+@pytest.mark.parametrize("n", [0, 1, 3, 4, 5, 1023, 4096, 4099, 100_001])
+def test_ragged_sizes(lq, n):
+    _check(lq, _random_groupby(10 + n, n, (7, 11, 5, 13), (3, 4, 1, 1)))
+
+
+def test_negative_keys_drop_rows(lq):
+    _check(lq, _random_groupby(30, 50_001, (9, 40, 33), (5, 1, 1), neg=True))
+
+
+def test_no_grouping_is_a_plain_masked_sum(lq):
+    w = _random_groupby(31, 70_003, (50, 60), (1, 1), n_measures=1)
+    w, ws, wc = _check(lq, w)
+    assert ws.shape == (1, 1)
+
+
+def test_no_masks_no_fact_mask_counts_every_row(lq):
+    w = _random_groupby(32, 33_333, (6, 9), (6, 9), fact_mask=False)
+    w.dim_mask = [None, None]
+    w, ws, wc = _check(lq, w)
+    assert wc.sum() == 33_333
+
+
+def test_empty_and_full_selections(lq):
+    w = _random_groupby(33, 20_000, (10, 20, 30), (2, 5, 1))
+    w.dim_mask[2] = torch.zeros(30, dtype=torch.uint8)
+    w, ws, wc = _check(lq, w)
+    assert wc.sum() == 0 and ws.sum() == 0
+    w = _random_groupby(34, 20_000, (10, 20, 30), (2, 5, 1), fact_mask=False)
+    w.dim_mask = [torch.ones(r, dtype=torch.uint8) for r in (10, 20, 30)]
+    w, ws, wc = _check(lq, w)
+    assert wc.sum() == 20_000
+
+
+def test_three_grouping_dimensions_and_wide_codes(lq):
+    # 3 grouping dimensions; one with cardinality > 255 (16-bit side table)
+    _check(lq, _random_groupby(35, 60_000, (400, 30, 8, 50), (300, 3, 2, 1), n_measures=1))
+    _check(lq, _random_groupby(36, 60_000, (40, 30, 8), (10, 10, 8), n_measures=4))
+
+
+def test_side_tables_too_large_for_lds_are_read_from_memory(lq):
+    # 400,000 + 300,000 byte-coded rows exceed the 160 KB of LDS
+    _check(lq, _random_groupby(37, 300_007, (400_000, 300_000, 1_000), (7, 5, 1), n_measures=1))
+
+
+def test_unaligned_columns_take_the_scalar_path(lq):
+    w = _random_groupby(38, 40_001, (20, 30), (4, 5))
+    ws, wc = _oracle(w)
+    w = to_dev(w)
+    # shift every column by one element so that no pointer is 16-byte aligned
+    def shift(t):
+        buf = torch.empty(t.numel() + 1, dtype=t.dtype, device="cuda")
+        buf[1:] = t
+        return buf[1:]
+    w.fks = [shift(f) for f in w.fks]
+    w.measures = [shift(m) for m in w.measures]
+    w.fact_mask = shift(w.fact_mask)
+    s, c = _gpu(lq, w)
+    np.testing.assert_array_equal(s, ws)
+    np.testing.assert_array_equal(c, wc)
+
+
+def test_counts_are_optional_and_outputs_are_overwritten(lq):
+    w = _random_groupby(39, 10_000, (5, 6), (5, 6))
+    ws, wc = _oracle(w)
+    w = to_dev(w)
+    sums = torch.full((2, 30), 123456789, dtype=torch.int64, device="cuda")
+    s, c = _gpu(lq, w, sums=sums, want_counts=False)
+    assert c is None
+    np.testing.assert_array_equal(s, ws)
+
+
+def test_check_fks_flag(lq):
+    w = to_dev(_random_groupby(40, 9_000, (5, 6), (5, 6)))
+    _gpu(lq, w, flags=lq.LQ_CHECK_FKS)
+    w.fks[1][77] = 6
+    with pytest.raises(lq.LQError) as e:
+        _gpu(lq, w, flags=lq.LQ_CHECK_FKS)
+    assert e.value.status == "LQ_ERR_FK_RANGE"
+    w.fks[1][77] = -5                                        # negative = no match: allowed
+    _gpu(lq, w, flags=lq.LQ_CHECK_FKS)

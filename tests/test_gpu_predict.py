@@ -1,0 +1,190 @@
+"""GPU parity: pre-fusion, fused join+predict and the materialised pipeline against the fp64 oracle.
+
+Bar: fp32 paths within 1e-4, bf16 paths within 2e-2, per element as
+|y - want| <= tol * (|want| + rms(want)); foreign-key indexing bit-exact (integer-valued
+features and one-hot / small-integer weights make every result exactly representable)."""
+import numpy as np
+import pytest
+import torch
+
+from oracle import lq_oracle as O
+from tests.helpers import TOL_BF16, TOL_F32, assert_close, cpu_list, to_dev
+from workloads import star as WL
+
+pytestmark = pytest.mark.gpu
+
+
+@pytest.fixture(scope="module")
+def lq():
+    import paper_2306_08367_amd as lq
+    return lq
+
+
+def _oracle(w, nthreads=8):
+    return O.join_predict(None if w.X is None else w.X.cpu(), cpu_list(w.dims), cpu_list(w.fks),
+                          cpu_list(w.weights), cpu_list(w.biases), nthreads=nthreads)
+
+
+def _run_fused(lq, w, p_dtype=None, y_dtype=None, flags=0):
+    P = lq.lq_project_dims(w.dims, w.weights[0], w.c_f, p_dtype=p_dtype or w.dtype)
+    Y = lq.lq_fused_join_predict(w.X, w.fks, P, w.weights, w.biases, y_dtype=y_dtype, flags=flags)
+    torch.cuda.synchronize()
+    return P, Y
+
+
+SHAPES = [
+    # name, n, c_f, dim_rows, dim_cols, layers, bias
+    ("linear_l1", 10_000, 4, (100, 50), (8, 8), (1,), False),
+    ("linear_l4_cf8", 5_003, 8, (300, 200), (16, 12), (4,), True),
+    ("linear_l64", 3_001, 4, (64, 1000), (8, 8), (64,), True),
+    ("linear_l3_odd", 777, 3, (20, 30, 40), (5, 7, 2), (3,), True),
+    ("mlp_64_1", 20_037, 4, (1000, 5000, 200), (32, 32, 32), (64, 1), False),
+    ("mlp_64_4_bias", 4_099, 4, (100, 50), (8, 8), (64, 4), True),
+    ("mlp_32_16_8_generic", 2_050, 5, (30, 7), (6, 3), (32, 16, 8), True),
+    ("mlp_100_10", 1_111, 0, (50, 60), (9, 9), (100, 10), True),
+    ("no_fact_cols_K1", 4_000, 0, (17,), (11,), (8,), False),
+    ("single_row_dims", 1_000, 2, (1, 1), (4, 4), (16, 2), True),
+    ("one_fact_row", 1, 4, (10, 10), (8, 8), (64, 1), True),
+    ("k8_dims", 3_000, 4, (10,) * 8, (4,) * 8, (16,), False),
+]
+
+
+@pytest.mark.parametrize("shape", SHAPES, ids=[s[0] for s in SHAPES])
+def test_fused_matches_oracle_fp32(lq, shape):
+    name, n, c_f, rows, cols, layers, bias = shape
+    w = WL.make_predict(name, n, c_f, rows, cols, layers, seed=WL.SEED0 + 1000 + len(name),
+                        w_sigma=[0.3] * len(layers), bias=bias)
+    want = _oracle(w)
+    w = to_dev(w)
+    P, Y = _run_fused(lq, w)
+    Pw = O.project_dims(cpu_list(w.dims), w.weights[0].cpu(), w.c_f)
+    for k in range(len(P)):
+        assert_close(P[k], Pw[k], TOL_F32, f"{name}: P[{k}]")
+    assert_close(Y, want, TOL_F32, f"{name}: fused")
+    # the shape-agnostic kernel must agree with whichever kernel the dispatcher picked
+    _, Yg = _run_fused(lq, w, flags=lq.LQ_FORCE_GENERIC)
+    assert_close(Yg, want, TOL_F32, f"{name}: generic kernel")
+    # the non-fused pipeline computes the same function
+    Ym = lq.lq_materialized_join_predict(w.X, w.dims, w.fks, w.weights, w.biases, chunk_rows=1024)
+    torch.cuda.synchronize()
+    assert_close(Ym, want, TOL_F32, f"{name}: materialised")
+
+
+def test_config1_tiny_linear_regression(lq):
+    w = WL.c1_tiny_linear()
+    want = _oracle(w)
+    w = to_dev(w)
+    _, Y = _run_fused(lq, w)
+    assert_close(Y, want, TOL_F32, "config 1")
+
+
+def test_fk_indexing_is_bit_exact_fp32(lq):
+    """Integer-valued features and weights: every partial sum is an integer far below 2^24,
+    so fp32 must reproduce the fp64 oracle exactly, for the fused and the materialised path."""
+    for layers in ((4,), (64,), (64, 1), (16, 4)):
+        w = WL.make_predict("exact", 6_011, 4, (97, 1_013, 31), (8, 4, 8), layers,
+                            seed=WL.SEED0 + 77, integer_valued=True, bias=True)
+        want = _oracle(w)
+        assert np.abs(want).max() < 2 ** 22
+        w = to_dev(w)
+        _, Y = _run_fused(lq, w)
+        np.testing.assert_array_equal(Y.cpu().double().numpy(), want)
+        Ym = lq.lq_materialized_join_predict(w.X, w.dims, w.fks, w.weights, w.biases, chunk_rows=2048)
+        np.testing.assert_array_equal(Ym.cpu().double().numpy(), want)
+
+
+def test_one_hot_weights_make_the_output_a_pure_gather(lq):
+    w = WL.make_predict("gather", 5_000, 2, (50, 70), (3, 4), (4,), seed=WL.SEED0 + 78)
+    W = torch.zeros((9, 4))
+    for o, s in enumerate([8, 0, 3, 6]):
+        W[s, o] = 1
+    w.weights = [W]
+    want = torch.stack([w.dims[1][w.fks[1].long(), 3], w.X[:, 0], w.dims[0][w.fks[0].long(), 1],
+                        w.dims[1][w.fks[1].long(), 1]], dim=1)
+    w = to_dev(w)
+    _, Y = _run_fused(lq, w)
+    assert torch.equal(Y.cpu(), want)
+
+
+def test_all_keys_equal_and_strided_inputs(lq):
+    w = WL.make_predict("strided", 2_500, 4, (40, 60), (8, 8), (64, 1), seed=WL.SEED0 + 79,
+                        w_sigma=(0.2, 0.2))
+    w.fks = [torch.full((2_500,), 7, dtype=torch.int32), torch.full((2_500,), 59, dtype=torch.int32)]
+    want = _oracle(w)
+    w = to_dev(w)
+    # X, a dimension table and Y as column slices of wider buffers (ld > cols, unaligned rows)
+    Xw = torch.zeros((2_500, 7), device="cuda"); Xw[:, 1:5] = w.X
+    Dw = torch.zeros((40, 11), device="cuda"); Dw[:, 3:11] = w.dims[0]
+    Yw = torch.full((2_500, 3), -1.0, device="cuda")
+    P = lq.lq_project_dims([Dw[:, 3:11], w.dims[1]], w.weights[0], 4)
+    lq.lq_fused_join_predict(Xw[:, 1:5], w.fks, P, w.weights, Y=Yw[:, 1:2])
+    torch.cuda.synchronize()
+    assert_close(Yw[:, 1:2], want, TOL_F32, "strided fused")
+    assert (Yw[:, 0] == -1).all() and (Yw[:, 2] == -1).all()     # neighbours untouched
+    Ym = lq.lq_materialized_join_predict(Xw[:, 1:5], [Dw[:, 3:11], w.dims[1]], w.fks, w.weights)
+    torch.cuda.synchronize()
+    assert_close(Ym, want, TOL_F32, "strided materialised")
+
+
+def test_bf16_paths(lq):
+    for name, c_f, layers in (("bf16_linear", 8, (8,)), ("bf16_mlp", 0, (64, 4)), ("bf16_mlp16", 4, (256, 16))):
+        w = WL.make_predict(name, 6_007, c_f, (300, 1_000), (32, 64), layers, seed=WL.SEED0 + 80,
+                            dtype=torch.bfloat16, w_sigma=[0.1] * len(layers), bias=True)
+        want = _oracle(w)
+        w = to_dev(w)
+        for p_dtype, y_dtype in ((torch.bfloat16, torch.bfloat16), (torch.float32, torch.float32),
+                                 (torch.bfloat16, torch.float32)):
+            P, Y = _run_fused(lq, w, p_dtype=p_dtype, y_dtype=y_dtype)
+            assert Y.dtype == y_dtype and P[0].dtype == p_dtype
+            assert_close(Y, want, TOL_BF16, f"{name} P {p_dtype} Y {y_dtype}")
+        Ym = lq.lq_materialized_join_predict(w.X, w.dims, w.fks, w.weights, w.biases)
+        torch.cuda.synchronize()
+        assert_close(Ym, want, TOL_BF16, f"{name} materialised")
+
+
+def test_bf16_fk_indexing_is_bit_exact(lq):
+    """Small integers are exact in bf16; with one-hot-like integer weights the bf16 path must
+    return exactly the oracle's integers (|values| <= 256 stay representable)."""
+    w = WL.make_predict("bf16_exact", 4_001, 0, (50, 60), (8, 8), (8,), seed=WL.SEED0 + 81,
+                        dtype=torch.bfloat16, integer_valued=True)
+    want = _oracle(w)
+    assert np.abs(want).max() <= 256
+    w = to_dev(w)
+    _, Y = _run_fused(lq, w)
+    np.testing.assert_array_equal(Y.float().cpu().double().numpy(), want)
+
+
+def test_empty_fact_table(lq):
+    w = to_dev(WL.make_predict("empty", 0, 4, (10,), (4,), (8, 2), seed=1))
+    P, Y = _run_fused(lq, w)
+    assert Y.shape == (0, 2)
+    Ym = lq.lq_materialized_join_predict(w.X, w.dims, w.fks, w.weights, w.biases)
+    assert Ym.shape == (0, 2)
+
+
+def test_check_fks_flag(lq):
+    w = to_dev(WL.make_predict("fkcheck", 5_000, 4, (10, 20), (4, 4), (8,), seed=2))
+    P = lq.lq_project_dims(w.dims, w.weights[0], 4)
+    Y0 = lq.lq_fused_join_predict(w.X, w.fks, P, w.weights, flags=lq.LQ_CHECK_FKS)
+    torch.cuda.synchronize()
+    bad = [w.fks[0], w.fks[1].clone()]
+    bad[1][4_321] = 20
+    Y = torch.full_like(Y0, 7.0)
+    with pytest.raises(lq.LQError) as e:
+        lq.lq_fused_join_predict(w.X, bad, P, w.weights, Y=Y, flags=lq.LQ_CHECK_FKS)
+    assert e.value.status == "LQ_ERR_FK_RANGE"
+    torch.cuda.synchronize()
+    assert (Y == 7.0).all()                                  # outputs untouched on error
+    bad[1][4_321] = -1
+    with pytest.raises(lq.LQError):
+        lq.lq_materialized_join_predict(w.X, w.dims, bad, w.weights, flags=lq.LQ_CHECK_FKS)
+
+
+def test_materialised_chunking_does_not_change_results(lq):
+    w = WL.make_predict("chunks", 10_001, 4, (100, 300), (16, 16), (32, 2), seed=3, w_sigma=(0.2, 0.2))
+    want = _oracle(w)
+    w = to_dev(w)
+    for chunk in (256, 1_024, 16_384):
+        Y = lq.lq_materialized_join_predict(w.X, w.dims, w.fks, w.weights, chunk_rows=chunk)
+        torch.cuda.synchronize()
+        assert_close(Y, want, TOL_F32, f"chunk {chunk}")

@@ -1,0 +1,154 @@
+"""CPU-only checks: the C-ABI library loads, exports every declared symbol, and its host-side
+validation rejects bad arguments before anything is enqueued (no GPU needed: every call here
+fails validation, so no kernel is launched and no device pointer is dereferenced)."""
+import ctypes
+import os
+import re
+
+import pytest
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+HEADER = os.path.join(ROOT, "include", "lq.h")
+LIB = os.path.join(ROOT, "paper_2306_08367_amd", "liblq.so")
+
+pytestmark = pytest.mark.skipif(not os.path.exists(LIB), reason="liblq.so not built")
+
+
+def declared_functions():
+    text = open(HEADER).read()
+    text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
+    return sorted(set(re.findall(r"\b(lq_[a-z_]+)\s*\(", text)))
+
+
+def test_library_exports_every_declared_symbol():
+    lib = ctypes.CDLL(LIB)
+    names = declared_functions()
+    assert {"lq_project_dims", "lq_fused_join_predict", "lq_materialized_join_predict",
+            "lq_masked_groupby_sum", "lq_workspace_bytes", "lq_groupby_workspace_bytes",
+            "lq_stream_copy", "lq_last_error", "lq_version"} <= set(names)
+    for n in names:
+        assert hasattr(lib, n), f"{n} is declared in lq.h but not exported"
+
+
+def _binding():
+    from paper_2306_08367_amd import binding
+    return binding
+
+
+def test_struct_layout_matches_the_header():
+    b = _binding()
+    # void* (8) + int64 (8) + int32 (4) + pad (4) + int64 (8) + int32 (4) + pad (4)
+    assert ctypes.sizeof(b.lq_mat) == 40
+    assert b.lq_mat.ld.offset == 24 and b.lq_mat.dtype.offset == 32
+    assert b.lq_star.fact.offset == 8 and b.lq_star.n_dims.offset == 48
+    assert b.lq_star.dims.offset == 56 and b.lq_star.fks.offset == 64
+    assert b.lq_model.W.offset == 8 and b.lq_model.bias.offset == 16
+
+
+FAKE = 0x10000   # non-NULL, aligned; never dereferenced because validation fails first
+
+
+def _star_model(b, n=10, c_f=2, dims=((5, 3),), l=(4,), dtype=0, w_rows=None):
+    K = len(dims)
+    dims_arr = (b.lq_mat * max(1, K))()
+    for k, (r, c) in enumerate(dims):
+        dims_arr[k] = b.lq_mat(FAKE, r, c, c, dtype)
+    fks = (ctypes.c_void_p * max(1, K))(*([FAKE] * K))
+    star = b.lq_star(n, b.lq_mat(FAKE, n, c_f, max(c_f, 1), dtype), K, dims_arr, fks)
+    kw = c_f + sum(c for _, c in dims)
+    W = (b.lq_mat * len(l))()
+    rows = kw if w_rows is None else w_rows
+    for j, lo in enumerate(l):
+        W[j] = b.lq_mat(FAKE, rows, lo, lo, dtype)
+        rows = lo
+    bias = (ctypes.c_void_p * len(l))()
+    model = b.lq_model(len(l), W, bias)
+    return star, model, (dims_arr, fks, W, bias)
+
+
+def test_project_dims_rejects_bad_arguments():
+    b = _binding()
+    lib = b._lib
+    star, model, keep = _star_model(b, w_rows=4)            # joined width is 5
+    P = (b.lq_mat * 1)(b.lq_mat(FAKE, 5, 4, 4, 0))
+    assert lib.lq_project_dims(ctypes.byref(star), ctypes.byref(model), P, None) == 2
+    assert "joined width" in b.lq_last_error()
+    star, model, keep = _star_model(b)
+    P = (b.lq_mat * 1)(b.lq_mat(FAKE, 6, 4, 4, 0))           # wrong row count
+    assert lib.lq_project_dims(ctypes.byref(star), ctypes.byref(model), P, None) == 2
+    P = (b.lq_mat * 1)(b.lq_mat(FAKE, 5, 4, 4, 1))           # bf16 P for an f32 model
+    assert lib.lq_project_dims(ctypes.byref(star), ctypes.byref(model), P, None) == 3
+    assert lib.lq_project_dims(None, ctypes.byref(model), P, None) == 1
+    P = (b.lq_mat * 1)(b.lq_mat(None, 5, 4, 4, 0))
+    assert lib.lq_project_dims(ctypes.byref(star), ctypes.byref(model), P, None) == 1
+    star, model, keep = _star_model(b, l=(4, 3, 2))
+    keep[2][2].rows = 5                                       # layer widths do not chain
+    assert lib.lq_project_dims(ctypes.byref(star), ctypes.byref(model), P, None) == 2
+
+
+def test_fused_rejects_bad_arguments():
+    b = _binding()
+    lib = b._lib
+    star, model, keep = _star_model(b)
+    P = (b.lq_mat * 1)(b.lq_mat(FAKE, 5, 4, 4, 0))
+    Y = b.lq_mat(FAKE, 10, 3, 3, 0)                           # l_out is 4
+    args = (ctypes.byref(star), ctypes.byref(model), P, ctypes.byref(Y), None, 0, 0, None)
+    assert lib.lq_fused_join_predict(*args) == 2
+    Y = b.lq_mat(FAKE, 10, 4, 4, 1)                           # bf16 Y for an f32 model
+    args = (ctypes.byref(star), ctypes.byref(model), P, ctypes.byref(Y), None, 0, 0, None)
+    assert lib.lq_fused_join_predict(*args) == 3
+    Y = b.lq_mat(FAKE, 10, 4, 2, 0)                           # ld < cols
+    args = (ctypes.byref(star), ctypes.byref(model), P, ctypes.byref(Y), None, 0, 0, None)
+    assert lib.lq_fused_join_predict(*args) == 2
+    Y = b.lq_mat(FAKE, 10, 4, 4, 0)
+    args = (ctypes.byref(star), ctypes.byref(model), P, ctypes.byref(Y), None, 0, b.LQ_CHECK_FKS, None)
+    assert lib.lq_fused_join_predict(*args) == 4              # key check needs a workspace
+    star.n_dims = 9
+    args = (ctypes.byref(star), ctypes.byref(model), P, ctypes.byref(Y), None, 0, 0, None)
+    assert lib.lq_fused_join_predict(*args) == 2
+    assert b.lq_last_error() != ""
+
+
+def test_materialized_rejects_small_or_missing_workspace():
+    b = _binding()
+    lib = b._lib
+    star, model, keep = _star_model(b)
+    Y = b.lq_mat(FAKE, 10, 4, 4, 0)
+    assert lib.lq_materialized_join_predict(ctypes.byref(star), ctypes.byref(model), ctypes.byref(Y),
+                                            None, 0, 0, None) == 4
+    assert lib.lq_materialized_join_predict(ctypes.byref(star), ctypes.byref(model), ctypes.byref(Y),
+                                            0x10000, 1024, 0, None) == 4
+    need = lib.lq_workspace_bytes(b.LQ_CALL_MATERIALIZED, ctypes.byref(star), ctypes.byref(model), 256)
+    assert need >= 256 * 5 * 4
+    assert lib.lq_workspace_bytes(99, ctypes.byref(star), ctypes.byref(model), 256) == 0
+
+
+def test_groupby_rejects_bad_arguments():
+    b = _binding()
+    lib = b._lib
+    vp, i64, i32 = ctypes.c_void_p, ctypes.c_int64, ctypes.c_int32
+    fks = (vp * 2)(FAKE, FAKE)
+    rows = (i64 * 2)(10, 20)
+    codes = (vp * 2)(FAKE, FAKE)
+    meas = (vp * 1)(FAKE)
+
+    def call(card, n_meas=1, ws=FAKE, ws_bytes=1 << 20, sums=FAKE, K=2):
+        return lib.lq_masked_groupby_sum(100, K, fks, rows, None, codes, (i32 * 2)(*card), None,
+                                         n_meas, meas, sums, None, ws, ws_bytes, 0, None)
+    assert call((100, 100)) == 6                              # 10,000 groups > 8192
+    assert call((0, 5)) == 2
+    assert call((5, 5), n_meas=0) == 2
+    assert call((5, 5), n_meas=5) == 2
+    assert call((5, 5), ws=None) == 4
+    assert call((5, 5), ws_bytes=16) == 4
+    assert call((5, 5), sums=None) == 1
+    assert call((5, 5), K=9) == 2
+    assert b.lq_groupby_workspace_bytes([10, 20], [5, 5], 1) >= 60
+
+
+def test_stream_copy_rejects_misaligned():
+    b = _binding()
+    assert b._lib.lq_stream_copy(0x10008, 0x20000, 64, None) == 2
+    assert b._lib.lq_stream_copy(0x10000, 0x20000, 60, None) == 2
+    assert b._lib.lq_stream_copy(None, 0x20000, 64, None) == 1
+    assert b._lib.lq_stream_copy(None, None, 0, None) == 0
