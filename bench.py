@@ -1,0 +1,234 @@
+#!/usr/bin/env python3
+"""Benchmark of the fused star-join + prediction hot path on one MI355X.
+
+One "step" = one pass of the method over the workload, inputs resident in HBM:
+pre-fusion (lq_project_dims) followed by the join-computation stage
+(lq_fused_join_predict).  The headline workload is the 2-layer-MLP star schema
+(10M fact rows, dimensions of 1e3/1e4/1e5 rows, MLP 100 -> 64 -> 1, fp32).
+
+Prints ONE JSON line.  Besides the contract fields it carries
+  roofline      - the dominant kernel (the fused gather kernel) against the HBM roof,
+                  from algorithmic bytes / its own event-timed duration
+  cpu_baseline  - the fp64 CPU oracle timed on a bounded prefix of the same workload
+  stages, materialized, groupby_c3, fused_c4, stream_copy - the other numbers the
+                  method is judged by (each timed with events on the launch stream).
+"""
+from __future__ import annotations
+
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+HBM_PEAK_GBPS = 8000.0          # MI355X published HBM3E bandwidth
+TRAFFIC_FILE = os.path.join(ROOT, "profiles", "hbm_traffic.json")
+
+
+def _events(n):
+    import torch
+    return [torch.cuda.Event(enable_timing=True) for _ in range(n)]
+
+
+def time_call(fn, iters, warmup):
+    """Average milliseconds of fn() over `iters` runs, event-timed on the current stream."""
+    import torch
+    for _ in range(warmup):
+        fn()
+    torch.cuda.synchronize()
+    a, b = _events(iters), _events(iters)
+    for i in range(iters):
+        a[i].record()
+        fn()
+        b[i].record()
+    torch.cuda.synchronize()
+    ts = sorted(x.elapsed_time(y) for x, y in zip(a, b))
+    return sum(ts) / len(ts), ts[0], ts[len(ts) // 2]
+
+
+def measured_traffic(key):
+    """HBM bytes per launch measured with rocprofv3 counters (committed summary), or None."""
+    try:
+        with open(TRAFFIC_FILE) as f:
+            return json.load(f).get(key)
+    except Exception:
+        return None
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=20)
+    ap.add_argument("--warmup", type=int, default=3)
+    ap.add_argument("--rows", type=int, default=10_000_000, help="fact rows of the headline workload")
+    ap.add_argument("--no-extras", action="store_true", help="skip materialised / group-by / skewed legs")
+    ap.add_argument("--no-cpu", action="store_true", help="skip the CPU oracle baseline")
+    ap.add_argument("--only", default="", help="run a single leg for profiling: fused|groupby|c4|materialized|copy")
+    args = ap.parse_args()
+    if args.gpus != 1:
+        sys.exit("bench.py: this build is single-GPU by design (no collectives, no sharding); "
+                 "run with --gpus 1")
+
+    import torch
+    import paper_2306_08367_amd as lq
+    from tests.helpers import to_dev
+    from workloads import star as WL
+
+    assert torch.cuda.is_available(), "bench.py needs a GPU"
+    dev = torch.device("cuda:0")
+    torch.cuda.set_device(dev)
+    out = {}
+
+    # ---------------------------------------------------------------- headline: fused MLP
+    n = args.rows
+    w = WL.c2_mlp(device=dev, n=n)
+    P = [torch.empty((d.shape[0], 64), dtype=torch.float32, device=dev) for d in w.dims]
+    Y = torch.empty((n, 1), dtype=torch.float32, device=dev)
+
+    def project():
+        lq.lq_project_dims(w.dims, w.weights[0], w.c_f, P=P)
+
+    def fused():
+        lq.lq_fused_join_predict(w.X, w.fks, P, w.weights, w.biases, Y=Y)
+
+    def step():
+        project()
+        fused()
+
+    if args.only in ("", "fused"):
+        for _ in range(args.warmup):
+            step()
+        torch.cuda.synchronize()
+        ea, eb = _events(args.steps), _events(args.steps)
+        t0 = time.perf_counter()
+        for i in range(args.steps):
+            project()
+            ea[i].record()
+            fused()
+            eb[i].record()
+        torch.cuda.synchronize()
+        wall = time.perf_counter() - t0
+        ms_step = wall * 1e3 / args.steps
+        fused_ms = sum(a.elapsed_time(b) for a, b in zip(ea, eb)) / args.steps
+        proj_ms, _, _ = time_call(project, 10, 2)
+        alg_bytes = 32.0 * n                      # 16 B fact columns + 12 B keys + 4 B output per row
+        gather_bytes = 768.0 * n                  # 3 rows of 64 fp32 from the projected tables
+        achieved = alg_bytes / (fused_ms * 1e-3) / 1e9
+        out.update({
+            "metric": "fact rows/s, fused join+predict",
+            "value": n * args.steps / wall,
+            "unit": "rows/s",
+            "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
+            "ms_per_step": ms_step,
+            "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+            "dtype": "f32", "data": "synthetic",
+            "config": {"workload": "c2_mlp: fused join + 2-layer MLP, fact 10M x 4 fp32, dims "
+                                   "1e3/1e4/1e5 x 32 fp32, uniform int32 keys, MLP 100->64 ReLU ->1",
+                       "fact_rows": n, "step": "lq_project_dims + lq_fused_join_predict"},
+            "roofline": {"bound": "hbm", "kernel": "fused_join_predict (gather + MLP epilogue)",
+                         "achieved": achieved, "peak": HBM_PEAK_GBPS, "unit": "GB/s",
+                         "frac": achieved / HBM_PEAK_GBPS,
+                         "traffic": measured_traffic("fused_c2"),
+                         "algorithmic_bytes_per_row": 32,
+                         "note": "768 B/row are gathered from L2/Infinity-Cache-resident projected "
+                                 "tables; that gather, not HBM, is the binding roof of this workload",
+                         "gather_GBps": gather_bytes / (fused_ms * 1e-3) / 1e9},
+            "stages": {"project_dims_ms": proj_ms, "fused_join_predict_ms": fused_ms,
+                       "fused_rows_per_s": n / (fused_ms * 1e-3)},
+        })
+
+    # ---------------------------------------------------------------- CPU oracle baseline
+    if args.only == "" and not args.no_cpu:
+        from oracle import lq_oracle as O
+        sample = min(n, 1 << 21)
+        Xs = w.X[:sample].cpu()
+        fs = [f[:sample].cpu() for f in w.fks]
+        ds = [d.cpu() for d in w.dims]
+        Ws = [x.cpu() for x in w.weights]
+        threads = min(O.max_threads(), 16, os.cpu_count() or 1)
+        t0 = time.perf_counter()
+        O.join_predict(Xs, ds, fs, Ws, None, nthreads=threads)
+        dt = time.perf_counter() - t0
+        out["cpu_baseline"] = {"value": sample / dt, "unit": "rows/s", "cores": threads, "kind": "oracle",
+                               "sample": f"first {sample} fact rows of the same workload (fp64, "
+                                         "tuple materialised then MLP), includes the exact fp32->fp64 "
+                                         "widening of the inputs; cost is linear in rows"}
+
+    # ---------------------------------------------------------------- stream-copy yardstick
+    if args.only in ("", "copy"):
+        nb = 2 << 30
+        src = torch.empty(nb, dtype=torch.uint8, device=dev)
+        dst = torch.empty(nb, dtype=torch.uint8, device=dev)
+        src.zero_()
+        ms, _, _ = time_call(lambda: lq.lq_stream_copy(dst, src), 10, 2)
+        out["stream_copy"] = {"GBps_read_plus_write": 2 * nb / (ms * 1e-3) / 1e9, "bytes_copied": nb}
+        del src, dst
+
+    # ---------------------------------------------------------------- non-fused pipeline
+    if (args.only == "" and not args.no_extras) or args.only == "materialized":
+        chunk = 1 << 22
+        ws_bytes = lq.lq_workspace_bytes(lq.binding.LQ_CALL_MATERIALIZED, w.k, w.weights, chunk)
+        ws = torch.empty(ws_bytes, dtype=torch.uint8, device=dev)
+        Ym = torch.empty_like(Y)
+        ms, _, _ = time_call(lambda: lq.lq_materialized_join_predict(
+            w.X, w.dims, w.fks, w.weights, w.biases, Y=Ym, ws=ws), 3, 1)
+        out["materialized"] = {"rows_per_s": n / (ms * 1e-3), "ms": ms, "chunk_rows": chunk}
+        if "stages" in out:
+            out["materialized"]["fused_speedup"] = ms / (out["stages"]["fused_join_predict_ms"]
+                                                        + out["stages"]["project_dims_ms"])
+        del ws, Ym
+    del w, P, Y
+    torch.cuda.empty_cache()
+
+    # ---------------------------------------------------------------- LA group-by (SSB-sf1 shape)
+    if (args.only == "" and not args.no_extras) or args.only == "groupby":
+        g = WL.c3_groupby(device=dev)
+        # rotate over several copies of the fact columns so that repeats are not served from cache
+        copies = 6
+        cols = [([f.clone() for f in g.fks], [m.clone() for m in g.measures]) for _ in range(copies)]
+        ws = torch.empty(lq.lq_groupby_workspace_bytes(g.dim_rows, g.group_card, 1), dtype=torch.uint8, device=dev)
+        sums = torch.empty((1, g.G), dtype=torch.int64, device=dev)
+        counts = torch.empty((g.G,), dtype=torch.int64, device=dev)
+        it = [0]
+
+        def gb():
+            fk, me = cols[it[0] % copies]
+            it[0] += 1
+            lq.lq_masked_groupby_sum(fk, g.dim_rows, g.dim_mask, g.dim_code, g.group_card, None, me,
+                                     sums=sums, counts=counts, ws=ws)
+        ms, mn, med = time_call(gb, 30, 6)
+        gbps = 20.0 * g.n / (ms * 1e-3) / 1e9
+        out["groupby_c3"] = {"rows_per_s": g.n / (ms * 1e-3), "ms": ms, "ms_min": mn, "fact_rows": g.n,
+                             "roofline": {"bound": "hbm", "achieved": gbps, "peak": HBM_PEAK_GBPS,
+                                          "unit": "GB/s", "frac": gbps / HBM_PEAK_GBPS,
+                                          "algorithmic_bytes_per_row": 20,
+                                          "traffic": measured_traffic("groupby_c3")}}
+        del g, cols
+        torch.cuda.empty_cache()
+
+    # ---------------------------------------------------------------- skewed linear model (HBM-bound)
+    if (args.only == "" and not args.no_extras) or args.only == "c4":
+        n4 = 100_000_000
+        w4 = WL.c4_skewed(device=dev, n=n4)
+        P4 = [torch.empty((d.shape[0], 4), dtype=torch.float32, device=dev) for d in w4.dims]
+        Y4 = torch.empty((n4, 4), dtype=torch.float32, device=dev)
+        pms, _, _ = time_call(lambda: lq.lq_project_dims(w4.dims, w4.weights[0], w4.c_f, P=P4), 5, 1)
+        ms, mn, _ = time_call(lambda: lq.lq_fused_join_predict(w4.X, w4.fks, P4, w4.weights, None, Y=Y4), 10, 2)
+        gbps = 56.0 * n4 / (ms * 1e-3) / 1e9
+        out["fused_c4"] = {"rows_per_s": n4 / (ms * 1e-3), "ms": ms, "project_dims_ms": pms, "fact_rows": n4,
+                           "roofline": {"bound": "hbm", "achieved": gbps, "peak": HBM_PEAK_GBPS,
+                                        "unit": "GB/s", "frac": gbps / HBM_PEAK_GBPS,
+                                        "algorithmic_bytes_per_row": 56,
+                                        "traffic": measured_traffic("fused_c4")},
+                           "project_dims_GBps": 2 * 1_000_000 * 128 * 4 / (pms * 1e-3) / 1e9}
+        del w4, P4, Y4
+
+    print(json.dumps(out))
+
+
+if __name__ == "__main__":
+    main()

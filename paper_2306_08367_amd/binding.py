@@ -107,6 +107,8 @@ def _mat(t: Optional[torch.Tensor], rows: int = 0, cols: int = 0, dtype: int = L
         return lq_mat(None, rows, cols, max(cols, 1), dtype)
     if t.dim() != 2:
         raise ValueError("matrices are 2-D tensors")
+    if t.numel() == 0:
+        return lq_mat(None, int(t.shape[0]), int(t.shape[1]), max(int(t.shape[1]), 1), _dtype_code(t))
     if t.shape[1] > 1 and t.stride(1) != 1:
         raise ValueError("matrix columns must be contiguous (row-major)")
     ld = t.stride(0) if t.shape[0] > 1 else max(int(t.shape[1]), 1)
