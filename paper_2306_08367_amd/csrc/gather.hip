@@ -63,11 +63,12 @@ __global__ __launch_bounds__(256) void zero_flag_kernel(int32_t* flag) {
   if (threadIdx.x == 0 && blockIdx.x == 0) *flag = 0;
 }
 
+// One 16-byte element per thread: workgroups sweep memory in launch order, which keeps the
+// set of open DRAM pages compact (measurably faster here than a grid-stride loop).
 __global__ __launch_bounds__(256) void copy_kernel(uint4* __restrict__ dst,
                                                    const uint4* __restrict__ src, int64_t n16) {
-  const int64_t stride = static_cast<int64_t>(gridDim.x) * blockDim.x;
-  for (int64_t i = static_cast<int64_t>(blockIdx.x) * blockDim.x + threadIdx.x; i < n16; i += stride)
-    dst[i] = src[i];
+  const int64_t i = static_cast<int64_t>(blockIdx.x) * blockDim.x + threadIdx.x;
+  if (i < n16) dst[i] = src[i];
 }
 
 }  // namespace
@@ -113,12 +114,16 @@ int launch_check_fks(int64_t n, int32_t K, const int32_t* const* fks, const int6
 }
 
 int launch_copy(void* dst, const void* src, size_t bytes, hipStream_t s) {
-  const int64_t n16 = static_cast<int64_t>(bytes / 16);
-  if (n16 == 0) return LQ_OK;
-  const int64_t blocks = std::min<int64_t>((n16 + 255) / 256, static_cast<int64_t>(num_cus()) * 16);
-  hipLaunchKernelGGL(copy_kernel, dim3(static_cast<unsigned>(blocks)), dim3(256), 0, s,
-                     static_cast<uint4*>(dst), static_cast<const uint4*>(src), n16);
-  LQ_LAUNCH_CHECK("copy_kernel");
+  int64_t n16 = static_cast<int64_t>(bytes / 16);
+  const uint4* sp = static_cast<const uint4*>(src);
+  uint4* dp = static_cast<uint4*>(dst);
+  const int64_t per_launch = static_cast<int64_t>(1) << 37 >> 4;   // 128 GiB per launch keeps the grid below 2^31
+  while (n16 > 0) {
+    const int64_t m = std::min<int64_t>(n16, per_launch);
+    hipLaunchKernelGGL(copy_kernel, dim3(static_cast<unsigned>((m + 255) / 256)), dim3(256), 0, s, dp, sp, m);
+    LQ_LAUNCH_CHECK("copy_kernel");
+    sp += m; dp += m; n16 -= m;
+  }
   return LQ_OK;
 }
 
