@@ -128,7 +128,7 @@ constexpr int VEC_THREADS = 256;
 // TX: dtype of X / W / bias, TP: dtype of P, TY: dtype of Y.
 // LPR lanes per fact row (power of two, <= 64), VEC hidden columns per lane: l_1 == LPR * VEC.
 // CF: compile-time c_f.  NL: 1 (linear) or 2 (ReLU then W_2 with L2 outputs).
-template <typename TX, typename TP, typename TY, int VEC, int LPR, int CF, int NL, int L2>
+template <typename TX, typename TP, typename TY, int VEC, int LPR, int CF, int NL, int L2, bool XV>
 __global__ __launch_bounds__(VEC_THREADS) void fused_vec_kernel(PredictArgs a) {
   constexpr int RPW = 64 / LPR;                 // fact rows per wavefront pass
   constexpr int RPB = RPW * (VEC_THREADS / 64); // per workgroup pass
@@ -175,12 +175,21 @@ __global__ __launch_bounds__(VEC_THREADS) void fused_vec_kernel(PredictArgs a) {
     for (int v = 0; v < VEC; ++v) z[v] = b1[v];
     if (CF > 0) {
       const TX* xr = X + rr * a.ldx;
+      float xq[CF > 0 ? CF : 1];
+      if constexpr (XV) {   // fp32 fact columns in 16-byte pieces
 #pragma unroll
-      for (int q = 0; q < CF; ++q) {
-        const float xq = Elem<TX>::load(xr + q);
+        for (int q = 0; q < CF; q += 4) {
+          const float4 t = *reinterpret_cast<const float4*>(xr + q);
+          xq[q] = t.x; xq[q + 1] = t.y; xq[q + 2] = t.z; xq[q + 3] = t.w;
+        }
+      } else {
 #pragma unroll
-        for (int v = 0; v < VEC; ++v) z[v] = fmaf(xq, wf[q][v], z[v]);
+        for (int q = 0; q < CF; ++q) xq[q] = Elem<TX>::load(xr + q);
       }
+#pragma unroll
+      for (int q = 0; q < CF; ++q)
+#pragma unroll
+        for (int v = 0; v < VEC; ++v) z[v] = fmaf(xq[q], wf[q][v], z[v]);
     }
     for (int k = 0; k < a.K; ++k) {
       const int64_t j = a.fk[k][rr];
@@ -219,10 +228,17 @@ template <typename TX, typename TP, typename TY, int VEC, int LPR, int CF, int N
 int launch_vec_inst(const PredictArgs& a, hipStream_t s) {
   constexpr int RPB = (64 / LPR) * (VEC_THREADS / 64);
   const int64_t n_pass = (a.n + RPB - 1) / RPB;
-  const int64_t blocks = std::min<int64_t>(n_pass, static_cast<int64_t>(num_cus()) * 8);
+  // One pass per workgroup: workgroups then sweep the fact table in launch order, which streams
+  // from HBM measurably faster than a strided persistent loop.
+  const int64_t blocks = std::min<int64_t>(n_pass, 0x7fffffffLL);
   if (blocks <= 0) return LQ_OK;
-  hipLaunchKernelGGL((fused_vec_kernel<TX, TP, TY, VEC, LPR, CF, NL, L2>),
-                     dim3(static_cast<unsigned>(blocks)), dim3(VEC_THREADS), 0, s, a);
+  constexpr bool can_xv = sizeof(TX) == 4 && CF > 0 && CF % 4 == 0;
+  if (can_xv && aligned(a.X, 16) && a.ldx % 4 == 0)
+    hipLaunchKernelGGL((fused_vec_kernel<TX, TP, TY, VEC, LPR, CF, NL, L2, can_xv>),
+                       dim3(static_cast<unsigned>(blocks)), dim3(VEC_THREADS), 0, s, a);
+  else
+    hipLaunchKernelGGL((fused_vec_kernel<TX, TP, TY, VEC, LPR, CF, NL, L2, false>),
+                       dim3(static_cast<unsigned>(blocks)), dim3(VEC_THREADS), 0, s, a);
   LQ_LAUNCH_CHECK("fused_vec_kernel");
   return LQ_OK;
 }

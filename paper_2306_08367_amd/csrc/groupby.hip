@@ -19,6 +19,8 @@
 namespace lq {
 namespace {
 
+typedef int v4i __attribute__((ext_vector_type(4)));
+
 enum DimKind : int32_t { DK_NONE = 0, DK_BITMAP = 1, DK_BYTE = 2, DK_U16 = 3 };
 
 struct GbDim {
@@ -48,37 +50,53 @@ struct GbArgs {
 
 // ---------------------------------------------------------------- pack ------------------
 
+// Work is cut into 256-thread units: unit u of dimension k covers 64*4 = 256 ... see unit_count().
+// BITMAP: a wavefront turns 64 mask bytes into one 64-bit ballot word per step.
+// BYTE / U16: one thread builds 4 consecutive entries and stores them as one word (pair).
 __global__ __launch_bounds__(256) void pack_kernel(GbArgs a) {
   const int64_t gtid = static_cast<int64_t>(blockIdx.x) * blockDim.x + threadIdx.x;
   const int64_t gstride = static_cast<int64_t>(gridDim.x) * blockDim.x;
   for (int64_t i = gtid; i < static_cast<int64_t>(a.M) * a.G; i += gstride) a.sums[i] = 0ull;
   if (a.counts)
     for (int64_t i = gtid; i < a.G; i += gstride) a.counts[i] = 0ull;
+  const int lane = threadIdx.x & 63;
+  const int64_t gwave = gtid >> 6, nwave = gstride >> 6;
   for (int k = 0; k < a.K; ++k) {
     const GbDim& d = a.d[k];
     if (d.kind == DK_BITMAP) {
-      uint32_t* out = reinterpret_cast<uint32_t*>(a.packed + d.off);
-      const int64_t words = d.bytes / 4;
-      for (int64_t w = gtid; w < words; w += gstride) {
-        uint32_t bits = 0;
-        const int64_t j0 = w * 32;
-        for (int b = 0; b < 32; ++b)
-          if (j0 + b < d.rows && d.mask[j0 + b]) bits |= 1u << b;
-        out[w] = bits;
+      unsigned long long* out = reinterpret_cast<unsigned long long*>(a.packed + d.off);
+      const int64_t steps = d.bytes / 8;               // 64 rows per step
+      for (int64_t q = gwave; q < steps; q += nwave) {
+        const int64_t j = q * 64 + lane;
+        const bool on = j < d.rows && d.mask[j] != 0;
+        const unsigned long long bits = __ballot(on);
+        if (lane == 0) out[q] = bits;
       }
     } else if (d.kind == DK_BYTE) {
-      uint8_t* out = a.packed + d.off;
-      for (int64_t j = gtid; j < d.bytes; j += gstride) {
-        uint8_t v = 0xff;
-        if (j < d.rows && (!d.mask || d.mask[j])) v = d.code ? static_cast<uint8_t>(d.code[j]) : 0;
-        out[j] = v;
+      uint32_t* out = reinterpret_cast<uint32_t*>(a.packed + d.off);
+      for (int64_t q = gtid; q < d.bytes / 4; q += gstride) {
+        uint32_t w = 0;
+#pragma unroll
+        for (int b = 0; b < 4; ++b) {
+          const int64_t j = q * 4 + b;
+          uint32_t v = 0xffu;
+          if (j < d.rows && (!d.mask || d.mask[j])) v = d.code ? static_cast<uint32_t>(d.code[j]) & 0xffu : 0u;
+          w |= v << (8 * b);
+        }
+        out[q] = w;
       }
     } else if (d.kind == DK_U16) {
-      uint16_t* out = reinterpret_cast<uint16_t*>(a.packed + d.off);
-      for (int64_t j = gtid; j < d.bytes / 2; j += gstride) {
-        uint16_t v = 0xffff;
-        if (j < d.rows && (!d.mask || d.mask[j])) v = static_cast<uint16_t>(d.code[j]);
-        out[j] = v;
+      uint32_t* out = reinterpret_cast<uint32_t*>(a.packed + d.off);
+      for (int64_t q = gtid; q < d.bytes / 4; q += gstride) {
+        uint32_t w = 0;
+#pragma unroll
+        for (int b = 0; b < 2; ++b) {
+          const int64_t j = q * 2 + b;
+          uint32_t v = 0xffffu;
+          if (j < d.rows && (!d.mask || d.mask[j])) v = static_cast<uint32_t>(d.code[j]) & 0xffffu;
+          w |= v << (16 * b);
+        }
+        out[q] = w;
       }
     }
   }
@@ -89,12 +107,12 @@ __global__ __launch_bounds__(256) void pack_kernel(GbArgs a) {
 constexpr int SCAN_THREADS = 1024;
 
 // One fact row: returns the group number, or -1 when the row is filtered out.
-template <bool LDS_TABLES>
-__device__ __forceinline__ int32_t classify(const GbArgs& a, const uint8_t* tab, const int32_t* fk) {
+template <int KMAX>
+__device__ __forceinline__ int32_t classify(const GbArgs& a, const uint8_t* tab, const int32_t (&fk)[KMAX]) {
   bool alive = true;
   int32_t g = 0;
 #pragma unroll
-  for (int k = 0; k < LQ_MAX_DIMS; ++k) {
+  for (int k = 0; k < KMAX; ++k) {
     if (k >= a.K) break;
     const GbDim& d = a.d[k];
     const int32_t j = fk[k];
@@ -117,14 +135,83 @@ __device__ __forceinline__ int32_t classify(const GbArgs& a, const uint8_t* tab,
   return alive ? g : -1;
 }
 
-template <bool LDS_TABLES, int VEC>
-__global__ __launch_bounds__(SCAN_THREADS) void scan_kernel(GbArgs a) {
+// Key columns (and fact mask) of VEC consecutive fact rows.
+template <int VEC, int KMAX> struct KeyRegs {
+  int32_t fk[VEC][KMAX];
+  uint32_t fm;
+};
+
+template <int VEC, int KMAX>
+__device__ __forceinline__ void load_keys(const GbArgs& a, int64_t v, KeyRegs<VEC, KMAX>& r) {
+  r.fm = 0x01010101u;
+  if constexpr (VEC == 4) {
+#pragma unroll
+    for (int k = 0; k < KMAX; ++k) {
+      if (k >= a.K) break;
+      const v4i t = __builtin_nontemporal_load(reinterpret_cast<const v4i*>(a.d[k].fk) + v);
+      r.fk[0][k] = t[0]; r.fk[1][k] = t[1]; r.fk[2][k] = t[2]; r.fk[3][k] = t[3];
+    }
+    if (a.fact_mask) r.fm = reinterpret_cast<const uint32_t*>(a.fact_mask)[v];
+  } else {
+#pragma unroll
+    for (int k = 0; k < KMAX; ++k) {
+      if (k >= a.K) break;
+      r.fk[0][k] = a.d[k].fk[v];
+    }
+    if (a.fact_mask) r.fm = a.fact_mask[v];
+  }
+}
+
+template <int VEC, int KMAX>
+__device__ __forceinline__ void consume(const GbArgs& a, const uint8_t* tab, unsigned long long* acc,
+                                        int64_t v, const KeyRegs<VEC, KMAX>& r) {
+  int32_t g[VEC];
+  bool any = false;
+#pragma unroll
+  for (int q = 0; q < VEC; ++q) {
+    g[q] = classify<KMAX>(a, tab, r.fk[q]);
+    if (((r.fm >> (8 * q)) & 0xffu) == 0) g[q] = -1;
+    any = any || g[q] >= 0;
+  }
+  if (!any) return;   // the measure columns are only touched where a row survives
+#pragma unroll
+  for (int m = 0; m < LQ_MAX_MEASURES; ++m) {
+    if (m >= a.M) break;
+    int32_t val[VEC];
+    if constexpr (VEC == 4) {
+      const int4 t = reinterpret_cast<const int4*>(a.meas[m])[v];
+      val[0] = t.x; val[1] = t.y; val[2] = t.z; val[3] = t.w;
+    } else {
+      val[0] = a.meas[m][v];
+    }
+#pragma unroll
+    for (int q = 0; q < VEC; ++q)
+      if (g[q] >= 0)
+        atomicAdd(&acc[m * a.G + g[q]], static_cast<unsigned long long>(static_cast<long long>(val[q])));
+  }
+#pragma unroll
+  for (int q = 0; q < VEC; ++q)
+    if (g[q] >= 0) atomicAdd(&acc[a.M * a.G + g[q]], 1ull);
+}
+
+// Workgroup b streams the VEC-row groups [b * per_block, (b + 1) * per_block): consecutive
+// workgroups sweep memory in order.  The first keys are requested before the side tables are
+// copied into LDS, and each iteration requests the next keys before it consumes its own.
+template <bool LDS_TABLES, int VEC, int KMAX>
+__global__ __launch_bounds__(SCAN_THREADS) void scan_kernel(GbArgs a, int64_t per_block) {
   extern __shared__ __align__(16) uint8_t smem[];
   // layout: accumulators [(M+1) x G] int64, then (LDS_TABLES) the packed tables
   unsigned long long* acc = reinterpret_cast<unsigned long long*>(smem);
   const int n_acc = (a.M + 1) * a.G;
   uint8_t* tab_lds = smem + round_up(static_cast<size_t>(n_acc) * 8, 16);
   const int tid = threadIdx.x;
+
+  const int64_t n_vec = a.n / VEC;   // full VEC-row groups; the tail is done by workgroup 0
+  const int64_t v_begin = static_cast<int64_t>(blockIdx.x) * per_block;
+  const int64_t v_end = min(n_vec, v_begin + per_block);
+  int64_t v = v_begin + tid;
+  KeyRegs<VEC, KMAX> cur, nxt;
+  if (v < v_end) load_keys<VEC, KMAX>(a, v, cur);
 
   for (int i = tid; i < n_acc; i += SCAN_THREADS) acc[i] = 0ull;
   if (LDS_TABLES) {
@@ -135,68 +222,24 @@ __global__ __launch_bounds__(SCAN_THREADS) void scan_kernel(GbArgs a) {
   __syncthreads();
   const uint8_t* tab = LDS_TABLES ? tab_lds : a.packed;
 
-  const int64_t n_vec = a.n / VEC;   // full VEC-row groups; the tail is done by workgroup 0
-  const int64_t gstride = static_cast<int64_t>(gridDim.x) * SCAN_THREADS;
-  for (int64_t v = static_cast<int64_t>(blockIdx.x) * SCAN_THREADS + tid; v < n_vec; v += gstride) {
-    int32_t fk[VEC][LQ_MAX_DIMS];
-    uint32_t fm = 0x01010101u;
-    if constexpr (VEC == 4) {
-#pragma unroll
-      for (int k = 0; k < LQ_MAX_DIMS; ++k) {
-        if (k >= a.K) break;
-        const int4 t = reinterpret_cast<const int4*>(a.d[k].fk)[v];
-        fk[0][k] = t.x; fk[1][k] = t.y; fk[2][k] = t.z; fk[3][k] = t.w;
-      }
-      if (a.fact_mask) fm = reinterpret_cast<const uint32_t*>(a.fact_mask)[v];
-    } else {
-#pragma unroll
-      for (int k = 0; k < LQ_MAX_DIMS; ++k) {
-        if (k >= a.K) break;
-        fk[0][k] = a.d[k].fk[v];
-      }
-      if (a.fact_mask) fm = a.fact_mask[v];
-    }
-    int32_t g[VEC];
-    bool any = false;
-#pragma unroll
-    for (int r = 0; r < VEC; ++r) {
-      g[r] = classify<LDS_TABLES>(a, tab, fk[r]);
-      if (((fm >> (8 * r)) & 0xffu) == 0) g[r] = -1;
-      any = any || g[r] >= 0;
-    }
-    if (any) {
-#pragma unroll
-      for (int m = 0; m < LQ_MAX_MEASURES; ++m) {
-        if (m >= a.M) break;
-        int32_t val[VEC];
-        if constexpr (VEC == 4) {
-          const int4 t = reinterpret_cast<const int4*>(a.meas[m])[v];
-          val[0] = t.x; val[1] = t.y; val[2] = t.z; val[3] = t.w;
-        } else {
-          val[0] = a.meas[m][v];
-        }
-#pragma unroll
-        for (int r = 0; r < VEC; ++r)
-          if (g[r] >= 0)
-            atomicAdd(&acc[m * a.G + g[r]],
-                      static_cast<unsigned long long>(static_cast<long long>(val[r])));
-      }
-#pragma unroll
-      for (int r = 0; r < VEC; ++r)
-        if (g[r] >= 0) atomicAdd(&acc[a.M * a.G + g[r]], 1ull);
-    }
+  while (v < v_end) {
+    const int64_t vn = v + SCAN_THREADS;
+    if (vn < v_end) load_keys<VEC, KMAX>(a, vn, nxt);
+    consume<VEC, KMAX>(a, tab, acc, v, cur);
+    cur = nxt;
+    v = vn;
   }
   // ragged tail (n % VEC rows)
   if (VEC > 1 && blockIdx.x == 0) {
     const int64_t i = n_vec * VEC + tid;
     if (i < a.n) {
-      int32_t fk1[LQ_MAX_DIMS];
+      int32_t fk1[KMAX];
 #pragma unroll
-      for (int k = 0; k < LQ_MAX_DIMS; ++k) {
+      for (int k = 0; k < KMAX; ++k) {
         if (k >= a.K) break;
         fk1[k] = a.d[k].fk[i];
       }
-      int32_t g = classify<LDS_TABLES>(a, tab, fk1);
+      int32_t g = classify<KMAX>(a, tab, fk1);
       if (a.fact_mask && a.fact_mask[i] == 0) g = -1;
       if (g >= 0) {
         for (int m = 0; m < a.M; ++m)
@@ -208,10 +251,10 @@ __global__ __launch_bounds__(SCAN_THREADS) void scan_kernel(GbArgs a) {
   }
   __syncthreads();
   for (int i = tid; i < n_acc; i += SCAN_THREADS) {
-    const unsigned long long v = acc[i];
-    if (v == 0ull) continue;
-    if (i < a.M * a.G) atomicAdd(&a.sums[i], v);
-    else if (a.counts) atomicAdd(&a.counts[i - a.M * a.G], v);
+    const unsigned long long t = acc[i];
+    if (t == 0ull) continue;
+    if (i < a.M * a.G) atomicAdd(&a.sums[i], t);
+    else if (a.counts) atomicAdd(&a.counts[i - a.M * a.G], t);
   }
 }
 
@@ -278,8 +321,12 @@ int launch_groupby(int64_t n, int32_t K, const int32_t* const* fks, const int64_
   const int cus = num_cus();
   {
     size_t work = static_cast<size_t>(M + 1) * G;
-    for (int k = 0; k < K; ++k) work = std::max(work, static_cast<size_t>(a.d[k].bytes));
-    const int64_t blocks = std::min<int64_t>(static_cast<int64_t>((work + 255) / 256) , cus * 4);
+    for (int k = 0; k < K; ++k) {
+      const size_t w = a.d[k].kind == DK_BITMAP ? static_cast<size_t>(a.d[k].bytes) * 8   // one lane per row
+                                                : static_cast<size_t>(a.d[k].bytes) / 4;   // one thread per word
+      work = std::max(work, w);
+    }
+    const int64_t blocks = std::min<int64_t>(static_cast<int64_t>((work + 255) / 256), cus * 8);
     hipLaunchKernelGGL(pack_kernel, dim3(static_cast<unsigned>(std::max<int64_t>(blocks, 1))), dim3(256), 0, s, a);
     LQ_LAUNCH_CHECK("pack_kernel");
   }
@@ -291,19 +338,32 @@ int launch_groupby(int64_t n, int32_t K, const int32_t* const* fks, const int64_
   // Workgroups per CU the LDS footprint allows (at most two 1024-thread workgroups fit a CU).
   const int per_cu = lds * 2 <= 160 * 1024 ? 2 : 1;
   const int vec = vec_ok ? 4 : 1;
-  const int64_t want = (n / vec + SCAN_THREADS - 1) / SCAN_THREADS;
-  const unsigned blocks = static_cast<unsigned>(std::max<int64_t>(1, std::min<int64_t>(want, static_cast<int64_t>(cus) * per_cu)));
+  const int64_t n_vec = n / vec;
+  // Resident workgroups each take one contiguous slice (a multiple of the workgroup size).
+  int64_t blocks64 = std::max<int64_t>(1, std::min<int64_t>((n_vec + SCAN_THREADS - 1) / SCAN_THREADS,
+                                                            static_cast<int64_t>(cus) * per_cu));
+  int64_t per_block = (n_vec + blocks64 - 1) / blocks64;
+  per_block = std::max<int64_t>(SCAN_THREADS, (per_block + SCAN_THREADS - 1) / SCAN_THREADS * SCAN_THREADS);
+  blocks64 = std::max<int64_t>(1, (n_vec + per_block - 1) / per_block);
+  const unsigned blocks = static_cast<unsigned>(blocks64);
+  const int kmax = K <= 2 ? 2 : (K <= 4 ? 4 : 8);
 
-#define LQ_SCAN(LT, V)                                                                        \
+#define LQ_SCAN(LT, V, KM)                                                                    \
   do {                                                                                        \
     if (lds > 64 * 1024)                                                                      \
-      LQ_HIP_TRY(hipFuncSetAttribute(reinterpret_cast<const void*>(&scan_kernel<LT, V>),      \
+      LQ_HIP_TRY(hipFuncSetAttribute(reinterpret_cast<const void*>(&scan_kernel<LT, V, KM>),  \
                                      hipFuncAttributeMaxDynamicSharedMemorySize,              \
                                      static_cast<int>(lds)));                                 \
-    hipLaunchKernelGGL((scan_kernel<LT, V>), dim3(blocks), dim3(SCAN_THREADS), lds, s, a);    \
+    hipLaunchKernelGGL((scan_kernel<LT, V, KM>), dim3(blocks), dim3(SCAN_THREADS), lds, s, a, \
+                       per_block);                                                            \
   } while (0)
-  if (lds_tables) { if (vec == 4) LQ_SCAN(true, 4); else LQ_SCAN(true, 1); }
-  else            { if (vec == 4) LQ_SCAN(false, 4); else LQ_SCAN(false, 1); }
+#define LQ_SCAN_K(LT, V)                                                                      \
+  do {                                                                                        \
+    if (kmax == 2) LQ_SCAN(LT, V, 2); else if (kmax == 4) LQ_SCAN(LT, V, 4); else LQ_SCAN(LT, V, 8); \
+  } while (0)
+  if (lds_tables) { if (vec == 4) LQ_SCAN_K(true, 4); else LQ_SCAN_K(true, 1); }
+  else            { if (vec == 4) LQ_SCAN_K(false, 4); else LQ_SCAN_K(false, 1); }
+#undef LQ_SCAN_K
 #undef LQ_SCAN
   LQ_LAUNCH_CHECK("scan_kernel");
   return LQ_OK;
