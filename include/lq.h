@@ -172,7 +172,9 @@ int lq_masked_groupby_sum(int64_t n_fact, int32_t n_dims, const int32_t* const* 
                           const int32_t* const* measures, int64_t* sums, int64_t* counts,
                           void* ws, size_t ws_bytes, uint32_t flags, void* hip_stream);
 
-/* Workspace sizes in bytes (host-only computations, 0 on invalid arguments). */
+/* Workspace sizes in bytes (0 on invalid arguments).  For the group-by, group_card[k] must be
+ * 1 for dimensions that do not group (group_card may be NULL when none does); the size depends
+ * on the number of compute units of the current device. */
 size_t lq_workspace_bytes(int which_call, const lq_star* star, const lq_model* model,
                           int64_t chunk_rows);
 size_t lq_groupby_workspace_bytes(int32_t n_dims, const int64_t* dim_rows,

@@ -4,16 +4,19 @@
 // (s_i = prod_k mask_k[fk_k[i]]) and the group-mapping matrix is applied row by row
 // (g_i = mixed-radix number of code_k[fk_k[i]]); neither matrix is ever built.
 //
-// Two launches per call:
+// Three launches per call:
 //   1. pack_kernel   - folds mask and code of every dimension into one compact side table
 //                      per dimension (a bitmap for mask-only dimensions, one byte or one
 //                      16-bit word "code, or all-ones if filtered out" for grouping
-//                      dimensions) and zeroes the outputs.
+//                      dimensions).
 //   2. scan_kernel   - streams the fact columns once.  The side tables sit in LDS when they
 //                      fit (they are read through L2 otherwise); survivors add into int64
-//                      accumulators in LDS, which each workgroup flushes to the global result
-//                      with 64-bit atomics at the end.  Integer addition commutes, so the
-//                      result is exact and independent of scheduling.
+//                      accumulators in LDS, which each workgroup stores, as they are, into its
+//                      own row of a partial-result matrix in the workspace.
+//   3. fold_kernel   - adds the partial rows up into the caller's arrays.  (Flushing with
+//                      global atomics instead costs more than this third launch: a few hundred
+//                      workgroups queueing on the same few cache lines.)
+// Integer addition commutes, so the result is exact and independent of scheduling.
 #include "lq_common.h"
 
 namespace lq {
@@ -30,6 +33,7 @@ struct GbDim {
   int64_t rows;
   int32_t kind;
   int32_t card;          // 1 when not grouping
+  int32_t stride;        // weight of this dimension's code in the group number (0 when not grouping)
   uint32_t off;          // byte offset of the packed table (16-byte aligned)
   uint32_t bytes;        // packed size, multiple of 16
 };
@@ -46,6 +50,7 @@ struct GbArgs {
   int32_t G;
   uint8_t* packed;             // workspace: all packed tables
   uint32_t packed_bytes;
+  unsigned long long* partial; // workspace: [workgroups x (M+1) x G]
 };
 
 // ---------------------------------------------------------------- pack ------------------
@@ -56,9 +61,6 @@ struct GbArgs {
 __global__ __launch_bounds__(256) void pack_kernel(GbArgs a) {
   const int64_t gtid = static_cast<int64_t>(blockIdx.x) * blockDim.x + threadIdx.x;
   const int64_t gstride = static_cast<int64_t>(gridDim.x) * blockDim.x;
-  for (int64_t i = gtid; i < static_cast<int64_t>(a.M) * a.G; i += gstride) a.sums[i] = 0ull;
-  if (a.counts)
-    for (int64_t i = gtid; i < a.G; i += gstride) a.counts[i] = 0ull;
   const int lane = threadIdx.x & 63;
   const int64_t gwave = gtid >> 6, nwave = gstride >> 6;
   for (int k = 0; k < a.K; ++k) {
@@ -106,33 +108,53 @@ __global__ __launch_bounds__(256) void pack_kernel(GbArgs a) {
 
 constexpr int SCAN_THREADS = 1024;
 
-// One fact row: returns the group number, or -1 when the row is filtered out.
-template <int KMAX>
-__device__ __forceinline__ int32_t classify(const GbArgs& a, const uint8_t* tab, const int32_t (&fk)[KMAX]) {
-  bool alive = true;
-  int32_t g = 0;
+// VEC fact rows at once: g[q] becomes the group number of row q, or -1 when the row is filtered
+// out.  Dimensions form the outer loop so that the (wavefront-uniform) choice of side-table format
+// is made once per dimension, not once per row.  fk is [row][dimension].
+template <int VEC, int KMAX>
+__device__ __forceinline__ void classify(const GbArgs& a, const uint8_t* tab,
+                                         const int32_t (&fk)[VEC][KMAX], int32_t (&g)[VEC]) {
+  bool alive[VEC];
+#pragma unroll
+  for (int q = 0; q < VEC; ++q) { alive[q] = true; g[q] = 0; }
 #pragma unroll
   for (int k = 0; k < KMAX; ++k) {
     if (k >= a.K) break;
     const GbDim& d = a.d[k];
-    const int32_t j = fk[k];
-    alive = alive && j >= 0;
-    const uint32_t jj = j < 0 ? 0u : static_cast<uint32_t>(j);   // keep the lookup in bounds
     const uint8_t* t = tab + d.off;
+    const int32_t stride = d.stride;
+    uint32_t jj[VEC];
+#pragma unroll
+    for (int q = 0; q < VEC; ++q) {
+      const int32_t j = fk[q][k];
+      alive[q] = alive[q] && j >= 0;
+      jj[q] = j < 0 ? 0u : static_cast<uint32_t>(j);   // keep the lookup in bounds
+    }
     if (d.kind == DK_BITMAP) {
-      const uint32_t w = reinterpret_cast<const uint32_t*>(t)[jj >> 5];
-      alive = alive && ((w >> (jj & 31)) & 1u);
+#pragma unroll
+      for (int q = 0; q < VEC; ++q) {
+        const uint32_t w = reinterpret_cast<const uint32_t*>(t)[jj[q] >> 5];
+        alive[q] = alive[q] && ((w >> (jj[q] & 31)) & 1u);
+      }
     } else if (d.kind == DK_BYTE) {
-      const uint32_t v = t[jj];
-      alive = alive && v != 0xffu;
-      g = g * d.card + static_cast<int32_t>(v);
+#pragma unroll
+      for (int q = 0; q < VEC; ++q) {
+        const uint32_t v = t[jj[q]];
+        alive[q] = alive[q] && v != 0xffu;
+        g[q] += static_cast<int32_t>(v) * stride;
+      }
     } else if (d.kind == DK_U16) {
-      const uint32_t v = reinterpret_cast<const uint16_t*>(t)[jj];
-      alive = alive && v != 0xffffu;
-      g = g * d.card + static_cast<int32_t>(v);
+#pragma unroll
+      for (int q = 0; q < VEC; ++q) {
+        const uint32_t v = reinterpret_cast<const uint16_t*>(t)[jj[q]];
+        alive[q] = alive[q] && v != 0xffffu;
+        g[q] += static_cast<int32_t>(v) * stride;
+      }
     }
   }
-  return alive ? g : -1;
+#pragma unroll
+  for (int q = 0; q < VEC; ++q)
+    if (!alive[q]) g[q] = -1;
 }
 
 // Key columns (and fact mask) of VEC consecutive fact rows.
@@ -166,10 +188,10 @@ template <int VEC, int KMAX>
 __device__ __forceinline__ void consume(const GbArgs& a, const uint8_t* tab, unsigned long long* acc,
                                         int64_t v, const KeyRegs<VEC, KMAX>& r) {
   int32_t g[VEC];
+  classify<VEC, KMAX>(a, tab, r.fk, g);
   bool any = false;
 #pragma unroll
   for (int q = 0; q < VEC; ++q) {
-    g[q] = classify<KMAX>(a, tab, r.fk[q]);
     if (((r.fm >> (8 * q)) & 0xffu) == 0) g[q] = -1;
     any = any || g[q] >= 0;
   }
@@ -233,13 +255,15 @@ __global__ __launch_bounds__(SCAN_THREADS) void scan_kernel(GbArgs a, int64_t pe
   if (VEC > 1 && blockIdx.x == 0) {
     const int64_t i = n_vec * VEC + tid;
     if (i < a.n) {
-      int32_t fk1[KMAX];
+      int32_t fk1[1][KMAX];
 #pragma unroll
       for (int k = 0; k < KMAX; ++k) {
         if (k >= a.K) break;
-        fk1[k] = a.d[k].fk[i];
+        fk1[0][k] = a.d[k].fk[i];
       }
-      int32_t g = classify<KMAX>(a, tab, fk1);
+      int32_t g1[1];
+      classify<1, KMAX>(a, tab, fk1, g1);
+      int32_t g = g1[0];
       if (a.fact_mask && a.fact_mask[i] == 0) g = -1;
       if (g >= 0) {
         for (int m = 0; m < a.M; ++m)
@@ -250,11 +274,197 @@ __global__ __launch_bounds__(SCAN_THREADS) void scan_kernel(GbArgs a, int64_t pe
     }
   }
   __syncthreads();
-  for (int i = tid; i < n_acc; i += SCAN_THREADS) {
-    const unsigned long long t = acc[i];
-    if (t == 0ull) continue;
-    if (i < a.M * a.G) atomicAdd(&a.sums[i], t);
-    else if (a.counts) atomicAdd(&a.counts[i - a.M * a.G], t);
+  unsigned long long* mine = a.partial + static_cast<size_t>(blockIdx.x) * n_acc;
+  for (int i = tid; i < n_acc; i += SCAN_THREADS) mine[i] = acc[i];
+}
+
+
+// ---------------------------------------------------------------- scan, common case -----
+
+// The same scan with everything the generic kernel decides at run time fixed at compile time:
+// NB dimensions with byte side tables (grouping, optionally masked), NM mask-only dimensions
+// with bitmaps, MM measures, no fact mask, 16-byte aligned columns, side tables in LDS.
+// The host lists the byte dimensions first; group numbers use per-dimension strides, so the
+// order in which dimensions are visited does not matter.
+struct FastArgs {
+  int64_t n;
+  const int32_t* fk[LQ_MAX_DIMS];    // byte dimensions, then bitmap dimensions
+  uint32_t off[LQ_MAX_DIMS];
+  int32_t stride[LQ_MAX_DIMS];
+  const int32_t* meas[LQ_MAX_MEASURES];
+  const uint8_t* packed;
+  uint32_t packed_bytes;
+  int32_t G;
+  unsigned long long* partial;
+};
+
+template <int NB, int NM, int MM>
+__global__ __launch_bounds__(SCAN_THREADS) void scan_fast_kernel(FastArgs a, int64_t per_block) {
+  extern __shared__ __align__(16) uint8_t smem[];
+  constexpr int ND = NB + NM;
+  unsigned long long* acc = reinterpret_cast<unsigned long long*>(smem);
+  const int n_acc = (MM + 1) * a.G;
+  uint8_t* tab = smem + round_up(static_cast<size_t>(n_acc) * 8, 16);
+  const int tid = threadIdx.x;
+
+  const int64_t n_vec = a.n / 4;
+  const int64_t v_begin = static_cast<int64_t>(blockIdx.x) * per_block;
+  const int64_t v_end = min(n_vec, v_begin + per_block);
+  int64_t v = v_begin + tid;
+  v4i cur[ND], nxt[ND];
+  if (v < v_end) {
+#pragma unroll
+    for (int k = 0; k < ND; ++k) cur[k] = __builtin_nontemporal_load(reinterpret_cast<const v4i*>(a.fk[k]) + v);
+  }
+  for (int i = tid; i < n_acc; i += SCAN_THREADS) acc[i] = 0ull;
+  {
+    const uint4* src = reinterpret_cast<const uint4*>(a.packed);
+    uint4* dst = reinterpret_cast<uint4*>(tab);
+    for (uint32_t i = tid; i < a.packed_bytes / 16; i += SCAN_THREADS) dst[i] = src[i];
+  }
+  __syncthreads();
+
+  while (v < v_end) {
+    const int64_t vn = v + SCAN_THREADS;
+    if (vn < v_end) {
+#pragma unroll
+      for (int k = 0; k < ND; ++k) nxt[k] = __builtin_nontemporal_load(reinterpret_cast<const v4i*>(a.fk[k]) + vn);
+    }
+    int32_t g[4];
+    bool alive[4];
+#pragma unroll
+    for (int q = 0; q < 4; ++q) { g[q] = 0; alive[q] = true; }
+#pragma unroll
+    for (int k = 0; k < ND; ++k) {
+      const uint8_t* t = tab + a.off[k];
+#pragma unroll
+      for (int q = 0; q < 4; ++q) {
+        const int32_t j = cur[k][q];
+        alive[q] = alive[q] && j >= 0;
+        const uint32_t jj = j < 0 ? 0u : static_cast<uint32_t>(j);
+        if (k < NB) {
+          const uint32_t b = t[jj];
+          alive[q] = alive[q] && b != 0xffu;
+          g[q] += static_cast<int32_t>(b) * a.stride[k];
+        } else {
+          const uint32_t w = reinterpret_cast<const uint32_t*>(t)[jj >> 5];
+          alive[q] = alive[q] && ((w >> (jj & 31)) & 1u);
+        }
+      }
+    }
+    if (alive[0] || alive[1] || alive[2] || alive[3]) {
+#pragma unroll
+      for (int m = 0; m < MM; ++m) {
+        const v4i val = *(reinterpret_cast<const v4i*>(a.meas[m]) + v);
+#pragma unroll
+        for (int q = 0; q < 4; ++q)
+          if (alive[q])
+            atomicAdd(&acc[m * a.G + g[q]], static_cast<unsigned long long>(static_cast<long long>(val[q])));
+      }
+#pragma unroll
+      for (int q = 0; q < 4; ++q)
+        if (alive[q]) atomicAdd(&acc[MM * a.G + g[q]], 1ull);
+    }
+#pragma unroll
+    for (int k = 0; k < ND; ++k) cur[k] = nxt[k];
+    v = vn;
+  }
+  // ragged tail (n % 4 rows)
+  if (blockIdx.x == 0) {
+    const int64_t i = n_vec * 4 + tid;
+    if (i < a.n) {
+      int32_t g = 0;
+      bool alive = true;
+#pragma unroll
+      for (int k = 0; k < ND; ++k) {
+        const uint8_t* t = tab + a.off[k];
+        const int32_t j = a.fk[k][i];
+        alive = alive && j >= 0;
+        const uint32_t jj = j < 0 ? 0u : static_cast<uint32_t>(j);
+        if (k < NB) {
+          const uint32_t b = t[jj];
+          alive = alive && b != 0xffu;
+          g += static_cast<int32_t>(b) * a.stride[k];
+        } else {
+          const uint32_t w = reinterpret_cast<const uint32_t*>(t)[jj >> 5];
+          alive = alive && ((w >> (jj & 31)) & 1u);
+        }
+      }
+      if (alive) {
+#pragma unroll
+        for (int m = 0; m < MM; ++m)
+          atomicAdd(&acc[m * a.G + g], static_cast<unsigned long long>(static_cast<long long>(a.meas[m][i])));
+        atomicAdd(&acc[MM * a.G + g], 1ull);
+      }
+    }
+  }
+  __syncthreads();
+  unsigned long long* mine = a.partial + static_cast<size_t>(blockIdx.x) * n_acc;
+  for (int i = tid; i < n_acc; i += SCAN_THREADS) mine[i] = acc[i];
+}
+
+template <int NB, int NM, int MM>
+int launch_fast_inst(const FastArgs& a, unsigned blocks, size_t lds, int64_t per_block, hipStream_t s) {
+  if (lds > 64 * 1024)
+    LQ_HIP_TRY(hipFuncSetAttribute(reinterpret_cast<const void*>(&scan_fast_kernel<NB, NM, MM>),
+                                   hipFuncAttributeMaxDynamicSharedMemorySize, static_cast<int>(lds)));
+  hipLaunchKernelGGL((scan_fast_kernel<NB, NM, MM>), dim3(blocks), dim3(SCAN_THREADS), lds, s, a, per_block);
+  LQ_LAUNCH_CHECK("scan_fast_kernel");
+  return LQ_OK;
+}
+template <int NB, int NM>
+int launch_fast_m(const FastArgs& a, int M, unsigned blocks, size_t lds, int64_t pb, hipStream_t s) {
+  if (M == 1) return launch_fast_inst<NB, NM, 1>(a, blocks, lds, pb, s);
+  if (M == 2) return launch_fast_inst<NB, NM, 2>(a, blocks, lds, pb, s);
+  return -1;
+}
+template <int NB>
+int launch_fast_nm(const FastArgs& a, int nm, int M, unsigned blocks, size_t lds, int64_t pb, hipStream_t s) {
+  switch (nm) {
+    case 0: if constexpr (NB > 0) return launch_fast_m<NB, 0>(a, M, blocks, lds, pb, s); else return -1;
+    case 1: return launch_fast_m<NB, 1>(a, M, blocks, lds, pb, s);
+    case 2: return launch_fast_m<NB, 2>(a, M, blocks, lds, pb, s);
+    case 3: return launch_fast_m<NB, 3>(a, M, blocks, lds, pb, s);
+    default: return -1;
+  }
+}
+// Returns -1 when there is no instantiation for this mix of dimensions.
+int launch_fast(const FastArgs& a, int nb, int nm, int M, unsigned blocks, size_t lds, int64_t pb, hipStream_t s) {
+  switch (nb) {
+    case 0: return launch_fast_nm<0>(a, nm, M, blocks, lds, pb, s);
+    case 1: return launch_fast_nm<1>(a, nm, M, blocks, lds, pb, s);
+    case 2: return launch_fast_nm<2>(a, nm, M, blocks, lds, pb, s);
+    case 3: return launch_fast_nm<3>(a, nm, M, blocks, lds, pb, s);
+    default: return -1;
+  }
+}
+
+// ---------------------------------------------------------------- fold ------------------
+
+constexpr int FOLD_THREADS = 256;
+constexpr int FOLD_PARTS = 32;                       // threads sharing one accumulator
+constexpr int FOLD_ACCS = FOLD_THREADS / FOLD_PARTS; // accumulators per workgroup
+
+// sums / counts [i] = sum over workgroups b of partial[b][i].  Eight consecutive accumulators per
+// workgroup, each summed by 32 threads striding over the partial rows, then combined in LDS.
+__global__ __launch_bounds__(FOLD_THREADS) void fold_kernel(GbArgs a, int rows_written) {
+  __shared__ unsigned long long part[FOLD_PARTS][FOLD_ACCS];
+  const int n_acc = (a.M + 1) * a.G;
+  const int il = threadIdx.x % FOLD_ACCS, p = threadIdx.x / FOLD_ACCS;
+  const int i = blockIdx.x * FOLD_ACCS + il;
+  unsigned long long t = 0ull;
+  if (i < n_acc) {
+#pragma unroll 8
+    for (int b = p; b < rows_written; b += FOLD_PARTS) t += a.partial[static_cast<size_t>(b) * n_acc + i];
+  }
+  part[p][il] = t;
+  __syncthreads();
+  if (threadIdx.x < FOLD_ACCS && i < n_acc) {
+    unsigned long long tot = 0ull;
+#pragma unroll
+    for (int q = 0; q < FOLD_PARTS; ++q) tot += part[q][il];
+    if (i < a.M * a.G) a.sums[i] = tot;
+    else if (a.counts) a.counts[i - a.M * a.G] = tot;
   }
 }
 
@@ -287,12 +497,18 @@ size_t plan_tables(int32_t K, const int64_t* rows, const uint8_t* const* mask,
 
 }  // namespace
 
-size_t groupby_ws_bytes(int32_t K, const int64_t* rows) {
+// Workspace layout: [side tables | partial results, one row per scan workgroup].
+size_t groupby_tables_bytes(int32_t K, const int64_t* rows) {
   // Upper bound that does not depend on which dimensions carry masks or codes:
   // two bytes per dimension row, each table rounded to 16 bytes.
   size_t t = 0;
   for (int k = 0; k < K; ++k) t += round_up(static_cast<size_t>(rows[k]) * 2, 16);
   return round_up(t, 256) + 256;
+}
+int groupby_max_workgroups() { return 2 * num_cus(); }
+size_t groupby_ws_bytes(int32_t K, const int64_t* rows, int64_t n_acc) {
+  return groupby_tables_bytes(K, rows) +
+         round_up(static_cast<size_t>(groupby_max_workgroups()) * n_acc * 8, 256);
 }
 
 int launch_groupby(int64_t n, int32_t K, const int32_t* const* fks, const int64_t* rows,
@@ -304,6 +520,7 @@ int launch_groupby(int64_t n, int32_t K, const int32_t* const* fks, const int64_
   a.sums = reinterpret_cast<unsigned long long*>(sums);
   a.counts = reinterpret_cast<unsigned long long*>(counts);
   a.packed = static_cast<uint8_t*>(ws);
+  a.partial = reinterpret_cast<unsigned long long*>(a.packed + groupby_tables_bytes(K, rows));
   bool vec_ok = aligned(fact_mask, 4);
   for (int k = 0; k < K; ++k) {
     a.d[k].fk = fks[k];
@@ -314,13 +531,21 @@ int launch_groupby(int64_t n, int32_t K, const int32_t* const* fks, const int64_
     vec_ok = vec_ok && aligned(fks[k], 16);
   }
   for (int m = 0; m < M; ++m) { a.meas[m] = meas[m]; vec_ok = vec_ok && aligned(meas[m], 16); }
+  {   // mixed-radix weights, last grouping dimension fastest
+    int32_t stride = 1;
+    for (int k = K - 1; k >= 0; --k) {
+      const bool grouping = code && code[k];
+      a.d[k].stride = grouping ? stride : 0;
+      if (grouping) stride *= card[k];
+    }
+  }
   const size_t packed = plan_tables(K, rows, mask, code, card, a.d);
   if (packed > 0xffffffffull) return fail(LQ_ERR_UNSUPPORTED, "group-by: dimension side tables exceed 4 GiB");
   a.packed_bytes = static_cast<uint32_t>(packed);
 
   const int cus = num_cus();
   {
-    size_t work = static_cast<size_t>(M + 1) * G;
+    size_t work = 1;
     for (int k = 0; k < K; ++k) {
       const size_t w = a.d[k].kind == DK_BITMAP ? static_cast<size_t>(a.d[k].bytes) * 8   // one lane per row
                                                 : static_cast<size_t>(a.d[k].bytes) / 4;   // one thread per word
@@ -330,7 +555,13 @@ int launch_groupby(int64_t n, int32_t K, const int32_t* const* fks, const int64_
     hipLaunchKernelGGL(pack_kernel, dim3(static_cast<unsigned>(std::max<int64_t>(blocks, 1))), dim3(256), 0, s, a);
     LQ_LAUNCH_CHECK("pack_kernel");
   }
-  if (n == 0) return LQ_OK;
+  const int n_acc = (M + 1) * G;
+  const unsigned fold_blocks = static_cast<unsigned>((n_acc + FOLD_ACCS - 1) / FOLD_ACCS);
+  if (n == 0) {   // nothing to scan: the fold alone writes the all-zero result
+    hipLaunchKernelGGL(fold_kernel, dim3(fold_blocks), dim3(FOLD_THREADS), 0, s, a, 0);
+    LQ_LAUNCH_CHECK("fold_kernel");
+    return LQ_OK;
+  }
 
   const size_t acc_bytes = round_up(static_cast<size_t>(M + 1) * G * 8, 16);
   const bool lds_tables = acc_bytes + packed <= LDS_BUDGET;
@@ -342,11 +573,39 @@ int launch_groupby(int64_t n, int32_t K, const int32_t* const* fks, const int64_
   // Resident workgroups each take one contiguous slice (a multiple of the workgroup size).
   int64_t blocks64 = std::max<int64_t>(1, std::min<int64_t>((n_vec + SCAN_THREADS - 1) / SCAN_THREADS,
                                                             static_cast<int64_t>(cus) * per_cu));
+  blocks64 = std::min<int64_t>(blocks64, groupby_max_workgroups());
   int64_t per_block = (n_vec + blocks64 - 1) / blocks64;
   per_block = std::max<int64_t>(SCAN_THREADS, (per_block + SCAN_THREADS - 1) / SCAN_THREADS * SCAN_THREADS);
   blocks64 = std::max<int64_t>(1, (n_vec + per_block - 1) / per_block);
   const unsigned blocks = static_cast<unsigned>(blocks64);
   const int kmax = K <= 2 ? 2 : (K <= 4 ? 4 : 8);
+
+  // Common case: compile-time specialised kernel.
+  if (lds_tables && vec == 4 && !fact_mask) {
+    FastArgs f{};
+    int nb = 0, nm = 0;
+    bool ok = true;
+    for (int pass = 0; pass < 2 && ok; ++pass)
+      for (int k = 0; k < K; ++k) {
+        const int kind = a.d[k].kind;
+        if (kind != DK_BYTE && kind != DK_BITMAP) { ok = false; break; }
+        if ((pass == 0) != (kind == DK_BYTE)) continue;
+        const int slot = nb + nm;
+        f.fk[slot] = a.d[k].fk; f.off[slot] = a.d[k].off; f.stride[slot] = a.d[k].stride;
+        if (kind == DK_BYTE) ++nb; else ++nm;
+      }
+    if (ok) {
+      f.n = n; f.packed = a.packed; f.packed_bytes = a.packed_bytes; f.G = G; f.partial = a.partial;
+      for (int m = 0; m < M; ++m) f.meas[m] = meas[m];
+      const int rc = launch_fast(f, nb, nm, M, blocks, lds, per_block, s);
+      if (rc > 0) return rc;
+      if (rc == 0) {
+        hipLaunchKernelGGL(fold_kernel, dim3(fold_blocks), dim3(FOLD_THREADS), 0, s, a, static_cast<int>(blocks));
+        LQ_LAUNCH_CHECK("fold_kernel");
+        return LQ_OK;
+      }
+    }
+  }
 
 #define LQ_SCAN(LT, V, KM)                                                                    \
   do {                                                                                        \
@@ -366,6 +625,8 @@ int launch_groupby(int64_t n, int32_t K, const int32_t* const* fks, const int64_
 #undef LQ_SCAN_K
 #undef LQ_SCAN
   LQ_LAUNCH_CHECK("scan_kernel");
+  hipLaunchKernelGGL(fold_kernel, dim3(fold_blocks), dim3(FOLD_THREADS), 0, s, a, static_cast<int>(blocks));
+  LQ_LAUNCH_CHECK("fold_kernel");
   return LQ_OK;
 }
 

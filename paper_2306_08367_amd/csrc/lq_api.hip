@@ -37,7 +37,7 @@ int launch_groupby(int64_t n, int32_t K, const int32_t* const* fks, const int64_
                    const uint8_t* const* mask, const int32_t* const* code, const int32_t* card,
                    const uint8_t* fact_mask, int32_t M, const int32_t* const* meas, int64_t* sums,
                    int64_t* counts, int32_t G, void* ws, hipStream_t s);
-size_t groupby_ws_bytes(int32_t K, const int64_t* rows);
+size_t groupby_ws_bytes(int32_t K, const int64_t* rows, int64_t n_acc);
 
 namespace {
 
@@ -313,11 +313,18 @@ int lq_materialized_join_predict(const lq_star* star, const lq_model* model, lq_
 
 size_t lq_groupby_workspace_bytes(int32_t n_dims, const int64_t* dim_rows, const int32_t* group_card,
                                   int32_t n_measures) {
-  (void)group_card; (void)n_measures;
   if (n_dims < 0 || n_dims > LQ_MAX_DIMS || (n_dims > 0 && !dim_rows)) return 0;
-  for (int k = 0; k < n_dims; ++k)
+  if (n_measures < 1 || n_measures > LQ_MAX_MEASURES) return 0;
+  int64_t G = 1;
+  for (int k = 0; k < n_dims; ++k) {
     if (dim_rows[k] < 0) return 0;
-  return groupby_ws_bytes(n_dims, dim_rows);
+    if (group_card) {
+      if (group_card[k] < 1 || group_card[k] > 65535) return 0;
+      G *= group_card[k];
+      if (G > 8192) return 0;
+    }
+  }
+  return groupby_ws_bytes(n_dims, dim_rows, G * (n_measures + 1));
 }
 
 int lq_masked_groupby_sum(int64_t n_fact, int32_t n_dims, const int32_t* const* fks,
@@ -356,7 +363,7 @@ int lq_masked_groupby_sum(int64_t n_fact, int32_t n_dims, const int32_t* const* 
     if (n_fact > 0 && !measures[m]) return fail(LQ_ERR_NULL, "measures[%d] is NULL", m);
     if (!aligned(measures[m], 4)) return fail(LQ_ERR_SHAPE, "measures[%d] is not 4-byte aligned", m);
   }
-  const size_t need = lq_groupby_workspace_bytes(n_dims, dim_rows, group_card, n_measures);
+  const size_t need = groupby_ws_bytes(n_dims, dim_rows, G * (n_measures + 1));
   if (!ws || !aligned(ws, 256) || ws_bytes < need)
     return fail(LQ_ERR_WORKSPACE, "group-by needs a 256-byte aligned workspace of %zu bytes", need);
   hipStream_t s = static_cast<hipStream_t>(hip_stream);
