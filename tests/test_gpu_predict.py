@@ -142,6 +142,42 @@ def test_bf16_paths(lq):
         assert_close(Ym, want, TOL_BF16, f"{name} materialised")
 
 
+BF16_MFMA_SHAPES = [
+    # name, n, dim_rows, dim_cols, layers, bias   (no fact columns: the matrix-core epilogue kernel)
+    ("bf16_256_16", 5_003, (500, 700, 300, 900), (64, 64, 32, 48), (256, 16), False),
+    ("bf16_128_10_bias", 3_001, (100, 200), (32, 40), (128, 10), True),
+    ("bf16_32_1", 2_047, (50,), (16,), (32, 1), True),
+    ("bf16_linear_256", 1_999, (64, 80, 96), (24, 24, 24), (256,), True),
+    ("bf16_linear_64", 4_100, (64, 80), (24, 24), (64,), False),
+]
+
+
+@pytest.mark.parametrize("shape", BF16_MFMA_SHAPES, ids=[s[0] for s in BF16_MFMA_SHAPES])
+def test_bf16_wide_models(lq, shape):
+    name, n, rows, cols, layers, bias = shape
+    w = WL.make_predict(name, n, 0, rows, cols, layers, seed=WL.SEED0 + 300 + len(name),
+                        dtype=torch.bfloat16, w_sigma=[1.0 / np.sqrt(sum(cols))] + [0.1] * (len(layers) - 1),
+                        bias=bias)
+    want = _oracle(w)
+    w = to_dev(w)
+    for y_dtype in (torch.bfloat16, torch.float32):
+        P, Y = _run_fused(lq, w, p_dtype=torch.bfloat16, y_dtype=y_dtype)
+        assert_close(Y, want, TOL_BF16, f"{name} Y {y_dtype}")
+    _, Yg = _run_fused(lq, w, p_dtype=torch.bfloat16, y_dtype=torch.float32, flags=lq.LQ_FORCE_GENERIC)
+    assert_close(Yg, want, TOL_BF16, f"{name} generic")
+
+
+def test_bf16_matrix_core_epilogue_is_exact_on_small_integers(lq):
+    """Integer features/weights small enough that every hidden unit and output is an exactly
+    representable bf16 / fp32 integer: the MFMA path must reproduce the oracle bit for bit."""
+    w = WL.make_predict("bf16_mfma_exact", 3_333, 0, (40, 50), (4, 4), (32, 16), seed=WL.SEED0 + 82,
+                        dtype=torch.bfloat16, integer_valued=True, bias=True)
+    want = _oracle(w)                       # |z| <= 8*4*2+2 = 66, |y| <= 32*66*2+2 < 2^13
+    w = to_dev(w)
+    _, Y = _run_fused(lq, w, p_dtype=torch.bfloat16, y_dtype=torch.float32)
+    np.testing.assert_array_equal(Y.cpu().double().numpy(), want)
+
+
 def test_bf16_fk_indexing_is_bit_exact(lq):
     """Small integers are exact in bf16; with one-hot-like integer weights the bf16 path must
     return exactly the oracle's integers (|values| <= 256 stay representable)."""
