@@ -67,7 +67,7 @@ def main():
     ap.add_argument("--rows", type=int, default=10_000_000, help="fact rows of the headline workload")
     ap.add_argument("--no-extras", action="store_true", help="skip materialised / group-by / skewed legs")
     ap.add_argument("--no-cpu", action="store_true", help="skip the CPU oracle baseline")
-    ap.add_argument("--only", default="", help="run a single leg for profiling: fused|groupby|c4|materialized|copy")
+    ap.add_argument("--only", default="", help="run a single leg for profiling: fused|groupby|groupby16|c4|c5|materialized|copy")
     args = ap.parse_args()
     if args.gpus != 1:
         sys.exit("bench.py: this build is single-GPU by design (no collectives, no sharding); "
@@ -226,6 +226,47 @@ def main():
                                         "traffic": measured_traffic("fused_c4")},
                            "project_dims_GBps": 2 * 1_000_000 * 128 * 4 / (pms * 1e-3) / 1e9}
         del w4, P4, Y4
+        torch.cuda.empty_cache()
+
+    # ---------------------------------------------------------------- wide bf16 MLP (cache-gather bound)
+    if (args.only == "" and not args.no_extras) or args.only == "c5":
+        n5 = 50_000_000
+        w5 = WL.c5_wide_bf16(device=dev, n=n5)
+        P5 = [torch.empty((d.shape[0], 256), dtype=torch.bfloat16, device=dev) for d in w5.dims]
+        Y5 = torch.empty((n5, 16), dtype=torch.bfloat16, device=dev)
+        pms, _, _ = time_call(lambda: lq.lq_project_dims(w5.dims, w5.weights[0], 0, P=P5), 5, 1)
+        ms, mn, _ = time_call(lambda: lq.lq_fused_join_predict(None, w5.fks, P5, w5.weights, None, Y=Y5), 5, 1)
+        m5 = 1 << 22                                  # non-fused pipeline on a slice: T of all rows is 102 GB
+        ws5 = torch.empty(lq.lq_workspace_bytes(lq.binding.LQ_CALL_MATERIALIZED, w5.k, w5.weights, 1 << 20),
+                          dtype=torch.uint8, device=dev)
+        fk5 = [f[:m5] for f in w5.fks]
+        Ym5 = torch.empty((m5, 16), dtype=torch.bfloat16, device=dev)
+        mms, _, _ = time_call(lambda: lq.lq_materialized_join_predict(None, w5.dims, fk5, w5.weights, None,
+                                                                      Y=Ym5, ws=ws5), 2, 1)
+        out["fused_c5"] = {"rows_per_s": n5 / (ms * 1e-3), "ms": ms, "project_dims_ms": pms, "fact_rows": n5,
+                           "dtype": "bf16", "gather_GBps": 2048.0 * n5 / (ms * 1e-3) / 1e9,
+                           "hbm_GBps_algorithmic": 48.0 * n5 / (ms * 1e-3) / 1e9,
+                           "materialized_rows_per_s": m5 / (mms * 1e-3),
+                           "fused_speedup": (mms / m5) / ((ms + pms) / n5)}
+        del w5, P5, Y5, ws5, Ym5
+        torch.cuda.empty_cache()
+
+    # ---------------------------------------------------------------- group-by at 16x the fact rows
+    if (args.only == "" and not args.no_extras) or args.only == "groupby16":
+        g = WL.c3_groupby(device=dev, n=96_000_000, dim_rows=(2_556, 480_000, 32_000, 1_000_000))
+        ws = torch.empty(lq.lq_groupby_workspace_bytes(g.dim_rows, g.group_card, 1), dtype=torch.uint8, device=dev)
+        sums = torch.empty((1, g.G), dtype=torch.int64, device=dev)
+        counts = torch.empty((g.G,), dtype=torch.int64, device=dev)
+        ms, mn, _ = time_call(lambda: lq.lq_masked_groupby_sum(g.fks, g.dim_rows, g.dim_mask, g.dim_code,
+                                                               g.group_card, None, g.measures, sums=sums,
+                                                               counts=counts, ws=ws), 10, 2)
+        gbps = 20.0 * g.n / (ms * 1e-3) / 1e9
+        out["groupby_sf16_shape"] = {"rows_per_s": g.n / (ms * 1e-3), "ms": ms, "fact_rows": g.n,
+                                     "dim_rows": list(g.dim_rows),
+                                     "roofline": {"bound": "hbm", "achieved": gbps, "peak": HBM_PEAK_GBPS,
+                                                  "unit": "GB/s", "frac": gbps / HBM_PEAK_GBPS,
+                                                  "algorithmic_bytes_per_row": 20}}
+        del g
 
     print(json.dumps(out))
 

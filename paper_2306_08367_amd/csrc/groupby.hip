@@ -36,6 +36,7 @@ struct GbDim {
   int32_t stride;        // weight of this dimension's code in the group number (0 when not grouping)
   uint32_t off;          // byte offset of the packed table (16-byte aligned)
   uint32_t bytes;        // packed size, multiple of 16
+  int32_t in_lds;        // 1 when the table is part of the LDS-resident prefix
 };
 
 struct GbArgs {
@@ -282,26 +283,57 @@ __global__ __launch_bounds__(SCAN_THREADS) void scan_kernel(GbArgs a, int64_t pe
 // ---------------------------------------------------------------- scan, common case -----
 
 // The same scan with everything the generic kernel decides at run time fixed at compile time:
-// NB dimensions with byte side tables (grouping, optionally masked), NM mask-only dimensions
-// with bitmaps, MM measures, no fact mask, 16-byte aligned columns, side tables in LDS.
-// The host lists the byte dimensions first; group numbers use per-dimension strides, so the
-// order in which dimensions are visited does not matter.
+// no fact mask, 16-byte aligned columns, only byte tables (grouping dimensions, optionally
+// masked) and bitmaps (mask-only dimensions).  The host orders the dimensions into four runs:
+//   NBL byte tables in LDS, NML bitmaps in LDS, NMG bitmaps in memory, NBG byte tables in memory.
+// Tables that do not fit LDS stay in memory (L2) and are only consulted for rows that survived
+// every LDS-resident predicate, so a selective query sends few requests to L2.  Group numbers use
+// per-dimension strides, so the order in which dimensions are visited does not matter.
 struct FastArgs {
   int64_t n;
-  const int32_t* fk[LQ_MAX_DIMS];    // byte dimensions, then bitmap dimensions
-  uint32_t off[LQ_MAX_DIMS];
+  const int32_t* fk[LQ_MAX_DIMS];    // in the order of the four runs above
+  uint32_t off[LQ_MAX_DIMS];         // byte offset inside the packed buffer
   int32_t stride[LQ_MAX_DIMS];
   const int32_t* meas[LQ_MAX_MEASURES];
   const uint8_t* packed;
-  uint32_t packed_bytes;
+  uint32_t lds_bytes;                // prefix of the packed buffer that is copied into LDS
   int32_t G;
   unsigned long long* partial;
 };
 
-template <int NB, int NM, int MM>
+template <bool BYTE, bool GUARDED>
+__device__ __forceinline__ void lookup(const uint8_t* t, int32_t j, int32_t stride, bool& alive, int32_t& g) {
+  alive = alive && j >= 0;
+  if (GUARDED && !alive) return;
+  const uint32_t jj = j < 0 ? 0u : static_cast<uint32_t>(j);   // keep the lookup in bounds
+  if (BYTE) {
+    const uint32_t b = t[jj];
+    alive = alive && b != 0xffu;
+    g += static_cast<int32_t>(b) * stride;
+  } else {
+    const uint32_t w = reinterpret_cast<const uint32_t*>(t)[jj >> 5];
+    alive = alive && ((w >> (jj & 31)) & 1u);
+  }
+}
+
+// All dimensions of one fact row.
+template <int NBL, int NML, int NMG, int NBG>
+__device__ __forceinline__ void classify_fast(const FastArgs& a, const uint8_t* tab, const int32_t* j,
+                                              bool& alive, int32_t& g) {
+  constexpr int NL = NBL + NML, ND = NL + NMG + NBG;
+#pragma unroll
+  for (int k = 0; k < ND; ++k) {
+    if (k < NBL) lookup<true, false>(tab + a.off[k], j[k], a.stride[k], alive, g);
+    else if (k < NL) lookup<false, false>(tab + a.off[k], j[k], 0, alive, g);
+    else if (k < NL + NMG) lookup<false, true>(a.packed + a.off[k], j[k], 0, alive, g);
+    else lookup<true, true>(a.packed + a.off[k], j[k], a.stride[k], alive, g);
+  }
+}
+
+template <int NBL, int NML, int NMG, int NBG, int MM>
 __global__ __launch_bounds__(SCAN_THREADS) void scan_fast_kernel(FastArgs a, int64_t per_block) {
   extern __shared__ __align__(16) uint8_t smem[];
-  constexpr int ND = NB + NM;
+  constexpr int ND = NBL + NML + NMG + NBG;
   unsigned long long* acc = reinterpret_cast<unsigned long long*>(smem);
   const int n_acc = (MM + 1) * a.G;
   uint8_t* tab = smem + round_up(static_cast<size_t>(n_acc) * 8, 16);
@@ -320,7 +352,7 @@ __global__ __launch_bounds__(SCAN_THREADS) void scan_fast_kernel(FastArgs a, int
   {
     const uint4* src = reinterpret_cast<const uint4*>(a.packed);
     uint4* dst = reinterpret_cast<uint4*>(tab);
-    for (uint32_t i = tid; i < a.packed_bytes / 16; i += SCAN_THREADS) dst[i] = src[i];
+    for (uint32_t i = tid; i < a.lds_bytes / 16; i += SCAN_THREADS) dst[i] = src[i];
   }
   __syncthreads();
 
@@ -333,24 +365,13 @@ __global__ __launch_bounds__(SCAN_THREADS) void scan_fast_kernel(FastArgs a, int
     int32_t g[4];
     bool alive[4];
 #pragma unroll
-    for (int q = 0; q < 4; ++q) { g[q] = 0; alive[q] = true; }
+    for (int q = 0; q < 4; ++q) {
+      int32_t j[ND];
 #pragma unroll
-    for (int k = 0; k < ND; ++k) {
-      const uint8_t* t = tab + a.off[k];
-#pragma unroll
-      for (int q = 0; q < 4; ++q) {
-        const int32_t j = cur[k][q];
-        alive[q] = alive[q] && j >= 0;
-        const uint32_t jj = j < 0 ? 0u : static_cast<uint32_t>(j);
-        if (k < NB) {
-          const uint32_t b = t[jj];
-          alive[q] = alive[q] && b != 0xffu;
-          g[q] += static_cast<int32_t>(b) * a.stride[k];
-        } else {
-          const uint32_t w = reinterpret_cast<const uint32_t*>(t)[jj >> 5];
-          alive[q] = alive[q] && ((w >> (jj & 31)) & 1u);
-        }
-      }
+      for (int k = 0; k < ND; ++k) j[k] = cur[k][q];
+      g[q] = 0;
+      alive[q] = true;
+      classify_fast<NBL, NML, NMG, NBG>(a, tab, j, alive[q], g[q]);
     }
     if (alive[0] || alive[1] || alive[2] || alive[3]) {
 #pragma unroll
@@ -373,23 +394,12 @@ __global__ __launch_bounds__(SCAN_THREADS) void scan_fast_kernel(FastArgs a, int
   if (blockIdx.x == 0) {
     const int64_t i = n_vec * 4 + tid;
     if (i < a.n) {
+      int32_t j[ND];
+#pragma unroll
+      for (int k = 0; k < ND; ++k) j[k] = a.fk[k][i];
       int32_t g = 0;
       bool alive = true;
-#pragma unroll
-      for (int k = 0; k < ND; ++k) {
-        const uint8_t* t = tab + a.off[k];
-        const int32_t j = a.fk[k][i];
-        alive = alive && j >= 0;
-        const uint32_t jj = j < 0 ? 0u : static_cast<uint32_t>(j);
-        if (k < NB) {
-          const uint32_t b = t[jj];
-          alive = alive && b != 0xffu;
-          g += static_cast<int32_t>(b) * a.stride[k];
-        } else {
-          const uint32_t w = reinterpret_cast<const uint32_t*>(t)[jj >> 5];
-          alive = alive && ((w >> (jj & 31)) & 1u);
-        }
-      }
+      classify_fast<NBL, NML, NMG, NBG>(a, tab, j, alive, g);
       if (alive) {
 #pragma unroll
         for (int m = 0; m < MM; ++m)
@@ -403,38 +413,52 @@ __global__ __launch_bounds__(SCAN_THREADS) void scan_fast_kernel(FastArgs a, int
   for (int i = tid; i < n_acc; i += SCAN_THREADS) mine[i] = acc[i];
 }
 
-template <int NB, int NM, int MM>
-int launch_fast_inst(const FastArgs& a, unsigned blocks, size_t lds, int64_t per_block, hipStream_t s) {
-  if (lds > 64 * 1024)
-    LQ_HIP_TRY(hipFuncSetAttribute(reinterpret_cast<const void*>(&scan_fast_kernel<NB, NM, MM>),
-                                   hipFuncAttributeMaxDynamicSharedMemorySize, static_cast<int>(lds)));
-  hipLaunchKernelGGL((scan_fast_kernel<NB, NM, MM>), dim3(blocks), dim3(SCAN_THREADS), lds, s, a, per_block);
+struct FastLaunch { unsigned blocks; size_t lds; int64_t per_block; hipStream_t s; int nbl, nml, nmg, nbg, M; };
+
+template <int NBL, int NML, int NMG, int NBG, int MM>
+int launch_fast_inst(const FastArgs& a, const FastLaunch& L) {
+  if (L.lds > 64 * 1024)
+    LQ_HIP_TRY(hipFuncSetAttribute(reinterpret_cast<const void*>(&scan_fast_kernel<NBL, NML, NMG, NBG, MM>),
+                                   hipFuncAttributeMaxDynamicSharedMemorySize, static_cast<int>(L.lds)));
+  hipLaunchKernelGGL((scan_fast_kernel<NBL, NML, NMG, NBG, MM>), dim3(L.blocks), dim3(SCAN_THREADS), L.lds,
+                     L.s, a, L.per_block);
   LQ_LAUNCH_CHECK("scan_fast_kernel");
   return LQ_OK;
 }
-template <int NB, int NM>
-int launch_fast_m(const FastArgs& a, int M, unsigned blocks, size_t lds, int64_t pb, hipStream_t s) {
-  if (M == 1) return launch_fast_inst<NB, NM, 1>(a, blocks, lds, pb, s);
-  if (M == 2) return launch_fast_inst<NB, NM, 2>(a, blocks, lds, pb, s);
+template <int NBL, int NML, int NMG, int NBG>
+int launch_fast_m(const FastArgs& a, const FastLaunch& L) {
+  if constexpr (NBL + NML + NMG + NBG == 0) return -1;
+  else {
+    if (L.M == 1) return launch_fast_inst<NBL, NML, NMG, NBG, 1>(a, L);
+    if (L.M == 2) return launch_fast_inst<NBL, NML, NMG, NBG, 2>(a, L);
+    return -1;
+  }
+}
+template <int NBL, int NML>
+int launch_fast_g(const FastArgs& a, const FastLaunch& L) {
+  if (L.nmg == 0 && L.nbg == 0) return launch_fast_m<NBL, NML, 0, 0>(a, L);
+  if (L.nmg == 1 && L.nbg == 0) return launch_fast_m<NBL, NML, 1, 0>(a, L);
+  if (L.nmg == 0 && L.nbg == 1) return launch_fast_m<NBL, NML, 0, 1>(a, L);
+  if (L.nmg == 1 && L.nbg == 1) return launch_fast_m<NBL, NML, 1, 1>(a, L);
   return -1;
 }
-template <int NB>
-int launch_fast_nm(const FastArgs& a, int nm, int M, unsigned blocks, size_t lds, int64_t pb, hipStream_t s) {
-  switch (nm) {
-    case 0: if constexpr (NB > 0) return launch_fast_m<NB, 0>(a, M, blocks, lds, pb, s); else return -1;
-    case 1: return launch_fast_m<NB, 1>(a, M, blocks, lds, pb, s);
-    case 2: return launch_fast_m<NB, 2>(a, M, blocks, lds, pb, s);
-    case 3: return launch_fast_m<NB, 3>(a, M, blocks, lds, pb, s);
+template <int NBL>
+int launch_fast_ml(const FastArgs& a, const FastLaunch& L) {
+  switch (L.nml) {
+    case 0: return launch_fast_g<NBL, 0>(a, L);
+    case 1: return launch_fast_g<NBL, 1>(a, L);
+    case 2: return launch_fast_g<NBL, 2>(a, L);
+    case 3: return launch_fast_g<NBL, 3>(a, L);
     default: return -1;
   }
 }
 // Returns -1 when there is no instantiation for this mix of dimensions.
-int launch_fast(const FastArgs& a, int nb, int nm, int M, unsigned blocks, size_t lds, int64_t pb, hipStream_t s) {
-  switch (nb) {
-    case 0: return launch_fast_nm<0>(a, nm, M, blocks, lds, pb, s);
-    case 1: return launch_fast_nm<1>(a, nm, M, blocks, lds, pb, s);
-    case 2: return launch_fast_nm<2>(a, nm, M, blocks, lds, pb, s);
-    case 3: return launch_fast_nm<3>(a, nm, M, blocks, lds, pb, s);
+int launch_fast(const FastArgs& a, const FastLaunch& L) {
+  switch (L.nbl) {
+    case 0: return launch_fast_ml<0>(a, L);
+    case 1: return launch_fast_ml<1>(a, L);
+    case 2: return launch_fast_ml<2>(a, L);
+    case 3: return launch_fast_ml<3>(a, L);
     default: return -1;
   }
 }
@@ -470,28 +494,42 @@ __global__ __launch_bounds__(FOLD_THREADS) void fold_kernel(GbArgs a, int rows_w
 
 constexpr size_t LDS_BUDGET = 160 * 1024 - 1024;   // gfx950 workgroups may use the whole 160 KB
 
-// Fills kind / off / bytes of every dimension; returns the packed size.
+// Fills kind / off / bytes of every dimension; returns the packed size.  Tables are laid out by
+// ascending size so that "the tables that fit in LDS" is always a prefix of the packed buffer;
+// *lds_prefix receives the length of the longest prefix that fits `lds_room` bytes.
 size_t plan_tables(int32_t K, const int64_t* rows, const uint8_t* const* mask,
-                   const int32_t* const* code, const int32_t* card, GbDim* d) {
-  size_t off = 0;
+                   const int32_t* const* code, const int32_t* card, GbDim* d, size_t lds_room,
+                   size_t* lds_prefix) {
+  size_t bytes[LQ_MAX_DIMS];
+  int order[LQ_MAX_DIMS];
   for (int k = 0; k < K; ++k) {
     const bool has_mask = mask && mask[k];
     const bool has_code = code && code[k];
     const int64_t r = rows[k];
-    size_t bytes = 0;
+    size_t b = 0;
     int32_t kind = DK_NONE;
     if (has_code) {
-      if (card[k] <= 255) { kind = DK_BYTE; bytes = static_cast<size_t>(r); }
-      else { kind = DK_U16; bytes = static_cast<size_t>(r) * 2; }
+      if (card[k] <= 255) { kind = DK_BYTE; b = static_cast<size_t>(r); }
+      else { kind = DK_U16; b = static_cast<size_t>(r) * 2; }
     } else if (has_mask) {
-      kind = DK_BITMAP; bytes = static_cast<size_t>((r + 31) / 32) * 4;
+      kind = DK_BITMAP; b = static_cast<size_t>((r + 31) / 32) * 4;
     }
-    bytes = round_up(bytes, 16);
-    if (d) {
-      d[k].kind = kind; d[k].off = static_cast<uint32_t>(off); d[k].bytes = static_cast<uint32_t>(bytes);
-    }
-    off += bytes;
+    bytes[k] = round_up(b, 16);
+    d[k].kind = kind;
+    order[k] = k;
   }
+  std::stable_sort(order, order + K, [&](int x, int y) { return bytes[x] < bytes[y]; });
+  size_t off = 0, prefix = 0;
+  bool fits = true;
+  for (int q = 0; q < K; ++q) {
+    const int k = order[q];
+    d[k].off = static_cast<uint32_t>(off);
+    d[k].bytes = static_cast<uint32_t>(bytes[k]);
+    d[k].in_lds = 0;
+    off += bytes[k];
+    if (fits && off <= lds_room) { prefix = off; d[k].in_lds = 1; } else fits = false;
+  }
+  if (lds_prefix) *lds_prefix = prefix;
   return off;
 }
 
@@ -539,7 +577,10 @@ int launch_groupby(int64_t n, int32_t K, const int32_t* const* fks, const int64_
       if (grouping) stride *= card[k];
     }
   }
-  const size_t packed = plan_tables(K, rows, mask, code, card, a.d);
+  const int n_acc = (M + 1) * G;
+  const size_t acc_bytes = round_up(static_cast<size_t>(n_acc) * 8, 16);
+  size_t lds_prefix = 0;
+  const size_t packed = plan_tables(K, rows, mask, code, card, a.d, LDS_BUDGET - acc_bytes, &lds_prefix);
   if (packed > 0xffffffffull) return fail(LQ_ERR_UNSUPPORTED, "group-by: dimension side tables exceed 4 GiB");
   a.packed_bytes = static_cast<uint32_t>(packed);
 
@@ -555,7 +596,6 @@ int launch_groupby(int64_t n, int32_t K, const int32_t* const* fks, const int64_
     hipLaunchKernelGGL(pack_kernel, dim3(static_cast<unsigned>(std::max<int64_t>(blocks, 1))), dim3(256), 0, s, a);
     LQ_LAUNCH_CHECK("pack_kernel");
   }
-  const int n_acc = (M + 1) * G;
   const unsigned fold_blocks = static_cast<unsigned>((n_acc + FOLD_ACCS - 1) / FOLD_ACCS);
   if (n == 0) {   // nothing to scan: the fold alone writes the all-zero result
     hipLaunchKernelGGL(fold_kernel, dim3(fold_blocks), dim3(FOLD_THREADS), 0, s, a, 0);
@@ -563,49 +603,62 @@ int launch_groupby(int64_t n, int32_t K, const int32_t* const* fks, const int64_
     return LQ_OK;
   }
 
-  const size_t acc_bytes = round_up(static_cast<size_t>(M + 1) * G * 8, 16);
-  const bool lds_tables = acc_bytes + packed <= LDS_BUDGET;
-  const size_t lds = acc_bytes + (lds_tables ? packed : 0);
-  // Workgroups per CU the LDS footprint allows (at most two 1024-thread workgroups fit a CU).
-  const int per_cu = lds * 2 <= 160 * 1024 ? 2 : 1;
   const int vec = vec_ok ? 4 : 1;
   const int64_t n_vec = n / vec;
   // Resident workgroups each take one contiguous slice (a multiple of the workgroup size).
-  int64_t blocks64 = std::max<int64_t>(1, std::min<int64_t>((n_vec + SCAN_THREADS - 1) / SCAN_THREADS,
-                                                            static_cast<int64_t>(cus) * per_cu));
-  blocks64 = std::min<int64_t>(blocks64, groupby_max_workgroups());
-  int64_t per_block = (n_vec + blocks64 - 1) / blocks64;
-  per_block = std::max<int64_t>(SCAN_THREADS, (per_block + SCAN_THREADS - 1) / SCAN_THREADS * SCAN_THREADS);
-  blocks64 = std::max<int64_t>(1, (n_vec + per_block - 1) / per_block);
-  const unsigned blocks = static_cast<unsigned>(blocks64);
-  const int kmax = K <= 2 ? 2 : (K <= 4 ? 4 : 8);
+  auto slices = [&](size_t lds_bytes, unsigned* blocks, int64_t* per_block) {
+    // Workgroups per CU the LDS footprint allows (at most two 1024-thread workgroups fit a CU).
+    const int per_cu = lds_bytes * 2 <= 160 * 1024 ? 2 : 1;
+    int64_t b = std::max<int64_t>(1, std::min<int64_t>((n_vec + SCAN_THREADS - 1) / SCAN_THREADS,
+                                                       static_cast<int64_t>(cus) * per_cu));
+    b = std::min<int64_t>(b, groupby_max_workgroups());
+    int64_t pb = (n_vec + b - 1) / b;
+    pb = std::max<int64_t>(SCAN_THREADS, (pb + SCAN_THREADS - 1) / SCAN_THREADS * SCAN_THREADS);
+    b = std::max<int64_t>(1, (n_vec + pb - 1) / pb);
+    *blocks = static_cast<unsigned>(b);
+    *per_block = pb;
+  };
 
-  // Common case: compile-time specialised kernel.
-  if (lds_tables && vec == 4 && !fact_mask) {
+  // Common case: compile-time specialised kernel, side tables in LDS as far as they fit.
+  if (vec == 4 && !fact_mask) {
     FastArgs f{};
-    int nb = 0, nm = 0;
+    FastLaunch L{};
     bool ok = true;
-    for (int pass = 0; pass < 2 && ok; ++pass)
+    int slot = 0;
+    // runs: byte in LDS, bitmap in LDS, bitmap in memory, byte in memory
+    for (int run = 0; run < 4 && ok; ++run)
       for (int k = 0; k < K; ++k) {
         const int kind = a.d[k].kind;
         if (kind != DK_BYTE && kind != DK_BITMAP) { ok = false; break; }
-        if ((pass == 0) != (kind == DK_BYTE)) continue;
-        const int slot = nb + nm;
+        const int want_kind = (run == 0 || run == 3) ? DK_BYTE : DK_BITMAP;
+        const int want_lds = run < 2 ? 1 : 0;
+        if (kind != want_kind || a.d[k].in_lds != want_lds) continue;
         f.fk[slot] = a.d[k].fk; f.off[slot] = a.d[k].off; f.stride[slot] = a.d[k].stride;
-        if (kind == DK_BYTE) ++nb; else ++nm;
+        ++slot;
+        if (run == 0) ++L.nbl; else if (run == 1) ++L.nml; else if (run == 2) ++L.nmg; else ++L.nbg;
       }
     if (ok) {
-      f.n = n; f.packed = a.packed; f.packed_bytes = a.packed_bytes; f.G = G; f.partial = a.partial;
+      f.n = n; f.packed = a.packed; f.lds_bytes = static_cast<uint32_t>(lds_prefix); f.G = G; f.partial = a.partial;
       for (int m = 0; m < M; ++m) f.meas[m] = meas[m];
-      const int rc = launch_fast(f, nb, nm, M, blocks, lds, per_block, s);
+      L.lds = acc_bytes + lds_prefix; L.s = s; L.M = M;
+      slices(L.lds, &L.blocks, &L.per_block);
+      const int rc = launch_fast(f, L);
       if (rc > 0) return rc;
       if (rc == 0) {
-        hipLaunchKernelGGL(fold_kernel, dim3(fold_blocks), dim3(FOLD_THREADS), 0, s, a, static_cast<int>(blocks));
+        hipLaunchKernelGGL(fold_kernel, dim3(fold_blocks), dim3(FOLD_THREADS), 0, s, a, static_cast<int>(L.blocks));
         LQ_LAUNCH_CHECK("fold_kernel");
         return LQ_OK;
       }
     }
   }
+
+  // Everything else: the run-time generic kernel, side tables all in LDS or all in memory.
+  const bool lds_tables = lds_prefix == packed;
+  const size_t lds = acc_bytes + (lds_tables ? packed : 0);
+  unsigned blocks = 0;
+  int64_t per_block = 0;
+  slices(lds, &blocks, &per_block);
+  const int kmax = K <= 2 ? 2 : (K <= 4 ? 4 : 8);
 
 #define LQ_SCAN(LT, V, KM)                                                                    \
   do {                                                                                        \

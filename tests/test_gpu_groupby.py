@@ -116,6 +116,15 @@ def test_side_tables_too_large_for_lds_are_read_from_memory(lq):
     _check(lq, _random_groupby(37, 300_007, (400_000, 300_000, 1_000), (7, 5, 1), n_measures=1))
 
 
+def test_mixed_residency_small_tables_in_lds_large_ones_in_memory(lq):
+    # byte table of 500,000 rows and bitmap of 2,000,000 rows stay in memory, the 3,000-row byte
+    # table lives in LDS; memory tables are only consulted for rows the LDS predicates let through
+    _check(lq, _random_groupby(41, 200_003, (500_000, 3_000, 2_000_000), (7, 5, 1), n_measures=2))
+    # one large bitmap in memory, everything else in LDS (the 16x-scaled star-schema shape)
+    _check(lq, _random_groupby(42, 150_001, (2_556, 100_000, 32_000, 1_500_000), (7, 25, 1, 1), n_measures=1,
+                               fact_mask=False))
+
+
 def test_unaligned_columns_take_the_scalar_path(lq):
     w = _random_groupby(38, 40_001, (20, 30), (4, 5))
     ws, wc = _oracle(w)
