@@ -41,6 +41,37 @@ __global__ __launch_bounds__(256) void materialize_kernel(MatArgs a) {
   }
 }
 
+// 16-byte version: every segment of the joined row (fact columns, each dimension's columns) is a
+// whole number of 16-byte chunks and every row start is 16-byte aligned.  A group of GROUP lanes
+// copies one joined row, chunk by chunk; a dimension row is read as one contiguous run.
+template <int GROUP>
+__global__ __launch_bounds__(256) void materialize_vec_kernel(MatArgs a, int vec /*elements per chunk*/,
+                                                              int chunks_per_row) {
+  const int sub = threadIdx.x / GROUP, c0 = threadIdx.x % GROUP;
+  constexpr int ROWS_PER_BLOCK = 256 / GROUP;
+  const size_t es = 16 / vec;
+  for (int64_t r = static_cast<int64_t>(blockIdx.x) * ROWS_PER_BLOCK + sub; r < a.rows;
+       r += static_cast<int64_t>(gridDim.x) * ROWS_PER_BLOCK) {
+    const int64_t row = a.row0 + r;
+    for (int ch = c0; ch < chunks_per_row; ch += GROUP) {
+      const int col = ch * vec;
+      const char* src;
+      if (col < a.c_f) {
+        src = static_cast<const char*>(a.X) + (row * a.ldx + col) * es;
+      } else {
+        int k = 0;
+#pragma unroll
+        for (int q = 1; q < LQ_MAX_DIMS; ++q)
+          if (q < a.K && col >= a.off[q]) k = q;
+        const int64_t j = a.fk[k][row];
+        src = static_cast<const char*>(a.D[k]) + (j * a.ldd[k] + (col - a.off[k])) * es;
+      }
+      const uint4 v = *reinterpret_cast<const uint4*>(src);
+      *reinterpret_cast<uint4*>(static_cast<char*>(a.T) + (r * a.ldt + col) * es) = v;
+    }
+  }
+}
+
 struct CheckArgs {
   int64_t n; int32_t K;
   const int32_t* fk[LQ_MAX_DIMS];
@@ -88,6 +119,30 @@ int launch_materialize(const lq_star& star, void* T, int64_t ldt, int64_t row0, 
   a.T = T; a.ldt = ldt; a.kw = off;
   const int64_t total = rows * off;
   if (total <= 0) return LQ_OK;
+  {
+    const int32_t dt0 = a.c_f > 0 ? star.fact.dtype : star.dims[0].dtype;
+    const int vec = dt0 == LQ_BF16 ? 8 : 4;
+    const size_t es = dtype_size(dt0);
+    bool ok = aligned(T, 16) && ldt % vec == 0 && a.c_f % vec == 0 &&
+              (a.c_f == 0 || (aligned(a.X, 16) && a.ldx % vec == 0));
+    for (int k = 0; k < a.K && ok; ++k)
+      ok = a.c[k] % vec == 0 && a.ldd[k] % vec == 0 && aligned(a.D[k], 16);
+    (void)es;
+    if (ok) {
+      const int cpr = off / vec;
+      int group = 1;
+      while (group < cpr && group < 64) group <<= 1;
+      const int rpb = 256 / group;
+      const int64_t blocks = std::min<int64_t>((rows + rpb - 1) / rpb, 0x7fffffffLL);
+      switch (group) {
+#define LQ_MAT_CASE(G) case G: hipLaunchKernelGGL(materialize_vec_kernel<G>, dim3(static_cast<unsigned>(blocks)), dim3(256), 0, s, a, vec, cpr); break;
+        LQ_MAT_CASE(1) LQ_MAT_CASE(2) LQ_MAT_CASE(4) LQ_MAT_CASE(8) LQ_MAT_CASE(16) LQ_MAT_CASE(32) LQ_MAT_CASE(64)
+#undef LQ_MAT_CASE
+      }
+      LQ_LAUNCH_CHECK("materialize_vec_kernel");
+      return LQ_OK;
+    }
+  }
   const int64_t blocks = std::min<int64_t>((total + 255) / 256, static_cast<int64_t>(num_cus()) * 16);
   const int32_t dt = a.c_f > 0 ? star.fact.dtype : star.dims[0].dtype;
   if (dt == LQ_BF16)

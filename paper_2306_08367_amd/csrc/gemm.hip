@@ -1,113 +1,303 @@
 // Dense C = act(A * B + bias) on the matrix cores, fp32 accumulate.
 //
-// Used for the pre-fusion products P_k = D_k * (rows of L owned by dimension k)
-// (underlined terms of Eq. 1) and for the layer-by-layer model evaluation of the
-// non-fused pipeline (T * L, second line of Eq. 1).
-//
-// Tiling: a 256-thread workgroup (4 wavefronts) owns a 128 x 64 tile of C; each
-// wavefront owns 32 rows x 64 columns as two 32x32 MFMA accumulators.  A and B
-// tiles are staged through LDS k-major so that the 32 lanes reading one MFMA
-// operand hit 32 consecutive words.
+// Used for the pre-fusion products P_k = D_k * (rows of L owned by dimension k) (underlined terms
+// of Eq. 1) and for the layer-by-layer model evaluation of the non-fused pipeline (T * L, second
+// line of Eq. 1).  Two kernels:
+//   gemm_tiled_kernel  - 128 x BN tiles (BN = 64 or 128) staged through LDS, 4 wavefronts in a
+//                        2 x 2 arrangement, each owning 64 x BN/2 as 32x32 MFMA accumulators.
+//                        fp32 inputs use the 32x32x2 f32 MFMA; bf16 inputs stay bf16 in LDS and
+//                        use the 32x32x16 bf16 MFMA.  The next k-tile is fetched into registers
+//                        while the current one is multiplied.
+//   gemm_skinny_kernel - N <= 16 (linear models with a handful of outputs).  Bandwidth-shaped:
+//                        no LDS, every wavefront streams 16 rows of A at a time straight into
+//                        16x16 MFMA operands; B is tiny and comes from cache.
 #include "lq_common.h"
 
 namespace lq {
 namespace {
 
+typedef float v4f __attribute__((ext_vector_type(4)));
 typedef float v16f __attribute__((ext_vector_type(16)));
+typedef unsigned int v4u __attribute__((ext_vector_type(4)));
+typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
 
-constexpr int BM = 128, BN = 64, BK = 16;
-constexpr int PAD = 4;  // keeps rows of the k-major tiles on different banks for the staging stores
+struct GemmArgs {
+  const void* A; int64_t lda;
+  const void* B; int64_t ldb;
+  void* C; int64_t ldc;
+  const void* bias;
+  int64_t M; int32_t N; int32_t Kd;
+  int32_t relu;
+  int32_t a_vec_ok, b_vec_ok;   // 16-byte loads of A / B rows are legal
+  int32_t tiles_n;
+};
 
-template <typename TA, typename TC>
-__global__ __launch_bounds__(256) void gemm_kernel(const TA* __restrict__ A, int64_t lda,
-                                                   const TA* __restrict__ B, int64_t ldb,
-                                                   TC* __restrict__ C, int64_t ldc,
-                                                   const TA* __restrict__ bias, int64_t M,
-                                                   int32_t N, int32_t Kd, int relu,
-                                                   int32_t tiles_n) {
-  __shared__ float As[BK][BM + PAD];
-  __shared__ float Bs[BK][BN + PAD];
+// ------------------------------------------------------------------ tiled --------------
 
-  const int tid = threadIdx.x;
-  const int lane = tid & 63;
-  const int wave = tid >> 6;
-  const int64_t tile_m = static_cast<int64_t>(blockIdx.x) / tiles_n;
-  const int tile_n = static_cast<int>(static_cast<int64_t>(blockIdx.x) % tiles_n);
+constexpr int BM = 128;
+constexpr int TILED_THREADS = 256;
+
+template <typename T> struct Tile;
+template <> struct Tile<float> {
+  static constexpr int BK = 32;        // k per LDS tile
+  static constexpr int VEC = 4;        // elements per 16-byte chunk
+};
+template <> struct Tile<bf16_t> {
+  static constexpr int BK = 64;
+  static constexpr int VEC = 8;
+};
+
+// 16 bytes starting at p, of which only the first `valid` elements exist (others read as zero).
+template <typename T>
+__device__ __forceinline__ v4u load_chunk(const T* p, int valid, bool vec_ok) {
+  constexpr int VEC = Tile<T>::VEC;
+  if (valid >= VEC && vec_ok) return *reinterpret_cast<const v4u*>(p);
+  v4u r = {0u, 0u, 0u, 0u};
+  if (valid <= 0) return r;
+  if constexpr (sizeof(T) == 4) {
+#pragma unroll
+    for (int q = 0; q < 4; ++q)
+      if (q < valid) r[q] = reinterpret_cast<const unsigned int*>(p)[q];
+  } else {
+#pragma unroll
+    for (int q = 0; q < 8; ++q)
+      if (q < valid) r[q >> 1] |= static_cast<unsigned int>(p[q]) << (16 * (q & 1));
+  }
+  return r;
+}
+
+template <typename TA, typename TC, int BN>
+__global__ __launch_bounds__(TILED_THREADS) void gemm_tiled_kernel(GemmArgs g) {
+  constexpr int BK = Tile<TA>::BK, VEC = Tile<TA>::VEC;
+  constexpr bool F32 = sizeof(TA) == 4;
+  constexpr int WN = BN / 2;              // columns per wavefront
+  constexpr int TN = WN / 32;             // 32-wide MFMA tiles per wavefront along n (1 or 2)
+  constexpr int A_CHUNKS = BM * BK / VEC / TILED_THREADS;   // 16-byte chunks per thread
+  constexpr int B_CHUNKS = BK * BN / VEC / TILED_THREADS;
+  constexpr int A_CPR = BK / VEC;         // chunks per A row
+  constexpr int B_CPR = BN / VEC;         // chunks per B row
+  // fp32: k-major tiles  As[k][m], Bs[k][n] (one word per MFMA operand read).
+  // bf16: As[m][k], Bs[n][k] with k contiguous (eight consecutive k per MFMA operand read).
+  constexpr int PADF = 4, PADH = 8;
+  constexpr int A_WORDS = F32 ? BK * (BM + PADF) : BM * (BK + PADH) / 2;
+  constexpr int B_WORDS = F32 ? BK * (BN + PADF) : BN * (BK + PADH) / 2;
+  __shared__ __align__(16) unsigned int smemA[A_WORDS];
+  __shared__ __align__(16) unsigned int smemB[B_WORDS];
+
+  const TA* __restrict__ A = static_cast<const TA*>(g.A);
+  const TA* __restrict__ B = static_cast<const TA*>(g.B);
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  const int wm = wave >> 1, wn = wave & 1;
+  const int64_t tile_m = static_cast<int64_t>(blockIdx.x) / g.tiles_n;
+  const int tile_n = static_cast<int>(static_cast<int64_t>(blockIdx.x) % g.tiles_n);
   const int64_t m0 = tile_m * BM;
   const int n0 = tile_n * BN;
 
-  v16f acc0 = {0}, acc1 = {0};
+  v16f acc[2][TN];
+#pragma unroll
+  for (int i = 0; i < 2; ++i)
+#pragma unroll
+    for (int j = 0; j < TN; ++j)
+#pragma unroll
+      for (int v = 0; v < 16; ++v) acc[i][j][v] = 0.f;
 
-  for (int k0 = 0; k0 < Kd; k0 += BK) {
-    // A tile: 128 rows x 16 k.  Thread t stages row t/2, k in [8*(t&1), +8).
-    {
-      const int r = tid >> 1;
-      const int kb = (tid & 1) * 8;
-      const int64_t row = m0 + r;
-      const TA* src = A + row * lda + k0 + kb;
+  v4u ra[A_CHUNKS], rb[B_CHUNKS];
+  auto fetch = [&](int k0) {
 #pragma unroll
-      for (int q = 0; q < 8; ++q) {
-        float v = 0.f;
-        if (row < M && k0 + kb + q < Kd) v = Elem<TA>::load(src + q);
-        As[kb + q][r] = v;
+    for (int c = 0; c < A_CHUNKS; ++c) {
+      const int id = tid + c * TILED_THREADS;
+      const int r = id / A_CPR, kc = (id % A_CPR) * VEC;
+      const int64_t row = min(m0 + r, g.M - 1);            // rows past the end repeat the last row
+      ra[c] = load_chunk<TA>(A + row * g.lda + k0 + kc, g.Kd - (k0 + kc), g.a_vec_ok);
+    }
+#pragma unroll
+    for (int c = 0; c < B_CHUNKS; ++c) {
+      const int id = tid + c * TILED_THREADS;
+      const int kk = id / B_CPR, nc = (id % B_CPR) * VEC;
+      const int k = k0 + kk;
+      rb[c] = load_chunk<TA>(B + static_cast<int64_t>(min(k, g.Kd - 1)) * g.ldb + n0 + nc,
+                             k < g.Kd ? g.N - (n0 + nc) : 0, g.b_vec_ok);
+    }
+  };
+  auto stage = [&]() {
+#pragma unroll
+    for (int c = 0; c < A_CHUNKS; ++c) {
+      const int id = tid + c * TILED_THREADS;
+      const int r = id / A_CPR, kc = (id % A_CPR) * VEC;
+      if constexpr (F32) {
+#pragma unroll
+        for (int q = 0; q < 4; ++q) smemA[(kc + q) * (BM + PADF) + r] = ra[c][q];
+      } else {
+        *reinterpret_cast<v4u*>(&smemA[(r * (BK + PADH) + kc) / 2]) = ra[c];
       }
     }
-    // B tile: 16 k x 64 columns.  Thread t stages k = t/16, columns 4*(t%16) .. +4.
-    {
-      const int kk = tid >> 4;
-      const int cb = (tid & 15) * 4;
-      const TA* src = B + static_cast<int64_t>(k0 + kk) * ldb + n0 + cb;
 #pragma unroll
-      for (int q = 0; q < 4; ++q) {
-        float v = 0.f;
-        if (k0 + kk < Kd && n0 + cb + q < N) v = Elem<TA>::load(src + q);
-        Bs[kk][cb + q] = v;
+    for (int c = 0; c < B_CHUNKS; ++c) {
+      const int id = tid + c * TILED_THREADS;
+      const int kk = id / B_CPR, nc = (id % B_CPR) * VEC;
+      if constexpr (F32) {
+        *reinterpret_cast<v4u*>(&smemB[kk * (BN + PADF) + nc]) = rb[c];
+      } else {
+        unsigned short* sb = reinterpret_cast<unsigned short*>(smemB);
+#pragma unroll
+        for (int q = 0; q < 8; ++q)
+          sb[(nc + q) * (BK + PADH) + kk] = static_cast<unsigned short>(rb[c][q >> 1] >> (16 * (q & 1)));
       }
     }
+  };
+
+  fetch(0);
+  for (int k0 = 0; k0 < g.Kd; k0 += BK) {
+    __syncthreads();          // previous tile fully consumed
+    stage();
     __syncthreads();
+    if (k0 + BK < g.Kd) fetch(k0 + BK);
+    if constexpr (F32) {
+      const float* As = reinterpret_cast<const float*>(smemA);
+      const float* Bs = reinterpret_cast<const float*>(smemB);
+#pragma unroll 4
+      for (int kk = 0; kk < BK; kk += 2) {
+        const int k = kk + (lane >> 5);
+        float a[2], b[TN];
 #pragma unroll
-    for (int kk = 0; kk < BK; kk += 2) {
-      const int k = kk + (lane >> 5);
-      const float a = As[k][wave * 32 + (lane & 31)];
-      const float b0 = Bs[k][lane & 31];
-      const float b1 = Bs[k][32 + (lane & 31)];
-      acc0 = __builtin_amdgcn_mfma_f32_32x32x2f32(a, b0, acc0, 0, 0, 0);
-      acc1 = __builtin_amdgcn_mfma_f32_32x32x2f32(a, b1, acc1, 0, 0, 0);
+        for (int i = 0; i < 2; ++i) a[i] = As[k * (BM + PADF) + wm * 64 + i * 32 + (lane & 31)];
+#pragma unroll
+        for (int j = 0; j < TN; ++j) b[j] = Bs[k * (BN + PADF) + wn * WN + j * 32 + (lane & 31)];
+#pragma unroll
+        for (int i = 0; i < 2; ++i)
+#pragma unroll
+          for (int j = 0; j < TN; ++j)
+            acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x2f32(a[i], b[j], acc[i][j], 0, 0, 0);
+      }
+    } else {
+#pragma unroll
+      for (int kk = 0; kk < BK; kk += 16) {
+        const int k = kk + 8 * (lane >> 5);
+        v4u a[2], b[TN];
+#pragma unroll
+        for (int i = 0; i < 2; ++i)
+          a[i] = *reinterpret_cast<const v4u*>(&smemA[((wm * 64 + i * 32 + (lane & 31)) * (BK + PADH) + k) / 2]);
+#pragma unroll
+        for (int j = 0; j < TN; ++j)
+          b[j] = *reinterpret_cast<const v4u*>(&smemB[((wn * WN + j * 32 + (lane & 31)) * (BK + PADH) + k) / 2]);
+#pragma unroll
+        for (int i = 0; i < 2; ++i)
+#pragma unroll
+          for (int j = 0; j < TN; ++j)
+            acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, a[i]),
+                                                                __builtin_bit_cast(bf16x8, b[j]), acc[i][j], 0, 0, 0);
+      }
     }
-    __syncthreads();
   }
 
-  // 32x32 accumulator layout: register v of lane l holds row 8*(v/4) + 4*(l/32) + v%4, column l%32.
-  const int col_in = lane & 31;
+  // 32x32 accumulator: register v of lane l is row 8*(v/4) + 4*(l/32) + v%4, column l%32.
+  TC* __restrict__ C = static_cast<TC*>(g.C);
+  const TA* bias = static_cast<const TA*>(g.bias);
 #pragma unroll
-  for (int half = 0; half < 2; ++half) {
-    const int col = n0 + half * 32 + col_in;
-    if (col >= N) continue;
+  for (int j = 0; j < TN; ++j) {
+    const int col = n0 + wn * WN + j * 32 + (lane & 31);
+    if (col >= g.N) continue;
     const float bv = bias ? Elem<TA>::load(bias + col) : 0.f;
 #pragma unroll
-    for (int v = 0; v < 16; ++v) {
-      const int r = wave * 32 + 8 * (v >> 2) + 4 * (lane >> 5) + (v & 3);
-      const int64_t row = m0 + r;
-      if (row >= M) continue;
-      float x = (half ? acc1[v] : acc0[v]) + bv;
-      if (relu) x = fmaxf(x, 0.f);
-      Elem<TC>::store(C + row * ldc + col, x);
+    for (int i = 0; i < 2; ++i)
+#pragma unroll
+      for (int v = 0; v < 16; ++v) {
+        const int64_t row = m0 + wm * 64 + i * 32 + 8 * (v >> 2) + 4 * (lane >> 5) + (v & 3);
+        if (row >= g.M) continue;
+        float x = acc[i][j][v] + bv;
+        if (g.relu) x = fmaxf(x, 0.f);
+        Elem<TC>::store(C + row * g.ldc + col, x);
+      }
+  }
+}
+
+// ------------------------------------------------------------------ skinny -------------
+
+constexpr int SKINNY_THREADS = 256;
+
+// N <= 16.  A wavefront takes 16 rows per pass; lane (g = lane / 16, i = lane % 16) loads 16-byte
+// pieces of row i at k = kc + VEC*g and feeds them element by element as the K-slices of 16x16
+// MFMAs whose B operand holds the matching rows of the weight matrix (which rows of k a slot
+// means is irrelevant as long as A and B agree, and they are built from the same index).
+template <typename TA, typename TC>
+__global__ __launch_bounds__(SKINNY_THREADS) void gemm_skinny_kernel(GemmArgs g) {
+  constexpr int VEC = Tile<TA>::VEC;
+  constexpr bool F32 = sizeof(TA) == 4;
+  constexpr int KSTEP = 4 * VEC;             // k covered by one 16-byte load per lane
+  const TA* __restrict__ A = static_cast<const TA*>(g.A);
+  const TA* __restrict__ B = static_cast<const TA*>(g.B);
+  const int lane = threadIdx.x & 63, grp = lane >> 4, i = lane & 15;
+  const int64_t wave = static_cast<int64_t>(blockIdx.x) * (SKINNY_THREADS / 64) + (threadIdx.x >> 6);
+  const int64_t nwaves = static_cast<int64_t>(gridDim.x) * (SKINNY_THREADS / 64);
+  const int64_t npass = (g.M + 15) / 16;
+  const float bv = (g.bias && i < g.N) ? Elem<TA>::load(static_cast<const TA*>(g.bias) + i) : 0.f;
+
+  for (int64_t pass = wave; pass < npass; pass += nwaves) {
+    const int64_t row = min(pass * 16 + i, g.M - 1);
+    const TA* ar = A + row * g.lda;
+    v4f acc = {0.f, 0.f, 0.f, 0.f};
+    for (int kc = 0; kc < g.Kd; kc += KSTEP) {
+      const int k = kc + VEC * grp;
+      const v4u a = load_chunk<TA>(ar + k, g.Kd - k, g.a_vec_ok);
+      // B operand: lane (grp, n = i) needs W[k + t][n] for t = 0..VEC-1
+      if constexpr (F32) {
+#pragma unroll
+        for (int t = 0; t < 4; ++t) {
+          const float b = (k + t < g.Kd && i < g.N) ? B[static_cast<int64_t>(k + t) * g.ldb + i] : 0.f;
+          acc = __builtin_amdgcn_mfma_f32_16x16x4f32(__uint_as_float(a[t]), b, acc, 0, 0, 0);
+        }
+      } else {
+        v4u b = {0u, 0u, 0u, 0u};
+#pragma unroll
+        for (int t = 0; t < 8; ++t)
+          if (k + t < g.Kd && i < g.N)
+            b[t >> 1] |= static_cast<unsigned int>(B[static_cast<int64_t>(k + t) * g.ldb + i]) << (16 * (t & 1));
+        acc = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, a), __builtin_bit_cast(bf16x8, b),
+                                                      acc, 0, 0, 0);
+      }
+    }
+    // register v of lane (grp, n) is row 4*grp + v of the pass, column n
+    if (i < g.N) {
+      TC* __restrict__ C = static_cast<TC*>(g.C);
+#pragma unroll
+      for (int v = 0; v < 4; ++v) {
+        const int64_t r = pass * 16 + 4 * grp + v;
+        if (r >= g.M) continue;
+        float x = acc[v] + bv;
+        if (g.relu) x = fmaxf(x, 0.f);
+        Elem<TC>::store(C + r * g.ldc + i, x);
+      }
     }
   }
 }
 
 template <typename TA, typename TC>
-int launch_typed(const void* A, int64_t lda, const void* B, int64_t ldb, void* C, int64_t ldc,
-                 const void* bias, int64_t M, int32_t N, int32_t Kd, int relu, hipStream_t s) {
-  const int64_t tiles_m = (M + BM - 1) / BM;
-  const int32_t tiles_n = (N + BN - 1) / BN;
-  const int64_t blocks = tiles_m * tiles_n;
-  if (blocks <= 0) return LQ_OK;
+int launch_typed(GemmArgs g, hipStream_t s) {
+  if (g.M <= 0 || g.N <= 0) return LQ_OK;
+  const size_t es = sizeof(TA);
+  constexpr int VEC = Tile<TA>::VEC;
+  g.a_vec_ok = aligned(g.A, 16) && (g.lda * es) % 16 == 0;
+  g.b_vec_ok = aligned(g.B, 16) && (g.ldb * es) % 16 == 0;
+  (void)VEC;
+  if (g.N <= 16) {
+    const int64_t npass = (g.M + 15) / 16;
+    const int64_t blocks = std::min<int64_t>((npass + 3) / 4, static_cast<int64_t>(num_cus()) * 8);
+    hipLaunchKernelGGL((gemm_skinny_kernel<TA, TC>), dim3(static_cast<unsigned>(blocks)), dim3(SKINNY_THREADS),
+                       0, s, g);
+    LQ_LAUNCH_CHECK("gemm_skinny_kernel");
+    return LQ_OK;
+  }
+  const bool wide = g.N > 64;
+  const int bn = wide ? 128 : 64;
+  const int64_t tiles_m = (g.M + BM - 1) / BM;
+  g.tiles_n = (g.N + bn - 1) / bn;
+  const int64_t blocks = tiles_m * g.tiles_n;
   if (blocks > 0x7fffffffLL) return fail(LQ_ERR_UNSUPPORTED, "gemm: %lld tiles exceed one grid", (long long)blocks);
-  hipLaunchKernelGGL((gemm_kernel<TA, TC>), dim3(static_cast<unsigned>(blocks)), dim3(256), 0, s,
-                     static_cast<const TA*>(A), lda, static_cast<const TA*>(B), ldb,
-                     static_cast<TC*>(C), ldc, static_cast<const TA*>(bias), M, N, Kd, relu, tiles_n);
-  LQ_LAUNCH_CHECK("gemm_kernel");
+  if (wide)
+    hipLaunchKernelGGL((gemm_tiled_kernel<TA, TC, 128>), dim3(static_cast<unsigned>(blocks)), dim3(TILED_THREADS), 0, s, g);
+  else
+    hipLaunchKernelGGL((gemm_tiled_kernel<TA, TC, 64>), dim3(static_cast<unsigned>(blocks)), dim3(TILED_THREADS), 0, s, g);
+  LQ_LAUNCH_CHECK("gemm_tiled_kernel");
   return LQ_OK;
 }
 
@@ -117,12 +307,12 @@ int launch_typed(const void* A, int64_t lda, const void* B, int64_t ldb, void* C
 int launch_gemm(const void* A, int64_t lda, const void* B, int64_t ldb, void* C, int64_t ldc,
                 const void* bias, int64_t M, int32_t N, int32_t Kd, int relu, int32_t in_dtype,
                 int32_t out_dtype, hipStream_t s) {
-  if (in_dtype == LQ_F32 && out_dtype == LQ_F32)
-    return launch_typed<float, float>(A, lda, B, ldb, C, ldc, bias, M, N, Kd, relu, s);
-  if (in_dtype == LQ_BF16 && out_dtype == LQ_F32)
-    return launch_typed<bf16_t, float>(A, lda, B, ldb, C, ldc, bias, M, N, Kd, relu, s);
-  if (in_dtype == LQ_BF16 && out_dtype == LQ_BF16)
-    return launch_typed<bf16_t, bf16_t>(A, lda, B, ldb, C, ldc, bias, M, N, Kd, relu, s);
+  GemmArgs g{};
+  g.A = A; g.lda = lda; g.B = B; g.ldb = ldb; g.C = C; g.ldc = ldc; g.bias = bias;
+  g.M = M; g.N = N; g.Kd = Kd; g.relu = relu;
+  if (in_dtype == LQ_F32 && out_dtype == LQ_F32) return launch_typed<float, float>(g, s);
+  if (in_dtype == LQ_BF16 && out_dtype == LQ_F32) return launch_typed<bf16_t, float>(g, s);
+  if (in_dtype == LQ_BF16 && out_dtype == LQ_BF16) return launch_typed<bf16_t, bf16_t>(g, s);
   return fail(LQ_ERR_DTYPE, "gemm: f32 inputs cannot produce a bf16 result");
 }
 
