@@ -92,7 +92,9 @@ template <> struct Chunk<float, 4> {
     v[0] = t.x; v[1] = t.y; v[2] = t.z; v[3] = t.w;
   }
   static __device__ __forceinline__ void store(float* p, const float (&v)[4]) {
-    *reinterpret_cast<float4*>(p) = make_float4(v[0], v[1], v[2], v[3]);
+    typedef float v4f_ __attribute__((ext_vector_type(4)));
+    const v4f_ t = {v[0], v[1], v[2], v[3]};
+    __builtin_nontemporal_store(t, reinterpret_cast<v4f_*>(p));   // written once, never re-read here
   }
 };
 template <> struct Chunk<float, 1> {
@@ -192,7 +194,7 @@ __global__ __launch_bounds__(VEC_THREADS) void fused_vec_kernel(PredictArgs a) {
         for (int v = 0; v < VEC; ++v) z[v] = fmaf(xq[q], wf[q][v], z[v]);
     }
     for (int k = 0; k < a.K; ++k) {
-      const int64_t j = a.fk[k][rr];
+      const int64_t j = __builtin_nontemporal_load(a.fk[k] + rr);   // keys are read once: do not let them displace table rows in cache
       float p[VEC];
       Chunk<TP, VEC>::load(static_cast<const TP*>(a.P[k]) + j * a.ldp[k] + col0, p);
 #pragma unroll

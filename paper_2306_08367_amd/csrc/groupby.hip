@@ -465,12 +465,12 @@ int launch_fast(const FastArgs& a, const FastLaunch& L) {
 
 // ---------------------------------------------------------------- fold ------------------
 
-constexpr int FOLD_THREADS = 256;
-constexpr int FOLD_PARTS = 32;                       // threads sharing one accumulator
+constexpr int FOLD_THREADS = 512;
+constexpr int FOLD_PARTS = 64;                       // threads sharing one accumulator
 constexpr int FOLD_ACCS = FOLD_THREADS / FOLD_PARTS; // accumulators per workgroup
 
 // sums / counts [i] = sum over workgroups b of partial[b][i].  Eight consecutive accumulators per
-// workgroup, each summed by 32 threads striding over the partial rows, then combined in LDS.
+// workgroup, each summed by 64 threads striding over the partial rows, then combined in LDS.
 __global__ __launch_bounds__(FOLD_THREADS) void fold_kernel(GbArgs a, int rows_written) {
   __shared__ unsigned long long part[FOLD_PARTS][FOLD_ACCS];
   const int n_acc = (a.M + 1) * a.G;
