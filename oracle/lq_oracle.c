@@ -255,3 +255,77 @@ int lqo_groupby_sum(int64_t n, int32_t K, const int32_t* const* fk,
   free(priv);
   return bad ? -2 : 0;
 }
+
+/* ------------------------------------------------------------------------------------------
+ * Decision tree in matrix form (Section 3.3.1) and its fusion with the dimensions (Eq. 2).
+ *
+ *   feature[q]  column of the joined table T tested by internal node q: the matrix F of step 1
+ *               has its single 1 of column q in row feature[q] (F only selects columns)
+ *   v[q]        threshold of node q (step 2: B = (T F > v), entries 0/1)
+ *   H [p x l]   H[q][j] = +1 / -1 if node q lies on the path to leaf j and the path takes its
+ *               True / False side, 0 if node q is not on that path (step 3: R = B H)
+ *   h[j]        value R takes exactly when leaf j is reached.  A leaf is reached iff all its +1
+ *               nodes are true and all its -1 nodes are false, i.e. R_j = number of +1 entries
+ *               of column j.  (The paper words h as "the column sum of H", which cannot be meant
+ *               literally for a 0/1 predicate matrix; see the design notes.)
+ *   step 4      onehot[i][j] = (R[i][j] == h[j]);  leaf[i] = first j with onehot 1, -1 if none.
+ * ------------------------------------------------------------------------------------------ */
+
+/* Plain definition: materialise the tuple, then the four steps.  R (int32, [n x l]) may be NULL. */
+int lqo_tree_predict(int64_t n, int32_t c_f, const double* X, int32_t K, const int32_t* c,
+                     const double* const* D, const int32_t* const* fk, int32_t p, int32_t l,
+                     const int32_t* feature, const double* v, const int8_t* H, int32_t* R,
+                     uint8_t* onehot, int32_t* leaf) {
+  int64_t kw = c_f;
+  for (int32_t k = 0; k < K; ++k) kw += c[k];
+  for (int32_t q = 0; q < p; ++q)
+    if (feature[q] < 0 || feature[q] >= kw) return -1;
+  double* t = (double*)malloc(sizeof(double) * (size_t)(kw + 1));
+  int32_t* r = (int32_t*)malloc(sizeof(int32_t) * (size_t)(l + 1));
+  int32_t* h = (int32_t*)malloc(sizeof(int32_t) * (size_t)(l + 1));
+  if (!t || !r || !h) { free(t); free(r); free(h); return -1; }
+  for (int32_t j = 0; j < l; ++j) {
+    h[j] = 0;
+    for (int32_t q = 0; q < p; ++q) h[j] += H[(int64_t)q * l + j] == 1;
+  }
+  for (int64_t i = 0; i < n; ++i) {
+    build_tuple(i, c_f, X, K, c, D, fk, t);
+    for (int32_t j = 0; j < l; ++j) r[j] = 0;
+    for (int32_t q = 0; q < p; ++q) {
+      const int b = t[feature[q]] > v[q];                 /* steps 1 and 2 */
+      if (b)
+        for (int32_t j = 0; j < l; ++j) r[j] += H[(int64_t)q * l + j];   /* step 3 */
+    }
+    int32_t first = -1;
+    for (int32_t j = 0; j < l; ++j) {
+      const int hit = r[j] == h[j];                       /* step 4 */
+      if (R) R[i * (int64_t)l + j] = r[j];
+      if (onehot) onehot[i * (int64_t)l + j] = (uint8_t)hit;
+      if (hit && first < 0) first = j;
+    }
+    if (leaf) leaf[i] = first;
+  }
+  free(t); free(r); free(h);
+  return 0;
+}
+
+/*
+ * Pre-fused table of one dimension (the terms T_j of Eq. 2):
+ *   Tk[r][j] = sum over the nodes q whose tested column belongs to this dimension of
+ *              (D[r][feature[q] - col_off] > v[q]) * H[q][j].
+ * Nodes testing other tables' columns contribute nothing here (they are evaluated where their
+ * column lives), so that the partial tables add up to (T F > v) H.
+ */
+int lqo_tree_project(int64_t r, int32_t c, const double* D, int32_t col_off, int32_t p, int32_t l,
+                     const int32_t* feature, const double* v, const int8_t* H, int32_t* Tk) {
+  for (int64_t i = 0; i < r; ++i) {
+    for (int32_t j = 0; j < l; ++j) Tk[i * l + j] = 0;
+    for (int32_t q = 0; q < p; ++q) {
+      const int32_t f = feature[q] - col_off;
+      if (f < 0 || f >= c) continue;
+      if (D[i * c + f] > v[q])
+        for (int32_t j = 0; j < l; ++j) Tk[i * l + j] += H[(int64_t)q * l + j];
+    }
+  }
+  return 0;
+}

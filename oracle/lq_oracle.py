@@ -41,7 +41,7 @@ def _load():
         lib = ctypes.CDLL(_LIB)
         lib.lqo_max_threads.restype = ctypes.c_int
         for name in ("lqo_join_predict", "lqo_materialize", "lqo_project_dims",
-                     "lqo_gather_sum", "lqo_groupby_sum"):
+                     "lqo_gather_sum", "lqo_groupby_sum", "lqo_tree_predict", "lqo_tree_project"):
             getattr(lib, name).restype = ctypes.c_int
         _lib = lib
     return _lib
@@ -235,3 +235,53 @@ def groupby_sum(fks, dim_rows, dim_mask, dim_code, group_card, fact_mask, measur
     if rc != 0:
         raise MemoryError("oracle allocation failed")
     return sums, counts
+
+
+def _tree_arrays(feature, threshold, H):
+    feature = _i32(feature).reshape(-1)
+    v = _f64(threshold).reshape(-1)
+    if hasattr(H, "detach"):
+        H = H.detach().cpu().numpy()
+    H = np.ascontiguousarray(np.asarray(H).astype(np.int8))
+    if H.ndim != 2 or H.shape[0] != feature.shape[0] or v.shape[0] != feature.shape[0]:
+        raise ValueError("feature, threshold and H disagree on the number of nodes")
+    if H.size and (H.min() < -1 or H.max() > 1):
+        raise ValueError("H entries must be -1, 0 or 1")
+    return feature, v, H
+
+
+def tree_predict(X, dims, fks, feature, threshold, H):
+    """((T F > v) H) == h on the materialised join.  Returns (R int32 [n x l], onehot uint8 [n x l],
+    leaf int32 [n])."""
+    lib = _load()
+    n, c_f, X, dims, fks = _prep_star(X, dims, fks)
+    feature, v, H = _tree_arrays(feature, threshold, H)
+    p, l = H.shape
+    R = np.empty((n, l), dtype=np.int32)
+    onehot = np.empty((n, l), dtype=np.uint8)
+    leaf = np.empty((n,), dtype=np.int32)
+    rc = lib.lqo_tree_predict(ctypes.c_int64(n), ctypes.c_int32(c_f), _pd(X), ctypes.c_int32(len(dims)),
+                              _i32_array([d.shape[1] for d in dims]), _ptr_array(dims), _ptr_array(fks),
+                              ctypes.c_int32(p), ctypes.c_int32(l), _pd(feature), _pd(v), _pd(H),
+                              _pd(R), _pd(onehot), _pd(leaf))
+    if rc != 0:
+        raise ValueError("a node tests a column outside the joined table")
+    return R, onehot, leaf
+
+
+def tree_project(dims, c_f, feature, threshold, H) -> list:
+    """Pre-fused tables of Eq. 2, one int32 [r_k x l] per dimension (each node is evaluated only
+    in the table that owns its column)."""
+    lib = _load()
+    feature, v, H = _tree_arrays(feature, threshold, H)
+    p, l = H.shape
+    out, off = [], int(c_f)
+    for d in dims:
+        d = _f64(d)
+        Tk = np.empty((d.shape[0], l), dtype=np.int32)
+        lib.lqo_tree_project(ctypes.c_int64(d.shape[0]), ctypes.c_int32(d.shape[1]), _pd(d),
+                             ctypes.c_int32(off), ctypes.c_int32(p), ctypes.c_int32(l), _pd(feature),
+                             _pd(v), _pd(H), _pd(Tk))
+        out.append(Tk)
+        off += d.shape[1]
+    return out

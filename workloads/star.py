@@ -238,3 +238,80 @@ def take_rows(w: PredictWorkload, rows: torch.Tensor) -> PredictWorkload:
                            [d.cpu() for d in w.dims], [f[dev_rows].cpu() for f in w.fks],
                            [x.cpu() for x in w.weights],
                            [None if b is None else b.cpu() for b in w.biases], w.dtype)
+
+
+# --- decision trees in matrix form (Section 3.3.1) ----------------------------------------
+
+@dataclass
+class TreeModel:
+    """A binary decision tree both as a linked structure and in the matrix form of the paper."""
+    feature: torch.Tensor        # int32 [p]   column of the joined table tested by node q
+    threshold: torch.Tensor      # fp32  [p]   node q goes to its True side when value > threshold
+    H: torch.Tensor              # int8  [p x l]  +1 / -1 / 0 path matrix
+    true_child: List[int]        # >= 0: internal node, < 0: leaf -(id + 1)
+    false_child: List[int]
+
+    @property
+    def n_nodes(self) -> int:
+        return int(self.feature.shape[0])
+
+    @property
+    def n_leaves(self) -> int:
+        return int(self.H.shape[1])
+
+
+def make_tree(n_cols: int, n_leaves: int, seed: int, cols: Optional[Sequence[int]] = None,
+              sigma: float = 0.7) -> TreeModel:
+    """Random binary tree with ``n_leaves`` leaves over the columns ``cols`` (default: all
+    ``n_cols`` columns of the joined table).  Internal nodes are numbered in creation order
+    (root = 0), leaves left to right with the False side on the left."""
+    if n_leaves < 2:
+        raise ValueError("a tree needs at least two leaves")
+    rng = np.random.default_rng(seed)
+    cols = list(range(n_cols)) if cols is None else list(cols)
+    # grow: every leaf is a slot (parent, side); splitting a slot creates a node with two slots
+    true_child, false_child = [], []
+    slots = [None]                      # root slot
+    while len(slots) + len(true_child) < 2 * n_leaves - 1 or len(slots) < n_leaves:
+        if len(slots) >= n_leaves:
+            break
+        s = slots.pop(int(rng.integers(0, len(slots))))
+        q = len(true_child)
+        true_child.append(None)
+        false_child.append(None)
+        if s is not None:
+            parent, side = s
+            (true_child if side else false_child)[parent] = q
+        slots.append((q, 0))
+        slots.append((q, 1))
+    p = len(true_child)
+    # number the leaves left to right (False side first) by a walk from the root
+    leaf_of_slot = {}
+    order = []
+
+    def walk(q):
+        for side, arr in ((0, false_child), (1, true_child)):
+            if arr[q] is None:
+                leaf_of_slot[(q, side)] = len(order)
+                order.append((q, side))
+            else:
+                walk(arr[q])
+    walk(0)
+    for (q, side), leaf in leaf_of_slot.items():
+        (true_child if side else false_child)[q] = -(leaf + 1)
+    l = len(order)
+    H = np.zeros((p, l), dtype=np.int8)
+
+    def mark(q, path):
+        for side, arr in ((0, false_child), (1, true_child)):
+            step = path + [(q, 1 if side else -1)]
+            if arr[q] < 0:
+                for node, sign in step:
+                    H[node, -arr[q] - 1] = sign
+            else:
+                mark(arr[q], step)
+    mark(0, [])
+    feature = rng.choice(np.asarray(cols), size=p).astype(np.int32)
+    threshold = (rng.standard_normal(p) * sigma).astype(np.float32)
+    return TreeModel(torch.from_numpy(feature), torch.from_numpy(threshold), torch.from_numpy(H),
+                     [int(x) for x in true_child], [int(x) for x in false_child])
