@@ -180,6 +180,64 @@ size_t lq_workspace_bytes(int which_call, const lq_star* star, const lq_model* m
 size_t lq_groupby_workspace_bytes(int32_t n_dims, const int64_t* dim_rows,
                                   const int32_t* group_card, int32_t n_measures);
 
+/* ---------------------------------------------------------------------------------------
+ * Decision trees (Section 3.3).  The tree is given in the matrix form of Section 3.3.1:
+ *   feature[q]    column of the joined table T that internal node q tests (the matrix F only
+ *                 selects columns: its column q has its single 1 in row feature[q])
+ *   threshold[q]  the vector v: node q is true when the tested value is > threshold[q]
+ *   H [p x l]     +1 / -1 where node q lies on the path to leaf j on its True / False side, else 0
+ * The vector h the result is compared with is the number of +1 entries per column of H (the
+ * value R = (T F > v) H takes exactly when that leaf is reached).  All three arrays live on the
+ * device.  Paths longer than 255 nodes are not supported.
+ * ------------------------------------------------------------------------------------- */
+typedef struct {
+  int32_t        n_nodes;    /* p >= 1 */
+  int32_t        n_leaves;   /* l >= 1 */
+  const int32_t* feature;    /* device, [p], values in [0, c_f + sum c_k) */
+  const float*   threshold;  /* device, [p] */
+  const int8_t*  H;          /* device, [p x l] row-major */
+} lq_tree;
+
+/* Row stride (bytes) of the pre-fused tree tables for l leaves: l rounded up to 16. */
+int64_t lq_tree_table_ld(int32_t n_leaves);
+
+/*
+ * Pre-fusion of a tree (the tables T_j of Eq. 2), one uint8 table [r_k x ld] per dimension.
+ * Each dimension evaluates only the nodes whose tested column it owns (a node of another table
+ * would otherwise be evaluated on a zero and counted where its threshold is negative).  The
+ * tables do not hold the signed partial sums of (D_k M_k F > v) H but the same information
+ * shifted to be non-negative: entry [r][j] = number of owned nodes on the path to leaf j whose
+ * outcome for row r agrees with the path (+1 nodes true, -1 nodes false).  Summed over the
+ * tables (and the fact table's own nodes) it equals the path length exactly when R_j = h_j.
+ *   tables  host array of K device pointers, each r_k * ld bytes, ld = lq_tree_table_ld(l)
+ *   target  device, ld bytes: path length of leaf j for j < l, 0xFF padding after
+ * star->fks is not used.  dims must be f32.
+ */
+int lq_tree_project_dims(const lq_star* star, const lq_tree* tree, void* const* tables,
+                         uint8_t* target, void* hip_stream);
+
+/*
+ * Join-computation stage of Eq. 2: per fact row, gather one table row per dimension, add them
+ * (plus the agreement counts of nodes that test fact-table columns, evaluated on the spot),
+ * compare with `target`.
+ *   leaf    device int32 [n] or NULL: the first leaf j with R_j = h_j, -1 if none
+ *   onehot  device uint8 [n x l] (row stride l) or NULL: (R == h), the paper's binary encoding
+ * star->dims is not used (may be NULL); star->fact is needed only if a node tests a fact column.
+ */
+int lq_fused_join_tree(const lq_star* star, const lq_tree* tree, const void* const* tables,
+                       const uint8_t* target, int32_t* leaf, uint8_t* onehot, uint32_t flags,
+                       void* ws, size_t ws_bytes, void* hip_stream);
+
+/*
+ * Non-fused tree pipeline: T is written to the workspace chunk by chunk, then
+ * ((T F > v) H) == h is evaluated on it.  Workspace as for lq_materialized_join_predict with a
+ * one-layer model of the joined width (lq_tree_workspace_bytes gives the size).
+ */
+int lq_materialized_join_tree(const lq_star* star, const lq_tree* tree, int32_t* leaf,
+                              uint8_t* onehot, void* ws, size_t ws_bytes, uint32_t flags,
+                              void* hip_stream);
+size_t lq_tree_workspace_bytes(const lq_star* star, int64_t chunk_rows);
+
 /*
  * Plain device-to-device copy of `bytes` bytes (16-byte aligned pointers, bytes a
  * multiple of 16) by a grid-stride kernel.  Not part of the method: it is the

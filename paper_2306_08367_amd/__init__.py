@@ -9,5 +9,6 @@ from .binding import (  # noqa: F401
     LQ_CHECK_FKS, LQ_FORCE_GENERIC, LQError, lib_path, lq_fused_join_predict,
     lq_groupby_workspace_bytes, lq_last_error, lq_masked_groupby_sum,
     lq_materialized_join_predict, lq_project_dims, lq_stream_copy, lq_version,
-    lq_workspace_bytes,
+    lq_workspace_bytes, lq_tree_table_ld, lq_tree_project_dims, lq_fused_join_tree,
+    lq_materialized_join_tree,
 )

@@ -41,6 +41,11 @@ class lq_star(ctypes.Structure):
                 ("dims", ctypes.POINTER(lq_mat)), ("fks", ctypes.POINTER(ctypes.c_void_p))]
 
 
+class lq_tree(ctypes.Structure):
+    _fields_ = [("n_nodes", ctypes.c_int32), ("n_leaves", ctypes.c_int32), ("feature", ctypes.c_void_p),
+                ("threshold", ctypes.c_void_p), ("H", ctypes.c_void_p)]
+
+
 class lq_model(ctypes.Structure):
     _fields_ = [("n_layers", ctypes.c_int32), ("W", ctypes.POINTER(lq_mat)),
                 ("bias", ctypes.POINTER(ctypes.c_void_p))]
@@ -70,10 +75,19 @@ def _load():
     lib.lq_groupby_workspace_bytes.argtypes = [i32, ctypes.POINTER(i64), ctypes.POINTER(i32), i32]
     lib.lq_groupby_workspace_bytes.restype = sz
     lib.lq_stream_copy.argtypes = [vp, vp, sz, vp]
+    pt = ctypes.POINTER(lq_tree)
+    lib.lq_tree_table_ld.argtypes = [i32]
+    lib.lq_tree_table_ld.restype = i64
+    lib.lq_tree_project_dims.argtypes = [ps, pt, ctypes.POINTER(vp), vp, vp]
+    lib.lq_fused_join_tree.argtypes = [ps, pt, ctypes.POINTER(vp), vp, vp, vp, u32, vp, sz, vp]
+    lib.lq_materialized_join_tree.argtypes = [ps, pt, vp, vp, vp, sz, u32, vp]
+    lib.lq_tree_workspace_bytes.argtypes = [ps, i64]
+    lib.lq_tree_workspace_bytes.restype = sz
     lib.lq_last_error.restype = ctypes.c_char_p
     lib.lq_version.restype = ctypes.c_char_p
     for f in ("lq_project_dims", "lq_fused_join_predict", "lq_materialized_join_predict",
-              "lq_masked_groupby_sum", "lq_stream_copy"):
+              "lq_masked_groupby_sum", "lq_stream_copy", "lq_tree_project_dims", "lq_fused_join_tree",
+              "lq_materialized_join_tree"):
         getattr(lib, f).restype = ctypes.c_int
     return lib
 
@@ -312,3 +326,69 @@ def lq_stream_copy(dst: torch.Tensor, src: torch.Tensor, stream=None) -> None:
     if dst.numel() * dst.element_size() < nbytes:
         raise ValueError("destination smaller than source")
     _check(_lib.lq_stream_copy(dst.data_ptr(), src.data_ptr(), nbytes, _stream(stream)))
+
+
+# ---------------------------------------------------------------- decision trees --------------
+
+def _tree(feature: torch.Tensor, threshold: torch.Tensor, H: torch.Tensor) -> lq_tree:
+    _expect(feature, torch.int32, "tree feature index")
+    _expect(threshold, torch.float32, "tree thresholds")
+    if H.dtype != torch.int8 or not H.is_cuda or H.dim() != 2 or not H.is_contiguous():
+        raise TypeError("H must be a contiguous int8 [nodes x leaves] tensor on the GPU")
+    if feature.shape[0] != H.shape[0] or threshold.shape[0] != H.shape[0]:
+        raise ValueError("feature, threshold and H disagree on the number of nodes")
+    return lq_tree(int(H.shape[0]), int(H.shape[1]), feature.data_ptr(), threshold.data_ptr(), H.data_ptr())
+
+
+def lq_tree_table_ld(n_leaves: int) -> int:
+    return int(_lib.lq_tree_table_ld(n_leaves))
+
+
+def lq_tree_project_dims(dims: Sequence[torch.Tensor], c_f: int, feature, threshold, H, stream=None):
+    """Pre-fused tree tables (uint8 [r_k x ld] per dimension) and the target vector (uint8 [ld])."""
+    tree = _tree(feature, threshold, H)
+    ld = lq_tree_table_ld(tree.n_leaves)
+    dev = H.device
+    tables = [torch.empty((d.shape[0], ld), dtype=torch.uint8, device=dev) for d in dims]
+    target = torch.empty((ld,), dtype=torch.uint8, device=dev)
+    fact = lq_mat(None, 0, int(c_f), max(int(c_f), 1), LQ_F32)
+    dims_arr = _mat_array(dims)
+    star = lq_star(0, fact, len(dims), dims_arr, _ptr_array([None] * len(dims)))
+    _check(_lib.lq_tree_project_dims(ctypes.byref(star), ctypes.byref(tree), _ptr_array(tables),
+                                     target.data_ptr(), _stream(stream)))
+    return tables, target
+
+
+def lq_fused_join_tree(X: Optional[torch.Tensor], fks: Sequence[torch.Tensor], tables, target, feature,
+                       threshold, H, want_leaf: bool = True, want_onehot: bool = False, stream=None):
+    """Leaf reached by every fact row (int32 [n]) and / or the one-hot matrix (uint8 [n x l])."""
+    tree = _tree(feature, threshold, H)
+    n = _n_of(X, fks)
+    dev = H.device
+    leaf = torch.empty((n,), dtype=torch.int32, device=dev) if want_leaf else None
+    onehot = torch.empty((n, tree.n_leaves), dtype=torch.uint8, device=dev) if want_onehot else None
+    star = _Star(n, X, None, fks)
+    _check(_lib.lq_fused_join_tree(ctypes.byref(star.c), ctypes.byref(tree), _ptr_array(tables),
+                                   target.data_ptr(), None if leaf is None else leaf.data_ptr(),
+                                   None if onehot is None else onehot.data_ptr(), 0, None, 0, _stream(stream)))
+    return leaf, onehot
+
+
+def lq_materialized_join_tree(X: Optional[torch.Tensor], dims, fks, feature, threshold, H,
+                              want_leaf: bool = True, want_onehot: bool = False,
+                              ws: Optional[torch.Tensor] = None, chunk_rows: Optional[int] = None, stream=None):
+    """Non-fused tree pipeline: materialise T chunk by chunk, then ((T F > v) H) == h."""
+    tree = _tree(feature, threshold, H)
+    n = _n_of(X, fks)
+    dev = H.device
+    leaf = torch.empty((n,), dtype=torch.int32, device=dev) if want_leaf else None
+    onehot = torch.empty((n, tree.n_leaves), dtype=torch.uint8, device=dev) if want_onehot else None
+    star = _Star(n, X, dims, fks)
+    if ws is None:
+        rows = chunk_rows or min(max(n, 256), 1 << 22)
+        ws = torch.empty(int(_lib.lq_tree_workspace_bytes(ctypes.byref(star.c), rows)), dtype=torch.uint8, device=dev)
+    _check(_lib.lq_materialized_join_tree(ctypes.byref(star.c), ctypes.byref(tree),
+                                          None if leaf is None else leaf.data_ptr(),
+                                          None if onehot is None else onehot.data_ptr(), ws.data_ptr(),
+                                          ws.numel(), 0, _stream(stream)))
+    return leaf, onehot

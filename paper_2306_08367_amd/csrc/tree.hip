@@ -1,0 +1,349 @@
+// Decision-tree fusion (Section 3.3, Eq. 2): pre-fused per-dimension tables, the join-computation
+// stage that adds them up per fact row and compares with h, and the non-fused pipeline
+// ((T F > v) H) == h on the materialised join.
+//
+// Representation.  Instead of the signed partial sums of (D_k M_k F > v) H the tables hold, per
+// dimension row r and leaf j, the number of nodes owned by that dimension on the path to leaf j
+// whose outcome for r AGREES with the path (+1 node true, -1 node false).  This is the signed sum
+// plus the number of the dimension's -1 entries in column j: never negative, at most the path
+// length, so a byte suffices and packed 32-bit adds never carry between bytes.  Leaf j is reached
+// iff the agreement counts of all tables add up to its path length (`target`), which is the same
+// statement as R_j == h_j.
+#include "lq_common.h"
+
+namespace lq {
+namespace {
+
+typedef unsigned int v4u __attribute__((ext_vector_type(4)));
+
+struct TreeArgs {
+  int32_t p, l;
+  int64_t ld;                 // row stride of the tables in bytes (multiple of 16)
+  const int32_t* feature;
+  const float* thr;
+  const int8_t* H;
+};
+
+// ---------------------------------------------------------------- pre-fusion --------------
+
+__global__ __launch_bounds__(256) void tree_target_kernel(TreeArgs t, uint8_t* target) {
+  const int j = blockIdx.x * blockDim.x + threadIdx.x;
+  if (j >= t.ld) return;
+  if (j >= t.l) { target[j] = 0xff; return; }
+  int cnt = 0;
+  for (int q = 0; q < t.p; ++q) cnt += t.H[static_cast<int64_t>(q) * t.l + j] != 0;
+  target[j] = static_cast<uint8_t>(min(cnt, 255));
+}
+
+// One thread per (dimension row, leaf), leaves fastest.  col_off / c: the dimension's columns in T.
+__global__ __launch_bounds__(256) void tree_project_kernel(TreeArgs t, const float* __restrict__ D,
+                                                           int64_t ldd, int64_t rows, int32_t col_off,
+                                                           int32_t c, uint8_t* __restrict__ out) {
+  const int64_t total = rows * t.ld;
+  const int64_t stride = static_cast<int64_t>(gridDim.x) * blockDim.x;
+  for (int64_t idx = static_cast<int64_t>(blockIdx.x) * blockDim.x + threadIdx.x; idx < total; idx += stride) {
+    const int64_t r = idx / t.ld;
+    const int j = static_cast<int>(idx - r * t.ld);
+    int agree = 0;
+    if (j < t.l) {
+      const float* dr = D + r * ldd;
+      for (int q = 0; q < t.p; ++q) {
+        const int f = t.feature[q] - col_off;
+        if (f < 0 || f >= c) continue;                       // node owned by another table
+        const int hv = t.H[static_cast<int64_t>(q) * t.l + j];
+        if (hv == 0) continue;
+        const bool bit = dr[f] > t.thr[q];
+        agree += bit == (hv > 0);
+      }
+    }
+    out[idx] = static_cast<uint8_t>(min(agree, 255));
+  }
+}
+
+// ---------------------------------------------------------------- fused join ---------------
+
+struct FusedTreeArgs {
+  int64_t n;
+  int32_t K;
+  const uint8_t* T[LQ_MAX_DIMS];
+  const int32_t* fk[LQ_MAX_DIMS];
+  int32_t chunks;              // ld / 16
+  const uint8_t* target;
+  int32_t* leaf;
+  uint8_t* onehot;
+  int32_t onehot_vec_ok;       // 16-byte stores into onehot rows are legal
+  // nodes that test fact-table columns (evaluated per fact row)
+  const float* X; int64_t ldx; int32_t c_f; int32_t has_fact_nodes;
+  TreeArgs t;
+};
+
+// 0x80 in every byte of w that is zero, 0 elsewhere (exact, no borrow effects).
+__device__ __forceinline__ unsigned int zero_bytes(unsigned int w) {
+  const unsigned int t = (w & 0x7f7f7f7fu) + 0x7f7f7f7fu;
+  return ~(t | w | 0x7f7f7f7fu);
+}
+
+// G lanes per fact row; lane c handles 16-leaf chunks c, c + G, ...
+template <int G>
+__global__ __launch_bounds__(256) void fused_tree_kernel(FusedTreeArgs a) {
+  constexpr int RPB = 256 / G;
+  const int sub = threadIdx.x / G, c = threadIdx.x % G;
+  const int64_t row = static_cast<int64_t>(blockIdx.x) * RPB + sub;
+  const bool live = row < a.n;
+  const int64_t rr = live ? row : a.n - 1;
+  int64_t base[LQ_MAX_DIMS];
+#pragma unroll
+  for (int k = 0; k < LQ_MAX_DIMS; ++k)
+    if (k < a.K) base[k] = static_cast<int64_t>(__builtin_nontemporal_load(a.fk[k] + rr)) * a.t.ld;
+  int first = 0x7fffffff;
+  for (int ch = c; ch < a.chunks; ch += G) {
+    v4u sum = {0u, 0u, 0u, 0u};
+#pragma unroll
+    for (int k = 0; k < LQ_MAX_DIMS; ++k)
+      if (k < a.K) sum += *reinterpret_cast<const v4u*>(a.T[k] + base[k] + 16 * ch);
+    if (a.has_fact_nodes) {
+      const float* xr = a.X + rr * a.ldx;
+      for (int q = 0; q < a.t.p; ++q) {
+        const int f = a.t.feature[q];
+        if (f >= a.c_f) continue;
+        const bool bit = xr[f] > a.t.thr[q];
+#pragma unroll
+        for (int b = 0; b < 16; ++b) {
+          const int j = 16 * ch + b;
+          const int hv = j < a.t.l ? a.t.H[static_cast<int64_t>(q) * a.t.l + j] : 0;
+          if (hv != 0 && bit == (hv > 0)) sum[b >> 2] += 1u << (8 * (b & 3));
+        }
+      }
+    }
+    const v4u tg = *reinterpret_cast<const v4u*>(a.target + 16 * ch);
+    v4u hit;
+#pragma unroll
+    for (int d = 0; d < 4; ++d) {
+      hit[d] = zero_bytes(sum[d] ^ tg[d]);
+      if (hit[d] != 0u) first = min(first, 16 * ch + 4 * d + (__builtin_ctz(hit[d]) >> 3));
+    }
+    if (a.onehot && live) {
+      uint8_t* o = a.onehot + row * a.t.l + 16 * ch;
+      if (a.onehot_vec_ok && 16 * ch + 16 <= a.t.l) {
+        const v4u ones = {hit[0] >> 7, hit[1] >> 7, hit[2] >> 7, hit[3] >> 7};
+        __builtin_nontemporal_store(ones, reinterpret_cast<v4u*>(o));
+      } else {
+#pragma unroll
+        for (int b = 0; b < 16; ++b)
+          if (16 * ch + b < a.t.l) o[b] = static_cast<uint8_t>((hit[b >> 2] >> (8 * (b & 3) + 7)) & 1u);
+      }
+    }
+  }
+#pragma unroll
+  for (int m = 1; m < G; m <<= 1) first = min(first, __shfl_xor(first, m, 64));
+  if (a.leaf && live && c == 0) a.leaf[row] = first == 0x7fffffff ? -1 : first;
+}
+
+// ---------------------------------------------------------------- non-fused ----------------
+
+// ((T F > v) H) == h on a chunk of the materialised join.  A workgroup takes RB rows at a time:
+// step 2 of the matrix form (the predicate bits of every node) goes to LDS, step 3/4 is one
+// thread per (row, leaf).
+__global__ __launch_bounds__(256) void tree_eval_kernel(TreeArgs t, const float* __restrict__ T, int64_t ldt,
+                                                        int64_t rows, int64_t row0, const uint8_t* target,
+                                                        int32_t* leaf, uint8_t* onehot, int RB) {
+  extern __shared__ int smem_i[];
+  int* first = smem_i;                                   // [RB]
+  uint8_t* bits = reinterpret_cast<uint8_t*>(smem_i + RB);   // [RB][p]
+  const int tid = threadIdx.x;
+  const int64_t n_tiles = (rows + RB - 1) / RB;
+  for (int64_t tile = blockIdx.x; tile < n_tiles; tile += gridDim.x) {
+    const int64_t r0 = tile * RB;
+    const int nr = static_cast<int>(min<int64_t>(RB, rows - r0));
+    for (int i = tid; i < nr; i += 256) first[i] = 0x7fffffff;
+    for (int idx = tid; idx < nr * t.p; idx += 256) {
+      const int r = idx / t.p, q = idx - r * t.p;
+      bits[r * t.p + q] = T[(r0 + r) * ldt + t.feature[q]] > t.thr[q];
+    }
+    __syncthreads();
+    for (int idx = tid; idx < nr * t.l; idx += 256) {
+      const int r = idx / t.l, j = idx - r * t.l;
+      int agree = 0;
+      for (int q = 0; q < t.p; ++q) {
+        const int hv = t.H[static_cast<int64_t>(q) * t.l + j];
+        agree += hv != 0 && (bits[r * t.p + q] != 0) == (hv > 0);
+      }
+      const bool hit = agree == target[j];
+      if (onehot) onehot[(row0 + r0 + r) * t.l + j] = hit;
+      if (hit) atomicMin(&first[r], j);
+    }
+    __syncthreads();
+    if (leaf)
+      for (int i = tid; i < nr; i += 256) leaf[row0 + r0 + i] = first[i] == 0x7fffffff ? -1 : first[i];
+    __syncthreads();
+  }
+}
+
+int check_tree(const lq_tree* tree, TreeArgs* t) {
+  if (!tree) return fail(LQ_ERR_NULL, "tree is NULL");
+  if (tree->n_nodes < 1 || tree->n_leaves < 1) return fail(LQ_ERR_SHAPE, "tree needs nodes and leaves");
+  if (tree->n_leaves > 16384) return fail(LQ_ERR_UNSUPPORTED, "more than 16384 leaves");
+  if (!tree->feature || !tree->threshold || !tree->H) return fail(LQ_ERR_NULL, "tree arrays are NULL");
+  if (!aligned(tree->feature, 4) || !aligned(tree->threshold, 4))
+    return fail(LQ_ERR_SHAPE, "tree arrays are misaligned");
+  t->p = tree->n_nodes; t->l = tree->n_leaves;
+  t->ld = static_cast<int64_t>(round_up(static_cast<size_t>(tree->n_leaves), 16));
+  t->feature = tree->feature; t->thr = tree->threshold; t->H = tree->H;
+  return LQ_OK;
+}
+
+int check_star_basic(const lq_star* star, bool need_dims) {
+  if (!star) return fail(LQ_ERR_NULL, "star is NULL");
+  if (star->n_fact < 0) return fail(LQ_ERR_SHAPE, "n_fact < 0");
+  if (star->n_dims < 0 || star->n_dims > LQ_MAX_DIMS) return fail(LQ_ERR_SHAPE, "n_dims outside 0..%d", LQ_MAX_DIMS);
+  if (star->fact.cols < 0) return fail(LQ_ERR_SHAPE, "fact.cols < 0");
+  if (star->fact.cols > 0 && star->fact.dtype != LQ_F32) return fail(LQ_ERR_DTYPE, "tree paths take f32 tables");
+  if (need_dims) {
+    if (star->n_dims > 0 && !star->dims) return fail(LQ_ERR_NULL, "star->dims is NULL");
+    for (int k = 0; k < star->n_dims; ++k) {
+      const lq_mat& d = star->dims[k];
+      if (d.dtype != LQ_F32) return fail(LQ_ERR_DTYPE, "tree paths take f32 tables");
+      if (d.rows < 1 || d.cols < 1 || d.ld < d.cols || !d.data || !aligned(d.data, 4))
+        return fail(LQ_ERR_SHAPE, "dims[%d] is malformed", k);
+    }
+  }
+  return LQ_OK;
+}
+
+}  // namespace
+}  // namespace lq
+
+using namespace lq;
+
+extern "C" {
+
+int64_t lq_tree_table_ld(int32_t n_leaves) {
+  return n_leaves < 1 ? 0 : static_cast<int64_t>(round_up(static_cast<size_t>(n_leaves), 16));
+}
+
+int lq_tree_project_dims(const lq_star* star, const lq_tree* tree, void* const* tables, uint8_t* target,
+                         void* hip_stream) {
+  clear_error();
+  TreeArgs t{};
+  int rc = check_star_basic(star, true);
+  if (rc) return rc;
+  if ((rc = check_tree(tree, &t))) return rc;
+  if (!target) return fail(LQ_ERR_NULL, "target is NULL");
+  if (star->n_dims > 0 && !tables) return fail(LQ_ERR_NULL, "tables is NULL");
+  for (int k = 0; k < star->n_dims; ++k)
+    if (!tables[k] || !aligned(tables[k], 16)) return fail(LQ_ERR_NULL, "tables[%d] is NULL or not 16-byte aligned", k);
+  hipStream_t s = static_cast<hipStream_t>(hip_stream);
+  hipLaunchKernelGGL(tree_target_kernel, dim3(static_cast<unsigned>((t.ld + 255) / 256)), dim3(256), 0, s, t, target);
+  LQ_LAUNCH_CHECK("tree_target_kernel");
+  int32_t off = star->fact.cols;
+  for (int k = 0; k < star->n_dims; ++k) {
+    const lq_mat& d = star->dims[k];
+    const int64_t total = d.rows * t.ld;
+    const int64_t blocks = std::min<int64_t>((total + 255) / 256, static_cast<int64_t>(num_cus()) * 32);
+    hipLaunchKernelGGL(tree_project_kernel, dim3(static_cast<unsigned>(blocks)), dim3(256), 0, s, t,
+                       static_cast<const float*>(d.data), d.ld, d.rows, off, d.cols,
+                       static_cast<uint8_t*>(tables[k]));
+    LQ_LAUNCH_CHECK("tree_project_kernel");
+    off += d.cols;
+  }
+  return LQ_OK;
+}
+
+int lq_fused_join_tree(const lq_star* star, const lq_tree* tree, const void* const* tables,
+                       const uint8_t* target, int32_t* leaf, uint8_t* onehot, uint32_t flags, void* ws,
+                       size_t ws_bytes, void* hip_stream) {
+  clear_error();
+  FusedTreeArgs a{};
+  int rc = check_star_basic(star, false);
+  if (rc) return rc;
+  if ((rc = check_tree(tree, &a.t))) return rc;
+  if (!target || !aligned(target, 16)) return fail(LQ_ERR_NULL, "target is NULL or not 16-byte aligned");
+  if (star->n_dims > 0 && (!tables || !star->fks)) return fail(LQ_ERR_NULL, "tables or fks is NULL");
+  if (!leaf && !onehot) return fail(LQ_ERR_NULL, "neither leaf nor onehot requested");
+  if (leaf && !aligned(leaf, 4)) return fail(LQ_ERR_SHAPE, "leaf is misaligned");
+  a.n = star->n_fact; a.K = star->n_dims;
+  for (int k = 0; k < a.K; ++k) {
+    if (!tables[k] || !aligned(tables[k], 16)) return fail(LQ_ERR_NULL, "tables[%d] is NULL or not 16-byte aligned", k);
+    if (a.n > 0 && (!star->fks[k] || !aligned(star->fks[k], 4))) return fail(LQ_ERR_NULL, "fks[%d] is NULL or misaligned", k);
+    a.T[k] = static_cast<const uint8_t*>(tables[k]);
+    a.fk[k] = star->fks[k];
+  }
+  a.chunks = static_cast<int32_t>(a.t.ld / 16);
+  a.target = target; a.leaf = leaf; a.onehot = onehot;
+  a.onehot_vec_ok = onehot && aligned(onehot, 16) && a.t.l % 16 == 0;
+  a.c_f = star->fact.cols;
+  a.has_fact_nodes = a.c_f > 0;      // nodes are only evaluated if their column index is < c_f
+  if (a.c_f > 0) {
+    if (a.n > 0 && (!star->fact.data || star->fact.ld < a.c_f)) return fail(LQ_ERR_NULL, "fact table is malformed");
+    a.X = static_cast<const float*>(star->fact.data); a.ldx = star->fact.ld;
+  }
+  (void)flags; (void)ws; (void)ws_bytes;
+  if (a.n == 0) return LQ_OK;
+  hipStream_t s = static_cast<hipStream_t>(hip_stream);
+  int G = 1;
+  while (G < a.chunks && G < 64) G <<= 1;
+  const int64_t blocks = (a.n + 256 / G - 1) / (256 / G);
+  if (blocks > 0x7fffffffLL) return fail(LQ_ERR_UNSUPPORTED, "too many rows for one launch");
+  switch (G) {
+#define LQ_TREE_CASE(GG) case GG: hipLaunchKernelGGL(fused_tree_kernel<GG>, dim3(static_cast<unsigned>(blocks)), dim3(256), 0, s, a); break;
+    LQ_TREE_CASE(1) LQ_TREE_CASE(2) LQ_TREE_CASE(4) LQ_TREE_CASE(8) LQ_TREE_CASE(16) LQ_TREE_CASE(32) LQ_TREE_CASE(64)
+#undef LQ_TREE_CASE
+  }
+  LQ_LAUNCH_CHECK("fused_tree_kernel");
+  return LQ_OK;
+}
+
+size_t lq_tree_workspace_bytes(const lq_star* star, int64_t chunk_rows) {
+  if (!star || chunk_rows < 1 || star->n_dims < 0 || star->n_dims > LQ_MAX_DIMS) return 0;
+  if (star->n_dims > 0 && !star->dims) return 0;
+  size_t kw = star->fact.cols > 0 ? star->fact.cols : 0;
+  for (int k = 0; k < star->n_dims; ++k) kw += star->dims[k].cols;
+  const size_t rows = round_up(static_cast<size_t>(chunk_rows), 256);
+  return 256 + round_up(rows * round_up(kw, 4) * 4, 256) + 256 + 16384;
+}
+
+int lq_materialized_join_tree(const lq_star* star, const lq_tree* tree, int32_t* leaf, uint8_t* onehot,
+                              void* ws, size_t ws_bytes, uint32_t flags, void* hip_stream) {
+  clear_error();
+  TreeArgs t{};
+  int rc = check_star_basic(star, true);
+  if (rc) return rc;
+  if ((rc = check_tree(tree, &t))) return rc;
+  if (!leaf && !onehot) return fail(LQ_ERR_NULL, "neither leaf nor onehot requested");
+  if (star->n_dims > 0 && !star->fks) return fail(LQ_ERR_NULL, "fks is NULL");
+  if (star->n_fact == 0) return LQ_OK;
+  if (star->fact.cols > 0 && !star->fact.data) return fail(LQ_ERR_NULL, "fact data is NULL");
+  for (int k = 0; k < star->n_dims; ++k)
+    if (!star->fks[k]) return fail(LQ_ERR_NULL, "fks[%d] is NULL", k);
+  if (!ws || !aligned(ws, 256)) return fail(LQ_ERR_WORKSPACE, "workspace is NULL or not 256-byte aligned");
+  size_t kw = star->fact.cols;
+  for (int k = 0; k < star->n_dims; ++k) kw += star->dims[k].cols;
+  const int64_t ldt = static_cast<int64_t>(round_up(kw, 4));
+  const size_t fixed = 256 + 256 + 16384;            // header, slack, target vector
+  if (ws_bytes < fixed + 256 * static_cast<size_t>(ldt) * 4)
+    return fail(LQ_ERR_WORKSPACE, "workspace cannot hold one 256-row chunk");
+  int64_t chunk = static_cast<int64_t>((ws_bytes - fixed) / (static_cast<size_t>(ldt) * 4)) / 256 * 256;
+  chunk = std::min<int64_t>(chunk, static_cast<int64_t>(round_up(static_cast<size_t>(star->n_fact), 256)));
+  uint8_t* target = static_cast<uint8_t*>(ws) + 256;                       // ld <= 16384 bytes
+  float* T = reinterpret_cast<float*>(static_cast<char*>(ws) + 256 + 16384 + 256);
+  (void)flags;
+  hipStream_t s = static_cast<hipStream_t>(hip_stream);
+  hipLaunchKernelGGL(tree_target_kernel, dim3(static_cast<unsigned>((t.ld + 255) / 256)), dim3(256), 0, s, t, target);
+  LQ_LAUNCH_CHECK("tree_target_kernel");
+  int RB = 8;
+  while (RB > 1 && static_cast<size_t>(RB) * (t.p + 4) > 48 * 1024) RB >>= 1;
+  if (static_cast<size_t>(RB) * (t.p + 4) > 48 * 1024) return fail(LQ_ERR_UNSUPPORTED, "too many tree nodes");
+  const size_t lds = static_cast<size_t>(RB) * 4 + round_up(static_cast<size_t>(RB) * t.p, 4);
+  for (int64_t r0 = 0; r0 < star->n_fact; r0 += chunk) {
+    const int64_t m = std::min<int64_t>(chunk, star->n_fact - r0);
+    if ((rc = launch_materialize(*star, T, ldt, r0, m, s))) return rc;
+    const int64_t tiles = (m + RB - 1) / RB;
+    const int64_t blocks = std::min<int64_t>(tiles, static_cast<int64_t>(num_cus()) * 16);
+    hipLaunchKernelGGL(tree_eval_kernel, dim3(static_cast<unsigned>(blocks)), dim3(256), lds, s, t, T, ldt, m, r0,
+                       target, leaf, onehot, RB);
+    LQ_LAUNCH_CHECK("tree_eval_kernel");
+  }
+  return LQ_OK;
+}
+
+}  // extern "C"

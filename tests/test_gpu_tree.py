@@ -1,0 +1,125 @@
+"""GPU parity of the decision-tree fusion (Section 3.3, Eq. 2) against the oracle: bit-exact
+(every decision is a comparison of an fp32 table value with an fp32 threshold, and the rest is
+integer arithmetic)."""
+import numpy as np
+import pytest
+import torch
+
+from oracle import lq_oracle as O
+from tests.helpers import cpu_list, to_dev
+from workloads import star as WL
+
+pytestmark = pytest.mark.gpu
+
+
+@pytest.fixture(scope="module")
+def lq():
+    import paper_2306_08367_amd as lq
+    return lq
+
+
+def _case(name, n, c_f, rows, cols, leaves, seed, tree_cols=None):
+    w = WL.make_predict(name, n, c_f, rows, cols, (1,), seed=seed)
+    kw = c_f + sum(cols)
+    tree = WL.make_tree(kw, leaves, seed + 1, cols=tree_cols)
+    return w, tree
+
+
+def _run(lq, w, tree, onehot=True):
+    f, t, H = tree.feature.cuda(), tree.threshold.cuda(), tree.H.cuda()
+    tables, target = lq.lq_tree_project_dims(w.dims, w.c_f, f, t, H)
+    leaf, oh = lq.lq_fused_join_tree(w.X, w.fks, tables, target, f, t, H, want_onehot=onehot)
+    leaf_m, oh_m = lq.lq_materialized_join_tree(w.X, w.dims, w.fks, f, t, H, want_onehot=onehot, chunk_rows=1024)
+    torch.cuda.synchronize()
+    return tables, target, leaf, oh, leaf_m, oh_m
+
+
+CASES = [
+    # name, n, c_f, dim_rows, dim_cols, leaves
+    ("two_leaves", 1_000, 0, (10, 7), (3, 2), 2),
+    ("five_leaves", 5_003, 0, (50, 70, 30), (4, 4, 4), 5),
+    ("sixteen", 4_099, 0, (100, 200), (8, 8), 16),
+    ("setting1_like", 20_011, 0, (800, 160, 255), (43, 43, 42), 64),
+    ("hundred_leaves", 3_333, 0, (64, 64, 64, 64), (5, 5, 5, 5), 100),
+    ("wide_256", 2_049, 0, (300, 200), (16, 16), 256),
+    ("very_wide_1500", 1_025, 0, (120, 90), (32, 32), 1_500),
+    ("fact_columns", 2_500, 3, (40, 60), (4, 4), 24),
+    ("one_row", 1, 0, (5,), (3,), 4),
+]
+
+
+@pytest.mark.parametrize("case", CASES, ids=[c[0] for c in CASES])
+def test_tree_paths_match_oracle(lq, case):
+    name, n, c_f, rows, cols, leaves = case
+    w, tree = _case(name, n, c_f, rows, cols, leaves, WL.SEED0 + 500 + leaves)
+    R, onehot, leaf = O.tree_predict(w.X, w.dims, w.fks, tree.feature, tree.threshold, tree.H)
+    Tk = O.tree_project(w.dims, c_f, tree.feature, tree.threshold, tree.H)
+    w = to_dev(w)
+    tables, target, g_leaf, g_oh, m_leaf, m_oh = _run(lq, w, tree)
+    # pre-fused tables: agreement counts = signed partial sums + the table's own -1 entries per leaf
+    Hn = tree.H.numpy().astype(np.int64)
+    feat = tree.feature.numpy()
+    off = c_f
+    for k, d in enumerate(w.dims):
+        own = (feat >= off) & (feat < off + d.shape[1])
+        neg = (Hn[own] == -1).sum(axis=0)
+        np.testing.assert_array_equal(tables[k].cpu().numpy()[:, :leaves].astype(np.int64), Tk[k] + neg)
+        assert (tables[k].cpu().numpy()[:, leaves:] == 0).all()
+        off += d.shape[1]
+    np.testing.assert_array_equal(target.cpu().numpy()[:leaves], (Hn != 0).sum(axis=0))
+    assert (target.cpu().numpy()[leaves:] == 0xFF).all()
+    np.testing.assert_array_equal(g_leaf.cpu().numpy(), leaf)
+    np.testing.assert_array_equal(g_oh.cpu().numpy(), onehot)
+    np.testing.assert_array_equal(m_leaf.cpu().numpy(), leaf)
+    np.testing.assert_array_equal(m_oh.cpu().numpy(), onehot)
+    assert (onehot.sum(axis=1) == 1).all()
+
+
+def test_tree_on_a_subset_of_columns_and_leaf_only_output(lq):
+    # the tree only tests columns of dimension 1; dimension 0 contributes all-zero tables
+    w, tree = _case("subset", 6_007, 0, (30, 40), (6, 6), 12, WL.SEED0 + 600, tree_cols=range(6, 12))
+    _, _, leaf = O.tree_predict(w.X, w.dims, w.fks, tree.feature, tree.threshold, tree.H)
+    w = to_dev(w)
+    tables, target, g_leaf, g_oh, m_leaf, _ = _run(lq, w, tree, onehot=False)
+    assert g_oh is None
+    assert (tables[0] == 0).all()
+    np.testing.assert_array_equal(g_leaf.cpu().numpy(), leaf)
+    np.testing.assert_array_equal(m_leaf.cpu().numpy(), leaf)
+
+
+def test_degenerate_matrices_without_a_matching_leaf_give_minus_one(lq):
+    """H need not come from a tree: a leaf that needs a node both true (+1) elsewhere is fine, but a
+    column can also be unreachable for some rows; then no leaf matches and the index is -1."""
+    w = WL.make_predict("degenerate", 2_000, 0, (20,), (2,), (1,), seed=WL.SEED0 + 601)
+    feature = torch.tensor([0, 1], dtype=torch.int32)
+    thr = torch.tensor([0.0, 0.0])
+    H = torch.tensor([[1], [1]], dtype=torch.int8)            # one "leaf" that needs both nodes true
+    _, onehot, leaf = O.tree_predict(w.X, w.dims, w.fks, feature, thr, H)
+    assert (leaf == -1).any() and (leaf == 0).any()
+    w = to_dev(w)
+    tables, target = lq.lq_tree_project_dims(w.dims, 0, feature.cuda(), thr.cuda(), H.cuda())
+    g_leaf, g_oh = lq.lq_fused_join_tree(None, w.fks, tables, target, feature.cuda(), thr.cuda(), H.cuda(),
+                                         want_onehot=True)
+    torch.cuda.synchronize()
+    np.testing.assert_array_equal(g_leaf.cpu().numpy(), leaf)
+    np.testing.assert_array_equal(g_oh.cpu().numpy(), onehot)
+
+
+def test_tree_full_size_setting1_shape(lq):
+    """Cardinality setting 1 at scale factor 8 (4.8M fact rows; dimensions 80,000 / 16,000 / 2,555),
+    128 joined columns, 64 leaves: oracle on a row sample, fused vs non-fused over all rows."""
+    n = 4_800_000
+    w = WL.make_predict("tree_s1_sf8", n, 0, (80_000, 16_000, 2_555), (43, 43, 42), (1,), seed=WL.SEED0 + 700,
+                        device="cuda")
+    tree = WL.make_tree(128, 64, WL.SEED0 + 701)
+    f, t, H = tree.feature.cuda(), tree.threshold.cuda(), tree.H.cuda()
+    tables, target = lq.lq_tree_project_dims(w.dims, 0, f, t, H)
+    leaf, _ = lq.lq_fused_join_tree(None, w.fks, tables, target, f, t, H)
+    leaf_m, _ = lq.lq_materialized_join_tree(None, w.dims, w.fks, f, t, H, chunk_rows=1 << 20)
+    torch.cuda.synchronize()
+    assert torch.equal(leaf, leaf_m)
+    rows = WL.sample_rows(n)
+    sub = WL.take_rows(w, rows)
+    _, _, want = O.tree_predict(None, sub.dims, sub.fks, tree.feature, tree.threshold, tree.H)
+    np.testing.assert_array_equal(leaf[rows.cuda()].cpu().numpy(), want)
+    assert len(np.unique(want)) > 20                      # the rows really spread over the leaves
