@@ -67,7 +67,7 @@ def main():
     ap.add_argument("--rows", type=int, default=10_000_000, help="fact rows of the headline workload")
     ap.add_argument("--no-extras", action="store_true", help="skip materialised / group-by / skewed legs")
     ap.add_argument("--no-cpu", action="store_true", help="skip the CPU oracle baseline")
-    ap.add_argument("--only", default="", help="run a single leg for profiling: fused|groupby|groupby16|c4|c5|materialized|copy")
+    ap.add_argument("--only", default="", help="run a single leg for profiling: fused|groupby|groupby16|c4|c5|tree|materialized|copy")
     args = ap.parse_args()
     if args.gpus != 1:
         sys.exit("bench.py: this build is single-GPU by design (no collectives, no sharding); "
@@ -267,6 +267,28 @@ def main():
                                                   "unit": "GB/s", "frac": gbps / HBM_PEAK_GBPS,
                                                   "algorithmic_bytes_per_row": 20}}
         del g
+
+    # ---------------------------------------------------------------- decision tree (setting 1, sf 8)
+    if (args.only == "" and not args.no_extras) or args.only == "tree":
+        nt = 4_800_000
+        wt = WL.make_predict("tree_s1_sf8", nt, 0, (80_000, 16_000, 2_555), (43, 43, 42), (1,),
+                             seed=WL.SEED0 + 700, device=dev)
+        tree = WL.make_tree(128, 64, WL.SEED0 + 701)
+        tf, tt, tH = tree.feature.to(dev), tree.threshold.to(dev), tree.H.to(dev)
+        tables, target = lq.lq_tree_project_dims(wt.dims, 0, tf, tt, tH)
+        pms, _, _ = time_call(lambda: lq.lq_tree_project_dims(wt.dims, 0, tf, tt, tH), 5, 1)
+        ms, mn, _ = time_call(lambda: lq.lq_fused_join_tree(None, wt.fks, tables, target, tf, tt, tH), 20, 3)
+        mms, _, _ = time_call(lambda: lq.lq_materialized_join_tree(None, wt.dims, wt.fks, tf, tt, tH,
+                                                                   chunk_rows=1 << 20), 2, 1)
+        gbps = 16.0 * nt / (ms * 1e-3) / 1e9
+        out["fused_tree"] = {"rows_per_s": nt / (ms * 1e-3), "ms": ms, "project_ms": pms, "fact_rows": nt,
+                             "leaves": 64, "nodes": 63, "joined_cols": 128,
+                             "materialized_rows_per_s": nt / (mms * 1e-3),
+                             "fused_speedup": mms / (ms + pms),
+                             "roofline": {"bound": "hbm", "achieved": gbps, "peak": HBM_PEAK_GBPS, "unit": "GB/s",
+                                          "frac": gbps / HBM_PEAK_GBPS, "algorithmic_bytes_per_row": 16,
+                                          "gather_GBps": 192.0 * nt / (ms * 1e-3) / 1e9}}
+        del wt, tables
 
     print(json.dumps(out))
 

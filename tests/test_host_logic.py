@@ -152,3 +152,29 @@ def test_stream_copy_rejects_misaligned():
     assert b._lib.lq_stream_copy(0x10000, 0x20000, 60, None) == 2
     assert b._lib.lq_stream_copy(None, 0x20000, 64, None) == 1
     assert b._lib.lq_stream_copy(None, None, 0, None) == 0
+
+
+def test_tree_entry_points_reject_bad_arguments():
+    b = _binding()
+    lib = b._lib
+    assert b.lq_tree_table_ld(64) == 64 and b.lq_tree_table_ld(65) == 80 and b.lq_tree_table_ld(0) == 0
+    star, model, keep = _star_model(b)
+    tree = b.lq_tree(3, 4, FAKE, FAKE, FAKE)
+    tables = (ctypes.c_void_p * 1)(FAKE)
+    assert lib.lq_tree_project_dims(ctypes.byref(star), ctypes.byref(tree), tables, None, None) == 1
+    bad = b.lq_tree(0, 4, FAKE, FAKE, FAKE)
+    assert lib.lq_tree_project_dims(ctypes.byref(star), ctypes.byref(bad), tables, FAKE, None) == 2
+    bad = b.lq_tree(3, 4, None, FAKE, FAKE)
+    assert lib.lq_tree_project_dims(ctypes.byref(star), ctypes.byref(bad), tables, FAKE, None) == 1
+    keep[0][0].dtype = 1                                      # bf16 dimension table
+    assert lib.lq_tree_project_dims(ctypes.byref(star), ctypes.byref(tree), tables, FAKE, None) == 3
+    keep[0][0].dtype = 0
+    # fused: neither output requested; misaligned target
+    assert lib.lq_fused_join_tree(ctypes.byref(star), ctypes.byref(tree), tables, FAKE, None, None, 0,
+                                  None, 0, None) == 1
+    assert lib.lq_fused_join_tree(ctypes.byref(star), ctypes.byref(tree), tables, FAKE + 8, FAKE, None, 0,
+                                  None, 0, None) == 1
+    # materialised: workspace too small
+    assert lib.lq_materialized_join_tree(ctypes.byref(star), ctypes.byref(tree), FAKE, None, FAKE, 1024, 0,
+                                         None) == 4
+    assert lib.lq_tree_workspace_bytes(ctypes.byref(star), 256) >= 256 * 5 * 4
