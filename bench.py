@@ -144,7 +144,7 @@ def main():
     # ---------------------------------------------------------------- CPU oracle baseline
     if args.only == "" and not args.no_cpu:
         from oracle import lq_oracle as O
-        sample = min(n, 1 << 21)
+        sample = min(n, 1 << 23)
         Xs = w.X[:sample].cpu()
         fs = [f[:sample].cpu() for f in w.fks]
         ds = [d.cpu() for d in w.dims]
