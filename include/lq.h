@@ -51,13 +51,15 @@ typedef enum {
   LQ_ERR_WORKSPACE = 4,   /* workspace missing, misaligned or too small */
   LQ_ERR_FK_RANGE = 5,    /* LQ_CHECK_FKS found a key outside its table */
   LQ_ERR_UNSUPPORTED = 6, /* valid request this build cannot run */
-  LQ_ERR_HIP = 7          /* the HIP runtime reported an error */
+  LQ_ERR_HIP = 7,         /* the HIP runtime reported an error */
+  LQ_ERR_DUPLICATE_KEY = 8 /* LQ_CHECK_KEYS found a dimension key twice */
 } lq_status;
 
 typedef enum { LQ_F32 = 0, LQ_BF16 = 1 } lq_dtype;
 
 /* flags */
 #define LQ_CHECK_FKS 1u
+#define LQ_CHECK_KEYS 2u
 /* Testing aid for lq_fused_join_predict: run the shape-agnostic kernel even where a
  * specialised one exists, so that the two can be compared. */
 #define LQ_FORCE_GENERIC 0x100u
@@ -237,6 +239,43 @@ int lq_materialized_join_tree(const lq_star* star, const lq_tree* tree, int32_t*
                               uint8_t* onehot, void* ws, size_t ws_bytes, uint32_t flags,
                               void* hip_stream);
 size_t lq_tree_workspace_bytes(const lq_star* star, int64_t chunk_rows);
+
+/* ---------------------------------------------------------------------------------------
+ * Key -> row mapping (the "domain generation" of the MM-Join, Algorithm 1, and the domain
+ * caching proposed with it): turns key VALUES of a fact column into row numbers of a dimension
+ * table, i.e. builds the row-matching matrix I of Section 2.3 in the form the calls above take.
+ * The cached domain is a hash table over the dimension keys kept in a caller-owned buffer.
+ * ------------------------------------------------------------------------------------- */
+
+/* Bytes of a key map that can hold max_keys keys (256-byte aligned buffer; 0 if out of range). */
+size_t lq_keymap_bytes(int64_t max_keys);
+
+/*
+ * Build the map from the n_keys int32 keys of a dimension (device array; key of row j at keys[j];
+ * keys must be unique).  With LQ_CHECK_KEYS the call waits and returns LQ_ERR_DUPLICATE_KEY if a
+ * value occurs twice; otherwise a duplicate silently keeps the row that got there first.
+ */
+int lq_keymap_build(void* table, size_t table_bytes, const int32_t* keys, int64_t n_keys,
+                    uint32_t flags, void* hip_stream);
+
+/* Add the keys of rows first_row .. first_row + n_keys - 1 to an existing map (the update of a
+ * cached domain).  The map must have been sized for the total number of keys. */
+int lq_keymap_insert(void* table, size_t table_bytes, const int32_t* keys, int64_t n_keys,
+                     int64_t first_row, uint32_t flags, void* hip_stream);
+
+/* fk[i] = row whose key equals fact_keys[i], or -1 (no match: the row drops out of an inner join). */
+int lq_keymap_lookup(const void* table, size_t table_bytes, const int32_t* fact_keys, int64_t n,
+                     int32_t* fk, void* hip_stream);
+
+/*
+ * The row-mapping matrices I_R and I_S of Section 2.3.3 as COO index vectors aligned with
+ * m = <0 .. nnz-1>: rows[m] is the fact row and cols[m] the dimension row of materialised row m,
+ * in ascending fact-row order.  rows / cols need room for n entries; *nnz (device) receives the
+ * number of matches.  ws: lq_compact_workspace_bytes(n) bytes, 256-byte aligned.
+ */
+int lq_compact_matches(const int32_t* fk, int64_t n, int64_t* rows, int32_t* cols, int64_t* nnz,
+                       void* ws, size_t ws_bytes, void* hip_stream);
+size_t lq_compact_workspace_bytes(int64_t n);
 
 /*
  * Plain device-to-device copy of `bytes` bytes (16-byte aligned pointers, bytes a

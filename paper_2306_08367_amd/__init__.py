@@ -10,5 +10,6 @@ from .binding import (  # noqa: F401
     lq_groupby_workspace_bytes, lq_last_error, lq_masked_groupby_sum,
     lq_materialized_join_predict, lq_project_dims, lq_stream_copy, lq_version,
     lq_workspace_bytes, lq_tree_table_ld, lq_tree_project_dims, lq_fused_join_tree,
-    lq_materialized_join_tree,
+    lq_materialized_join_tree, LQ_CHECK_KEYS, lq_keymap_bytes, lq_keymap_build, lq_keymap_insert,
+    lq_keymap_lookup, lq_compact_matches,
 )

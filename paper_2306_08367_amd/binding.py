@@ -20,7 +20,8 @@ LQ_FORCE_GENERIC = 0x100
 LQ_CALL_FUSED = 1
 LQ_CALL_MATERIALIZED = 2
 LQ_F32, LQ_BF16 = 0, 1
-_STATUS = {1: "LQ_ERR_NULL", 2: "LQ_ERR_SHAPE", 3: "LQ_ERR_DTYPE", 4: "LQ_ERR_WORKSPACE",
+LQ_CHECK_KEYS = 2
+_STATUS = {8: "LQ_ERR_DUPLICATE_KEY", 1: "LQ_ERR_NULL", 2: "LQ_ERR_SHAPE", 3: "LQ_ERR_DTYPE", 4: "LQ_ERR_WORKSPACE",
            5: "LQ_ERR_FK_RANGE", 6: "LQ_ERR_UNSUPPORTED", 7: "LQ_ERR_HIP"}
 
 
@@ -75,6 +76,14 @@ def _load():
     lib.lq_groupby_workspace_bytes.argtypes = [i32, ctypes.POINTER(i64), ctypes.POINTER(i32), i32]
     lib.lq_groupby_workspace_bytes.restype = sz
     lib.lq_stream_copy.argtypes = [vp, vp, sz, vp]
+    lib.lq_keymap_bytes.argtypes = [i64]
+    lib.lq_keymap_bytes.restype = sz
+    lib.lq_keymap_build.argtypes = [vp, sz, vp, i64, u32, vp]
+    lib.lq_keymap_insert.argtypes = [vp, sz, vp, i64, i64, u32, vp]
+    lib.lq_keymap_lookup.argtypes = [vp, sz, vp, i64, vp, vp]
+    lib.lq_compact_matches.argtypes = [vp, i64, vp, vp, vp, vp, sz, vp]
+    lib.lq_compact_workspace_bytes.argtypes = [i64]
+    lib.lq_compact_workspace_bytes.restype = sz
     pt = ctypes.POINTER(lq_tree)
     lib.lq_tree_table_ld.argtypes = [i32]
     lib.lq_tree_table_ld.restype = i64
@@ -87,7 +96,8 @@ def _load():
     lib.lq_version.restype = ctypes.c_char_p
     for f in ("lq_project_dims", "lq_fused_join_predict", "lq_materialized_join_predict",
               "lq_masked_groupby_sum", "lq_stream_copy", "lq_tree_project_dims", "lq_fused_join_tree",
-              "lq_materialized_join_tree"):
+              "lq_materialized_join_tree", "lq_keymap_build", "lq_keymap_insert", "lq_keymap_lookup",
+              "lq_compact_matches"):
         getattr(lib, f).restype = ctypes.c_int
     return lib
 
@@ -392,3 +402,49 @@ def lq_materialized_join_tree(X: Optional[torch.Tensor], dims, fks, feature, thr
                                           None if onehot is None else onehot.data_ptr(), ws.data_ptr(),
                                           ws.numel(), 0, _stream(stream)))
     return leaf, onehot
+
+
+# ---------------------------------------------------------------- key -> row mapping ----------
+
+def lq_keymap_bytes(max_keys: int) -> int:
+    return int(_lib.lq_keymap_bytes(max_keys))
+
+
+def lq_keymap_build(keys: torch.Tensor, max_keys: Optional[int] = None, flags: int = 0, stream=None) -> torch.Tensor:
+    """Hash map from the key values of a dimension to its row numbers; returns the map buffer."""
+    _expect(keys, torch.int32, "dimension key column")
+    nbytes = lq_keymap_bytes(max(int(keys.shape[0]), max_keys or 0))
+    table = torch.empty(nbytes, dtype=torch.uint8, device=keys.device)
+    _check(_lib.lq_keymap_build(table.data_ptr(), nbytes, keys.data_ptr(), int(keys.shape[0]), flags, _stream(stream)))
+    return table
+
+
+def lq_keymap_insert(table: torch.Tensor, keys: torch.Tensor, first_row: int, flags: int = 0, stream=None) -> None:
+    _expect(keys, torch.int32, "dimension key column")
+    _check(_lib.lq_keymap_insert(table.data_ptr(), table.numel(), keys.data_ptr(), int(keys.shape[0]),
+                                 int(first_row), flags, _stream(stream)))
+
+
+def lq_keymap_lookup(table: torch.Tensor, fact_keys: torch.Tensor, fk: Optional[torch.Tensor] = None,
+                     stream=None) -> torch.Tensor:
+    """fk[i] = dimension row whose key equals fact_keys[i], -1 where there is none."""
+    _expect(fact_keys, torch.int32, "fact key column")
+    if fk is None:
+        fk = torch.empty_like(fact_keys)
+    _check(_lib.lq_keymap_lookup(table.data_ptr(), table.numel(), fact_keys.data_ptr(),
+                                 int(fact_keys.shape[0]), fk.data_ptr(), _stream(stream)))
+    return fk
+
+
+def lq_compact_matches(fk: torch.Tensor, stream=None):
+    """COO index vectors of the row-matching matrix: (rows int64 [n], cols int32 [n], nnz int64 [1]);
+    only the first nnz entries of rows / cols are meaningful."""
+    _expect(fk, torch.int32, "mapped key column")
+    n = int(fk.shape[0])
+    rows = torch.empty(n, dtype=torch.int64, device=fk.device)
+    cols = torch.empty(n, dtype=torch.int32, device=fk.device)
+    nnz = torch.empty(1, dtype=torch.int64, device=fk.device)
+    ws = torch.empty(int(_lib.lq_compact_workspace_bytes(n)), dtype=torch.uint8, device=fk.device)
+    _check(_lib.lq_compact_matches(fk.data_ptr(), n, rows.data_ptr(), cols.data_ptr(), nnz.data_ptr(),
+                                   ws.data_ptr(), ws.numel(), _stream(stream)))
+    return rows, cols, nnz

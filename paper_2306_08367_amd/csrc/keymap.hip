@@ -1,0 +1,239 @@
+// Key -> row mapping for the MM-Join (Algorithm 1): the "domain generation" step that turns the
+// key values of a fact column into row numbers of the dimension table, i.e. into the one-nonzero-
+// per-row matrix I that the fused paths consume as an int32 column.
+//
+// The paper builds a sorted key domain and looks keys up in it (two binary searches per join,
+// its measured bottleneck) and proposes to cache the domain of the rarely changing side.  Here the
+// cached object is an open-addressing hash table over the dimension keys (capacity a power of two
+// of at least twice the key count, linear probing, 8-byte slots "key << 32 | row"): one or two
+// probes per fact row instead of log2(r) dependent searches, inserts for incremental updates, and
+// the fact side streams through once.  A key that is not in the table maps to -1 (the row does not
+// appear in the join result, Section 2.3.2).  The row-mapping matrices I_R / I_S of Section 2.3.3
+// (COO index vectors aligned with m = <0..nnz-1>) come from a stable compaction of the matches.
+#include "lq_common.h"
+
+namespace lq {
+namespace {
+
+typedef unsigned long long u64;
+constexpr u64 EMPTY = 0xffffffffffffffffull;
+constexpr size_t HEADER = 256;          // [0] capacity (u64), [8] error flags (u32)
+constexpr unsigned FLAG_DUPLICATE = 1u, FLAG_FULL = 2u;
+
+__device__ __forceinline__ uint32_t slot_of(int32_t key, uint32_t shift) {
+  return (static_cast<uint32_t>(key) * 0x9E3779B1u) >> shift;
+}
+
+__global__ __launch_bounds__(256) void keymap_clear_kernel(u64* slots, u64 capacity, u64* header) {
+  const u64 i = static_cast<u64>(blockIdx.x) * 256 + threadIdx.x;
+  if (i < capacity) slots[i] = EMPTY;
+  if (i == 0) { header[0] = capacity; reinterpret_cast<unsigned*>(header)[2] = 0u; }
+}
+
+__global__ __launch_bounds__(256) void keymap_insert_kernel(u64* slots, uint32_t mask, uint32_t shift,
+                                                            const int32_t* __restrict__ keys, int64_t r,
+                                                            int64_t row0, unsigned* flags) {
+  const int64_t i = static_cast<int64_t>(blockIdx.x) * 256 + threadIdx.x;
+  if (i >= r) return;
+  const int32_t key = keys[i];
+  const u64 mine = (static_cast<u64>(static_cast<uint32_t>(key)) << 32) | static_cast<uint32_t>(row0 + i);
+  uint32_t s = slot_of(key, shift) & mask;
+  for (uint32_t probes = 0; probes <= mask; ++probes) {           // bounded: at most one sweep of the table
+    const u64 old = atomicCAS(&slots[s], EMPTY, mine);
+    if (old == EMPTY) return;
+    if (static_cast<int32_t>(old >> 32) == key) { atomicOr(flags, FLAG_DUPLICATE); return; }
+    s = (s + 1) & mask;
+  }
+  atomicOr(flags, FLAG_FULL);
+}
+
+__global__ __launch_bounds__(256) void keymap_lookup_kernel(const u64* __restrict__ slots, uint32_t mask,
+                                                            uint32_t shift, const int32_t* __restrict__ keys,
+                                                            int64_t n, int32_t* __restrict__ fk) {
+  const int64_t i = static_cast<int64_t>(blockIdx.x) * 256 + threadIdx.x;
+  if (i >= n) return;
+  const int32_t key = __builtin_nontemporal_load(keys + i);
+  uint32_t s = slot_of(key, shift) & mask;
+  int32_t row = -1;
+  for (uint32_t probes = 0; probes <= mask; ++probes) {
+    const u64 v = slots[s];
+    if (v == EMPTY) break;
+    if (static_cast<int32_t>(v >> 32) == key) { row = static_cast<int32_t>(v & 0xffffffffu); break; }
+    s = (s + 1) & mask;
+  }
+  __builtin_nontemporal_store(row, fk + i);
+}
+
+// ---- stable compaction of the matches: COO index vectors of I --------------------------------
+constexpr int CB = 1024;   // rows per workgroup
+
+__global__ __launch_bounds__(CB) void compact_count_kernel(const int32_t* __restrict__ fk, int64_t n,
+                                                           int64_t* __restrict__ block_count) {
+  __shared__ int wave_cnt[CB / 64];
+  const int64_t i = static_cast<int64_t>(blockIdx.x) * CB + threadIdx.x;
+  const bool hit = i < n && fk[i] >= 0;
+  const int c = __popcll(__ballot(hit));
+  if ((threadIdx.x & 63) == 0) wave_cnt[threadIdx.x >> 6] = c;
+  __syncthreads();
+  if (threadIdx.x == 0) {
+    int t = 0;
+    for (int w = 0; w < CB / 64; ++w) t += wave_cnt[w];
+    block_count[blockIdx.x] = t;
+  }
+}
+
+// One workgroup: exclusive scan of the per-workgroup counts (in place) and the total.
+__global__ __launch_bounds__(1024) void compact_scan_kernel(int64_t* block_count, int64_t nb, int64_t* nnz) {
+  __shared__ int64_t part[1024];
+  const int tid = threadIdx.x;
+  const int64_t per = (nb + 1023) / 1024;
+  const int64_t lo = std::min<int64_t>(nb, tid * per), hi = std::min<int64_t>(nb, lo + per);
+  int64_t s = 0;
+  for (int64_t b = lo; b < hi; ++b) s += block_count[b];
+  part[tid] = s;
+  __syncthreads();
+  if (tid == 0) {
+    int64_t run = 0;
+    for (int t = 0; t < 1024; ++t) { const int64_t v = part[t]; part[t] = run; run += v; }
+    *nnz = run;
+  }
+  __syncthreads();
+  int64_t run = part[tid];
+  for (int64_t b = lo; b < hi; ++b) { const int64_t v = block_count[b]; block_count[b] = run; run += v; }
+}
+
+__global__ __launch_bounds__(CB) void compact_scatter_kernel(const int32_t* __restrict__ fk, int64_t n,
+                                                             const int64_t* __restrict__ block_off,
+                                                             int64_t* __restrict__ rows, int32_t* __restrict__ cols) {
+  __shared__ int wave_off[CB / 64];
+  const int64_t i = static_cast<int64_t>(blockIdx.x) * CB + threadIdx.x;
+  const int32_t v = i < n ? fk[i] : -1;
+  const bool hit = v >= 0;
+  const u64 bal = __ballot(hit);
+  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+  if (lane == 0) wave_off[wave] = __popcll(bal);
+  __syncthreads();
+  if (threadIdx.x == 0) {
+    int run = 0;
+    for (int w = 0; w < CB / 64; ++w) { const int c = wave_off[w]; wave_off[w] = run; run += c; }
+  }
+  __syncthreads();
+  if (hit) {
+    const int64_t m = block_off[blockIdx.x] + wave_off[wave] + __popcll(bal & ((1ull << lane) - 1ull));
+    rows[m] = i;
+    cols[m] = v;
+  }
+}
+
+struct Geometry { u64 capacity; uint32_t mask, shift; };
+bool geometry(size_t table_bytes, Geometry* g) {
+  if (table_bytes < HEADER + 16) return false;
+  u64 cap = 2;
+  while (cap * 2 * 8 + HEADER <= table_bytes && cap < (1ull << 31)) cap <<= 1;
+  int log2 = 0;
+  while ((1ull << log2) < cap) ++log2;
+  g->capacity = cap; g->mask = static_cast<uint32_t>(cap - 1); g->shift = static_cast<uint32_t>(32 - log2);
+  return true;
+}
+
+}  // namespace
+}  // namespace lq
+
+using namespace lq;
+
+extern "C" {
+
+size_t lq_keymap_bytes(int64_t max_keys) {
+  if (max_keys < 0 || max_keys > (1ll << 29)) return 0;
+  u64 cap = 2;
+  while (cap < static_cast<u64>(max_keys) * 2) cap <<= 1;
+  return HEADER + cap * 8;
+}
+
+int lq_keymap_insert(void* table, size_t table_bytes, const int32_t* keys, int64_t n_keys, int64_t first_row,
+                     uint32_t flags, void* hip_stream) {
+  clear_error();
+  Geometry g;
+  if (!table || !aligned(table, 256) || !geometry(table_bytes, &g)) return fail(LQ_ERR_WORKSPACE, "key map buffer is NULL, misaligned or too small");
+  if (n_keys < 0 || first_row < 0 || first_row + n_keys > 0x7fffffffLL) return fail(LQ_ERR_SHAPE, "row numbers do not fit int32");
+  if (n_keys > 0 && (!keys || !aligned(keys, 4))) return fail(LQ_ERR_NULL, "keys is NULL or misaligned");
+  hipStream_t s = static_cast<hipStream_t>(hip_stream);
+  u64* header = static_cast<u64*>(table);
+  u64* slots = header + HEADER / 8;
+  if (n_keys > 0) {
+    hipLaunchKernelGGL(keymap_insert_kernel, dim3(static_cast<unsigned>((n_keys + 255) / 256)), dim3(256), 0, s, slots,
+                       g.mask, g.shift, keys, n_keys, first_row, reinterpret_cast<unsigned*>(header) + 2);
+    LQ_LAUNCH_CHECK("keymap_insert_kernel");
+  }
+  if (flags & LQ_CHECK_KEYS) {
+    unsigned h = 0;
+    LQ_HIP_TRY(hipMemcpyAsync(&h, reinterpret_cast<unsigned*>(header) + 2, sizeof(h), hipMemcpyDeviceToHost, s));
+    LQ_HIP_TRY(hipStreamSynchronize(s));
+    if (h & FLAG_DUPLICATE) return fail(LQ_ERR_DUPLICATE_KEY, "the dimension key column holds a value twice");
+    if (h & FLAG_FULL) return fail(LQ_ERR_WORKSPACE, "key map is full");
+  }
+  return LQ_OK;
+}
+
+int lq_keymap_build(void* table, size_t table_bytes, const int32_t* keys, int64_t n_keys, uint32_t flags,
+                    void* hip_stream) {
+  clear_error();
+  Geometry g;
+  if (!table || !aligned(table, 256) || !geometry(table_bytes, &g)) return fail(LQ_ERR_WORKSPACE, "key map buffer is NULL, misaligned or too small");
+  if (n_keys < 0 || static_cast<u64>(n_keys) * 2 > g.capacity) return fail(LQ_ERR_WORKSPACE, "key map buffer holds %llu slots, %lld keys need twice as many", (unsigned long long)g.capacity, (long long)n_keys);
+  hipStream_t s = static_cast<hipStream_t>(hip_stream);
+  u64* header = static_cast<u64*>(table);
+  hipLaunchKernelGGL(keymap_clear_kernel, dim3(static_cast<unsigned>((g.capacity + 255) / 256)), dim3(256), 0, s,
+                     header + HEADER / 8, g.capacity, header);
+  LQ_LAUNCH_CHECK("keymap_clear_kernel");
+  return lq_keymap_insert(table, table_bytes, keys, n_keys, 0, flags, hip_stream);
+}
+
+int lq_keymap_lookup(const void* table, size_t table_bytes, const int32_t* fact_keys, int64_t n, int32_t* fk,
+                     void* hip_stream) {
+  clear_error();
+  Geometry g;
+  if (!table || !aligned(table, 256) || !geometry(table_bytes, &g)) return fail(LQ_ERR_WORKSPACE, "key map buffer is NULL, misaligned or too small");
+  if (n < 0) return fail(LQ_ERR_SHAPE, "n < 0");
+  if (n == 0) return LQ_OK;
+  if (!fact_keys || !fk || !aligned(fact_keys, 4) || !aligned(fk, 4)) return fail(LQ_ERR_NULL, "fact_keys or fk is NULL or misaligned");
+  const int64_t blocks = (n + 255) / 256;
+  if (blocks > 0x7fffffffLL) return fail(LQ_ERR_UNSUPPORTED, "too many rows for one launch");
+  hipLaunchKernelGGL(keymap_lookup_kernel, dim3(static_cast<unsigned>(blocks)), dim3(256), 0,
+                     static_cast<hipStream_t>(hip_stream), static_cast<const u64*>(table) + HEADER / 8, g.mask, g.shift,
+                     fact_keys, n, fk);
+  LQ_LAUNCH_CHECK("keymap_lookup_kernel");
+  return LQ_OK;
+}
+
+size_t lq_compact_workspace_bytes(int64_t n) {
+  if (n < 0) return 0;
+  return round_up(static_cast<size_t>((n + CB - 1) / CB + 1) * 8, 256);
+}
+
+int lq_compact_matches(const int32_t* fk, int64_t n, int64_t* rows, int32_t* cols, int64_t* nnz, void* ws,
+                       size_t ws_bytes, void* hip_stream) {
+  clear_error();
+  if (n < 0) return fail(LQ_ERR_SHAPE, "n < 0");
+  if (!nnz || !aligned(nnz, 8)) return fail(LQ_ERR_NULL, "nnz is NULL or misaligned");
+  if (n > 0 && (!fk || !rows || !cols)) return fail(LQ_ERR_NULL, "fk, rows or cols is NULL");
+  if (!aligned(rows, 8) || !aligned(cols, 4) || !aligned(fk, 4)) return fail(LQ_ERR_SHAPE, "misaligned array");
+  if (!ws || !aligned(ws, 256) || ws_bytes < lq_compact_workspace_bytes(n)) return fail(LQ_ERR_WORKSPACE, "compaction needs %zu bytes of 256-byte aligned workspace", lq_compact_workspace_bytes(n));
+  const int64_t nb = (n + CB - 1) / CB;
+  if (nb > 0x7fffffffLL) return fail(LQ_ERR_UNSUPPORTED, "too many rows for one launch");
+  hipStream_t s = static_cast<hipStream_t>(hip_stream);
+  int64_t* counts = static_cast<int64_t*>(ws);
+  if (nb > 0) {
+    hipLaunchKernelGGL(compact_count_kernel, dim3(static_cast<unsigned>(nb)), dim3(CB), 0, s, fk, n, counts);
+    LQ_LAUNCH_CHECK("compact_count_kernel");
+  }
+  hipLaunchKernelGGL(compact_scan_kernel, dim3(1), dim3(1024), 0, s, counts, nb, nnz);
+  LQ_LAUNCH_CHECK("compact_scan_kernel");
+  if (nb > 0) {
+    hipLaunchKernelGGL(compact_scatter_kernel, dim3(static_cast<unsigned>(nb)), dim3(CB), 0, s, fk, n, counts, rows, cols);
+    LQ_LAUNCH_CHECK("compact_scatter_kernel");
+  }
+  return LQ_OK;
+}
+
+}  // extern "C"

@@ -1,0 +1,100 @@
+"""GPU parity of the key -> row mapping (Algorithm 1's domain generation + row-matching matrix)
+against the MM-Join oracle: bit-exact, including the COO form of I and its use by the group-by."""
+import numpy as np
+import pytest
+import torch
+
+from oracle import lq_oracle as O
+from oracle import mmjoin_oracle as MJ
+
+pytestmark = pytest.mark.gpu
+
+
+@pytest.fixture(scope="module")
+def lq():
+    import paper_2306_08367_amd as lq
+    return lq
+
+
+def _keys(seed, r, n, miss=0.05, lo=-2**31, hi=2**31 - 1):
+    g = np.random.default_rng(seed)
+    pool = np.unique(g.integers(lo, hi, size=int(r * 1.3) + 8, dtype=np.int64))
+    g.shuffle(pool)
+    key_S = pool[:r].astype(np.int32)
+    extra = pool[r:]
+    key_R = g.choice(key_S, size=n).astype(np.int32) if r else np.zeros(n, dtype=np.int32)
+    if len(extra) and n:
+        m = g.random(n) < miss
+        key_R[m] = g.choice(extra, size=int(m.sum())).astype(np.int32)
+    return key_S, key_R
+
+
+@pytest.mark.parametrize("r,n", [(1, 1), (1, 100), (7, 1_000), (2_556, 100_003), (30_000, 200_001), (200_000, 1_000_000)])
+def test_lookup_and_compaction_match_algorithm_1(lq, r, n):
+    key_S, key_R = _keys(r + n, r, n)
+    fk_w, rows_w, cols_w = MJ.key_to_row(key_R, key_S)
+    table = lq.lq_keymap_build(torch.from_numpy(key_S).cuda(), flags=lq.LQ_CHECK_KEYS)
+    fk = lq.lq_keymap_lookup(table, torch.from_numpy(key_R).cuda())
+    rows, cols, nnz = lq.lq_compact_matches(fk)
+    torch.cuda.synchronize()
+    np.testing.assert_array_equal(fk.cpu().numpy(), fk_w)
+    m = int(nnz.item())
+    assert m == len(rows_w)
+    np.testing.assert_array_equal(rows[:m].cpu().numpy(), rows_w)
+    np.testing.assert_array_equal(cols[:m].cpu().numpy(), cols_w)
+
+
+def test_extreme_key_values_and_no_matches(lq):
+    key_S = np.array([-2**31, 2**31 - 1, 0, -1, 1], dtype=np.int32)
+    key_R = np.array([0, -1, 2**31 - 1, -2**31, 5, 1, 1, -7], dtype=np.int32)
+    table = lq.lq_keymap_build(torch.from_numpy(key_S).cuda())
+    fk = lq.lq_keymap_lookup(table, torch.from_numpy(key_R).cuda())
+    assert fk.cpu().tolist() == [2, 3, 1, 0, -1, 4, 4, -1]
+    none = lq.lq_keymap_lookup(table, torch.full((1000,), 77, dtype=torch.int32, device="cuda"))
+    rows, cols, nnz = lq.lq_compact_matches(none)
+    assert int(nnz.item()) == 0 and (none == -1).all()
+    rows, cols, nnz = lq.lq_compact_matches(torch.empty(0, dtype=torch.int32, device="cuda"))
+    assert int(nnz.item()) == 0
+
+
+def test_duplicate_dimension_keys_are_reported(lq):
+    keys = torch.tensor([5, 9, 5, 3], dtype=torch.int32, device="cuda")
+    with pytest.raises(lq.LQError) as e:
+        lq.lq_keymap_build(keys, flags=lq.LQ_CHECK_KEYS)
+    assert e.value.status == "LQ_ERR_DUPLICATE_KEY"
+
+
+def test_incremental_insert_equals_rebuild(lq):
+    """Updating a cached domain: keys of new dimension rows are inserted into the existing map."""
+    key_S, key_R = _keys(99, 50_000, 300_000, miss=0.2)
+    full = lq.lq_keymap_build(torch.from_numpy(key_S).cuda())
+    part = lq.lq_keymap_build(torch.from_numpy(key_S[:30_000]).cuda(), max_keys=50_000)
+    kr = torch.from_numpy(key_R).cuda()
+    before = lq.lq_keymap_lookup(part, kr)
+    lq.lq_keymap_insert(part, torch.from_numpy(key_S[30_000:]).cuda(), 30_000, flags=lq.LQ_CHECK_KEYS)
+    after = lq.lq_keymap_lookup(part, kr)
+    want = lq.lq_keymap_lookup(full, kr)
+    torch.cuda.synchronize()
+    assert torch.equal(after, want)
+    fk_w, _, _ = MJ.key_to_row(key_R, key_S[:30_000])
+    np.testing.assert_array_equal(before.cpu().numpy(), fk_w)
+
+
+def test_mapped_keys_feed_the_group_by(lq):
+    """End to end on raw key values: map four key columns, then aggregate; unmatched keys drop out."""
+    g = np.random.default_rng(5)
+    n, rows_k, card = 200_003, (50, 400, 30), (5, 7, 1)
+    keys_S, keys_R = zip(*[_keys(200 + k, r, n, miss=0.1) for k, r in enumerate(rows_k)])
+    codes = [g.integers(0, c, size=r).astype(np.int32) if c > 1 else None for r, c in zip(rows_k, card)]
+    masks = [None, None, (g.random(30) < 0.5).astype(np.uint8)]
+    meas = g.integers(1, 1000, size=n).astype(np.int32)
+    fks_w = [MJ.key_to_row(kr, ks)[0] for kr, ks in zip(keys_R, keys_S)]
+    want_s, want_c = O.groupby_sum(fks_w, list(rows_k), masks, codes, list(card), None, [meas])
+    fks = [lq.lq_keymap_lookup(lq.lq_keymap_build(torch.from_numpy(ks).cuda()), torch.from_numpy(kr).cuda())
+           for kr, ks in zip(keys_R, keys_S)]
+    dev = lambda a: None if a is None else torch.from_numpy(a).cuda()
+    s, c = lq.lq_masked_groupby_sum(fks, list(rows_k), [dev(m) for m in masks], [dev(x) for x in codes],
+                                    list(card), None, [dev(meas)])
+    torch.cuda.synchronize()
+    np.testing.assert_array_equal(s.cpu().numpy(), want_s)
+    np.testing.assert_array_equal(c.cpu().numpy(), want_c)
