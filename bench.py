@@ -67,7 +67,7 @@ def main():
     ap.add_argument("--rows", type=int, default=10_000_000, help="fact rows of the headline workload")
     ap.add_argument("--no-extras", action="store_true", help="skip materialised / group-by / skewed legs")
     ap.add_argument("--no-cpu", action="store_true", help="skip the CPU oracle baseline")
-    ap.add_argument("--only", default="", help="run a single leg for profiling: fused|groupby|groupby16|c4|c5|tree|materialized|copy")
+    ap.add_argument("--only", default="", help="run a single leg for profiling: fused|groupby|groupby16|c4|c5|tree|keymap|materialized|copy")
     args = ap.parse_args()
     if args.gpus != 1:
         sys.exit("bench.py: this build is single-GPU by design (no collectives, no sharding); "
@@ -289,6 +289,27 @@ def main():
                                           "frac": gbps / HBM_PEAK_GBPS, "algorithmic_bytes_per_row": 16,
                                           "gather_GBps": 192.0 * nt / (ms * 1e-3) / 1e9}}
         del wt, tables
+
+    # ---------------------------------------------------------------- key -> row mapping (SSB sf1 shape)
+    if (args.only == "" and not args.no_extras) or args.only == "keymap":
+        nk = 6_000_000
+        gen = torch.Generator(device=dev); gen.manual_seed(WL.SEED0 + 900)
+        res = {}
+        tot_ms = 0.0
+        for r in (2_556, 30_000, 2_000, 200_000):
+            # sparse unique keys: a random subset of 0 .. 8r, shuffled
+            keys_S = torch.randperm(8 * r, generator=gen, device=dev)[:r].to(torch.int32)
+            fact = keys_S[torch.randint(0, r, (nk,), generator=gen, device=dev)]
+            table = lq.lq_keymap_build(keys_S)
+            fk = torch.empty(nk, dtype=torch.int32, device=dev)
+            bms, _, _ = time_call(lambda: lq.lq_keymap_build(keys_S), 5, 1)
+            lms, _, _ = time_call(lambda: lq.lq_keymap_lookup(table, fact, fk=fk), 20, 3)
+            res[str(r)] = {"build_ms": bms, "lookup_ms": lms, "lookup_GBps": 8.0 * nk / (lms * 1e-3) / 1e9}
+            tot_ms += lms
+        gbps = 4 * 8.0 * nk / (tot_ms * 1e-3) / 1e9
+        out["keymap_ssb_sf1"] = {"fact_rows": nk, "rows_per_s_all_4_columns": nk / (tot_ms * 1e-3), "per_dimension": res,
+                                 "roofline": {"bound": "hbm", "achieved": gbps, "peak": HBM_PEAK_GBPS, "unit": "GB/s",
+                                              "frac": gbps / HBM_PEAK_GBPS, "algorithmic_bytes_per_row": 8}}
 
     print(json.dumps(out))
 

@@ -47,21 +47,69 @@ __global__ __launch_bounds__(256) void keymap_insert_kernel(u64* slots, uint32_t
   atomicOr(flags, FLAG_FULL);
 }
 
-__global__ __launch_bounds__(256) void keymap_lookup_kernel(const u64* __restrict__ slots, uint32_t mask,
-                                                            uint32_t shift, const int32_t* __restrict__ keys,
-                                                            int64_t n, int32_t* __restrict__ fk) {
-  const int64_t i = static_cast<int64_t>(blockIdx.x) * 256 + threadIdx.x;
-  if (i >= n) return;
-  const int32_t key = __builtin_nontemporal_load(keys + i);
+__device__ __forceinline__ int32_t probe(const u64* slots, uint32_t mask, uint32_t shift, int32_t key) {
   uint32_t s = slot_of(key, shift) & mask;
-  int32_t row = -1;
-  for (uint32_t probes = 0; probes <= mask; ++probes) {
+  for (uint32_t probes = 0; probes <= mask; ++probes) {           // bounded: at most one sweep of the table
     const u64 v = slots[s];
-    if (v == EMPTY) break;
-    if (static_cast<int32_t>(v >> 32) == key) { row = static_cast<int32_t>(v & 0xffffffffu); break; }
+    if (v == EMPTY) return -1;
+    if (static_cast<int32_t>(v >> 32) == key) return static_cast<int32_t>(v & 0xffffffffu);
     s = (s + 1) & mask;
   }
-  __builtin_nontemporal_store(row, fk + i);
+  return -1;
+}
+
+typedef int v4i __attribute__((ext_vector_type(4)));
+
+// Four keys per thread (one 16-byte load, four probes in flight); the tail is done one by one.
+__global__ __launch_bounds__(256) void keymap_lookup_kernel(const u64* __restrict__ slots, uint32_t mask,
+                                                            uint32_t shift, const int32_t* __restrict__ keys,
+                                                            int64_t n, int32_t* __restrict__ fk, int vec_ok) {
+  const int64_t t = static_cast<int64_t>(blockIdx.x) * 256 + threadIdx.x;
+  if (vec_ok) {
+    const int64_t n4 = n / 4;
+    if (t < n4) {
+      const v4i k = __builtin_nontemporal_load(reinterpret_cast<const v4i*>(keys) + t);
+      v4i r;
+#pragma unroll
+      for (int q = 0; q < 4; ++q) r[q] = probe(slots, mask, shift, k[q]);
+      __builtin_nontemporal_store(r, reinterpret_cast<v4i*>(fk) + t);
+    } else if (t - n4 < n - 4 * n4) {
+      const int64_t i = 4 * n4 + (t - n4);
+      fk[i] = probe(slots, mask, shift, keys[i]);
+    }
+  } else if (t < n) {
+    fk[t] = probe(slots, mask, shift, keys[t]);
+  }
+}
+
+// Small maps: every workgroup copies the whole slot array into LDS and serves a contiguous slice of
+// the fact keys from there, so probes never leave the compute unit.
+constexpr int LDS_LOOKUP_THREADS = 1024;
+__global__ __launch_bounds__(LDS_LOOKUP_THREADS) void keymap_lookup_lds_kernel(const u64* __restrict__ slots,
+                                                                              uint32_t mask, uint32_t shift,
+                                                                              const int32_t* __restrict__ keys,
+                                                                              int64_t n, int32_t* __restrict__ fk,
+                                                                              int64_t per_block) {
+  extern __shared__ __align__(16) u64 lds_slots[];
+  {
+    const uint4* src = reinterpret_cast<const uint4*>(slots);
+    uint4* dst = reinterpret_cast<uint4*>(lds_slots);
+    for (uint32_t i = threadIdx.x; i < (mask + 1u) / 2u; i += LDS_LOOKUP_THREADS) dst[i] = src[i];
+  }
+  __syncthreads();
+  const int64_t n4 = n / 4;
+  const int64_t lo = static_cast<int64_t>(blockIdx.x) * per_block, hi = min(n4, lo + per_block);
+  for (int64_t t = lo + threadIdx.x; t < hi; t += LDS_LOOKUP_THREADS) {
+    const v4i k = __builtin_nontemporal_load(reinterpret_cast<const v4i*>(keys) + t);
+    v4i r;
+#pragma unroll
+    for (int q = 0; q < 4; ++q) r[q] = probe(lds_slots, mask, shift, k[q]);
+    __builtin_nontemporal_store(r, reinterpret_cast<v4i*>(fk) + t);
+  }
+  if (blockIdx.x == 0) {
+    const int64_t i = 4 * n4 + threadIdx.x;
+    if (i < n) fk[i] = probe(lds_slots, mask, shift, keys[i]);
+  }
 }
 
 // ---- stable compaction of the matches: COO index vectors of I --------------------------------
@@ -197,11 +245,27 @@ int lq_keymap_lookup(const void* table, size_t table_bytes, const int32_t* fact_
   if (n < 0) return fail(LQ_ERR_SHAPE, "n < 0");
   if (n == 0) return LQ_OK;
   if (!fact_keys || !fk || !aligned(fact_keys, 4) || !aligned(fk, 4)) return fail(LQ_ERR_NULL, "fact_keys or fk is NULL or misaligned");
-  const int64_t blocks = (n + 255) / 256;
+  hipStream_t s = static_cast<hipStream_t>(hip_stream);
+  const u64* slots = static_cast<const u64*>(table) + HEADER / 8;
+  const int vec_ok = aligned(fact_keys, 16) && aligned(fk, 16);
+  const size_t slot_bytes = static_cast<size_t>(g.capacity) * 8;
+  if (vec_ok && slot_bytes <= 128 * 1024 && n >= (1 << 20)) {
+    const int64_t n4 = n / 4;
+    const int64_t blocks = std::max<int64_t>(1, std::min<int64_t>((n4 + LDS_LOOKUP_THREADS - 1) / LDS_LOOKUP_THREADS, num_cus()));
+    const int64_t per_block = (n4 + blocks - 1) / blocks;
+    if (slot_bytes > 64 * 1024)
+      LQ_HIP_TRY(hipFuncSetAttribute(reinterpret_cast<const void*>(&keymap_lookup_lds_kernel),
+                                     hipFuncAttributeMaxDynamicSharedMemorySize, static_cast<int>(slot_bytes)));
+    hipLaunchKernelGGL(keymap_lookup_lds_kernel, dim3(static_cast<unsigned>(blocks)), dim3(LDS_LOOKUP_THREADS), slot_bytes, s,
+                       slots, g.mask, g.shift, fact_keys, n, fk, per_block);
+    LQ_LAUNCH_CHECK("keymap_lookup_lds_kernel");
+    return LQ_OK;
+  }
+  const int64_t threads = vec_ok ? n / 4 + n % 4 : n;
+  const int64_t blocks = (threads + 255) / 256;
   if (blocks > 0x7fffffffLL) return fail(LQ_ERR_UNSUPPORTED, "too many rows for one launch");
-  hipLaunchKernelGGL(keymap_lookup_kernel, dim3(static_cast<unsigned>(blocks)), dim3(256), 0,
-                     static_cast<hipStream_t>(hip_stream), static_cast<const u64*>(table) + HEADER / 8, g.mask, g.shift,
-                     fact_keys, n, fk);
+  hipLaunchKernelGGL(keymap_lookup_kernel, dim3(static_cast<unsigned>(blocks)), dim3(256), 0, s, slots, g.mask, g.shift,
+                     fact_keys, n, fk, vec_ok);
   LQ_LAUNCH_CHECK("keymap_lookup_kernel");
   return LQ_OK;
 }

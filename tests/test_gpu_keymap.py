@@ -29,7 +29,7 @@ def _keys(seed, r, n, miss=0.05, lo=-2**31, hi=2**31 - 1):
     return key_S, key_R
 
 
-@pytest.mark.parametrize("r,n", [(1, 1), (1, 100), (7, 1_000), (2_556, 100_003), (30_000, 200_001), (200_000, 1_000_000)])
+@pytest.mark.parametrize("r,n", [(1, 1), (1, 100), (7, 1_000), (2_556, 100_003), (30_000, 200_001), (200_000, 1_000_000), (2_000, 1_200_003), (8_000, 1_100_000)])
 def test_lookup_and_compaction_match_algorithm_1(lq, r, n):
     key_S, key_R = _keys(r + n, r, n)
     fk_w, rows_w, cols_w = MJ.key_to_row(key_R, key_S)

@@ -178,3 +178,21 @@ def test_tree_entry_points_reject_bad_arguments():
     assert lib.lq_materialized_join_tree(ctypes.byref(star), ctypes.byref(tree), FAKE, None, FAKE, 1024, 0,
                                          None) == 4
     assert lib.lq_tree_workspace_bytes(ctypes.byref(star), 256) >= 256 * 5 * 4
+
+
+def test_keymap_entry_points_reject_bad_arguments():
+    b = _binding()
+    lib = b._lib
+    assert b.lq_keymap_bytes(0) == 256 + 16 and b.lq_keymap_bytes(1000) == 256 + 2048 * 8
+    assert b.lq_keymap_bytes(-1) == 0
+    nbytes = b.lq_keymap_bytes(1000)
+    assert lib.lq_keymap_build(None, nbytes, FAKE, 10, 0, None) == 4
+    assert lib.lq_keymap_build(FAKE, nbytes, FAKE, 2000, 0, None) == 4      # sized for 1000 keys
+    assert lib.lq_keymap_build(FAKE + 8, nbytes, FAKE, 10, 0, None) == 4    # misaligned buffer
+    assert lib.lq_keymap_insert(FAKE, nbytes, None, 10, 0, 0, None) == 1
+    assert lib.lq_keymap_insert(FAKE, nbytes, FAKE, 10, 2**31, 0, None) == 2
+    assert lib.lq_keymap_lookup(FAKE, nbytes, None, 10, FAKE, None) == 1
+    assert lib.lq_keymap_lookup(FAKE, 8, FAKE, 10, FAKE, None) == 4
+    assert lib.lq_compact_matches(FAKE, 10, FAKE, FAKE, None, FAKE, 4096, None) == 1
+    assert lib.lq_compact_matches(FAKE, 10, FAKE, FAKE, FAKE, FAKE, 8, None) == 4
+    assert lib.lq_compact_workspace_bytes(10) >= 16
