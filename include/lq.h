@@ -117,6 +117,35 @@ typedef struct {
 int lq_project_dims(const lq_star* star, const lq_model* model, lq_mat* P, void* hip_stream);
 
 /*
+ * Incremental pre-fusion: recompute only rows [first_row, first_row + n_rows) of P[dim] after those
+ * rows of dimension `dim` changed (the pre-fused tables are "constants in a period", Section 3.2;
+ * the cost of refreshing them is the trade-off discussed with Q6 and Q8).  Same result as running
+ * lq_project_dims again, restricted to those rows.
+ */
+int lq_project_dim_rows(const lq_star* star, const lq_model* model, lq_mat* P, int32_t dim,
+                        int64_t first_row, int64_t n_rows, void* hip_stream);
+
+/*
+ * The complexity model of Section 3.2.1 evaluated for a concrete star schema and model (host only,
+ * nothing is enqueued; only shapes are read).  With k the joined width, l = l_1, i = n_fact:
+ *   cost_no_fusion = sum_j c_j k r_j + i k sum_j r_j + i k l        (C_mmjoin + C_op)
+ *   cost_fusion    = i l sum_j r_j                                   (C_fusion)
+ *   ratio          = cost_no_fusion / cost_fusion                    (Eq. 3 for equal c_j, K = 3)
+ *   cost_prefusion = sum_j r_j c_j l                                 (D_j M_j L, paid per update)
+ *   memory_growth  = sum_j r_j l / sum_j r_j c_j                     (> 1 when l exceeds the columns, Q6)
+ *   fuse           = 1 when queries_per_update * (cost_no_fusion - cost_fusion) > cost_prefusion
+ * bytes_per_row_*  what one fact row moves in this library's kernels (one nonzero per row of I_k).
+ */
+typedef struct {
+  double cost_no_fusion, cost_fusion, cost_prefusion;
+  double ratio, ratio_leading_term, memory_growth;
+  double bytes_per_row_fused, bytes_per_row_no_fusion;
+  int32_t fuse;
+} lq_advice;
+int lq_fusion_advice(const lq_star* star, const lq_model* model, double queries_per_update,
+                     lq_advice* out);
+
+/*
  * Join-computation stage (last line of Eq. 1) with the rest of the model fused in:
  *   z_i = x_i W[0][0:c_f, :] + sum_k P_k[fks[k][i], :] + bias[0]
  *   y_i = z_i for a linear operator; otherwise ReLU and the remaining layers are

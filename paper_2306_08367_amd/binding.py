@@ -42,6 +42,12 @@ class lq_star(ctypes.Structure):
                 ("dims", ctypes.POINTER(lq_mat)), ("fks", ctypes.POINTER(ctypes.c_void_p))]
 
 
+class lq_advice(ctypes.Structure):
+    _fields_ = [(n, ctypes.c_double) for n in ("cost_no_fusion", "cost_fusion", "cost_prefusion", "ratio",
+                                               "ratio_leading_term", "memory_growth", "bytes_per_row_fused",
+                                               "bytes_per_row_no_fusion")] + [("fuse", ctypes.c_int32)]
+
+
 class lq_tree(ctypes.Structure):
     _fields_ = [("n_nodes", ctypes.c_int32), ("n_leaves", ctypes.c_int32), ("feature", ctypes.c_void_p),
                 ("threshold", ctypes.c_void_p), ("H", ctypes.c_void_p)]
@@ -76,6 +82,10 @@ def _load():
     lib.lq_groupby_workspace_bytes.argtypes = [i32, ctypes.POINTER(i64), ctypes.POINTER(i32), i32]
     lib.lq_groupby_workspace_bytes.restype = sz
     lib.lq_stream_copy.argtypes = [vp, vp, sz, vp]
+    lib.lq_project_dim_rows.argtypes = [ps, pmod, pm, i32, i64, i64, vp]
+    lib.lq_project_dim_rows.restype = ctypes.c_int
+    lib.lq_fusion_advice.argtypes = [ps, pmod, ctypes.c_double, ctypes.POINTER(lq_advice)]
+    lib.lq_fusion_advice.restype = ctypes.c_int
     lib.lq_keymap_bytes.argtypes = [i64]
     lib.lq_keymap_bytes.restype = sz
     lib.lq_keymap_build.argtypes = [vp, sz, vp, i64, u32, vp]
@@ -448,3 +458,38 @@ def lq_compact_matches(fk: torch.Tensor, stream=None):
     _check(_lib.lq_compact_matches(fk.data_ptr(), n, rows.data_ptr(), cols.data_ptr(), nnz.data_ptr(),
                                    ws.data_ptr(), ws.numel(), _stream(stream)))
     return rows, cols, nnz
+
+
+# ---------------------------------------------------------------- incremental pre-fusion, advice
+
+def lq_project_dim_rows(dims: Sequence[torch.Tensor], W0: torch.Tensor, c_f: int, P: List[torch.Tensor],
+                        dim: int, first_row: int, n_rows: int, stream=None) -> None:
+    """Refresh rows [first_row, first_row + n_rows) of P[dim] after those dimension rows changed."""
+    fact = lq_mat(None, 0, int(c_f), max(int(c_f), 1), _dtype_code(W0))
+    dims_arr = _mat_array(dims)
+    star = lq_star(0, fact, len(dims), dims_arr, _ptr_array([None] * len(dims)))
+    model = _Model([W0], None)
+    P_arr = _mat_array(P)
+    _check(_lib.lq_project_dim_rows(ctypes.byref(star), ctypes.byref(model.c), P_arr, dim, first_row, n_rows,
+                                    _stream(stream)))
+
+
+def lq_fusion_advice(n_fact: int, c_f: int, dim_shapes: Sequence[Sequence[int]], layer_widths: Sequence[int],
+                     queries_per_update: float = 1.0, dtype: int = LQ_F32) -> dict:
+    """Complexity model of Section 3.2.1 for a star of the given shapes (no device memory touched)."""
+    fake = 0x10000
+    dims_arr = (lq_mat * max(1, len(dim_shapes)))()
+    for j, (r, c) in enumerate(dim_shapes):
+        dims_arr[j] = lq_mat(fake, int(r), int(c), int(c), dtype)
+    fks = (ctypes.c_void_p * max(1, len(dim_shapes)))(*([fake] * len(dim_shapes)))
+    star = lq_star(int(n_fact), lq_mat(fake, int(n_fact), int(c_f), max(int(c_f), 1), dtype), len(dim_shapes), dims_arr, fks)
+    W = (lq_mat * len(layer_widths))()
+    rows = int(c_f) + sum(int(c) for _, c in dim_shapes)
+    for j, lo in enumerate(layer_widths):
+        W[j] = lq_mat(fake, rows, int(lo), int(lo), dtype)
+        rows = int(lo)
+    bias = (ctypes.c_void_p * len(layer_widths))()
+    model = lq_model(len(layer_widths), W, bias)
+    out = lq_advice()
+    _check(_lib.lq_fusion_advice(ctypes.byref(star), ctypes.byref(model), float(queries_per_update), ctypes.byref(out)))
+    return {n: getattr(out, n) for n, _ in lq_advice._fields_}

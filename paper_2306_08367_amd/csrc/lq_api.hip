@@ -191,6 +191,65 @@ int lq_project_dims(const lq_star* star, const lq_model* model, lq_mat* P, void*
   return LQ_OK;
 }
 
+int lq_project_dim_rows(const lq_star* star, const lq_model* model, lq_mat* P, int32_t dim,
+                        int64_t first_row, int64_t n_rows, void* hip_stream) {
+  clear_error();
+  Checked c;
+  int rc = check_star_model(star, model, true, &c);
+  if (rc) return rc;
+  if (!P) return fail(LQ_ERR_NULL, "P is NULL");
+  if (dim < 0 || dim >= star->n_dims) return fail(LQ_ERR_SHAPE, "dimension %d outside 0..%d", dim, star->n_dims - 1);
+  if ((rc = check_mat(P[dim], "P[dim]", true))) return rc;
+  const lq_mat& D = star->dims[dim];
+  if (P[dim].rows != D.rows || P[dim].cols != c.l1) return fail(LQ_ERR_SHAPE, "P[dim] does not match its dimension table");
+  if (P[dim].dtype == LQ_BF16 && c.dtype != LQ_BF16) return fail(LQ_ERR_DTYPE, "bf16 projected tables need a bf16 model");
+  if (first_row < 0 || n_rows < 0 || first_row + n_rows > D.rows)
+    return fail(LQ_ERR_SHAPE, "rows %lld .. +%lld outside the dimension table", (long long)first_row, (long long)n_rows);
+  if (n_rows == 0) return LQ_OK;
+  int32_t off = star->fact.cols > 0 ? star->fact.cols : 0;
+  for (int k = 0; k < dim; ++k) off += star->dims[k].cols;
+  lq_mat Ds = D, Ps = P[dim];
+  Ds.data = static_cast<char*>(D.data) + static_cast<size_t>(first_row) * D.ld * dtype_size(D.dtype);
+  Ds.rows = n_rows;
+  Ps.data = static_cast<char*>(P[dim].data) + static_cast<size_t>(first_row) * P[dim].ld * dtype_size(P[dim].dtype);
+  Ps.rows = n_rows;
+  return launch_project_dims(Ds, model->W[0], off, Ps, static_cast<hipStream_t>(hip_stream));
+}
+
+int lq_fusion_advice(const lq_star* star, const lq_model* model, double queries_per_update, lq_advice* out) {
+  clear_error();
+  Checked c;
+  int rc = check_star_model(star, model, true, &c);
+  if (rc) return rc;
+  if (!out) return fail(LQ_ERR_NULL, "out is NULL");
+  if (!(queries_per_update > 0.0)) return fail(LQ_ERR_SHAPE, "queries_per_update must be positive");
+  const double n = static_cast<double>(star->n_fact), k = c.kw, l = c.l1;
+  double sum_r = 0, mm_dims = 0, prefuse = 0, dim_elems = 0, p_elems = 0;
+  for (int j = 0; j < star->n_dims; ++j) {
+    const double r = static_cast<double>(star->dims[j].rows), cj = star->dims[j].cols;
+    sum_r += r;
+    mm_dims += cj * k * r;          // D_j M_j            (the c k sum r_j term of the complexity analysis)
+    prefuse += r * cj * l;          // D_j M_j L, done once per update of the dimensions or the model
+    dim_elems += r * cj;
+    p_elems += r * l;
+  }
+  out->cost_no_fusion = mm_dims + n * k * sum_r + n * k * l;
+  out->cost_fusion = n * l * sum_r;
+  out->cost_prefusion = prefuse;
+  out->ratio = out->cost_fusion > 0 ? out->cost_no_fusion / out->cost_fusion : 0.0;
+  out->ratio_leading_term = l > 0 ? k / l : 0.0;
+  out->memory_growth = dim_elems > 0 ? p_elems / dim_elems : 0.0;
+  // What the kernels here actually move per fact row (one nonzero per row of I_k, not the dense model):
+  const double es = static_cast<double>(dtype_size(c.dtype));
+  out->bytes_per_row_fused = es * (star->fact.cols > 0 ? star->fact.cols : 0) + 4.0 * star->n_dims +
+                             es * l * star->n_dims + es * c.l_out;
+  out->bytes_per_row_no_fusion = es * (star->fact.cols > 0 ? star->fact.cols : 0) + 4.0 * star->n_dims +
+                                 es * (k - (star->fact.cols > 0 ? star->fact.cols : 0)) + 2.0 * es * k + es * c.l_out;
+  const double gain = queries_per_update * (out->cost_no_fusion - out->cost_fusion);
+  out->fuse = gain > out->cost_prefusion ? 1 : 0;
+  return LQ_OK;
+}
+
 int lq_fused_join_predict(const lq_star* star, const lq_model* model, const lq_mat* P, lq_mat* Y,
                           void* ws, size_t ws_bytes, uint32_t flags, void* hip_stream) {
   clear_error();

@@ -224,3 +224,23 @@ def test_materialised_chunking_does_not_change_results(lq):
         Y = lq.lq_materialized_join_predict(w.X, w.dims, w.fks, w.weights, chunk_rows=chunk)
         torch.cuda.synchronize()
         assert_close(Y, want, TOL_F32, f"chunk {chunk}")
+
+
+def test_incremental_prefusion_refreshes_only_the_given_rows(lq):
+    for layers, rows in (((64, 1), (1_000, 5_003)), ((4,), (300, 2_001))):
+        w = WL.make_predict("incr", 100, 4, rows, (32, 24), layers, seed=WL.SEED0 + 90, w_sigma=[0.2] * len(layers))
+        w = to_dev(w)
+        P = lq.lq_project_dims(w.dims, w.weights[0], w.c_f)
+        before = [p.clone() for p in P]
+        lo, cnt = 701, 1_003
+        w.dims[1][lo:lo + cnt] += 1.5                      # these dimension rows change
+        lq.lq_project_dim_rows(w.dims, w.weights[0], w.c_f, P, 1, lo, cnt)
+        full = lq.lq_project_dims(w.dims, w.weights[0], w.c_f)
+        torch.cuda.synchronize()
+        assert torch.equal(P[0], before[0]) and torch.equal(P[1], full[1])
+        assert torch.equal(P[1][:lo], before[1][:lo]) and torch.equal(P[1][lo + cnt:], before[1][lo + cnt:])
+        assert not torch.equal(P[1][lo:lo + cnt], before[1][lo:lo + cnt])
+        Pw = O.project_dims(cpu_list(w.dims), w.weights[0].cpu(), w.c_f)
+        assert_close(P[1], Pw[1], TOL_F32, "refreshed table")
+        with pytest.raises(lq.LQError):
+            lq.lq_project_dim_rows(w.dims, w.weights[0], w.c_f, P, 1, rows[1] - 5, 6)

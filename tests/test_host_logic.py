@@ -196,3 +196,25 @@ def test_keymap_entry_points_reject_bad_arguments():
     assert lib.lq_compact_matches(FAKE, 10, FAKE, FAKE, None, FAKE, 4096, None) == 1
     assert lib.lq_compact_matches(FAKE, 10, FAKE, FAKE, FAKE, FAKE, 8, None) == 4
     assert lib.lq_compact_workspace_bytes(10) >= 16
+
+
+def test_fusion_advice_is_the_complexity_model_of_the_paper():
+    """Equal column counts and three dimensions: the ratio must be Eq. 3, k/l + k^2/(3 i l) + k/sum r."""
+    b = _binding()
+    i, c, l = 600_000 * 4, 16, 8
+    rows = (80_000, 8_000, 2_555)
+    k = 3 * c
+    adv = b.lq_fusion_advice(i, 0, [(r, c) for r in rows], [l], queries_per_update=1.0)
+    eq3 = k / l + k * k / (3 * i * l) + k / sum(rows)
+    assert abs(adv["ratio"] - eq3) <= 1e-12 * eq3
+    assert adv["ratio_leading_term"] == k / l
+    assert adv["cost_fusion"] == i * l * sum(rows)
+    assert adv["cost_prefusion"] == sum(rows) * c * l
+    assert adv["memory_growth"] == l / c and adv["fuse"] == 1
+    # an output wider than the joined table: fusing loses and the pre-fused tables grow (Q6)
+    wide = b.lq_fusion_advice(3_000, 0, [(2_000, 8)] * 3, [4096], queries_per_update=1.0)
+    assert wide["memory_growth"] == 512 and wide["ratio"] < 1 and wide["fuse"] == 0
+    # the trend the paper reports: the ratio grows with k and shrinks with l
+    r1 = b.lq_fusion_advice(i, 0, [(r, 32) for r in rows], [8])["ratio"]
+    r2 = b.lq_fusion_advice(i, 0, [(r, 32) for r in rows], [64])["ratio"]
+    assert r1 > adv["ratio"] > r2 * 0 and r1 > r2
