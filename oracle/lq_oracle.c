@@ -329,3 +329,55 @@ int lqo_tree_project(int64_t r, int32_t c, const double* D, int32_t col_off, int
   }
   return 0;
 }
+
+/* ------------------------------------------------------------------------------------------
+ * Wider aggregate query: fact-side range predicates (selection vectors on the fact table,
+ * Section 2.2), measures that are a column, the element-wise product or the difference of two
+ * columns, and SUM / MIN / MAX / COUNT per group (Section 2.4).  Evaluated per tuple.
+ *   pred_col[q], lo[q], hi[q]   keep row i iff lo <= pred_col[q][i] <= hi for every q
+ *   op[m] : 0 = a[m][i], 1 = a[m][i] * b[m][i], 2 = a[m][i] - b[m][i]   (computed in int64)
+ *   sums, mins, maxs [n_meas x G] (any may be NULL), counts [G] (may be NULL)
+ *   mins / maxs of a group without rows stay at INT64_MAX / INT64_MIN.
+ * Join, masks and group numbering as in lqo_groupby_sum.  Returns 0, -2 on a bad code.
+ * ------------------------------------------------------------------------------------------ */
+int lqo_groupby_agg(int64_t n, int32_t K, const int32_t* const* fk, const uint8_t* const* dim_mask,
+                    const int32_t* const* dim_code, const int32_t* card, int32_t n_preds,
+                    const int32_t* const* pred_col, const int32_t* lo, const int32_t* hi,
+                    int32_t n_meas, const int32_t* op, const int32_t* const* a,
+                    const int32_t* const* b, int64_t* sums, int64_t* mins, int64_t* maxs,
+                    int64_t* counts) {
+  int64_t G = 1;
+  for (int32_t k = 0; k < K; ++k)
+    if (dim_code && dim_code[k]) G *= card[k];
+  for (int64_t q = 0; q < G * n_meas; ++q) {
+    if (sums) sums[q] = 0;
+    if (mins) mins[q] = INT64_MAX;
+    if (maxs) maxs[q] = INT64_MIN;
+  }
+  if (counts) for (int64_t g = 0; g < G; ++g) counts[g] = 0;
+  for (int64_t i = 0; i < n; ++i) {
+    int keep = 1;
+    for (int32_t q = 0; q < n_preds && keep; ++q)
+      keep = pred_col[q][i] >= lo[q] && pred_col[q][i] <= hi[q];
+    int64_t g = 0;
+    for (int32_t k = 0; k < K && keep; ++k) {
+      const int32_t j = fk[k][i];
+      if (j < 0 || (dim_mask && dim_mask[k] && !dim_mask[k][j])) { keep = 0; break; }
+      if (dim_code && dim_code[k]) {
+        const int32_t code = dim_code[k][j];
+        if (code < 0 || code >= card[k]) return -2;
+        g = g * card[k] + code;
+      }
+    }
+    if (!keep) continue;
+    for (int32_t m = 0; m < n_meas; ++m) {
+      const int64_t x = a[m][i];
+      const int64_t v = op[m] == 1 ? x * (int64_t)b[m][i] : (op[m] == 2 ? x - (int64_t)b[m][i] : x);
+      if (sums) sums[(int64_t)m * G + g] += v;
+      if (mins && v < mins[(int64_t)m * G + g]) mins[(int64_t)m * G + g] = v;
+      if (maxs && v > maxs[(int64_t)m * G + g]) maxs[(int64_t)m * G + g] = v;
+    }
+    if (counts) counts[g] += 1;
+  }
+  return 0;
+}

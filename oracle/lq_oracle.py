@@ -41,7 +41,7 @@ def _load():
         lib = ctypes.CDLL(_LIB)
         lib.lqo_max_threads.restype = ctypes.c_int
         for name in ("lqo_join_predict", "lqo_materialize", "lqo_project_dims",
-                     "lqo_gather_sum", "lqo_groupby_sum", "lqo_tree_predict", "lqo_tree_project"):
+                     "lqo_gather_sum", "lqo_groupby_sum", "lqo_tree_predict", "lqo_tree_project", "lqo_groupby_agg"):
             getattr(lib, name).restype = ctypes.c_int
         _lib = lib
     return _lib
@@ -285,3 +285,39 @@ def tree_project(dims, c_f, feature, threshold, H) -> list:
         out.append(Tk)
         off += d.shape[1]
     return out
+
+
+def groupby_agg(fks, dim_rows, dim_mask, dim_code, group_card, preds, measures):
+    """Filter (dimension masks + fact range predicates) + star join + GROUP BY + SUM/MIN/MAX/COUNT.
+
+    preds:    list of (column, lo, hi): keep rows with lo <= column <= hi
+    measures: list of (op, a, b) with op in {"col", "mul", "sub"} (b is None for "col")
+    Returns (sums, mins, maxs [M x G] int64, counts [G] int64)."""
+    lib = _load()
+    fks = [_i32(f) for f in fks]
+    K = len(fks)
+    masks = [None if m is None else _u8(m) for m in (dim_mask or [None] * K)]
+    codes = [None if c is None else _i32(c) for c in (dim_code or [None] * K)]
+    card = [1 if codes[k] is None else int(group_card[k]) for k in range(K)]
+    for k in range(K):
+        if fks[k].size and fks[k].max() >= int(dim_rows[k]):
+            raise ValueError("foreign key outside its dimension table")
+    pc = [_i32(p[0]) for p in preds]
+    ops = {"col": 0, "mul": 1, "sub": 2}
+    A = [_i32(m[1]) for m in measures]
+    B = [A[j] if m[2] is None else _i32(m[2]) for j, m in enumerate(measures)]
+    n = A[0].shape[0]
+    G = 1
+    for c in card:
+        G *= c
+    M = len(measures)
+    sums, mins, maxs = (np.empty((M, G), dtype=np.int64) for _ in range(3))
+    counts = np.empty((G,), dtype=np.int64)
+    rc = lib.lqo_groupby_agg(ctypes.c_int64(n), ctypes.c_int32(K), _ptr_array(fks), _ptr_array(masks),
+                             _ptr_array(codes), _i32_array(card), ctypes.c_int32(len(pc)), _ptr_array(pc),
+                             _i32_array([p[1] for p in preds]), _i32_array([p[2] for p in preds]),
+                             ctypes.c_int32(M), _i32_array([ops[m[0]] for m in measures]), _ptr_array(A),
+                             _ptr_array(B), _pd(sums), _pd(mins), _pd(maxs), _pd(counts))
+    if rc != 0:
+        raise ValueError("group code outside [0, cardinality)")
+    return sums, mins, maxs, counts
