@@ -203,6 +203,32 @@ int lq_masked_groupby_sum(int64_t n_fact, int32_t n_dims, const int32_t* const* 
                           const int32_t* const* measures, int64_t* sums, int64_t* counts,
                           void* ws, size_t ws_bytes, uint32_t flags, void* hip_stream);
 
+/*
+ * The same aggregate with the rest of the query shapes of the benchmark's query groups: range
+ * predicates on fact columns (selection vectors on the fact table, Section 2.2), measures that are
+ * a column, the element-wise product or the difference of two columns (computed in int64), and
+ * SUM / MIN / MAX / COUNT per group.  AVG is sums / counts.  Arguments as for
+ * lq_masked_groupby_sum, plus:
+ *   preds     host array of n_preds (0..4) predicates: keep row i iff lo <= col[i] <= hi
+ *   measures  host array of n_measures (1..LQ_MAX_MEASURES) expressions over device int32 columns
+ *   sums, mins, maxs  int64 [n_measures x G], each may be NULL; groups without rows get 0,
+ *             INT64_MAX and INT64_MIN;  counts int64 [G] or NULL
+ *   G * (3 * n_measures + 1) <= 8192;  ws: lq_groupby_agg_workspace_bytes(..)
+ */
+typedef struct { const int32_t* col; int32_t lo; int32_t hi; } lq_range_pred;
+#define LQ_MEASURE_COL 0
+#define LQ_MEASURE_MUL 1
+#define LQ_MEASURE_SUB 2
+typedef struct { int32_t op; const int32_t* a; const int32_t* b; } lq_measure;
+int lq_groupby_agg(int64_t n_fact, int32_t n_dims, const int32_t* const* fks, const int64_t* dim_rows,
+                   const uint8_t* const* dim_mask, const int32_t* const* dim_code,
+                   const int32_t* group_card, int32_t n_preds, const lq_range_pred* preds,
+                   int32_t n_measures, const lq_measure* measures, int64_t* sums, int64_t* mins,
+                   int64_t* maxs, int64_t* counts, void* ws, size_t ws_bytes, uint32_t flags,
+                   void* hip_stream);
+size_t lq_groupby_agg_workspace_bytes(int32_t n_dims, const int64_t* dim_rows,
+                                      const int32_t* group_card, int32_t n_measures);
+
 /* Workspace sizes in bytes (0 on invalid arguments).  For the group-by, group_card[k] must be
  * 1 for dimensions that do not group (group_card may be NULL when none does); the size depends
  * on the number of compute units of the current device. */

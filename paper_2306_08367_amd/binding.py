@@ -42,6 +42,14 @@ class lq_star(ctypes.Structure):
                 ("dims", ctypes.POINTER(lq_mat)), ("fks", ctypes.POINTER(ctypes.c_void_p))]
 
 
+class lq_range_pred(ctypes.Structure):
+    _fields_ = [("col", ctypes.c_void_p), ("lo", ctypes.c_int32), ("hi", ctypes.c_int32)]
+
+
+class lq_measure(ctypes.Structure):
+    _fields_ = [("op", ctypes.c_int32), ("a", ctypes.c_void_p), ("b", ctypes.c_void_p)]
+
+
 class lq_advice(ctypes.Structure):
     _fields_ = [(n, ctypes.c_double) for n in ("cost_no_fusion", "cost_fusion", "cost_prefusion", "ratio",
                                                "ratio_leading_term", "memory_growth", "bytes_per_row_fused",
@@ -82,6 +90,12 @@ def _load():
     lib.lq_groupby_workspace_bytes.argtypes = [i32, ctypes.POINTER(i64), ctypes.POINTER(i32), i32]
     lib.lq_groupby_workspace_bytes.restype = sz
     lib.lq_stream_copy.argtypes = [vp, vp, sz, vp]
+    lib.lq_groupby_agg.argtypes = [i64, i32, ctypes.POINTER(vp), ctypes.POINTER(i64), ctypes.POINTER(vp),
+                                   ctypes.POINTER(vp), ctypes.POINTER(i32), i32, ctypes.POINTER(lq_range_pred),
+                                   i32, ctypes.POINTER(lq_measure), vp, vp, vp, vp, vp, sz, u32, vp]
+    lib.lq_groupby_agg.restype = ctypes.c_int
+    lib.lq_groupby_agg_workspace_bytes.argtypes = [i32, ctypes.POINTER(i64), ctypes.POINTER(i32), i32]
+    lib.lq_groupby_agg_workspace_bytes.restype = sz
     lib.lq_project_dim_rows.argtypes = [ps, pmod, pm, i32, i64, i64, vp]
     lib.lq_project_dim_rows.restype = ctypes.c_int
     lib.lq_fusion_advice.argtypes = [ps, pmod, ctypes.c_double, ctypes.POINTER(lq_advice)]
@@ -493,3 +507,50 @@ def lq_fusion_advice(n_fact: int, c_f: int, dim_shapes: Sequence[Sequence[int]],
     out = lq_advice()
     _check(_lib.lq_fusion_advice(ctypes.byref(star), ctypes.byref(model), float(queries_per_update), ctypes.byref(out)))
     return {n: getattr(out, n) for n, _ in lq_advice._fields_}
+
+
+# ---------------------------------------------------------------- wider aggregate query --------
+
+_MEASURE_OPS = {"col": 0, "mul": 1, "sub": 2}
+
+
+def lq_groupby_agg(fks: Sequence[torch.Tensor], dim_rows: Sequence[int], dim_mask, dim_code,
+                   group_card: Sequence[int], preds, measures, want=("sum", "min", "max", "count"),
+                   ws: Optional[torch.Tensor] = None, flags: int = 0, stream=None) -> dict:
+    """Filtered star join + GROUP BY with fact range predicates ``[(column, lo, hi)]``, measures
+    ``[(op, a, b)]`` (op in col / mul / sub) and SUM / MIN / MAX / COUNT.  Returns a dict of int64 tensors."""
+    K = len(fks)
+    n = int(measures[0][1].shape[0])
+    dev = measures[0][1].device
+    for f in fks:
+        _expect(f, torch.int32, "foreign-key column")
+    masks = list(dim_mask) if dim_mask is not None else [None] * K
+    codes = list(dim_code) if dim_code is not None else [None] * K
+    G = 1
+    for k in range(K):
+        if codes[k] is not None:
+            G *= int(group_card[k])
+    M = len(measures)
+    pa = (lq_range_pred * max(1, len(preds)))()
+    for q, (col, lo, hi) in enumerate(preds):
+        _expect(col, torch.int32, "predicate column")
+        pa[q] = lq_range_pred(col.data_ptr(), int(lo), int(hi))
+    ma = (lq_measure * M)()
+    for m, (op, a, b) in enumerate(measures):
+        _expect(a, torch.int32, "measure column")
+        if b is not None:
+            _expect(b, torch.int32, "measure column")
+        ma[m] = lq_measure(_MEASURE_OPS[op], a.data_ptr(), None if b is None else b.data_ptr())
+    out = {}
+    for name in ("sum", "min", "max"):
+        out[name] = torch.empty((M, G), dtype=torch.int64, device=dev) if name in want else None
+    out["count"] = torch.empty((G,), dtype=torch.int64, device=dev) if "count" in want else None
+    rows = (ctypes.c_int64 * max(1, K))(*[int(r) for r in dim_rows])
+    card = (ctypes.c_int32 * max(1, K))(*[int(c) for c in group_card])
+    if ws is None:
+        ws = torch.empty(int(_lib.lq_groupby_agg_workspace_bytes(K, rows, card, M)), dtype=torch.uint8, device=dev)
+    ptr = lambda t: None if t is None else t.data_ptr()
+    _check(_lib.lq_groupby_agg(n, K, _ptr_array(fks), rows, _ptr_array(masks), _ptr_array(codes), card,
+                               len(preds), pa, M, ma, ptr(out["sum"]), ptr(out["min"]), ptr(out["max"]),
+                               ptr(out["count"]), ws.data_ptr(), ws.numel(), flags, _stream(stream)))
+    return out

@@ -492,6 +492,123 @@ __global__ __launch_bounds__(FOLD_THREADS) void fold_kernel(GbArgs a, int rows_w
   }
 }
 
+
+// ---------------------------------------------------------------- wider aggregate ----------
+
+// Fact-side range predicates (selection vectors on the fact table), measures that are a column or
+// the element-wise product / difference of two columns, SUM / MIN / MAX / COUNT per group.
+constexpr int MAX_PREDS = 4;
+struct AggExtra {
+  int32_t n_preds;
+  const int32_t* pcol[MAX_PREDS];
+  int32_t lo[MAX_PREDS], hi[MAX_PREDS];
+  int32_t op[LQ_MAX_MEASURES];                 // 0 column, 1 product, 2 difference
+  const int32_t* b[LQ_MAX_MEASURES];
+  unsigned long long* mins;                    // caller arrays (may be NULL), int64 bit patterns
+  unsigned long long* maxs;
+};
+// Accumulator layout (LDS, partial rows): [sums M x G | counts G | mins M x G | maxs M x G].
+constexpr long long AGG_MIN_INIT = 0x7fffffffffffffffLL;
+constexpr long long AGG_MAX_INIT = -0x7fffffffffffffffLL - 1;
+
+__device__ __forceinline__ long long agg_init(int i, int M, int G) {
+  return i < (M + 1) * G ? 0LL : (i < (2 * M + 1) * G ? AGG_MIN_INIT : AGG_MAX_INIT);
+}
+
+template <bool LDS_TABLES, int VEC, int KMAX>
+__global__ __launch_bounds__(SCAN_THREADS) void agg_scan_kernel(GbArgs a, AggExtra x, int64_t per_block) {
+  extern __shared__ __align__(16) uint8_t smem[];
+  long long* acc = reinterpret_cast<long long*>(smem);
+  const int MG = a.M * a.G;
+  const int n_acc = (3 * a.M + 1) * a.G;
+  uint8_t* tab_lds = smem + round_up(static_cast<size_t>(n_acc) * 8, 16);
+  const int tid = threadIdx.x;
+  for (int i = tid; i < n_acc; i += SCAN_THREADS) acc[i] = agg_init(i, a.M, a.G);
+  if (LDS_TABLES) {
+    const uint4* src = reinterpret_cast<const uint4*>(a.packed);
+    uint4* dst = reinterpret_cast<uint4*>(tab_lds);
+    for (uint32_t i = tid; i < a.packed_bytes / 16; i += SCAN_THREADS) dst[i] = src[i];
+  }
+  __syncthreads();
+  const uint8_t* tab = LDS_TABLES ? tab_lds : a.packed;
+
+  // VEC rows starting at fact row i0 (rows >= a.n are skipped)
+  auto rows = [&](int64_t i0, int cnt) {
+    int32_t fk[VEC][KMAX];
+    bool pass[VEC];
+#pragma unroll
+    for (int q = 0; q < VEC; ++q) {
+      pass[q] = q < cnt;
+#pragma unroll
+      for (int k = 0; k < KMAX; ++k) fk[q][k] = (q < cnt && k < a.K) ? a.d[k].fk[i0 + q] : 0;
+    }
+    for (int pq = 0; pq < x.n_preds; ++pq)
+#pragma unroll
+      for (int q = 0; q < VEC; ++q)
+        if (q < cnt) {
+          const int32_t v = x.pcol[pq][i0 + q];
+          pass[q] = pass[q] && v >= x.lo[pq] && v <= x.hi[pq];
+        }
+    int32_t g[VEC];
+    classify<VEC, KMAX>(a, tab, fk, g);
+#pragma unroll
+    for (int q = 0; q < VEC; ++q) {
+      if (!pass[q] || g[q] < 0) continue;
+      for (int m = 0; m < a.M; ++m) {
+        const long long av = a.meas[m][i0 + q];
+        long long v = av;
+        if (x.op[m] == 1) v = av * static_cast<long long>(x.b[m][i0 + q]);
+        else if (x.op[m] == 2) v = av - static_cast<long long>(x.b[m][i0 + q]);
+        atomicAdd(reinterpret_cast<unsigned long long*>(&acc[m * a.G + g[q]]), static_cast<unsigned long long>(v));
+        atomicMin(&acc[(a.M + 1) * a.G + m * a.G + g[q]], v);
+        atomicMax(&acc[(2 * a.M + 1) * a.G + m * a.G + g[q]], v);
+      }
+      atomicAdd(reinterpret_cast<unsigned long long*>(&acc[MG + g[q]]), 1ull);
+    }
+  };
+
+  const int64_t n_vec = (a.n + VEC - 1) / VEC;
+  const int64_t v_begin = static_cast<int64_t>(blockIdx.x) * per_block;
+  const int64_t v_end = min(n_vec, v_begin + per_block);
+  for (int64_t v = v_begin + tid; v < v_end; v += SCAN_THREADS) {
+    const int64_t i0 = v * VEC;
+    rows(i0, static_cast<int>(min<int64_t>(VEC, a.n - i0)));
+  }
+  __syncthreads();
+  long long* mine = reinterpret_cast<long long*>(a.partial) + static_cast<size_t>(blockIdx.x) * n_acc;
+  for (int i = tid; i < n_acc; i += SCAN_THREADS) mine[i] = acc[i];
+}
+
+// Fold of the wider aggregate: add, min or max depending on the segment the accumulator is in.
+__global__ __launch_bounds__(FOLD_THREADS) void fold_agg_kernel(GbArgs a, AggExtra x, int rows_written) {
+  __shared__ long long part[FOLD_PARTS][FOLD_ACCS];
+  const int n_acc = (3 * a.M + 1) * a.G;
+  const int il = threadIdx.x % FOLD_ACCS, p = threadIdx.x / FOLD_ACCS;
+  const int i = blockIdx.x * FOLD_ACCS + il;
+  const int seg = i < (a.M + 1) * a.G ? 0 : (i < (2 * a.M + 1) * a.G ? 1 : 2);
+  long long t = i < n_acc ? agg_init(i, a.M, a.G) : 0;
+  const long long* partial = reinterpret_cast<const long long*>(a.partial);
+  if (i < n_acc)
+    for (int b = p; b < rows_written; b += FOLD_PARTS) {
+      const long long v = partial[static_cast<size_t>(b) * n_acc + i];
+      t = seg == 0 ? t + v : (seg == 1 ? min(t, v) : max(t, v));
+    }
+  part[p][il] = t;
+  __syncthreads();
+  if (threadIdx.x < FOLD_ACCS && i < n_acc) {
+    long long tot = part[0][il];
+    for (int q = 1; q < FOLD_PARTS; ++q) {
+      const long long v = part[q][il];
+      tot = seg == 0 ? tot + v : (seg == 1 ? min(tot, v) : max(tot, v));
+    }
+    const int MG = a.M * a.G;
+    if (i < MG) { if (a.sums) a.sums[i] = static_cast<unsigned long long>(tot); }
+    else if (i < MG + a.G) { if (a.counts) a.counts[i - MG] = static_cast<unsigned long long>(tot); }
+    else if (i < 2 * MG + a.G) { if (x.mins) x.mins[i - MG - a.G] = static_cast<unsigned long long>(tot); }
+    else if (x.maxs) x.maxs[i - 2 * MG - a.G] = static_cast<unsigned long long>(tot);
+  }
+}
+
 constexpr size_t LDS_BUDGET = 160 * 1024 - 1024;   // gfx950 workgroups may use the whole 160 KB
 
 // Fills kind / off / bytes of every dimension; returns the packed size.  Tables are laid out by
@@ -680,6 +797,88 @@ int launch_groupby(int64_t n, int32_t K, const int32_t* const* fks, const int64_
   LQ_LAUNCH_CHECK("scan_kernel");
   hipLaunchKernelGGL(fold_kernel, dim3(fold_blocks), dim3(FOLD_THREADS), 0, s, a, static_cast<int>(blocks));
   LQ_LAUNCH_CHECK("fold_kernel");
+  return LQ_OK;
+}
+
+
+int launch_groupby_agg(int64_t n, int32_t K, const int32_t* const* fks, const int64_t* rows,
+                       const uint8_t* const* mask, const int32_t* const* code, const int32_t* card,
+                       int32_t n_preds, const lq_range_pred* preds, int32_t M, const lq_measure* meas,
+                       int64_t* sums, int64_t* mins, int64_t* maxs, int64_t* counts, int32_t G, void* ws,
+                       hipStream_t s) {
+  GbArgs a{};
+  AggExtra x{};
+  a.n = n; a.K = K; a.fact_mask = nullptr; a.M = M; a.G = G;
+  a.sums = reinterpret_cast<unsigned long long*>(sums);
+  a.counts = reinterpret_cast<unsigned long long*>(counts);
+  x.mins = reinterpret_cast<unsigned long long*>(mins);
+  x.maxs = reinterpret_cast<unsigned long long*>(maxs);
+  a.packed = static_cast<uint8_t*>(ws);
+  a.partial = reinterpret_cast<unsigned long long*>(a.packed + groupby_tables_bytes(K, rows));
+  bool vec_ok = true;
+  for (int k = 0; k < K; ++k) {
+    a.d[k].fk = fks[k];
+    a.d[k].mask = mask ? mask[k] : nullptr;
+    a.d[k].code = code ? code[k] : nullptr;
+    a.d[k].rows = rows[k];
+    a.d[k].card = (code && code[k]) ? card[k] : 1;
+  }
+  {
+    int32_t stride = 1;
+    for (int k = K - 1; k >= 0; --k) {
+      const bool grouping = code && code[k];
+      a.d[k].stride = grouping ? stride : 0;
+      if (grouping) stride *= card[k];
+    }
+  }
+  x.n_preds = n_preds;
+  for (int q = 0; q < n_preds; ++q) { x.pcol[q] = preds[q].col; x.lo[q] = preds[q].lo; x.hi[q] = preds[q].hi; }
+  for (int m = 0; m < M; ++m) { a.meas[m] = meas[m].a; x.op[m] = meas[m].op; x.b[m] = meas[m].b ? meas[m].b : meas[m].a; }
+  (void)vec_ok;
+  const int n_acc = (3 * M + 1) * G;
+  const size_t acc_bytes = round_up(static_cast<size_t>(n_acc) * 8, 16);
+  size_t lds_prefix = 0;
+  const size_t packed = plan_tables(K, rows, mask, code, card, a.d, LDS_BUDGET - acc_bytes, &lds_prefix);
+  if (packed > 0xffffffffull) return fail(LQ_ERR_UNSUPPORTED, "group-by: dimension side tables exceed 4 GiB");
+  a.packed_bytes = static_cast<uint32_t>(packed);
+  const int cus = num_cus();
+  {
+    size_t work = 1;
+    for (int k = 0; k < K; ++k) {
+      const size_t w = a.d[k].kind == DK_BITMAP ? static_cast<size_t>(a.d[k].bytes) * 8 : static_cast<size_t>(a.d[k].bytes) / 4;
+      work = std::max(work, w);
+    }
+    const int64_t blocks = std::min<int64_t>(static_cast<int64_t>((work + 255) / 256), cus * 8);
+    hipLaunchKernelGGL(pack_kernel, dim3(static_cast<unsigned>(std::max<int64_t>(blocks, 1))), dim3(256), 0, s, a);
+    LQ_LAUNCH_CHECK("pack_kernel");
+  }
+  const unsigned fold_blocks = static_cast<unsigned>((n_acc + FOLD_ACCS - 1) / FOLD_ACCS);
+  unsigned blocks = 0;
+  if (n > 0) {
+    constexpr int VEC = 4;
+    const bool lds_tables = lds_prefix == packed;
+    const size_t lds = acc_bytes + (lds_tables ? packed : 0);
+    const int per_cu = lds * 2 <= 160 * 1024 ? 2 : 1;
+    const int64_t n_vec = (n + VEC - 1) / VEC;
+    int64_t b = std::max<int64_t>(1, std::min<int64_t>((n_vec + SCAN_THREADS - 1) / SCAN_THREADS, static_cast<int64_t>(cus) * per_cu));
+    b = std::min<int64_t>(b, groupby_max_workgroups());
+    int64_t pb = (n_vec + b - 1) / b;
+    pb = std::max<int64_t>(SCAN_THREADS, (pb + SCAN_THREADS - 1) / SCAN_THREADS * SCAN_THREADS);
+    b = std::max<int64_t>(1, (n_vec + pb - 1) / pb);
+    blocks = static_cast<unsigned>(b);
+#define LQ_AGG(LT)                                                                               \
+  do {                                                                                           \
+    if (lds > 64 * 1024)                                                                         \
+      LQ_HIP_TRY(hipFuncSetAttribute(reinterpret_cast<const void*>(&agg_scan_kernel<LT, 4, 8>),  \
+                                     hipFuncAttributeMaxDynamicSharedMemorySize, static_cast<int>(lds))); \
+    hipLaunchKernelGGL((agg_scan_kernel<LT, 4, 8>), dim3(blocks), dim3(SCAN_THREADS), lds, s, a, x, pb); \
+  } while (0)
+    if (lds_tables) LQ_AGG(true); else LQ_AGG(false);
+#undef LQ_AGG
+    LQ_LAUNCH_CHECK("agg_scan_kernel");
+  }
+  hipLaunchKernelGGL(fold_agg_kernel, dim3(fold_blocks), dim3(FOLD_THREADS), 0, s, a, x, static_cast<int>(blocks));
+  LQ_LAUNCH_CHECK("fold_agg_kernel");
   return LQ_OK;
 }
 

@@ -38,6 +38,11 @@ int launch_groupby(int64_t n, int32_t K, const int32_t* const* fks, const int64_
                    const uint8_t* fact_mask, int32_t M, const int32_t* const* meas, int64_t* sums,
                    int64_t* counts, int32_t G, void* ws, hipStream_t s);
 size_t groupby_ws_bytes(int32_t K, const int64_t* rows, int64_t n_acc);
+int launch_groupby_agg(int64_t n, int32_t K, const int32_t* const* fks, const int64_t* rows,
+                       const uint8_t* const* mask, const int32_t* const* code, const int32_t* card,
+                       int32_t n_preds, const lq_range_pred* preds, int32_t M, const lq_measure* meas,
+                       int64_t* sums, int64_t* mins, int64_t* maxs, int64_t* counts, int32_t G, void* ws,
+                       hipStream_t s);
 
 namespace {
 
@@ -431,6 +436,69 @@ int lq_masked_groupby_sum(int64_t n_fact, int32_t n_dims, const int32_t* const* 
     if ((rc = run_fk_check(n_fact, n_dims, fks, dim_rows, true, ws, ws_bytes, s))) return rc;
   return launch_groupby(n_fact, n_dims, fks, dim_rows, dim_mask, dim_code, group_card, fact_mask,
                         n_measures, measures, sums, counts, static_cast<int32_t>(G), ws, s);
+}
+
+size_t lq_groupby_agg_workspace_bytes(int32_t n_dims, const int64_t* dim_rows, const int32_t* group_card,
+                                      int32_t n_measures) {
+  if (n_dims < 0 || n_dims > LQ_MAX_DIMS || (n_dims > 0 && !dim_rows)) return 0;
+  if (n_measures < 1 || n_measures > LQ_MAX_MEASURES) return 0;
+  int64_t G = 1;
+  for (int k = 0; k < n_dims; ++k) {
+    if (dim_rows[k] < 0) return 0;
+    if (group_card) {
+      if (group_card[k] < 1 || group_card[k] > 65535) return 0;
+      G *= group_card[k];
+      if (G > 8192) return 0;
+    }
+  }
+  return groupby_ws_bytes(n_dims, dim_rows, G * (3 * n_measures + 1));
+}
+
+int lq_groupby_agg(int64_t n_fact, int32_t n_dims, const int32_t* const* fks, const int64_t* dim_rows,
+                   const uint8_t* const* dim_mask, const int32_t* const* dim_code, const int32_t* group_card,
+                   int32_t n_preds, const lq_range_pred* preds, int32_t n_measures, const lq_measure* measures,
+                   int64_t* sums, int64_t* mins, int64_t* maxs, int64_t* counts, void* ws, size_t ws_bytes,
+                   uint32_t flags, void* hip_stream) {
+  clear_error();
+  if (n_fact < 0) return fail(LQ_ERR_SHAPE, "n_fact < 0");
+  if (n_dims < 0 || n_dims > LQ_MAX_DIMS) return fail(LQ_ERR_SHAPE, "n_dims %d outside 0..%d", n_dims, LQ_MAX_DIMS);
+  if (n_measures < 1 || n_measures > LQ_MAX_MEASURES) return fail(LQ_ERR_SHAPE, "n_measures %d outside 1..%d", n_measures, LQ_MAX_MEASURES);
+  if (n_preds < 0 || n_preds > 4) return fail(LQ_ERR_SHAPE, "n_preds %d outside 0..4", n_preds);
+  if (n_dims > 0 && (!fks || !dim_rows)) return fail(LQ_ERR_NULL, "fks or dim_rows is NULL");
+  if (!measures || (n_preds > 0 && !preds)) return fail(LQ_ERR_NULL, "measures or preds is NULL");
+  if (!sums && !mins && !maxs && !counts) return fail(LQ_ERR_NULL, "no output requested");
+  if (!aligned(sums, 8) || !aligned(mins, 8) || !aligned(maxs, 8) || !aligned(counts, 8))
+    return fail(LQ_ERR_SHAPE, "outputs are not 8-byte aligned");
+  int64_t G = 1;
+  for (int k = 0; k < n_dims; ++k) {
+    if (n_fact > 0 && !fks[k]) return fail(LQ_ERR_NULL, "fks[%d] is NULL", k);
+    if (!aligned(fks[k], 4)) return fail(LQ_ERR_SHAPE, "fks[%d] is not 4-byte aligned", k);
+    if (dim_rows[k] < 0 || dim_rows[k] > 0x7fffffffLL) return fail(LQ_ERR_SHAPE, "dim_rows[%d] out of range", k);
+    if (dim_code && dim_code[k]) {
+      if (!group_card) return fail(LQ_ERR_NULL, "group_card is NULL");
+      if (group_card[k] < 1 || group_card[k] > 65535) return fail(LQ_ERR_SHAPE, "group_card[%d] outside 1..65535", k);
+      G *= group_card[k];
+      if (G > 8192) return fail(LQ_ERR_UNSUPPORTED, "more than 8192 groups");
+    }
+    if (dim_rows[k] == 0 && n_fact > 0 && ((dim_code && dim_code[k]) || (dim_mask && dim_mask[k])))
+      return fail(LQ_ERR_SHAPE, "dimension %d has no rows", k);
+  }
+  if (G * (3 * n_measures + 1) > 8192) return fail(LQ_ERR_UNSUPPORTED, "groups x (3 measures + 1) exceeds 8192");
+  for (int m = 0; m < n_measures; ++m) {
+    if (measures[m].op < 0 || measures[m].op > 2) return fail(LQ_ERR_SHAPE, "measures[%d].op is unknown", m);
+    if (n_fact > 0 && (!measures[m].a || (measures[m].op != 0 && !measures[m].b))) return fail(LQ_ERR_NULL, "measures[%d] lacks a column", m);
+    if (!aligned(measures[m].a, 4) || !aligned(measures[m].b, 4)) return fail(LQ_ERR_SHAPE, "measures[%d] is misaligned", m);
+  }
+  for (int q = 0; q < n_preds; ++q)
+    if ((n_fact > 0 && !preds[q].col) || !aligned(preds[q].col, 4)) return fail(LQ_ERR_NULL, "preds[%d].col is NULL or misaligned", q);
+  const size_t need = groupby_ws_bytes(n_dims, dim_rows, G * (3 * n_measures + 1));
+  if (!ws || !aligned(ws, 256) || ws_bytes < need) return fail(LQ_ERR_WORKSPACE, "aggregate needs a 256-byte aligned workspace of %zu bytes", need);
+  hipStream_t s = static_cast<hipStream_t>(hip_stream);
+  int rc;
+  if ((flags & LQ_CHECK_FKS) && n_dims > 0 && n_fact > 0)
+    if ((rc = run_fk_check(n_fact, n_dims, fks, dim_rows, true, ws, ws_bytes, s))) return rc;
+  return launch_groupby_agg(n_fact, n_dims, fks, dim_rows, dim_mask, dim_code, group_card, n_preds, preds,
+                            n_measures, measures, sums, mins, maxs, counts, static_cast<int32_t>(G), ws, s);
 }
 
 int lq_stream_copy(void* dst, const void* src, size_t bytes, void* hip_stream) {

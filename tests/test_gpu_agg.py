@@ -1,0 +1,79 @@
+"""GPU parity of the wider aggregate query (fact range predicates, product / difference measures,
+SUM / MIN / MAX / COUNT) against the oracle: bit-exact."""
+import numpy as np
+import pytest
+import torch
+
+from oracle import lq_oracle as O
+
+pytestmark = pytest.mark.gpu
+
+
+@pytest.fixture(scope="module")
+def lq():
+    import paper_2306_08367_amd as lq
+    return lq
+
+
+def _case(seed, n, rows, card, big=False):
+    r = np.random.default_rng(seed)
+    K = len(rows)
+    fks = [r.integers(0, a, size=n).astype(np.int32) for a in rows]
+    if n:
+        fks[-1][r.integers(0, n, size=max(1, n // 97))] = -1
+    codes = [r.integers(0, card[k], size=rows[k]).astype(np.int32) if card[k] > 1 else None for k in range(K)]
+    masks = [None] + [(r.random(rows[k]) < 0.6).astype(np.uint8) for k in range(1, K)]
+    hi = 2**31 - 1 if big else 100_000
+    cols = {"price": r.integers(-hi if big else 1, hi, size=n).astype(np.int32), "disc": r.integers(0, 11, size=n).astype(np.int32),
+            "qty": r.integers(1, 51, size=n).astype(np.int32), "cost": r.integers(-hi if big else 1, hi, size=n).astype(np.int32)}
+    return fks, list(rows), masks, codes, list(card), cols
+
+
+def _check(lq, fks, rows, masks, codes, card, preds, meas):
+    want = O.groupby_agg(fks, rows, masks, codes, card, preds, meas)
+    dev = lambda a: None if a is None else torch.from_numpy(a).cuda()
+    got = lq.lq_groupby_agg([dev(f) for f in fks], rows, [dev(m) for m in masks], [dev(c) for c in codes], card,
+                            [(dev(c), lo, hi) for c, lo, hi in preds], [(op, dev(a), dev(b)) for op, a, b in meas])
+    torch.cuda.synchronize()
+    for name, w in zip(("sum", "min", "max", "count"), want):
+        np.testing.assert_array_equal(got[name].cpu().numpy(), w, err_msg=name)
+    return want
+
+
+@pytest.mark.parametrize("n", [0, 1, 5, 1_023, 4_099, 300_001])
+def test_product_and_difference_measures_with_fact_predicates(lq, n):
+    fks, rows, masks, codes, card, c = _case(n + 1, n, (7, 40, 13), (7, 5, 1))
+    preds = [(c["disc"], 1, 3), (c["qty"], 1, 24)]
+    meas = [("mul", c["price"], c["disc"]), ("sub", c["price"], c["cost"]), ("col", c["qty"], None)]
+    _check(lq, fks, rows, masks, codes, card, preds, meas)
+
+
+def test_single_join_no_grouping_shape(lq):
+    """One join, fact predicates, SUM of a product, no GROUP BY (the shape of the benchmark's group 1)."""
+    fks, rows, masks, codes, card, c = _case(50, 500_003, (2_556,), (1,))
+    masks = [(np.arange(2_556) % 7 == 3).astype(np.uint8)]
+    want = _check(lq, fks, rows, masks, [None], [1], [(c["disc"], 1, 3), (c["qty"], 1, 24)], [("mul", c["price"], c["disc"])])
+    assert want[3][0] > 1_000
+
+
+def test_four_joins_difference_measure_shape(lq):
+    """Four joins, two masks, GROUP BY two dimensions, SUM(a - b) (the shape of the benchmark's group 4)."""
+    fks, rows, masks, codes, card, c = _case(51, 400_001, (2_556, 30_000, 2_000, 200_000), (7, 25, 1, 1))
+    _check(lq, fks, rows, masks, codes, card, [], [("sub", c["price"], c["cost"])])
+
+
+def test_full_range_int32_values_do_not_wrap(lq):
+    fks, rows, masks, codes, card, c = _case(52, 50_001, (5, 9), (5, 3), big=True)
+    _check(lq, fks, rows, masks, codes, card, [(c["disc"], 0, 10)], [("mul", c["price"], c["cost"]), ("sub", c["price"], c["cost"])])
+
+
+def test_tables_too_large_for_lds_and_optional_outputs(lq):
+    fks, rows, masks, codes, card, c = _case(53, 200_003, (300_000, 250_000), (4, 3))
+    want = O.groupby_agg(fks, rows, masks, codes, card, [], [("col", c["price"], None)])
+    dev = lambda a: None if a is None else torch.from_numpy(a).cuda()
+    got = lq.lq_groupby_agg([dev(f) for f in fks], rows, [dev(m) for m in masks], [dev(x) for x in codes], card, [],
+                            [("col", dev(c["price"]), None)], want=("sum", "count"))
+    torch.cuda.synchronize()
+    assert got["min"] is None and got["max"] is None
+    np.testing.assert_array_equal(got["sum"].cpu().numpy(), want[0])
+    np.testing.assert_array_equal(got["count"].cpu().numpy(), want[3])
