@@ -67,7 +67,7 @@ def main():
     ap.add_argument("--rows", type=int, default=10_000_000, help="fact rows of the headline workload")
     ap.add_argument("--no-extras", action="store_true", help="skip materialised / group-by / skewed legs")
     ap.add_argument("--no-cpu", action="store_true", help="skip the CPU oracle baseline")
-    ap.add_argument("--only", default="", help="run a single leg for profiling: fused|groupby|groupby16|c4|c5|tree|keymap|materialized|copy")
+    ap.add_argument("--only", default="", help="run a single leg for profiling: fused|groupby|groupby16|c4|c5|tree|keymap|agg|materialized|copy")
     args = ap.parse_args()
     if args.gpus != 1:
         sys.exit("bench.py: this build is single-GPU by design (no collectives, no sharding); "
@@ -310,6 +310,22 @@ def main():
         out["keymap_ssb_sf1"] = {"fact_rows": nk, "rows_per_s_all_4_columns": nk / (tot_ms * 1e-3), "per_dimension": res,
                                  "roofline": {"bound": "hbm", "achieved": gbps, "peak": HBM_PEAK_GBPS, "unit": "GB/s",
                                               "frac": gbps / HBM_PEAK_GBPS, "algorithmic_bytes_per_row": 8}}
+
+    # ---------------------------------------------------------------- wider aggregate (1 join, fact predicates, SUM(a*b))
+    if (args.only == "" and not args.no_extras) or args.only == "agg":
+        na = 6_000_000
+        gen = torch.Generator(device=dev); gen.manual_seed(WL.SEED0 + 950)
+        ri = lambda lo, hi: torch.randint(lo, hi, (na,), generator=gen, device=dev, dtype=torch.int32)
+        fk = ri(0, 2_556)
+        price, disc, qty = ri(1, 100_001), ri(0, 11), ri(1, 51)
+        dmask = (torch.arange(2_556, device=dev) % 7 == 3).to(torch.uint8)
+        call = lambda: lq.lq_groupby_agg([fk], [2_556], [dmask], [None], [1], [(disc, 1, 3), (qty, 1, 24)],
+                                         [("mul", price, disc)], want=("sum", "count"))
+        ms, mn, _ = time_call(call, 20, 3)
+        gbps = 16.0 * na / (ms * 1e-3) / 1e9
+        out["agg_one_join"] = {"rows_per_s": na / (ms * 1e-3), "ms": ms, "fact_rows": na,
+                               "roofline": {"bound": "hbm", "achieved": gbps, "peak": HBM_PEAK_GBPS, "unit": "GB/s",
+                                            "frac": gbps / HBM_PEAK_GBPS, "algorithmic_bytes_per_row": 16}}
 
     print(json.dumps(out))
 

@@ -516,7 +516,7 @@ __device__ __forceinline__ long long agg_init(int i, int M, int G) {
 }
 
 template <bool LDS_TABLES, int VEC, int KMAX>
-__global__ __launch_bounds__(SCAN_THREADS) void agg_scan_kernel(GbArgs a, AggExtra x, int64_t per_block) {
+__global__ __launch_bounds__(SCAN_THREADS) void agg_scan_kernel(GbArgs a, AggExtra x, int64_t per_block, int vec_ok) {
   extern __shared__ __align__(16) uint8_t smem[];
   long long* acc = reinterpret_cast<long long*>(smem);
   const int MG = a.M * a.G;
@@ -532,39 +532,60 @@ __global__ __launch_bounds__(SCAN_THREADS) void agg_scan_kernel(GbArgs a, AggExt
   __syncthreads();
   const uint8_t* tab = LDS_TABLES ? tab_lds : a.packed;
 
+  // VEC consecutive values of a column starting at row i0 (16-byte load when the column allows it)
+  auto load4 = [&](const int32_t* col, int64_t i0, int cnt, int32_t (&out)[VEC]) {
+    if (vec_ok && cnt == VEC) {
+      const v4i t = *reinterpret_cast<const v4i*>(col + i0);
+#pragma unroll
+      for (int q = 0; q < VEC; ++q) out[q] = t[q];
+    } else {
+#pragma unroll
+      for (int q = 0; q < VEC; ++q) out[q] = q < cnt ? col[i0 + q] : 0;
+    }
+  };
   // VEC rows starting at fact row i0 (rows >= a.n are skipped)
   auto rows = [&](int64_t i0, int cnt) {
     int32_t fk[VEC][KMAX];
     bool pass[VEC];
 #pragma unroll
-    for (int q = 0; q < VEC; ++q) {
-      pass[q] = q < cnt;
+    for (int q = 0; q < VEC; ++q) pass[q] = q < cnt;
 #pragma unroll
-      for (int k = 0; k < KMAX; ++k) fk[q][k] = (q < cnt && k < a.K) ? a.d[k].fk[i0 + q] : 0;
+    for (int k = 0; k < KMAX; ++k) {
+      int32_t t[VEC] = {0, 0, 0, 0};
+      if (k < a.K) load4(a.d[k].fk, i0, cnt, t);
+#pragma unroll
+      for (int q = 0; q < VEC; ++q) fk[q][k] = t[q];
     }
-    for (int pq = 0; pq < x.n_preds; ++pq)
+    for (int pq = 0; pq < x.n_preds; ++pq) {
+      int32_t t[VEC];
+      load4(x.pcol[pq], i0, cnt, t);
 #pragma unroll
-      for (int q = 0; q < VEC; ++q)
-        if (q < cnt) {
-          const int32_t v = x.pcol[pq][i0 + q];
-          pass[q] = pass[q] && v >= x.lo[pq] && v <= x.hi[pq];
-        }
+      for (int q = 0; q < VEC; ++q) pass[q] = pass[q] && t[q] >= x.lo[pq] && t[q] <= x.hi[pq];
+    }
     int32_t g[VEC];
     classify<VEC, KMAX>(a, tab, fk, g);
+    bool any = false;
 #pragma unroll
-    for (int q = 0; q < VEC; ++q) {
-      if (!pass[q] || g[q] < 0) continue;
-      for (int m = 0; m < a.M; ++m) {
-        const long long av = a.meas[m][i0 + q];
-        long long v = av;
-        if (x.op[m] == 1) v = av * static_cast<long long>(x.b[m][i0 + q]);
-        else if (x.op[m] == 2) v = av - static_cast<long long>(x.b[m][i0 + q]);
+    for (int q = 0; q < VEC; ++q) { pass[q] = pass[q] && g[q] >= 0; any = any || pass[q]; }
+    if (!any) return;            // measure columns are only touched where a row survives
+    for (int m = 0; m < a.M; ++m) {
+      int32_t av[VEC], bv[VEC];
+      load4(a.meas[m], i0, cnt, av);
+      if (x.op[m] != 0) load4(x.b[m], i0, cnt, bv);
+#pragma unroll
+      for (int q = 0; q < VEC; ++q) {
+        if (!pass[q]) continue;
+        long long v = av[q];
+        if (x.op[m] == 1) v *= static_cast<long long>(bv[q]);
+        else if (x.op[m] == 2) v -= static_cast<long long>(bv[q]);
         atomicAdd(reinterpret_cast<unsigned long long*>(&acc[m * a.G + g[q]]), static_cast<unsigned long long>(v));
         atomicMin(&acc[(a.M + 1) * a.G + m * a.G + g[q]], v);
         atomicMax(&acc[(2 * a.M + 1) * a.G + m * a.G + g[q]], v);
       }
-      atomicAdd(reinterpret_cast<unsigned long long*>(&acc[MG + g[q]]), 1ull);
     }
+#pragma unroll
+    for (int q = 0; q < VEC; ++q)
+      if (pass[q]) atomicAdd(reinterpret_cast<unsigned long long*>(&acc[MG + g[q]]), 1ull);
   };
 
   const int64_t n_vec = (a.n + VEC - 1) / VEC;
@@ -832,9 +853,12 @@ int launch_groupby_agg(int64_t n, int32_t K, const int32_t* const* fks, const in
     }
   }
   x.n_preds = n_preds;
-  for (int q = 0; q < n_preds; ++q) { x.pcol[q] = preds[q].col; x.lo[q] = preds[q].lo; x.hi[q] = preds[q].hi; }
-  for (int m = 0; m < M; ++m) { a.meas[m] = meas[m].a; x.op[m] = meas[m].op; x.b[m] = meas[m].b ? meas[m].b : meas[m].a; }
-  (void)vec_ok;
+  for (int k = 0; k < K; ++k) vec_ok = vec_ok && aligned(fks[k], 16);
+  for (int q = 0; q < n_preds; ++q) { x.pcol[q] = preds[q].col; x.lo[q] = preds[q].lo; x.hi[q] = preds[q].hi; vec_ok = vec_ok && aligned(preds[q].col, 16); }
+  for (int m = 0; m < M; ++m) {
+    a.meas[m] = meas[m].a; x.op[m] = meas[m].op; x.b[m] = meas[m].b ? meas[m].b : meas[m].a;
+    vec_ok = vec_ok && aligned(a.meas[m], 16) && aligned(x.b[m], 16);
+  }
   const int n_acc = (3 * M + 1) * G;
   const size_t acc_bytes = round_up(static_cast<size_t>(n_acc) * 8, 16);
   size_t lds_prefix = 0;
@@ -866,14 +890,16 @@ int launch_groupby_agg(int64_t n, int32_t K, const int32_t* const* fks, const in
     pb = std::max<int64_t>(SCAN_THREADS, (pb + SCAN_THREADS - 1) / SCAN_THREADS * SCAN_THREADS);
     b = std::max<int64_t>(1, (n_vec + pb - 1) / pb);
     blocks = static_cast<unsigned>(b);
-#define LQ_AGG(LT)                                                                               \
+#define LQ_AGG(LT, KM)                                                                           \
   do {                                                                                           \
     if (lds > 64 * 1024)                                                                         \
-      LQ_HIP_TRY(hipFuncSetAttribute(reinterpret_cast<const void*>(&agg_scan_kernel<LT, 4, 8>),  \
+      LQ_HIP_TRY(hipFuncSetAttribute(reinterpret_cast<const void*>(&agg_scan_kernel<LT, 4, KM>), \
                                      hipFuncAttributeMaxDynamicSharedMemorySize, static_cast<int>(lds))); \
-    hipLaunchKernelGGL((agg_scan_kernel<LT, 4, 8>), dim3(blocks), dim3(SCAN_THREADS), lds, s, a, x, pb); \
+    hipLaunchKernelGGL((agg_scan_kernel<LT, 4, KM>), dim3(blocks), dim3(SCAN_THREADS), lds, s, a, x, pb, \
+                       vec_ok ? 1 : 0);                                                          \
   } while (0)
-    if (lds_tables) LQ_AGG(true); else LQ_AGG(false);
+    if (lds_tables) { if (K <= 2) LQ_AGG(true, 2); else if (K <= 4) LQ_AGG(true, 4); else LQ_AGG(true, 8); }
+    else            { if (K <= 2) LQ_AGG(false, 2); else if (K <= 4) LQ_AGG(false, 4); else LQ_AGG(false, 8); }
 #undef LQ_AGG
     LQ_LAUNCH_CHECK("agg_scan_kernel");
   }

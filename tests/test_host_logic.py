@@ -218,3 +218,29 @@ def test_fusion_advice_is_the_complexity_model_of_the_paper():
     r1 = b.lq_fusion_advice(i, 0, [(r, 32) for r in rows], [8])["ratio"]
     r2 = b.lq_fusion_advice(i, 0, [(r, 32) for r in rows], [64])["ratio"]
     assert r1 > adv["ratio"] > r2 * 0 and r1 > r2
+
+
+def test_groupby_agg_rejects_bad_arguments():
+    b = _binding()
+    lib = b._lib
+    vp, i64, i32 = ctypes.c_void_p, ctypes.c_int64, ctypes.c_int32
+    fks = (vp * 1)(FAKE)
+    rows = (i64 * 1)(10)
+    card = (i32 * 1)(5)
+    codes = (vp * 1)(FAKE)
+    preds = (b.lq_range_pred * 1)(b.lq_range_pred(FAKE, 0, 3))
+    meas = (b.lq_measure * 1)(b.lq_measure(1, FAKE, None))            # product without a second column
+
+    def call(n_preds=1, n_meas=1, m=meas, sums=FAKE, ws=FAKE, ws_bytes=1 << 22):
+        return lib.lq_groupby_agg(100, 1, fks, rows, None, codes, card, n_preds, preds, n_meas, m, sums, None, None,
+                                  None, ws, ws_bytes, 0, None)
+    assert call() == 1
+    ok = (b.lq_measure * 1)(b.lq_measure(7, FAKE, FAKE))
+    assert call(m=ok) == 2                                            # unknown op
+    ok = (b.lq_measure * 1)(b.lq_measure(0, FAKE, None))
+    assert call(m=ok, n_preds=5) == 2
+    assert call(m=ok, n_meas=0) == 2
+    assert call(m=ok, sums=None) == 1                                 # no output requested
+    assert call(m=ok, ws=None) == 4
+    assert call(m=ok, ws_bytes=64) == 4
+    assert lib.lq_groupby_agg_workspace_bytes(1, rows, card, 1) > 0
