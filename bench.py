@@ -75,7 +75,6 @@ def main():
 
     import torch
     import paper_2306_08367_amd as lq
-    from tests.helpers import to_dev
     from workloads import star as WL
 
     assert torch.cuda.is_available(), "bench.py needs a GPU"

@@ -97,6 +97,15 @@ template <> struct Chunk<float, 4> {
     __builtin_nontemporal_store(t, reinterpret_cast<v4f_*>(p));   // written once, never re-read here
   }
 };
+template <> struct Chunk<float, 2> {
+  static __device__ __forceinline__ void load(const float* p, float (&v)[2]) {
+    const float2 t = *reinterpret_cast<const float2*>(p);
+    v[0] = t.x; v[1] = t.y;
+  }
+  static __device__ __forceinline__ void store(float* p, const float (&v)[2]) {
+    *reinterpret_cast<float2*>(p) = make_float2(v[0], v[1]);
+  }
+};
 template <> struct Chunk<float, 1> {
   static __device__ __forceinline__ void load(const float* p, float (&v)[1]) { v[0] = *p; }
   static __device__ __forceinline__ void store(float* p, const float (&v)[1]) { *p = v[0]; }
@@ -128,8 +137,10 @@ template <> struct Chunk<bf16_t, 1> {
 constexpr int VEC_THREADS = 256;
 
 // TX: dtype of X / W / bias, TP: dtype of P, TY: dtype of Y.
-// LPR lanes per fact row (power of two, <= 64), VEC hidden columns per lane: l_1 == LPR * VEC.
-// CF: compile-time c_f.  NL: 1 (linear) or 2 (ReLU then W_2 with L2 outputs).
+// LPR lanes per fact row (power of two, <= 64), VEC hidden columns per lane: l_1 <= LPR * VEC, l_1 a
+// multiple of VEC; lanes whose slice starts at or beyond l_1 idle (zero weights, no loads, no stores).
+// CF: compile-time bound on c_f (fact columns beyond the real c_f count as zero).
+// NL: 1 (linear) or 2 (ReLU then W_2 with L2 outputs).
 template <typename TX, typename TP, typename TY, int VEC, int LPR, int CF, int NL, int L2, bool XV>
 __global__ __launch_bounds__(VEC_THREADS) void fused_vec_kernel(PredictArgs a) {
   constexpr int RPW = 64 / LPR;                 // fact rows per wavefront pass
@@ -138,6 +149,7 @@ __global__ __launch_bounds__(VEC_THREADS) void fused_vec_kernel(PredictArgs a) {
   const int sub = tid / LPR;                    // which row of the workgroup pass
   const int c = tid % LPR;                      // which VEC-wide column slice
   const int col0 = c * VEC;
+  const bool active = col0 < a.wout[0];
 
   const TX* __restrict__ X = static_cast<const TX*>(a.X);
   const TX* __restrict__ W0 = static_cast<const TX*>(a.W[0]);
@@ -146,11 +158,12 @@ __global__ __launch_bounds__(VEC_THREADS) void fused_vec_kernel(PredictArgs a) {
 #pragma unroll
   for (int q = 0; q < CF; ++q)
 #pragma unroll
-    for (int v = 0; v < VEC; ++v) wf[q][v] = Elem<TX>::load(W0 + static_cast<int64_t>(q) * a.ldw[0] + col0 + v);
+    for (int v = 0; v < VEC; ++v)
+      wf[q][v] = (active && q < a.c_f) ? Elem<TX>::load(W0 + static_cast<int64_t>(q) * a.ldw[0] + col0 + v) : 0.f;
   float b1[VEC];
 #pragma unroll
   for (int v = 0; v < VEC; ++v)
-    b1[v] = a.bias[0] ? Elem<TX>::load(static_cast<const TX*>(a.bias[0]) + col0 + v) : 0.f;
+    b1[v] = (active && a.bias[0]) ? Elem<TX>::load(static_cast<const TX*>(a.bias[0]) + col0 + v) : 0.f;
 
   float w2[NL == 2 ? VEC : 1][NL == 2 ? L2 : 1];
   float b2[NL == 2 ? L2 : 1];
@@ -160,7 +173,7 @@ __global__ __launch_bounds__(VEC_THREADS) void fused_vec_kernel(PredictArgs a) {
     for (int v = 0; v < VEC; ++v)
 #pragma unroll
       for (int o = 0; o < L2; ++o)
-        w2[v][o] = Elem<TX>::load(W1 + static_cast<int64_t>(col0 + v) * a.ldw[1] + o);
+        w2[v][o] = active ? Elem<TX>::load(W1 + static_cast<int64_t>(col0 + v) * a.ldw[1] + o) : 0.f;
 #pragma unroll
     for (int o = 0; o < L2; ++o)
       b2[o] = a.bias[1] ? Elem<TX>::load(static_cast<const TX*>(a.bias[1]) + o) : 0.f;
@@ -186,7 +199,7 @@ __global__ __launch_bounds__(VEC_THREADS) void fused_vec_kernel(PredictArgs a) {
         }
       } else {
 #pragma unroll
-        for (int q = 0; q < CF; ++q) xq[q] = Elem<TX>::load(xr + q);
+        for (int q = 0; q < CF; ++q) xq[q] = q < a.c_f ? Elem<TX>::load(xr + q) : 0.f;
       }
 #pragma unroll
       for (int q = 0; q < CF; ++q)
@@ -195,14 +208,16 @@ __global__ __launch_bounds__(VEC_THREADS) void fused_vec_kernel(PredictArgs a) {
     }
     for (int k = 0; k < a.K; ++k) {
       const int64_t j = __builtin_nontemporal_load(a.fk[k] + rr);   // keys are read once: do not let them displace table rows in cache
-      float p[VEC];
-      Chunk<TP, VEC>::load(static_cast<const TP*>(a.P[k]) + j * a.ldp[k] + col0, p);
+      if (active) {
+        float p[VEC];
+        Chunk<TP, VEC>::load(static_cast<const TP*>(a.P[k]) + j * a.ldp[k] + col0, p);
 #pragma unroll
-      for (int v = 0; v < VEC; ++v) z[v] += p[v];
+        for (int v = 0; v < VEC; ++v) z[v] += p[v];
+      }
     }
 
     if (NL == 1) {
-      if (live) Chunk<TY, VEC>::store(static_cast<TY*>(a.Y) + row * a.ldy + col0, z);
+      if (live && active) Chunk<TY, VEC>::store(static_cast<TY*>(a.Y) + row * a.ldy + col0, z);
     } else {
       float y[L2];
 #pragma unroll
@@ -235,7 +250,7 @@ int launch_vec_inst(const PredictArgs& a, hipStream_t s) {
   const int64_t blocks = std::min<int64_t>(n_pass, 0x7fffffffLL);
   if (blocks <= 0) return LQ_OK;
   constexpr bool can_xv = sizeof(TX) == 4 && CF > 0 && CF % 4 == 0;
-  if (can_xv && aligned(a.X, 16) && a.ldx % 4 == 0)
+  if (can_xv && a.c_f == CF && aligned(a.X, 16) && a.ldx % 4 == 0)
     hipLaunchKernelGGL((fused_vec_kernel<TX, TP, TY, VEC, LPR, CF, NL, L2, can_xv>),
                        dim3(static_cast<unsigned>(blocks)), dim3(VEC_THREADS), 0, s, a);
   else
@@ -262,31 +277,29 @@ int pick_layers(const PredictArgs& a, hipStream_t s) {
 
 template <typename TX, typename TP, typename TY, int VEC, int LPR>
 int pick_cf(const PredictArgs& a, hipStream_t s) {
-  switch (a.c_f) {
-    case 0: return pick_layers<TX, TP, TY, VEC, LPR, 0>(a, s);
-    case 4: return pick_layers<TX, TP, TY, VEC, LPR, 4>(a, s);
-    case 8: return pick_layers<TX, TP, TY, VEC, LPR, 8>(a, s);
-    default: return -1;
-  }
+  if (a.c_f == 0) return pick_layers<TX, TP, TY, VEC, LPR, 0>(a, s);
+  if (a.c_f <= 4) return pick_layers<TX, TP, TY, VEC, LPR, 4>(a, s);
+  if (a.c_f <= 8) return pick_layers<TX, TP, TY, VEC, LPR, 8>(a, s);
+  if (a.c_f <= 16) return pick_layers<TX, TP, TY, VEC, LPR, 16>(a, s);
+  return -1;
 }
 
 template <typename TX, typename TP, typename TY, int VEC>
 int pick_lpr(const PredictArgs& a, hipStream_t s) {
   const int l1 = a.wout[0];
   if (l1 % VEC) return -1;
-  switch (l1 / VEC) {
-    case 1: return pick_cf<TX, TP, TY, VEC, 1>(a, s);
-    case 2: return pick_cf<TX, TP, TY, VEC, 2>(a, s);
-    case 4: return pick_cf<TX, TP, TY, VEC, 4>(a, s);
-    case 8: return pick_cf<TX, TP, TY, VEC, 8>(a, s);
-    case 16: return pick_cf<TX, TP, TY, VEC, 16>(a, s);
-    case 32: return pick_cf<TX, TP, TY, VEC, 32>(a, s);
-    case 64: return pick_cf<TX, TP, TY, VEC, 64>(a, s);
-    default: return -1;
-  }
+  const int chunks = l1 / VEC;
+  if (chunks <= 1) return pick_cf<TX, TP, TY, VEC, 1>(a, s);
+  if (chunks <= 2) return pick_cf<TX, TP, TY, VEC, 2>(a, s);
+  if (chunks <= 4) return pick_cf<TX, TP, TY, VEC, 4>(a, s);
+  if (chunks <= 8) return pick_cf<TX, TP, TY, VEC, 8>(a, s);
+  if (chunks <= 16) return pick_cf<TX, TP, TY, VEC, 16>(a, s);
+  if (chunks <= 32) return pick_cf<TX, TP, TY, VEC, 32>(a, s);
+  if (chunks <= 64) return pick_cf<TX, TP, TY, VEC, 64>(a, s);
+  return -1;
 }
 
-// Are 16-byte chunk accesses to P and Y legal?
+// Are vec-element chunk accesses to P and Y legal?
 bool chunks_aligned(const PredictArgs& a, int vec_p, int vec_y) {
   const size_t ps = dtype_size(a.p_dtype), ys = dtype_size(a.y_dtype);
   for (int k = 0; k < a.K; ++k)
@@ -298,12 +311,13 @@ bool chunks_aligned(const PredictArgs& a, int vec_p, int vec_y) {
 int try_vec(const PredictArgs& a, hipStream_t s) {
   const int l1 = a.wout[0];
   if (a.x_dtype == LQ_F32 && a.p_dtype == LQ_F32 && a.y_dtype == LQ_F32) {
-    if (l1 % 4 == 0 && chunks_aligned(a, 4, 4)) return pick_lpr<float, float, float, 4>(a, s);
-    if (l1 == 1) return pick_cf<float, float, float, 1, 1>(a, s);
+    if (l1 % 4 == 0 && l1 <= 256 && chunks_aligned(a, 4, 4)) return pick_lpr<float, float, float, 4>(a, s);
+    if (l1 % 2 == 0 && l1 <= 128 && chunks_aligned(a, 2, 2)) return pick_lpr<float, float, float, 2>(a, s);
+    if (l1 <= 64) return pick_lpr<float, float, float, 1>(a, s);
     return -1;
   }
   if (a.x_dtype == LQ_BF16 && a.p_dtype == LQ_BF16 && a.y_dtype == LQ_BF16) {
-    if (l1 % 8 == 0 && chunks_aligned(a, 8, 8)) return pick_lpr<bf16_t, bf16_t, bf16_t, 8>(a, s);
+    if (l1 % 8 == 0 && l1 <= 512 && chunks_aligned(a, 8, 8)) return pick_lpr<bf16_t, bf16_t, bf16_t, 8>(a, s);
     return -1;
   }
   return -1;

@@ -71,7 +71,6 @@ int launch_project_dims(const lq_mat& D, const lq_mat& W, int32_t row_off, const
 int launch_fused(const PredictArgs& a, hipStream_t s);
 int launch_materialize(const lq_star& star, void* T, int64_t ldt, int64_t row0, int64_t rows,
                        hipStream_t s);
-int launch_dense_mlp(const PredictArgs& a, hipStream_t s);
 int launch_check_fks(int64_t n, int32_t K, const int32_t* const* fks, const int64_t* rows,
                      bool negative_ok, int32_t* d_flag, hipStream_t s);
 int launch_copy(void* dst, const void* src, size_t bytes, hipStream_t s);

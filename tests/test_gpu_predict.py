@@ -46,6 +46,17 @@ SHAPES = [
     ("single_row_dims", 1_000, 2, (1, 1), (4, 4), (16, 2), True),
     ("one_fact_row", 1, 4, (10, 10), (8, 8), (64, 1), True),
     ("k8_dims", 3_000, 4, (10,) * 8, (4,) * 8, (16,), False),
+    # widths that do not fill a power-of-two lane group, odd fact-column counts (idle lanes, padded c_f)
+    ("linear_l2", 4_001, 1, (50, 60), (5, 5), (2,), True),
+    ("linear_l6_cf5", 3_003, 5, (50, 60), (5, 5), (6,), False),
+    ("linear_l12", 2_002, 4, (50,), (8,), (12,), True),
+    ("linear_l100", 1_501, 11, (70, 80), (6, 6), (100,), True),
+    ("linear_l50", 1_777, 16, (70, 80), (6, 6), (50,), False),
+    ("linear_l37", 1_234, 2, (70, 80), (6, 6), (37,), True),
+    ("mlp_24_2_cf3", 2_345, 3, (33, 44), (7, 7), (24, 2), True),
+    ("mlp_10_1", 3_210, 7, (33, 44), (7, 7), (10, 1), True),
+    ("linear_l128", 1_999, 4, (100, 200), (16, 16), (128,), False),
+    ("linear_l256", 1_001, 4, (100, 200), (16, 16), (256,), True),
 ]
 
 
