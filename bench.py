@@ -67,7 +67,7 @@ def main():
     ap.add_argument("--rows", type=int, default=10_000_000, help="fact rows of the headline workload")
     ap.add_argument("--no-extras", action="store_true", help="skip materialised / group-by / skewed legs")
     ap.add_argument("--no-cpu", action="store_true", help="skip the CPU oracle baseline")
-    ap.add_argument("--only", default="", help="run a single leg for profiling: fused|groupby|groupby16|c4|c5|tree|keymap|agg|materialized|copy")
+    ap.add_argument("--only", default="", help="run a single leg for profiling: fused|groupby|groupby16|c4|c5|tree|keymap|agg|sweep|materialized|copy")
     args = ap.parse_args()
     if args.gpus != 1:
         sys.exit("bench.py: this build is single-GPU by design (no collectives, no sharding); "
@@ -325,6 +325,30 @@ def main():
         out["agg_one_join"] = {"rows_per_s": na / (ms * 1e-3), "ms": ms, "fact_rows": na,
                                "roofline": {"bound": "hbm", "achieved": gbps, "peak": HBM_PEAK_GBPS, "unit": "GB/s",
                                             "frac": gbps / HBM_PEAK_GBPS, "algorithmic_bytes_per_row": 16}}
+
+    # ---------------------------------------------------------------- k x l sweep (setting 1, sf 4, linear operator)
+    if (args.only == "" and not args.no_extras) or args.only == "sweep":
+        ns = 2_400_000
+        rows_s = (60_000, 8_000, 2_555)
+        split = {16: (8, 4, 4), 32: (12, 12, 8), 64: (24, 20, 20), 128: (44, 44, 40)}
+        sweep = {}
+        ws_s = None
+        for k_in, cols in split.items():
+            for l_out in (2, 4, 8, 16, 32, 64, 128):
+                wk = WL.make_predict("sweep", ns, 0, rows_s, cols, (l_out,), seed=WL.SEED0 + 1000 + k_in, device=dev)
+                Pk = lq.lq_project_dims(wk.dims, wk.weights[0], 0)
+                Yk = torch.empty((ns, l_out), dtype=torch.float32, device=dev)
+                fms, _, _ = time_call(lambda: lq.lq_fused_join_predict(None, wk.fks, Pk, wk.weights, None, Y=Yk), 5, 1)
+                pms, _, _ = time_call(lambda: lq.lq_project_dims(wk.dims, wk.weights[0], 0, P=Pk), 3, 1)
+                need = lq.lq_workspace_bytes(lq.binding.LQ_CALL_MATERIALIZED, k_in, wk.weights, 1 << 21)
+                if ws_s is None or ws_s.numel() < need:
+                    ws_s = torch.empty(need, dtype=torch.uint8, device=dev)
+                mms, _, _ = time_call(lambda: lq.lq_materialized_join_predict(None, wk.dims, wk.fks, wk.weights, None,
+                                                                              Y=Yk, ws=ws_s), 2, 1)
+                sweep[f"k{k_in}_l{l_out}"] = {"fused_ms": round(fms, 4), "prefusion_ms": round(pms, 4),
+                                              "materialized_ms": round(mms, 4), "speedup": round(mms / fms, 2),
+                                              "k_over_l": k_in / l_out}
+        out["sweep_setting1_sf4"] = {"fact_rows": ns, "dim_rows": list(rows_s), "cells": sweep}
 
     print(json.dumps(out))
 
