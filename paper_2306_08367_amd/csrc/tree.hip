@@ -60,6 +60,58 @@ __global__ __launch_bounds__(256) void tree_project_kernel(TreeArgs t, const flo
   }
 }
 
+
+// Sparse version of the same computation.  A column of H has at most 255 nonzeros (longer paths are
+// unsupported), so a workgroup first turns the H columns of its 64 leaves into per-leaf lists of the
+// nodes this dimension owns (node number, sign bit) in LDS and then walks only those lists for every
+// (dimension row, leaf): r * l * depth / K evaluations instead of r * l * p.
+constexpr int TP_COLS = 64;         // leaves per workgroup
+constexpr int TP_MAXPATH = 256;     // list capacity per leaf
+__global__ __launch_bounds__(256) void tree_project_sparse_kernel(TreeArgs t, const float* __restrict__ D,
+                                                                  int64_t ldd, int64_t rows, int32_t col_off,
+                                                                  int32_t c, uint8_t* __restrict__ out,
+                                                                  int64_t rows_per_block) {
+  __shared__ unsigned short list[TP_COLS][TP_MAXPATH];
+  __shared__ int count[TP_COLS];
+  const int tid = threadIdx.x;
+  const int j0 = blockIdx.x * TP_COLS;
+  const int64_t r0 = static_cast<int64_t>(blockIdx.y) * rows_per_block;
+  const int64_t r1 = min(rows, r0 + rows_per_block);
+  if (tid < TP_COLS) count[tid] = 0;
+  __syncthreads();
+  {
+    const int j = tid % TP_COLS;
+    if (j0 + j < t.l)
+      for (int q = tid / TP_COLS; q < t.p; q += 256 / TP_COLS) {
+        const int hv = t.H[static_cast<int64_t>(q) * t.l + j0 + j];
+        if (hv == 0) continue;
+        const int f = t.feature[q] - col_off;
+        if (f < 0 || f >= c) continue;                       // node owned by another table
+        const int slot = atomicAdd(&count[j], 1);
+        if (slot < TP_MAXPATH) list[j][slot] = static_cast<unsigned short>(q | (hv < 0 ? 0x8000 : 0));
+      }
+  }
+  __syncthreads();
+  const int64_t total = (r1 - r0) * TP_COLS;
+  for (int64_t idx = tid; idx < total; idx += 256) {
+    const int64_t r = r0 + idx / TP_COLS;
+    const int j = static_cast<int>(idx % TP_COLS);
+    if (j0 + j >= t.ld) continue;
+    int agree = 0;
+    if (j0 + j < t.l) {
+      const float* dr = D + r * ldd;
+      const int n = min(count[j], TP_MAXPATH);
+      for (int e = 0; e < n; ++e) {
+        const int v = list[j][e];
+        const int q = v & 0x7fff;
+        const bool bit = dr[t.feature[q] - col_off] > t.thr[q];
+        agree += bit == ((v & 0x8000) == 0);
+      }
+    }
+    out[r * t.ld + j0 + j] = static_cast<uint8_t>(min(agree, 255));
+  }
+}
+
 // ---------------------------------------------------------------- fused join ---------------
 
 struct FusedTreeArgs {
@@ -238,12 +290,25 @@ int lq_tree_project_dims(const lq_star* star, const lq_tree* tree, void* const* 
   int32_t off = star->fact.cols;
   for (int k = 0; k < star->n_dims; ++k) {
     const lq_mat& d = star->dims[k];
-    const int64_t total = d.rows * t.ld;
-    const int64_t blocks = std::min<int64_t>((total + 255) / 256, static_cast<int64_t>(num_cus()) * 32);
-    hipLaunchKernelGGL(tree_project_kernel, dim3(static_cast<unsigned>(blocks)), dim3(256), 0, s, t,
-                       static_cast<const float*>(d.data), d.ld, d.rows, off, d.cols,
-                       static_cast<uint8_t*>(tables[k]));
-    LQ_LAUNCH_CHECK("tree_project_kernel");
+    if (t.p > 256 && t.p <= 0x7fff) {   // short node lists are cheaper to scan densely
+      const int64_t col_tiles = (t.ld + TP_COLS - 1) / TP_COLS;
+      // enough row slices to fill the GPU, each long enough to amortise building the lists
+      int64_t slices = std::max<int64_t>(1, std::min<int64_t>((static_cast<int64_t>(num_cus()) * 4 + col_tiles - 1) / col_tiles,
+                                                              (d.rows + 255) / 256));
+      slices = std::min<int64_t>(slices, 65535);
+      const int64_t rpb = (d.rows + slices - 1) / slices;
+      hipLaunchKernelGGL(tree_project_sparse_kernel, dim3(static_cast<unsigned>(col_tiles), static_cast<unsigned>(slices)),
+                         dim3(256), 0, s, t, static_cast<const float*>(d.data), d.ld, d.rows, off, d.cols,
+                         static_cast<uint8_t*>(tables[k]), rpb);
+      LQ_LAUNCH_CHECK("tree_project_sparse_kernel");
+    } else {
+      const int64_t total = d.rows * t.ld;
+      const int64_t blocks = std::min<int64_t>((total + 255) / 256, static_cast<int64_t>(num_cus()) * 32);
+      hipLaunchKernelGGL(tree_project_kernel, dim3(static_cast<unsigned>(blocks)), dim3(256), 0, s, t,
+                         static_cast<const float*>(d.data), d.ld, d.rows, off, d.cols,
+                         static_cast<uint8_t*>(tables[k]));
+      LQ_LAUNCH_CHECK("tree_project_kernel");
+    }
     off += d.cols;
   }
   return LQ_OK;

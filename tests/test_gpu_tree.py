@@ -43,6 +43,7 @@ CASES = [
     ("hundred_leaves", 3_333, 0, (64, 64, 64, 64), (5, 5, 5, 5), 100),
     ("wide_256", 2_049, 0, (300, 200), (16, 16), 256),
     ("very_wide_1500", 1_025, 0, (120, 90), (32, 32), 1_500),
+    ("wide_600_three_tables", 777, 0, (1_000, 37, 300), (20, 30, 10), 600),
     ("fact_columns", 2_500, 3, (40, 60), (4, 4), 24),
     ("one_row", 1, 0, (5,), (3,), 4),
 ]
