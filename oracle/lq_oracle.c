@@ -33,7 +33,7 @@
  *                        with relational filter / join / GROUP BY / SUM
  *                        semantics.
  *
- * Readings taken where the paper is silent (each listed in the design notes):
+ * Readings taken where the paper is silent:
  *   - fact-table feature columns come first in T, then dimension 0, 1, ...
  *   - bias (optional) is added once per layer after the sum
  *   - a ReLU sits between layers, none after the last
@@ -267,7 +267,7 @@ int lqo_groupby_sum(int64_t n, int32_t K, const int32_t* const* fk,
  *   h[j]        value R takes exactly when leaf j is reached.  A leaf is reached iff all its +1
  *               nodes are true and all its -1 nodes are false, i.e. R_j = number of +1 entries
  *               of column j.  (The paper words h as "the column sum of H", which cannot be meant
- *               literally for a 0/1 predicate matrix; see the design notes.)
+ *               literally for a 0/1 predicate matrix: a column with a -1 entry would then never match.)
  *   step 4      onehot[i][j] = (R[i][j] == h[j]);  leaf[i] = first j with onehot 1, -1 if none.
  * ------------------------------------------------------------------------------------------ */
 
