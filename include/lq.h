@@ -63,6 +63,8 @@ typedef enum { LQ_F32 = 0, LQ_BF16 = 1 } lq_dtype;
 /* Testing aid for lq_fused_join_predict: run the shape-agnostic kernel even where a
  * specialised one exists, so that the two can be compared. */
 #define LQ_FORCE_GENERIC 0x100u
+/* Likewise: run the LDS-tiled matrix-core MLP kernel where it covers the shape. */
+#define LQ_FORCE_TILE 0x200u
 
 /* which_call values of lq_workspace_bytes */
 #define LQ_CALL_FUSED 1

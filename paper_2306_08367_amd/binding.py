@@ -17,6 +17,7 @@ _LIB_PATH = os.path.join(_HERE, "liblq.so")
 LQ_OK = 0
 LQ_CHECK_FKS = 1
 LQ_FORCE_GENERIC = 0x100
+LQ_FORCE_TILE = 0x200
 LQ_CALL_FUSED = 1
 LQ_CALL_MATERIALIZED = 2
 LQ_F32, LQ_BF16 = 0, 1

@@ -327,6 +327,7 @@ int try_vec(const PredictArgs& a, hipStream_t s) {
 
 int try_rowbatch64(const PredictArgs& a, hipStream_t s);
 int try_fused_bf16(const PredictArgs& a, hipStream_t s);
+int try_fused_tile(const PredictArgs& a, hipStream_t s);
 
 int launch_fused(const PredictArgs& a, hipStream_t s) {
   if (a.n == 0) return LQ_OK;
@@ -335,6 +336,16 @@ int launch_fused(const PredictArgs& a, hipStream_t s) {
   rc = try_fused_bf16(a, s);
   if (rc >= 0) return rc;
   rc = try_vec(a, s);
+  if (rc >= 0) return rc;
+  rc = try_fused_tile(a, s);
+  if (rc >= 0) return rc;
+  return launch_generic(a, s);
+}
+
+// The tile kernel alone (testing / tuning aid), generic kernel if it does not cover the shape.
+int launch_fused_tile(const PredictArgs& a, hipStream_t s) {
+  if (a.n == 0) return LQ_OK;
+  const int rc = try_fused_tile(a, s);
   if (rc >= 0) return rc;
   return launch_generic(a, s);
 }

@@ -139,7 +139,10 @@ __device__ __forceinline__ void compute_group(const PredictArgs& a, int c, int64
 
 // K dimensions, CFC float4 chunks of fact columns (c_f = 4 CFC), NL layers (1 or 2), L2 outputs.
 template <int K, int CFC, int NL, int L2>
-__global__ __launch_bounds__(RB_THREADS) __attribute__((amdgpu_waves_per_eu(3, 3)))
+// (Three wavefronts per SIMD leave 170 registers each; with several outputs the per-pass partial sums no
+// longer fit and two per SIMD is faster than spilling.)
+__global__ __launch_bounds__(RB_THREADS)
+__attribute__((amdgpu_waves_per_eu((NL == 2 && L2 > 1) ? 2 : 3, (NL == 2 && L2 > 1) ? 2 : 3)))
 void fused_rowbatch64_kernel(PredictArgs a) {
   const int lane = threadIdx.x & 63, c = lane & 15, s = lane >> 4;
   const int64_t wave = static_cast<int64_t>(blockIdx.x) * (RB_THREADS / 64) + (threadIdx.x >> 6);
@@ -207,7 +210,7 @@ void fused_rowbatch64_kernel(PredictArgs a) {
 template <int K, int CFC, int NL, int L2>
 int launch_inst(const PredictArgs& a, hipStream_t s) {
   const int64_t nb = (a.n + 63) / 64;
-  const int64_t blocks = std::min<int64_t>((nb + 3) / 4, static_cast<int64_t>(num_cus()) * 3);
+  const int64_t blocks = std::min<int64_t>((nb + 3) / 4, static_cast<int64_t>(num_cus()) * ((NL == 2 && L2 > 1) ? 2 : 3));
   hipLaunchKernelGGL((fused_rowbatch64_kernel<K, CFC, NL, L2>), dim3(static_cast<unsigned>(blocks)),
                      dim3(RB_THREADS), 0, s, a);
   LQ_LAUNCH_CHECK("fused_rowbatch64_kernel");

@@ -33,6 +33,7 @@ int launch_gemm(const void* A, int64_t lda, const void* B, int64_t ldb, void* C,
                 const void* bias, int64_t M, int32_t N, int32_t Kd, int relu, int32_t in_dtype,
                 int32_t out_dtype, hipStream_t s);
 int launch_fused_generic(const PredictArgs& a, hipStream_t s);
+int launch_fused_tile(const PredictArgs& a, hipStream_t s);
 int launch_groupby(int64_t n, int32_t K, const int32_t* const* fks, const int64_t* rows,
                    const uint8_t* const* mask, const int32_t* const* code, const int32_t* card,
                    const uint8_t* fact_mask, int32_t M, const int32_t* const* meas, int64_t* sums,
@@ -301,6 +302,7 @@ int lq_fused_join_predict(const lq_star* star, const lq_model* model, const lq_m
   if ((flags & LQ_CHECK_FKS) && a.K > 0 && a.n > 0)
     if ((rc = run_fk_check(a.n, a.K, star->fks, rows, false, ws, ws_bytes, s))) return rc;
   if (flags & FLAG_FORCE_GENERIC) return launch_fused_generic(a, s);
+  if (flags & LQ_FORCE_TILE) return launch_fused_tile(a, s);
   return launch_fused(a, s);
 }
 

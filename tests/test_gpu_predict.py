@@ -57,6 +57,12 @@ SHAPES = [
     ("mlp_10_1", 3_210, 7, (33, 44), (7, 7), (10, 1), True),
     ("linear_l128", 1_999, 4, (100, 200), (16, 16), (128,), False),
     ("linear_l256", 1_001, 4, (100, 200), (16, 16), (256,), True),
+    # shapes only the tiled matrix-core MLP kernel covers: wide second layers, three layers
+    ("mlp_64_10", 5_555, 4, (100, 2_000, 50), (16, 16, 16), (64, 10), True),
+    ("mlp_128_16", 3_001, 4, (100, 200), (16, 16), (128, 16), False),
+    ("mlp_64_32_1", 4_321, 4, (100, 200), (16, 16), (64, 32, 1), True),
+    ("mlp_256_64_8_3", 1_033, 0, (100, 200), (16, 16), (256, 64, 8, 3), True),
+    ("mlp_37_5_odd", 2_047, 3, (60, 70), (5, 9), (37, 5), True),
 ]
 
 
@@ -75,6 +81,8 @@ def test_fused_matches_oracle_fp32(lq, shape):
     # the shape-agnostic kernel must agree with whichever kernel the dispatcher picked
     _, Yg = _run_fused(lq, w, flags=lq.LQ_FORCE_GENERIC)
     assert_close(Yg, want, TOL_F32, f"{name}: generic kernel")
+    _, Yt = _run_fused(lq, w, flags=lq.LQ_FORCE_TILE)
+    assert_close(Yt, want, TOL_F32, f"{name}: tile kernel")
     # the non-fused pipeline computes the same function
     Ym = lq.lq_materialized_join_predict(w.X, w.dims, w.fks, w.weights, w.biases, chunk_rows=1024)
     torch.cuda.synchronize()
@@ -176,6 +184,8 @@ def test_bf16_wide_models(lq, shape):
         assert_close(Y, want, TOL_BF16, f"{name} Y {y_dtype}")
     _, Yg = _run_fused(lq, w, p_dtype=torch.bfloat16, y_dtype=torch.float32, flags=lq.LQ_FORCE_GENERIC)
     assert_close(Yg, want, TOL_BF16, f"{name} generic")
+    _, Yt = _run_fused(lq, w, p_dtype=torch.bfloat16, y_dtype=torch.bfloat16, flags=lq.LQ_FORCE_TILE)
+    assert_close(Yt, want, TOL_BF16, f"{name} tile")
 
 
 def test_bf16_matrix_core_epilogue_is_exact_on_small_integers(lq):
