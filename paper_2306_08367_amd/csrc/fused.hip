@@ -136,6 +136,22 @@ template <> struct Chunk<bf16_t, 1> {
 
 constexpr int VEC_THREADS = 256;
 
+template <int CTRL> __device__ __forceinline__ float dpp_f(float v) {
+  return __int_as_float(__builtin_amdgcn_update_dpp(0, __float_as_int(v), CTRL, 0xf, 0xf, false));
+}
+// Sum over groups of LPR adjacent lanes (LPR a power of two), result in every lane of the group.
+// Steps inside a 16-lane DPP row are DPP adds (quad permutes, half-row and row mirrors); only the
+// steps across DPP rows go through the cross-lane network.
+template <int LPR> __device__ __forceinline__ float group_allreduce(float y) {
+  if (LPR >= 2) y += dpp_f<0xB1>(y);     // quad_perm [1,0,3,2]
+  if (LPR >= 4) y += dpp_f<0x4E>(y);     // quad_perm [2,3,0,1]
+  if (LPR >= 8) y += dpp_f<0x141>(y);    // row_half_mirror
+  if (LPR >= 16) y += dpp_f<0x140>(y);   // row_mirror
+  if (LPR >= 32) y += __shfl_xor(y, 16, 64);
+  if (LPR >= 64) y += __shfl_xor(y, 32, 64);
+  return y;
+}
+
 // TX: dtype of X / W / bias, TP: dtype of P, TY: dtype of Y.
 // LPR lanes per fact row (power of two, <= 64), VEC hidden columns per lane: l_1 <= LPR * VEC, l_1 a
 // multiple of VEC; lanes whose slice starts at or beyond l_1 idle (zero weights, no loads, no stores).
@@ -229,9 +245,7 @@ __global__ __launch_bounds__(VEC_THREADS) void fused_vec_kernel(PredictArgs a) {
         for (int o = 0; o < L2; ++o) y[o] = fmaf(h, w2[v][o], y[o]);
       }
 #pragma unroll
-      for (int m = 1; m < LPR; m <<= 1)
-#pragma unroll
-        for (int o = 0; o < L2; ++o) y[o] += __shfl_xor(y[o], m, 64);
+      for (int o = 0; o < L2; ++o) y[o] = group_allreduce<LPR>(y[o]);
       if (live && c == 0) {
         TY* yr = static_cast<TY*>(a.Y) + row * a.ldy;
 #pragma unroll

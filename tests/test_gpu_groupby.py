@@ -111,6 +111,15 @@ def test_three_grouping_dimensions_and_wide_codes(lq):
     _check(lq, _random_groupby(36, 60_000, (40, 30, 8), (10, 10, 8), n_measures=4))
 
 
+def test_largest_supported_group_count(lq):
+    # 64 x 64 = 4,096 groups with one measure: (M + 1) * G = 8,192 accumulators, the documented limit
+    _check(lq, _random_groupby(43, 300_001, (500, 700, 20), (64, 64, 1), n_measures=1))
+    w = to_dev(_random_groupby(44, 1_000, (500, 700), (64, 64), n_measures=2))
+    with pytest.raises(lq.LQError) as e:
+        _gpu(lq, w)
+    assert e.value.status == "LQ_ERR_UNSUPPORTED"
+
+
 def test_side_tables_too_large_for_lds_are_read_from_memory(lq):
     # 400,000 + 300,000 byte-coded rows exceed the 160 KB of LDS
     _check(lq, _random_groupby(37, 300_007, (400_000, 300_000, 1_000), (7, 5, 1), n_measures=1))

@@ -63,6 +63,8 @@ SHAPES = [
     ("mlp_64_32_1", 4_321, 4, (100, 200), (16, 16), (64, 32, 1), True),
     ("mlp_256_64_8_3", 1_033, 0, (100, 200), (16, 16), (256, 64, 8, 3), True),
     ("mlp_37_5_odd", 2_047, 3, (60, 70), (5, 9), (37, 5), True),
+    # the limits of the interface: 8 layers, 8 dimensions
+    ("eight_layers_eight_dims", 1_500, 2, (9,) * 8, (3,) * 8, (24, 20, 16, 12, 10, 8, 6, 2), True),
 ]
 
 
