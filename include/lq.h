@@ -60,6 +60,14 @@ typedef enum { LQ_F32 = 0, LQ_BF16 = 1 } lq_dtype;
 /* flags */
 #define LQ_CHECK_FKS 1u
 #define LQ_CHECK_KEYS 2u
+/* lq_masked_groupby_sum / lq_groupby_agg: the caller states that the previous call of the same
+ * entry point with this workspace had the same dim_rows, dim_mask, dim_code and group_card (same
+ * pointers, unchanged contents) and the same n_measures, and that nothing else wrote to the
+ * workspace since.  The call then skips re-encoding the dimension side tables (the pushed-down
+ * selection vectors and group codes of Sections 2.2-2.4) and goes straight to the fact scan: a
+ * dashboard that re-runs a query over new fact rows, or with another fact_mask or other measures
+ * columns, pays for the dimension side once.  Results are undefined if the statement is false. */
+#define LQ_REUSE_SIDE_TABLES 4u
 /* Testing aid for lq_fused_join_predict: run the shape-agnostic kernel even where a
  * specialised one exists, so that the two can be compared. */
 #define LQ_FORCE_GENERIC 0x100u
@@ -195,7 +203,8 @@ int lq_materialized_join_predict(const lq_star* star, const lq_model* model, lq_
  *   fact_mask  uint8 [n] or NULL
  *   measures   host array of n_measures (1..LQ_MAX_MEASURES) device pointers, int32 [n]
  *   sums       int64 [n_measures x G], overwritten;  counts int64 [G] or NULL
- *   ws         lq_groupby_workspace_bytes(..) bytes, 256-byte aligned
+ *   ws         lq_groupby_workspace_bytes(..) bytes, 256-byte aligned; holds the encoded side
+ *              tables between calls for LQ_REUSE_SIDE_TABLES
  * A code outside [0, group_card[k]) on a surviving row is undefined behaviour.
  */
 int lq_masked_groupby_sum(int64_t n_fact, int32_t n_dims, const int32_t* const* fks,

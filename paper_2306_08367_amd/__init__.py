@@ -6,7 +6,7 @@ into its C interface.  There is no fallback: without the library, importing
 ``binding`` raises.
 """
 from .binding import (  # noqa: F401
-    LQ_CHECK_FKS, LQ_FORCE_GENERIC, LQ_FORCE_TILE, LQError, lib_path, lq_fused_join_predict,
+    LQ_CHECK_FKS, LQ_REUSE_SIDE_TABLES, LQ_FORCE_GENERIC, LQ_FORCE_TILE, LQError, lib_path, lq_fused_join_predict,
     lq_groupby_workspace_bytes, lq_last_error, lq_masked_groupby_sum,
     lq_materialized_join_predict, lq_project_dims, lq_stream_copy, lq_version,
     lq_workspace_bytes, lq_tree_table_ld, lq_tree_project_dims, lq_fused_join_tree,

@@ -22,6 +22,7 @@ LQ_CALL_FUSED = 1
 LQ_CALL_MATERIALIZED = 2
 LQ_F32, LQ_BF16 = 0, 1
 LQ_CHECK_KEYS = 2
+LQ_REUSE_SIDE_TABLES = 4
 _STATUS = {8: "LQ_ERR_DUPLICATE_KEY", 1: "LQ_ERR_NULL", 2: "LQ_ERR_SHAPE", 3: "LQ_ERR_DTYPE", 4: "LQ_ERR_WORKSPACE",
            5: "LQ_ERR_FK_RANGE", 6: "LQ_ERR_UNSUPPORTED", 7: "LQ_ERR_HIP"}
 

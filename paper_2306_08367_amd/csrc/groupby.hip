@@ -690,7 +690,7 @@ size_t groupby_ws_bytes(int32_t K, const int64_t* rows, int64_t n_acc) {
 int launch_groupby(int64_t n, int32_t K, const int32_t* const* fks, const int64_t* rows,
                    const uint8_t* const* mask, const int32_t* const* code, const int32_t* card,
                    const uint8_t* fact_mask, int32_t M, const int32_t* const* meas, int64_t* sums,
-                   int64_t* counts, int32_t G, void* ws, hipStream_t s) {
+                   int64_t* counts, int32_t G, void* ws, bool reuse_tables, hipStream_t s) {
   GbArgs a{};
   a.n = n; a.K = K; a.fact_mask = fact_mask; a.M = M; a.G = G;
   a.sums = reinterpret_cast<unsigned long long*>(sums);
@@ -723,7 +723,7 @@ int launch_groupby(int64_t n, int32_t K, const int32_t* const* fks, const int64_
   a.packed_bytes = static_cast<uint32_t>(packed);
 
   const int cus = num_cus();
-  {
+  if (!reuse_tables) {
     size_t work = 1;
     for (int k = 0; k < K; ++k) {
       const size_t w = a.d[k].kind == DK_BITMAP ? static_cast<size_t>(a.d[k].bytes) * 8   // one lane per row
@@ -826,7 +826,7 @@ int launch_groupby_agg(int64_t n, int32_t K, const int32_t* const* fks, const in
                        const uint8_t* const* mask, const int32_t* const* code, const int32_t* card,
                        int32_t n_preds, const lq_range_pred* preds, int32_t M, const lq_measure* meas,
                        int64_t* sums, int64_t* mins, int64_t* maxs, int64_t* counts, int32_t G, void* ws,
-                       hipStream_t s) {
+                       bool reuse_tables, hipStream_t s) {
   GbArgs a{};
   AggExtra x{};
   a.n = n; a.K = K; a.fact_mask = nullptr; a.M = M; a.G = G;
@@ -866,7 +866,7 @@ int launch_groupby_agg(int64_t n, int32_t K, const int32_t* const* fks, const in
   if (packed > 0xffffffffull) return fail(LQ_ERR_UNSUPPORTED, "group-by: dimension side tables exceed 4 GiB");
   a.packed_bytes = static_cast<uint32_t>(packed);
   const int cus = num_cus();
-  {
+  if (!reuse_tables) {
     size_t work = 1;
     for (int k = 0; k < K; ++k) {
       const size_t w = a.d[k].kind == DK_BITMAP ? static_cast<size_t>(a.d[k].bytes) * 8 : static_cast<size_t>(a.d[k].bytes) / 4;

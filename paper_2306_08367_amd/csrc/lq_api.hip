@@ -37,13 +37,14 @@ int launch_fused_tile(const PredictArgs& a, hipStream_t s);
 int launch_groupby(int64_t n, int32_t K, const int32_t* const* fks, const int64_t* rows,
                    const uint8_t* const* mask, const int32_t* const* code, const int32_t* card,
                    const uint8_t* fact_mask, int32_t M, const int32_t* const* meas, int64_t* sums,
-                   int64_t* counts, int32_t G, void* ws, hipStream_t s);
+                   int64_t* counts, int32_t G, void* ws, bool reuse_tables, hipStream_t s);
 size_t groupby_ws_bytes(int32_t K, const int64_t* rows, int64_t n_acc);
 int launch_groupby_agg(int64_t n, int32_t K, const int32_t* const* fks, const int64_t* rows,
                        const uint8_t* const* mask, const int32_t* const* code, const int32_t* card,
                        int32_t n_preds, const lq_range_pred* preds, int32_t M, const lq_measure* meas,
                        int64_t* sums, int64_t* mins, int64_t* maxs, int64_t* counts, int32_t G, void* ws,
-                       hipStream_t s);
+                       bool reuse_tables, hipStream_t s);
+size_t groupby_tables_bytes(int32_t K, const int64_t* rows);
 
 namespace {
 
@@ -158,6 +159,15 @@ int run_fk_check(int64_t n, int32_t K, const int32_t* const* fks, const int64_t*
   LQ_HIP_TRY(hipStreamSynchronize(s));
   if (h) return fail(LQ_ERR_FK_RANGE, "a foreign key lies outside its dimension table");
   return LQ_OK;
+}
+
+// Group-by calls keep the packed side tables at the start of their workspace (and may be asked to
+// reuse them), so the check's flag word goes behind them, into the partial-sum area that the scan
+// overwrites afterwards.
+int check_groupby_fks(int64_t n, int32_t K, const int32_t* const* fks, const int64_t* rows, void* ws,
+                      size_t ws_bytes, hipStream_t s) {
+  const size_t off = groupby_tables_bytes(K, rows);
+  return run_fk_check(n, K, fks, rows, true, static_cast<uint8_t*>(ws) + off, ws_bytes - off, s);
 }
 
 constexpr uint32_t FLAG_FORCE_GENERIC = 0x100u;   // testing aid, see lq_fused_join_predict
@@ -435,9 +445,10 @@ int lq_masked_groupby_sum(int64_t n_fact, int32_t n_dims, const int32_t* const* 
   hipStream_t s = static_cast<hipStream_t>(hip_stream);
   int rc;
   if ((flags & LQ_CHECK_FKS) && n_dims > 0 && n_fact > 0)
-    if ((rc = run_fk_check(n_fact, n_dims, fks, dim_rows, true, ws, ws_bytes, s))) return rc;
+    if ((rc = check_groupby_fks(n_fact, n_dims, fks, dim_rows, ws, ws_bytes, s))) return rc;
   return launch_groupby(n_fact, n_dims, fks, dim_rows, dim_mask, dim_code, group_card, fact_mask,
-                        n_measures, measures, sums, counts, static_cast<int32_t>(G), ws, s);
+                        n_measures, measures, sums, counts, static_cast<int32_t>(G), ws,
+                        (flags & LQ_REUSE_SIDE_TABLES) != 0, s);
 }
 
 size_t lq_groupby_agg_workspace_bytes(int32_t n_dims, const int64_t* dim_rows, const int32_t* group_card,
@@ -498,9 +509,10 @@ int lq_groupby_agg(int64_t n_fact, int32_t n_dims, const int32_t* const* fks, co
   hipStream_t s = static_cast<hipStream_t>(hip_stream);
   int rc;
   if ((flags & LQ_CHECK_FKS) && n_dims > 0 && n_fact > 0)
-    if ((rc = run_fk_check(n_fact, n_dims, fks, dim_rows, true, ws, ws_bytes, s))) return rc;
+    if ((rc = check_groupby_fks(n_fact, n_dims, fks, dim_rows, ws, ws_bytes, s))) return rc;
   return launch_groupby_agg(n_fact, n_dims, fks, dim_rows, dim_mask, dim_code, group_card, n_preds, preds,
-                            n_measures, measures, sums, mins, maxs, counts, static_cast<int32_t>(G), ws, s);
+                            n_measures, measures, sums, mins, maxs, counts, static_cast<int32_t>(G), ws,
+                            (flags & LQ_REUSE_SIDE_TABLES) != 0, s);
 }
 
 int lq_stream_copy(void* dst, const void* src, size_t bytes, void* hip_stream) {

@@ -170,3 +170,28 @@ def test_check_fks_flag(lq):
     assert e.value.status == "LQ_ERR_FK_RANGE"
     w.fks[1][77] = -5                                        # negative = no match: allowed
     _gpu(lq, w, flags=lq.LQ_CHECK_FKS)
+
+
+def test_reuse_side_tables_skips_the_dimension_pass_and_gives_the_same_result(lq):
+    # first call encodes the dimension side into the workspace; the following ones reuse it over
+    # other fact rows, another fact mask and other measures
+    w = _random_groupby(45, 120_001, (2_556, 3_000, 500_000), (7, 25, 1))
+    ws_, wc_ = _oracle(w)
+    w = to_dev(w)
+    ws = torch.empty(lq.lq_groupby_workspace_bytes(w.dim_rows, w.group_card, len(w.measures)),
+                     dtype=torch.uint8, device="cuda")
+    s, c = _gpu(lq, w, ws=ws, flags=lq.LQ_CHECK_FKS)
+    np.testing.assert_array_equal(s, ws_)
+    for _ in range(2):
+        s, c = _gpu(lq, w, ws=ws, flags=lq.LQ_REUSE_SIDE_TABLES | lq.LQ_CHECK_FKS)
+        np.testing.assert_array_equal(s, ws_)
+        np.testing.assert_array_equal(c, wc_)
+    w2 = _random_groupby(46, 77_777, (2_556, 3_000, 500_000), (7, 25, 1))
+    w2.dim_mask = [None if m is None else m.cpu() for m in w.dim_mask]
+    w2.dim_code = [None if m is None else m.cpu() for m in w.dim_code]
+    ws2, wc2 = _oracle(w2)
+    w2 = to_dev(w2)
+    w2.dim_mask, w2.dim_code = w.dim_mask, w.dim_code            # the very same device arrays
+    s, c = _gpu(lq, w2, ws=ws, flags=lq.LQ_REUSE_SIDE_TABLES)
+    np.testing.assert_array_equal(s, ws2)
+    np.testing.assert_array_equal(c, wc2)
