@@ -67,7 +67,7 @@ def main():
     ap.add_argument("--rows", type=int, default=10_000_000, help="fact rows of the headline workload")
     ap.add_argument("--no-extras", action="store_true", help="skip materialised / group-by / skewed legs")
     ap.add_argument("--no-cpu", action="store_true", help="skip the CPU oracle baseline")
-    ap.add_argument("--only", default="", help="run a single leg for profiling: fused|groupby|groupby16|c4|c5|tree|keymap|agg|sweep|materialized|copy")
+    ap.add_argument("--only", default="", help="run a single leg for profiling: fused|groupby|groupby16|c4|c5|tree|keymap|agg|sweep|sfsweep|materialized|copy")
     args = ap.parse_args()
     if args.gpus != 1:
         sys.exit("bench.py: this build is single-GPU by design (no collectives, no sharding); "
@@ -357,6 +357,33 @@ def main():
                                               "materialized_ms": round(mms, 4), "speedup": round(mms / fms, 2),
                                               "k_over_l": k_in / l_out}
         out["sweep_setting1_sf4"] = {"fact_rows": ns, "dim_rows": list(rows_s), "cells": sweep}
+
+    # ---------------------------------------------------------------- group-by over scale factors 1..16
+    # (only on request: the table cardinalities grow as in Section 4.1; rows/s over sf is the scaling curve)
+    if args.only == "sfsweep":
+        import math
+        cells = {}
+        for sf in (1, 2, 4, 8, 16):
+            rows_sf = (2_556, 30_000 * sf, 2_000 * sf, int(200_000 * (1 + math.log2(sf))))
+            g = WL.c3_groupby(device=dev, n=6_000_000 * sf, dim_rows=rows_sf)
+            copies = max(1, 8 // sf)                      # rotate copies while the columns would fit in cache
+            cols = [([f.clone() for f in g.fks], [m.clone() for m in g.measures]) for _ in range(copies)]
+            ws = torch.empty(lq.lq_groupby_workspace_bytes(g.dim_rows, g.group_card, 1), dtype=torch.uint8, device=dev)
+            sums = torch.empty((1, g.G), dtype=torch.int64, device=dev)
+            counts = torch.empty((g.G,), dtype=torch.int64, device=dev)
+            it = [0]
+
+            def gb():
+                fk, me = cols[it[0] % copies]
+                it[0] += 1
+                lq.lq_masked_groupby_sum(fk, g.dim_rows, g.dim_mask, g.dim_code, g.group_card, None, me,
+                                         sums=sums, counts=counts, ws=ws)
+            ms, mn, _ = time_call(gb, 20, 4)
+            cells[f"sf{sf}"] = {"fact_rows": g.n, "dim_rows": list(rows_sf), "ms": round(ms, 4),
+                                "rows_per_s": g.n / (ms * 1e-3), "GBps": 20.0 * g.n / (ms * 1e-3) / 1e9}
+            del g, cols, ws
+            torch.cuda.empty_cache()
+        out["groupby_sf_sweep"] = cells
 
     print(json.dumps(out))
 
