@@ -67,7 +67,7 @@ def main():
     ap.add_argument("--rows", type=int, default=10_000_000, help="fact rows of the headline workload")
     ap.add_argument("--no-extras", action="store_true", help="skip materialised / group-by / skewed legs")
     ap.add_argument("--no-cpu", action="store_true", help="skip the CPU oracle baseline")
-    ap.add_argument("--only", default="", help="run a single leg for profiling: fused|groupby|groupby16|c4|c5|tree|keymap|agg|sweep|sfsweep|materialized|copy")
+    ap.add_argument("--only", default="", help="run a single leg for profiling: fused|groupby|groupby16|c4|c5|tree|keymap|agg|domain|sweep|sfsweep|materialized|copy")
     args = ap.parse_args()
     if args.gpus != 1:
         sys.exit("bench.py: this build is single-GPU by design (no collectives, no sharding); "
@@ -333,6 +333,27 @@ def main():
         out["agg_one_join"] = {"rows_per_s": na / (ms * 1e-3), "ms": ms, "fact_rows": na,
                                "roofline": {"bound": "hbm", "achieved": gbps, "peak": HBM_PEAK_GBPS, "unit": "GB/s",
                                             "frac": gbps / HBM_PEAK_GBPS, "algorithmic_bytes_per_row": 16}}
+
+    # ---------------------------------------------------------------- group discovery + ORDER BY (query set-up / tail)
+    if (args.only == "" and not args.no_extras) or args.only == "domain":
+        gen = torch.Generator(device=dev); gen.manual_seed(WL.SEED0 + 960)
+        rd = 1_400_000                                                       # part dimension at sf 16
+        a5 = torch.randint(0, 5, (rd,), generator=gen, device=dev, dtype=torch.int32) * 11 + 3
+        b25 = a5 * 5 + torch.randint(0, 5, (rd,), generator=gen, device=dev, dtype=torch.int32)
+        dms, _, _ = time_call(lambda: lq.lq_group_domain([a5, b25]), 10, 2)   # includes its one host wait
+        Gd = 7 * 25
+        cnt = torch.randint(0, 1000, (Gd,), generator=gen, device=dev, dtype=torch.int64)
+        sm = torch.randint(0, 1 << 40, (1, Gd), generator=gen, device=dev, dtype=torch.int64)
+        o_buf = torch.empty(8192, dtype=torch.int32, device=dev)
+        n_buf = torch.empty(1, dtype=torch.int32, device=dev)
+        oms, _, _ = time_call(lambda: lq.lq_order_groups([7, 25], sm, cnt, [(0, 0, False), (1, 0, True)],
+                                                         order=o_buf, n_out=n_buf), 20, 3)
+        cnt8 = torch.randint(0, 3, (8192,), generator=gen, device=dev, dtype=torch.int64)
+        sm8 = torch.randint(0, 1 << 40, (1, 8192), generator=gen, device=dev, dtype=torch.int64)
+        oms8, _, _ = time_call(lambda: lq.lq_order_groups([64, 128], sm8, cnt8, [(1, 0, True)],
+                                                          order=o_buf, n_out=n_buf), 20, 3)
+        out["group_domain_and_order"] = {"group_domain_ms": dms, "dim_rows": rd, "columns": 2, "groups": 25,
+                                         "order_175_groups_ms": oms, "order_8192_groups_ms": oms8}
 
     # ---------------------------------------------------------------- k x l sweep (setting 1, sf 4, linear operator)
     if (args.only == "" and not args.no_extras) or args.only == "sweep":

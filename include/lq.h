@@ -344,6 +344,56 @@ int lq_compact_matches(const int32_t* fk, int64_t n, int64_t* rows, int32_t* col
 size_t lq_compact_workspace_bytes(int64_t n);
 
 /*
+ * Group discovery for one table (Sections 2.4.1-2.4.2): the groups are the distinct values of an
+ * attribute (one column) or the distinct tuples of several (the paper's sort-unique); they are
+ * numbered in ascending lexicographic order, first column most significant, signed comparison.
+ *   cols      host array of n_cols (1..4) device pointers, int32 [rows]
+ *   max_card  most groups the caller has room for (1..65535)
+ *   code      device int32 [rows]: out, the group number of every row -- the dim_code argument of
+ *             lq_masked_groupby_sum / lq_groupby_agg
+ *   values    device int32 [max_card x n_cols], row-major: out, row g = the tuple of group g
+ *   card      HOST int32: out, the number of groups -- the matching group_card entry
+ *   ws        lq_group_domain_workspace_bytes(rows) bytes, 256-byte aligned
+ * The call waits for the stream once (it has to learn the number of groups).  More than max_card
+ * groups: LQ_ERR_UNSUPPORTED, code and values are then undefined.  rows == 0 gives *card = 0.
+ * Because codes follow the sorted domain, a dense group-by result indexed by them is already in
+ * ascending order of the grouping attributes (Section 2.5).
+ */
+int lq_group_domain(int64_t rows, int32_t n_cols, const int32_t* const* cols, int32_t max_card,
+                    int32_t* code, int32_t* values, int32_t* card, void* ws, size_t ws_bytes,
+                    void* hip_stream);
+size_t lq_group_domain_workspace_bytes(int64_t rows);
+
+/* Sort keys of lq_order_groups. */
+#define LQ_KEY_GROUP_COLUMN 0 /* the code of grouping column `index` (position among the grouping dimensions) */
+#define LQ_KEY_SUM 1          /* sums[index][g] */
+#define LQ_KEY_COUNT 2        /* counts[g] */
+typedef struct {
+  int32_t kind;       /* LQ_KEY_* */
+  int32_t index;
+  int32_t descending; /* 0 = ascending */
+} lq_sort_key;
+
+/*
+ * ORDER BY on the result of lq_masked_groupby_sum / lq_groupby_agg (Section 2.5 covers sorting
+ * on the join / grouping keys through the sorted domain; sorting by an aggregate is not linear
+ * algebra and is done here on the small dense result).  The populated groups (counts[g] > 0) are
+ * put in the order given by keys[0], keys[1], ...; remaining ties go by ascending group index, so
+ * the result is unique.  Group g decomposes as a mixed-radix number over group_card, last column
+ * fastest, exactly as the group-by builds it.
+ *   group_card  host array of the n_group_cols (0..LQ_MAX_DIMS) cardinalities of the grouping
+ *               dimensions, in dimension order; G = their product <= 8192
+ *   sums        device int64 [n_measures x G] (may be NULL if no key uses it); counts device int64 [G]
+ *   keys        host array of n_keys (0..4) sort keys
+ *   order       device int32 [G]: out, the populated groups in order, then -1s
+ *   n_out       device int32: out, the number of populated groups
+ * Asynchronous; one small workgroup.
+ */
+int lq_order_groups(int32_t n_group_cols, const int32_t* group_card, int32_t n_measures,
+                    const int64_t* sums, const int64_t* counts, int32_t n_keys,
+                    const lq_sort_key* keys, int32_t* order, int32_t* n_out, void* hip_stream);
+
+/*
  * Plain device-to-device copy of `bytes` bytes (16-byte aligned pointers, bytes a
  * multiple of 16) by a grid-stride kernel.  Not part of the method: it is the
  * yardstick the benchmarks use for "what a pure stream reaches on this GPU".

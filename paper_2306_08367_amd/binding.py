@@ -23,6 +23,7 @@ LQ_CALL_MATERIALIZED = 2
 LQ_F32, LQ_BF16 = 0, 1
 LQ_CHECK_KEYS = 2
 LQ_REUSE_SIDE_TABLES = 4
+LQ_KEY_GROUP_COLUMN, LQ_KEY_SUM, LQ_KEY_COUNT = 0, 1, 2
 _STATUS = {8: "LQ_ERR_DUPLICATE_KEY", 1: "LQ_ERR_NULL", 2: "LQ_ERR_SHAPE", 3: "LQ_ERR_DTYPE", 4: "LQ_ERR_WORKSPACE",
            5: "LQ_ERR_FK_RANGE", 6: "LQ_ERR_UNSUPPORTED", 7: "LQ_ERR_HIP"}
 
@@ -50,6 +51,10 @@ class lq_range_pred(ctypes.Structure):
 
 class lq_measure(ctypes.Structure):
     _fields_ = [("op", ctypes.c_int32), ("a", ctypes.c_void_p), ("b", ctypes.c_void_p)]
+
+
+class lq_sort_key(ctypes.Structure):
+    _fields_ = [("kind", ctypes.c_int32), ("index", ctypes.c_int32), ("descending", ctypes.c_int32)]
 
 
 class lq_advice(ctypes.Structure):
@@ -110,6 +115,12 @@ def _load():
     lib.lq_compact_matches.argtypes = [vp, i64, vp, vp, vp, vp, sz, vp]
     lib.lq_compact_workspace_bytes.argtypes = [i64]
     lib.lq_compact_workspace_bytes.restype = sz
+    lib.lq_group_domain.argtypes = [i64, i32, ctypes.POINTER(vp), i32, vp, vp, ctypes.POINTER(i32), vp, sz, vp]
+    lib.lq_group_domain.restype = ctypes.c_int
+    lib.lq_group_domain_workspace_bytes.argtypes = [i64]
+    lib.lq_group_domain_workspace_bytes.restype = sz
+    lib.lq_order_groups.argtypes = [i32, ctypes.POINTER(i32), i32, vp, vp, i32, ctypes.POINTER(lq_sort_key), vp, vp, vp]
+    lib.lq_order_groups.restype = ctypes.c_int
     pt = ctypes.POINTER(lq_tree)
     lib.lq_tree_table_ld.argtypes = [i32]
     lib.lq_tree_table_ld.restype = i64
@@ -474,6 +485,66 @@ def lq_compact_matches(fk: torch.Tensor, stream=None):
     _check(_lib.lq_compact_matches(fk.data_ptr(), n, rows.data_ptr(), cols.data_ptr(), nnz.data_ptr(),
                                    ws.data_ptr(), ws.numel(), _stream(stream)))
     return rows, cols, nnz
+
+
+# ---------------------------------------------------------------- group discovery, result ordering
+
+def lq_group_domain_workspace_bytes(rows: int) -> int:
+    return int(_lib.lq_group_domain_workspace_bytes(int(rows)))
+
+
+def lq_group_domain(cols: Sequence[torch.Tensor], max_card: int = 65535, stream=None):
+    """Distinct tuples of the attribute columns of one table, numbered in ascending order.
+    Returns (code int32 [rows], values int32 [card x n_cols], card)."""
+    for c in cols:
+        _expect(c, torch.int32, "attribute column")
+        if c.shape[0] != cols[0].shape[0]:
+            raise ValueError("attribute columns differ in length")
+    rows = int(cols[0].shape[0])
+    dev = cols[0].device
+    code = torch.empty(rows, dtype=torch.int32, device=dev)
+    values = torch.empty((int(max_card), len(cols)), dtype=torch.int32, device=dev)
+    ws = torch.empty(lq_group_domain_workspace_bytes(rows), dtype=torch.uint8, device=dev)
+    card = ctypes.c_int32(0)
+    _check(_lib.lq_group_domain(rows, len(cols), _ptr_array(cols), int(max_card), code.data_ptr(),
+                                values.data_ptr(), ctypes.byref(card), ws.data_ptr(), ws.numel(), _stream(stream)))
+    return code, values[:card.value], int(card.value)
+
+
+def lq_order_groups(group_card: Sequence[int], sums: Optional[torch.Tensor], counts: torch.Tensor,
+                    keys: Sequence[Sequence[int]], order: Optional[torch.Tensor] = None,
+                    n_out: Optional[torch.Tensor] = None, stream=None):
+    """ORDER BY over the populated groups.  keys: (kind, index, descending) triples.
+    Returns (order int32 [G] padded with -1, n_out int32 [1]), both on the device."""
+    _expect(counts, torch.int64, "counts")
+    G = int(counts.shape[0])
+    n_measures = 0
+    if sums is not None:
+        _expect(sums, torch.int64, "sums")
+        if sums.dim() != 2 or sums.shape[1] != G or not sums.is_contiguous():
+            raise ValueError("sums must be a contiguous [n_measures x G] tensor")
+        n_measures = int(sums.shape[0])
+    prod = 1
+    for c in group_card:
+        prod *= int(c)
+    if prod != G:
+        raise ValueError("counts length differs from the product of group_card")
+    card = (ctypes.c_int32 * max(1, len(group_card)))(*[int(c) for c in group_card])
+    karr = (lq_sort_key * max(1, len(keys)))()
+    for q, (kind, index, desc) in enumerate(keys):
+        karr[q] = lq_sort_key(int(kind), int(index), int(bool(desc)))
+    if order is None:
+        order = torch.empty(G, dtype=torch.int32, device=counts.device)
+    if n_out is None:
+        n_out = torch.empty(1, dtype=torch.int32, device=counts.device)
+    _expect(order, torch.int32, "order")
+    _expect(n_out, torch.int32, "n_out")
+    if order.numel() < G or n_out.numel() < 1:
+        raise ValueError("order needs G entries and n_out one")
+    _check(_lib.lq_order_groups(len(group_card), card, n_measures, None if sums is None else sums.data_ptr(),
+                                counts.data_ptr(), len(keys), karr, order.data_ptr(), n_out.data_ptr(),
+                                _stream(stream)))
+    return order, n_out
 
 
 # ---------------------------------------------------------------- incremental pre-fusion, advice
