@@ -8,6 +8,12 @@
 //                        fp32 inputs use the 32x32x2 f32 MFMA; bf16 inputs stay bf16 in LDS and
 //                        use the 32x32x16 bf16 MFMA.  The next k-tile is fetched into registers
 //                        while the current one is multiplied.
+//   gemm_rowsplit_kernel - fp32, N <= 16, 32 <= K: the shape of projecting a wide dimension table
+//                        onto a handful of outputs, bound by reading A once.  The lanes of a
+//                        wavefront read A as contiguous 16-byte pieces (a row is split over 8..64
+//                        neighbouring lanes), multiply with the weights held in LDS and sum over
+//                        the lanes of a row with DPP adds: no matrix cores, every load a full
+//                        coalesced run.
 //   gemm_skinny_kernel - N <= 16 (linear models with a handful of outputs).  Bandwidth-shaped:
 //                        no LDS, every wavefront streams 16 rows of A at a time straight into
 //                        16x16 MFMA operands; B is tiny and comes from cache.
@@ -301,6 +307,123 @@ int launch_typed(GemmArgs g, hipStream_t s) {
   return LQ_OK;
 }
 
+// ------------------------------------------------------------------ row split ----------
+
+constexpr int RS_THREADS = 256;
+
+template <int CTRL> __device__ __forceinline__ float rs_dpp(float v) {
+  return __int_as_float(__builtin_amdgcn_update_dpp(0, __float_as_int(v), CTRL, 0xf, 0xf, false));
+}
+// Sum over groups of LPR adjacent lanes (8, 16, 32 or 64), result in every lane of the group.
+template <int LPR> __device__ __forceinline__ float rs_allreduce(float y) {
+  y += rs_dpp<0xB1>(y);                  // quad_perm [1,0,3,2]
+  y += rs_dpp<0x4E>(y);                  // quad_perm [2,3,0,1]
+  y += rs_dpp<0x141>(y);                 // row_half_mirror
+  if (LPR >= 16) y += rs_dpp<0x140>(y);  // row_mirror
+  if (LPR >= 32) y += __shfl_xor(y, 16, 64);
+  if (LPR >= 64) y += __shfl_xor(y, 32, 64);
+  return y;
+}
+
+// LPR lanes share a row (piece c, c + LPR, ... of its K / 4 pieces); a wavefront works on
+// U x (64 / LPR) rows per step, all loads of a step issued before the first is used.
+// NN = N rounded up to 4, 8 or 16; the weights sit in LDS as [K][NN] with zero padding.
+template <int LPR, int NN>
+__global__ __launch_bounds__(RS_THREADS) void gemm_rowsplit_kernel(GemmArgs g) {
+  constexpr int RPW = 64 / LPR;             // rows per wavefront and sub-step
+  constexpr int U = NN == 16 ? 2 : 4;       // sub-steps in flight
+  extern __shared__ __align__(16) float Bs[];
+  const float* __restrict__ A = static_cast<const float*>(g.A);
+  const float* __restrict__ B = static_cast<const float*>(g.B);
+  for (int idx = threadIdx.x; idx < g.Kd * NN; idx += RS_THREADS) {
+    const int k = idx / NN, n = idx - k * NN;
+    Bs[idx] = n < g.N ? B[static_cast<int64_t>(k) * g.ldb + n] : 0.f;
+  }
+  __syncthreads();
+  const int lane = threadIdx.x & 63, c = lane % LPR, sub = lane / LPR;
+  const int ppr = g.Kd / 4;                 // 16-byte pieces per row
+  const int64_t wave = static_cast<int64_t>(blockIdx.x) * (RS_THREADS / 64) + (threadIdx.x >> 6);
+  const int64_t nwaves = static_cast<int64_t>(gridDim.x) * (RS_THREADS / 64);
+  const int64_t nsteps = (g.M + RPW * U - 1) / (RPW * U);
+  float bv[NN];
+#pragma unroll
+  for (int n = 0; n < NN; ++n) bv[n] = (g.bias && n < g.N) ? static_cast<const float*>(g.bias)[n] : 0.f;
+
+  for (int64_t step = wave; step < nsteps; step += nwaves) {
+    float acc[U][NN];
+#pragma unroll
+    for (int u = 0; u < U; ++u)
+#pragma unroll
+      for (int n = 0; n < NN; ++n) acc[u][n] = 0.f;
+    for (int p = c; p < ppr; p += LPR) {
+      v4f a[U];
+#pragma unroll
+      for (int u = 0; u < U; ++u) {
+        const int64_t row = (step * U + u) * RPW + sub;
+        a[u] = v4f{0.f, 0.f, 0.f, 0.f};
+        if (row < g.M) a[u] = __builtin_nontemporal_load(reinterpret_cast<const v4f*>(A + row * g.lda) + p);
+      }
+#pragma unroll
+      for (int t = 0; t < 4; ++t) {
+        float b[NN];
+#pragma unroll
+        for (int q = 0; q < NN / 4; ++q) {
+          const v4f bq = *reinterpret_cast<const v4f*>(Bs + (4 * p + t) * NN + 4 * q);
+          b[4 * q] = bq[0]; b[4 * q + 1] = bq[1]; b[4 * q + 2] = bq[2]; b[4 * q + 3] = bq[3];
+        }
+#pragma unroll
+        for (int u = 0; u < U; ++u)
+#pragma unroll
+          for (int n = 0; n < NN; ++n) acc[u][n] = fmaf(a[u][t], b[n], acc[u][n]);
+      }
+    }
+#pragma unroll
+    for (int u = 0; u < U; ++u) {
+#pragma unroll
+      for (int n = 0; n < NN; ++n) acc[u][n] = rs_allreduce<LPR>(acc[u][n]);
+      const int64_t row = (step * U + u) * RPW + sub;
+      if (c == 0 && row < g.M) {
+        float* cr = static_cast<float*>(g.C) + row * g.ldc;
+#pragma unroll
+        for (int n = 0; n < NN; ++n)
+          if (n < g.N) {
+            float x = acc[u][n] + bv[n];
+            if (g.relu) x = fmaxf(x, 0.f);
+            cr[n] = x;
+          }
+      }
+    }
+  }
+}
+
+template <int LPR>
+int launch_rowsplit_n(const GemmArgs& g, hipStream_t s) {
+  const int nn = g.N <= 4 ? 4 : (g.N <= 8 ? 8 : 16);
+  const size_t lds = static_cast<size_t>(g.Kd) * nn * sizeof(float);
+  const int rows_per_step = (64 / LPR) * (nn == 16 ? 2 : 4);
+  const int64_t nsteps = (g.M + rows_per_step - 1) / rows_per_step;
+  const int64_t blocks = std::min<int64_t>((nsteps + 3) / 4, static_cast<int64_t>(num_cus()) * 16);
+  const dim3 grid(static_cast<unsigned>(blocks)), block(RS_THREADS);
+  if (nn == 4) hipLaunchKernelGGL((gemm_rowsplit_kernel<LPR, 4>), grid, block, lds, s, g);
+  else if (nn == 8) hipLaunchKernelGGL((gemm_rowsplit_kernel<LPR, 8>), grid, block, lds, s, g);
+  else hipLaunchKernelGGL((gemm_rowsplit_kernel<LPR, 16>), grid, block, lds, s, g);
+  LQ_LAUNCH_CHECK("gemm_rowsplit_kernel");
+  return LQ_OK;
+}
+
+// Returns -1 when the shape is not one this kernel covers.  The choice depends on N, K, the row
+// stride and the alignment only, never on M, so a row computed alone equals the same row computed
+// as part of the whole table.
+int try_rowsplit(const GemmArgs& g, hipStream_t s) {
+  if (g.N > 16 || g.Kd < 32 || g.Kd % 4 || g.lda % 4 || !aligned(g.A, 16) || !aligned(g.C, 4)) return -1;
+  if (static_cast<size_t>(g.Kd) * 16 * sizeof(float) > 64 * 1024) return -1;
+  const int ppr = g.Kd / 4;
+  if (ppr <= 8) return launch_rowsplit_n<8>(g, s);
+  if (ppr <= 16) return launch_rowsplit_n<16>(g, s);
+  if (ppr <= 32) return launch_rowsplit_n<32>(g, s);
+  return launch_rowsplit_n<64>(g, s);
+}
+
 }  // namespace
 
 // C[M x N] = act(A[M x Kd] * B[Kd x N] + bias).  A, B, bias share `in_dtype`.
@@ -310,7 +433,13 @@ int launch_gemm(const void* A, int64_t lda, const void* B, int64_t ldb, void* C,
   GemmArgs g{};
   g.A = A; g.lda = lda; g.B = B; g.ldb = ldb; g.C = C; g.ldc = ldc; g.bias = bias;
   g.M = M; g.N = N; g.Kd = Kd; g.relu = relu;
-  if (in_dtype == LQ_F32 && out_dtype == LQ_F32) return launch_typed<float, float>(g, s);
+  if (in_dtype == LQ_F32 && out_dtype == LQ_F32) {
+    if (M > 0 && N > 0) {
+      const int rc = try_rowsplit(g, s);
+      if (rc >= 0) return rc;
+    }
+    return launch_typed<float, float>(g, s);
+  }
   if (in_dtype == LQ_BF16 && out_dtype == LQ_F32) return launch_typed<bf16_t, float>(g, s);
   if (in_dtype == LQ_BF16 && out_dtype == LQ_BF16) return launch_typed<bf16_t, bf16_t>(g, s);
   return fail(LQ_ERR_DTYPE, "gemm: f32 inputs cannot produce a bf16 result");
