@@ -320,12 +320,18 @@ size_t lq_keymap_bytes(int64_t max_keys);
  * Build the map from the n_keys int32 keys of a dimension (device array; key of row j at keys[j];
  * keys must be unique).  With LQ_CHECK_KEYS the call waits and returns LQ_ERR_DUPLICATE_KEY if a
  * value occurs twice; otherwise a duplicate silently keeps the row that got there first.
+ * The map takes one of two forms, decided on the device from the key range: if largest - smallest
+ * key is below the number of 4-byte cells of the buffer (at least 4 x max_keys) it is a direct
+ * array indexed by key - smallest key, otherwise a hash table.  Lookups give the same answers
+ * either way.
  */
 int lq_keymap_build(void* table, size_t table_bytes, const int32_t* keys, int64_t n_keys,
                     uint32_t flags, void* hip_stream);
 
 /* Add the keys of rows first_row .. first_row + n_keys - 1 to an existing map (the update of a
- * cached domain).  The map must have been sized for the total number of keys. */
+ * cached domain).  The map must have been sized for the total number of keys.  A direct map only
+ * takes keys inside its window [smallest key at build, + number of cells): a key outside it is
+ * not added, and LQ_CHECK_KEYS reports LQ_ERR_WORKSPACE (rebuild the map with all keys then). */
 int lq_keymap_insert(void* table, size_t table_bytes, const int32_t* keys, int64_t n_keys,
                      int64_t first_row, uint32_t flags, void* hip_stream);
 

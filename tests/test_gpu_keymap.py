@@ -98,3 +98,65 @@ def test_mapped_keys_feed_the_group_by(lq):
     torch.cuda.synchronize()
     np.testing.assert_array_equal(s.cpu().numpy(), want_s)
     np.testing.assert_array_equal(c.cpu().numpy(), want_c)
+
+
+def _is_direct(table):
+    return int(table[12:16].view(torch.int32).item()) == 1
+
+
+def _dense_keys(seed, r, n, base, fill=0.7, miss=0.05):
+    """r distinct keys out of a window of r / fill consecutive integers starting at `base`, shuffled."""
+    g = np.random.default_rng(seed)
+    window = np.arange(int(r / fill) + 1, dtype=np.int64) + base
+    g.shuffle(window)
+    key_S = window[:r].astype(np.int32)
+    key_R = g.choice(window, size=n).astype(np.int32)              # some hit the gaps: no match
+    m = g.random(n) < miss
+    key_R[m] = (base - 1 - g.integers(0, 1000, size=int(m.sum()))).astype(np.int32)   # and some lie outside the window
+    return key_S, key_R
+
+
+@pytest.mark.parametrize("r,n,base", [(1, 10, 5), (2_556, 1_300_001, 19920101), (2_000, 100_003, 1), (30_000, 1_200_000, 1),
+                                      (200_000, 1_000_003, -150_000), (8_192, 1_048_576, -2**31 + 1000)])
+def test_dense_key_ranges_use_the_direct_form(lq, r, n, base):
+    key_S, key_R = _dense_keys(r + n, r, n, base)
+    fk_w, rows_w, cols_w = MJ.key_to_row(key_R, key_S)
+    table = lq.lq_keymap_build(torch.from_numpy(key_S).cuda(), flags=lq.LQ_CHECK_KEYS)
+    assert _is_direct(table)
+    fk = lq.lq_keymap_lookup(table, torch.from_numpy(key_R).cuda())
+    torch.cuda.synchronize()
+    np.testing.assert_array_equal(fk.cpu().numpy(), fk_w)
+    # unaligned key columns take the one-key-per-thread path
+    kr = torch.empty(n + 1, dtype=torch.int32, device="cuda")
+    kr[1:] = torch.from_numpy(key_R)
+    np.testing.assert_array_equal(lq.lq_keymap_lookup(table, kr[1:]).cpu().numpy(), fk_w)
+
+
+def test_sparse_key_ranges_use_the_hashed_form(lq):
+    key_S, key_R = _keys(17, 5_000, 1_100_000)
+    table = lq.lq_keymap_build(torch.from_numpy(key_S).cuda(), flags=lq.LQ_CHECK_KEYS)
+    assert not _is_direct(table)
+    fk_w, _, _ = MJ.key_to_row(key_R, key_S)
+    np.testing.assert_array_equal(lq.lq_keymap_lookup(table, torch.from_numpy(key_R).cuda()).cpu().numpy(), fk_w)
+
+
+def test_direct_form_duplicates_and_inserts(lq):
+    keys = torch.tensor([5, 9, 5, 3], dtype=torch.int32, device="cuda")
+    with pytest.raises(lq.LQError) as e:
+        lq.lq_keymap_build(keys, flags=lq.LQ_CHECK_KEYS)
+    assert e.value.status == "LQ_ERR_DUPLICATE_KEY"
+    # surrogate keys 1..r, new dimension rows appended with the next keys: inside the window
+    key_S = np.arange(1, 40_001, dtype=np.int32)
+    g = np.random.default_rng(3)
+    key_R = g.integers(-5, 40_020, size=500_000).astype(np.int32)
+    part = lq.lq_keymap_build(torch.from_numpy(key_S[:25_000]).cuda(), max_keys=40_000)
+    assert _is_direct(part)
+    lq.lq_keymap_insert(part, torch.from_numpy(key_S[25_000:]).cuda(), 25_000, flags=lq.LQ_CHECK_KEYS)
+    fk_w, _, _ = MJ.key_to_row(key_R, key_S)
+    np.testing.assert_array_equal(lq.lq_keymap_lookup(part, torch.from_numpy(key_R).cuda()).cpu().numpy(), fk_w)
+    # a key far outside the window cannot be added to a direct map: reported, the map stays usable
+    with pytest.raises(lq.LQError) as e:
+        lq.lq_keymap_insert(part, torch.tensor([2_000_000_000], dtype=torch.int32, device="cuda"), 40_000,
+                            flags=lq.LQ_CHECK_KEYS)
+    assert e.value.status == "LQ_ERR_WORKSPACE"
+    np.testing.assert_array_equal(lq.lq_keymap_lookup(part, torch.from_numpy(key_R).cuda()).cpu().numpy(), fk_w)
