@@ -38,6 +38,14 @@ struct GemmArgs {
   int32_t tiles_n;
 };
 
+// Up to LQ_MAX_DIMS independent products of the same type in one launch (the projections of all
+// dimension tables): workgroup b works on problem p where first_tile[p] <= b < first_tile[p + 1].
+struct GemmBatch {
+  GemmArgs g[LQ_MAX_DIMS];
+  int32_t first_tile[LQ_MAX_DIMS + 1];
+  int32_t count;
+};
+
 // ------------------------------------------------------------------ tiled --------------
 
 constexpr int BM = 128;
@@ -73,7 +81,11 @@ __device__ __forceinline__ v4u load_chunk(const T* p, int valid, bool vec_ok) {
 }
 
 template <typename TA, typename TC, int BN>
-__global__ __launch_bounds__(TILED_THREADS) void gemm_tiled_kernel(GemmArgs g) {
+__global__ __launch_bounds__(TILED_THREADS) void gemm_tiled_kernel(GemmBatch batch) {
+  int problem = 0;
+  while (problem + 1 < batch.count && static_cast<int32_t>(blockIdx.x) >= batch.first_tile[problem + 1]) ++problem;
+  const GemmArgs g = batch.g[problem];
+  const int64_t tile = static_cast<int64_t>(blockIdx.x) - batch.first_tile[problem];
   constexpr int BK = Tile<TA>::BK, VEC = Tile<TA>::VEC;
   constexpr bool F32 = sizeof(TA) == 4;
   constexpr int WN = BN / 2;              // columns per wavefront
@@ -94,8 +106,8 @@ __global__ __launch_bounds__(TILED_THREADS) void gemm_tiled_kernel(GemmArgs g) {
   const TA* __restrict__ B = static_cast<const TA*>(g.B);
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   const int wm = wave >> 1, wn = wave & 1;
-  const int64_t tile_m = static_cast<int64_t>(blockIdx.x) / g.tiles_n;
-  const int tile_n = static_cast<int>(static_cast<int64_t>(blockIdx.x) % g.tiles_n);
+  const int64_t tile_m = tile / g.tiles_n;
+  const int tile_n = static_cast<int>(tile % g.tiles_n);
   const int64_t m0 = tile_m * BM;
   const int n0 = tile_n * BN;
 
@@ -277,6 +289,31 @@ __global__ __launch_bounds__(SKINNY_THREADS) void gemm_skinny_kernel(GemmArgs g)
   }
 }
 
+// All problems of the batch share N (hence the tile width) and the element types.
+template <typename TA, typename TC>
+int launch_tiled_batch(GemmBatch& b, hipStream_t s) {
+  const bool wide = b.g[0].N > 64;
+  const int bn = wide ? 128 : 64;
+  int64_t blocks = 0;
+  for (int p = 0; p < b.count; ++p) {
+    GemmArgs& g = b.g[p];
+    g.a_vec_ok = aligned(g.A, 16) && (g.lda * sizeof(TA)) % 16 == 0;
+    g.b_vec_ok = aligned(g.B, 16) && (g.ldb * sizeof(TA)) % 16 == 0;
+    g.tiles_n = (g.N + bn - 1) / bn;
+    b.first_tile[p] = static_cast<int32_t>(blocks);
+    blocks += (g.M + BM - 1) / BM * g.tiles_n;
+    if (blocks > 0x7fffffffLL) return fail(LQ_ERR_UNSUPPORTED, "gemm: %lld tiles exceed one grid", (long long)blocks);
+  }
+  b.first_tile[b.count] = static_cast<int32_t>(blocks);
+  if (blocks == 0) return LQ_OK;
+  if (wide)
+    hipLaunchKernelGGL((gemm_tiled_kernel<TA, TC, 128>), dim3(static_cast<unsigned>(blocks)), dim3(TILED_THREADS), 0, s, b);
+  else
+    hipLaunchKernelGGL((gemm_tiled_kernel<TA, TC, 64>), dim3(static_cast<unsigned>(blocks)), dim3(TILED_THREADS), 0, s, b);
+  LQ_LAUNCH_CHECK("gemm_tiled_kernel");
+  return LQ_OK;
+}
+
 template <typename TA, typename TC>
 int launch_typed(GemmArgs g, hipStream_t s) {
   if (g.M <= 0 || g.N <= 0) return LQ_OK;
@@ -293,18 +330,10 @@ int launch_typed(GemmArgs g, hipStream_t s) {
     LQ_LAUNCH_CHECK("gemm_skinny_kernel");
     return LQ_OK;
   }
-  const bool wide = g.N > 64;
-  const int bn = wide ? 128 : 64;
-  const int64_t tiles_m = (g.M + BM - 1) / BM;
-  g.tiles_n = (g.N + bn - 1) / bn;
-  const int64_t blocks = tiles_m * g.tiles_n;
-  if (blocks > 0x7fffffffLL) return fail(LQ_ERR_UNSUPPORTED, "gemm: %lld tiles exceed one grid", (long long)blocks);
-  if (wide)
-    hipLaunchKernelGGL((gemm_tiled_kernel<TA, TC, 128>), dim3(static_cast<unsigned>(blocks)), dim3(TILED_THREADS), 0, s, g);
-  else
-    hipLaunchKernelGGL((gemm_tiled_kernel<TA, TC, 64>), dim3(static_cast<unsigned>(blocks)), dim3(TILED_THREADS), 0, s, g);
-  LQ_LAUNCH_CHECK("gemm_tiled_kernel");
-  return LQ_OK;
+  GemmBatch b{};
+  b.g[0] = g;
+  b.count = 1;
+  return launch_tiled_batch<TA, TC>(b, s);
 }
 
 // ------------------------------------------------------------------ row split ----------
@@ -442,6 +471,42 @@ int launch_gemm(const void* A, int64_t lda, const void* B, int64_t ldb, void* C,
   }
   if (in_dtype == LQ_BF16 && out_dtype == LQ_F32) return launch_typed<bf16_t, float>(g, s);
   if (in_dtype == LQ_BF16 && out_dtype == LQ_BF16) return launch_typed<bf16_t, bf16_t>(g, s);
+  return fail(LQ_ERR_DTYPE, "gemm: f32 inputs cannot produce a bf16 result");
+}
+
+int launch_project_dims(const lq_mat& D, const lq_mat& W, int32_t row_off, const lq_mat& P, hipStream_t s);
+
+// P_k = D_k W[off_k .. off_k + c_k) for all K dimensions; one launch when the tiled kernel serves them.
+int launch_project_dims_all(int32_t K, const lq_mat* D, const lq_mat& W, int32_t first_off, const lq_mat* P,
+                            hipStream_t s) {
+  const size_t es = dtype_size(W.dtype);
+  bool batch = K > 1 && W.cols > 16;
+  for (int k = 0; k < K && batch; ++k) batch = D[k].dtype == D[0].dtype && P[k].dtype == P[0].dtype;
+  if (!batch) {
+    int32_t off = first_off;
+    for (int k = 0; k < K; ++k) {
+      const int rc = launch_project_dims(D[k], W, off, P[k], s);
+      if (rc) return rc;
+      off += D[k].cols;
+    }
+    return LQ_OK;
+  }
+  GemmBatch b{};
+  int32_t off = first_off;
+  for (int k = 0; k < K; ++k) {
+    GemmArgs& g = b.g[b.count];
+    g.A = D[k].data; g.lda = D[k].ld;
+    g.B = static_cast<const char*>(W.data) + static_cast<size_t>(off) * W.ld * es; g.ldb = W.ld;
+    g.C = P[k].data; g.ldc = P[k].ld;
+    g.M = D[k].rows; g.N = W.cols; g.Kd = D[k].cols;
+    off += D[k].cols;
+    if (g.M > 0) ++b.count;
+  }
+  if (b.count == 0) return LQ_OK;
+  const int32_t in = D[0].dtype, out = P[0].dtype;
+  if (in == LQ_F32 && out == LQ_F32) return launch_tiled_batch<float, float>(b, s);
+  if (in == LQ_BF16 && out == LQ_F32) return launch_tiled_batch<bf16_t, float>(b, s);
+  if (in == LQ_BF16 && out == LQ_BF16) return launch_tiled_batch<bf16_t, bf16_t>(b, s);
   return fail(LQ_ERR_DTYPE, "gemm: f32 inputs cannot produce a bf16 result");
 }
 

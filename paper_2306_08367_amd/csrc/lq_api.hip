@@ -199,12 +199,8 @@ int lq_project_dims(const lq_star* star, const lq_model* model, lq_mat* P, void*
       return fail(LQ_ERR_DTYPE, "%s: bf16 projected tables need a bf16 model", name);
   }
   hipStream_t s = static_cast<hipStream_t>(hip_stream);
-  int32_t off = star->fact.cols > 0 ? star->fact.cols : 0;
-  for (int k = 0; k < star->n_dims; ++k) {
-    if ((rc = launch_project_dims(star->dims[k], model->W[0], off, P[k], s))) return rc;
-    off += star->dims[k].cols;
-  }
-  return LQ_OK;
+  const int32_t off = star->fact.cols > 0 ? star->fact.cols : 0;
+  return launch_project_dims_all(star->n_dims, star->dims, model->W[0], off, P, s);
 }
 
 int lq_project_dim_rows(const lq_star* star, const lq_model* model, lq_mat* P, int32_t dim,

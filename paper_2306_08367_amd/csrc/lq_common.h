@@ -68,6 +68,8 @@ struct PredictArgs {
 // Kernel launchers implemented in the .hip files.  Each returns an lq_status.
 int launch_project_dims(const lq_mat& D, const lq_mat& W, int32_t row_off, const lq_mat& P,
                         hipStream_t s);
+int launch_project_dims_all(int32_t K, const lq_mat* D, const lq_mat& W, int32_t first_off, const lq_mat* P,
+                            hipStream_t s);
 int launch_fused(const PredictArgs& a, hipStream_t s);
 int launch_materialize(const lq_star& star, void* T, int64_t ldt, int64_t row0, int64_t rows,
                        hipStream_t s);
