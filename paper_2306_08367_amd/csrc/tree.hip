@@ -61,6 +61,69 @@ __global__ __launch_bounds__(256) void tree_project_kernel(TreeArgs t, const flo
 }
 
 
+// Bit-mask version for trees of up to 256 nodes.  A wavefront takes one dimension row at a time:
+// lane i evaluates node 64 w + i (if this dimension owns it) and a ballot packs the outcomes of 64
+// nodes into one word; lane j then holds leaf j and counts the agreements with two popcounts per
+// word against the +1 / -1 node masks of its path, which it built once from its column of H.
+// r * (p + l) / 64 wavefront steps instead of r * l * p thread steps.
+template <int W>
+__global__ __launch_bounds__(256) void tree_project_bits_kernel(TreeArgs t, const float* __restrict__ D,
+                                                                int64_t ldd, int64_t rows, int32_t col_off,
+                                                                int32_t c, uint8_t* __restrict__ out) {
+  typedef unsigned long long u64;
+  const int lane = threadIdx.x & 63;
+  const int64_t wave = static_cast<int64_t>(blockIdx.x) * 4 + (threadIdx.x >> 6);
+  const int64_t nwaves = static_cast<int64_t>(gridDim.x) * 4;
+  int fcol[W];
+  float thr[W];
+#pragma unroll
+  for (int w = 0; w < W; ++w) {
+    const int q = 64 * w + lane;
+    fcol[w] = -1; thr[w] = 0.f;
+    if (q < t.p) {
+      const int f = t.feature[q] - col_off;
+      if (f >= 0 && f < c) { fcol[w] = f; thr[w] = t.thr[q]; }
+    }
+  }
+  for (int j0 = 0; j0 < t.ld; j0 += 64) {
+    const int j = j0 + lane;
+    u64 plus[W], minus[W];
+#pragma unroll
+    for (int w = 0; w < W; ++w) { plus[w] = 0; minus[w] = 0; }
+    if (j < t.l) {
+#pragma unroll
+      for (int w = 0; w < W; ++w)
+        for (int b = 0; b < 64 && 64 * w + b < t.p; ++b) {
+          const int q = 64 * w + b;
+          const int f = t.feature[q] - col_off;                // uniform: the same node for all lanes
+          if (f < 0 || f >= c) continue;                       // node owned by another table
+          const int hv = t.H[static_cast<int64_t>(q) * t.l + j];
+          if (hv > 0) plus[w] |= 1ull << b;
+          if (hv < 0) minus[w] |= 1ull << b;
+        }
+    }
+    for (int64_t r0 = wave * 4; r0 < rows; r0 += nwaves * 4) {
+      float v[4][W];
+#pragma unroll
+      for (int u = 0; u < 4; ++u) {
+        const int64_t r = min(r0 + u, rows - 1);
+#pragma unroll
+        for (int w = 0; w < W; ++w) v[u][w] = fcol[w] >= 0 ? D[r * ldd + fcol[w]] : 0.f;
+      }
+#pragma unroll
+      for (int u = 0; u < 4; ++u) {
+        int agree = 0;
+#pragma unroll
+        for (int w = 0; w < W; ++w) {
+          const u64 bits = __ballot(fcol[w] >= 0 && v[u][w] > thr[w]);
+          agree += __popcll(bits & plus[w]) + __popcll(~bits & minus[w]);
+        }
+        if (r0 + u < rows && j < t.ld) out[(r0 + u) * t.ld + j] = static_cast<uint8_t>(min(agree, 255));
+      }
+    }
+  }
+}
+
 // Sparse version of the same computation.  A column of H has at most 255 nonzeros (longer paths are
 // unsupported), so a workgroup first turns the H columns of its 64 leaves into per-leaf lists of the
 // nodes this dimension owns (node number, sign bit) in LDS and then walks only those lists for every
@@ -301,6 +364,15 @@ int lq_tree_project_dims(const lq_star* star, const lq_tree* tree, void* const* 
                          dim3(256), 0, s, t, static_cast<const float*>(d.data), d.ld, d.rows, off, d.cols,
                          static_cast<uint8_t*>(tables[k]), rpb);
       LQ_LAUNCH_CHECK("tree_project_sparse_kernel");
+    } else if (t.p <= 256) {
+      const int64_t blocks = std::max<int64_t>(1, std::min<int64_t>((d.rows + 15) / 16, static_cast<int64_t>(num_cus()) * 8));
+      const dim3 grid(static_cast<unsigned>(blocks)), block(256);
+      const float* dd = static_cast<const float*>(d.data);
+      uint8_t* tab = static_cast<uint8_t*>(tables[k]);
+      if (t.p <= 64) hipLaunchKernelGGL(tree_project_bits_kernel<1>, grid, block, 0, s, t, dd, d.ld, d.rows, off, d.cols, tab);
+      else if (t.p <= 128) hipLaunchKernelGGL(tree_project_bits_kernel<2>, grid, block, 0, s, t, dd, d.ld, d.rows, off, d.cols, tab);
+      else hipLaunchKernelGGL(tree_project_bits_kernel<4>, grid, block, 0, s, t, dd, d.ld, d.rows, off, d.cols, tab);
+      LQ_LAUNCH_CHECK("tree_project_bits_kernel");
     } else {
       const int64_t total = d.rows * t.ld;
       const int64_t blocks = std::min<int64_t>((total + 255) / 256, static_cast<int64_t>(num_cus()) * 32);
