@@ -254,6 +254,70 @@ __global__ __launch_bounds__(256) void fused_tree_kernel(FusedTreeArgs a) {
   if (a.leaf && live && c == 0) a.leaf[row] = first == 0x7fffffff ? -1 : first;
 }
 
+// The same join stage for trees of up to 256 leaves without fact-table nodes, organised so that a
+// wavefront has many gathers in flight: it owns 64 consecutive fact rows, reads their keys once,
+// coalesced (lane = row), and hands them to the G-lane groups through the cross-lane network; in
+// pass t group g works on row (64 / G) t + g.  The gathers of up to four passes are issued before
+// the first is consumed.
+template <int G>
+__global__ __launch_bounds__(256) void fused_tree_batch_kernel(FusedTreeArgs a) {
+  constexpr int RPP = 64 / G;                 // rows per pass
+  constexpr int PB = G < 4 ? G : 4;           // passes in flight together (G passes cover the 64 rows)
+  const int lane = threadIdx.x & 63, g = lane / G, c = lane % G;
+  const int64_t wave = static_cast<int64_t>(blockIdx.x) * 4 + (threadIdx.x >> 6);
+  const int64_t row0 = wave * 64;
+  if (row0 >= a.n) return;
+  const int64_t myrow = min(row0 + lane, a.n - 1);
+  int key[LQ_MAX_DIMS];
+#pragma unroll
+  for (int k = 0; k < LQ_MAX_DIMS; ++k) key[k] = k < a.K ? __builtin_nontemporal_load(a.fk[k] + myrow) : 0;
+  const bool active = c < a.chunks;
+  v4u tg = {0u, 0u, 0u, 0u};
+  if (active) tg = *reinterpret_cast<const v4u*>(a.target + 16 * c);
+  for (int pb = 0; pb < G; pb += PB) {
+    v4u sum[PB];
+#pragma unroll
+    for (int u = 0; u < PB; ++u) {
+      const int src = RPP * (pb + u) + g;     // the lane that holds this row's keys
+      sum[u] = v4u{0u, 0u, 0u, 0u};
+#pragma unroll
+      for (int k = 0; k < LQ_MAX_DIMS; ++k)
+        if (k < a.K) {
+          const int64_t j = __shfl(key[k], src, 64);
+          if (active) sum[u] += *reinterpret_cast<const v4u*>(a.T[k] + j * a.t.ld + 16 * c);
+        }
+    }
+#pragma unroll
+    for (int u = 0; u < PB; ++u) {
+      const int64_t row = row0 + RPP * (pb + u) + g;
+      const bool live = row < a.n;
+      int first = 0x7fffffff;
+      v4u hit = {0u, 0u, 0u, 0u};
+      if (active) {
+#pragma unroll
+        for (int d = 0; d < 4; ++d) {
+          hit[d] = zero_bytes(sum[u][d] ^ tg[d]);
+          if (hit[d] != 0u) first = min(first, 16 * c + 4 * d + (__builtin_ctz(hit[d]) >> 3));
+        }
+        if (a.onehot && live) {
+          uint8_t* o = a.onehot + row * a.t.l + 16 * c;
+          if (a.onehot_vec_ok && 16 * c + 16 <= a.t.l) {
+            const v4u ones = {hit[0] >> 7, hit[1] >> 7, hit[2] >> 7, hit[3] >> 7};
+            __builtin_nontemporal_store(ones, reinterpret_cast<v4u*>(o));
+          } else {
+#pragma unroll
+            for (int b = 0; b < 16; ++b)
+              if (16 * c + b < a.t.l) o[b] = static_cast<uint8_t>((hit[b >> 2] >> (8 * (b & 3) + 7)) & 1u);
+          }
+        }
+      }
+#pragma unroll
+      for (int m = 1; m < G; m <<= 1) first = min(first, __shfl_xor(first, m, 64));
+      if (a.leaf && live && c == 0) a.leaf[row] = first == 0x7fffffff ? -1 : first;
+    }
+  }
+}
+
 // ---------------------------------------------------------------- non-fused ----------------
 
 // ((T F > v) H) == h on a chunk of the materialised join.  A workgroup takes RB rows at a time:
@@ -419,6 +483,17 @@ int lq_fused_join_tree(const lq_star* star, const lq_tree* tree, const void* con
   hipStream_t s = static_cast<hipStream_t>(hip_stream);
   int G = 1;
   while (G < a.chunks && G < 64) G <<= 1;
+  if (!a.has_fact_nodes && a.chunks <= 16) {
+    const int64_t bblocks = (a.n + 255) / 256;
+    if (bblocks > 0x7fffffffLL) return fail(LQ_ERR_UNSUPPORTED, "too many rows for one launch");
+    switch (G) {
+#define LQ_TREE_CASE(GG) case GG: hipLaunchKernelGGL(fused_tree_batch_kernel<GG>, dim3(static_cast<unsigned>(bblocks)), dim3(256), 0, s, a); break;
+      LQ_TREE_CASE(1) LQ_TREE_CASE(2) LQ_TREE_CASE(4) LQ_TREE_CASE(8) LQ_TREE_CASE(16)
+#undef LQ_TREE_CASE
+    }
+    LQ_LAUNCH_CHECK("fused_tree_batch_kernel");
+    return LQ_OK;
+  }
   const int64_t blocks = (a.n + 256 / G - 1) / (256 / G);
   if (blocks > 0x7fffffffLL) return fail(LQ_ERR_UNSUPPORTED, "too many rows for one launch");
   switch (G) {
