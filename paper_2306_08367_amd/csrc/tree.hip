@@ -259,8 +259,10 @@ __global__ __launch_bounds__(256) void fused_tree_kernel(FusedTreeArgs a) {
 // coalesced (lane = row), and hands them to the G-lane groups through the cross-lane network; in
 // pass t group g works on row (64 / G) t + g.  The gathers of up to four passes are issued before
 // the first is consumed.
-template <int G>
+// KT: number of dimensions when it is 1..4 (loops unroll without guards), 0 = any number.
+template <int G, int KT>
 __global__ __launch_bounds__(256) void fused_tree_batch_kernel(FusedTreeArgs a) {
+  constexpr int KK = KT > 0 ? KT : LQ_MAX_DIMS;
   constexpr int RPP = 64 / G;                 // rows per pass
   constexpr int PB = G < 4 ? G : 4;           // passes in flight together (G passes cover the 64 rows)
   const int lane = threadIdx.x & 63, g = lane / G, c = lane % G;
@@ -268,9 +270,14 @@ __global__ __launch_bounds__(256) void fused_tree_batch_kernel(FusedTreeArgs a) 
   const int64_t row0 = wave * 64;
   if (row0 >= a.n) return;
   const int64_t myrow = min(row0 + lane, a.n - 1);
-  int key[LQ_MAX_DIMS];
+  int key[KK];
+  const uint8_t* tab[KK];
 #pragma unroll
-  for (int k = 0; k < LQ_MAX_DIMS; ++k) key[k] = k < a.K ? __builtin_nontemporal_load(a.fk[k] + myrow) : 0;
+  for (int k = 0; k < KK; ++k) {
+    const bool used = KT > 0 || k < a.K;
+    key[k] = used ? __builtin_nontemporal_load(a.fk[k] + myrow) : 0;
+    tab[k] = (used ? a.T[k] : a.T[0]) + 16 * c;
+  }
   const bool active = c < a.chunks;
   v4u tg = {0u, 0u, 0u, 0u};
   if (active) tg = *reinterpret_cast<const v4u*>(a.target + 16 * c);
@@ -281,10 +288,10 @@ __global__ __launch_bounds__(256) void fused_tree_batch_kernel(FusedTreeArgs a) 
       const int src = RPP * (pb + u) + g;     // the lane that holds this row's keys
       sum[u] = v4u{0u, 0u, 0u, 0u};
 #pragma unroll
-      for (int k = 0; k < LQ_MAX_DIMS; ++k)
-        if (k < a.K) {
+      for (int k = 0; k < KK; ++k)
+        if (KT > 0 || k < a.K) {
           const int64_t j = __shfl(key[k], src, 64);
-          if (active) sum[u] += *reinterpret_cast<const v4u*>(a.T[k] + j * a.t.ld + 16 * c);
+          if (active) sum[u] += *reinterpret_cast<const v4u*>(tab[k] + j * a.t.ld);
         }
     }
 #pragma unroll
@@ -297,18 +304,13 @@ __global__ __launch_bounds__(256) void fused_tree_batch_kernel(FusedTreeArgs a) 
 #pragma unroll
         for (int d = 0; d < 4; ++d) {
           hit[d] = zero_bytes(sum[u][d] ^ tg[d]);
-          if (hit[d] != 0u) first = min(first, 16 * c + 4 * d + (__builtin_ctz(hit[d]) >> 3));
+          // 0x80 marks a matching byte: its position is that of the lowest set bit
+          const int at = 16 * c + 4 * d + ((__builtin_ctz(hit[d] | 0x80000000u)) >> 3);
+          first = min(first, hit[d] != 0u ? at : 0x7fffffff);
         }
-        if (a.onehot && live) {
-          uint8_t* o = a.onehot + row * a.t.l + 16 * c;
-          if (a.onehot_vec_ok && 16 * c + 16 <= a.t.l) {
-            const v4u ones = {hit[0] >> 7, hit[1] >> 7, hit[2] >> 7, hit[3] >> 7};
-            __builtin_nontemporal_store(ones, reinterpret_cast<v4u*>(o));
-          } else {
-#pragma unroll
-            for (int b = 0; b < 16; ++b)
-              if (16 * c + b < a.t.l) o[b] = static_cast<uint8_t>((hit[b >> 2] >> (8 * (b & 3) + 7)) & 1u);
-          }
+        if (a.onehot && live) {               // (this kernel is only chosen when whole 16-byte stores fit)
+          const v4u ones = {hit[0] >> 7, hit[1] >> 7, hit[2] >> 7, hit[3] >> 7};
+          __builtin_nontemporal_store(ones, reinterpret_cast<v4u*>(a.onehot + row * a.t.l + 16 * c));
         }
       }
 #pragma unroll
@@ -483,14 +485,22 @@ int lq_fused_join_tree(const lq_star* star, const lq_tree* tree, const void* con
   hipStream_t s = static_cast<hipStream_t>(hip_stream);
   int G = 1;
   while (G < a.chunks && G < 64) G <<= 1;
-  if (!a.has_fact_nodes && a.chunks <= 16) {
+  if (!a.has_fact_nodes && a.chunks <= 16 && (!a.onehot || (a.onehot_vec_ok && a.t.l % 16 == 0))) {
     const int64_t bblocks = (a.n + 255) / 256;
     if (bblocks > 0x7fffffffLL) return fail(LQ_ERR_UNSUPPORTED, "too many rows for one launch");
+    const dim3 grid(static_cast<unsigned>(bblocks)), block(256);
+#define LQ_TREE_K(GG, KT_) hipLaunchKernelGGL((fused_tree_batch_kernel<GG, KT_>), grid, block, 0, s, a)
+#define LQ_TREE_CASE(GG)                                                            \
+  case GG:                                                                          \
+    if (a.K == 1) LQ_TREE_K(GG, 1); else if (a.K == 2) LQ_TREE_K(GG, 2);            \
+    else if (a.K == 3) LQ_TREE_K(GG, 3); else if (a.K == 4) LQ_TREE_K(GG, 4);       \
+    else LQ_TREE_K(GG, 0);                                                          \
+    break;
     switch (G) {
-#define LQ_TREE_CASE(GG) case GG: hipLaunchKernelGGL(fused_tree_batch_kernel<GG>, dim3(static_cast<unsigned>(bblocks)), dim3(256), 0, s, a); break;
       LQ_TREE_CASE(1) LQ_TREE_CASE(2) LQ_TREE_CASE(4) LQ_TREE_CASE(8) LQ_TREE_CASE(16)
-#undef LQ_TREE_CASE
     }
+#undef LQ_TREE_CASE
+#undef LQ_TREE_K
     LQ_LAUNCH_CHECK("fused_tree_batch_kernel");
     return LQ_OK;
   }
