@@ -8,7 +8,7 @@
 //                        fp32 inputs use the 32x32x2 f32 MFMA; bf16 inputs stay bf16 in LDS and
 //                        use the 32x32x16 bf16 MFMA.  The next k-tile is fetched into registers
 //                        while the current one is multiplied.
-//   gemm_rowsplit_kernel - fp32, N <= 16, 32 <= K: the shape of projecting a wide dimension table
+//   gemm_rowsplit_kernel - fp32, N <= 8, 32 <= K: the shape of projecting a wide dimension table
 //                        onto a handful of outputs, bound by reading A once.  The lanes of a
 //                        wavefront read A as contiguous 16-byte pieces (a row is split over 8..64
 //                        neighbouring lanes), multiply with the weights held in LDS and sum over
@@ -356,11 +356,12 @@ template <int LPR> __device__ __forceinline__ float rs_allreduce(float y) {
 
 // LPR lanes share a row (piece c, c + LPR, ... of its K / 4 pieces); a wavefront works on
 // U x (64 / LPR) rows per step, all loads of a step issued before the first is used.
-// NN = N rounded up to 4, 8 or 16; the weights sit in LDS as [K][NN] with zero padding.
+// NN = N rounded up to 4 or 8; the weights sit in LDS as [K][NN] with zero padding.  (With more
+// outputs the products and the per-row sums outweigh the loads and the matrix-core kernel wins.)
 template <int LPR, int NN>
 __global__ __launch_bounds__(RS_THREADS) void gemm_rowsplit_kernel(GemmArgs g) {
   constexpr int RPW = 64 / LPR;             // rows per wavefront and sub-step
-  constexpr int U = NN == 16 ? 2 : 4;       // sub-steps in flight
+  constexpr int U = 4;                      // sub-steps in flight
   extern __shared__ __align__(16) float Bs[];
   const float* __restrict__ A = static_cast<const float*>(g.A);
   const float* __restrict__ B = static_cast<const float*>(g.B);
@@ -427,15 +428,14 @@ __global__ __launch_bounds__(RS_THREADS) void gemm_rowsplit_kernel(GemmArgs g) {
 
 template <int LPR>
 int launch_rowsplit_n(const GemmArgs& g, hipStream_t s) {
-  const int nn = g.N <= 4 ? 4 : (g.N <= 8 ? 8 : 16);
+  const int nn = g.N <= 4 ? 4 : 8;
   const size_t lds = static_cast<size_t>(g.Kd) * nn * sizeof(float);
-  const int rows_per_step = (64 / LPR) * (nn == 16 ? 2 : 4);
+  const int rows_per_step = (64 / LPR) * 4;
   const int64_t nsteps = (g.M + rows_per_step - 1) / rows_per_step;
   const int64_t blocks = std::min<int64_t>((nsteps + 3) / 4, static_cast<int64_t>(num_cus()) * 16);
   const dim3 grid(static_cast<unsigned>(blocks)), block(RS_THREADS);
   if (nn == 4) hipLaunchKernelGGL((gemm_rowsplit_kernel<LPR, 4>), grid, block, lds, s, g);
-  else if (nn == 8) hipLaunchKernelGGL((gemm_rowsplit_kernel<LPR, 8>), grid, block, lds, s, g);
-  else hipLaunchKernelGGL((gemm_rowsplit_kernel<LPR, 16>), grid, block, lds, s, g);
+  else hipLaunchKernelGGL((gemm_rowsplit_kernel<LPR, 8>), grid, block, lds, s, g);
   LQ_LAUNCH_CHECK("gemm_rowsplit_kernel");
   return LQ_OK;
 }
@@ -444,8 +444,8 @@ int launch_rowsplit_n(const GemmArgs& g, hipStream_t s) {
 // stride and the alignment only, never on M, so a row computed alone equals the same row computed
 // as part of the whole table.
 int try_rowsplit(const GemmArgs& g, hipStream_t s) {
-  if (g.N > 16 || g.Kd < 32 || g.Kd % 4 || g.lda % 4 || !aligned(g.A, 16) || !aligned(g.C, 4)) return -1;
-  if (static_cast<size_t>(g.Kd) * 16 * sizeof(float) > 64 * 1024) return -1;
+  if (g.N > 8 || g.Kd < 32 || g.Kd % 4 || g.lda % 4 || !aligned(g.A, 16) || !aligned(g.C, 4)) return -1;
+  if (static_cast<size_t>(g.Kd) * 8 * sizeof(float) > 64 * 1024) return -1;
   const int ppr = g.Kd / 4;
   if (ppr <= 8) return launch_rowsplit_n<8>(g, s);
   if (ppr <= 16) return launch_rowsplit_n<16>(g, s);
