@@ -57,6 +57,14 @@ SHAPES = [
     ("mlp_10_1", 3_210, 7, (33, 44), (7, 7), (10, 1), True),
     ("linear_l128", 1_999, 4, (100, 200), (16, 16), (128,), False),
     ("linear_l256", 1_001, 4, (100, 200), (16, 16), (256,), True),
+    # hidden widths 128 / 256 with 1..4 dimensions, 0 / 4 / 8 fact columns, linear and one-output MLP
+    ("mlp_128_1_k3", 20_037, 4, (1000, 5000, 200), (32, 32, 32), (128, 1), True),
+    ("mlp_256_1_k3", 8_195, 4, (1000, 5000, 200), (32, 32, 32), (256, 1), False),
+    ("mlp_128_1_k1_cf0", 4_099, 0, (300,), (20,), (128, 1), True),
+    ("mlp_256_1_k4_cf8", 3_333, 8, (50, 60, 70, 80), (6, 6, 6, 6), (256, 1), True),
+    ("linear_l128_k4_cf8", 2_817, 8, (50, 60, 70, 80), (6, 6, 6, 6), (128,), True),
+    ("linear_l256_k2_cf0", 257, 0, (50, 60), (6, 6), (256,), False),
+    ("mlp_128_1_k2_cf8", 641, 8, (50, 60), (6, 6), (128, 1), False),
     # shapes only the tiled matrix-core MLP kernel covers: wide second layers, three layers
     ("mlp_64_10", 5_555, 4, (100, 2_000, 50), (16, 16, 16), (64, 10), True),
     ("mlp_128_16", 3_001, 4, (100, 200), (16, 16), (128, 16), False),
