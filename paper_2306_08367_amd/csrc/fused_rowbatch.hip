@@ -149,6 +149,7 @@ void fused_rowbatch64_kernel(PredictArgs a) {
   const int64_t nwaves = static_cast<int64_t>(gridDim.x) * (RB_THREADS / 64);
   const int64_t nb = (a.n + 63) / 64;
   if (wave >= nb) return;
+  const bool y_vec = a.ldy % 4 == 0 && (reinterpret_cast<uintptr_t>(a.Y) & 15) == 0;
 
   LaneConsts<CFC, NL, L2> w;
   {
@@ -196,8 +197,14 @@ void fused_rowbatch64_kernel(PredictArgs a) {
     if constexpr (NL == 2) {
       if (row < a.n) {
         float* yr = static_cast<float*>(a.Y) + row * a.ldy;
+        if (L2 == 4 && y_vec) {            // the row's four outputs as one 16-byte store
+          const v4f o4 = {yk[0] + w.b2[0], yk[L2 > 1 ? 1 : 0] + w.b2[L2 > 1 ? 1 : 0],
+                          yk[L2 > 2 ? 2 : 0] + w.b2[L2 > 2 ? 2 : 0], yk[L2 > 3 ? 3 : 0] + w.b2[L2 > 3 ? 3 : 0]};
+          __builtin_nontemporal_store(o4, reinterpret_cast<v4f*>(yr));
+        } else {
 #pragma unroll
-        for (int o = 0; o < L2; ++o) __builtin_nontemporal_store(yk[o] + w.b2[o], yr + o);
+          for (int o = 0; o < L2; ++o) __builtin_nontemporal_store(yk[o] + w.b2[o], yr + o);
+        }
       }
     }
     if (!more) break;

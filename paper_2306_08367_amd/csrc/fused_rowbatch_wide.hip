@@ -1,15 +1,16 @@
-// Join-computation stage (last line of Eq. 1) for hidden widths 128 and 256 in fp32: the same
-// organisation as the width-64 kernel, with 32 or 64 lanes per fact row.
+// Join-computation stage (last line of Eq. 1) in fp32 for hidden widths 32, 64, 128 and 256, as a
+// linear operator or followed by a second layer of up to 16 outputs: the organisation of the
+// width-64 kernel with a run-time pass loop, so that it covers 8 to 64 lanes per fact row.
 //
 // A wavefront owns 64 consecutive fact rows at a time.  Their fact columns and keys are read once,
 // coalesced (lane l holds row l).  With LPR = l_1 / 4 lanes per row the wavefront is 64 / LPR lane
 // groups; in pass t (0 .. LPR-1) group g works on fact row g LPR + t, lane c of the group owning
-// hidden columns 4c..4c+3, so that a projected row (512 or 1024 bytes) is fetched by one group as
+// hidden columns 4c..4c+3, so that a projected row (128 to 1024 bytes) is fetched by one group as
 // one contiguous run.  The row's key and fact values reach the group through the cross-lane
 // network (a lane read for 64 lanes per row, a permute otherwise).  Gathers are software-pipelined
-// in groups of four passes, across batches too; the pass loop is a run-time loop, so the code
-// stays small for 32 or 64 passes.  A 2-layer model with one output sums over the lanes of a row
-// and parks the result of pass t in lane t of the group: one coalesced store per batch.
+// in groups of four (two, with many outputs) passes, across batches too.  A second layer is
+// 4 x l_2 multiply-adds per lane and a sum over the lanes of the row per output (DPP adds); the
+// results of pass t are parked in lane t of the group, so a batch ends with one store per row.
 #include "lq_common.h"
 
 namespace lq {
@@ -22,14 +23,14 @@ constexpr int RBW_THREADS = 256;
 template <int CTRL> __device__ __forceinline__ float dppw(float v) {
   return __int_as_float(__builtin_amdgcn_update_dpp(0, __float_as_int(v), CTRL, 0xf, 0xf, false));
 }
-// Sum over the LPR (32 or 64) lanes of a group, result in every lane.
+// Sum over the LPR (8 .. 64) lanes of a group, result in every lane.
 template <int LPR> __device__ __forceinline__ float group_sum(float y) {
   y += dppw<0xB1>(y);                  // quad_perm [1,0,3,2]
   y += dppw<0x4E>(y);                  // quad_perm [2,3,0,1]
   y += dppw<0x141>(y);                 // row_half_mirror
-  y += dppw<0x140>(y);                 // row_mirror
-  y += __shfl_xor(y, 16, 64);
-  if (LPR == 64) y += __shfl_xor(y, 32, 64);
+  if (LPR >= 16) y += dppw<0x140>(y);  // row_mirror
+  if (LPR >= 32) y += __shfl_xor(y, 16, 64);
+  if (LPR >= 64) y += __shfl_xor(y, 32, 64);
   return y;
 }
 // Value that lane (group base + t) holds, for every lane of the group.
@@ -42,7 +43,7 @@ template <int K, int CFC> struct WRow {
   int fk[K];
   v4f x[CFC > 0 ? CFC : 1];
 };
-template <int K> struct WGather { v4f p[4][K]; };
+template <int K, int PG> struct WGather { v4f p[PG][K]; };
 
 template <int K, int CFC>
 __device__ __forceinline__ void load_rows(const PredictArgs& a, int64_t rr, WRow<K, CFC>& r) {
@@ -53,34 +54,35 @@ __device__ __forceinline__ void load_rows(const PredictArgs& a, int64_t rr, WRow
   for (int q = 0; q < CFC; ++q) r.x[q] = __builtin_nontemporal_load(reinterpret_cast<const v4f*>(xr) + q);
 }
 
-// Gathers of passes 4 grp .. 4 grp + 3.
-template <int LPR, int K, int CFC>
+// Gathers of passes PG grp .. PG grp + PG - 1.
+template <int LPR, int K, int CFC, int PG>
 __device__ __forceinline__ void issue_group(const PredictArgs& a, int c, int group_base, int grp,
-                                            const WRow<K, CFC>& r, WGather<K>& g) {
+                                            const WRow<K, CFC>& r, WGather<K, PG>& g) {
 #pragma unroll
-  for (int u = 0; u < 4; ++u)
+  for (int u = 0; u < PG; ++u)
 #pragma unroll
     for (int k = 0; k < K; ++k) {
-      const int j = from_lane<LPR>(r.fk[k], 4 * grp + u, group_base);
+      const int j = from_lane<LPR>(r.fk[k], PG * grp + u, group_base);
       g.p[u][k] = *reinterpret_cast<const v4f*>(static_cast<const float*>(a.P[k]) +
                                                 static_cast<int64_t>(j) * a.ldp[k] + 4 * c);
     }
 }
 
-template <int CFC, int NL> struct WConsts {
+// L2P: outputs of the second layer rounded up to 1, 4 or 16 (weights of the padding are zero).
+template <int CFC, int L2P> struct WConsts {
   float wf[CFC > 0 ? CFC * 4 : 1][4];   // W_f rows x this lane's 4 columns
   float b1[4];
-  float w2[4];
-  float b2;
+  float w2[4][L2P];
+  float b2[L2P];
 };
 
-template <int LPR, int K, int CFC, int NL>
+template <int LPR, int K, int CFC, int NL, int L2P, int PG>
 __device__ __forceinline__ void compute_group(const PredictArgs& a, int c, int group_base, int grp, int64_t row0,
-                                              const WRow<K, CFC>& r, const WGather<K>& g,
-                                              const WConsts<CFC, NL>& w, float& ykeep) {
+                                              const WRow<K, CFC>& r, const WGather<K, PG>& g,
+                                              const WConsts<CFC, L2P>& w, float (&ykeep)[L2P]) {
 #pragma unroll
-  for (int u = 0; u < 4; ++u) {
-    const int t = 4 * grp + u;
+  for (int u = 0; u < PG; ++u) {
+    const int t = PG * grp + u;
     float z[4];
 #pragma unroll
     for (int v = 0; v < 4; ++v) z[v] = w.b1[v];
@@ -103,33 +105,46 @@ __device__ __forceinline__ void compute_group(const PredictArgs& a, int c, int g
         __builtin_nontemporal_store(o, reinterpret_cast<v4f*>(static_cast<float*>(a.Y) + row * a.ldy + 4 * c));
       }
     } else {
-      float y = 0.f;
+      float y[L2P];
 #pragma unroll
-      for (int v = 0; v < 4; ++v) y = fmaf(fmaxf(z[v], 0.f), w.w2[v], y);
-      y = group_sum<LPR>(y);
-      if (c == t) ykeep = y;
+      for (int o = 0; o < L2P; ++o) y[o] = 0.f;
+#pragma unroll
+      for (int v = 0; v < 4; ++v) {
+        const float h = fmaxf(z[v], 0.f);
+#pragma unroll
+        for (int o = 0; o < L2P; ++o) y[o] = fmaf(h, w.w2[v][o], y[o]);
+      }
+#pragma unroll
+      for (int o = 0; o < L2P; ++o) {
+        const float tot = group_sum<LPR>(y[o]);
+        if (c == t) ykeep[o] = tot;
+      }
     }
   }
 }
 
-// LPR lanes per row (l_1 = 4 LPR), K dimensions, CFC float4 chunks of fact columns, NL layers
-// (the second one with a single output).
+// LPR lanes per row (l_1 = 4 LPR), K dimensions, CFC float4 chunks of fact columns, NL layers,
+// L2P padded outputs of the second layer.
 // Three wavefronts per SIMD leave 170 registers each; the double-buffered gathers of many
-// dimensions plus many fact columns need more, and two per SIMD is faster than spilling.
-constexpr int waves_per_simd(int K, int CFC) { return 32 * K + 24 * CFC > 100 ? 2 : 3; }
+// dimensions plus many fact columns, or the weights of a wide second layer, need more, and two per
+// SIMD is faster than spilling.
+constexpr int waves_per_simd(int K, int CFC, int L2P) { return (L2P > 4 || 32 * K + 24 * CFC + 6 * L2P > 106) ? 2 : 3; }
 
-template <int LPR, int K, int CFC, int NL>
+template <int LPR, int K, int CFC, int NL, int L2P>
 __global__ __launch_bounds__(RBW_THREADS)
-__attribute__((amdgpu_waves_per_eu(waves_per_simd(K, CFC), waves_per_simd(K, CFC))))
+__attribute__((amdgpu_waves_per_eu(waves_per_simd(K, CFC, L2P), waves_per_simd(K, CFC, L2P))))
 void fused_rowbatch_wide_kernel(PredictArgs a) {
-  constexpr int NG = LPR / 4;            // groups of four passes per batch (8 or 16)
+  constexpr int PG = L2P > 4 ? 2 : 4;    // passes whose gathers travel together
+  constexpr int NG = LPR / PG;           // such groups per batch (even)
   const int lane = threadIdx.x & 63, c = lane & (LPR - 1), group_base = lane & ~(LPR - 1);
   const int64_t wave = static_cast<int64_t>(blockIdx.x) * (RBW_THREADS / 64) + (threadIdx.x >> 6);
   const int64_t nwaves = static_cast<int64_t>(gridDim.x) * (RBW_THREADS / 64);
   const int64_t nb = (a.n + 63) / 64;
   if (wave >= nb) return;
+  const int l2 = NL == 2 ? a.wout[1] : 0;
+  const bool y_vec = l2 % 4 == 0 && a.ldy % 4 == 0 && (reinterpret_cast<uintptr_t>(a.Y) & 15) == 0;
 
-  WConsts<CFC, NL> w;
+  WConsts<CFC, L2P> w;
   {
     const float* W0 = static_cast<const float*>(a.W[0]);
 #pragma unroll
@@ -139,34 +154,55 @@ void fused_rowbatch_wide_kernel(PredictArgs a) {
 #pragma unroll
     for (int v = 0; v < 4; ++v) w.b1[v] = a.bias[0] ? static_cast<const float*>(a.bias[0])[4 * c + v] : 0.f;
 #pragma unroll
-    for (int v = 0; v < 4; ++v)
-      w.w2[v] = NL == 2 ? static_cast<const float*>(a.W[1])[static_cast<int64_t>(4 * c + v) * a.ldw[1]] : 0.f;
-    w.b2 = (NL == 2 && a.bias[1]) ? static_cast<const float*>(a.bias[1])[0] : 0.f;
+    for (int o = 0; o < L2P; ++o) {
+      const bool real = NL == 2 && o < l2;
+#pragma unroll
+      for (int v = 0; v < 4; ++v)
+        w.w2[v][o] = real ? static_cast<const float*>(a.W[1])[static_cast<int64_t>(4 * c + v) * a.ldw[1] + o] : 0.f;
+      w.b2[o] = (real && a.bias[1]) ? static_cast<const float*>(a.bias[1])[o] : 0.f;
+    }
   }
 
   int64_t b = wave;
   int64_t row = b * 64 + lane;
   WRow<K, CFC> cur, nxt;
   load_rows<K, CFC>(a, row < a.n ? row : a.n - 1, cur);
-  WGather<K> ga, gb;
-  issue_group<LPR, K, CFC>(a, c, group_base, 0, cur, ga);
+  WGather<K, PG> ga, gb;
+  issue_group<LPR, K, CFC, PG>(a, c, group_base, 0, cur, ga);
   for (;;) {
     const int64_t bn = b + nwaves;
     const bool more = bn < nb;
     const int64_t rown = bn * 64 + lane;
     load_rows<K, CFC>(a, (more && rown < a.n) ? rown : a.n - 1, nxt);
-    float yk = 0.f;
+    float yk[L2P];
+#pragma unroll
+    for (int o = 0; o < L2P; ++o) yk[o] = 0.f;
     const int64_t row0 = b * 64;
 #pragma unroll 1
     for (int grp = 0; grp < NG; grp += 2) {
-      issue_group<LPR, K, CFC>(a, c, group_base, grp + 1, cur, gb);
-      compute_group<LPR, K, CFC, NL>(a, c, group_base, grp, row0, cur, ga, w, yk);
-      if (grp + 2 < NG) issue_group<LPR, K, CFC>(a, c, group_base, grp + 2, cur, ga);
-      else issue_group<LPR, K, CFC>(a, c, group_base, 0, nxt, ga);   // first group of the next batch (valid rows repeated at the end)
-      compute_group<LPR, K, CFC, NL>(a, c, group_base, grp + 1, row0, cur, gb, w, yk);
+      issue_group<LPR, K, CFC, PG>(a, c, group_base, grp + 1, cur, gb);
+      compute_group<LPR, K, CFC, NL, L2P, PG>(a, c, group_base, grp, row0, cur, ga, w, yk);
+      if (grp + 2 < NG) issue_group<LPR, K, CFC, PG>(a, c, group_base, grp + 2, cur, ga);
+      else issue_group<LPR, K, CFC, PG>(a, c, group_base, 0, nxt, ga);   // first group of the next batch (valid rows repeated at the end)
+      compute_group<LPR, K, CFC, NL, L2P, PG>(a, c, group_base, grp + 1, row0, cur, gb, w, yk);
     }
     if constexpr (NL == 2) {
-      if (row < a.n) __builtin_nontemporal_store(yk + w.b2, static_cast<float*>(a.Y) + row * a.ldy);
+      if (row < a.n) {
+        float* yr = static_cast<float*>(a.Y) + row * a.ldy;
+        if (L2P >= 4 && y_vec) {             // whole 16-byte pieces of the output row
+#pragma unroll
+          for (int q = 0; q < L2P / 4; ++q)
+            if (4 * q < l2) {
+              const v4f o4 = {yk[4 * q] + w.b2[4 * q], yk[4 * q + 1] + w.b2[4 * q + 1],
+                              yk[4 * q + 2] + w.b2[4 * q + 2], yk[4 * q + 3] + w.b2[4 * q + 3]};
+              *reinterpret_cast<v4f*>(yr + 4 * q) = o4;
+            }
+        } else {
+#pragma unroll
+          for (int o = 0; o < L2P; ++o)
+            if (o < l2) yr[o] = yk[o] + w.b2[o];
+        }
+      }
     }
     if (!more) break;
     b = bn;
@@ -175,38 +211,50 @@ void fused_rowbatch_wide_kernel(PredictArgs a) {
   }
 }
 
-template <int LPR, int K, int CFC, int NL>
+template <int LPR, int K, int CFC, int NL, int L2P>
 int launch_inst(const PredictArgs& a, hipStream_t s) {
   const int64_t nb = (a.n + 63) / 64;
-  const int64_t blocks = std::min<int64_t>((nb + 3) / 4, static_cast<int64_t>(num_cus()) * waves_per_simd(K, CFC));
-  hipLaunchKernelGGL((fused_rowbatch_wide_kernel<LPR, K, CFC, NL>), dim3(static_cast<unsigned>(blocks)),
+  const int64_t blocks = std::min<int64_t>((nb + 3) / 4, static_cast<int64_t>(num_cus()) * waves_per_simd(K, CFC, L2P));
+  hipLaunchKernelGGL((fused_rowbatch_wide_kernel<LPR, K, CFC, NL, L2P>), dim3(static_cast<unsigned>(blocks)),
                      dim3(RBW_THREADS), 0, s, a);
   LQ_LAUNCH_CHECK("fused_rowbatch_wide_kernel");
   return LQ_OK;
 }
 
-template <int LPR, int K, int CFC>
+// NARROW: the shapes with one to four outputs at this width belong to another kernel.
+template <int LPR, int K, int CFC, bool NARROW>
 int pick_layers(const PredictArgs& a, hipStream_t s) {
-  return a.n_layers == 1 ? launch_inst<LPR, K, CFC, 1>(a, s) : launch_inst<LPR, K, CFC, 2>(a, s);
+  if (a.n_layers == 1) {
+    if constexpr (NARROW) return launch_inst<LPR, K, CFC, 1, 1>(a, s);
+    else return -1;
+  }
+  const int l2 = a.wout[1];
+  if (l2 > 16) return -1;
+  if (l2 > 4) return launch_inst<LPR, K, CFC, 2, 16>(a, s);
+  if constexpr (NARROW) {
+    if (l2 == 1) return launch_inst<LPR, K, CFC, 2, 1>(a, s);
+    return launch_inst<LPR, K, CFC, 2, 4>(a, s);
+  }
+  return -1;
 }
 
-template <int LPR, int K>
+template <int LPR, int K, bool NARROW>
 int pick_cf(const PredictArgs& a, hipStream_t s) {
   switch (a.c_f) {
-    case 0: return pick_layers<LPR, K, 0>(a, s);
-    case 4: return pick_layers<LPR, K, 1>(a, s);
-    case 8: return pick_layers<LPR, K, 2>(a, s);
+    case 0: return pick_layers<LPR, K, 0, NARROW>(a, s);
+    case 4: return pick_layers<LPR, K, 1, NARROW>(a, s);
+    case 8: return pick_layers<LPR, K, 2, NARROW>(a, s);
     default: return -1;
   }
 }
 
-template <int LPR>
+template <int LPR, bool NARROW>
 int pick_k(const PredictArgs& a, hipStream_t s) {
   switch (a.K) {
-    case 1: return pick_cf<LPR, 1>(a, s);
-    case 2: return pick_cf<LPR, 2>(a, s);
-    case 3: return pick_cf<LPR, 3>(a, s);
-    case 4: return pick_cf<LPR, 4>(a, s);
+    case 1: return pick_cf<LPR, 1, NARROW>(a, s);
+    case 2: return pick_cf<LPR, 2, NARROW>(a, s);
+    case 3: return pick_cf<LPR, 3, NARROW>(a, s);
+    case 4: return pick_cf<LPR, 4, NARROW>(a, s);
     default: return -1;
   }
 }
@@ -216,14 +264,18 @@ int pick_k(const PredictArgs& a, hipStream_t s) {
 // Returns -1 when the shape is not one this kernel covers.
 int try_rowbatch_wide(const PredictArgs& a, hipStream_t s) {
   if (a.x_dtype != LQ_F32 || a.p_dtype != LQ_F32 || a.y_dtype != LQ_F32) return -1;
-  if (a.wout[0] != 128 && a.wout[0] != 256) return -1;
-  if (a.n_layers > 2 || (a.n_layers == 2 && a.wout[1] != 1)) return -1;
-  if (a.n < 256) return -1;
+  if (a.n_layers > 2 || a.n < 256) return -1;
   for (int k = 0; k < a.K; ++k)
     if (!aligned(a.P[k], 16) || a.ldp[k] % 4) return -1;
   if (a.c_f > 0 && (!aligned(a.X, 16) || a.ldx % 4)) return -1;
   if (a.n_layers == 1 && (!aligned(a.Y, 16) || a.ldy % 4)) return -1;
-  return a.wout[0] == 128 ? pick_k<32>(a, s) : pick_k<64>(a, s);
+  switch (a.wout[0]) {
+    case 32: return pick_k<8, true>(a, s);
+    case 64: return pick_k<16, false>(a, s);     // one to four outputs: the unrolled width-64 kernel, tried first
+    case 128: return pick_k<32, true>(a, s);
+    case 256: return pick_k<64, true>(a, s);
+    default: return -1;
+  }
 }
 
 }  // namespace lq

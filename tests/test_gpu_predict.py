@@ -65,6 +65,16 @@ SHAPES = [
     ("linear_l128_k4_cf8", 2_817, 8, (50, 60, 70, 80), (6, 6, 6, 6), (128,), True),
     ("linear_l256_k2_cf0", 257, 0, (50, 60), (6, 6), (256,), False),
     ("mlp_128_1_k2_cf8", 641, 8, (50, 60), (6, 6), (128, 1), False),
+    # second layers of up to 16 outputs and hidden width 32 in the same kernel family
+    ("mlp_32_1_k3", 6_151, 4, (1000, 5000, 200), (32, 32, 32), (32, 1), True),
+    ("linear_l32_k2_cf8", 2_051, 8, (50, 60), (6, 6), (32,), False),
+    ("mlp_32_8_k4", 3_079, 0, (50, 60, 70, 80), (6, 6, 6, 6), (32, 8), True),
+    ("mlp_64_16_k3", 9_001, 4, (1000, 5000, 200), (32, 32, 32), (64, 16), True),
+    ("mlp_64_7_k1", 1_283, 8, (90,), (12,), (64, 7), False),
+    ("mlp_128_3_k2", 2_311, 4, (50, 60), (6, 6), (128, 3), True),
+    ("mlp_128_9_k4_cf8", 1_931, 8, (50, 60, 70, 80), (6, 6, 6, 6), (128, 9), True),
+    ("mlp_256_16_k3", 4_111, 0, (100, 200, 300), (16, 16, 16), (256, 16), True),
+    ("mlp_256_5_k2", 769, 4, (100, 200), (16, 16), (256, 5), False),
     # shapes only the tiled matrix-core MLP kernel covers: wide second layers, three layers
     ("mlp_64_10", 5_555, 4, (100, 2_000, 50), (16, 16, 16), (64, 10), True),
     ("mlp_128_16", 3_001, 4, (100, 200), (16, 16), (128, 16), False),
