@@ -1,5 +1,5 @@
 // Join-computation stage (last line of Eq. 1) for wide bf16 models: hidden width a multiple of
-// 32, no fact-owned columns, optional second layer of at most 16 outputs on the matrix cores.
+// 32, up to 16 fact-owned columns, optional second layer of at most 16 outputs on the matrix cores.
 //
 // A wavefront handles 16 fact rows per pass.  Lane (g = lane / 16, j = lane % 16) works on row j
 // and, in each 32-wide block kb of hidden units, owns units 32 kb + 8 g .. + 7 - exactly the
@@ -30,13 +30,15 @@ __device__ __forceinline__ unsigned int pack2(float lo, float hi) {
 }
 
 // KB = l_1 / 32.  NL = 1: Y = z (TY = bf16 or float).  NL = 2: Y = W_2^T relu(z) + b_2, l_2 <= 16.
-template <int KB, int NL, typename TY>
+// HAS_X: the fact table has columns of its own.
+template <int KB, int NL, typename TY, bool HAS_X>
 __global__ __launch_bounds__(BF_THREADS) void fused_bf16_kernel(PredictArgs a) {
   const int lane = threadIdx.x & 63, g = lane >> 4, j = lane & 15;
   const int64_t wave = static_cast<int64_t>(blockIdx.x) * (BF_THREADS / 64) + (threadIdx.x >> 6);
   const int64_t nwaves = static_cast<int64_t>(gridDim.x) * (BF_THREADS / 64);
   const int64_t npass = (a.n + 15) / 16;
   const int l2 = NL == 2 ? a.wout[1] : 0;
+  const bool w0_vec = (reinterpret_cast<uintptr_t>(a.W[0]) & 15) == 0 && a.ldw[0] % 8 == 0;
 
   // A operand of the second layer: lane (g, i = j) holds W_2[32 kb + 8 g + t][i], t = 0..7.
   v4u afrag[NL == 2 ? KB : 1];
@@ -74,6 +76,28 @@ __global__ __launch_bounds__(BF_THREADS) void fused_bf16_kernel(PredictArgs a) {
       for (int kb = 0; kb < KB; ++kb)
 #pragma unroll
         for (int t = 0; t < 8; ++t) acc[kb][t] = 0.f;
+    }
+    if constexpr (HAS_X) {                 // the fact table's own columns: z += x W_f, weights from cache
+      const bf16_t* xr = static_cast<const bf16_t*>(a.X) + rr * a.ldx;
+      const bf16_t* W0 = static_cast<const bf16_t*>(a.W[0]) + 8 * g;
+      for (int q = 0; q < a.c_f; ++q) {
+        const float x = bf16_to_f32(xr[q]);
+        const bf16_t* wq = W0 + static_cast<int64_t>(q) * a.ldw[0];
+#pragma unroll
+        for (int kb = 0; kb < KB; ++kb) {
+          float wv[8];
+          if (w0_vec) {
+            const v4u t = *reinterpret_cast<const v4u*>(wq + 32 * kb);
+#pragma unroll
+            for (int e = 0; e < 4; ++e) { wv[2 * e] = __uint_as_float(t[e] << 16); wv[2 * e + 1] = __uint_as_float(t[e] & 0xffff0000u); }
+          } else {
+#pragma unroll
+            for (int e = 0; e < 8; ++e) wv[e] = bf16_to_f32(wq[32 * kb + e]);
+          }
+#pragma unroll
+          for (int e = 0; e < 8; ++e) acc[kb][e] = fmaf(x, wv[e], acc[kb][e]);
+        }
+      }
     }
     for (int k = 0; k < a.K; ++k) {
       const int64_t f = a.fk[k][rr];
@@ -126,8 +150,9 @@ template <int KB, int NL, typename TY>
 int launch_inst(const PredictArgs& a, hipStream_t s) {
   const int64_t npass = (a.n + 15) / 16;
   const int64_t blocks = std::min<int64_t>((npass + 3) / 4, static_cast<int64_t>(num_cus()) * 8);
-  hipLaunchKernelGGL((fused_bf16_kernel<KB, NL, TY>), dim3(static_cast<unsigned>(blocks)), dim3(BF_THREADS),
-                     0, s, a);
+  const dim3 grid(static_cast<unsigned>(blocks)), block(BF_THREADS);
+  if (a.c_f > 0) hipLaunchKernelGGL((fused_bf16_kernel<KB, NL, TY, true>), grid, block, 0, s, a);
+  else hipLaunchKernelGGL((fused_bf16_kernel<KB, NL, TY, false>), grid, block, 0, s, a);
   LQ_LAUNCH_CHECK("fused_bf16_kernel");
   return LQ_OK;
 }
@@ -144,7 +169,7 @@ int pick(const PredictArgs& a, hipStream_t s) {
 // Returns -1 when the shape is not one this kernel covers.
 int try_fused_bf16(const PredictArgs& a, hipStream_t s) {
   if (a.x_dtype != LQ_BF16 || a.p_dtype != LQ_BF16) return -1;
-  if (a.c_f != 0 || a.K < 1 || a.n_layers > 2) return -1;
+  if (a.c_f > 16 || a.K < 1 || a.n_layers > 2) return -1;
   const int l1 = a.wout[0];
   if (l1 % 32 || l1 > 256) return -1;
   if (a.n_layers == 2 && a.wout[1] > 16) return -1;

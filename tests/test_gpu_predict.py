@@ -182,19 +182,25 @@ def test_bf16_paths(lq):
 
 
 BF16_MFMA_SHAPES = [
-    # name, n, dim_rows, dim_cols, layers, bias   (no fact columns: the matrix-core epilogue kernel)
+    # name, n, dim_rows, dim_cols, layers, bias[, c_f]   (the matrix-core epilogue kernel)
     ("bf16_256_16", 5_003, (500, 700, 300, 900), (64, 64, 32, 48), (256, 16), False),
     ("bf16_128_10_bias", 3_001, (100, 200), (32, 40), (128, 10), True),
     ("bf16_32_1", 2_047, (50,), (16,), (32, 1), True),
     ("bf16_linear_256", 1_999, (64, 80, 96), (24, 24, 24), (256,), True),
     ("bf16_linear_64", 4_100, (64, 80), (24, 24), (64,), False),
+    # with fact columns (a seventh entry): x W_f is added in the same kernel
+    ("bf16_64_1_cf4", 6_011, (1000, 5000, 200), (32, 32, 32), (64, 1), True, 4),
+    ("bf16_256_16_cf3", 2_111, (300, 200), (32, 32), (256, 16), False, 3),
+    ("bf16_linear_128_cf16", 1_777, (64, 80), (24, 24), (128,), True, 16),
+    ("bf16_32_8_cf1", 3_001, (70,), (9,), (32, 8), True, 1),
 ]
 
 
 @pytest.mark.parametrize("shape", BF16_MFMA_SHAPES, ids=[s[0] for s in BF16_MFMA_SHAPES])
 def test_bf16_wide_models(lq, shape):
-    name, n, rows, cols, layers, bias = shape
-    w = WL.make_predict(name, n, 0, rows, cols, layers, seed=WL.SEED0 + 300 + len(name),
+    name, n, rows, cols, layers, bias = shape[:6]
+    c_f = shape[6] if len(shape) > 6 else 0
+    w = WL.make_predict(name, n, c_f, rows, cols, layers, seed=WL.SEED0 + 300 + len(name),
                         dtype=torch.bfloat16, w_sigma=[1.0 / np.sqrt(sum(cols))] + [0.1] * (len(layers) - 1),
                         bias=bias)
     want = _oracle(w)
