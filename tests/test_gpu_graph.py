@@ -73,3 +73,45 @@ def test_prefusion_and_fused_predict_replays_match_eager(lq):
         assert torch.equal(Y, ref)
         call()
         torch.cuda.synchronize()
+
+
+def test_raw_keys_to_ordered_aggregate_replays_match_eager(lq):
+    """Key lookup -> group-by with reused side tables -> ORDER BY, recorded as one graph."""
+    import numpy as np
+    r = np.random.default_rng(12)
+    n, rows = 300_007, (2_556, 3_000)
+    keys_S = [torch.from_numpy((r.permutation(a) + 1).astype(np.int32)).cuda() for a in rows]
+    keys_R = [torch.from_numpy(r.integers(0, a + 40, size=n).astype(np.int32)).cuda() for a in rows]
+    maps = [lq.lq_keymap_build(k) for k in keys_S]
+    codes = [torch.from_numpy(r.integers(0, c, size=a).astype(np.int32)).cuda() for a, c in zip(rows, (7, 25))]
+    meas = [torch.from_numpy(r.integers(1, 1000, size=n).astype(np.int32)).cuda()]
+    fks = [torch.empty(n, dtype=torch.int32, device="cuda") for _ in rows]
+    ws = torch.empty(lq.lq_groupby_workspace_bytes(rows, (7, 25), 1), dtype=torch.uint8, device="cuda")
+    sums = torch.empty((1, 175), dtype=torch.int64, device="cuda")
+    counts = torch.empty((175,), dtype=torch.int64, device="cuda")
+    order = torch.empty(175, dtype=torch.int32, device="cuda")
+    n_out = torch.empty(1, dtype=torch.int32, device="cuda")
+    keys = [(lq.LQ_KEY_GROUP_COLUMN, 0, False), (lq.LQ_KEY_SUM, 0, True)]
+    lq.lq_masked_groupby_sum(fks, rows, None, codes, (7, 25), None, meas, sums=sums, counts=counts, ws=ws)  # encodes the side tables
+
+    def call():
+        for m, kr, fk in zip(maps, keys_R, fks):
+            lq.lq_keymap_lookup(m, kr, fk=fk)
+        lq.lq_masked_groupby_sum(fks, rows, None, codes, (7, 25), None, meas, sums=sums, counts=counts, ws=ws,
+                                 flags=lq.LQ_REUSE_SIDE_TABLES)
+        lq.lq_order_groups((7, 25), sums, counts, keys, order=order, n_out=n_out)
+    call()
+    torch.cuda.synchronize()
+    ref = [t.clone() for t in (sums, counts, order, n_out, fks[0], fks[1])]
+    assert int(n_out.item()) > 100 and int((fks[1] < 0).sum()) > 0
+    graph = _capture(call)
+    for _ in range(3):
+        for t in (sums, counts, order, n_out, fks[0], fks[1]):
+            t.fill_(-3)
+        torch.cuda.synchronize()
+        graph.replay()
+        torch.cuda.synchronize()
+        for got, want in zip((sums, counts, order, n_out, fks[0], fks[1]), ref):
+            assert torch.equal(got, want)
+        call()
+        torch.cuda.synchronize()
