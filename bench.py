@@ -67,7 +67,7 @@ def main():
     ap.add_argument("--rows", type=int, default=10_000_000, help="fact rows of the headline workload")
     ap.add_argument("--no-extras", action="store_true", help="skip materialised / group-by / skewed legs")
     ap.add_argument("--no-cpu", action="store_true", help="skip the CPU oracle baseline")
-    ap.add_argument("--only", default="", help="run a single leg for profiling: fused|groupby|groupby16|c4|c5|tree|keymap|agg|domain|sweep|sfsweep|materialized|copy")
+    ap.add_argument("--only", default="", help="run a single leg for profiling: fused|groupby|groupby16|c4|c5|tree|treesweep|keymap|agg|domain|sweep|sfsweep|materialized|copy")
     args = ap.parse_args()
     if args.gpus != 1:
         sys.exit("bench.py: this build is single-GPU by design (no collectives, no sharding); "
@@ -299,6 +299,31 @@ def main():
                                           "frac": gbps / HBM_PEAK_GBPS, "algorithmic_bytes_per_row": 16,
                                           "gather_GBps": 192.0 * nt / (ms * 1e-3) / 1e9}}
         del wt, tables
+
+    # ---------------------------------------------------------------- trees of growing size (only on request)
+    # cardinality settings 1 (large dimension tables, sf 4) and 2 (small ones), leaves 8 .. 2,048:
+    # where the pre-fusion stage starts to dominate (Section 4.4, the tree experiments)
+    if args.only == "treesweep":
+        cells = {}
+        for setting, nt, rows in (("setting1_sf4", 2_400_000, (40_000, 8_000, 2_555)),
+                                  ("setting2", 2_400_000, (1_000, 500, 2_555))):
+            wt = WL.make_predict("tree_sweep", nt, 0, rows, (43, 43, 42), (1,), seed=WL.SEED0 + 720, device=dev)
+            for leaves in (8, 64, 256, 1024, 2048):
+                tree = WL.make_tree(128, leaves, WL.SEED0 + 721 + leaves)
+                tf, tt, tH = tree.feature.to(dev), tree.threshold.to(dev), tree.H.to(dev)
+                tables, target = lq.lq_tree_project_dims(wt.dims, 0, tf, tt, tH)
+                pms, _, _ = time_call(lambda: lq.lq_tree_project_dims(wt.dims, 0, tf, tt, tH), 3, 1)
+                ms, _, _ = time_call(lambda: lq.lq_fused_join_tree(None, wt.fks, tables, target, tf, tt, tH), 5, 1)
+                mms, _, _ = time_call(lambda: lq.lq_materialized_join_tree(None, wt.dims, wt.fks, tf, tt, tH,
+                                                                           chunk_rows=1 << 19), 1, 1)
+                cells[f"{setting}_l{leaves}"] = {"fused_ms": round(ms, 4), "prefusion_ms": round(pms, 4),
+                                                 "materialized_ms": round(mms, 3),
+                                                 "speedup_join_stage": round(mms / ms, 1),
+                                                 "speedup_with_prefusion": round(mms / (ms + pms), 1)}
+                del tables
+            del wt
+            torch.cuda.empty_cache()
+        out["tree_sweep"] = {"fact_rows": 2_400_000, "joined_cols": 128, "cells": cells}
 
     # ---------------------------------------------------------------- key -> row mapping (SSB sf1 shape)
     if (args.only == "" and not args.no_extras) or args.only == "keymap":

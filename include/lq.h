@@ -297,14 +297,16 @@ int lq_fused_join_tree(const lq_star* star, const lq_tree* tree, const void* con
                        void* ws, size_t ws_bytes, void* hip_stream);
 
 /*
- * Non-fused tree pipeline: T is written to the workspace chunk by chunk, then
- * ((T F > v) H) == h is evaluated on it.  Workspace as for lq_materialized_join_predict with a
- * one-layer model of the joined width (lq_tree_workspace_bytes gives the size).
+ * Non-fused tree pipeline in the matrix form of Section 3.3.1: T is written to the workspace chunk
+ * by chunk, then B = (T F > v) (0 / 1), R = B H as a dense product on the matrix cores and
+ * (R == h) are evaluated on it.  The workspace holds h, H in bf16 and, per chunk row, a row of T, of
+ * B and of R; ws_bytes decides the chunk (at least 256 rows must fit;
+ * lq_tree_workspace_bytes(star, tree, chunk_rows) gives the size for a wanted chunk).
  */
 int lq_materialized_join_tree(const lq_star* star, const lq_tree* tree, int32_t* leaf,
                               uint8_t* onehot, void* ws, size_t ws_bytes, uint32_t flags,
                               void* hip_stream);
-size_t lq_tree_workspace_bytes(const lq_star* star, int64_t chunk_rows);
+size_t lq_tree_workspace_bytes(const lq_star* star, const lq_tree* tree, int64_t chunk_rows);
 
 /* ---------------------------------------------------------------------------------------
  * Key -> row mapping (the "domain generation" of the MM-Join, Algorithm 1, and the domain

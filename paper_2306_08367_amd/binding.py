@@ -127,7 +127,7 @@ def _load():
     lib.lq_tree_project_dims.argtypes = [ps, pt, ctypes.POINTER(vp), vp, vp]
     lib.lq_fused_join_tree.argtypes = [ps, pt, ctypes.POINTER(vp), vp, vp, vp, u32, vp, sz, vp]
     lib.lq_materialized_join_tree.argtypes = [ps, pt, vp, vp, vp, sz, u32, vp]
-    lib.lq_tree_workspace_bytes.argtypes = [ps, i64]
+    lib.lq_tree_workspace_bytes.argtypes = [ps, pt, i64]
     lib.lq_tree_workspace_bytes.restype = sz
     lib.lq_last_error.restype = ctypes.c_char_p
     lib.lq_version.restype = ctypes.c_char_p
@@ -433,7 +433,8 @@ def lq_materialized_join_tree(X: Optional[torch.Tensor], dims, fks, feature, thr
     star = _Star(n, X, dims, fks)
     if ws is None:
         rows = chunk_rows or min(max(n, 256), 1 << 22)
-        ws = torch.empty(int(_lib.lq_tree_workspace_bytes(ctypes.byref(star.c), rows)), dtype=torch.uint8, device=dev)
+        ws = torch.empty(int(_lib.lq_tree_workspace_bytes(ctypes.byref(star.c), ctypes.byref(tree), rows)), dtype=torch.uint8,
+                         device=dev)
     _check(_lib.lq_materialized_join_tree(ctypes.byref(star.c), ctypes.byref(tree),
                                           None if leaf is None else leaf.data_ptr(),
                                           None if onehot is None else onehot.data_ptr(), ws.data_ptr(),

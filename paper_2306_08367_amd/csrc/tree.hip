@@ -12,6 +12,9 @@
 #include "lq_common.h"
 
 namespace lq {
+int launch_gemm(const void* A, int64_t lda, const void* B, int64_t ldb, void* C, int64_t ldc,
+                const void* bias, int64_t M, int32_t N, int32_t Kd, int relu, int32_t in_dtype,
+                int32_t out_dtype, hipStream_t s);
 namespace {
 
 typedef unsigned int v4u __attribute__((ext_vector_type(4)));
@@ -85,21 +88,33 @@ __global__ __launch_bounds__(256) void tree_project_bits_kernel(TreeArgs t, cons
       if (f >= 0 && f < c) { fcol[w] = f; thr[w] = t.thr[q]; }
     }
   }
-  for (int j0 = 0; j0 < t.ld; j0 += 64) {
+  u64 owned[W];
+#pragma unroll
+  for (int w = 0; w < W; ++w) owned[w] = __ballot(fcol[w] >= 0);
+  {                                       // blockIdx.y selects the 64 leaves this workgroup writes
+    const int j0 = blockIdx.y * 64;
     const int j = j0 + lane;
     u64 plus[W], minus[W];
 #pragma unroll
     for (int w = 0; w < W; ++w) { plus[w] = 0; minus[w] = 0; }
+    // sixteen entries of the leaf's column of H are requested at a time; which nodes this dimension owns
+    // is known from the lanes' own nodes (owned[w], the same for every lane)
     if (j < t.l) {
 #pragma unroll
       for (int w = 0; w < W; ++w)
-        for (int b = 0; b < 64 && 64 * w + b < t.p; ++b) {
-          const int q = 64 * w + b;
-          const int f = t.feature[q] - col_off;                // uniform: the same node for all lanes
-          if (f < 0 || f >= c) continue;                       // node owned by another table
-          const int hv = t.H[static_cast<int64_t>(q) * t.l + j];
-          if (hv > 0) plus[w] |= 1ull << b;
-          if (hv < 0) minus[w] |= 1ull << b;
+        for (int b0 = 0; b0 < 64 && 64 * w + b0 < t.p; b0 += 16) {
+          int hv[16];
+#pragma unroll
+          for (int u = 0; u < 16; ++u) {
+            const int q = 64 * w + b0 + u;
+            const bool use = q < t.p && ((owned[w] >> (b0 + u)) & 1ull);
+            hv[u] = use ? t.H[static_cast<int64_t>(q) * t.l + j] : 0;
+          }
+#pragma unroll
+          for (int u = 0; u < 16; ++u) {
+            if (hv[u] > 0) plus[w] |= 1ull << (b0 + u);
+            if (hv[u] < 0) minus[w] |= 1ull << (b0 + u);
+          }
         }
     }
     for (int64_t r0 = wave * 4; r0 < rows; r0 += nwaves * 4) {
@@ -322,41 +337,58 @@ __global__ __launch_bounds__(256) void fused_tree_batch_kernel(FusedTreeArgs a) 
 
 // ---------------------------------------------------------------- non-fused ----------------
 
-// ((T F > v) H) == h on a chunk of the materialised join.  A workgroup takes RB rows at a time:
-// step 2 of the matrix form (the predicate bits of every node) goes to LDS, step 3/4 is one
-// thread per (row, leaf).
-__global__ __launch_bounds__(256) void tree_eval_kernel(TreeArgs t, const float* __restrict__ T, int64_t ldt,
-                                                        int64_t rows, int64_t row0, const uint8_t* target,
-                                                        int32_t* leaf, uint8_t* onehot, int RB) {
-  extern __shared__ int smem_i[];
-  int* first = smem_i;                                   // [RB]
-  uint8_t* bits = reinterpret_cast<uint8_t*>(smem_i + RB);   // [RB][p]
-  const int tid = threadIdx.x;
-  const int64_t n_tiles = (rows + RB - 1) / RB;
-  for (int64_t tile = blockIdx.x; tile < n_tiles; tile += gridDim.x) {
-    const int64_t r0 = tile * RB;
-    const int nr = static_cast<int>(min<int64_t>(RB, rows - r0));
-    for (int i = tid; i < nr; i += 256) first[i] = 0x7fffffff;
-    for (int idx = tid; idx < nr * t.p; idx += 256) {
-      const int r = idx / t.p, q = idx - r * t.p;
-      bits[r * t.p + q] = T[(r0 + r) * ldt + t.feature[q]] > t.thr[q];
+// The non-fused pipeline in the matrix form of Section 3.3.1 on a chunk of the materialised join:
+//   step 1-2  B = (T F > v): F holds a single 1 per column, so T F is the gather of one column of
+//             T per node; B is written as bf16 0 / 1, its row padded with zeros to a multiple of 8
+//   step 3    R = B H as a dense product on the matrix cores (H in bf16; 0 / +-1 values and counts
+//             up to 255 are exact in bf16 x bf16 -> fp32)
+//   step 4    (R == h), h_j = number of +1 entries of column j of H
+__global__ __launch_bounds__(256) void tree_bits_kernel(TreeArgs t, const float* __restrict__ T, int64_t ldt,
+                                                        int64_t rows, bf16_t* __restrict__ B, int64_t ldb) {
+  const int64_t total = rows * ldb;
+  for (int64_t idx = static_cast<int64_t>(blockIdx.x) * 256 + threadIdx.x; idx < total;
+       idx += static_cast<int64_t>(gridDim.x) * 256) {
+    const int64_t r = idx / ldb;
+    const int q = static_cast<int>(idx - r * ldb);
+    const bool bit = q < t.p && T[r * ldt + t.feature[q]] > t.thr[q];
+    B[idx] = bit ? static_cast<bf16_t>(0x3F80) : static_cast<bf16_t>(0);
+  }
+}
+
+// H as bf16 [p_pad x ldh] (zero padding) and h as fp32 [l].
+__global__ __launch_bounds__(256) void tree_h_kernel(TreeArgs t, int32_t p_pad, bf16_t* __restrict__ Hb, int64_t ldh,
+                                                     float* __restrict__ hplus) {
+  const int64_t total = static_cast<int64_t>(p_pad) * ldh;
+  for (int64_t idx = static_cast<int64_t>(blockIdx.x) * 256 + threadIdx.x; idx < total;
+       idx += static_cast<int64_t>(gridDim.x) * 256) {
+    const int q = static_cast<int>(idx / ldh), j = static_cast<int>(idx - static_cast<int64_t>(q) * ldh);
+    const int hv = (q < t.p && j < t.l) ? t.H[static_cast<int64_t>(q) * t.l + j] : 0;
+    Hb[idx] = hv > 0 ? static_cast<bf16_t>(0x3F80) : (hv < 0 ? static_cast<bf16_t>(0xBF80) : static_cast<bf16_t>(0));
+  }
+  for (int j = blockIdx.x * 256 + threadIdx.x; j < t.l; j += gridDim.x * 256) {
+    int cnt = 0;
+    for (int q = 0; q < t.p; ++q) cnt += t.H[static_cast<int64_t>(q) * t.l + j] > 0;
+    hplus[j] = static_cast<float>(cnt);
+  }
+}
+
+// One wavefront per row: lanes sweep the leaves, a ballot finds the first match.
+__global__ __launch_bounds__(256) void tree_match_kernel(int32_t l, const float* __restrict__ R, int64_t ldr,
+                                                         int64_t rows, int64_t row0, const float* __restrict__ hplus,
+                                                         int32_t* __restrict__ leaf, uint8_t* __restrict__ onehot) {
+  const int lane = threadIdx.x & 63;
+  const int64_t wave = static_cast<int64_t>(blockIdx.x) * 4 + (threadIdx.x >> 6);
+  const int64_t nwaves = static_cast<int64_t>(gridDim.x) * 4;
+  for (int64_t r = wave; r < rows; r += nwaves) {
+    int first = -1;
+    for (int j0 = 0; j0 < l; j0 += 64) {
+      const int j = j0 + lane;
+      const bool hit = j < l && R[r * ldr + j] == hplus[j];
+      if (onehot && j < l) onehot[(row0 + r) * l + j] = hit;
+      const unsigned long long m = __ballot(hit);
+      if (first < 0 && m != 0ull) first = j0 + __builtin_ctzll(m);
     }
-    __syncthreads();
-    for (int idx = tid; idx < nr * t.l; idx += 256) {
-      const int r = idx / t.l, j = idx - r * t.l;
-      int agree = 0;
-      for (int q = 0; q < t.p; ++q) {
-        const int hv = t.H[static_cast<int64_t>(q) * t.l + j];
-        agree += hv != 0 && (bits[r * t.p + q] != 0) == (hv > 0);
-      }
-      const bool hit = agree == target[j];
-      if (onehot) onehot[(row0 + r0 + r) * t.l + j] = hit;
-      if (hit) atomicMin(&first[r], j);
-    }
-    __syncthreads();
-    if (leaf)
-      for (int i = tid; i < nr; i += 256) leaf[row0 + r0 + i] = first[i] == 0x7fffffff ? -1 : first[i];
-    __syncthreads();
+    if (leaf && lane == 0) leaf[row0 + r] = first;
   }
 }
 
@@ -419,7 +451,7 @@ int lq_tree_project_dims(const lq_star* star, const lq_tree* tree, void* const* 
   int32_t off = star->fact.cols;
   for (int k = 0; k < star->n_dims; ++k) {
     const lq_mat& d = star->dims[k];
-    if (t.p > 256 && t.p <= 0x7fff) {   // short node lists are cheaper to scan densely
+    if (t.p > 256 && t.p <= 0x7fff) {   // beyond 4 mask words per leaf the per-leaf node lists are as fast or faster (measured up to 16 words)
       const int64_t col_tiles = (t.ld + TP_COLS - 1) / TP_COLS;
       // enough row slices to fill the GPU, each long enough to amortise building the lists
       int64_t slices = std::max<int64_t>(1, std::min<int64_t>((static_cast<int64_t>(num_cus()) * 4 + col_tiles - 1) / col_tiles,
@@ -431,8 +463,12 @@ int lq_tree_project_dims(const lq_star* star, const lq_tree* tree, void* const* 
                          static_cast<uint8_t*>(tables[k]), rpb);
       LQ_LAUNCH_CHECK("tree_project_sparse_kernel");
     } else if (t.p <= 256) {
-      const int64_t blocks = std::max<int64_t>(1, std::min<int64_t>((d.rows + 15) / 16, static_cast<int64_t>(num_cus()) * 8));
-      const dim3 grid(static_cast<unsigned>(blocks)), block(256);
+      // every wavefront builds the node masks of its 64 leaves once (p loads): give it at least p / 8
+      // rows to spread that over
+      const int64_t rows_per_block = 4 * std::max<int64_t>(4, t.p / 8);
+      const int64_t blocks = std::max<int64_t>(1, std::min<int64_t>((d.rows + rows_per_block - 1) / rows_per_block,
+                                                                    static_cast<int64_t>(num_cus()) * 8));
+      const dim3 grid(static_cast<unsigned>(blocks), static_cast<unsigned>((t.ld + 63) / 64)), block(256);
       const float* dd = static_cast<const float*>(d.data);
       uint8_t* tab = static_cast<uint8_t*>(tables[k]);
       if (t.p <= 64) hipLaunchKernelGGL(tree_project_bits_kernel<1>, grid, block, 0, s, t, dd, d.ld, d.rows, off, d.cols, tab);
@@ -515,13 +551,29 @@ int lq_fused_join_tree(const lq_star* star, const lq_tree* tree, const void* con
   return LQ_OK;
 }
 
-size_t lq_tree_workspace_bytes(const lq_star* star, int64_t chunk_rows) {
-  if (!star || chunk_rows < 1 || star->n_dims < 0 || star->n_dims > LQ_MAX_DIMS) return 0;
-  if (star->n_dims > 0 && !star->dims) return 0;
+// Workspace layout of the non-fused pipeline: [256 header | h fp32 | H bf16 | per chunk: T, B, R].
+struct TreeWs { size_t fixed, per_row; int64_t ldt, ldb, ldh, ldr; int32_t p_pad; };
+static bool tree_ws_layout(const lq_star* star, const lq_tree* tree, TreeWs* w) {
+  if (!star || !tree || star->n_dims < 0 || star->n_dims > LQ_MAX_DIMS) return false;
+  if (star->n_dims > 0 && !star->dims) return false;
+  if (tree->n_nodes < 1 || tree->n_leaves < 1 || tree->n_leaves > 16384) return false;
   size_t kw = star->fact.cols > 0 ? star->fact.cols : 0;
   for (int k = 0; k < star->n_dims; ++k) kw += star->dims[k].cols;
-  const size_t rows = round_up(static_cast<size_t>(chunk_rows), 256);
-  return 256 + round_up(rows * round_up(kw, 4) * 4, 256) + 256 + 16384;
+  w->ldt = static_cast<int64_t>(round_up(kw, 4));
+  w->p_pad = static_cast<int32_t>(round_up(static_cast<size_t>(tree->n_nodes), 8));
+  w->ldb = w->p_pad;
+  w->ldh = static_cast<int64_t>(round_up(static_cast<size_t>(tree->n_leaves), 8));
+  w->ldr = w->ldh;
+  w->fixed = 256 + round_up(static_cast<size_t>(tree->n_leaves) * 4, 256) +
+             round_up(static_cast<size_t>(w->p_pad) * w->ldh * 2, 256);
+  w->per_row = static_cast<size_t>(w->ldt) * 4 + static_cast<size_t>(w->ldb) * 2 + static_cast<size_t>(w->ldr) * 4;
+  return true;
+}
+
+size_t lq_tree_workspace_bytes(const lq_star* star, const lq_tree* tree, int64_t chunk_rows) {
+  TreeWs w;
+  if (chunk_rows < 1 || !tree_ws_layout(star, tree, &w)) return 0;
+  return w.fixed + round_up(static_cast<size_t>(chunk_rows), 256) * w.per_row + 3 * 256;
 }
 
 int lq_materialized_join_tree(const lq_star* star, const lq_tree* tree, int32_t* leaf, uint8_t* onehot,
@@ -538,32 +590,40 @@ int lq_materialized_join_tree(const lq_star* star, const lq_tree* tree, int32_t*
   for (int k = 0; k < star->n_dims; ++k)
     if (!star->fks[k]) return fail(LQ_ERR_NULL, "fks[%d] is NULL", k);
   if (!ws || !aligned(ws, 256)) return fail(LQ_ERR_WORKSPACE, "workspace is NULL or not 256-byte aligned");
-  size_t kw = star->fact.cols;
-  for (int k = 0; k < star->n_dims; ++k) kw += star->dims[k].cols;
-  const int64_t ldt = static_cast<int64_t>(round_up(kw, 4));
-  const size_t fixed = 256 + 256 + 16384;            // header, slack, target vector
-  if (ws_bytes < fixed + 256 * static_cast<size_t>(ldt) * 4)
-    return fail(LQ_ERR_WORKSPACE, "workspace cannot hold one 256-row chunk");
-  int64_t chunk = static_cast<int64_t>((ws_bytes - fixed) / (static_cast<size_t>(ldt) * 4)) / 256 * 256;
+  TreeWs w;
+  if (!tree_ws_layout(star, tree, &w)) return fail(LQ_ERR_SHAPE, "star or tree is malformed");
+  if (ws_bytes < w.fixed + 3 * 256 + 256 * w.per_row)
+    return fail(LQ_ERR_WORKSPACE, "workspace cannot hold one 256-row chunk (%zu bytes needed)",
+                w.fixed + 3 * 256 + 256 * w.per_row);
+  int64_t chunk = static_cast<int64_t>((ws_bytes - w.fixed - 3 * 256) / w.per_row) / 256 * 256;
   chunk = std::min<int64_t>(chunk, static_cast<int64_t>(round_up(static_cast<size_t>(star->n_fact), 256)));
-  uint8_t* target = static_cast<uint8_t*>(ws) + 256;                       // ld <= 16384 bytes
-  float* T = reinterpret_cast<float*>(static_cast<char*>(ws) + 256 + 16384 + 256);
+  char* base = static_cast<char*>(ws) + 256;
+  float* hplus = reinterpret_cast<float*>(base);
+  bf16_t* Hb = reinterpret_cast<bf16_t*>(base + round_up(static_cast<size_t>(t.l) * 4, 256));
+  char* per_chunk = static_cast<char*>(ws) + w.fixed;
+  float* T = reinterpret_cast<float*>(per_chunk);
+  bf16_t* B = reinterpret_cast<bf16_t*>(per_chunk + round_up(static_cast<size_t>(chunk) * w.ldt * 4, 256));
+  float* R = reinterpret_cast<float*>(reinterpret_cast<char*>(B) + round_up(static_cast<size_t>(chunk) * w.ldb * 2, 256));
   (void)flags;
   hipStream_t s = static_cast<hipStream_t>(hip_stream);
-  hipLaunchKernelGGL(tree_target_kernel, dim3(static_cast<unsigned>((t.ld + 255) / 256)), dim3(256), 0, s, t, target);
-  LQ_LAUNCH_CHECK("tree_target_kernel");
-  int RB = 8;
-  while (RB > 1 && static_cast<size_t>(RB) * (t.p + 4) > 48 * 1024) RB >>= 1;
-  if (static_cast<size_t>(RB) * (t.p + 4) > 48 * 1024) return fail(LQ_ERR_UNSUPPORTED, "too many tree nodes");
-  const size_t lds = static_cast<size_t>(RB) * 4 + round_up(static_cast<size_t>(RB) * t.p, 4);
+  const int cus = num_cus();
+  {
+    const int64_t total = static_cast<int64_t>(w.p_pad) * w.ldh;
+    const int64_t blocks = std::max<int64_t>(1, std::min<int64_t>((total + 255) / 256, static_cast<int64_t>(cus) * 8));
+    hipLaunchKernelGGL(tree_h_kernel, dim3(static_cast<unsigned>(blocks)), dim3(256), 0, s, t, w.p_pad, Hb, w.ldh, hplus);
+    LQ_LAUNCH_CHECK("tree_h_kernel");
+  }
   for (int64_t r0 = 0; r0 < star->n_fact; r0 += chunk) {
     const int64_t m = std::min<int64_t>(chunk, star->n_fact - r0);
-    if ((rc = launch_materialize(*star, T, ldt, r0, m, s))) return rc;
-    const int64_t tiles = (m + RB - 1) / RB;
-    const int64_t blocks = std::min<int64_t>(tiles, static_cast<int64_t>(num_cus()) * 16);
-    hipLaunchKernelGGL(tree_eval_kernel, dim3(static_cast<unsigned>(blocks)), dim3(256), lds, s, t, T, ldt, m, r0,
-                       target, leaf, onehot, RB);
-    LQ_LAUNCH_CHECK("tree_eval_kernel");
+    if ((rc = launch_materialize(*star, T, w.ldt, r0, m, s))) return rc;
+    const int64_t bit_blocks = std::min<int64_t>((m * w.ldb + 255) / 256, static_cast<int64_t>(cus) * 32);
+    hipLaunchKernelGGL(tree_bits_kernel, dim3(static_cast<unsigned>(bit_blocks)), dim3(256), 0, s, t, T, w.ldt, m, B, w.ldb);
+    LQ_LAUNCH_CHECK("tree_bits_kernel");
+    if ((rc = launch_gemm(B, w.ldb, Hb, w.ldh, R, w.ldr, nullptr, m, t.l, w.p_pad, 0, LQ_BF16, LQ_F32, s))) return rc;
+    const int64_t match_blocks = std::min<int64_t>((m + 3) / 4, static_cast<int64_t>(cus) * 16);
+    hipLaunchKernelGGL(tree_match_kernel, dim3(static_cast<unsigned>(match_blocks)), dim3(256), 0, s, t.l, R, w.ldr, m, r0,
+                       hplus, leaf, onehot);
+    LQ_LAUNCH_CHECK("tree_match_kernel");
   }
   return LQ_OK;
 }

@@ -177,7 +177,7 @@ def test_tree_entry_points_reject_bad_arguments():
     # materialised: workspace too small
     assert lib.lq_materialized_join_tree(ctypes.byref(star), ctypes.byref(tree), FAKE, None, FAKE, 1024, 0,
                                          None) == 4
-    assert lib.lq_tree_workspace_bytes(ctypes.byref(star), 256) >= 256 * 5 * 4
+    assert lib.lq_tree_workspace_bytes(ctypes.byref(star), ctypes.byref(tree), 256) >= 256 * 5 * 4
 
 
 def test_keymap_entry_points_reject_bad_arguments():
