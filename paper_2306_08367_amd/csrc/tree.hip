@@ -160,13 +160,22 @@ __global__ __launch_bounds__(256) void tree_project_sparse_kernel(TreeArgs t, co
   {
     const int j = tid % TP_COLS;
     if (j0 + j < t.l)
-      for (int q = tid / TP_COLS; q < t.p; q += 256 / TP_COLS) {
-        const int hv = t.H[static_cast<int64_t>(q) * t.l + j0 + j];
-        if (hv == 0) continue;
-        const int f = t.feature[q] - col_off;
-        if (f < 0 || f >= c) continue;                       // node owned by another table
-        const int slot = atomicAdd(&count[j], 1);
-        if (slot < TP_MAXPATH) list[j][slot] = static_cast<unsigned short>(q | (hv < 0 ? 0x8000 : 0));
+      for (int q0 = tid / TP_COLS; q0 < t.p; q0 += 8 * (256 / TP_COLS)) {   // eight entries of H requested at a time
+        int hv[8];
+#pragma unroll
+        for (int u = 0; u < 8; ++u) {
+          const int q = q0 + u * (256 / TP_COLS);
+          hv[u] = q < t.p ? t.H[static_cast<int64_t>(q) * t.l + j0 + j] : 0;
+        }
+#pragma unroll
+        for (int u = 0; u < 8; ++u) {
+          if (hv[u] == 0) continue;
+          const int q = q0 + u * (256 / TP_COLS);
+          const int f = t.feature[q] - col_off;
+          if (f < 0 || f >= c) continue;                     // node owned by another table
+          const int slot = atomicAdd(&count[j], 1);
+          if (slot < TP_MAXPATH) list[j][slot] = static_cast<unsigned short>(q | (hv[u] < 0 ? 0x8000 : 0));
+        }
       }
   }
   __syncthreads();
