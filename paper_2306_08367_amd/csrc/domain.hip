@@ -48,9 +48,10 @@ __global__ __launch_bounds__(256) void domain_clear_kernel(int32_t* slots, uint3
 
 // Every row either finds a slot whose representative row holds the same tuple or claims an empty
 // slot for itself.  Claimed slots are listed in `reps` (the first MAX_DISTINCT + 1 of them).
-__global__ __launch_bounds__(256) void domain_insert_kernel(Cols t, int64_t rows, int32_t* slots, uint32_t mask,
-                                                            uint32_t shift, uint32_t* header, uint32_t* reps) {
-  const int64_t i = static_cast<int64_t>(blockIdx.x) * 256 + threadIdx.x;
+__global__ __launch_bounds__(256) void domain_insert_kernel(Cols t, int64_t first, int64_t rows, int32_t* slots,
+                                                            uint32_t mask, uint32_t shift, uint32_t* header,
+                                                            uint32_t* reps) {
+  const int64_t i = first + static_cast<int64_t>(blockIdx.x) * 256 + threadIdx.x;
   if (i >= rows) return;
   uint32_t s = hash_row(t, i, shift) & mask;
   for (uint32_t probes = 0; probes <= mask; ++probes) {           // bounded: at most one sweep of the table
@@ -247,8 +248,17 @@ int lq_group_domain(int64_t rows, int32_t n_cols, const int32_t* const* cols, in
   const unsigned row_blocks = static_cast<unsigned>((rows + 255) / 256);
   hipLaunchKernelGGL(domain_clear_kernel, dim3((cap + 255) / 256), dim3(256), 0, s, slots, cap, header);
   LQ_LAUNCH_CHECK("domain_clear_kernel");
-  hipLaunchKernelGGL(domain_insert_kernel, dim3(row_blocks), dim3(256), 0, s, t, rows, slots, cap - 1, shift, header, reps);
+  // A small first slice claims the slots of the frequent tuples, so that the bulk of the rows only reads
+  // them: with few distinct tuples, half a million lanes racing for the same empty slots cost 20x more.
+  const int64_t head = std::min<int64_t>(rows, 8192);
+  hipLaunchKernelGGL(domain_insert_kernel, dim3(static_cast<unsigned>((head + 255) / 256)), dim3(256), 0, s, t,
+                     static_cast<int64_t>(0), head, slots, cap - 1, shift, header, reps);
   LQ_LAUNCH_CHECK("domain_insert_kernel");
+  if (rows > head) {
+    hipLaunchKernelGGL(domain_insert_kernel, dim3(static_cast<unsigned>((rows - head + 255) / 256)), dim3(256), 0, s, t,
+                       head, rows, slots, cap - 1, shift, header, reps);
+    LQ_LAUNCH_CHECK("domain_insert_kernel");
+  }
   uint32_t d = 0;
   LQ_HIP_TRY(hipMemcpyAsync(&d, header, sizeof(d), hipMemcpyDeviceToHost, s));
   LQ_HIP_TRY(hipStreamSynchronize(s));
