@@ -67,7 +67,7 @@ def main():
     ap.add_argument("--rows", type=int, default=10_000_000, help="fact rows of the headline workload")
     ap.add_argument("--no-extras", action="store_true", help="skip materialised / group-by / skewed legs")
     ap.add_argument("--no-cpu", action="store_true", help="skip the CPU oracle baseline")
-    ap.add_argument("--only", default="", help="run a single leg for profiling: fused|groupby|groupby16|c4|c5|tree|treesweep|keymap|agg|domain|sweep|sfsweep|materialized|copy")
+    ap.add_argument("--only", default="", help="run a single leg for profiling: fused|c1|groupby|groupby16|c4|c5|tree|treesweep|keymap|agg|domain|sweep|sfsweep|materialized|copy")
     args = ap.parse_args()
     if args.gpus != 1:
         sys.exit("bench.py: this build is single-GPU by design (no collectives, no sharding); "
@@ -185,6 +185,21 @@ def main():
         del ws, Ym
     del w, P, Y
     torch.cuda.empty_cache()
+
+    # ---------------------------------------------------------------- tiny linear regression (launch-latency sized)
+    if (args.only == "" and not args.no_extras) or args.only == "c1":
+        w1 = WL.c1_tiny_linear(device=dev)
+        P1 = [torch.empty((d.shape[0], 1), dtype=torch.float32, device=dev) for d in w1.dims]
+        Y1 = torch.empty((w1.n, 1), dtype=torch.float32, device=dev)
+        ws1 = torch.empty(lq.lq_workspace_bytes(lq.binding.LQ_CALL_MATERIALIZED, w1.k, w1.weights, 16_384),
+                          dtype=torch.uint8, device=dev)
+        pus, _, _ = time_call(lambda: lq.lq_project_dims(w1.dims, w1.weights[0], w1.c_f, P=P1), 50, 5)
+        fus, _, _ = time_call(lambda: lq.lq_fused_join_predict(w1.X, w1.fks, P1, w1.weights, None, Y=Y1), 50, 5)
+        mus, _, _ = time_call(lambda: lq.lq_materialized_join_predict(w1.X, w1.dims, w1.fks, w1.weights, None,
+                                                                      Y=Y1, ws=ws1), 50, 5)
+        out["fused_c1"] = {"fact_rows": w1.n, "fused_us": fus * 1e3, "project_dims_us": pus * 1e3,
+                           "materialized_us": mus * 1e3, "rows_per_s": w1.n / (fus * 1e-3),
+                           "note": "280 KB of traffic: bound by launch latency, reported in microseconds per call"}
 
     # ---------------------------------------------------------------- LA group-by (SSB-sf1 shape)
     if (args.only == "" and not args.no_extras) or args.only == "groupby":
