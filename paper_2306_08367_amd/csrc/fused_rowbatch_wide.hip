@@ -68,7 +68,7 @@ __device__ __forceinline__ void issue_group(const PredictArgs& a, int c, int gro
     }
 }
 
-// L2P: outputs of the second layer rounded up to 1, 4 or 16 (weights of the padding are zero).
+// L2P: outputs of the second layer rounded up to 1, 4, 8 or 16 (weights of the padding are zero).
 template <int CFC, int L2P> struct WConsts {
   float wf[CFC > 0 ? CFC * 4 : 1][4];   // W_f rows x this lane's 4 columns
   float b1[4];
@@ -230,7 +230,8 @@ int pick_layers(const PredictArgs& a, hipStream_t s) {
   }
   const int l2 = a.wout[1];
   if (l2 > 16) return -1;
-  if (l2 > 4) return launch_inst<LPR, K, CFC, 2, 16>(a, s);
+  if (l2 > 8) return launch_inst<LPR, K, CFC, 2, 16>(a, s);
+  if (l2 > 4) return launch_inst<LPR, K, CFC, 2, 8>(a, s);
   if constexpr (NARROW) {
     if (l2 == 1) return launch_inst<LPR, K, CFC, 2, 1>(a, s);
     return launch_inst<LPR, K, CFC, 2, 4>(a, s);
