@@ -1,3 +1,6 @@
+// (Internal header: the kernel template, instantiated in fused_rowbatch_wide_a.hip for 8 / 16 lanes per
+// row and in fused_rowbatch_wide_b.hip for 32 / 64, so that the two halves compile in parallel.)
+//
 // Join-computation stage (last line of Eq. 1) in fp32 for hidden widths 32, 64, 128 and 256, as a
 // linear operator or followed by a second layer of up to 16 outputs: the organisation of the
 // width-64 kernel with a run-time pass loop, so that it covers 8 to 64 lanes per fact row.
@@ -11,6 +14,8 @@
 // in groups of four (two, with many outputs) passes, across batches too.  A second layer is
 // 4 x l_2 multiply-adds per lane and a sum over the lanes of the row per output (DPP adds); the
 // results of pass t are parked in lane t of the group, so a batch ends with one store per row.
+#ifndef LQ_FUSED_ROWBATCH_WIDE_H_
+#define LQ_FUSED_ROWBATCH_WIDE_H_
 #include "lq_common.h"
 
 namespace lq {
@@ -45,13 +50,22 @@ template <int K, int CFC> struct WRow {
 };
 template <int K, int PG> struct WGather { v4f p[PG][K]; };
 
+// x_vec: the row's fact columns are whole, aligned 16-byte pieces; otherwise they are read one by one
+// and the pieces padded with zeros (the matching rows of W_f are zero as well).
 template <int K, int CFC>
-__device__ __forceinline__ void load_rows(const PredictArgs& a, int64_t rr, WRow<K, CFC>& r) {
+__device__ __forceinline__ void load_rows(const PredictArgs& a, int64_t rr, bool x_vec, WRow<K, CFC>& r) {
 #pragma unroll
   for (int k = 0; k < K; ++k) r.fk[k] = __builtin_nontemporal_load(a.fk[k] + rr);
   const float* xr = static_cast<const float*>(a.X) + rr * a.ldx;
+  if (x_vec) {
 #pragma unroll
-  for (int q = 0; q < CFC; ++q) r.x[q] = __builtin_nontemporal_load(reinterpret_cast<const v4f*>(xr) + q);
+    for (int q = 0; q < CFC; ++q) r.x[q] = __builtin_nontemporal_load(reinterpret_cast<const v4f*>(xr) + q);
+  } else {
+#pragma unroll
+    for (int q = 0; q < CFC; ++q)
+#pragma unroll
+      for (int e = 0; e < 4; ++e) r.x[q][e] = 4 * q + e < a.c_f ? xr[4 * q + e] : 0.f;
+  }
 }
 
 // Gathers of passes PG grp .. PG grp + PG - 1.
@@ -142,6 +156,7 @@ void fused_rowbatch_wide_kernel(PredictArgs a) {
   const int64_t nb = (a.n + 63) / 64;
   if (wave >= nb) return;
   const int l2 = NL == 2 ? a.wout[1] : 0;
+  const bool x_vec = a.c_f == 4 * CFC && a.ldx % 4 == 0 && (reinterpret_cast<uintptr_t>(a.X) & 15) == 0;
   const bool y_vec = l2 % 4 == 0 && a.ldy % 4 == 0 && (reinterpret_cast<uintptr_t>(a.Y) & 15) == 0;
 
   WConsts<CFC, L2P> w;
@@ -150,7 +165,7 @@ void fused_rowbatch_wide_kernel(PredictArgs a) {
 #pragma unroll
     for (int q = 0; q < CFC * 4; ++q)
 #pragma unroll
-      for (int v = 0; v < 4; ++v) w.wf[q][v] = W0[static_cast<int64_t>(q) * a.ldw[0] + 4 * c + v];
+      for (int v = 0; v < 4; ++v) w.wf[q][v] = q < a.c_f ? W0[static_cast<int64_t>(q) * a.ldw[0] + 4 * c + v] : 0.f;
 #pragma unroll
     for (int v = 0; v < 4; ++v) w.b1[v] = a.bias[0] ? static_cast<const float*>(a.bias[0])[4 * c + v] : 0.f;
 #pragma unroll
@@ -166,14 +181,14 @@ void fused_rowbatch_wide_kernel(PredictArgs a) {
   int64_t b = wave;
   int64_t row = b * 64 + lane;
   WRow<K, CFC> cur, nxt;
-  load_rows<K, CFC>(a, row < a.n ? row : a.n - 1, cur);
+  load_rows<K, CFC>(a, row < a.n ? row : a.n - 1, x_vec, cur);
   WGather<K, PG> ga, gb;
   issue_group<LPR, K, CFC, PG>(a, c, group_base, 0, cur, ga);
   for (;;) {
     const int64_t bn = b + nwaves;
     const bool more = bn < nb;
     const int64_t rown = bn * 64 + lane;
-    load_rows<K, CFC>(a, (more && rown < a.n) ? rown : a.n - 1, nxt);
+    load_rows<K, CFC>(a, (more && rown < a.n) ? rown : a.n - 1, x_vec, nxt);
     float yk[L2P];
 #pragma unroll
     for (int o = 0; o < L2P; ++o) yk[o] = 0.f;
@@ -241,12 +256,10 @@ int pick_layers(const PredictArgs& a, hipStream_t s) {
 
 template <int LPR, int K, bool NARROW>
 int pick_cf(const PredictArgs& a, hipStream_t s) {
-  switch (a.c_f) {
-    case 0: return pick_layers<LPR, K, 0, NARROW>(a, s);
-    case 4: return pick_layers<LPR, K, 1, NARROW>(a, s);
-    case 8: return pick_layers<LPR, K, 2, NARROW>(a, s);
-    default: return -1;
-  }
+  if (a.c_f == 0) return pick_layers<LPR, K, 0, NARROW>(a, s);
+  if (a.c_f <= 4) return pick_layers<LPR, K, 1, NARROW>(a, s);
+  if (a.c_f <= 8) return pick_layers<LPR, K, 2, NARROW>(a, s);
+  return -1;
 }
 
 template <int LPR, bool NARROW>
@@ -261,22 +274,5 @@ int pick_k(const PredictArgs& a, hipStream_t s) {
 }
 
 }  // namespace
-
-// Returns -1 when the shape is not one this kernel covers.
-int try_rowbatch_wide(const PredictArgs& a, hipStream_t s) {
-  if (a.x_dtype != LQ_F32 || a.p_dtype != LQ_F32 || a.y_dtype != LQ_F32) return -1;
-  if (a.n_layers > 2 || a.n < 256) return -1;
-  for (int k = 0; k < a.K; ++k)
-    if (!aligned(a.P[k], 16) || a.ldp[k] % 4) return -1;
-  if (a.c_f > 0 && (!aligned(a.X, 16) || a.ldx % 4)) return -1;
-  if (a.n_layers == 1 && (!aligned(a.Y, 16) || a.ldy % 4)) return -1;
-  switch (a.wout[0]) {
-    case 32: return pick_k<8, true>(a, s);
-    case 64: return pick_k<16, false>(a, s);     // one to four outputs: the unrolled width-64 kernel, tried first
-    case 128: return pick_k<32, true>(a, s);
-    case 256: return pick_k<64, true>(a, s);
-    default: return -1;
-  }
-}
-
 }  // namespace lq
+#endif  // LQ_FUSED_ROWBATCH_WIDE_H_

@@ -75,6 +75,12 @@ SHAPES = [
     ("mlp_128_9_k4_cf8", 1_931, 8, (50, 60, 70, 80), (6, 6, 6, 6), (128, 9), True),
     ("mlp_256_16_k3", 4_111, 0, (100, 200, 300), (16, 16, 16), (256, 16), True),
     ("mlp_256_5_k2", 769, 4, (100, 200), (16, 16), (256, 5), False),
+    # fact-column counts that are not whole 16-byte pieces (read one by one, padded with zeros)
+    ("mlp_64_1_cf3", 7_001, 3, (1000, 5000, 200), (32, 32, 32), (64, 1), True),
+    ("mlp_128_4_cf5", 2_500, 5, (100, 200), (16, 16), (128, 4), False),
+    ("linear_l32_cf7", 1_900, 7, (100, 200), (16, 16), (32,), True),
+    ("mlp_256_16_cf1", 1_300, 1, (100, 200, 50), (16, 16, 8), (256, 16), True),
+    ("mlp_64_8_cf6_k4", 2_222, 6, (50, 60, 70, 80), (6, 6, 6, 6), (64, 8), True),
     # shapes only the tiled matrix-core MLP kernel covers: wide second layers, three layers
     ("mlp_64_10", 5_555, 4, (100, 2_000, 50), (16, 16, 16), (64, 10), True),
     ("mlp_128_16", 3_001, 4, (100, 200), (16, 16), (128, 16), False),
