@@ -244,3 +244,39 @@ def test_groupby_agg_rejects_bad_arguments():
     assert call(m=ok, ws=None) == 4
     assert call(m=ok, ws_bytes=64) == 4
     assert lib.lq_groupby_agg_workspace_bytes(1, rows, card, 1) > 0
+
+
+def test_group_domain_and_order_groups_reject_bad_arguments():
+    b = _binding()
+    lib = b._lib
+    vp = ctypes.c_void_p
+    cols = (vp * 4)(FAKE, FAKE, FAKE, FAKE)
+    card = ctypes.c_int32(-1)
+    need = lib.lq_group_domain_workspace_bytes(1000)
+    assert need >= 256 + 2 * 2048 * 4 + 65536 * 4 and lib.lq_group_domain_workspace_bytes(-1) == 0
+    args = lambda **kw: dict(dict(rows=1000, n_cols=1, cols=cols, max_card=100, code=FAKE, values=FAKE,
+                                  card=ctypes.byref(card), ws=FAKE, ws_bytes=need), **kw)
+    call = lambda a: lib.lq_group_domain(a["rows"], a["n_cols"], a["cols"], a["max_card"], a["code"], a["values"],
+                                         a["card"], a["ws"], a["ws_bytes"], None)
+    assert call(args(n_cols=0)) == 2 and call(args(n_cols=5)) == 2
+    assert call(args(max_card=0)) == 2 and call(args(max_card=65536)) == 2
+    assert call(args(rows=-1)) == 2
+    assert call(args(cols=None)) == 1 and call(args(card=None)) == 1 and call(args(code=None)) == 1
+    assert call(args(ws=None)) == 4 and call(args(ws_bytes=need - 1)) == 4 and call(args(ws=FAKE + 8)) == 4
+    assert call(args(rows=0, code=None, values=None, ws_bytes=lib.lq_group_domain_workspace_bytes(0))) == 0
+    assert card.value == 0                                        # an empty table has no groups; nothing is launched
+
+    gc = (ctypes.c_int32 * 2)(7, 25)
+    keys = (b.lq_sort_key * 2)(b.lq_sort_key(b.LQ_KEY_GROUP_COLUMN, 0, 0), b.lq_sort_key(b.LQ_KEY_SUM, 0, 1))
+    order = lambda **kw: lib.lq_order_groups(*[dict(dict(n=2, gc=gc, m=1, sums=FAKE, counts=FAKE, nk=2, keys=keys,
+                                                           order=FAKE, n_out=FAKE), **kw)[x]
+                                               for x in ("n", "gc", "m", "sums", "counts", "nk", "keys", "order", "n_out")], None)
+    assert order(n=9) == 2 and order(nk=5) == 2 and order(m=5) == 2
+    assert order(counts=None) == 1 and order(order=None) == 1 and order(n_out=None) == 1 and order(keys=None) == 1
+    assert order(sums=None) == 2                                   # a key asks for a sum that is not given
+    assert order(m=0) == 2                                         # ... or for a measure that does not exist
+    assert order(gc=(ctypes.c_int32 * 2)(8192, 2)) == 6            # more than 8,192 groups
+    assert order(gc=(ctypes.c_int32 * 2)(0, 2)) == 2
+    bad = (b.lq_sort_key * 2)(b.lq_sort_key(b.LQ_KEY_GROUP_COLUMN, 2, 0), b.lq_sort_key(9, 0, 0))
+    assert order(keys=bad) == 2
+    assert order(counts=FAKE + 4) == 2
