@@ -1,18 +1,20 @@
-// (Internal header: the kernel template, instantiated in fused_rowbatch_wide_a.hip for 8 / 16 lanes per
-// row and in fused_rowbatch_wide_b.hip for 32 / 64, so that the two halves compile in parallel.)
+// (Internal header: the kernel template, instantiated in fused_rowbatch_wide_a.hip for fp32 with 8 / 16
+// lanes per row, in fused_rowbatch_wide_b.hip for fp32 with 32 / 64 and in fused_rowbatch_wide_c.hip for
+// bf16, so that the parts compile in parallel.)
 //
-// Join-computation stage (last line of Eq. 1) in fp32 for hidden widths 32, 64, 128 and 256, as a
-// linear operator or followed by a second layer of up to 16 outputs: the organisation of the
-// width-64 kernel with a run-time pass loop, so that it covers 8 to 64 lanes per fact row.
+// Join-computation stage (last line of Eq. 1) as a linear operator or followed by a second layer of
+// up to 16 outputs: the organisation of the width-64 kernel with a run-time pass loop, so that it
+// covers 8 to 64 lanes per fact row, in fp32 (hidden widths 32 .. 256, 4 columns per lane) and in
+// bf16 (hidden widths 64 .. 512, 8 columns per lane, fp32 arithmetic).
 //
 // A wavefront owns 64 consecutive fact rows at a time.  Their fact columns and keys are read once,
-// coalesced (lane l holds row l).  With LPR = l_1 / 4 lanes per row the wavefront is 64 / LPR lane
-// groups; in pass t (0 .. LPR-1) group g works on fact row g LPR + t, lane c of the group owning
-// hidden columns 4c..4c+3, so that a projected row (128 to 1024 bytes) is fetched by one group as
-// one contiguous run.  The row's key and fact values reach the group through the cross-lane
+// coalesced (lane l holds row l).  With LPR lanes per row the wavefront is 64 / LPR lane groups; in
+// pass t (0 .. LPR-1) group g works on fact row g LPR + t, lane c of the group owning the hidden
+// columns of its 16-byte piece, so that a projected row (128 to 1024 bytes) is fetched by one group
+// as one contiguous run.  The row's key and fact values reach the group through the cross-lane
 // network (a lane read for 64 lanes per row, a permute otherwise).  Gathers are software-pipelined
 // in groups of four (two, with many outputs) passes, across batches too.  A second layer is
-// 4 x l_2 multiply-adds per lane and a sum over the lanes of the row per output (DPP adds); the
+// COLS x l_2 multiply-adds per lane and a sum over the lanes of the row per output (DPP adds); the
 // results of pass t are parked in lane t of the group, so a batch ends with one store per row.
 #ifndef LQ_FUSED_ROWBATCH_WIDE_H_
 #define LQ_FUSED_ROWBATCH_WIDE_H_
@@ -22,8 +24,40 @@ namespace lq {
 namespace {
 
 typedef float v4f __attribute__((ext_vector_type(4)));
+typedef unsigned int v4u __attribute__((ext_vector_type(4)));
+typedef unsigned int v2u __attribute__((ext_vector_type(2)));
 
 constexpr int RBW_THREADS = 256;
+
+// What a 16-byte piece of a projected row holds.
+template <typename T> struct Piece;
+template <> struct Piece<float> {
+  static constexpr int COLS = 4;
+  static __device__ __forceinline__ void add(const v4u& raw, float (&z)[4]) {
+#pragma unroll
+    for (int v = 0; v < 4; ++v) z[v] += __uint_as_float(raw[v]);
+  }
+  static __device__ __forceinline__ v4u pack(const float (&z)[4]) {
+    return v4u{__float_as_uint(z[0]), __float_as_uint(z[1]), __float_as_uint(z[2]), __float_as_uint(z[3])};
+  }
+};
+template <> struct Piece<bf16_t> {
+  static constexpr int COLS = 8;
+  static __device__ __forceinline__ void add(const v4u& raw, float (&z)[8]) {
+#pragma unroll
+    for (int q = 0; q < 4; ++q) {
+      z[2 * q] += __uint_as_float(raw[q] << 16);
+      z[2 * q + 1] += __uint_as_float(raw[q] & 0xffff0000u);
+    }
+  }
+  static __device__ __forceinline__ v4u pack(const float (&z)[8]) {
+    v4u o;
+#pragma unroll
+    for (int q = 0; q < 4; ++q)
+      o[q] = static_cast<unsigned int>(f32_to_bf16(z[2 * q])) | (static_cast<unsigned int>(f32_to_bf16(z[2 * q + 1])) << 16);
+    return o;
+  }
+};
 
 template <int CTRL> __device__ __forceinline__ float dppw(float v) {
   return __int_as_float(__builtin_amdgcn_update_dpp(0, __float_as_int(v), CTRL, 0xf, 0xf, false));
@@ -44,32 +78,41 @@ template <int LPR> __device__ __forceinline__ int from_lane(int v, int t, int gr
   else return __shfl(v, group_base | t, 64);
 }
 
+// Per-batch registers: lane l holds fact row (batch * 64 + l); fact columns as fp32.
 template <int K, int CFC> struct WRow {
   int fk[K];
   v4f x[CFC > 0 ? CFC : 1];
 };
-template <int K, int PG> struct WGather { v4f p[PG][K]; };
+template <int K, int PG> struct WGather { v4u p[PG][K]; };
 
-// x_vec: the row's fact columns are whole, aligned 16-byte pieces; otherwise they are read one by one
-// and the pieces padded with zeros (the matching rows of W_f are zero as well).
-template <int K, int CFC>
+// x_vec: the row's fact columns are whole, aligned groups of four; otherwise they are read
+// one by one and the groups padded with zeros (the matching rows of W_f are zero as well).
+template <typename T, int K, int CFC>
 __device__ __forceinline__ void load_rows(const PredictArgs& a, int64_t rr, bool x_vec, WRow<K, CFC>& r) {
 #pragma unroll
   for (int k = 0; k < K; ++k) r.fk[k] = __builtin_nontemporal_load(a.fk[k] + rr);
-  const float* xr = static_cast<const float*>(a.X) + rr * a.ldx;
+  const T* xr = static_cast<const T*>(a.X) + rr * a.ldx;
   if (x_vec) {
 #pragma unroll
-    for (int q = 0; q < CFC; ++q) r.x[q] = __builtin_nontemporal_load(reinterpret_cast<const v4f*>(xr) + q);
+    for (int q = 0; q < CFC; ++q) {
+      if constexpr (sizeof(T) == 4) {
+        r.x[q] = __builtin_nontemporal_load(reinterpret_cast<const v4f*>(xr) + q);
+      } else {                                    // four bf16 values in 8 bytes
+        const v2u t = __builtin_nontemporal_load(reinterpret_cast<const v2u*>(xr) + q);
+        r.x[q] = v4f{__uint_as_float(t[0] << 16), __uint_as_float(t[0] & 0xffff0000u),
+                     __uint_as_float(t[1] << 16), __uint_as_float(t[1] & 0xffff0000u)};
+      }
+    }
   } else {
 #pragma unroll
     for (int q = 0; q < CFC; ++q)
 #pragma unroll
-      for (int e = 0; e < 4; ++e) r.x[q][e] = 4 * q + e < a.c_f ? xr[4 * q + e] : 0.f;
+      for (int e = 0; e < 4; ++e) r.x[q][e] = 4 * q + e < a.c_f ? Elem<T>::load(xr + 4 * q + e) : 0.f;
   }
 }
 
 // Gathers of passes PG grp .. PG grp + PG - 1.
-template <int LPR, int K, int CFC, int PG>
+template <typename T, int LPR, int K, int CFC, int PG>
 __device__ __forceinline__ void issue_group(const PredictArgs& a, int c, int group_base, int grp,
                                             const WRow<K, CFC>& r, WGather<K, PG>& g) {
 #pragma unroll
@@ -77,53 +120,50 @@ __device__ __forceinline__ void issue_group(const PredictArgs& a, int c, int gro
 #pragma unroll
     for (int k = 0; k < K; ++k) {
       const int j = from_lane<LPR>(r.fk[k], PG * grp + u, group_base);
-      g.p[u][k] = *reinterpret_cast<const v4f*>(static_cast<const float*>(a.P[k]) +
-                                                static_cast<int64_t>(j) * a.ldp[k] + 4 * c);
+      g.p[u][k] = *reinterpret_cast<const v4u*>(static_cast<const T*>(a.P[k]) + static_cast<int64_t>(j) * a.ldp[k] +
+                                                Piece<T>::COLS * c);
     }
 }
 
 // L2P: outputs of the second layer rounded up to 1, 4, 8 or 16 (weights of the padding are zero).
-template <int CFC, int L2P> struct WConsts {
-  float wf[CFC > 0 ? CFC * 4 : 1][4];   // W_f rows x this lane's 4 columns
-  float b1[4];
-  float w2[4][L2P];
+template <int COLS, int CFC, int L2P> struct WConsts {
+  float wf[CFC > 0 ? CFC * 4 : 1][COLS];   // W_f rows x this lane's columns
+  float b1[COLS];
+  float w2[COLS][L2P];
   float b2[L2P];
 };
 
-template <int LPR, int K, int CFC, int NL, int L2P, int PG>
+template <typename T, int LPR, int K, int CFC, int NL, int L2P, int PG>
 __device__ __forceinline__ void compute_group(const PredictArgs& a, int c, int group_base, int grp, int64_t row0,
                                               const WRow<K, CFC>& r, const WGather<K, PG>& g,
-                                              const WConsts<CFC, L2P>& w, float (&ykeep)[L2P]) {
+                                              const WConsts<Piece<T>::COLS, CFC, L2P>& w, float (&ykeep)[L2P]) {
+  constexpr int COLS = Piece<T>::COLS;
 #pragma unroll
   for (int u = 0; u < PG; ++u) {
     const int t = PG * grp + u;
-    float z[4];
+    float z[COLS];
 #pragma unroll
-    for (int v = 0; v < 4; ++v) z[v] = w.b1[v];
+    for (int v = 0; v < COLS; ++v) z[v] = w.b1[v];
 #pragma unroll
     for (int q = 0; q < CFC; ++q)
 #pragma unroll
       for (int e = 0; e < 4; ++e) {
         const float xe = __int_as_float(from_lane<LPR>(__float_as_int(r.x[q][e]), t, group_base));
 #pragma unroll
-        for (int v = 0; v < 4; ++v) z[v] = fmaf(xe, w.wf[q * 4 + e][v], z[v]);
+        for (int v = 0; v < COLS; ++v) z[v] = fmaf(xe, w.wf[q * 4 + e][v], z[v]);
       }
 #pragma unroll
-    for (int k = 0; k < K; ++k)
-#pragma unroll
-      for (int v = 0; v < 4; ++v) z[v] += g.p[u][k][v];
+    for (int k = 0; k < K; ++k) Piece<T>::add(g.p[u][k], z);
     if constexpr (NL == 1) {
       const int64_t row = row0 + group_base + t;
-      if (row < a.n) {
-        const v4f o = {z[0], z[1], z[2], z[3]};
-        __builtin_nontemporal_store(o, reinterpret_cast<v4f*>(static_cast<float*>(a.Y) + row * a.ldy + 4 * c));
-      }
+      if (row < a.n)
+        __builtin_nontemporal_store(Piece<T>::pack(z), reinterpret_cast<v4u*>(static_cast<T*>(a.Y) + row * a.ldy + COLS * c));
     } else {
       float y[L2P];
 #pragma unroll
       for (int o = 0; o < L2P; ++o) y[o] = 0.f;
 #pragma unroll
-      for (int v = 0; v < 4; ++v) {
+      for (int v = 0; v < COLS; ++v) {
         const float h = fmaxf(z[v], 0.f);
 #pragma unroll
         for (int o = 0; o < L2P; ++o) y[o] = fmaf(h, w.w2[v][o], y[o]);
@@ -137,17 +177,20 @@ __device__ __forceinline__ void compute_group(const PredictArgs& a, int c, int g
   }
 }
 
-// LPR lanes per row (l_1 = 4 LPR), K dimensions, CFC float4 chunks of fact columns, NL layers,
-// L2P padded outputs of the second layer.
 // Three wavefronts per SIMD leave 170 registers each; the double-buffered gathers of many
 // dimensions plus many fact columns, or the weights of a wide second layer, need more, and two per
 // SIMD is faster than spilling.
-constexpr int waves_per_simd(int K, int CFC, int L2P) { return (L2P > 4 || 32 * K + 24 * CFC + 6 * L2P > 106) ? 2 : 3; }
+constexpr int waves_per_simd(int COLS, int K, int CFC, int L2P) {
+  return (L2P > 4 || 32 * K + (24 * CFC + 6 * L2P) * (COLS / 4) > 106) ? 2 : 3;
+}
 
-template <int LPR, int K, int CFC, int NL, int L2P>
+// T: element type of the model, the tables and the output.  LPR lanes per row (l_1 = COLS x LPR),
+// K dimensions, CFC groups of four fact columns, NL layers, L2P padded outputs of the second layer.
+template <typename T, int LPR, int K, int CFC, int NL, int L2P>
 __global__ __launch_bounds__(RBW_THREADS)
-__attribute__((amdgpu_waves_per_eu(waves_per_simd(K, CFC, L2P), waves_per_simd(K, CFC, L2P))))
+__attribute__((amdgpu_waves_per_eu(waves_per_simd(Piece<T>::COLS, K, CFC, L2P), waves_per_simd(Piece<T>::COLS, K, CFC, L2P))))
 void fused_rowbatch_wide_kernel(PredictArgs a) {
+  constexpr int COLS = Piece<T>::COLS;
   constexpr int PG = L2P > 4 ? 2 : 4;    // passes whose gathers travel together
   constexpr int NG = LPR / PG;           // such groups per batch (even)
   const int lane = threadIdx.x & 63, c = lane & (LPR - 1), group_base = lane & ~(LPR - 1);
@@ -156,66 +199,73 @@ void fused_rowbatch_wide_kernel(PredictArgs a) {
   const int64_t nb = (a.n + 63) / 64;
   if (wave >= nb) return;
   const int l2 = NL == 2 ? a.wout[1] : 0;
-  const bool x_vec = a.c_f == 4 * CFC && a.ldx % 4 == 0 && (reinterpret_cast<uintptr_t>(a.X) & 15) == 0;
+  const bool x_vec = a.c_f == 4 * CFC && a.ldx % 4 == 0 && (reinterpret_cast<uintptr_t>(a.X) & (4 * sizeof(T) - 1)) == 0;
   const bool y_vec = l2 % 4 == 0 && a.ldy % 4 == 0 && (reinterpret_cast<uintptr_t>(a.Y) & 15) == 0;
 
-  WConsts<CFC, L2P> w;
+  WConsts<COLS, CFC, L2P> w;
   {
-    const float* W0 = static_cast<const float*>(a.W[0]);
+    const T* W0 = static_cast<const T*>(a.W[0]);
 #pragma unroll
     for (int q = 0; q < CFC * 4; ++q)
 #pragma unroll
-      for (int v = 0; v < 4; ++v) w.wf[q][v] = q < a.c_f ? W0[static_cast<int64_t>(q) * a.ldw[0] + 4 * c + v] : 0.f;
+      for (int v = 0; v < COLS; ++v)
+        w.wf[q][v] = q < a.c_f ? Elem<T>::load(W0 + static_cast<int64_t>(q) * a.ldw[0] + COLS * c + v) : 0.f;
 #pragma unroll
-    for (int v = 0; v < 4; ++v) w.b1[v] = a.bias[0] ? static_cast<const float*>(a.bias[0])[4 * c + v] : 0.f;
+    for (int v = 0; v < COLS; ++v) w.b1[v] = a.bias[0] ? Elem<T>::load(static_cast<const T*>(a.bias[0]) + COLS * c + v) : 0.f;
 #pragma unroll
     for (int o = 0; o < L2P; ++o) {
       const bool real = NL == 2 && o < l2;
 #pragma unroll
-      for (int v = 0; v < 4; ++v)
-        w.w2[v][o] = real ? static_cast<const float*>(a.W[1])[static_cast<int64_t>(4 * c + v) * a.ldw[1] + o] : 0.f;
-      w.b2[o] = (real && a.bias[1]) ? static_cast<const float*>(a.bias[1])[o] : 0.f;
+      for (int v = 0; v < COLS; ++v)
+        w.w2[v][o] = real ? Elem<T>::load(static_cast<const T*>(a.W[1]) + static_cast<int64_t>(COLS * c + v) * a.ldw[1] + o) : 0.f;
+      w.b2[o] = (real && a.bias[1]) ? Elem<T>::load(static_cast<const T*>(a.bias[1]) + o) : 0.f;
     }
   }
 
   int64_t b = wave;
   int64_t row = b * 64 + lane;
   WRow<K, CFC> cur, nxt;
-  load_rows<K, CFC>(a, row < a.n ? row : a.n - 1, x_vec, cur);
+  load_rows<T, K, CFC>(a, row < a.n ? row : a.n - 1, x_vec, cur);
   WGather<K, PG> ga, gb;
-  issue_group<LPR, K, CFC, PG>(a, c, group_base, 0, cur, ga);
+  issue_group<T, LPR, K, CFC, PG>(a, c, group_base, 0, cur, ga);
   for (;;) {
     const int64_t bn = b + nwaves;
     const bool more = bn < nb;
     const int64_t rown = bn * 64 + lane;
-    load_rows<K, CFC>(a, (more && rown < a.n) ? rown : a.n - 1, x_vec, nxt);
+    load_rows<T, K, CFC>(a, (more && rown < a.n) ? rown : a.n - 1, x_vec, nxt);
     float yk[L2P];
 #pragma unroll
     for (int o = 0; o < L2P; ++o) yk[o] = 0.f;
     const int64_t row0 = b * 64;
 #pragma unroll 1
     for (int grp = 0; grp < NG; grp += 2) {
-      issue_group<LPR, K, CFC, PG>(a, c, group_base, grp + 1, cur, gb);
-      compute_group<LPR, K, CFC, NL, L2P, PG>(a, c, group_base, grp, row0, cur, ga, w, yk);
-      if (grp + 2 < NG) issue_group<LPR, K, CFC, PG>(a, c, group_base, grp + 2, cur, ga);
-      else issue_group<LPR, K, CFC, PG>(a, c, group_base, 0, nxt, ga);   // first group of the next batch (valid rows repeated at the end)
-      compute_group<LPR, K, CFC, NL, L2P, PG>(a, c, group_base, grp + 1, row0, cur, gb, w, yk);
+      issue_group<T, LPR, K, CFC, PG>(a, c, group_base, grp + 1, cur, gb);
+      compute_group<T, LPR, K, CFC, NL, L2P, PG>(a, c, group_base, grp, row0, cur, ga, w, yk);
+      if (grp + 2 < NG) issue_group<T, LPR, K, CFC, PG>(a, c, group_base, grp + 2, cur, ga);
+      else issue_group<T, LPR, K, CFC, PG>(a, c, group_base, 0, nxt, ga);   // first group of the next batch (valid rows repeated at the end)
+      compute_group<T, LPR, K, CFC, NL, L2P, PG>(a, c, group_base, grp + 1, row0, cur, gb, w, yk);
     }
     if constexpr (NL == 2) {
       if (row < a.n) {
-        float* yr = static_cast<float*>(a.Y) + row * a.ldy;
-        if (L2P >= 4 && y_vec) {             // whole 16-byte pieces of the output row
+        T* yr = static_cast<T*>(a.Y) + row * a.ldy;
+        if (L2P >= 4 && y_vec) {             // whole pieces of the output row
 #pragma unroll
           for (int q = 0; q < L2P / 4; ++q)
             if (4 * q < l2) {
-              const v4f o4 = {yk[4 * q] + w.b2[4 * q], yk[4 * q + 1] + w.b2[4 * q + 1],
-                              yk[4 * q + 2] + w.b2[4 * q + 2], yk[4 * q + 3] + w.b2[4 * q + 3]};
-              *reinterpret_cast<v4f*>(yr + 4 * q) = o4;
+              const float o4[4] = {yk[4 * q] + w.b2[4 * q], yk[4 * q + 1] + w.b2[4 * q + 1],
+                                   yk[4 * q + 2] + w.b2[4 * q + 2], yk[4 * q + 3] + w.b2[4 * q + 3]};
+              if constexpr (sizeof(T) == 4) {
+                *reinterpret_cast<v4f*>(yr + 4 * q) = v4f{o4[0], o4[1], o4[2], o4[3]};
+              } else {
+                *reinterpret_cast<v2u*>(yr + 4 * q) =
+                    v2u{static_cast<unsigned int>(f32_to_bf16(o4[0])) | (static_cast<unsigned int>(f32_to_bf16(o4[1])) << 16),
+                        static_cast<unsigned int>(f32_to_bf16(o4[2])) | (static_cast<unsigned int>(f32_to_bf16(o4[3])) << 16)};
+              }
             }
         } else {
 #pragma unroll
           for (int o = 0; o < L2P; ++o)
-            if (o < l2) yr[o] = yk[o] + w.b2[o];
+            if (o < l2) Elem<T>::store(yr + o, yk[o] + w.b2[o]);
         }
       }
     }
@@ -226,49 +276,45 @@ void fused_rowbatch_wide_kernel(PredictArgs a) {
   }
 }
 
-template <int LPR, int K, int CFC, int NL, int L2P>
+template <typename T, int LPR, int K, int CFC, int NL, int L2P>
 int launch_inst(const PredictArgs& a, hipStream_t s) {
   const int64_t nb = (a.n + 63) / 64;
-  const int64_t blocks = std::min<int64_t>((nb + 3) / 4, static_cast<int64_t>(num_cus()) * waves_per_simd(K, CFC, L2P));
-  hipLaunchKernelGGL((fused_rowbatch_wide_kernel<LPR, K, CFC, NL, L2P>), dim3(static_cast<unsigned>(blocks)),
+  const int64_t blocks = std::min<int64_t>((nb + 3) / 4, static_cast<int64_t>(num_cus()) * waves_per_simd(Piece<T>::COLS, K, CFC, L2P));
+  hipLaunchKernelGGL((fused_rowbatch_wide_kernel<T, LPR, K, CFC, NL, L2P>), dim3(static_cast<unsigned>(blocks)),
                      dim3(RBW_THREADS), 0, s, a);
   LQ_LAUNCH_CHECK("fused_rowbatch_wide_kernel");
   return LQ_OK;
 }
 
-// NARROW: the shapes with one to four outputs at this width belong to another kernel.
-template <int LPR, int K, int CFC, bool NARROW>
+// MAXL2: the widest second layer this element type is instantiated for.
+template <typename T, int LPR, int K, int CFC, int MAXL2>
 int pick_layers(const PredictArgs& a, hipStream_t s) {
-  if (a.n_layers == 1) {
-    if constexpr (NARROW) return launch_inst<LPR, K, CFC, 1, 1>(a, s);
-    else return -1;
-  }
+  if (a.n_layers == 1) return launch_inst<T, LPR, K, CFC, 1, 1>(a, s);
   const int l2 = a.wout[1];
-  if (l2 > 16) return -1;
-  if (l2 > 8) return launch_inst<LPR, K, CFC, 2, 16>(a, s);
-  if (l2 > 4) return launch_inst<LPR, K, CFC, 2, 8>(a, s);
-  if constexpr (NARROW) {
-    if (l2 == 1) return launch_inst<LPR, K, CFC, 2, 1>(a, s);
-    return launch_inst<LPR, K, CFC, 2, 4>(a, s);
+  if (l2 > MAXL2) return -1;
+  if constexpr (MAXL2 > 4) {
+    if (l2 > 8) return launch_inst<T, LPR, K, CFC, 2, 16>(a, s);
+    if (l2 > 4) return launch_inst<T, LPR, K, CFC, 2, 8>(a, s);
   }
-  return -1;
+  if (l2 == 1) return launch_inst<T, LPR, K, CFC, 2, 1>(a, s);
+  return launch_inst<T, LPR, K, CFC, 2, 4>(a, s);
 }
 
-template <int LPR, int K, bool NARROW>
+template <typename T, int LPR, int K, int MAXL2>
 int pick_cf(const PredictArgs& a, hipStream_t s) {
-  if (a.c_f == 0) return pick_layers<LPR, K, 0, NARROW>(a, s);
-  if (a.c_f <= 4) return pick_layers<LPR, K, 1, NARROW>(a, s);
-  if (a.c_f <= 8) return pick_layers<LPR, K, 2, NARROW>(a, s);
+  if (a.c_f == 0) return pick_layers<T, LPR, K, 0, MAXL2>(a, s);
+  if (a.c_f <= 4) return pick_layers<T, LPR, K, 1, MAXL2>(a, s);
+  if (a.c_f <= 8) return pick_layers<T, LPR, K, 2, MAXL2>(a, s);
   return -1;
 }
 
-template <int LPR, bool NARROW>
+template <typename T, int LPR, int MAXL2>
 int pick_k(const PredictArgs& a, hipStream_t s) {
   switch (a.K) {
-    case 1: return pick_cf<LPR, 1, NARROW>(a, s);
-    case 2: return pick_cf<LPR, 2, NARROW>(a, s);
-    case 3: return pick_cf<LPR, 3, NARROW>(a, s);
-    case 4: return pick_cf<LPR, 4, NARROW>(a, s);
+    case 1: return pick_cf<T, LPR, 1, MAXL2>(a, s);
+    case 2: return pick_cf<T, LPR, 2, MAXL2>(a, s);
+    case 3: return pick_cf<T, LPR, 3, MAXL2>(a, s);
+    case 4: return pick_cf<T, LPR, 4, MAXL2>(a, s);
     default: return -1;
   }
 }

@@ -1,23 +1,25 @@
-// Instantiations of the row-batch join stage for 8 and 16 lanes per fact row (hidden widths 32 and 64)
-// and the dispatcher of the whole family.
+// Instantiations of the row-batch join stage for fp32 with 8 and 16 lanes per fact row (hidden widths
+// 32 and 64) and the dispatcher of the whole family.
 #include "fused_rowbatch_wide.h"
 
 namespace lq {
 
-int try_rowbatch_wide_32_64_lanes(const PredictArgs& a, hipStream_t s);   // fused_rowbatch_wide_b.hip
+int try_rowbatch_wide_f32_32_64_lanes(const PredictArgs& a, hipStream_t s);   // fused_rowbatch_wide_b.hip
+int try_rowbatch_wide_bf16(const PredictArgs& a, hipStream_t s);              // fused_rowbatch_wide_c.hip
 
 // Returns -1 when the shape is not one this kernel family covers.
 int try_rowbatch_wide(const PredictArgs& a, hipStream_t s) {
-  if (a.x_dtype != LQ_F32 || a.p_dtype != LQ_F32 || a.y_dtype != LQ_F32) return -1;
   if (a.n_layers > 2 || a.n < 256) return -1;
+  if (a.x_dtype == LQ_BF16 && a.p_dtype == LQ_BF16 && a.y_dtype == LQ_BF16) return try_rowbatch_wide_bf16(a, s);
+  if (a.x_dtype != LQ_F32 || a.p_dtype != LQ_F32 || a.y_dtype != LQ_F32) return -1;
   for (int k = 0; k < a.K; ++k)
     if (!aligned(a.P[k], 16) || a.ldp[k] % 4) return -1;
   if (a.n_layers == 1 && (!aligned(a.Y, 16) || a.ldy % 4)) return -1;
   switch (a.wout[0]) {
-    case 32: return pick_k<8, true>(a, s);
-    case 64: return pick_k<16, true>(a, s);      // (0 / 4 / 8 aligned fact columns and 1 / 2 / 4 outputs: the unrolled width-64 kernel, tried first)
+    case 32: return pick_k<float, 8, 16>(a, s);
+    case 64: return pick_k<float, 16, 16>(a, s);   // (0 / 4 / 8 aligned fact columns and 1 / 2 / 4 outputs: the unrolled width-64 kernel, tried first)
     case 128:
-    case 256: return try_rowbatch_wide_32_64_lanes(a, s);
+    case 256: return try_rowbatch_wide_f32_32_64_lanes(a, s);
     default: return -1;
   }
 }

@@ -1,0 +1,23 @@
+// Instantiations of the row-batch join stage for bf16 models, tables and outputs (hidden widths 64 to
+// 512, eight columns per lane, fp32 arithmetic), as a linear operator or with a second layer of up to
+// four outputs; wider second layers go to the matrix-core kernel.
+#include "fused_rowbatch_wide.h"
+
+namespace lq {
+
+// n and the layer count are checked by the caller (try_rowbatch_wide).
+int try_rowbatch_wide_bf16(const PredictArgs& a, hipStream_t s) {
+  if (a.K == 4 && a.c_f > 4) return -1;      // (would not fit the register file without spilling)
+  for (int k = 0; k < a.K; ++k)
+    if (!aligned(a.P[k], 16) || a.ldp[k] % 8) return -1;
+  if (a.n_layers == 1 && (!aligned(a.Y, 16) || a.ldy % 8)) return -1;
+  switch (a.wout[0]) {
+    case 64: return pick_k<bf16_t, 8, 4>(a, s);
+    case 128: return pick_k<bf16_t, 16, 4>(a, s);
+    case 256: return pick_k<bf16_t, 32, 4>(a, s);
+    case 512: return pick_k<bf16_t, 64, 4>(a, s);
+    default: return -1;
+  }
+}
+
+}  // namespace lq

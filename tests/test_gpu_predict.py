@@ -199,6 +199,13 @@ BF16_MFMA_SHAPES = [
     ("bf16_256_16_cf3", 2_111, (300, 200), (32, 32), (256, 16), False, 3),
     ("bf16_linear_128_cf16", 1_777, (64, 80), (24, 24), (128,), True, 16),
     ("bf16_32_8_cf1", 3_001, (70,), (9,), (32, 8), True, 1),
+    # one to four outputs or a linear operator: the lane-group form with eight columns per lane
+    ("bf16_64_1_k3", 20_037, (1000, 5000, 200), (32, 32, 32), (64, 1), True),
+    ("bf16_128_2_cf5", 2_311, (50, 60), (6, 6), (128, 2), True, 5),
+    ("bf16_256_4_k4", 3_001, (50, 60, 70, 80), (6, 6, 6, 6), (256, 4), False, 4),
+    ("bf16_512_3_k1", 1_025, (90,), (12,), (512, 3), True),
+    ("bf16_linear_512_cf8", 777, (64, 80), (24, 24), (512,), True, 8),
+    ("bf16_linear_128_k4_cf8", 1_301, (50, 60, 70, 80), (6, 6, 6, 6), (128,), False, 8),
 ]
 
 
