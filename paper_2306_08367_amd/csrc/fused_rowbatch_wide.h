@@ -113,15 +113,17 @@ __device__ __forceinline__ void load_rows(const PredictArgs& a, int64_t rr, bool
 
 // Gathers of passes PG grp .. PG grp + PG - 1.
 template <typename T, int LPR, int K, int CFC, int PG>
-__device__ __forceinline__ void issue_group(const PredictArgs& a, int c, int group_base, int grp,
+__device__ __forceinline__ void issue_group(const PredictArgs& a, int c, bool active, int group_base, int grp,
                                             const WRow<K, CFC>& r, WGather<K, PG>& g) {
 #pragma unroll
   for (int u = 0; u < PG; ++u)
 #pragma unroll
     for (int k = 0; k < K; ++k) {
       const int j = from_lane<LPR>(r.fk[k], PG * grp + u, group_base);
-      g.p[u][k] = *reinterpret_cast<const v4u*>(static_cast<const T*>(a.P[k]) + static_cast<int64_t>(j) * a.ldp[k] +
-                                                Piece<T>::COLS * c);
+      g.p[u][k] = v4u{0u, 0u, 0u, 0u};
+      if (active)
+        g.p[u][k] = *reinterpret_cast<const v4u*>(static_cast<const T*>(a.P[k]) + static_cast<int64_t>(j) * a.ldp[k] +
+                                                  Piece<T>::COLS * c);
     }
 }
 
@@ -134,7 +136,7 @@ template <int COLS, int CFC, int L2P> struct WConsts {
 };
 
 template <typename T, int LPR, int K, int CFC, int NL, int L2P, int PG>
-__device__ __forceinline__ void compute_group(const PredictArgs& a, int c, int group_base, int grp, int64_t row0,
+__device__ __forceinline__ void compute_group(const PredictArgs& a, int c, bool active, int group_base, int grp, int64_t row0,
                                               const WRow<K, CFC>& r, const WGather<K, PG>& g,
                                               const WConsts<Piece<T>::COLS, CFC, L2P>& w, float (&ykeep)[L2P]) {
   constexpr int COLS = Piece<T>::COLS;
@@ -156,7 +158,7 @@ __device__ __forceinline__ void compute_group(const PredictArgs& a, int c, int g
     for (int k = 0; k < K; ++k) Piece<T>::add(g.p[u][k], z);
     if constexpr (NL == 1) {
       const int64_t row = row0 + group_base + t;
-      if (row < a.n)
+      if (row < a.n && active)
         __builtin_nontemporal_store(Piece<T>::pack(z), reinterpret_cast<v4u*>(static_cast<T*>(a.Y) + row * a.ldy + COLS * c));
     } else {
       float y[L2P];
@@ -199,6 +201,7 @@ void fused_rowbatch_wide_kernel(PredictArgs a) {
   const int64_t nb = (a.n + 63) / 64;
   if (wave >= nb) return;
   const int l2 = NL == 2 ? a.wout[1] : 0;
+  const bool active = COLS * c < a.wout[0];   // lanes beyond the hidden width idle (widths that are not COLS x a power of two)
   const bool x_vec = a.c_f == 4 * CFC && a.ldx % 4 == 0 && (reinterpret_cast<uintptr_t>(a.X) & (4 * sizeof(T) - 1)) == 0;
   const bool y_vec = l2 % 4 == 0 && a.ldy % 4 == 0 && (reinterpret_cast<uintptr_t>(a.Y) & 15) == 0;
 
@@ -209,16 +212,17 @@ void fused_rowbatch_wide_kernel(PredictArgs a) {
     for (int q = 0; q < CFC * 4; ++q)
 #pragma unroll
       for (int v = 0; v < COLS; ++v)
-        w.wf[q][v] = q < a.c_f ? Elem<T>::load(W0 + static_cast<int64_t>(q) * a.ldw[0] + COLS * c + v) : 0.f;
+        w.wf[q][v] = (q < a.c_f && active) ? Elem<T>::load(W0 + static_cast<int64_t>(q) * a.ldw[0] + COLS * c + v) : 0.f;
 #pragma unroll
-    for (int v = 0; v < COLS; ++v) w.b1[v] = a.bias[0] ? Elem<T>::load(static_cast<const T*>(a.bias[0]) + COLS * c + v) : 0.f;
+    for (int v = 0; v < COLS; ++v)
+      w.b1[v] = (a.bias[0] && active) ? Elem<T>::load(static_cast<const T*>(a.bias[0]) + COLS * c + v) : 0.f;
 #pragma unroll
     for (int o = 0; o < L2P; ++o) {
-      const bool real = NL == 2 && o < l2;
+      const bool real = NL == 2 && o < l2 && active;
 #pragma unroll
       for (int v = 0; v < COLS; ++v)
         w.w2[v][o] = real ? Elem<T>::load(static_cast<const T*>(a.W[1]) + static_cast<int64_t>(COLS * c + v) * a.ldw[1] + o) : 0.f;
-      w.b2[o] = (real && a.bias[1]) ? Elem<T>::load(static_cast<const T*>(a.bias[1]) + o) : 0.f;
+      w.b2[o] = (NL == 2 && o < l2 && a.bias[1]) ? Elem<T>::load(static_cast<const T*>(a.bias[1]) + o) : 0.f;
     }
   }
 
@@ -227,7 +231,7 @@ void fused_rowbatch_wide_kernel(PredictArgs a) {
   WRow<K, CFC> cur, nxt;
   load_rows<T, K, CFC>(a, row < a.n ? row : a.n - 1, x_vec, cur);
   WGather<K, PG> ga, gb;
-  issue_group<T, LPR, K, CFC, PG>(a, c, group_base, 0, cur, ga);
+  issue_group<T, LPR, K, CFC, PG>(a, c, active, group_base, 0, cur, ga);
   for (;;) {
     const int64_t bn = b + nwaves;
     const bool more = bn < nb;
@@ -239,11 +243,11 @@ void fused_rowbatch_wide_kernel(PredictArgs a) {
     const int64_t row0 = b * 64;
 #pragma unroll 1
     for (int grp = 0; grp < NG; grp += 2) {
-      issue_group<T, LPR, K, CFC, PG>(a, c, group_base, grp + 1, cur, gb);
-      compute_group<T, LPR, K, CFC, NL, L2P, PG>(a, c, group_base, grp, row0, cur, ga, w, yk);
-      if (grp + 2 < NG) issue_group<T, LPR, K, CFC, PG>(a, c, group_base, grp + 2, cur, ga);
-      else issue_group<T, LPR, K, CFC, PG>(a, c, group_base, 0, nxt, ga);   // first group of the next batch (valid rows repeated at the end)
-      compute_group<T, LPR, K, CFC, NL, L2P, PG>(a, c, group_base, grp + 1, row0, cur, gb, w, yk);
+      issue_group<T, LPR, K, CFC, PG>(a, c, active, group_base, grp + 1, cur, gb);
+      compute_group<T, LPR, K, CFC, NL, L2P, PG>(a, c, active, group_base, grp, row0, cur, ga, w, yk);
+      if (grp + 2 < NG) issue_group<T, LPR, K, CFC, PG>(a, c, active, group_base, grp + 2, cur, ga);
+      else issue_group<T, LPR, K, CFC, PG>(a, c, active, group_base, 0, nxt, ga);   // first group of the next batch (valid rows repeated at the end)
+      compute_group<T, LPR, K, CFC, NL, L2P, PG>(a, c, active, group_base, grp + 1, row0, cur, gb, w, yk);
     }
     if constexpr (NL == 2) {
       if (row < a.n) {
@@ -305,6 +309,9 @@ int pick_cf(const PredictArgs& a, hipStream_t s) {
   if (a.c_f == 0) return pick_layers<T, LPR, K, 0, MAXL2>(a, s);
   if (a.c_f <= 4) return pick_layers<T, LPR, K, 1, MAXL2>(a, s);
   if (a.c_f <= 8) return pick_layers<T, LPR, K, 2, MAXL2>(a, s);
+  if constexpr (sizeof(T) == 4) {            // (bf16 lanes hold twice the columns: no room for more weights)
+    if (a.c_f <= 16 && K <= 3) return pick_layers<T, LPR, K, 4, MAXL2 < 8 ? MAXL2 : 8>(a, s);
+  }
   return -1;
 }
 

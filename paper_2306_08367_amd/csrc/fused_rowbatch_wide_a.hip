@@ -1,5 +1,5 @@
 // Instantiations of the row-batch join stage for fp32 with 8 and 16 lanes per fact row (hidden widths
-// 32 and 64) and the dispatcher of the whole family.
+// up to 64) and the dispatcher of the whole family.
 #include "fused_rowbatch_wide.h"
 
 namespace lq {
@@ -15,13 +15,11 @@ int try_rowbatch_wide(const PredictArgs& a, hipStream_t s) {
   for (int k = 0; k < a.K; ++k)
     if (!aligned(a.P[k], 16) || a.ldp[k] % 4) return -1;
   if (a.n_layers == 1 && (!aligned(a.Y, 16) || a.ldy % 4)) return -1;
-  switch (a.wout[0]) {
-    case 32: return pick_k<float, 8, 16>(a, s);
-    case 64: return pick_k<float, 16, 16>(a, s);   // (0 / 4 / 8 aligned fact columns and 1 / 2 / 4 outputs: the unrolled width-64 kernel, tried first)
-    case 128:
-    case 256: return try_rowbatch_wide_f32_32_64_lanes(a, s);
-    default: return -1;
-  }
+  const int l1 = a.wout[0];
+  if (l1 % 4 || l1 > 256 || l1 <= 16) return -1;        // (up to 16: one row per 1..4 lanes, the lane-group kernel)
+  if (l1 <= 32) return pick_k<float, 8, 16>(a, s);      // lanes beyond l_1 / 4 idle
+  if (l1 <= 64) return pick_k<float, 16, 16>(a, s);     // (64 with 0 / 4 / 8 aligned fact columns and 1 / 2 / 4 outputs: the unrolled kernel, tried first)
+  return try_rowbatch_wide_f32_32_64_lanes(a, s);
 }
 
 }  // namespace lq

@@ -11,13 +11,12 @@ int try_rowbatch_wide_bf16(const PredictArgs& a, hipStream_t s) {
   for (int k = 0; k < a.K; ++k)
     if (!aligned(a.P[k], 16) || a.ldp[k] % 8) return -1;
   if (a.n_layers == 1 && (!aligned(a.Y, 16) || a.ldy % 8)) return -1;
-  switch (a.wout[0]) {
-    case 64: return pick_k<bf16_t, 8, 4>(a, s);
-    case 128: return pick_k<bf16_t, 16, 4>(a, s);
-    case 256: return pick_k<bf16_t, 32, 4>(a, s);
-    case 512: return pick_k<bf16_t, 64, 4>(a, s);
-    default: return -1;
-  }
+  const int l1 = a.wout[0];
+  if (l1 % 8 || l1 > 512 || l1 <= 32) return -1;
+  if (l1 <= 64) return pick_k<bf16_t, 8, 4>(a, s);      // lanes beyond l_1 / 8 idle
+  if (l1 <= 128) return pick_k<bf16_t, 16, 4>(a, s);
+  if (l1 <= 256) return pick_k<bf16_t, 32, 4>(a, s);
+  return pick_k<bf16_t, 64, 4>(a, s);
 }
 
 }  // namespace lq

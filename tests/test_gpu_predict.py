@@ -81,6 +81,11 @@ SHAPES = [
     ("linear_l32_cf7", 1_900, 7, (100, 200), (16, 16), (32,), True),
     ("mlp_256_16_cf1", 1_300, 1, (100, 200, 50), (16, 16, 8), (256, 16), True),
     ("mlp_64_8_cf6_k4", 2_222, 6, (50, 60, 70, 80), (6, 6, 6, 6), (64, 8), True),
+    # hidden widths that are not 4 x a power of two (idle lanes) and 9..16 fact columns
+    ("mlp_48_1_k3", 5_003, 4, (1000, 5000, 200), (32, 32, 32), (48, 1), True),
+    ("mlp_200_6_k2_cf12", 2_111, 12, (100, 200), (16, 16), (200, 6), True),
+    ("linear_l72_cf16_k3", 1_501, 16, (70, 80, 90), (6, 6, 6), (72,), False),
+    ("mlp_20_3_cf9", 3_333, 9, (33, 44), (7, 7), (20, 3), True),
     # shapes only the tiled matrix-core MLP kernel covers: wide second layers, three layers
     ("mlp_64_10", 5_555, 4, (100, 2_000, 50), (16, 16, 16), (64, 10), True),
     ("mlp_128_16", 3_001, 4, (100, 200), (16, 16), (128, 16), False),
@@ -206,6 +211,8 @@ BF16_MFMA_SHAPES = [
     ("bf16_512_3_k1", 1_025, (90,), (12,), (512, 3), True),
     ("bf16_linear_512_cf8", 777, (64, 80), (24, 24), (512,), True, 8),
     ("bf16_linear_128_k4_cf8", 1_301, (50, 60, 70, 80), (6, 6, 6, 6), (128,), False, 8),
+    ("bf16_96_1_k2", 2_049, (100, 200), (16, 16), (96, 1), True, 4),
+    ("bf16_linear_40", 1_111, (100, 200), (16, 16), (40,), False),
 ]
 
 
