@@ -13,7 +13,7 @@
 // columns of its 16-byte piece, so that a projected row (128 to 1024 bytes) is fetched by one group
 // as one contiguous run.  The row's key and fact values reach the group through the cross-lane
 // network (a lane read for 64 lanes per row, a permute otherwise).  Gathers are software-pipelined
-// in groups of four (two, with many outputs) passes, across batches too.  A second layer is
+// in groups of four (two, with many outputs or more than four dimensions) passes, across batches too.  A second layer is
 // COLS x l_2 multiply-adds per lane and a sum over the lanes of the row per output (DPP adds); the
 // results of pass t are parked in lane t of the group, so a batch ends with one store per row.
 #ifndef LQ_FUSED_ROWBATCH_WIDE_H_
@@ -183,7 +183,7 @@ __device__ __forceinline__ void compute_group(const PredictArgs& a, int c, bool 
 // dimensions plus many fact columns, or the weights of a wide second layer, need more, and two per
 // SIMD is faster than spilling.
 constexpr int waves_per_simd(int COLS, int K, int CFC, int L2P) {
-  return (L2P > 4 || 32 * K + (24 * CFC + 6 * L2P) * (COLS / 4) > 106) ? 2 : 3;
+  return (L2P > 4 || (K > 4 ? 16 : 32) * K + (24 * CFC + 6 * L2P) * (COLS / 4) > 106) ? 2 : 3;
 }
 
 // T: element type of the model, the tables and the output.  LPR lanes per row (l_1 = COLS x LPR),
@@ -193,7 +193,7 @@ __global__ __launch_bounds__(RBW_THREADS)
 __attribute__((amdgpu_waves_per_eu(waves_per_simd(Piece<T>::COLS, K, CFC, L2P), waves_per_simd(Piece<T>::COLS, K, CFC, L2P))))
 void fused_rowbatch_wide_kernel(PredictArgs a) {
   constexpr int COLS = Piece<T>::COLS;
-  constexpr int PG = L2P > 4 ? 2 : 4;    // passes whose gathers travel together
+  constexpr int PG = (L2P > 4 || K > 4) ? 2 : 4;    // passes whose gathers travel together
   constexpr int NG = LPR / PG;           // such groups per batch (even)
   const int lane = threadIdx.x & 63, c = lane & (LPR - 1), group_base = lane & ~(LPR - 1);
   const int64_t wave = static_cast<int64_t>(blockIdx.x) * (RBW_THREADS / 64) + (threadIdx.x >> 6);
@@ -313,6 +313,24 @@ int pick_cf(const PredictArgs& a, hipStream_t s) {
     if (a.c_f <= 16 && K <= 3) return pick_layers<T, LPR, K, 4, MAXL2 < 8 ? MAXL2 : 8>(a, s);
   }
   return -1;
+}
+
+// 5 to 8 dimensions: fp32, at most 4 fact columns, linear or one more layer of one output.
+template <int LPR, int K>
+int pick_many_dims(const PredictArgs& a, hipStream_t s) {
+  if (a.c_f > 4 || (a.n_layers == 2 && a.wout[1] != 1)) return -1;
+  if (a.c_f == 0) return a.n_layers == 1 ? launch_inst<float, LPR, K, 0, 1, 1>(a, s) : launch_inst<float, LPR, K, 0, 2, 1>(a, s);
+  return a.n_layers == 1 ? launch_inst<float, LPR, K, 1, 1, 1>(a, s) : launch_inst<float, LPR, K, 1, 2, 1>(a, s);
+}
+template <int LPR>
+int pick_k_many(const PredictArgs& a, hipStream_t s) {
+  switch (a.K) {
+    case 5: return pick_many_dims<LPR, 5>(a, s);
+    case 6: return pick_many_dims<LPR, 6>(a, s);
+    case 7: return pick_many_dims<LPR, 7>(a, s);
+    case 8: return pick_many_dims<LPR, 8>(a, s);
+    default: return -1;
+  }
 }
 
 template <typename T, int LPR, int MAXL2>

@@ -6,6 +6,7 @@ namespace lq {
 
 int try_rowbatch_wide_f32_32_64_lanes(const PredictArgs& a, hipStream_t s);   // fused_rowbatch_wide_b.hip
 int try_rowbatch_wide_bf16(const PredictArgs& a, hipStream_t s);              // fused_rowbatch_wide_c.hip
+int try_rowbatch_wide_f32_many_dims(const PredictArgs& a, hipStream_t s);     // fused_rowbatch_wide_d.hip
 
 // Returns -1 when the shape is not one this kernel family covers.
 int try_rowbatch_wide(const PredictArgs& a, hipStream_t s) {
@@ -17,6 +18,7 @@ int try_rowbatch_wide(const PredictArgs& a, hipStream_t s) {
   if (a.n_layers == 1 && (!aligned(a.Y, 16) || a.ldy % 4)) return -1;
   const int l1 = a.wout[0];
   if (l1 % 4 || l1 > 256 || l1 <= 16) return -1;        // (up to 16: one row per 1..4 lanes, the lane-group kernel)
+  if (a.K > 4) return try_rowbatch_wide_f32_many_dims(a, s);
   if (l1 <= 32) return pick_k<float, 8, 16>(a, s);      // lanes beyond l_1 / 4 idle
   if (l1 <= 64) return pick_k<float, 16, 16>(a, s);     // (64 with 0 / 4 / 8 aligned fact columns and 1 / 2 / 4 outputs: the unrolled kernel, tried first)
   return try_rowbatch_wide_f32_32_64_lanes(a, s);

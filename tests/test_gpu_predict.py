@@ -86,6 +86,11 @@ SHAPES = [
     ("mlp_200_6_k2_cf12", 2_111, 12, (100, 200), (16, 16), (200, 6), True),
     ("linear_l72_cf16_k3", 1_501, 16, (70, 80, 90), (6, 6, 6), (72,), False),
     ("mlp_20_3_cf9", 3_333, 9, (33, 44), (7, 7), (20, 3), True),
+    # five to eight dimension tables
+    ("mlp_64_1_k8_cf4", 6_007, 4, (10, 20, 30, 40, 50, 60, 70, 80), (4,) * 8, (64, 1), True),
+    ("linear_l128_k5", 2_001, 0, (100, 200, 300, 400, 500), (8,) * 5, (128,), False),
+    ("mlp_24_1_k6_cf3", 3_003, 3, (9, 19, 29, 39, 49, 59), (5,) * 6, (24, 1), True),
+    ("mlp_256_1_k7", 1_111, 0, (9, 19, 29, 39, 49, 59, 69), (5,) * 7, (256, 1), False),
     # shapes only the tiled matrix-core MLP kernel covers: wide second layers, three layers
     ("mlp_64_10", 5_555, 4, (100, 2_000, 50), (16, 16, 16), (64, 10), True),
     ("mlp_128_16", 3_001, 4, (100, 200), (16, 16), (128, 16), False),
