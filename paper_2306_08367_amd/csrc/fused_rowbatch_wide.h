@@ -1,6 +1,6 @@
 // (Internal header: the kernel template, instantiated in fused_rowbatch_wide_a.hip for fp32 with 8 / 16
-// lanes per row, in fused_rowbatch_wide_b.hip for fp32 with 32 / 64 and in fused_rowbatch_wide_c.hip for
-// bf16, so that the parts compile in parallel.)
+// lanes per row, in fused_rowbatch_wide_b.hip for fp32 with 32 / 64, in fused_rowbatch_wide_c.hip for
+// bf16 and in fused_rowbatch_wide_d.hip for 5 to 8 dimension tables, so that the parts compile in parallel.)
 //
 // Join-computation stage (last line of Eq. 1) as a linear operator or followed by a second layer of
 // up to 16 outputs: the organisation of the width-64 kernel with a run-time pass loop, so that it
