@@ -342,6 +342,19 @@ int lq_keymap_lookup(const void* table, size_t table_bytes, const int32_t* fact_
                      int32_t* fk, void* hip_stream);
 
 /*
+ * The same map for 64-bit key values (device arrays of int64); row numbers stay int32.  The smallest
+ * int64 marks an empty slot and is not a legal key (LQ_CHECK_KEYS reports LQ_ERR_UNSUPPORTED for it;
+ * a lookup of it gives -1).  Sizes, forms, flags and errors as for the 32-bit entry points.
+ */
+size_t lq_keymap64_bytes(int64_t max_keys);
+int lq_keymap64_build(void* table, size_t table_bytes, const int64_t* keys, int64_t n_keys,
+                      uint32_t flags, void* hip_stream);
+int lq_keymap64_insert(void* table, size_t table_bytes, const int64_t* keys, int64_t n_keys,
+                       int64_t first_row, uint32_t flags, void* hip_stream);
+int lq_keymap64_lookup(const void* table, size_t table_bytes, const int64_t* fact_keys, int64_t n,
+                       int32_t* fk, void* hip_stream);
+
+/*
  * The row-mapping matrices I_R and I_S of Section 2.3.3 as COO index vectors aligned with
  * m = <0 .. nnz-1>: rows[m] is the fact row and cols[m] the dimension row of materialised row m,
  * in ascending fact-row order.  rows / cols need room for n entries; *nnz (device) receives the

@@ -12,5 +12,6 @@ from .binding import (  # noqa: F401
     lq_workspace_bytes, lq_tree_table_ld, lq_tree_project_dims, lq_fused_join_tree,
     lq_materialized_join_tree, LQ_CHECK_KEYS, lq_keymap_bytes, lq_keymap_build, lq_keymap_insert,
     lq_keymap_lookup, lq_compact_matches, lq_project_dim_rows, lq_fusion_advice, lq_groupby_agg,
+    lq_keymap64_bytes, lq_keymap64_build, lq_keymap64_insert, lq_keymap64_lookup,
     lq_group_domain, lq_group_domain_workspace_bytes, lq_order_groups, LQ_KEY_GROUP_COLUMN, LQ_KEY_SUM, LQ_KEY_COUNT,
 )

@@ -112,6 +112,13 @@ def _load():
     lib.lq_keymap_build.argtypes = [vp, sz, vp, i64, u32, vp]
     lib.lq_keymap_insert.argtypes = [vp, sz, vp, i64, i64, u32, vp]
     lib.lq_keymap_lookup.argtypes = [vp, sz, vp, i64, vp, vp]
+    lib.lq_keymap64_bytes.argtypes = [i64]
+    lib.lq_keymap64_bytes.restype = sz
+    lib.lq_keymap64_build.argtypes = [vp, sz, vp, i64, u32, vp]
+    lib.lq_keymap64_insert.argtypes = [vp, sz, vp, i64, i64, u32, vp]
+    lib.lq_keymap64_lookup.argtypes = [vp, sz, vp, i64, vp, vp]
+    for f in ("lq_keymap64_build", "lq_keymap64_insert", "lq_keymap64_lookup"):
+        getattr(lib, f).restype = ctypes.c_int
     lib.lq_compact_matches.argtypes = [vp, i64, vp, vp, vp, vp, sz, vp]
     lib.lq_compact_workspace_bytes.argtypes = [i64]
     lib.lq_compact_workspace_bytes.restype = sz
@@ -471,6 +478,36 @@ def lq_keymap_lookup(table: torch.Tensor, fact_keys: torch.Tensor, fk: Optional[
         fk = torch.empty_like(fact_keys)
     _check(_lib.lq_keymap_lookup(table.data_ptr(), table.numel(), fact_keys.data_ptr(),
                                  int(fact_keys.shape[0]), fk.data_ptr(), _stream(stream)))
+    return fk
+
+
+def lq_keymap64_bytes(max_keys: int) -> int:
+    return int(_lib.lq_keymap64_bytes(int(max_keys)))
+
+
+def lq_keymap64_build(keys: torch.Tensor, max_keys: Optional[int] = None, flags: int = 0, stream=None) -> torch.Tensor:
+    """Map from the int64 key values of a dimension to its row numbers; returns the map buffer."""
+    _expect(keys, torch.int64, "dimension key column")
+    nbytes = lq_keymap64_bytes(max(int(keys.shape[0]), max_keys or 0))
+    table = torch.empty(nbytes, dtype=torch.uint8, device=keys.device)
+    _check(_lib.lq_keymap64_build(table.data_ptr(), nbytes, keys.data_ptr(), int(keys.shape[0]), flags, _stream(stream)))
+    return table
+
+
+def lq_keymap64_insert(table: torch.Tensor, keys: torch.Tensor, first_row: int, flags: int = 0, stream=None) -> None:
+    _expect(keys, torch.int64, "dimension key column")
+    _check(_lib.lq_keymap64_insert(table.data_ptr(), table.numel(), keys.data_ptr(), int(keys.shape[0]),
+                                   int(first_row), flags, _stream(stream)))
+
+
+def lq_keymap64_lookup(table: torch.Tensor, fact_keys: torch.Tensor, fk: Optional[torch.Tensor] = None,
+                       stream=None) -> torch.Tensor:
+    """fk[i] = dimension row whose key equals fact_keys[i] (int64), -1 where there is none."""
+    _expect(fact_keys, torch.int64, "fact key column")
+    if fk is None:
+        fk = torch.empty(fact_keys.shape, dtype=torch.int32, device=fact_keys.device)
+    _check(_lib.lq_keymap64_lookup(table.data_ptr(), table.numel(), fact_keys.data_ptr(),
+                                   int(fact_keys.shape[0]), fk.data_ptr(), _stream(stream)))
     return fk
 
 

@@ -160,3 +160,67 @@ def test_direct_form_duplicates_and_inserts(lq):
                             flags=lq.LQ_CHECK_KEYS)
     assert e.value.status == "LQ_ERR_WORKSPACE"
     np.testing.assert_array_equal(lq.lq_keymap_lookup(part, torch.from_numpy(key_R).cuda()).cpu().numpy(), fk_w)
+
+
+# ---------------------------------------------------------------- 64-bit keys
+
+def _keys64(seed, r, n, dense, miss=0.1):
+    g = np.random.default_rng(seed)
+    if dense:
+        base = int(g.choice([-2**62, -7, 0, 10**15, 2**63 - 1 - 3 * r]))
+        pool = base + g.permutation(int(r * 1.4) + 1).astype(np.int64)
+    else:
+        pool = np.unique(g.integers(-2**63 + 1, 2**63 - 1, size=int(r * 1.4) + 8, dtype=np.int64))
+        g.shuffle(pool)
+    key_S = pool[:r].copy()
+    extra = pool[r:]
+    key_R = g.choice(key_S, size=n)
+    if len(extra) and n:
+        m = g.random(n) < miss
+        key_R[m] = g.choice(extra, size=int(m.sum()))
+    return key_S, key_R
+
+
+@pytest.mark.parametrize("dense", [True, False])
+@pytest.mark.parametrize("r,n", [(1, 3), (9, 1_001), (2_556, 100_003), (30_000, 400_000), (200_000, 1_000_001)])
+def test_int64_keys_match_algorithm_1(lq, r, n, dense):
+    key_S, key_R = _keys64(r + n + dense, r, n, dense)
+    fk_w, rows_w, cols_w = MJ.key_to_row(key_R, key_S)
+    table = lq.lq_keymap64_build(torch.from_numpy(key_S).cuda(), flags=lq.LQ_CHECK_KEYS)
+    assert _is_direct(table) == (dense and r > 1 or (r == 1))
+    fk = lq.lq_keymap64_lookup(table, torch.from_numpy(key_R).cuda())
+    rows, cols, nnz = lq.lq_compact_matches(fk)
+    torch.cuda.synchronize()
+    np.testing.assert_array_equal(fk.cpu().numpy(), fk_w)
+    m = int(nnz.item())
+    assert m == len(rows_w)
+    np.testing.assert_array_equal(rows[:m].cpu().numpy(), rows_w)
+    np.testing.assert_array_equal(cols[:m].cpu().numpy(), cols_w)
+    # unaligned key column: one key per thread
+    kr = torch.empty(n + 1, dtype=torch.int64, device="cuda")
+    kr[1:] = torch.from_numpy(key_R)
+    np.testing.assert_array_equal(lq.lq_keymap64_lookup(table, kr[1:]).cpu().numpy(), fk_w)
+
+
+def test_int64_extremes_duplicates_inserts_and_the_reserved_key(lq):
+    key_S = np.array([2**63 - 1, -2**63 + 1, 0, -1, 1, 2**40], dtype=np.int64)
+    key_R = np.array([0, -1, 2**63 - 1, -2**63 + 1, 5, 1, 2**40, -2**63], dtype=np.int64)
+    table = lq.lq_keymap64_build(torch.from_numpy(key_S).cuda(), flags=lq.LQ_CHECK_KEYS)
+    assert lq.lq_keymap64_lookup(table, torch.from_numpy(key_R).cuda()).cpu().tolist() == [2, 3, 0, 1, -1, 4, 5, -1]
+    with pytest.raises(lq.LQError) as e:
+        lq.lq_keymap64_build(torch.tensor([5, 9, 5, 2**50], dtype=torch.int64, device="cuda"), flags=lq.LQ_CHECK_KEYS)
+    assert e.value.status == "LQ_ERR_DUPLICATE_KEY"
+    with pytest.raises(lq.LQError) as e:
+        lq.lq_keymap64_build(torch.tensor([-2**63, 2**62], dtype=torch.int64, device="cuda"), flags=lq.LQ_CHECK_KEYS)
+    assert e.value.status == "LQ_ERR_UNSUPPORTED"
+    # incremental update of a hashed and of a direct map
+    for dense in (False, True):
+        ks, kr = _keys64(77 + dense, 40_000, 300_000, dense, miss=0.2)
+        part = lq.lq_keymap64_build(torch.from_numpy(ks[:25_000]).cuda(), max_keys=40_000)
+        try:
+            lq.lq_keymap64_insert(part, torch.from_numpy(ks[25_000:]).cuda(), 25_000, flags=lq.LQ_CHECK_KEYS)
+        except lq.LQError as err:                       # a direct map may have to be rebuilt for keys outside its window
+            assert dense and err.status == "LQ_ERR_WORKSPACE"
+            part = lq.lq_keymap64_build(torch.from_numpy(ks).cuda(), flags=lq.LQ_CHECK_KEYS)
+        fk_w, _, _ = MJ.key_to_row(kr, ks)
+        np.testing.assert_array_equal(lq.lq_keymap64_lookup(part, torch.from_numpy(kr).cuda()).cpu().numpy(), fk_w)

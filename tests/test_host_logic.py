@@ -280,3 +280,18 @@ def test_group_domain_and_order_groups_reject_bad_arguments():
     bad = (b.lq_sort_key * 2)(b.lq_sort_key(b.LQ_KEY_GROUP_COLUMN, 2, 0), b.lq_sort_key(9, 0, 0))
     assert order(keys=bad) == 2
     assert order(counts=FAKE + 4) == 2
+
+
+def test_keymap64_entry_points_reject_bad_arguments():
+    b = _binding()
+    lib = b._lib
+    assert b.lq_keymap64_bytes(0) == 256 + 2 * 12 and b.lq_keymap64_bytes(1000) == 256 + 2048 * 12
+    assert b.lq_keymap64_bytes(-1) == 0
+    nbytes = b.lq_keymap64_bytes(1000)
+    assert lib.lq_keymap64_build(None, nbytes, FAKE, 10, 0, None) == 4
+    assert lib.lq_keymap64_build(FAKE, nbytes, FAKE, 2000, 0, None) == 4       # sized for 1000 keys
+    assert lib.lq_keymap64_build(FAKE, nbytes, FAKE + 4, 10, 0, None) == 1     # keys not 8-byte aligned
+    assert lib.lq_keymap64_insert(FAKE, nbytes, None, 10, 0, 0, None) == 1
+    assert lib.lq_keymap64_insert(FAKE, nbytes, FAKE, 10, 2**31, 0, None) == 2
+    assert lib.lq_keymap64_lookup(FAKE, nbytes, None, 10, FAKE, None) == 1
+    assert lib.lq_keymap64_lookup(FAKE, 8, FAKE, 10, FAKE, None) == 4
