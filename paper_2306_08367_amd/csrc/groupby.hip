@@ -468,6 +468,7 @@ int launch_fast(const FastArgs& a, const FastLaunch& L) {
 constexpr int FOLD_THREADS = 512;
 constexpr int FOLD_PARTS = 64;                       // threads sharing one accumulator
 constexpr int FOLD_ACCS = FOLD_THREADS / FOLD_PARTS; // accumulators per workgroup
+static_assert((FOLD_PARTS - 1) % 9 == 0, "fold_agg_kernel combines the partial rows nine at a time");
 
 // sums / counts [i] = sum over workgroups b of partial[b][i].  Eight consecutive accumulators per
 // workgroup, each summed by 64 threads striding over the partial rows, then combined in LDS.
@@ -556,12 +557,17 @@ __global__ __launch_bounds__(SCAN_THREADS) void agg_scan_kernel(GbArgs a, AggExt
 #pragma unroll
       for (int q = 0; q < VEC; ++q) fk[q][k] = t[q];
     }
-    for (int pq = 0; pq < x.n_preds; ++pq) {
-      int32_t t[VEC];
-      load4(x.pcol[pq], i0, cnt, t);
+    // all predicate columns are requested before the first comparison waits for one of them
+    int32_t pv[MAX_PREDS][VEC];
 #pragma unroll
-      for (int q = 0; q < VEC; ++q) pass[q] = pass[q] && t[q] >= x.lo[pq] && t[q] <= x.hi[pq];
-    }
+    for (int pq = 0; pq < MAX_PREDS; ++pq)
+      if (pq < x.n_preds) load4(x.pcol[pq], i0, cnt, pv[pq]);
+#pragma unroll
+    for (int pq = 0; pq < MAX_PREDS; ++pq)
+      if (pq < x.n_preds) {
+#pragma unroll
+        for (int q = 0; q < VEC; ++q) pass[q] = pass[q] && pv[pq][q] >= x.lo[pq] && pv[pq][q] <= x.hi[pq];
+      }
     int32_t g[VEC];
     classify<VEC, KMAX>(a, tab, fk, g);
     bool any = false;
@@ -610,17 +616,27 @@ __global__ __launch_bounds__(FOLD_THREADS) void fold_agg_kernel(GbArgs a, AggExt
   long long t = i < n_acc ? agg_init(i, a.M, a.G) : 0;
   const long long* partial = reinterpret_cast<const long long*>(a.partial);
   if (i < n_acc)
-    for (int b = p; b < rows_written; b += FOLD_PARTS) {
-      const long long v = partial[static_cast<size_t>(b) * n_acc + i];
-      t = seg == 0 ? t + v : (seg == 1 ? min(t, v) : max(t, v));
+    for (int b0 = p; b0 < rows_written; b0 += 8 * FOLD_PARTS) {   // eight loads in flight per thread
+      long long v[8];
+#pragma unroll
+      for (int u = 0; u < 8; ++u) {
+        const int b = b0 + u * FOLD_PARTS;
+        v[u] = b < rows_written ? partial[static_cast<size_t>(b) * n_acc + i] : agg_init(i, a.M, a.G);
+      }
+#pragma unroll
+      for (int u = 0; u < 8; ++u) t = seg == 0 ? t + v[u] : (seg == 1 ? min(t, v[u]) : max(t, v[u]));
     }
   part[p][il] = t;
   __syncthreads();
   if (threadIdx.x < FOLD_ACCS && i < n_acc) {
     long long tot = part[0][il];
-    for (int q = 1; q < FOLD_PARTS; ++q) {
-      const long long v = part[q][il];
-      tot = seg == 0 ? tot + v : (seg == 1 ? min(tot, v) : max(tot, v));
+#pragma unroll
+    for (int q0 = 1; q0 < FOLD_PARTS; q0 += 9) {               // 63 = 7 x 9 LDS reads, nine in flight
+      long long v[9];
+#pragma unroll
+      for (int u = 0; u < 9; ++u) v[u] = part[q0 + u][il];
+#pragma unroll
+      for (int u = 0; u < 9; ++u) tot = seg == 0 ? tot + v[u] : (seg == 1 ? min(tot, v[u]) : max(tot, v[u]));
     }
     const int MG = a.M * a.G;
     if (i < MG) { if (a.sums) a.sums[i] = static_cast<unsigned long long>(tot); }
