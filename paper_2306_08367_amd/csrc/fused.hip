@@ -343,10 +343,13 @@ int try_rowbatch64(const PredictArgs& a, hipStream_t s);
 int try_rowbatch_wide(const PredictArgs& a, hipStream_t s);
 int try_fused_bf16(const PredictArgs& a, hipStream_t s);
 int try_fused_tile(const PredictArgs& a, hipStream_t s);
+int try_fused_deep(const PredictArgs& a, hipStream_t s);
 
 int launch_fused(const PredictArgs& a, hipStream_t s) {
   if (a.n == 0) return LQ_OK;
   int rc = try_rowbatch64(a, s);
+  if (rc >= 0) return rc;
+  rc = try_fused_deep(a, s);          // three or four layers, or a second layer of 5..64 outputs
   if (rc >= 0) return rc;
   rc = try_rowbatch_wide(a, s);
   if (rc >= 0) return rc;

@@ -97,6 +97,16 @@ SHAPES = [
     ("mlp_64_32_1", 4_321, 4, (100, 200), (16, 16), (64, 32, 1), True),
     ("mlp_256_64_8_3", 1_033, 0, (100, 200), (16, 16), (256, 64, 8, 3), True),
     ("mlp_37_5_odd", 2_047, 3, (60, 70), (5, 9), (37, 5), True),
+    # deeper / wider fp32 models whose later layers all run on the matrix cores from registers
+    ("deep_64_64_1_k3", 9_001, 4, (1000, 5000, 200), (32, 32, 32), (64, 64, 1), True),
+    ("deep_32_24_1_k1_cf0", 2_049, 0, (90,), (12,), (32, 24, 1), False),
+    ("deep_128_64_5_k4_cf13", 3_001, 13, (50, 60, 70, 80), (6, 6, 6, 6), (128, 64, 5), True),
+    ("deep_64_40_k2", 4_111, 4, (100, 200), (16, 16), (64, 40), True),
+    ("deep_64_33_k2_odd", 1_237, 2, (100, 200), (16, 16), (64, 33), False),
+    ("deep_32_16_16_3", 2_050, 5, (30, 7), (6, 3), (32, 16, 16, 3), True),
+    ("deep_64_48_20_1", 5_013, 4, (100, 2_000, 50), (16, 16, 16), (64, 48, 20, 1), True),
+    ("deep_128_32_16_k3_cf16", 2_777, 16, (70, 80, 90), (6, 6, 6), (128, 32, 16), True),
+    ("deep_one_row", 1, 4, (10, 10), (8, 8), (64, 64, 1), True),
     # the limits of the interface: 8 layers, 8 dimensions
     ("eight_layers_eight_dims", 1_500, 2, (9,) * 8, (3,) * 8, (24, 20, 16, 12, 10, 8, 6, 2), True),
 ]
