@@ -1,5 +1,5 @@
 // Join-computation stage (last line of Eq. 1) followed by a deeper or wider fp32 MLP (a second
-// layer of 5..64 outputs, or three or four layers), with every layer after the gather on the matrix
+// layer of 5..128 outputs, or three or four layers with later hidden widths up to 128), with every layer after the gather on the matrix
 // cores and all activations in registers.
 //
 // A wavefront owns 16 fact rows per step.  In the matrix layers lane l works for row l % 16 and, of
@@ -289,8 +289,8 @@ int try_fused_deep(const PredictArgs& a, hipStream_t s) {
   const int l_out = a.wout[NL - 1];
   if (NL > 2 && l_out > 16) return -1;
   if (NL == 2 && l_out <= 4) return -1;               // the row-batch kernels are at least as fast there
-  if (wide > 64) return -1;
-  const int TH = wide <= 16 ? 1 : (wide <= 32 ? 2 : 4);
+  if (wide > 128) return -1;
+  const int TH = wide <= 16 ? 1 : (wide <= 32 ? 2 : (wide <= 64 ? 4 : 8));
 
   DeepLds L{};
   L.kc = (a.c_f + 3) / 4;
@@ -331,9 +331,13 @@ int try_fused_deep(const PredictArgs& a, hipStream_t s) {
   do {                                                                                                      \
     if (T1 == 2) LQ_DEEP_K(2, TH_, NL_); else if (T1 == 4) LQ_DEEP_K(4, TH_, NL_); else LQ_DEEP_K(8, TH_, NL_); \
   } while (0)
-  if (NL == 2) { if (TH == 1) LQ_DEEP_T1(1, 2); else if (TH == 2) LQ_DEEP_T1(2, 2); else LQ_DEEP_T1(4, 2); }
-  else if (NL == 3) { if (TH == 1) LQ_DEEP_T1(1, 3); else if (TH == 2) LQ_DEEP_T1(2, 3); else LQ_DEEP_T1(4, 3); }
-  else { if (TH == 1) LQ_DEEP_T1(1, 4); else if (TH == 2) LQ_DEEP_T1(2, 4); else LQ_DEEP_T1(4, 4); }
+#define LQ_DEEP_TH(NL_)                                                                                     \
+  do {                                                                                                      \
+    if (TH == 1) LQ_DEEP_T1(1, NL_); else if (TH == 2) LQ_DEEP_T1(2, NL_);                                  \
+    else if (TH == 4) LQ_DEEP_T1(4, NL_); else LQ_DEEP_T1(8, NL_);                                          \
+  } while (0)
+  if (NL == 2) LQ_DEEP_TH(2); else if (NL == 3) LQ_DEEP_TH(3); else LQ_DEEP_TH(4);
+#undef LQ_DEEP_TH
 #undef LQ_DEEP_T1
 #undef LQ_DEEP_K
 #undef LQ_DEEP

@@ -1,0 +1,284 @@
+// Join-computation stage (last line of Eq. 1) followed by a deeper or wider bf16 MLP (a second
+// layer of 17..256 outputs, or three or four layers with later hidden widths up to 256 and at most
+// 16 outputs): hidden width a multiple of 32 up to 256, up to 16 fact-owned columns, every layer
+// after the gather on the matrix cores.
+//
+// A wavefront handles 16 fact rows per pass.  Lane (g = lane / 16, j = lane % 16) works on row j
+// and, in each 32-wide block kb of hidden units, owns units 32 kb + 8 g .. + 7: the eight bf16 values
+// one lane supplies as the K-slice of the B operand of the 16x16x32 bf16 matrix instruction.  The
+// gathered rows are summed in fp32 in place, rectified and rounded to bf16 once.  Layers are taken
+// transposed, H_(j+1)^T = W_j^T H_j^T: the result of a 16-output tile (register v of lane (g, j) =
+// output 4 g + v of row j, fp32) is rectified, rounded to bf16, and two such tiles side by side are
+// again a B operand (elements 0..3 from the even tile, 4..7 from the odd one), so layers chain in
+// registers.  The weights are staged once per workgroup in LDS in that operand order, zero-padded.
+// Activations are rounded to bf16 between layers, as in any layer-by-layer bf16 pipeline;
+// accumulation is fp32.
+#include "lq_common.h"
+
+namespace lq {
+namespace {
+
+typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
+typedef float v4f __attribute__((ext_vector_type(4)));
+typedef unsigned int v4u __attribute__((ext_vector_type(4)));
+
+constexpr int DBF_THREADS = 256;
+
+// Byte offsets of the staged model inside the dynamic LDS block.
+struct DeepBfLds {
+  int w[3];       // layer j + 1: [TOUT][chunks of 32 inputs][64 lanes] x 16 bytes
+  int b[3];       // fp32 [16 TOUT]
+  int total;
+};
+
+__device__ __forceinline__ void unpack_add(const v4u& w, float (&acc)[8]) {
+#pragma unroll
+  for (int q = 0; q < 4; ++q) {
+    acc[2 * q] += __uint_as_float(w[q] << 16);
+    acc[2 * q + 1] += __uint_as_float(w[q] & 0xffff0000u);
+  }
+}
+__device__ __forceinline__ unsigned int pack2(float lo, float hi) {
+  return static_cast<unsigned int>(f32_to_bf16(lo)) | (static_cast<unsigned int>(f32_to_bf16(hi)) << 16);
+}
+__device__ __forceinline__ unsigned int pack2_relu(float lo, float hi) { return pack2(fmaxf(lo, 0.f), fmaxf(hi, 0.f)); }
+
+// out^T = W^T h^T + b: CH chunks of 32 inputs (B operands hb), TOUT tiles of 16 outputs.
+template <int CH, int TOUT>
+__device__ __forceinline__ void dense_layer(const v4u (&hb)[CH], const v4u* w, const float* bias, int lane, v4f (&out)[TOUT]) {
+  const int g = lane >> 4;
+#pragma unroll
+  for (int ot = 0; ot < TOUT; ++ot) out[ot] = *reinterpret_cast<const v4f*>(bias + 16 * ot + 4 * g);
+#pragma unroll
+  for (int c = 0; c < CH; ++c)
+#pragma unroll
+    for (int ot = 0; ot < TOUT; ++ot)
+      out[ot] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, w[(ot * CH + c) * 64 + lane]),
+                                                        __builtin_bit_cast(bf16x8, hb[c]), out[ot], 0, 0, 0);
+}
+
+// ReLU, round to bf16, and put pairs of 16-output tiles side by side as B operands of the next layer.
+template <int T>
+__device__ __forceinline__ void next_operands(const v4f (&h)[T], v4u (&hb)[(T + 1) / 2]) {
+#pragma unroll
+  for (int m = 0; m < (T + 1) / 2; ++m) {
+    hb[m][0] = pack2_relu(h[2 * m][0], h[2 * m][1]);
+    hb[m][1] = pack2_relu(h[2 * m][2], h[2 * m][3]);
+    if (2 * m + 1 < T) {
+      hb[m][2] = pack2_relu(h[2 * m + 1][0], h[2 * m + 1][1]);
+      hb[m][3] = pack2_relu(h[2 * m + 1][2], h[2 * m + 1][3]);
+    } else {
+      hb[m][2] = 0u;
+      hb[m][3] = 0u;
+    }
+  }
+}
+
+template <int T>
+__device__ __forceinline__ void store_rows(const PredictArgs& a, const v4f (&y)[T], int64_t row, bool live, int g, int l_out) {
+  if (!live) return;
+#pragma unroll
+  for (int ot = 0; ot < T; ++ot)
+#pragma unroll
+    for (int v = 0; v < 4; ++v) {
+      const int c = 16 * ot + 4 * g + v;
+      if (c < l_out) store_from_f32(a.Y, row * a.ldy + c, a.y_dtype, y[ot][v]);
+    }
+}
+
+// Stages W (layer index `layer`) as A operands.  first: inputs are the hidden units of layer 1 (lane
+// (g, i) of chunk kb holds units 32 kb + 8 g + t); otherwise they are pairs of 16-output tiles (unit
+// 32 m + 4 g + e for e < 4, 32 m + 16 + 4 g + e - 4 for e >= 4).
+__device__ __forceinline__ void stage_weights(const PredictArgs& a, int layer, bool first, int chunks, int tout, v4u* dst, float* bias_dst) {
+  const bf16_t* W = static_cast<const bf16_t*>(a.W[layer]);
+  const int64_t ldw = a.ldw[layer];
+  const int win = a.win[layer], wout = a.wout[layer];
+  for (int i = threadIdx.x; i < tout * chunks * 64; i += DBF_THREADS) {
+    const int ln = i & 63, tile = i >> 6, ot = tile / chunks, c = tile - ot * chunks;
+    const int g = ln >> 4, col = 16 * ot + (ln & 15);
+    unsigned int h[8];
+#pragma unroll
+    for (int e = 0; e < 8; ++e) {
+      const int unit = first ? 32 * c + 8 * g + e : 32 * c + (e < 4 ? 4 * g + e : 16 + 4 * g + e - 4);
+      h[e] = (unit < win && col < wout) ? W[static_cast<int64_t>(unit) * ldw + col] : 0u;
+    }
+    dst[i] = (v4u){h[0] | (h[1] << 16), h[2] | (h[3] << 16), h[4] | (h[5] << 16), h[6] | (h[7] << 16)};
+  }
+  for (int i = threadIdx.x; i < 16 * tout; i += DBF_THREADS)
+    bias_dst[i] = (i < wout && a.bias[layer]) ? bf16_to_f32(static_cast<const bf16_t*>(a.bias[layer])[i]) : 0.f;
+}
+
+// KB = l_1 / 32.  TH: later hidden layers (and, with two layers, the output) are at most 16 TH wide.
+// NL: number of layers (2..4); with three or four layers the output is at most 16 wide.
+template <int KB, int TH, int NL>
+__global__ __launch_bounds__(DBF_THREADS) void fused_deep_bf16_kernel(PredictArgs a, DeepBfLds L) {
+  constexpr int M = (TH + 1) / 2;                       // 32-input chunks of a later hidden layer
+  constexpr int TLAST = NL == 2 ? TH : 1;
+  extern __shared__ __align__(16) unsigned char smem[];
+  const int lane = threadIdx.x & 63, g = lane >> 4, j = lane & 15;
+
+  stage_weights(a, 1, true, KB, NL == 2 ? TLAST : TH, reinterpret_cast<v4u*>(smem + L.w[0]), reinterpret_cast<float*>(smem + L.b[0]));
+  if (NL >= 3) stage_weights(a, 2, false, M, NL == 3 ? TLAST : TH, reinterpret_cast<v4u*>(smem + L.w[1]), reinterpret_cast<float*>(smem + L.b[1]));
+  if (NL == 4) stage_weights(a, 3, false, M, TLAST, reinterpret_cast<v4u*>(smem + L.w[2]), reinterpret_cast<float*>(smem + L.b[2]));
+  __syncthreads();
+
+  const int64_t wave = static_cast<int64_t>(blockIdx.x) * (DBF_THREADS / 64) + (threadIdx.x >> 6);
+  const int64_t nwaves = static_cast<int64_t>(gridDim.x) * (DBF_THREADS / 64);
+  const int64_t npass = (a.n + 15) / 16;
+  const int l_out = a.wout[NL - 1];
+  const bool w0_vec = (reinterpret_cast<uintptr_t>(a.W[0]) & 15) == 0 && a.ldw[0] % 8 == 0;
+
+  for (int64_t pass = wave; pass < npass; pass += nwaves) {
+    // The staged model is read from LDS where it is used (otherwise the reads are hoisted out of
+    // the loop and the weights take every register there is).
+    asm volatile("" ::: "memory");
+    const int64_t row = pass * 16 + j;
+    const bool live = row < a.n;
+    const int64_t rr = live ? row : a.n - 1;
+
+    // ---- layer 1: z = x W_f + sum_k P_k[fk_k] + b_1 in fp32, lane (g, j) owns units 32 kb + 8 g + t
+    float acc[KB][8];
+    if (a.bias[0]) {
+      const bf16_t* b1 = static_cast<const bf16_t*>(a.bias[0]);
+#pragma unroll
+      for (int kb = 0; kb < KB; ++kb)
+#pragma unroll
+        for (int t = 0; t < 8; ++t) acc[kb][t] = bf16_to_f32(b1[32 * kb + 8 * g + t]);
+    } else {
+#pragma unroll
+      for (int kb = 0; kb < KB; ++kb)
+#pragma unroll
+        for (int t = 0; t < 8; ++t) acc[kb][t] = 0.f;
+    }
+    if (a.c_f > 0) {
+      const bf16_t* xr = static_cast<const bf16_t*>(a.X) + rr * a.ldx;
+      const bf16_t* W0 = static_cast<const bf16_t*>(a.W[0]) + 8 * g;
+      for (int q = 0; q < a.c_f; ++q) {
+        const float x = bf16_to_f32(xr[q]);
+        const bf16_t* wq = W0 + static_cast<int64_t>(q) * a.ldw[0];
+#pragma unroll
+        for (int kb = 0; kb < KB; ++kb) {
+          float wv[8];
+          if (w0_vec) {
+            const v4u t = *reinterpret_cast<const v4u*>(wq + 32 * kb);
+#pragma unroll
+            for (int e = 0; e < 4; ++e) { wv[2 * e] = __uint_as_float(t[e] << 16); wv[2 * e + 1] = __uint_as_float(t[e] & 0xffff0000u); }
+          } else {
+#pragma unroll
+            for (int e = 0; e < 8; ++e) wv[e] = bf16_to_f32(wq[32 * kb + e]);
+          }
+#pragma unroll
+          for (int e = 0; e < 8; ++e) acc[kb][e] = fmaf(x, wv[e], acc[kb][e]);
+        }
+      }
+    }
+    for (int k = 0; k < a.K; ++k) {
+      const int64_t f = a.fk[k][rr];
+      const bf16_t* p = static_cast<const bf16_t*>(a.P[k]) + f * a.ldp[k] + 8 * g;
+      v4u w[KB];
+#pragma unroll
+      for (int kb = 0; kb < KB; ++kb) w[kb] = *reinterpret_cast<const v4u*>(p + 32 * kb);
+#pragma unroll
+      for (int kb = 0; kb < KB; ++kb) unpack_add(w[kb], acc[kb]);
+    }
+    v4u hb[KB];
+#pragma unroll
+    for (int kb = 0; kb < KB; ++kb)
+      hb[kb] = (v4u){pack2_relu(acc[kb][0], acc[kb][1]), pack2_relu(acc[kb][2], acc[kb][3]),
+                     pack2_relu(acc[kb][4], acc[kb][5]), pack2_relu(acc[kb][6], acc[kb][7])};
+
+    // ---- later layers
+    const v4u* w2 = reinterpret_cast<const v4u*>(smem + L.w[0]);
+    const float* b2 = reinterpret_cast<const float*>(smem + L.b[0]);
+    if constexpr (NL == 2) {
+      v4f y[TLAST];
+      dense_layer<KB, TLAST>(hb, w2, b2, lane, y);
+      store_rows<TLAST>(a, y, row, live, g, l_out);
+    } else {
+      v4f h2[TH];
+      dense_layer<KB, TH>(hb, w2, b2, lane, h2);
+      v4u hb2[M];
+      next_operands<TH>(h2, hb2);
+      const v4u* w3 = reinterpret_cast<const v4u*>(smem + L.w[1]);
+      const float* b3 = reinterpret_cast<const float*>(smem + L.b[1]);
+      if constexpr (NL == 4) {
+        v4f h3[TH];
+        dense_layer<M, TH>(hb2, w3, b3, lane, h3);
+        next_operands<TH>(h3, hb2);
+        v4f y[1];
+        dense_layer<M, 1>(hb2, reinterpret_cast<const v4u*>(smem + L.w[2]), reinterpret_cast<const float*>(smem + L.b[2]), lane, y);
+        store_rows<1>(a, y, row, live, g, l_out);
+      } else {
+        v4f y[1];
+        dense_layer<M, 1>(hb2, w3, b3, lane, y);
+        store_rows<1>(a, y, row, live, g, l_out);
+      }
+    }
+  }
+}
+
+}  // namespace
+
+// Returns -1 when the shape is not one this kernel covers.
+int try_fused_deep_bf16(const PredictArgs& a, hipStream_t s) {
+  if (a.x_dtype != LQ_BF16 || a.p_dtype != LQ_BF16) return -1;
+  const int NL = a.n_layers;
+  if (NL < 2 || NL > 4 || a.c_f > 16 || a.K < 1) return -1;
+  const int l1 = a.wout[0];
+  if (l1 % 32 || l1 > 256) return -1;
+  const int KB = l1 / 32;
+  if (KB != 1 && KB != 2 && KB != 4 && KB != 8) return -1;
+  for (int k = 0; k < a.K; ++k)
+    if (!aligned(a.P[k], 16) || a.ldp[k] % 8) return -1;
+  const int l_out = a.wout[NL - 1];
+  if (NL == 2 && l_out <= 16) return -1;              // the one-tile bf16 kernel covers these
+  if (NL > 2 && l_out > 16) return -1;
+  int wide = 0;
+  for (int j = 1; j < NL; ++j)
+    if (j < NL - 1 || NL == 2) wide = std::max(wide, a.wout[j]);
+  if (wide > 256) return -1;
+  const int TH = wide <= 16 ? 1 : (wide <= 32 ? 2 : (wide <= 64 ? 4 : (wide <= 128 ? 8 : 16)));
+  const int M = (TH + 1) / 2;
+
+  DeepBfLds L{};
+  int off = 0;
+  for (int j = 1; j < NL; ++j) {
+    const int chunks = j == 1 ? KB : M;
+    const int tout = j == NL - 1 ? (NL == 2 ? TH : 1) : TH;
+    L.w[j - 1] = off; off += tout * chunks * 64 * 16;
+    L.b[j - 1] = off; off += 16 * tout * 4;
+  }
+  L.total = off;
+  const size_t lds = static_cast<size_t>(off);
+  if (lds > 150 * 1024) return -1;
+
+  const int64_t npass = (a.n + 15) / 16;
+  const int64_t blocks = std::min<int64_t>((npass + 3) / 4, static_cast<int64_t>(num_cus()) * 8);
+  if (blocks <= 0) return LQ_OK;
+#define LQ_DBF(KB_, TH_, NL_)                                                                           \
+  do {                                                                                                  \
+    if (lds > 64 * 1024)                                                                                \
+      LQ_HIP_TRY(hipFuncSetAttribute(reinterpret_cast<const void*>(&fused_deep_bf16_kernel<KB_, TH_, NL_>), \
+                                     hipFuncAttributeMaxDynamicSharedMemorySize, static_cast<int>(lds))); \
+    hipLaunchKernelGGL((fused_deep_bf16_kernel<KB_, TH_, NL_>), dim3(static_cast<unsigned>(blocks)),     \
+                       dim3(DBF_THREADS), lds, s, a, L);                                                \
+  } while (0)
+#define LQ_DBF_KB(TH_, NL_)                                                                             \
+  do {                                                                                                  \
+    if (KB == 1) LQ_DBF(1, TH_, NL_); else if (KB == 2) LQ_DBF(2, TH_, NL_);                            \
+    else if (KB == 4) LQ_DBF(4, TH_, NL_); else LQ_DBF(8, TH_, NL_);                                    \
+  } while (0)
+#define LQ_DBF_TH(NL_)                                                                                  \
+  do {                                                                                                  \
+    if (TH == 1) LQ_DBF_KB(1, NL_); else if (TH == 2) LQ_DBF_KB(2, NL_); else if (TH == 4) LQ_DBF_KB(4, NL_); \
+    else if (TH == 8) LQ_DBF_KB(8, NL_); else LQ_DBF_KB(16, NL_);                                       \
+  } while (0)
+  if (NL == 2) LQ_DBF_TH(2); else if (NL == 3) LQ_DBF_TH(3); else LQ_DBF_TH(4);
+#undef LQ_DBF_TH
+#undef LQ_DBF_KB
+#undef LQ_DBF
+  LQ_LAUNCH_CHECK("fused_deep_bf16_kernel");
+  return LQ_OK;
+}
+
+}  // namespace lq

@@ -107,6 +107,9 @@ SHAPES = [
     ("deep_64_48_20_1", 5_013, 4, (100, 2_000, 50), (16, 16, 16), (64, 48, 20, 1), True),
     ("deep_128_32_16_k3_cf16", 2_777, 16, (70, 80, 90), (6, 6, 6), (128, 32, 16), True),
     ("deep_one_row", 1, 4, (10, 10), (8, 8), (64, 64, 1), True),
+    ("deep_64_128_1", 3_003, 4, (100, 200), (16, 16), (64, 128, 1), True),
+    ("deep_128_100_k2", 1_501, 0, (100, 200), (16, 16), (128, 100), False),
+    ("deep_32_96_72_4", 2_222, 3, (60, 70), (5, 9), (32, 96, 72, 4), True),
     # the limits of the interface: 8 layers, 8 dimensions
     ("eight_layers_eight_dims", 1_500, 2, (9,) * 8, (3,) * 8, (24, 20, 16, 12, 10, 8, 6, 2), True),
 ]
@@ -228,6 +231,16 @@ BF16_MFMA_SHAPES = [
     ("bf16_linear_128_k4_cf8", 1_301, (50, 60, 70, 80), (6, 6, 6, 6), (128,), False, 8),
     ("bf16_96_1_k2", 2_049, (100, 200), (16, 16), (96, 1), True, 4),
     ("bf16_linear_40", 1_111, (100, 200), (16, 16), (40,), False),
+    # deeper / wider bf16 models: later layers chained on the matrix cores
+    ("bf16_deep_256_64_16", 3_001, (500, 700, 300, 900), (64, 64, 32, 48), (256, 64, 16), True),
+    ("bf16_deep_64_64_1_cf4", 4_099, (1000, 5000, 200), (32, 32, 32), (64, 64, 1), True, 4),
+    ("bf16_deep_128_40", 2_049, (100, 200), (32, 40), (128, 40), False),
+    ("bf16_deep_32_24_8_3_cf2", 1_777, (64, 80), (24, 24), (32, 24, 8, 3), True, 2),
+    ("bf16_deep_256_48_5_k1", 1_025, (90,), (12,), (256, 48, 5), False),
+    ("bf16_deep_128_16_16_2", 2_000, (100, 200), (16, 16), (128, 16, 16, 2), True),
+    ("bf16_deep_256_256_16", 2_049, (500, 700, 300, 900), (64, 64, 32, 48), (256, 256, 16), True),
+    ("bf16_deep_64_100", 1_333, (100, 200), (32, 40), (64, 100), False),
+    ("bf16_deep_96_200_130_7_cf3", 1_111, (64, 80), (24, 24), (96, 200, 130, 7), True, 3),
 ]
 
 
