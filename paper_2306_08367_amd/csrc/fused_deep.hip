@@ -90,7 +90,7 @@ __device__ __forceinline__ void store_rows(const PredictArgs& a, const v4f (&y)[
   }
 }
 
-// T1: l_1 = 16 T1.  TH: later hidden layers (and, with two layers, the output) are at most 16 TH wide.
+// T1: l_1 <= 16 T1 (a multiple of 4).  TH: later hidden layers (and, with two layers, the output) are at most 16 TH wide.
 // NL: number of layers (2..4); with three or four layers the output is at most 16 wide.
 // KMAX: number of dimension tables (their gathers are all in flight at once).
 template <int T1, int TH, int NL, int KMAX>
@@ -149,13 +149,15 @@ __global__ __launch_bounds__(DEEP_THREADS) void fused_deep_kernel(PredictArgs a,
   int key1[KMAX];          // keys of the step after this one (lane l: row l % 16)
   float xv[4], x1[4];      // fact columns of this step and of the next
   v4f g[KMAX][T1];         // gathered pieces of this step: g[k][u] = row u RPI + gsub, piece gc
+  const bool active = 4 * gc < l1;        // widths below 16 T1: the lanes past the end of a row idle
   auto gather = [&](const int (&key)[KMAX]) {
 #pragma unroll
     for (int k = 0; k < KMAX; ++k) {
 #pragma unroll
       for (int u = 0; u < T1; ++u) {
         const int kr = __shfl(key[k], u * RPI + gsub);
-        g[k][u] = *reinterpret_cast<const v4f*>(static_cast<const float*>(a.P[k]) + static_cast<int64_t>(kr) * a.ldp[k] + 4 * gc);
+        g[k][u] = active ? *reinterpret_cast<const v4f*>(static_cast<const float*>(a.P[k]) + static_cast<int64_t>(kr) * a.ldp[k] + 4 * gc)
+                         : v4f{0.f, 0.f, 0.f, 0.f};
       }
     }
   };
@@ -278,11 +280,11 @@ int try_fused_deep(const PredictArgs& a, hipStream_t s) {
   const int NL = a.n_layers;
   if (NL < 2 || NL > 4) return -1;
   const int l1 = a.wout[0];
-  if (l1 != 32 && l1 != 64 && l1 != 128) return -1;
+  if (l1 % 4 || l1 < 20 || l1 > 128) return -1;
   if (a.c_f > 16 || a.K < 1 || a.K > 4) return -1;
   for (int k = 0; k < a.K; ++k)
     if (!aligned(a.P[k], 16) || a.ldp[k] % 4) return -1;
-  const int T1 = l1 / 16;
+  const int T1 = l1 <= 32 ? 2 : (l1 <= 64 ? 4 : 8);   // 16-unit tiles of the hidden layer, padded to a power of two
   int wide = 0;                                       // widest later layer that has to fit TH tiles
   for (int j = 1; j < NL; ++j)
     if (j < NL - 1 || NL == 2) wide = std::max(wide, a.wout[j]);

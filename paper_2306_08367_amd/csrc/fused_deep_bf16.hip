@@ -1,6 +1,6 @@
 // Join-computation stage (last line of Eq. 1) followed by a deeper or wider bf16 MLP (a second
 // layer of 17..256 outputs, or three or four layers with later hidden widths up to 256 and at most
-// 16 outputs): hidden width a multiple of 32 up to 256, up to 16 fact-owned columns, every layer
+// 16 outputs): hidden width a multiple of 8 up to 256, up to 16 fact-owned columns, every layer
 // after the gather on the matrix cores.
 //
 // A wavefront handles 16 fact rows per pass.  Lane (g = lane / 16, j = lane % 16) works on row j
@@ -108,7 +108,7 @@ __device__ __forceinline__ void stage_weights(const PredictArgs& a, int layer, b
     bias_dst[i] = (i < wout && a.bias[layer]) ? bf16_to_f32(static_cast<const bf16_t*>(a.bias[layer])[i]) : 0.f;
 }
 
-// KB = l_1 / 32.  TH: later hidden layers (and, with two layers, the output) are at most 16 TH wide.
+// KB: l_1 <= 32 KB (a multiple of 8; lanes whose units lie past l_1 idle).  TH: later hidden layers (and, with two layers, the output) are at most 16 TH wide.
 // NL: number of layers (2..4); with three or four layers the output is at most 16 wide.
 template <int KB, int TH, int NL>
 __global__ __launch_bounds__(DBF_THREADS) void fused_deep_bf16_kernel(PredictArgs a, DeepBfLds L) {
@@ -125,7 +125,7 @@ __global__ __launch_bounds__(DBF_THREADS) void fused_deep_bf16_kernel(PredictArg
   const int64_t wave = static_cast<int64_t>(blockIdx.x) * (DBF_THREADS / 64) + (threadIdx.x >> 6);
   const int64_t nwaves = static_cast<int64_t>(gridDim.x) * (DBF_THREADS / 64);
   const int64_t npass = (a.n + 15) / 16;
-  const int l_out = a.wout[NL - 1];
+  const int l_out = a.wout[NL - 1], l1 = a.wout[0];
   const bool w0_vec = (reinterpret_cast<uintptr_t>(a.W[0]) & 15) == 0 && a.ldw[0] % 8 == 0;
 
   for (int64_t pass = wave; pass < npass; pass += nwaves) {
@@ -143,7 +143,7 @@ __global__ __launch_bounds__(DBF_THREADS) void fused_deep_bf16_kernel(PredictArg
 #pragma unroll
       for (int kb = 0; kb < KB; ++kb)
 #pragma unroll
-        for (int t = 0; t < 8; ++t) acc[kb][t] = bf16_to_f32(b1[32 * kb + 8 * g + t]);
+        for (int t = 0; t < 8; ++t) acc[kb][t] = 32 * kb + 8 * g < l1 ? bf16_to_f32(b1[32 * kb + 8 * g + t]) : 0.f;
     } else {
 #pragma unroll
       for (int kb = 0; kb < KB; ++kb)
@@ -159,7 +159,10 @@ __global__ __launch_bounds__(DBF_THREADS) void fused_deep_bf16_kernel(PredictArg
 #pragma unroll
         for (int kb = 0; kb < KB; ++kb) {
           float wv[8];
-          if (w0_vec) {
+          if (32 * kb + 8 * g >= l1) {
+#pragma unroll
+            for (int e = 0; e < 8; ++e) wv[e] = 0.f;
+          } else if (w0_vec) {
             const v4u t = *reinterpret_cast<const v4u*>(wq + 32 * kb);
 #pragma unroll
             for (int e = 0; e < 4; ++e) { wv[2 * e] = __uint_as_float(t[e] << 16); wv[2 * e + 1] = __uint_as_float(t[e] & 0xffff0000u); }
@@ -177,7 +180,7 @@ __global__ __launch_bounds__(DBF_THREADS) void fused_deep_bf16_kernel(PredictArg
       const bf16_t* p = static_cast<const bf16_t*>(a.P[k]) + f * a.ldp[k] + 8 * g;
       v4u w[KB];
 #pragma unroll
-      for (int kb = 0; kb < KB; ++kb) w[kb] = *reinterpret_cast<const v4u*>(p + 32 * kb);
+      for (int kb = 0; kb < KB; ++kb) w[kb] = 32 * kb + 8 * g < l1 ? *reinterpret_cast<const v4u*>(p + 32 * kb) : v4u{0u, 0u, 0u, 0u};
 #pragma unroll
       for (int kb = 0; kb < KB; ++kb) unpack_add(w[kb], acc[kb]);
     }
@@ -225,9 +228,8 @@ int try_fused_deep_bf16(const PredictArgs& a, hipStream_t s) {
   const int NL = a.n_layers;
   if (NL < 2 || NL > 4 || a.c_f > 16 || a.K < 1) return -1;
   const int l1 = a.wout[0];
-  if (l1 % 32 || l1 > 256) return -1;
-  const int KB = l1 / 32;
-  if (KB != 1 && KB != 2 && KB != 4 && KB != 8) return -1;
+  if (l1 % 8 || l1 > 256) return -1;
+  const int KB = l1 <= 32 ? 1 : (l1 <= 64 ? 2 : (l1 <= 128 ? 4 : 8));   // 32-unit blocks, padded to a power of two
   for (int k = 0; k < a.K; ++k)
     if (!aligned(a.P[k], 16) || a.ldp[k] % 8) return -1;
   const int l_out = a.wout[NL - 1];

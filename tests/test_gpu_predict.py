@@ -110,6 +110,10 @@ SHAPES = [
     ("deep_64_128_1", 3_003, 4, (100, 200), (16, 16), (64, 128, 1), True),
     ("deep_128_100_k2", 1_501, 0, (100, 200), (16, 16), (128, 100), False),
     ("deep_32_96_72_4", 2_222, 3, (60, 70), (5, 9), (32, 96, 72, 4), True),
+    # hidden widths that do not fill the padded lane group
+    ("deep_48_32_1", 2_345, 4, (100, 200, 50), (16, 16, 8), (48, 32, 1), True),
+    ("deep_100_24", 1_999, 0, (100, 200), (16, 16), (100, 24), False),
+    ("deep_20_20_20_2", 1_500, 2, (30, 7), (6, 3), (20, 20, 20, 2), True),
     # the limits of the interface: 8 layers, 8 dimensions
     ("eight_layers_eight_dims", 1_500, 2, (9,) * 8, (3,) * 8, (24, 20, 16, 12, 10, 8, 6, 2), True),
 ]
@@ -241,6 +245,9 @@ BF16_MFMA_SHAPES = [
     ("bf16_deep_256_256_16", 2_049, (500, 700, 300, 900), (64, 64, 32, 48), (256, 256, 16), True),
     ("bf16_deep_64_100", 1_333, (100, 200), (32, 40), (64, 100), False),
     ("bf16_deep_96_200_130_7_cf3", 1_111, (64, 80), (24, 24), (96, 200, 130, 7), True, 3),
+    ("bf16_deep_40_24_1", 1_777, (64, 80), (24, 24), (40, 24, 1), True, 5),
+    ("bf16_deep_200_64", 1_025, (90, 70), (12, 12), (200, 64), False),
+    ("bf16_deep_8_8_8", 999, (33,), (7,), (8, 8, 8), True),
 ]
 
 
