@@ -37,30 +37,40 @@ struct DeepLds {
   int total;
 };
 
-// out^T = W^T h^T + b for one layer; w and bias point into LDS.  The 16x16 weight tiles are taken
-// in the order (kt, ot) and requested two tiles ahead of the products that use them, so that the
-// matrix cores do not wait for LDS.
-template <int TIN, int TOUT>
-__device__ __forceinline__ void dense_layer(const v4f (&h)[TIN], const float* w, const float* bias, int lane,
-                                            v4f (&out)[TOUT]) {
+// out^T += W^T h^T for TIN input tiles (tiles kt0 .. kt0 + TIN - 1 of a layer of TIN_ALL input
+// tiles); w points into LDS.  The 16x16 weight tiles are taken in the order (kt, ot) and requested
+// two tiles ahead of the products that use them, so that the matrix cores do not wait for LDS.
+template <int TIN, int TOUT, int TIN_ALL>
+__device__ __forceinline__ void dense_accumulate(const v4f (&h)[TIN], const float* w, int kt0, int lane, v4f (&out)[TOUT]) {
   constexpr int NB = TIN * TOUT, AHEAD = 2;
-  const int q4 = lane >> 4;
-  const v4f* wl = reinterpret_cast<const v4f*>(w) + lane;      // tile (ot, kt) at wl[(ot TIN + kt) 64]
+  const v4f* wl = reinterpret_cast<const v4f*>(w) + kt0 * 64 + lane;   // tile (ot, kt) at wl[(ot TIN_ALL + kt) 64]
   v4f wv[AHEAD + 1];
 #pragma unroll
-  for (int b = 0; b < AHEAD && b < NB; ++b) wv[b] = wl[((b % TOUT) * TIN + b / TOUT) * 64];
-#pragma unroll
-  for (int ot = 0; ot < TOUT; ++ot) out[ot] = *reinterpret_cast<const v4f*>(bias + 16 * ot + 4 * q4);
+  for (int b = 0; b < AHEAD && b < NB; ++b) wv[b] = wl[((b % TOUT) * TIN_ALL + b / TOUT) * 64];
 #pragma unroll
   for (int b = 0; b < NB; ++b) {
     const int kt = b / TOUT, ot = b % TOUT;
-    if (b + AHEAD < NB) wv[(b + AHEAD) % (AHEAD + 1)] = wl[(((b + AHEAD) % TOUT) * TIN + (b + AHEAD) / TOUT) * 64];
+    if (b + AHEAD < NB) wv[(b + AHEAD) % (AHEAD + 1)] = wl[(((b + AHEAD) % TOUT) * TIN_ALL + (b + AHEAD) / TOUT) * 64];
     __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
     for (int v = 0; v < 4; ++v)
       out[ot] = __builtin_amdgcn_mfma_f32_16x16x4f32(wv[b % (AHEAD + 1)][v], h[kt][v], out[ot], 0, 0, 0);
     __builtin_amdgcn_sched_barrier(0);
   }
+}
+
+template <int TOUT>
+__device__ __forceinline__ void load_bias(const float* bias, int lane, v4f (&out)[TOUT]) {
+#pragma unroll
+  for (int ot = 0; ot < TOUT; ++ot) out[ot] = *reinterpret_cast<const v4f*>(bias + 16 * ot + 4 * (lane >> 4));
+}
+
+// out^T = W^T h^T + b for one whole layer.
+template <int TIN, int TOUT>
+__device__ __forceinline__ void dense_layer(const v4f (&h)[TIN], const float* w, const float* bias, int lane,
+                                            v4f (&out)[TOUT]) {
+  load_bias<TOUT>(bias, lane, out);
+  dense_accumulate<TIN, TOUT, TIN>(h, w, 0, lane, out);
 }
 
 template <int T>
@@ -90,26 +100,28 @@ __device__ __forceinline__ void store_rows(const PredictArgs& a, const v4f (&y)[
   }
 }
 
-// T1: l_1 <= 16 T1 (a multiple of 4).  TH: later hidden layers (and, with two layers, the output) are at most 16 TH wide.
+// T1, PARTS: l_1 <= 16 T1 PARTS (a multiple of 4); the hidden layer is gathered and fed to the second
+// layer in PARTS column parts of 16 T1 units, so that at most 4 T1 registers per table are in flight.  TH: later hidden layers (and, with two layers, the output) are at most 16 TH wide.
 // NL: number of layers (2..4); with three or four layers the output is at most 16 wide.
 // KMAX: number of dimension tables (their gathers are all in flight at once).
-template <int T1, int TH, int NL, int KMAX>
+template <int T1, int PARTS, int TH, int NL, int KMAX>
 __global__ __launch_bounds__(DEEP_THREADS) void fused_deep_kernel(PredictArgs a, DeepLds L, int vec_y) {
+  constexpr int TALL = T1 * PARTS;                // 16-unit tiles of the whole hidden layer
   extern __shared__ __align__(16) float lds[];
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   const int r16 = lane & 15, q4 = lane >> 4;
   const int l1 = a.wout[0];
 
   // ---- stage the model in operand order
-  for (int i = tid; i < T1 * L.kc * 64; i += DEEP_THREADS) {
+  for (int i = tid; i < TALL * L.kc * 64; i += DEEP_THREADS) {
     const int ln = i & 63, tk = i >> 6, t = tk / L.kc, kc = tk - t * L.kc;
     const int q = 4 * kc + (ln >> 4), c = 16 * t + (ln & 15);
     lds[L.wf + i] = (q < a.c_f && c < l1) ? static_cast<const float*>(a.W[0])[static_cast<int64_t>(q) * a.ldw[0] + c] : 0.f;
   }
-  for (int i = tid; i < 16 * T1; i += DEEP_THREADS)
+  for (int i = tid; i < 16 * TALL; i += DEEP_THREADS)
     lds[L.b1 + i] = (i < l1 && a.bias[0]) ? static_cast<const float*>(a.bias[0])[i] : 0.f;
   for (int layer = 1; layer < NL; ++layer) {
-    const int tin = layer == 1 ? T1 : TH;
+    const int tin = layer == 1 ? TALL : TH;
     const int tout = layer == NL - 1 ? (NL == 2 ? TH : 1) : TH;
     const int win = a.win[layer], wout = a.wout[layer];
     const float* W = static_cast<const float*>(a.W[layer]);
@@ -146,17 +158,19 @@ __global__ __launch_bounds__(DEEP_THREADS) void fused_deep_kernel(PredictArgs a,
   const int gsub = lane / LPR, gc = lane % LPR;
   float* tile = lds + L.total + wave * 16 * LD;
   auto clamp_row = [&](int64_t st) { return min<int64_t>(min<int64_t>(st, n_steps - 1) * 16 + r16, a.n - 1); };
+  int key0[KMAX];          // keys of this step (only live when later parts still need them: PARTS > 1)
   int key1[KMAX];          // keys of the step after this one (lane l: row l % 16)
   float xv[4], x1[4];      // fact columns of this step and of the next
-  v4f g[KMAX][T1];         // gathered pieces of this step: g[k][u] = row u RPI + gsub, piece gc
-  const bool active = 4 * gc < l1;        // widths below 16 T1: the lanes past the end of a row idle
-  auto gather = [&](const int (&key)[KMAX]) {
+  v4f g[KMAX][T1];         // gathered pieces in flight: g[k][u] = row u RPI + gsub, piece gc of one part
+  auto gather = [&](const int (&key)[KMAX], int part) {
+    const int col = part * 16 * T1 + 4 * gc;
+    const bool active = col < l1;          // widths below 16 T1 PARTS: the lanes past the end of a row idle
 #pragma unroll
     for (int k = 0; k < KMAX; ++k) {
 #pragma unroll
       for (int u = 0; u < T1; ++u) {
         const int kr = __shfl(key[k], u * RPI + gsub);
-        g[k][u] = active ? *reinterpret_cast<const v4f*>(static_cast<const float*>(a.P[k]) + static_cast<int64_t>(kr) * a.ldp[k] + 4 * gc)
+        g[k][u] = active ? *reinterpret_cast<const v4f*>(static_cast<const float*>(a.P[k]) + static_cast<int64_t>(kr) * a.ldp[k] + col)
                          : v4f{0.f, 0.f, 0.f, 0.f};
       }
     }
@@ -174,7 +188,9 @@ __global__ __launch_bounds__(DEEP_THREADS) void fused_deep_kernel(PredictArgs a,
       xv[kc] = q < a.c_f ? X[row * a.ldx + q] : 0.f;
       x1[kc] = q < a.c_f ? X[row1 * a.ldx + q] : 0.f;
     }
-    gather(key);
+    gather(key, 0);
+#pragma unroll
+    for (int k = 0; k < KMAX; ++k) key0[k] = key[k];
   }
 
   for (;;) {
@@ -194,48 +210,53 @@ __global__ __launch_bounds__(DEEP_THREADS) void fused_deep_kernel(PredictArgs a,
       x2[kc] = q < a.c_f ? X[row2 * a.ldx + q] : 0.f;
     }
 
-    // ---- sum of the gathered rows -> LDS tile; then the gathers of the next step are requested
+    // ---- layers 1 and 2, one column part of the hidden layer at a time
+    constexpr int T2 = TH;                 // output tiles of the second layer (NL == 2: of the model)
+    v4f h2[T2];
 #pragma unroll
-    for (int u = 0; u < T1; ++u) {
-      v4f sum = g[0][u];
+    for (int part = 0; part < PARTS; ++part) {
+      // sum of the gathered rows -> LDS tile; then the next gathers are requested (the next part of
+      // this step, or the first part of the next step) and are in flight during the matrix work
 #pragma unroll
-      for (int k = 1; k < KMAX; ++k)
+      for (int u = 0; u < T1; ++u) {
+        v4f sum = g[0][u];
 #pragma unroll
-        for (int v = 0; v < 4; ++v) sum[v] += g[k][u][v];
-      *reinterpret_cast<v4f*>(tile + (u * RPI + gsub) * LD + 4 * gc) = sum;
-    }
-    gather(key1);
-
-    // ---- layer 1: z = x W_f + b_1 (matrix cores) + the gathered sum (back from the tile), ReLU
-    v4f h1[T1];
+        for (int k = 1; k < KMAX; ++k)
 #pragma unroll
-    for (int t = 0; t < T1; ++t) h1[t] = *reinterpret_cast<const v4f*>(lds + L.b1 + 16 * t + 4 * q4);
-#pragma unroll
-    for (int kc = 0; kc < 4; ++kc)
-      if (kc < L.kc) {
-        float wfv[T1];
-#pragma unroll
-        for (int t = 0; t < T1; ++t) wfv[t] = lds[L.wf + (t * L.kc + kc) * 64 + lane];
-#pragma unroll
-        for (int t = 0; t < T1; ++t) h1[t] = __builtin_amdgcn_mfma_f32_16x16x4f32(wfv[t], xv[kc], h1[t], 0, 0, 0);
+          for (int v = 0; v < 4; ++v) sum[v] += g[k][u][v];
+        *reinterpret_cast<v4f*>(tile + (u * RPI + gsub) * LD + 4 * gc) = sum;
       }
+      if (part + 1 < PARTS) gather(key0, part + 1); else gather(key1, 0);
+
+      // z = x W_f + b_1 (matrix cores) + the gathered sum (back from the tile), ReLU
+      v4f h1[T1];
 #pragma unroll
-    for (int t = 0; t < T1; ++t) {
-      const v4f z = *reinterpret_cast<const v4f*>(tile + r16 * LD + 16 * t + 4 * q4);
+      for (int t = 0; t < T1; ++t) h1[t] = *reinterpret_cast<const v4f*>(lds + L.b1 + 16 * (part * T1 + t) + 4 * q4);
 #pragma unroll
-      for (int v = 0; v < 4; ++v) h1[t][v] = fmaxf(h1[t][v] + z[v], 0.f);
+      for (int kc = 0; kc < 4; ++kc)
+        if (kc < L.kc) {
+          float wfv[T1];
+#pragma unroll
+          for (int t = 0; t < T1; ++t) wfv[t] = lds[L.wf + ((part * T1 + t) * L.kc + kc) * 64 + lane];
+#pragma unroll
+          for (int t = 0; t < T1; ++t) h1[t] = __builtin_amdgcn_mfma_f32_16x16x4f32(wfv[t], xv[kc], h1[t], 0, 0, 0);
+        }
+#pragma unroll
+      for (int t = 0; t < T1; ++t) {
+        const v4f z = *reinterpret_cast<const v4f*>(tile + r16 * LD + 16 * t + 4 * q4);
+#pragma unroll
+        for (int v = 0; v < 4; ++v) h1[t][v] = fmaxf(h1[t][v] + z[v], 0.f);
+      }
+      if (part == 0) load_bias<T2>(lds + L.b[0], lane, h2);
+      dense_accumulate<T1, T2, TALL>(h1, lds + L.w[0], part * T1, lane, h2);
     }
 
     // ---- later layers
     const int64_t row = step * 16 + r16;
     const bool valid = row < a.n;
     if constexpr (NL == 2) {
-      v4f y[TH];
-      dense_layer<T1, TH>(h1, lds + L.w[0], lds + L.b[0], lane, y);
-      store_rows<TH>(a, y, row, valid, q4, l_out, vec_y != 0);
+      store_rows<TH>(a, h2, row, valid, q4, l_out, vec_y != 0);
     } else {
-      v4f h2[TH];
-      dense_layer<T1, TH>(h1, lds + L.w[0], lds + L.b[0], lane, h2);
       relu<TH>(h2);
       if constexpr (NL == 4) {
         v4f h3[TH];
@@ -265,6 +286,10 @@ __global__ __launch_bounds__(DEEP_THREADS) void fused_deep_kernel(PredictArgs a,
     }
     if (!more) break;
     step += stride;
+    if constexpr (PARTS > 1) {
+#pragma unroll
+      for (int k = 0; k < KMAX; ++k) key0[k] = key1[k];
+    }
 #pragma unroll
     for (int k = 0; k < KMAX; ++k) key1[k] = key2[k];
 #pragma unroll
@@ -280,11 +305,14 @@ int try_fused_deep(const PredictArgs& a, hipStream_t s) {
   const int NL = a.n_layers;
   if (NL < 2 || NL > 4) return -1;
   const int l1 = a.wout[0];
-  if (l1 % 4 || l1 < 20 || l1 > 128) return -1;
+  if (l1 % 4 || l1 < 20 || l1 > 256) return -1;
   if (a.c_f > 16 || a.K < 1 || a.K > 4) return -1;
   for (int k = 0; k < a.K; ++k)
     if (!aligned(a.P[k], 16) || a.ldp[k] % 4) return -1;
-  const int T1 = l1 <= 32 ? 2 : (l1 <= 64 ? 4 : 8);   // 16-unit tiles of the hidden layer, padded to a power of two
+  // 16-unit tiles of the hidden layer, padded to a power of two; above 128 in two column parts
+  const int PARTS = l1 > 128 ? 2 : 1;
+  const int T1 = l1 <= 32 ? 2 : (l1 <= 64 ? 4 : 8);
+  const int TALL = T1 * PARTS;
   int wide = 0;                                       // widest later layer that has to fit TH tiles
   for (int j = 1; j < NL; ++j)
     if (j < NL - 1 || NL == 2) wide = std::max(wide, a.wout[j]);
@@ -297,10 +325,10 @@ int try_fused_deep(const PredictArgs& a, hipStream_t s) {
   DeepLds L{};
   L.kc = (a.c_f + 3) / 4;
   int off = 0;
-  L.wf = off; off += T1 * L.kc * 64;
-  L.b1 = off; off += 16 * T1;
+  L.wf = off; off += TALL * L.kc * 64;
+  L.b1 = off; off += 16 * TALL;
   for (int j = 1; j < NL; ++j) {
-    const int tin = j == 1 ? T1 : TH;
+    const int tin = j == 1 ? TALL : TH;
     const int tout = j == NL - 1 ? (NL == 2 ? TH : 1) : TH;
     L.w[j - 1] = off; off += tout * tin * 256;
     L.b[j - 1] = off; off += 16 * tout;
@@ -316,22 +344,24 @@ int try_fused_deep(const PredictArgs& a, hipStream_t s) {
   const int per_cu = static_cast<int>(std::max<size_t>(1, std::min<size_t>(4, (160 * 1024) / std::max<size_t>(lds, 1))));
   const int64_t blocks = std::min<int64_t>((n_steps + DEEP_WAVES - 1) / DEEP_WAVES, static_cast<int64_t>(num_cus()) * per_cu);
   if (blocks <= 0) return LQ_OK;
-#define LQ_DEEP(T1_, TH_, NL_, K_)                                                                          \
+#define LQ_DEEP(T1_, PARTS_, TH_, NL_, K_)                                                                  \
   do {                                                                                                      \
     if (lds > 64 * 1024)                                                                                    \
-      LQ_HIP_TRY(hipFuncSetAttribute(reinterpret_cast<const void*>(&fused_deep_kernel<T1_, TH_, NL_, K_>),  \
+      LQ_HIP_TRY(hipFuncSetAttribute(reinterpret_cast<const void*>(&fused_deep_kernel<T1_, PARTS_, TH_, NL_, K_>), \
                                      hipFuncAttributeMaxDynamicSharedMemorySize, static_cast<int>(lds)));   \
-    hipLaunchKernelGGL((fused_deep_kernel<T1_, TH_, NL_, K_>), dim3(static_cast<unsigned>(blocks)),         \
+    hipLaunchKernelGGL((fused_deep_kernel<T1_, PARTS_, TH_, NL_, K_>), dim3(static_cast<unsigned>(blocks)), \
                        dim3(DEEP_THREADS), lds, s, a, L, vec_y);                                            \
   } while (0)
-#define LQ_DEEP_K(T1_, TH_, NL_)                                                                            \
+#define LQ_DEEP_K(T1_, PARTS_, TH_, NL_)                                                                    \
   do {                                                                                                      \
-    if (a.K == 1) LQ_DEEP(T1_, TH_, NL_, 1); else if (a.K == 2) LQ_DEEP(T1_, TH_, NL_, 2);                  \
-    else if (a.K == 3) LQ_DEEP(T1_, TH_, NL_, 3); else LQ_DEEP(T1_, TH_, NL_, 4);                           \
+    if (a.K == 1) LQ_DEEP(T1_, PARTS_, TH_, NL_, 1); else if (a.K == 2) LQ_DEEP(T1_, PARTS_, TH_, NL_, 2);  \
+    else if (a.K == 3) LQ_DEEP(T1_, PARTS_, TH_, NL_, 3); else LQ_DEEP(T1_, PARTS_, TH_, NL_, 4);           \
   } while (0)
 #define LQ_DEEP_T1(TH_, NL_)                                                                                \
   do {                                                                                                      \
-    if (T1 == 2) LQ_DEEP_K(2, TH_, NL_); else if (T1 == 4) LQ_DEEP_K(4, TH_, NL_); else LQ_DEEP_K(8, TH_, NL_); \
+    if (PARTS == 2) LQ_DEEP_K(8, 2, TH_, NL_);                                                              \
+    else if (T1 == 2) LQ_DEEP_K(2, 1, TH_, NL_); else if (T1 == 4) LQ_DEEP_K(4, 1, TH_, NL_);               \
+    else LQ_DEEP_K(8, 1, TH_, NL_);                                                                         \
   } while (0)
 #define LQ_DEEP_TH(NL_)                                                                                     \
   do {                                                                                                      \

@@ -114,6 +114,11 @@ SHAPES = [
     ("deep_48_32_1", 2_345, 4, (100, 200, 50), (16, 16, 8), (48, 32, 1), True),
     ("deep_100_24", 1_999, 0, (100, 200), (16, 16), (100, 24), False),
     ("deep_20_20_20_2", 1_500, 2, (30, 7), (6, 3), (20, 20, 20, 2), True),
+    # hidden widths above 128: gathered and fed to the second layer in two column parts
+    ("deep_256_64_8_1_k3", 3_001, 4, (1000, 5000, 200), (32, 32, 32), (256, 64, 8, 1), True),
+    ("deep_256_16_k4_cf8", 2_049, 8, (50, 60, 70, 80), (6, 6, 6, 6), (256, 16), True),
+    ("deep_200_40_3_k1", 1_111, 0, (90,), (12,), (200, 40, 3), False),
+    ("deep_132_128_k2", 777, 3, (100, 200), (16, 16), (132, 128), True),
     # the limits of the interface: 8 layers, 8 dimensions
     ("eight_layers_eight_dims", 1_500, 2, (9,) * 8, (3,) * 8, (24, 20, 16, 12, 10, 8, 6, 2), True),
 ]
