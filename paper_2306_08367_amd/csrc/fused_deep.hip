@@ -1,5 +1,5 @@
 // Join-computation stage (last line of Eq. 1) followed by a deeper or wider fp32 MLP (a second
-// layer of 5..128 outputs, or three or four layers with later hidden widths up to 128), with every layer after the gather on the matrix
+// layer of 5..128 outputs, or three or more layers with later hidden widths up to 128), with every layer after the gather on the matrix
 // cores and all activations in registers.
 //
 // A wavefront owns 16 fact rows per step.  In the matrix layers lane l works for row l % 16 and, of
@@ -31,7 +31,7 @@ constexpr int DEEP_WAVES = DEEP_THREADS / 64;
 // Offsets (in floats) of the staged model inside the dynamic LDS block.
 struct DeepLds {
   int wf, b1;              // [T1][KC][64] and [16 T1]
-  int w[3], b[3];          // layer j + 1: [TOUT][TIN][64][4] and [16 TOUT]
+  int w[LQ_MAX_LAYERS - 1], b[LQ_MAX_LAYERS - 1];   // layer j + 1: [TOUT][TIN][64][4] and [16 TOUT]
   int wvec;                // last layer as a plain vector (used when it has one output)
   int kc;                  // ceil(c_f / 4)
   int total;
@@ -102,7 +102,8 @@ __device__ __forceinline__ void store_rows(const PredictArgs& a, const v4f (&y)[
 
 // T1, PARTS: l_1 <= 16 T1 PARTS (a multiple of 4); the hidden layer is gathered and fed to the second
 // layer in PARTS column parts of 16 T1 units, so that at most 4 T1 registers per table are in flight.  TH: later hidden layers (and, with two layers, the output) are at most 16 TH wide.
-// NL: number of layers (2..4); with three or four layers the output is at most 16 wide.
+// NL: number of layers, 2, 3, or 4 for "four or more" (the count is then read at run time); with
+// three or more layers the output is at most 16 wide.
 // KMAX: number of dimension tables (their gathers are all in flight at once).
 template <int T1, int PARTS, int TH, int NL, int KMAX>
 __global__ __launch_bounds__(DEEP_THREADS) void fused_deep_kernel(PredictArgs a, DeepLds L, int vec_y) {
@@ -120,9 +121,10 @@ __global__ __launch_bounds__(DEEP_THREADS) void fused_deep_kernel(PredictArgs a,
   }
   for (int i = tid; i < 16 * TALL; i += DEEP_THREADS)
     lds[L.b1 + i] = (i < l1 && a.bias[0]) ? static_cast<const float*>(a.bias[0])[i] : 0.f;
-  for (int layer = 1; layer < NL; ++layer) {
+  const int nl = NL == 4 ? a.n_layers : NL;
+  for (int layer = 1; layer < nl; ++layer) {
     const int tin = layer == 1 ? TALL : TH;
-    const int tout = layer == NL - 1 ? (NL == 2 ? TH : 1) : TH;
+    const int tout = layer == nl - 1 ? (NL == 2 ? TH : 1) : TH;
     const int win = a.win[layer], wout = a.wout[layer];
     const float* W = static_cast<const float*>(a.W[layer]);
     const int64_t ldw = a.ldw[layer];
@@ -135,9 +137,9 @@ __global__ __launch_bounds__(DEEP_THREADS) void fused_deep_kernel(PredictArgs a,
       lds[L.b[layer - 1] + i] = (i < wout && a.bias[layer]) ? static_cast<const float*>(a.bias[layer])[i] : 0.f;
   }
   if (NL > 2) {
-    const int win = a.win[NL - 1];
+    const int win = a.win[nl - 1];
     for (int i = tid; i < 16 * TH; i += DEEP_THREADS)
-      lds[L.wvec + i] = i < win ? static_cast<const float*>(a.W[NL - 1])[static_cast<int64_t>(i) * a.ldw[NL - 1]] : 0.f;
+      lds[L.wvec + i] = i < win ? static_cast<const float*>(a.W[nl - 1])[static_cast<int64_t>(i) * a.ldw[nl - 1]] : 0.f;
   }
   __syncthreads();
 
@@ -145,7 +147,7 @@ __global__ __launch_bounds__(DEEP_THREADS) void fused_deep_kernel(PredictArgs a,
   int64_t step = static_cast<int64_t>(blockIdx.x) * DEEP_WAVES + wave;
   if (step >= n_steps) return;
   const int64_t stride = static_cast<int64_t>(gridDim.x) * DEEP_WAVES;
-  const int l_out = a.wout[NL - 1];
+  const int l_out = a.wout[nl - 1];
   const float* X = static_cast<const float*>(a.X);
 
   // Software pipeline over the steps of this wavefront: while step s is on the matrix cores, the
@@ -259,11 +261,13 @@ __global__ __launch_bounds__(DEEP_THREADS) void fused_deep_kernel(PredictArgs a,
     } else {
       relu<TH>(h2);
       if constexpr (NL == 4) {
-        v4f h3[TH];
-        dense_layer<TH, TH>(h2, lds + L.w[1], lds + L.b[1], lane, h3);
-        relu<TH>(h3);
+        for (int layer = 2; layer < nl - 1; ++layer) {     // the hidden layers between the second and the last
+          v4f h3[TH];
+          dense_layer<TH, TH>(h2, lds + L.w[layer - 1], lds + L.b[layer - 1], lane, h3);
+          relu<TH>(h3);
 #pragma unroll
-        for (int t = 0; t < TH; ++t) h2[t] = h3[t];
+          for (int t = 0; t < TH; ++t) h2[t] = h3[t];
+        }
       }
       if (l_out == 1) {
         // one output: a dot product per row, summed over the four lanes of the row
@@ -276,11 +280,11 @@ __global__ __launch_bounds__(DEEP_THREADS) void fused_deep_kernel(PredictArgs a,
         }
         y += __shfl_xor(y, 16);
         y += __shfl_xor(y, 32);
-        y += lds[L.b[NL - 2]];
+        y += lds[L.b[nl - 2]];
         if (valid && q4 == 0) static_cast<float*>(a.Y)[row * a.ldy] = y;
       } else {
         v4f y[1];
-        dense_layer<TH, 1>(h2, lds + L.w[NL - 2], lds + L.b[NL - 2], lane, y);
+        dense_layer<TH, 1>(h2, lds + L.w[nl - 2], lds + L.b[nl - 2], lane, y);
         store_rows<1>(a, y, row, valid, q4, l_out, vec_y != 0);
       }
     }
@@ -303,7 +307,7 @@ __global__ __launch_bounds__(DEEP_THREADS) void fused_deep_kernel(PredictArgs a,
 int try_fused_deep(const PredictArgs& a, hipStream_t s) {
   if (a.x_dtype != LQ_F32 || a.p_dtype != LQ_F32 || a.y_dtype != LQ_F32) return -1;
   const int NL = a.n_layers;
-  if (NL < 2 || NL > 4) return -1;
+  if (NL < 2 || NL > LQ_MAX_LAYERS) return -1;
   const int l1 = a.wout[0];
   if (l1 % 4 || l1 < 20 || l1 > 256) return -1;
   if (a.c_f > 16 || a.K < 1 || a.K > 4) return -1;

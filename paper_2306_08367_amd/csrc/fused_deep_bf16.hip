@@ -1,18 +1,20 @@
 // Join-computation stage (last line of Eq. 1) followed by a deeper or wider bf16 MLP (a second
-// layer of 17..256 outputs, or three or four layers with later hidden widths up to 256 and at most
+// layer of 17..256 outputs, or three or more layers with later hidden widths up to 256 and at most
 // 16 outputs): hidden width a multiple of 8 up to 256, up to 16 fact-owned columns, every layer
 // after the gather on the matrix cores.
 //
 // A wavefront handles 16 fact rows per pass.  Lane (g = lane / 16, j = lane % 16) works on row j
 // and, in each 32-wide block kb of hidden units, owns units 32 kb + 8 g .. + 7: the eight bf16 values
 // one lane supplies as the K-slice of the B operand of the 16x16x32 bf16 matrix instruction.  The
-// gathered rows are summed in fp32 in place, rectified and rounded to bf16 once.  Layers are taken
-// transposed, H_(j+1)^T = W_j^T H_j^T: the result of a 16-output tile (register v of lane (g, j) =
-// output 4 g + v of row j, fp32) is rectified, rounded to bf16, and two such tiles side by side are
-// again a B operand (elements 0..3 from the even tile, 4..7 from the odd one), so layers chain in
-// registers.  The weights are staged once per workgroup in LDS in that operand order, zero-padded.
-// Activations are rounded to bf16 between layers, as in any layer-by-layer bf16 pipeline;
-// accumulation is fp32.
+// gathered rows are summed in fp32 in place and rectified.  Layers are taken transposed,
+// H_(j+1)^T = W_j^T H_j^T: the result of a 16-output tile (register v of lane (g, j) = output 4 g + v
+// of row j, fp32) is rectified, and two such tiles side by side are again a B operand (elements 0..3
+// from the even tile, 4..7 from the odd one), so layers chain in registers.  The weights are staged
+// once per workgroup in LDS in that operand order, zero-padded.
+// The instruction takes bf16 operands.  The wide first hidden layer is rounded to bf16 once, as in the
+// one-tile bf16 kernel; every activation of the later (narrower) layers is fed as two operands, its
+// bf16 rounding and the bf16 rounding of what that left over, which keeps those activations at about
+// fp32 precision (their rounding errors would not average out over few units).  Accumulation is fp32.
 #include "lq_common.h"
 
 namespace lq {
@@ -26,8 +28,8 @@ constexpr int DBF_THREADS = 256;
 
 // Byte offsets of the staged model inside the dynamic LDS block.
 struct DeepBfLds {
-  int w[3];       // layer j + 1: [TOUT][chunks of 32 inputs][64 lanes] x 16 bytes
-  int b[3];       // fp32 [16 TOUT]
+  int w[LQ_MAX_LAYERS - 1];       // layer j + 1: [TOUT][chunks of 32 inputs][64 lanes] x 16 bytes
+  int b[LQ_MAX_LAYERS - 1];       // fp32 [16 TOUT]
   int total;
 };
 
@@ -41,35 +43,46 @@ __device__ __forceinline__ void unpack_add(const v4u& w, float (&acc)[8]) {
 __device__ __forceinline__ unsigned int pack2(float lo, float hi) {
   return static_cast<unsigned int>(f32_to_bf16(lo)) | (static_cast<unsigned int>(f32_to_bf16(hi)) << 16);
 }
-__device__ __forceinline__ unsigned int pack2_relu(float lo, float hi) { return pack2(fmaxf(lo, 0.f), fmaxf(hi, 0.f)); }
+// ReLU of two activations, each split into a bf16 head and a bf16 tail (x = head + tail up to 2^-17
+// relative): feeding both to the matrix cores keeps the activations at about fp32 precision although
+// the instruction takes bf16 operands (the weights are bf16 values to begin with, so exact).
+struct HeadTail { unsigned int head, tail; };
+__device__ __forceinline__ HeadTail split2_relu(float x0, float x1) {
+  x0 = fmaxf(x0, 0.f); x1 = fmaxf(x1, 0.f);
+  const bf16_t h0 = f32_to_bf16(x0), h1 = f32_to_bf16(x1);
+  return {static_cast<unsigned int>(h0) | (static_cast<unsigned int>(h1) << 16),
+          pack2(x0 - bf16_to_f32(h0), x1 - bf16_to_f32(h1))};
+}
 
-// out^T = W^T h^T + b: CH chunks of 32 inputs (B operands hb), TOUT tiles of 16 outputs.
-template <int CH, int TOUT>
-__device__ __forceinline__ void dense_layer(const v4u (&hb)[CH], const v4u* w, const float* bias, int lane, v4f (&out)[TOUT]) {
+// out^T = W^T h^T + b: CH chunks of 32 inputs (B operands: heads hb and tails hl), TOUT tiles of 16 outputs.
+template <int CH, int TOUT, bool TAILS = true>
+__device__ __forceinline__ void dense_layer(const v4u (&hb)[CH], const v4u (&hl)[CH], const v4u* w, const float* bias, int lane,
+                                            v4f (&out)[TOUT]) {
   const int g = lane >> 4;
 #pragma unroll
   for (int ot = 0; ot < TOUT; ++ot) out[ot] = *reinterpret_cast<const v4f*>(bias + 16 * ot + 4 * g);
 #pragma unroll
   for (int c = 0; c < CH; ++c)
 #pragma unroll
-    for (int ot = 0; ot < TOUT; ++ot)
-      out[ot] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, w[(ot * CH + c) * 64 + lane]),
-                                                        __builtin_bit_cast(bf16x8, hb[c]), out[ot], 0, 0, 0);
+    for (int ot = 0; ot < TOUT; ++ot) {
+      const bf16x8 wv = __builtin_bit_cast(bf16x8, w[(ot * CH + c) * 64 + lane]);
+      out[ot] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(wv, __builtin_bit_cast(bf16x8, hb[c]), out[ot], 0, 0, 0);
+      if constexpr (TAILS) out[ot] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(wv, __builtin_bit_cast(bf16x8, hl[c]), out[ot], 0, 0, 0);
+    }
 }
 
-// ReLU, round to bf16, and put pairs of 16-output tiles side by side as B operands of the next layer.
+// ReLU, split, and put pairs of 16-output tiles side by side as B operands of the next layer.
 template <int T>
-__device__ __forceinline__ void next_operands(const v4f (&h)[T], v4u (&hb)[(T + 1) / 2]) {
+__device__ __forceinline__ void next_operands(const v4f (&h)[T], v4u (&hb)[(T + 1) / 2], v4u (&hl)[(T + 1) / 2]) {
 #pragma unroll
   for (int m = 0; m < (T + 1) / 2; ++m) {
-    hb[m][0] = pack2_relu(h[2 * m][0], h[2 * m][1]);
-    hb[m][1] = pack2_relu(h[2 * m][2], h[2 * m][3]);
-    if (2 * m + 1 < T) {
-      hb[m][2] = pack2_relu(h[2 * m + 1][0], h[2 * m + 1][1]);
-      hb[m][3] = pack2_relu(h[2 * m + 1][2], h[2 * m + 1][3]);
-    } else {
-      hb[m][2] = 0u;
-      hb[m][3] = 0u;
+#pragma unroll
+    for (int e = 0; e < 4; ++e) {
+      const int t = 2 * m + (e >> 1);                   // elements 0..3 from the even tile, 4..7 from the odd one
+      HeadTail s = {0u, 0u};
+      if (t < T) s = split2_relu(h[t][2 * (e & 1)], h[t][2 * (e & 1) + 1]);
+      hb[m][e] = s.head;
+      hl[m][e] = s.tail;
     }
   }
 }
@@ -109,7 +122,8 @@ __device__ __forceinline__ void stage_weights(const PredictArgs& a, int layer, b
 }
 
 // KB: l_1 <= 32 KB (a multiple of 8; lanes whose units lie past l_1 idle).  TH: later hidden layers (and, with two layers, the output) are at most 16 TH wide.
-// NL: number of layers (2..4); with three or four layers the output is at most 16 wide.
+// NL: number of layers, 2, 3, or 4 for "four or more" (the count is then read at run time); with
+// three or more layers the output is at most 16 wide.
 template <int KB, int TH, int NL>
 __global__ __launch_bounds__(DBF_THREADS) void fused_deep_bf16_kernel(PredictArgs a, DeepBfLds L) {
   constexpr int M = (TH + 1) / 2;                       // 32-input chunks of a later hidden layer
@@ -117,15 +131,17 @@ __global__ __launch_bounds__(DBF_THREADS) void fused_deep_bf16_kernel(PredictArg
   extern __shared__ __align__(16) unsigned char smem[];
   const int lane = threadIdx.x & 63, g = lane >> 4, j = lane & 15;
 
-  stage_weights(a, 1, true, KB, NL == 2 ? TLAST : TH, reinterpret_cast<v4u*>(smem + L.w[0]), reinterpret_cast<float*>(smem + L.b[0]));
-  if (NL >= 3) stage_weights(a, 2, false, M, NL == 3 ? TLAST : TH, reinterpret_cast<v4u*>(smem + L.w[1]), reinterpret_cast<float*>(smem + L.b[1]));
-  if (NL == 4) stage_weights(a, 3, false, M, TLAST, reinterpret_cast<v4u*>(smem + L.w[2]), reinterpret_cast<float*>(smem + L.b[2]));
+  const int nl = NL == 4 ? a.n_layers : NL;
+  stage_weights(a, 1, true, KB, TH, reinterpret_cast<v4u*>(smem + L.w[0]), reinterpret_cast<float*>(smem + L.b[0]));
+  for (int layer = 2; layer < nl; ++layer)
+    stage_weights(a, layer, false, M, layer == nl - 1 ? TLAST : TH, reinterpret_cast<v4u*>(smem + L.w[layer - 1]),
+                  reinterpret_cast<float*>(smem + L.b[layer - 1]));
   __syncthreads();
 
   const int64_t wave = static_cast<int64_t>(blockIdx.x) * (DBF_THREADS / 64) + (threadIdx.x >> 6);
   const int64_t nwaves = static_cast<int64_t>(gridDim.x) * (DBF_THREADS / 64);
   const int64_t npass = (a.n + 15) / 16;
-  const int l_out = a.wout[NL - 1], l1 = a.wout[0];
+  const int l_out = a.wout[nl - 1], l1 = a.wout[0];
   const bool w0_vec = (reinterpret_cast<uintptr_t>(a.W[0]) & 15) == 0 && a.ldw[0] % 8 == 0;
 
   for (int64_t pass = wave; pass < npass; pass += nwaves) {
@@ -184,38 +200,37 @@ __global__ __launch_bounds__(DBF_THREADS) void fused_deep_bf16_kernel(PredictArg
 #pragma unroll
       for (int kb = 0; kb < KB; ++kb) unpack_add(w[kb], acc[kb]);
     }
+    // the wide first hidden layer is rounded to bf16 once (rounding errors of many units average out),
+    // as in the one-tile bf16 kernel; the few activations of the later layers are fed head and tail
     v4u hb[KB];
 #pragma unroll
     for (int kb = 0; kb < KB; ++kb)
-      hb[kb] = (v4u){pack2_relu(acc[kb][0], acc[kb][1]), pack2_relu(acc[kb][2], acc[kb][3]),
-                     pack2_relu(acc[kb][4], acc[kb][5]), pack2_relu(acc[kb][6], acc[kb][7])};
+      hb[kb] = (v4u){pack2(fmaxf(acc[kb][0], 0.f), fmaxf(acc[kb][1], 0.f)), pack2(fmaxf(acc[kb][2], 0.f), fmaxf(acc[kb][3], 0.f)),
+                     pack2(fmaxf(acc[kb][4], 0.f), fmaxf(acc[kb][5], 0.f)), pack2(fmaxf(acc[kb][6], 0.f), fmaxf(acc[kb][7], 0.f))};
 
     // ---- later layers
     const v4u* w2 = reinterpret_cast<const v4u*>(smem + L.w[0]);
     const float* b2 = reinterpret_cast<const float*>(smem + L.b[0]);
     if constexpr (NL == 2) {
       v4f y[TLAST];
-      dense_layer<KB, TLAST>(hb, w2, b2, lane, y);
+      dense_layer<KB, TLAST, false>(hb, hb, w2, b2, lane, y);
       store_rows<TLAST>(a, y, row, live, g, l_out);
     } else {
       v4f h2[TH];
-      dense_layer<KB, TH>(hb, w2, b2, lane, h2);
-      v4u hb2[M];
-      next_operands<TH>(h2, hb2);
-      const v4u* w3 = reinterpret_cast<const v4u*>(smem + L.w[1]);
-      const float* b3 = reinterpret_cast<const float*>(smem + L.b[1]);
+      dense_layer<KB, TH, false>(hb, hb, w2, b2, lane, h2);
+      v4u hb2[M], hl2[M];
+      next_operands<TH>(h2, hb2, hl2);
       if constexpr (NL == 4) {
-        v4f h3[TH];
-        dense_layer<M, TH>(hb2, w3, b3, lane, h3);
-        next_operands<TH>(h3, hb2);
-        v4f y[1];
-        dense_layer<M, 1>(hb2, reinterpret_cast<const v4u*>(smem + L.w[2]), reinterpret_cast<const float*>(smem + L.b[2]), lane, y);
-        store_rows<1>(a, y, row, live, g, l_out);
-      } else {
-        v4f y[1];
-        dense_layer<M, 1>(hb2, w3, b3, lane, y);
-        store_rows<1>(a, y, row, live, g, l_out);
+        for (int layer = 2; layer < nl - 1; ++layer) {     // the hidden layers between the second and the last
+          v4f h3[TH];
+          dense_layer<M, TH>(hb2, hl2, reinterpret_cast<const v4u*>(smem + L.w[layer - 1]),
+                             reinterpret_cast<const float*>(smem + L.b[layer - 1]), lane, h3);
+          next_operands<TH>(h3, hb2, hl2);
+        }
       }
+      v4f y[1];
+      dense_layer<M, 1>(hb2, hl2, reinterpret_cast<const v4u*>(smem + L.w[nl - 2]), reinterpret_cast<const float*>(smem + L.b[nl - 2]), lane, y);
+      store_rows<1>(a, y, row, live, g, l_out);
     }
   }
 }
@@ -226,7 +241,7 @@ __global__ __launch_bounds__(DBF_THREADS) void fused_deep_bf16_kernel(PredictArg
 int try_fused_deep_bf16(const PredictArgs& a, hipStream_t s) {
   if (a.x_dtype != LQ_BF16 || a.p_dtype != LQ_BF16) return -1;
   const int NL = a.n_layers;
-  if (NL < 2 || NL > 4 || a.c_f > 16 || a.K < 1) return -1;
+  if (NL < 2 || NL > LQ_MAX_LAYERS || a.c_f > 16 || a.K < 1) return -1;
   const int l1 = a.wout[0];
   if (l1 % 8 || l1 > 256) return -1;
   const int KB = l1 <= 32 ? 1 : (l1 <= 64 ? 2 : (l1 <= 128 ? 4 : 8));   // 32-unit blocks, padded to a power of two

@@ -119,6 +119,9 @@ SHAPES = [
     ("deep_256_16_k4_cf8", 2_049, 8, (50, 60, 70, 80), (6, 6, 6, 6), (256, 16), True),
     ("deep_200_40_3_k1", 1_111, 0, (90,), (12,), (200, 40, 3), False),
     ("deep_132_128_k2", 777, 3, (100, 200), (16, 16), (132, 128), True),
+    # five to eight layers
+    ("deep_six_layers", 2_345, 4, (100, 200, 50), (16, 16, 8), (64, 48, 32, 32, 16, 3), True),
+    ("deep_eight_layers_256", 1_501, 0, (100, 200), (16, 16), (256, 24, 20, 16, 12, 10, 8, 1), True),
     # the limits of the interface: 8 layers, 8 dimensions
     ("eight_layers_eight_dims", 1_500, 2, (9,) * 8, (3,) * 8, (24, 20, 16, 12, 10, 8, 6, 2), True),
 ]
@@ -253,6 +256,7 @@ BF16_MFMA_SHAPES = [
     ("bf16_deep_40_24_1", 1_777, (64, 80), (24, 24), (40, 24, 1), True, 5),
     ("bf16_deep_200_64", 1_025, (90, 70), (12, 12), (200, 64), False),
     ("bf16_deep_8_8_8", 999, (33,), (7,), (8, 8, 8), True),
+    ("bf16_deep_five_layers", 2_049, (100, 200, 50), (16, 16, 8), (128, 64, 64, 32, 2), True, 4),
 ]
 
 
