@@ -326,14 +326,24 @@ def main():
         mms, _, _ = time_call(lambda: lq.lq_materialized_join_tree(None, wt.dims, wt.fks, tf, tt, tH,
                                                                    chunk_rows=1 << 20), 2, 1)
         gbps = 16.0 * nt / (ms * 1e-3) / 1e9
+        # leaf masks: the same tables compressed to one bit per leaf, AND instead of sum-and-compare
+        masks = lq.lq_tree_compress_tables(wt.dims, tables, tf, tt, tH)
+        cms, _, _ = time_call(lambda: lq.lq_tree_compress_tables(wt.dims, tables, tf, tt, tH), 5, 1)
+        kms, _, _ = time_call(lambda: lq.lq_fused_join_tree_masks(wt.fks, masks, tf, tt, tH), 20, 3)
+        kgbps = 16.0 * nt / (kms * 1e-3) / 1e9
         out["fused_tree"] = {"rows_per_s": nt / (ms * 1e-3), "ms": ms, "project_ms": pms, "fact_rows": nt,
                              "leaves": 64, "nodes": 63, "joined_cols": 128,
                              "materialized_rows_per_s": nt / (mms * 1e-3),
                              "fused_speedup": mms / (ms + pms),
                              "roofline": {"bound": "hbm", "achieved": gbps, "peak": HBM_PEAK_GBPS, "unit": "GB/s",
                                           "frac": gbps / HBM_PEAK_GBPS, "algorithmic_bytes_per_row": 16,
-                                          "gather_GBps": 192.0 * nt / (ms * 1e-3) / 1e9}}
-        del wt, tables
+                                          "gather_GBps": 192.0 * nt / (ms * 1e-3) / 1e9},
+                             "leaf_masks": {"rows_per_s": nt / (kms * 1e-3), "ms": kms, "compress_ms": cms,
+                                            "fused_speedup": mms / (kms + pms + cms),
+                                            "roofline": {"bound": "hbm", "achieved": kgbps, "peak": HBM_PEAK_GBPS,
+                                                         "unit": "GB/s", "frac": kgbps / HBM_PEAK_GBPS,
+                                                         "algorithmic_bytes_per_row": 16}}}
+        del wt, tables, masks
 
     # ---------------------------------------------------------------- trees of growing size (only on request)
     # cardinality settings 1 (large dimension tables, sf 4) and 2 (small ones), leaves 8 .. 2,048:
@@ -351,11 +361,17 @@ def main():
                 ms, _, _ = time_call(lambda: lq.lq_fused_join_tree(None, wt.fks, tables, target, tf, tt, tH), 5, 1)
                 mms, _, _ = time_call(lambda: lq.lq_materialized_join_tree(None, wt.dims, wt.fks, tf, tt, tH,
                                                                            chunk_rows=1 << 19), 1, 1)
+                masks = lq.lq_tree_compress_tables(wt.dims, tables, tf, tt, tH)
+                cms, _, _ = time_call(lambda: lq.lq_tree_compress_tables(wt.dims, tables, tf, tt, tH), 3, 1)
+                kms, _, _ = time_call(lambda: lq.lq_fused_join_tree_masks(wt.fks, masks, tf, tt, tH), 5, 1)
                 cells[f"{setting}_l{leaves}"] = {"fused_ms": round(ms, 4), "prefusion_ms": round(pms, 4),
                                                  "materialized_ms": round(mms, 3),
                                                  "speedup_join_stage": round(mms / ms, 1),
-                                                 "speedup_with_prefusion": round(mms / (ms + pms), 1)}
-                del tables
+                                                 "speedup_with_prefusion": round(mms / (ms + pms), 1),
+                                                 "masks_fused_ms": round(kms, 4), "masks_compress_ms": round(cms, 4),
+                                                 "masks_speedup_join_stage": round(mms / kms, 1),
+                                                 "masks_speedup_with_prefusion": round(mms / (kms + pms + cms), 1)}
+                del tables, masks
             del wt
             torch.cuda.empty_cache()
         out["tree_sweep"] = {"fact_rows": 2_400_000, "joined_cols": 128, "cells": cells}

@@ -297,6 +297,32 @@ int lq_fused_join_tree(const lq_star* star, const lq_tree* tree, const void* con
                        void* ws, size_t ws_bytes, void* hip_stream);
 
 /*
+ * Leaf masks: a compressed form of the pre-fused tables of Eq. 2, for stars whose fact table has
+ * no columns of its own (the setting of Section 3.3.2: every feature lives in a dimension table).
+ * The agreement count of a dimension for (row r, leaf j) never exceeds the number of nodes that
+ * dimension owns on the path to j, and the counts of all dimensions add up to the path length
+ * exactly when each one reaches that maximum.  Bit j of row r of masks[k] says "entry [r][j] of
+ * tables[k] equals the number of nodes dimension k owns on the path to leaf j"; the sum over the
+ * dimensions followed by `== h` is then a bitwise AND of one mask row per dimension, and the join
+ * stage gathers l / 8 bytes per dimension instead of l.
+ *   lq_tree_mask_words(l)   words (uint64) per mask row: ceil(l / 64); bits past l are 0
+ *   tables  as written by lq_tree_project_dims;  masks  host array of K device pointers,
+ *           r_k * words uint64 each;  star->dims gives r_k and c_k (data is not read), star->fact.cols
+ *           must be 0 (LQ_ERR_UNSUPPORTED otherwise)
+ */
+int64_t lq_tree_mask_words(int32_t n_leaves);
+int lq_tree_compress_tables(const lq_star* star, const lq_tree* tree, const void* const* tables,
+                            uint64_t* const* masks, void* hip_stream);
+
+/*
+ * Join-computation stage of Eq. 2 on the leaf masks: per fact row the AND of one mask row per
+ * dimension; leaf = position of its lowest set bit (-1 if it is zero), onehot = its bits as bytes.
+ * Results are identical to lq_fused_join_tree.  leaf / onehot as there; star->fact.cols must be 0.
+ */
+int lq_fused_join_tree_masks(const lq_star* star, const lq_tree* tree, const uint64_t* const* masks,
+                             int32_t* leaf, uint8_t* onehot, uint32_t flags, void* hip_stream);
+
+/*
  * Non-fused tree pipeline in the matrix form of Section 3.3.1: T is written to the workspace chunk
  * by chunk, then B = (T F > v) (0 / 1), R = B H as a dense product on the matrix cores and
  * (R == h) are evaluated on it.  The workspace holds h, H in bf16 and, per chunk row, a row of T, of

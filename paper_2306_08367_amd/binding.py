@@ -134,6 +134,12 @@ def _load():
     lib.lq_tree_project_dims.argtypes = [ps, pt, ctypes.POINTER(vp), vp, vp]
     lib.lq_fused_join_tree.argtypes = [ps, pt, ctypes.POINTER(vp), vp, vp, vp, u32, vp, sz, vp]
     lib.lq_materialized_join_tree.argtypes = [ps, pt, vp, vp, vp, sz, u32, vp]
+    lib.lq_tree_mask_words.argtypes = [i32]
+    lib.lq_tree_mask_words.restype = i64
+    lib.lq_tree_compress_tables.argtypes = [ps, pt, ctypes.POINTER(vp), ctypes.POINTER(vp), vp]
+    lib.lq_tree_compress_tables.restype = ctypes.c_int
+    lib.lq_fused_join_tree_masks.argtypes = [ps, pt, ctypes.POINTER(vp), vp, vp, u32, vp]
+    lib.lq_fused_join_tree_masks.restype = ctypes.c_int
     lib.lq_tree_workspace_bytes.argtypes = [ps, pt, i64]
     lib.lq_tree_workspace_bytes.restype = sz
     lib.lq_last_error.restype = ctypes.c_char_p
@@ -425,6 +431,39 @@ def lq_fused_join_tree(X: Optional[torch.Tensor], fks: Sequence[torch.Tensor], t
     _check(_lib.lq_fused_join_tree(ctypes.byref(star.c), ctypes.byref(tree), _ptr_array(tables),
                                    target.data_ptr(), None if leaf is None else leaf.data_ptr(),
                                    None if onehot is None else onehot.data_ptr(), 0, None, 0, _stream(stream)))
+    return leaf, onehot
+
+
+def lq_tree_mask_words(n_leaves: int) -> int:
+    return int(_lib.lq_tree_mask_words(n_leaves))
+
+
+def lq_tree_compress_tables(dims: Sequence[torch.Tensor], tables, feature, threshold, H, stream=None):
+    """Leaf masks (int64 bit patterns [r_k x words] per dimension) of pre-fused tree tables."""
+    tree = _tree(feature, threshold, H)
+    words = lq_tree_mask_words(tree.n_leaves)
+    dev = H.device
+    masks = [torch.empty((d.shape[0], words), dtype=torch.int64, device=dev) for d in dims]
+    fact = lq_mat(None, 0, 0, 1, LQ_F32)
+    dims_arr = _mat_array(dims)
+    star = lq_star(0, fact, len(dims), dims_arr, _ptr_array([None] * len(dims)))
+    _check(_lib.lq_tree_compress_tables(ctypes.byref(star), ctypes.byref(tree), _ptr_array(tables), _ptr_array(masks),
+                                        _stream(stream)))
+    return masks
+
+
+def lq_fused_join_tree_masks(fks: Sequence[torch.Tensor], masks, feature, threshold, H, want_leaf: bool = True,
+                             want_onehot: bool = False, stream=None):
+    """The join stage on leaf masks: same results as lq_fused_join_tree."""
+    tree = _tree(feature, threshold, H)
+    n = _n_of(None, fks)
+    dev = H.device
+    leaf = torch.empty((n,), dtype=torch.int32, device=dev) if want_leaf else None
+    onehot = torch.empty((n, tree.n_leaves), dtype=torch.uint8, device=dev) if want_onehot else None
+    star = _Star(n, None, None, fks)
+    _check(_lib.lq_fused_join_tree_masks(ctypes.byref(star.c), ctypes.byref(tree), _ptr_array(masks),
+                                         None if leaf is None else leaf.data_ptr(),
+                                         None if onehot is None else onehot.data_ptr(), 0, _stream(stream)))
     return leaf, onehot
 
 

@@ -401,6 +401,184 @@ __global__ __launch_bounds__(256) void tree_match_kernel(int32_t l, const float*
   }
 }
 
+// ---------------------------------------------------------------- leaf masks ---------------
+//
+// Compressed form of the pre-fused tables.  The agreement count of dimension k for (row r, leaf j)
+// is at most the number of nodes k owns on the path to j, and the counts of all dimensions add up
+// to the path length exactly when each of them reaches its own maximum.  One bit per (row, leaf) -
+// "this dimension row agrees with the path to leaf j on every node the dimension owns" - therefore
+// carries all the join stage needs, and the sum-and-compare of Eq. 2 becomes a bitwise AND of one
+// mask row per dimension: 8 bytes instead of 64 gathered per dimension for a 64-leaf tree.
+
+typedef unsigned long long u64;
+
+// Workgroup (blockIdx.y = word w) for up to 1,024 rows.  First the number of nodes this dimension
+// owns on the path to each of the 64 leaves of the word (lane = leaf, the four wavefronts split the
+// nodes, eight loads in flight each); then every thread compares the 64 table bytes of its rows with
+// those counts, four bytes per operation, and packs the 64 outcomes into the mask word of its row.
+constexpr int CMP_ROWS = 4;      // rows per thread
+__global__ __launch_bounds__(256) void tree_compress_kernel(TreeArgs t, const uint8_t* __restrict__ table, int64_t rows,
+                                                            int32_t col_off, int32_t c, u64* __restrict__ masks,
+                                                            int32_t words) {
+  __shared__ int part[4][64];
+  __shared__ unsigned int own_dw[16];
+  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6, w = blockIdx.y;
+  const int j = 64 * w + lane;
+  int own = 0;
+  for (int q0 = wave; q0 < t.p; q0 += 32) {
+    int f[8], h[8];
+#pragma unroll
+    for (int e = 0; e < 8; ++e) {
+      const int q = q0 + 4 * e;
+      f[e] = q < t.p ? t.feature[q] - col_off : -1;
+      h[e] = (q < t.p && j < t.l) ? t.H[static_cast<int64_t>(q) * t.l + j] : 0;
+    }
+#pragma unroll
+    for (int e = 0; e < 8; ++e) own += (f[e] >= 0 && f[e] < c && h[e] != 0) ? 1 : 0;
+  }
+  part[wave][lane] = own;
+  __syncthreads();
+  if (threadIdx.x < 64) {
+    int tot = part[0][lane] + part[1][lane] + part[2][lane] + part[3][lane];
+    tot = j < t.l ? min(tot, 255) : 0xff;               // leaves past l never match (their table bytes are 0)
+    part[0][lane] = tot;
+  }
+  __syncthreads();
+  if (threadIdx.x < 16)
+    own_dw[threadIdx.x] = static_cast<unsigned int>(part[0][4 * threadIdx.x]) | (static_cast<unsigned int>(part[0][4 * threadIdx.x + 1]) << 8) |
+                          (static_cast<unsigned int>(part[0][4 * threadIdx.x + 2]) << 16) | (static_cast<unsigned int>(part[0][4 * threadIdx.x + 3]) << 24);
+  __syncthreads();
+  const int pieces = static_cast<int>(min<int64_t>(4, (t.ld - 64 * w) / 16));   // 16-byte pieces of a row that exist in this word
+#pragma unroll
+  for (int i = 0; i < CMP_ROWS; ++i) {
+    const int64_t r = (static_cast<int64_t>(blockIdx.x) * CMP_ROWS + i) * 256 + threadIdx.x;
+    if (r >= rows) continue;
+    const uint8_t* src = table + r * t.ld + 64 * w;
+    v4u tb[4];
+#pragma unroll
+    for (int pc = 0; pc < 4; ++pc) tb[pc] = pc < pieces ? *reinterpret_cast<const v4u*>(src + 16 * pc) : v4u{0u, 0u, 0u, 0u};
+    u64 word = 0ull;
+#pragma unroll
+    for (int pc = 0; pc < 4; ++pc)
+#pragma unroll
+      for (int d = 0; d < 4; ++d) {
+        const unsigned int fl = zero_bytes(tb[pc][d] ^ own_dw[4 * pc + d]) >> 7;     // bit 0, 8, 16, 24: the byte matches
+        const unsigned int nib = (fl & 1u) | ((fl >> 7) & 2u) | ((fl >> 14) & 4u) | ((fl >> 21) & 8u);
+        word |= static_cast<u64>(nib) << (16 * pc + 4 * d);
+      }
+    masks[r * words + w] = word;
+  }
+}
+
+struct MaskJoinArgs {
+  int64_t n;
+  int32_t K, l, words;
+  const u64* M[LQ_MAX_DIMS];
+  const int32_t* fk[LQ_MAX_DIMS];
+  int32_t* leaf;
+  uint8_t* onehot;
+  int32_t onehot_vec;       // whole 16-byte stores of one-hot rows are legal (l % 16 == 0, aligned)
+};
+
+// Join stage on the masks.  A thread owns four fact rows (row = 256 wave + 64 u + lane, so that key
+// loads and leaf stores are coalesced) and has all their gathers of one load step in flight at once.
+// KT: number of dimensions when it is 1..4, 0 = any number.  WMAX: mask words kept per row for the
+// cooperative one-hot store (trees of up to 64 WMAX leaves), 0 = no one-hot output or the plain store.
+// WPL: mask words per load (2 = 16-byte loads, for an even number of words and 16-byte aligned masks).
+template <int KT, int WMAX, int WPL>
+__global__ __launch_bounds__(256) void fused_tree_mask_kernel(MaskJoinArgs a) {
+  constexpr int KK = KT > 0 ? KT : LQ_MAX_DIMS, R = 4;
+  typedef u64 wvec __attribute__((ext_vector_type(WPL)));
+  const int lane = threadIdx.x & 63;
+  const int64_t wave = static_cast<int64_t>(blockIdx.x) * 4 + (threadIdx.x >> 6);
+  const int64_t row0 = wave * (64 * R);
+  if (row0 >= a.n) return;
+  int key[R][KK];
+#pragma unroll
+  for (int u = 0; u < R; ++u) {
+    const int64_t row = min(row0 + 64 * u + lane, a.n - 1);
+#pragma unroll
+    for (int k = 0; k < KK; ++k) key[u][k] = (KT > 0 || k < a.K) ? __builtin_nontemporal_load(a.fk[k] + row) : 0;
+  }
+  int first[R];
+  u64 kept[R][WMAX > 0 ? WMAX : 1];
+#pragma unroll
+  for (int u = 0; u < R; ++u) {
+    first[u] = -1;
+#pragma unroll
+    for (int x = 0; x < (WMAX > 0 ? WMAX : 1); ++x) kept[u][x] = 0ull;
+  }
+  for (int w0 = 0; w0 < a.words; w0 += WPL) {
+    wvec mv[R];
+#pragma unroll
+    for (int u = 0; u < R; ++u) {
+#pragma unroll
+      for (int e = 0; e < WPL; ++e) mv[u][e] = ~0ull;
+#pragma unroll
+      for (int k = 0; k < KK; ++k)
+        if (KT > 0 || k < a.K) mv[u] &= *reinterpret_cast<const wvec*>(a.M[k] + static_cast<int64_t>(key[u][k]) * a.words + w0);
+    }
+#pragma unroll
+    for (int e = 0; e < WPL; ++e) {
+      const int w = w0 + e;
+#pragma unroll
+      for (int u = 0; u < R; ++u) {
+        const u64 m = a.K == 0 ? 0ull : mv[u][e];
+        if (first[u] < 0 && m != 0ull) first[u] = 64 * w + __builtin_ctzll(m);
+        if constexpr (WMAX > 0) {
+#pragma unroll
+          for (int x = 0; x < WMAX; ++x)
+            if (x == w) kept[u][x] = m;
+        } else if (a.onehot) {             // plain store: every thread writes the bytes of its own rows
+          const int64_t row = row0 + 64 * u + lane;
+          if (row < a.n)
+            for (int b = 0; b < 64 && 64 * w + b < a.l; ++b) a.onehot[row * a.l + 64 * w + b] = (m >> b) & 1ull;
+        }
+      }
+    }
+    if (!a.onehot) {                     // leaf only: done once every row of the wavefront has its leaf
+      bool done = true;
+#pragma unroll
+      for (int u = 0; u < R; ++u) done = done && first[u] >= 0;
+      if (__all(done)) break;
+    }
+  }
+  if (a.leaf) {
+#pragma unroll
+    for (int u = 0; u < R; ++u) {
+      const int64_t row = row0 + 64 * u + lane;
+      if (row < a.n) a.leaf[row] = first[u];
+    }
+  }
+  if constexpr (WMAX > 0) {
+    // one-hot rows, 16 bytes per lane: the C = l / 16 pieces of a row are written by neighbouring lanes
+    const int C = a.l / 16;
+#pragma unroll
+    for (int u = 0; u < R; ++u) {
+      for (int tpos = lane; tpos - lane < 64 * C; tpos += 64) {
+        const int ri = tpos / C, piece = tpos - ri * C;          // row 0..63 of this group, 16-byte piece of its row
+        u64 word = 0ull;
+#pragma unroll
+        for (int x = 0; x < WMAX; ++x) {
+          const u64 other = __shfl(kept[u][x], ri, 64);
+          if (x == piece / 4) word = other;
+        }
+        const int64_t row = row0 + 64 * u + ri;
+        if (row < a.n) {
+          const unsigned int bits = static_cast<unsigned int>(word >> (16 * (piece & 3))) & 0xffffu;
+          v4u out;
+#pragma unroll
+          for (int d = 0; d < 4; ++d) {
+            const unsigned int b = (bits >> (4 * d)) & 0xfu;
+            out[d] = (b & 1u) | ((b & 2u) << 7) | ((b & 4u) << 14) | ((b & 8u) << 21);
+          }
+          __builtin_nontemporal_store(out, reinterpret_cast<v4u*>(a.onehot + row * a.l + 16 * piece));
+        }
+      }
+    }
+  }
+}
+
 int check_tree(const lq_tree* tree, TreeArgs* t) {
   if (!tree) return fail(LQ_ERR_NULL, "tree is NULL");
   if (tree->n_nodes < 1 || tree->n_leaves < 1) return fail(LQ_ERR_SHAPE, "tree needs nodes and leaves");
@@ -634,6 +812,82 @@ int lq_materialized_join_tree(const lq_star* star, const lq_tree* tree, int32_t*
                        hplus, leaf, onehot);
     LQ_LAUNCH_CHECK("tree_match_kernel");
   }
+  return LQ_OK;
+}
+
+int64_t lq_tree_mask_words(int32_t n_leaves) { return n_leaves < 1 ? 0 : (static_cast<int64_t>(n_leaves) + 63) / 64; }
+
+int lq_tree_compress_tables(const lq_star* star, const lq_tree* tree, const void* const* tables,
+                            uint64_t* const* masks, void* hip_stream) {
+  clear_error();
+  TreeArgs t{};
+  int rc = check_star_basic(star, false);
+  if (rc) return rc;
+  if ((rc = check_tree(tree, &t))) return rc;
+  if (star->fact.cols > 0) return fail(LQ_ERR_UNSUPPORTED, "leaf masks need a fact table without columns of its own");
+  if (star->n_dims > 0 && (!tables || !masks || !star->dims)) return fail(LQ_ERR_NULL, "tables, masks or star->dims is NULL");
+  const int32_t words = static_cast<int32_t>(lq_tree_mask_words(t.l));
+  hipStream_t s = static_cast<hipStream_t>(hip_stream);
+  int32_t off = 0;
+  for (int k = 0; k < star->n_dims; ++k) {
+    const lq_mat& d = star->dims[k];
+    if (d.rows < 1 || d.cols < 1) return fail(LQ_ERR_SHAPE, "dims[%d] is malformed", k);
+    if (!tables[k] || !masks[k] || !aligned(masks[k], 8) || !aligned(tables[k], 16))
+      return fail(LQ_ERR_NULL, "tables[%d] or masks[%d] is NULL or misaligned", k, k);
+    const int64_t blocks = (d.rows + 256 * CMP_ROWS - 1) / (256 * CMP_ROWS);
+    if (blocks > 0x7fffffffLL) return fail(LQ_ERR_UNSUPPORTED, "too many rows for one launch");
+    hipLaunchKernelGGL(tree_compress_kernel, dim3(static_cast<unsigned>(blocks), static_cast<unsigned>(words)), dim3(256), 0, s,
+                       t, static_cast<const uint8_t*>(tables[k]), d.rows, off, d.cols,
+                       reinterpret_cast<u64*>(masks[k]), words);
+    LQ_LAUNCH_CHECK("tree_compress_kernel");
+    off += d.cols;
+  }
+  return LQ_OK;
+}
+
+int lq_fused_join_tree_masks(const lq_star* star, const lq_tree* tree, const uint64_t* const* masks,
+                             int32_t* leaf, uint8_t* onehot, uint32_t flags, void* hip_stream) {
+  clear_error();
+  (void)flags;
+  TreeArgs t{};
+  int rc = check_star_basic(star, false);
+  if (rc) return rc;
+  if ((rc = check_tree(tree, &t))) return rc;
+  if (star->fact.cols > 0) return fail(LQ_ERR_UNSUPPORTED, "leaf masks need a fact table without columns of its own");
+  if (star->n_dims > 0 && (!masks || !star->fks)) return fail(LQ_ERR_NULL, "masks or fks is NULL");
+  if (!leaf && !onehot) return fail(LQ_ERR_NULL, "neither leaf nor onehot requested");
+  if (leaf && !aligned(leaf, 4)) return fail(LQ_ERR_SHAPE, "leaf is misaligned");
+  MaskJoinArgs a{};
+  a.n = star->n_fact; a.K = star->n_dims; a.l = t.l; a.words = static_cast<int32_t>(lq_tree_mask_words(t.l));
+  for (int k = 0; k < a.K; ++k) {
+    if (!masks[k] || !aligned(masks[k], 8)) return fail(LQ_ERR_NULL, "masks[%d] is NULL or misaligned", k);
+    if (a.n > 0 && (!star->fks[k] || !aligned(star->fks[k], 4))) return fail(LQ_ERR_NULL, "fks[%d] is NULL or misaligned", k);
+    a.M[k] = reinterpret_cast<const u64*>(masks[k]);
+    a.fk[k] = star->fks[k];
+  }
+  a.leaf = leaf; a.onehot = onehot;
+  a.onehot_vec = onehot && aligned(onehot, 16) && t.l % 16 == 0;
+  if (a.n == 0) return LQ_OK;
+  const int64_t blocks = (a.n + 1023) / 1024;
+  if (blocks > 0x7fffffffLL) return fail(LQ_ERR_UNSUPPORTED, "too many rows for one launch");
+  const dim3 grid(static_cast<unsigned>(blocks)), block(256);
+  hipStream_t s = static_cast<hipStream_t>(hip_stream);
+  const int wmax = (a.onehot_vec && a.words <= 4) ? (a.words <= 1 ? 1 : (a.words <= 2 ? 2 : 4)) : 0;
+  bool wide_loads = a.words % 2 == 0;
+  for (int k = 0; k < a.K; ++k) wide_loads = wide_loads && aligned(masks[k], 16);
+#define LQ_TM(KT_, W_)                                                                                \
+  do {                                                                                                \
+    if (wide_loads) hipLaunchKernelGGL((fused_tree_mask_kernel<KT_, W_, 2>), grid, block, 0, s, a);   \
+    else hipLaunchKernelGGL((fused_tree_mask_kernel<KT_, W_, 1>), grid, block, 0, s, a);              \
+  } while (0)
+#define LQ_TM_W(KT_)                                                                                  \
+  do {                                                                                                \
+    if (wmax == 0) LQ_TM(KT_, 0); else if (wmax == 1) LQ_TM(KT_, 1); else if (wmax == 2) LQ_TM(KT_, 2); else LQ_TM(KT_, 4); \
+  } while (0)
+  if (a.K == 1) LQ_TM_W(1); else if (a.K == 2) LQ_TM_W(2); else if (a.K == 3) LQ_TM_W(3); else if (a.K == 4) LQ_TM_W(4); else LQ_TM_W(0);
+#undef LQ_TM_W
+#undef LQ_TM
+  LQ_LAUNCH_CHECK("fused_tree_mask_kernel");
   return LQ_OK;
 }
 

@@ -140,3 +140,7 @@ def test_fused_tree_over_more_than_2e31_rows(lq):
     want = torch.from_numpy(np.asarray(leaf_w, dtype=np.int32)).cuda()
     assert torch.equal(leaf[: reps * BLOCK].view(reps, BLOCK), want.expand(reps, BLOCK))
     assert torch.equal(leaf[reps * BLOCK:], want[:tail])
+    masks = lq.lq_tree_compress_tables(dims, tables, f, t, H)
+    leaf_k, _ = lq.lq_fused_join_tree_masks(fks, masks, f, t, H)
+    torch.cuda.synchronize()
+    assert torch.equal(leaf_k, leaf)

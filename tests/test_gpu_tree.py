@@ -74,6 +74,38 @@ def test_tree_paths_match_oracle(lq, case):
     np.testing.assert_array_equal(m_leaf.cpu().numpy(), leaf)
     np.testing.assert_array_equal(m_oh.cpu().numpy(), onehot)
     assert (onehot.sum(axis=1) == 1).all()
+    if c_f == 0:
+        _check_masks(lq, w, tree, tables, Tk, leaf, onehot)
+
+
+def _check_masks(lq, w, tree, tables, Tk, leaf, onehot):
+    """Leaf masks: bit j of a row = (its table entry equals the number of nodes the dimension owns on
+    the path to leaf j), from the oracle's tables; the join on the masks gives the oracle's leaves."""
+    f, t, H = tree.feature.cuda(), tree.threshold.cuda(), tree.H.cuda()
+    Hn = tree.H.numpy().astype(np.int64)
+    feat = tree.feature.numpy()
+    leaves = Hn.shape[1]
+    words = lq.lq_tree_mask_words(leaves)
+    masks = lq.lq_tree_compress_tables(w.dims, tables, f, t, H)
+    g_leaf, g_oh = lq.lq_fused_join_tree_masks(w.fks, masks, f, t, H, want_onehot=True)
+    g_leaf_only, none = lq.lq_fused_join_tree_masks(w.fks, masks, f, t, H)
+    torch.cuda.synchronize()
+    off = 0
+    for k, d in enumerate(w.dims):
+        own = (feat >= off) & (feat < off + d.shape[1])
+        neg = (Hn[own] == -1).sum(axis=0)
+        own_len = (Hn[own] != 0).sum(axis=0)
+        bits = (Tk[k] + neg == own_len)                                  # [r_k x leaves]
+        padded = np.zeros((bits.shape[0], words * 64), dtype=np.uint8)
+        padded[:, :leaves] = bits
+        want = np.packbits(padded.reshape(-1, words, 64), axis=2, bitorder="little").view(np.uint64).reshape(-1, words)
+        got = masks[k].cpu().numpy().view(np.uint64)
+        np.testing.assert_array_equal(got, want)
+        off += d.shape[1]
+    assert none is None
+    np.testing.assert_array_equal(g_leaf.cpu().numpy(), leaf)
+    np.testing.assert_array_equal(g_leaf_only.cpu().numpy(), leaf)
+    np.testing.assert_array_equal(g_oh.cpu().numpy(), onehot)
 
 
 def test_tree_on_a_subset_of_columns_and_leaf_only_output(lq):
@@ -104,6 +136,11 @@ def test_degenerate_matrices_without_a_matching_leaf_give_minus_one(lq):
     torch.cuda.synchronize()
     np.testing.assert_array_equal(g_leaf.cpu().numpy(), leaf)
     np.testing.assert_array_equal(g_oh.cpu().numpy(), onehot)
+    masks = lq.lq_tree_compress_tables(w.dims, tables, feature.cuda(), thr.cuda(), H.cuda())
+    k_leaf, k_oh = lq.lq_fused_join_tree_masks(w.fks, masks, feature.cuda(), thr.cuda(), H.cuda(), want_onehot=True)
+    torch.cuda.synchronize()
+    np.testing.assert_array_equal(k_leaf.cpu().numpy(), leaf)
+    np.testing.assert_array_equal(k_oh.cpu().numpy(), onehot)
 
 
 def test_tree_full_size_setting1_shape(lq):
@@ -119,6 +156,10 @@ def test_tree_full_size_setting1_shape(lq):
     leaf_m, _ = lq.lq_materialized_join_tree(None, w.dims, w.fks, f, t, H, chunk_rows=1 << 20)
     torch.cuda.synchronize()
     assert torch.equal(leaf, leaf_m)
+    masks = lq.lq_tree_compress_tables(w.dims, tables, f, t, H)
+    leaf_k, _ = lq.lq_fused_join_tree_masks(w.fks, masks, f, t, H)
+    torch.cuda.synchronize()
+    assert torch.equal(leaf, leaf_k)
     rows = WL.sample_rows(n)
     sub = WL.take_rows(w, rows)
     _, _, want = O.tree_predict(None, sub.dims, sub.fks, tree.feature, tree.threshold, tree.H)

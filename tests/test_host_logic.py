@@ -178,6 +178,17 @@ def test_tree_entry_points_reject_bad_arguments():
     assert lib.lq_materialized_join_tree(ctypes.byref(star), ctypes.byref(tree), FAKE, None, FAKE, 1024, 0,
                                          None) == 4
     assert lib.lq_tree_workspace_bytes(ctypes.byref(star), ctypes.byref(tree), 256) >= 256 * 5 * 4
+    # leaf masks: word count; a fact table with columns of its own is refused; missing arguments
+    assert b.lq_tree_mask_words(1) == 1 and b.lq_tree_mask_words(64) == 1 and b.lq_tree_mask_words(65) == 2
+    assert b.lq_tree_mask_words(0) == 0
+    masks = (ctypes.c_void_p * 1)(FAKE)
+    assert lib.lq_tree_compress_tables(ctypes.byref(star), ctypes.byref(tree), tables, masks, None) == 6
+    assert lib.lq_fused_join_tree_masks(ctypes.byref(star), ctypes.byref(tree), masks, FAKE, None, 0, None) == 6
+    star0, _, keep0 = _star_model(b, c_f=0)
+    assert lib.lq_tree_compress_tables(ctypes.byref(star0), ctypes.byref(tree), tables, None, None) == 1
+    assert lib.lq_fused_join_tree_masks(ctypes.byref(star0), ctypes.byref(tree), masks, None, None, 0, None) == 1
+    odd = (ctypes.c_void_p * 1)(FAKE + 4)
+    assert lib.lq_fused_join_tree_masks(ctypes.byref(star0), ctypes.byref(tree), odd, FAKE, None, 0, None) == 1
 
 
 def test_keymap_entry_points_reject_bad_arguments():
