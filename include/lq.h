@@ -318,6 +318,8 @@ int lq_tree_compress_tables(const lq_star* star, const lq_tree* tree, const void
  * Join-computation stage of Eq. 2 on the leaf masks: per fact row the AND of one mask row per
  * dimension; leaf = position of its lowest set bit (-1 if it is zero), onehot = its bits as bytes.
  * Results are identical to lq_fused_join_tree.  leaf / onehot as there; star->fact.cols must be 0.
+ * star->dims is optional: when given, only dims[k].rows is read (the number of rows of masks[k]),
+ * and mask tables that fit are kept in LDS for the call (it must then not be smaller than any key).
  */
 int lq_fused_join_tree_masks(const lq_star* star, const lq_tree* tree, const uint64_t* const* masks,
                              int32_t* leaf, uint8_t* onehot, uint32_t flags, void* hip_stream);

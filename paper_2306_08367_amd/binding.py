@@ -461,6 +461,9 @@ def lq_fused_join_tree_masks(fks: Sequence[torch.Tensor], masks, feature, thresh
     leaf = torch.empty((n,), dtype=torch.int32, device=dev) if want_leaf else None
     onehot = torch.empty((n, tree.n_leaves), dtype=torch.uint8, device=dev) if want_onehot else None
     star = _Star(n, None, None, fks)
+    # row counts of the mask tables (the library may then keep small tables in LDS); no data pointers
+    rows_arr = (lq_mat * max(1, len(masks)))(*[lq_mat(None, int(m.shape[0]), 1, 1, LQ_F32) for m in masks])
+    star.c.dims = rows_arr
     _check(_lib.lq_fused_join_tree_masks(ctypes.byref(star.c), ctypes.byref(tree), _ptr_array(masks),
                                          None if leaf is None else leaf.data_ptr(),
                                          None if onehot is None else onehot.data_ptr(), 0, _stream(stream)))

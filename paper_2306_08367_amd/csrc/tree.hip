@@ -579,6 +579,99 @@ __global__ __launch_bounds__(256) void fused_tree_mask_kernel(MaskJoinArgs a) {
   }
 }
 
+// The same join for trees of up to 64 leaves (one mask word) and leaf-only output, with the mask
+// tables that fit kept in LDS: one persistent workgroup per compute unit stages them once, then its
+// threads stride over the fact rows, four rows each per step.  Gathers from LDS do not go through the
+// address path of the vector memory unit, which is what bounds the kernel above.
+struct MaskLds {
+  int32_t off[LQ_MAX_DIMS];     // position of the table in LDS in words, -1 = stays in memory
+  int32_t rows[LQ_MAX_DIMS];
+  int32_t vec;                  // key columns and leaf are 16-byte aligned: four rows per load / store
+};
+constexpr int MLDS_THREADS = 1024;
+template <int KT>
+__global__ __launch_bounds__(MLDS_THREADS) void fused_tree_mask_lds_kernel(MaskJoinArgs a, MaskLds L) {
+  constexpr int KK = KT > 0 ? KT : LQ_MAX_DIMS, R = 4;
+  typedef u64 u64x2 __attribute__((ext_vector_type(2)));
+  extern __shared__ __align__(16) u64 tab[];
+  const int tid = threadIdx.x;
+  // stage: 16 bytes per thread and load, four loads requested before the first is stored
+  for (int k = 0; k < KK; ++k)
+    if ((KT > 0 || k < a.K) && L.off[k] >= 0) {
+      const int pairs = L.rows[k] / 2, half_off = L.off[k] / 2;      // (table offsets in LDS are even)
+      const u64x2* src = reinterpret_cast<const u64x2*>(a.M[k]);
+      for (int i0 = tid; i0 < pairs; i0 += 4 * MLDS_THREADS) {
+        u64x2 v[4];
+#pragma unroll
+        for (int e = 0; e < 4; ++e)
+          if (i0 + e * MLDS_THREADS < pairs) v[e] = src[i0 + e * MLDS_THREADS];
+#pragma unroll
+        for (int e = 0; e < 4; ++e)
+          if (i0 + e * MLDS_THREADS < pairs) {
+            tab[2 * (half_off + i0 + e * MLDS_THREADS)] = v[e][0];
+            tab[2 * (half_off + i0 + e * MLDS_THREADS) + 1] = v[e][1];
+          }
+      }
+      if (tid == 0 && (L.rows[k] & 1)) tab[L.off[k] + L.rows[k] - 1] = a.M[k][L.rows[k] - 1];
+    }
+  __syncthreads();
+  // every thread takes four consecutive fact rows per step: one 16-byte load per key column, one
+  // 16-byte store of the four leaves (plain loads: streaming hints made this kernel slower)
+  typedef int v4i __attribute__((ext_vector_type(4)));
+  const int64_t step = static_cast<int64_t>(gridDim.x) * MLDS_THREADS * R;
+  int64_t base = static_cast<int64_t>(blockIdx.x) * MLDS_THREADS * R + R * tid;
+  if (base - R * tid >= a.n) return;
+  v4i key[KK];
+  auto load_keys = [&](int64_t b, v4i (&out)[KK]) {
+#pragma unroll
+    for (int k = 0; k < KK; ++k) {
+      out[k] = v4i{0, 0, 0, 0};
+      if (KT > 0 || k < a.K) {
+        if (L.vec && b + R <= a.n) out[k] = *reinterpret_cast<const v4i*>(a.fk[k] + b);
+        else {
+#pragma unroll
+          for (int u = 0; u < R; ++u) out[k][u] = a.fk[k][min(b + u, a.n - 1)];
+        }
+      }
+    }
+  };
+  load_keys(min(base, a.n - 1), key);
+  for (;;) {
+    const int64_t nbase = base + step;
+    const bool more = nbase - R * tid < a.n;             // (uniform over the workgroup)
+    v4i nkey[KK];
+    load_keys(min(more ? nbase : base, a.n - 1), nkey);   // keys of the next step are in flight during this one
+    u64 m[R];
+#pragma unroll
+    for (int u = 0; u < R; ++u) m[u] = ~0ull;
+#pragma unroll
+    for (int k = 0; k < KK; ++k)
+      if (KT > 0 || k < a.K) {
+        if (L.off[k] >= 0) {                       // (uniform: a table is in LDS for every row or for none)
+#pragma unroll
+          for (int u = 0; u < R; ++u) m[u] &= tab[L.off[k] + key[k][u]];
+        } else {
+          const u64* __restrict__ g = a.M[k];
+#pragma unroll
+          for (int u = 0; u < R; ++u) m[u] &= g[key[k][u]];
+        }
+      }
+    v4i lf;
+#pragma unroll
+    for (int u = 0; u < R; ++u) lf[u] = m[u] != 0ull ? __builtin_ctzll(m[u]) : -1;
+    if (L.vec && base + R <= a.n) *reinterpret_cast<v4i*>(a.leaf + base) = lf;
+    else {
+#pragma unroll
+      for (int u = 0; u < R; ++u)
+        if (base + u < a.n) a.leaf[base + u] = lf[u];
+    }
+    if (!more) break;
+    base = nbase;
+#pragma unroll
+    for (int k = 0; k < KK; ++k) key[k] = nkey[k];
+  }
+}
+
 int check_tree(const lq_tree* tree, TreeArgs* t) {
   if (!tree) return fail(LQ_ERR_NULL, "tree is NULL");
   if (tree->n_nodes < 1 || tree->n_leaves < 1) return fail(LQ_ERR_SHAPE, "tree needs nodes and leaves");
@@ -868,10 +961,51 @@ int lq_fused_join_tree_masks(const lq_star* star, const lq_tree* tree, const uin
   a.leaf = leaf; a.onehot = onehot;
   a.onehot_vec = onehot && aligned(onehot, 16) && t.l % 16 == 0;
   if (a.n == 0) return LQ_OK;
+  hipStream_t s = static_cast<hipStream_t>(hip_stream);
+  if (a.words == 1 && !onehot && star->dims && a.K >= 1 && a.n >= (1 << 20)) {
+    // small mask tables go to LDS (smallest first) as long as they fit next to each other
+    MaskLds L{};
+    int order[LQ_MAX_DIMS];
+    bool ok = true;
+    for (int k = 0; k < a.K; ++k) {
+      order[k] = k;
+      L.off[k] = -1;
+      if (star->dims[k].rows < 1 || star->dims[k].rows > 0x7fffffffLL || !aligned(masks[k], 16)) ok = false;
+      else L.rows[k] = static_cast<int32_t>(star->dims[k].rows);
+    }
+    if (ok) {
+      std::stable_sort(order, order + a.K, [&](int x, int y) { return L.rows[x] < L.rows[y]; });
+      int64_t used = 0;
+      const int64_t budget = (144 * 1024) / 8;
+      for (int q = 0; q < a.K; ++q) {
+        const int k = order[q];
+        if (used + L.rows[k] > budget) break;
+        L.off[k] = static_cast<int32_t>(used);
+        used += (L.rows[k] + 1) / 2 * 2;
+      }
+      if (used > 0) {
+        L.vec = aligned(leaf, 16) ? 1 : 0;
+        for (int k = 0; k < a.K; ++k) L.vec = (L.vec && aligned(star->fks[k], 16)) ? 1 : 0;
+        const size_t lds = static_cast<size_t>(used) * 8;
+        const int64_t need = (a.n + MLDS_THREADS * 4 - 1) / (MLDS_THREADS * 4);
+        const dim3 grid(static_cast<unsigned>(std::min<int64_t>(need, num_cus()))), block(MLDS_THREADS);
+#define LQ_TML(KT_)                                                                                       \
+  do {                                                                                                    \
+    if (lds > 64 * 1024)                                                                                  \
+      LQ_HIP_TRY(hipFuncSetAttribute(reinterpret_cast<const void*>(&fused_tree_mask_lds_kernel<KT_>),     \
+                                     hipFuncAttributeMaxDynamicSharedMemorySize, static_cast<int>(lds))); \
+    hipLaunchKernelGGL((fused_tree_mask_lds_kernel<KT_>), grid, block, lds, s, a, L);                     \
+  } while (0)
+        if (a.K == 1) LQ_TML(1); else if (a.K == 2) LQ_TML(2); else if (a.K == 3) LQ_TML(3); else if (a.K == 4) LQ_TML(4); else LQ_TML(0);
+#undef LQ_TML
+        LQ_LAUNCH_CHECK("fused_tree_mask_lds_kernel");
+        return LQ_OK;
+      }
+    }
+  }
   const int64_t blocks = (a.n + 1023) / 1024;
   if (blocks > 0x7fffffffLL) return fail(LQ_ERR_UNSUPPORTED, "too many rows for one launch");
   const dim3 grid(static_cast<unsigned>(blocks)), block(256);
-  hipStream_t s = static_cast<hipStream_t>(hip_stream);
   const int wmax = (a.onehot_vec && a.words <= 4) ? (a.words <= 1 ? 1 : (a.words <= 2 ? 2 : 4)) : 0;
   bool wide_loads = a.words % 2 == 0;
   for (int k = 0; k < a.K; ++k) wide_loads = wide_loads && aligned(masks[k], 16);
