@@ -233,7 +233,7 @@ __global__ __launch_bounds__(256) void fused_tree_kernel(FusedTreeArgs a) {
   int64_t base[LQ_MAX_DIMS];
 #pragma unroll
   for (int k = 0; k < LQ_MAX_DIMS; ++k)
-    if (k < a.K) base[k] = static_cast<int64_t>(__builtin_nontemporal_load(a.fk[k] + rr)) * a.t.ld;
+    if (k < a.K) base[k] = static_cast<int64_t>(a.fk[k][rr]) * a.t.ld;
   int first = 0x7fffffff;
   for (int ch = c; ch < a.chunks; ch += G) {
     v4u sum = {0u, 0u, 0u, 0u};
@@ -299,7 +299,7 @@ __global__ __launch_bounds__(256) void fused_tree_batch_kernel(FusedTreeArgs a) 
 #pragma unroll
   for (int k = 0; k < KK; ++k) {
     const bool used = KT > 0 || k < a.K;
-    key[k] = used ? __builtin_nontemporal_load(a.fk[k] + myrow) : 0;
+    key[k] = used ? a.fk[k][myrow] : 0;
     tab[k] = (used ? a.T[k] : a.T[0]) + 16 * c;
   }
   const bool active = c < a.chunks;
@@ -498,7 +498,7 @@ __global__ __launch_bounds__(256) void fused_tree_mask_kernel(MaskJoinArgs a) {
   for (int u = 0; u < R; ++u) {
     const int64_t row = min(row0 + 64 * u + lane, a.n - 1);
 #pragma unroll
-    for (int k = 0; k < KK; ++k) key[u][k] = (KT > 0 || k < a.K) ? __builtin_nontemporal_load(a.fk[k] + row) : 0;
+    for (int k = 0; k < KK; ++k) key[u][k] = (KT > 0 || k < a.K) ? a.fk[k][row] : 0;
   }
   int first[R];
   u64 kept[R][WMAX > 0 ? WMAX : 1];
@@ -589,9 +589,9 @@ struct MaskLds {
   int32_t vec;                  // key columns and leaf are 16-byte aligned: four rows per load / store
 };
 constexpr int MLDS_THREADS = 1024;
-template <int KT>
+template <int KT>       // number of dimensions, 1..4
 __global__ __launch_bounds__(MLDS_THREADS) void fused_tree_mask_lds_kernel(MaskJoinArgs a, MaskLds L) {
-  constexpr int KK = KT > 0 ? KT : LQ_MAX_DIMS, R = 4;
+  constexpr int KK = KT, R = 4;
   typedef u64 u64x2 __attribute__((ext_vector_type(2)));
   extern __shared__ __align__(16) u64 tab[];
   const int tid = threadIdx.x;
@@ -667,7 +667,6 @@ __global__ __launch_bounds__(MLDS_THREADS) void fused_tree_mask_lds_kernel(MaskJ
     }
     if (!more) break;
     base = nbase;
-#pragma unroll
     for (int k = 0; k < KK; ++k) key[k] = nkey[k];
   }
 }
@@ -962,7 +961,7 @@ int lq_fused_join_tree_masks(const lq_star* star, const lq_tree* tree, const uin
   a.onehot_vec = onehot && aligned(onehot, 16) && t.l % 16 == 0;
   if (a.n == 0) return LQ_OK;
   hipStream_t s = static_cast<hipStream_t>(hip_stream);
-  if (a.words == 1 && !onehot && star->dims && a.K >= 1 && a.n >= (1 << 20)) {
+  if (a.words == 1 && !onehot && star->dims && a.K >= 1 && a.K <= 4 && a.n >= (1 << 20)) {
     // small mask tables go to LDS (smallest first) as long as they fit next to each other
     MaskLds L{};
     int order[LQ_MAX_DIMS];
@@ -996,7 +995,7 @@ int lq_fused_join_tree_masks(const lq_star* star, const lq_tree* tree, const uin
                                      hipFuncAttributeMaxDynamicSharedMemorySize, static_cast<int>(lds))); \
     hipLaunchKernelGGL((fused_tree_mask_lds_kernel<KT_>), grid, block, lds, s, a, L);                     \
   } while (0)
-        if (a.K == 1) LQ_TML(1); else if (a.K == 2) LQ_TML(2); else if (a.K == 3) LQ_TML(3); else if (a.K == 4) LQ_TML(4); else LQ_TML(0);
+        if (a.K == 1) LQ_TML(1); else if (a.K == 2) LQ_TML(2); else if (a.K == 3) LQ_TML(3); else LQ_TML(4);
 #undef LQ_TML
         LQ_LAUNCH_CHECK("fused_tree_mask_lds_kernel");
         return LQ_OK;
