@@ -206,6 +206,40 @@ def test_all_keys_equal_and_strided_inputs(lq):
     assert_close(Ym, want, TOL_F32, "strided materialised")
 
 
+@pytest.mark.parametrize("layers,dtype", [((64, 48, 1), torch.float32), ((200, 24), torch.float32),
+                                          ((64, 12), torch.float32), ((96, 40, 3), torch.bfloat16)],
+                         ids=["f32_64_48_1", "f32_200_24", "f32_64_12", "bf16_96_40_3"])
+def test_deeper_models_with_strided_inputs(lq, layers, dtype):
+    """The matrix-core kernels for deeper models on operands that are column slices of wider buffers:
+    X, the projected tables (row stride > l_1), the weights of the later layers and Y."""
+    n, c_f = 3_001, 4
+    w = WL.make_predict("deep_strided", n, c_f, (300, 200), (16, 16), layers, seed=WL.SEED0 + 90,
+                        dtype=dtype, w_sigma=[0.15] * len(layers), bias=True)
+    want = _oracle(w)
+    w = to_dev(w)
+    tol = TOL_F32 if dtype == torch.float32 else TOL_BF16
+    pad = 8                                          # keeps 16-byte alignment of the slices for both dtypes
+    Xw = torch.zeros((n, c_f + 3), dtype=dtype, device="cuda"); Xw[:, 2:2 + c_f] = w.X
+    P = []
+    for d in w.dims:
+        buf = torch.zeros((d.shape[0], layers[0] + 2 * pad), dtype=dtype, device="cuda")
+        P.append(buf[:, pad:pad + layers[0]])
+    lq.lq_project_dims(w.dims, w.weights[0], c_f, P=P)
+    weights = [w.weights[0]]
+    for W in w.weights[1:]:
+        buf = torch.zeros((W.shape[0], W.shape[1] + 5), dtype=dtype, device="cuda")
+        buf[:, 2:2 + W.shape[1]] = W
+        weights.append(buf[:, 2:2 + W.shape[1]])
+    Yw = torch.full((n, layers[-1] + 3), -1.0, dtype=dtype, device="cuda")
+    Y = Yw[:, 1:1 + layers[-1]]
+    lq.lq_fused_join_predict(Xw[:, 2:2 + c_f], w.fks, P, weights, w.biases, Y=Y)
+    torch.cuda.synchronize()
+    assert_close(Y, want, tol, "strided deep model")
+    assert (Yw[:, 0] == -1).all() and (Yw[:, 1 + layers[-1]:] == -1).all()      # neighbours untouched
+    for buf in P:
+        assert (buf._base[:, :pad] == 0).all() and (buf._base[:, pad + layers[0]:] == 0).all()
+
+
 def test_bf16_paths(lq):
     for name, c_f, layers in (("bf16_linear", 8, (8,)), ("bf16_mlp", 0, (64, 4)), ("bf16_mlp16", 4, (256, 16))):
         w = WL.make_predict(name, 6_007, c_f, (300, 1_000), (32, 64), layers, seed=WL.SEED0 + 80,
