@@ -119,6 +119,15 @@ SHAPES = [
     ("deep_256_16_k4_cf8", 2_049, 8, (50, 60, 70, 80), (6, 6, 6, 6), (256, 16), True),
     ("deep_200_40_3_k1", 1_111, 0, (90,), (12,), (200, 40, 3), False),
     ("deep_132_128_k2", 777, 3, (100, 200), (16, 16), (132, 128), True),
+    # five to eight dimension tables (the fifth and later ones are gathered inside the step)
+    ("deep_64_64_1_k5", 4_099, 4, (100, 200, 50, 70, 90), (8, 8, 8, 8, 8), (64, 64, 1), True),
+    ("deep_128_32_1_k6_cf0", 2_345, 0, (100, 200, 50, 70, 90, 30), (6,) * 6, (128, 32, 1), False),
+    ("deep_256_16_k8", 1_501, 3, (10, 20, 30, 40, 50, 60, 70, 80), (4,) * 8, (256, 16), True),
+    ("deep_40_24_k7", 1_111, 1, (10, 20, 30, 40, 50, 60, 70), (4,) * 7, (40, 24), True),
+    # 17 to 64 fact columns
+    ("deep_64_64_1_cf20", 3_003, 20, (100, 200, 50), (8, 8, 8), (64, 64, 1), True),
+    ("deep_128_24_cf64_k1", 1_777, 64, (90,), (12,), (128, 24), False),
+    ("deep_32_32_3_cf37", 2_222, 37, (60, 70), (5, 9), (32, 32, 3), True),
     # five to eight layers
     ("deep_six_layers", 2_345, 4, (100, 200, 50), (16, 16, 8), (64, 48, 32, 32, 16, 3), True),
     ("deep_eight_layers_256", 1_501, 0, (100, 200), (16, 16), (256, 24, 20, 16, 12, 10, 8, 1), True),
