@@ -179,17 +179,19 @@ def _dtype_code(t: torch.Tensor) -> int:
 def _mat(t: Optional[torch.Tensor], rows: int = 0, cols: int = 0, dtype: int = LQ_F32) -> lq_mat:
     if t is None:
         return lq_mat(None, rows, cols, max(cols, 1), dtype)
-    if t.dim() != 2:
+    shape = t.shape
+    if len(shape) != 2:
         raise ValueError("matrices are 2-D tensors")
-    if t.numel() == 0:
-        return lq_mat(None, int(t.shape[0]), int(t.shape[1]), max(int(t.shape[1]), 1), _dtype_code(t))
-    if t.shape[1] > 1 and t.stride(1) != 1:
+    r, c = shape
+    if r == 0 or c == 0:
+        return lq_mat(None, r, c, max(c, 1), _dtype_code(t))
+    s0, s1 = t.stride()
+    if c > 1 and s1 != 1:
         raise ValueError("matrix columns must be contiguous (row-major)")
-    ld = t.stride(0) if t.shape[0] > 1 else max(int(t.shape[1]), 1)
-    if t.shape[0] > 1 and ld < t.shape[1]:
+    ld = s0 if r > 1 else max(c, 1)
+    if r > 1 and ld < c:
         raise ValueError("row stride smaller than the row")
-    return lq_mat(t.data_ptr() if t.numel() else None, int(t.shape[0]), int(t.shape[1]), int(ld),
-                  _dtype_code(t))
+    return lq_mat(t.data_ptr(), r, c, ld, _dtype_code(t))
 
 
 def _mat_array(ts: Sequence[torch.Tensor]):
@@ -207,8 +209,8 @@ def _ptr_array(ts: Sequence[Optional[torch.Tensor]]):
 
 
 def _stream(stream) -> Optional[int]:
-    if stream is None:
-        stream = torch.cuda.current_stream()
+    if stream is None:     # the raw handle of torch's current stream, without building a Stream object
+        return int(torch._C._cuda_getCurrentRawStream(torch._C._cuda_getDevice())) or None
     return int(stream.cuda_stream) or None
 
 
