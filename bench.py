@@ -84,7 +84,7 @@ def main():
     ap.add_argument("--rows", type=int, default=10_000_000, help="fact rows of the headline workload")
     ap.add_argument("--no-extras", action="store_true", help="skip materialised / group-by / skewed legs")
     ap.add_argument("--no-cpu", action="store_true", help="skip the CPU oracle baseline")
-    ap.add_argument("--only", default="", help="run a single leg for profiling: fused|c1|groupby|groupby16|c4|c5|tree|treesweep|keymap|agg|domain|sweep|sfsweep|materialized|copy")
+    ap.add_argument("--only", default="", help="run a single leg for profiling: fused|c1|groupby|groupby16|c4|c5|deep|tree|treesweep|keymap|agg|domain|sweep|sfsweep|materialized|copy")
     args = ap.parse_args()
     if args.gpus != 1:
         sys.exit("bench.py: this build is single-GPU by design (no collectives, no sharding); "
@@ -312,6 +312,33 @@ def main():
                            "fused_speedup": (mms / m5) / ((ms + pms) / n5)}
         del w5, P5, Y5, ws5, Ym5
         torch.cuda.empty_cache()
+
+    # ---------------------------------------------------------------- deeper models (later layers on the matrix cores)
+    if (args.only == "" and not args.no_extras) or args.only == "deep":
+        nd = 4_000_000
+        cells = {}
+        for name, dt, rows, cols, c_f, layers, sig in (
+                ("f32_c2star_64_64_1", torch.float32, (1_000, 10_000, 100_000), (32, 32, 32), 4, (64, 64, 1), 0.1),
+                ("f32_c2star_128_64_1", torch.float32, (1_000, 10_000, 100_000), (32, 32, 32), 4, (128, 64, 1), 0.1),
+                ("f32_c2star_64_16", torch.float32, (1_000, 10_000, 100_000), (32, 32, 32), 4, (64, 16), 0.1),
+                ("bf16_c5star_256_64_16", torch.bfloat16, (10_000,) * 4, (64,) * 4, 0, (256, 64, 16), 0.06)):
+            wd = WL.make_predict(name, nd, c_f, rows, cols, layers, seed=WL.SEED0 + 950, dtype=dt, device=dev,
+                                 w_sigma=[sig] * len(layers))
+            Pd = lq.lq_project_dims(wd.dims, wd.weights[0], c_f, p_dtype=dt)
+            Yd = torch.empty((nd, layers[-1]), dtype=dt, device=dev)
+            ms, _, _ = time_call(lambda: lq.lq_fused_join_predict(wd.X, wd.fks, Pd, wd.weights, None, Y=Yd), 10, 2)
+            wsd = torch.empty(lq.lq_workspace_bytes(lq.binding.LQ_CALL_MATERIALIZED, wd.k, wd.weights, 1 << 20),
+                              dtype=torch.uint8, device=dev)
+            mms, _, _ = time_call(lambda: lq.lq_materialized_join_predict(wd.X, wd.dims, wd.fks, wd.weights, None,
+                                                                          Y=Yd, ws=wsd), 2, 1)
+            later_flop = 2.0 * sum(a * b for a, b in zip(layers[:-1], layers[1:])) * nd
+            cells[name] = {"fused_ms": round(ms, 4), "rows_per_s": nd / (ms * 1e-3),
+                           "later_layers_TFLOPs": later_flop / (ms * 1e-3) / 1e12,
+                           "gather_GBps": len(rows) * layers[0] * wd.dims[0].element_size() * nd / (ms * 1e-3) / 1e9,
+                           "materialized_ms": round(mms, 3), "fused_speedup": mms / ms}
+            del wd, Pd, Yd, wsd
+        torch.cuda.empty_cache()
+        out["deeper_models"] = {"fact_rows": nd, "cells": cells}
 
     # ---------------------------------------------------------------- group-by at 16x the fact rows
     if (args.only == "" and not args.no_extras) or args.only == "groupby16":
