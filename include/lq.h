@@ -291,6 +291,9 @@ int lq_tree_project_dims(const lq_star* star, const lq_tree* tree, void* const* 
  *   leaf    device int32 [n] or NULL: the first leaf j with R_j = h_j, -1 if none
  *   onehot  device uint8 [n x l] (row stride l) or NULL: (R == h), the paper's binary encoding
  * star->dims is not used (may be NULL); star->fact is needed only if a node tests a fact column.
+ * flags: LQ_CHECK_FKS checks every key against dims[k].rows first (synchronous; star->dims must then
+ * give the row counts, ws a 256-byte aligned buffer of at least 256 bytes) and returns
+ * LQ_ERR_FK_RANGE instead of reading outside a table; ws is not used otherwise.
  */
 int lq_fused_join_tree(const lq_star* star, const lq_tree* tree, const void* const* tables,
                        const uint8_t* target, int32_t* leaf, uint8_t* onehot, uint32_t flags,
@@ -320,6 +323,7 @@ int lq_tree_compress_tables(const lq_star* star, const lq_tree* tree, const void
  * Results are identical to lq_fused_join_tree.  leaf / onehot as there; star->fact.cols must be 0.
  * star->dims is optional: when given, only dims[k].rows is read (the number of rows of masks[k]),
  * and mask tables that fit are kept in LDS for the call (it must then not be smaller than any key).
+ * flags must be 0: the call has no workspace, LQ_CHECK_FKS returns LQ_ERR_UNSUPPORTED.
  */
 int lq_fused_join_tree_masks(const lq_star* star, const lq_tree* tree, const uint64_t* const* masks,
                              int32_t* leaf, uint8_t* onehot, uint32_t flags, void* hip_stream);
@@ -330,6 +334,7 @@ int lq_fused_join_tree_masks(const lq_star* star, const lq_tree* tree, const uin
  * (R == h) are evaluated on it.  The workspace holds h, H in bf16 and, per chunk row, a row of T, of
  * B and of R; ws_bytes decides the chunk (at least 256 rows must fit;
  * lq_tree_workspace_bytes(star, tree, chunk_rows) gives the size for a wanted chunk).
+ * flags: LQ_CHECK_FKS as for lq_fused_join_tree.
  */
 int lq_materialized_join_tree(const lq_star* star, const lq_tree* tree, int32_t* leaf,
                               uint8_t* onehot, void* ws, size_t ws_bytes, uint32_t flags,

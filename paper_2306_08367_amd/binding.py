@@ -422,17 +422,26 @@ def lq_tree_project_dims(dims: Sequence[torch.Tensor], c_f: int, feature, thresh
 
 
 def lq_fused_join_tree(X: Optional[torch.Tensor], fks: Sequence[torch.Tensor], tables, target, feature,
-                       threshold, H, want_leaf: bool = True, want_onehot: bool = False, stream=None):
-    """Leaf reached by every fact row (int32 [n]) and / or the one-hot matrix (uint8 [n x l])."""
+                       threshold, H, want_leaf: bool = True, want_onehot: bool = False, flags: int = 0,
+                       stream=None):
+    """Leaf reached by every fact row (int32 [n]) and / or the one-hot matrix (uint8 [n x l]).
+    With LQ_CHECK_FKS the keys are first checked against the row counts of the tables."""
     tree = _tree(feature, threshold, H)
     n = _n_of(X, fks)
     dev = H.device
     leaf = torch.empty((n,), dtype=torch.int32, device=dev) if want_leaf else None
     onehot = torch.empty((n, tree.n_leaves), dtype=torch.uint8, device=dev) if want_onehot else None
     star = _Star(n, X, None, fks)
+    ws = None
+    if flags & LQ_CHECK_FKS:
+        rows_arr = (lq_mat * max(1, len(tables)))(*[lq_mat(None, int(t.shape[0]), 1, 1, LQ_F32) for t in tables])
+        star.c.dims = rows_arr
+        ws = torch.empty(256, dtype=torch.uint8, device=dev)
     _check(_lib.lq_fused_join_tree(ctypes.byref(star.c), ctypes.byref(tree), _ptr_array(tables),
                                    target.data_ptr(), None if leaf is None else leaf.data_ptr(),
-                                   None if onehot is None else onehot.data_ptr(), 0, None, 0, _stream(stream)))
+                                   None if onehot is None else onehot.data_ptr(), flags,
+                                   None if ws is None else ws.data_ptr(), 0 if ws is None else ws.numel(),
+                                   _stream(stream)))
     return leaf, onehot
 
 
@@ -455,7 +464,7 @@ def lq_tree_compress_tables(dims: Sequence[torch.Tensor], tables, feature, thres
 
 
 def lq_fused_join_tree_masks(fks: Sequence[torch.Tensor], masks, feature, threshold, H, want_leaf: bool = True,
-                             want_onehot: bool = False, stream=None):
+                             want_onehot: bool = False, flags: int = 0, stream=None):
     """The join stage on leaf masks: same results as lq_fused_join_tree."""
     tree = _tree(feature, threshold, H)
     n = _n_of(None, fks)
@@ -468,13 +477,14 @@ def lq_fused_join_tree_masks(fks: Sequence[torch.Tensor], masks, feature, thresh
     star.c.dims = rows_arr
     _check(_lib.lq_fused_join_tree_masks(ctypes.byref(star.c), ctypes.byref(tree), _ptr_array(masks),
                                          None if leaf is None else leaf.data_ptr(),
-                                         None if onehot is None else onehot.data_ptr(), 0, _stream(stream)))
+                                         None if onehot is None else onehot.data_ptr(), flags, _stream(stream)))
     return leaf, onehot
 
 
 def lq_materialized_join_tree(X: Optional[torch.Tensor], dims, fks, feature, threshold, H,
                               want_leaf: bool = True, want_onehot: bool = False,
-                              ws: Optional[torch.Tensor] = None, chunk_rows: Optional[int] = None, stream=None):
+                              ws: Optional[torch.Tensor] = None, chunk_rows: Optional[int] = None, flags: int = 0,
+                              stream=None):
     """Non-fused tree pipeline: materialise T chunk by chunk, then ((T F > v) H) == h."""
     tree = _tree(feature, threshold, H)
     n = _n_of(X, fks)
@@ -489,7 +499,7 @@ def lq_materialized_join_tree(X: Optional[torch.Tensor], dims, fks, feature, thr
     _check(_lib.lq_materialized_join_tree(ctypes.byref(star.c), ctypes.byref(tree),
                                           None if leaf is None else leaf.data_ptr(),
                                           None if onehot is None else onehot.data_ptr(), ws.data_ptr(),
-                                          ws.numel(), 0, _stream(stream)))
+                                          ws.numel(), flags, _stream(stream)))
     return leaf, onehot
 
 

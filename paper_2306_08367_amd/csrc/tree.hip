@@ -671,6 +671,27 @@ __global__ __launch_bounds__(MLDS_THREADS) void fused_tree_mask_lds_kernel(MaskJ
   }
 }
 
+// LQ_CHECK_FKS for the tree calls: synchronous range check of the key columns against the row counts
+// in star->dims; `flag` is a device word inside the caller's workspace.
+int tree_check_fks(const lq_star* star, void* flag, size_t flag_bytes, hipStream_t s) {
+  if (star->n_dims == 0 || star->n_fact == 0) return LQ_OK;
+  if (!star->dims) return fail(LQ_ERR_NULL, "LQ_CHECK_FKS needs star->dims for the row counts");
+  if (!flag || flag_bytes < 256 || !aligned(flag, 256))
+    return fail(LQ_ERR_WORKSPACE, "LQ_CHECK_FKS needs a 256-byte aligned workspace of >= 256 bytes");
+  int64_t rows[LQ_MAX_DIMS];
+  for (int k = 0; k < star->n_dims; ++k) {
+    if (!star->fks || !star->fks[k] || !aligned(star->fks[k], 4)) return fail(LQ_ERR_NULL, "fks[%d] is NULL or misaligned", k);
+    rows[k] = star->dims[k].rows;
+  }
+  int rc = launch_check_fks(star->n_fact, star->n_dims, star->fks, rows, false, static_cast<int32_t*>(flag), s);
+  if (rc) return rc;
+  int32_t h = 0;
+  LQ_HIP_TRY(hipMemcpyAsync(&h, flag, sizeof(h), hipMemcpyDeviceToHost, s));
+  LQ_HIP_TRY(hipStreamSynchronize(s));
+  if (h) return fail(LQ_ERR_FK_RANGE, "a foreign key lies outside its dimension table");
+  return LQ_OK;
+}
+
 int check_tree(const lq_tree* tree, TreeArgs* t) {
   if (!tree) return fail(LQ_ERR_NULL, "tree is NULL");
   if (tree->n_nodes < 1 || tree->n_leaves < 1) return fail(LQ_ERR_SHAPE, "tree needs nodes and leaves");
@@ -795,9 +816,10 @@ int lq_fused_join_tree(const lq_star* star, const lq_tree* tree, const void* con
     if (a.n > 0 && (!star->fact.data || star->fact.ld < a.c_f)) return fail(LQ_ERR_NULL, "fact table is malformed");
     a.X = static_cast<const float*>(star->fact.data); a.ldx = star->fact.ld;
   }
-  (void)flags; (void)ws; (void)ws_bytes;
   if (a.n == 0) return LQ_OK;
   hipStream_t s = static_cast<hipStream_t>(hip_stream);
+  if (flags & LQ_CHECK_FKS)
+    if ((rc = tree_check_fks(star, ws, ws_bytes, s))) return rc;
   int G = 1;
   while (G < a.chunks && G < 64) G <<= 1;
   if (!a.has_fact_nodes && a.chunks <= 16 && (!a.onehot || (a.onehot_vec_ok && a.t.l % 16 == 0))) {
@@ -883,8 +905,9 @@ int lq_materialized_join_tree(const lq_star* star, const lq_tree* tree, int32_t*
   float* T = reinterpret_cast<float*>(per_chunk);
   bf16_t* B = reinterpret_cast<bf16_t*>(per_chunk + round_up(static_cast<size_t>(chunk) * w.ldt * 4, 256));
   float* R = reinterpret_cast<float*>(reinterpret_cast<char*>(B) + round_up(static_cast<size_t>(chunk) * w.ldb * 2, 256));
-  (void)flags;
   hipStream_t s = static_cast<hipStream_t>(hip_stream);
+  if (flags & LQ_CHECK_FKS)      // the flag word takes the first bytes of the workspace, which are rewritten below
+    if ((rc = tree_check_fks(star, ws, ws_bytes, s))) return rc;
   const int cus = num_cus();
   {
     const int64_t total = static_cast<int64_t>(w.p_pad) * w.ldh;
@@ -940,7 +963,8 @@ int lq_tree_compress_tables(const lq_star* star, const lq_tree* tree, const void
 int lq_fused_join_tree_masks(const lq_star* star, const lq_tree* tree, const uint64_t* const* masks,
                              int32_t* leaf, uint8_t* onehot, uint32_t flags, void* hip_stream) {
   clear_error();
-  (void)flags;
+  if (flags & LQ_CHECK_FKS)
+    return fail(LQ_ERR_UNSUPPORTED, "this call has no workspace for LQ_CHECK_FKS: check the keys with lq_fused_join_tree or map them with the key map");
   TreeArgs t{};
   int rc = check_star_basic(star, false);
   if (rc) return rc;

@@ -143,6 +143,30 @@ def test_degenerate_matrices_without_a_matching_leaf_give_minus_one(lq):
     np.testing.assert_array_equal(k_oh.cpu().numpy(), onehot)
 
 
+def test_check_fks_flag_on_the_tree_calls(lq):
+    w, tree = _case("fk_check", 3_000, 0, (30, 40), (6, 6), 12, WL.SEED0 + 602)
+    _, _, leaf = O.tree_predict(w.X, w.dims, w.fks, tree.feature, tree.threshold, tree.H)
+    w = to_dev(w)
+    f, t, H = tree.feature.cuda(), tree.threshold.cuda(), tree.H.cuda()
+    tables, target = lq.lq_tree_project_dims(w.dims, 0, f, t, H)
+    good, _ = lq.lq_fused_join_tree(None, w.fks, tables, target, f, t, H, flags=lq.LQ_CHECK_FKS)
+    good_m, _ = lq.lq_materialized_join_tree(None, w.dims, w.fks, f, t, H, flags=lq.LQ_CHECK_FKS)
+    torch.cuda.synchronize()
+    np.testing.assert_array_equal(good.cpu().numpy(), leaf)
+    np.testing.assert_array_equal(good_m.cpu().numpy(), leaf)
+    bad = [w.fks[0].clone(), w.fks[1]]
+    bad[0][1234] = 30                                   # one past the last row of dimension 0
+    for call in (lambda: lq.lq_fused_join_tree(None, bad, tables, target, f, t, H, flags=lq.LQ_CHECK_FKS),
+                 lambda: lq.lq_materialized_join_tree(None, w.dims, bad, f, t, H, flags=lq.LQ_CHECK_FKS)):
+        with pytest.raises(lq.LQError) as e:
+            call()
+        assert e.value.status == "LQ_ERR_FK_RANGE"
+    masks = lq.lq_tree_compress_tables(w.dims, tables, f, t, H)
+    with pytest.raises(lq.LQError) as e:
+        lq.lq_fused_join_tree_masks(w.fks, masks, f, t, H, flags=lq.LQ_CHECK_FKS)
+    assert e.value.status == "LQ_ERR_UNSUPPORTED"
+
+
 def test_tree_full_size_setting1_shape(lq):
     """Cardinality setting 1 at scale factor 8 (4.8M fact rows; dimensions 80,000 / 16,000 / 2,555),
     128 joined columns, 64 leaves: oracle on a row sample, fused vs non-fused over all rows."""
