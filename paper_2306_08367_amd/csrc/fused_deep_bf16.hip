@@ -1,6 +1,6 @@
 // Join-computation stage (last line of Eq. 1) followed by a deeper or wider bf16 MLP (a second
 // layer of 17..256 outputs, or three or more layers with later hidden widths up to 256 and at most
-// 16 outputs): hidden width a multiple of 8 up to 256, up to 16 fact-owned columns, every layer
+// 16 outputs): hidden width a multiple of 8 up to 256, up to 64 fact-owned columns, every layer
 // after the gather on the matrix cores.
 //
 // A wavefront handles 16 fact rows per pass.  Lane (g = lane / 16, j = lane % 16) works on row j
@@ -241,7 +241,7 @@ __global__ __launch_bounds__(DBF_THREADS) void fused_deep_bf16_kernel(PredictArg
 int try_fused_deep_bf16(const PredictArgs& a, hipStream_t s) {
   if (a.x_dtype != LQ_BF16 || a.p_dtype != LQ_BF16) return -1;
   const int NL = a.n_layers;
-  if (NL < 2 || NL > LQ_MAX_LAYERS || a.c_f > 16 || a.K < 1) return -1;
+  if (NL < 2 || NL > LQ_MAX_LAYERS || a.c_f > 64 || a.K < 1) return -1;
   const int l1 = a.wout[0];
   if (l1 % 8 || l1 > 256) return -1;
   const int KB = l1 <= 32 ? 1 : (l1 <= 64 ? 2 : (l1 <= 128 ? 4 : 8));   // 32-unit blocks, padded to a power of two

@@ -300,6 +300,7 @@ BF16_MFMA_SHAPES = [
     ("bf16_deep_200_64", 1_025, (90, 70), (12, 12), (200, 64), False),
     ("bf16_deep_8_8_8", 999, (33,), (7,), (8, 8, 8), True),
     ("bf16_deep_five_layers", 2_049, (100, 200, 50), (16, 16, 8), (128, 64, 64, 32, 2), True, 4),
+    ("bf16_deep_64_32_1_cf40", 1_501, (100, 200), (16, 16), (64, 32, 1), True, 40),
 ]
 
 
