@@ -107,8 +107,7 @@ __device__ __forceinline__ void store_rows(const PredictArgs& a, const v4f (&y)[
 
 // T1, PARTS: l_1 <= 16 T1 PARTS (a multiple of 4); the hidden layer is gathered and fed to the second
 // layer in PARTS column parts of 16 T1 units, so that at most 4 T1 registers per table are in flight.  TH: later hidden layers (and, with two layers, the output) are at most 16 TH wide.
-// NL: number of layers, 2, 3, or 4 for "four or more" (the count is then read at run time); with
-// three or more layers the output is at most 16 wide.
+// NL: number of layers, 2, 3, or 4 for "four or more" (the count is then read at run time).
 // KMAX: number of dimension tables whose gathers are all in flight at once (1..4).  EXTRA: there are
 // more than KMAX = 4 tables; the further ones are gathered inside the step, after the prefetch of the
 // next step has been requested.
@@ -131,7 +130,7 @@ __global__ __launch_bounds__(DEEP_THREADS) void fused_deep_kernel(PredictArgs a,
   const int nl = NL == 4 ? a.n_layers : NL;
   for (int layer = 1; layer < nl; ++layer) {
     const int tin = layer == 1 ? TALL : TH;
-    const int tout = layer == nl - 1 ? (NL == 2 ? TH : 1) : TH;
+    const int tout = (layer == nl - 1 && NL > 2 && a.wout[nl - 1] <= 16) ? 1 : TH;   // a narrow output layer is one tile
     const int win = a.win[layer], wout = a.wout[layer];
     const float* W = static_cast<const float*>(a.W[layer]);
     const int64_t ldw = a.ldw[layer];
@@ -329,10 +328,14 @@ __global__ __launch_bounds__(DEEP_THREADS) void fused_deep_kernel(PredictArgs a,
         y += __shfl_xor(y, 32);
         y += lds[L.b[nl - 2]];
         if (valid && q4 == 0) static_cast<float*>(a.Y)[row * a.ldy] = y;
-      } else {
+      } else if (l_out <= 16) {
         v4f y[1];
         dense_layer<TH, 1>(h2, lds + L.w[nl - 2], lds + L.b[nl - 2], lane, y);
         store_rows<1>(a, y, row, valid, q4, l_out, vec_y != 0);
+      } else {
+        v4f y[TH];
+        dense_layer<TH, TH>(h2, lds + L.w[nl - 2], lds + L.b[nl - 2], lane, y);
+        store_rows<TH>(a, y, row, valid, q4, l_out, vec_y != 0);
       }
     }
     if (!more) break;

@@ -25,10 +25,9 @@ int try_fused_deep(const PredictArgs& a, hipStream_t s) {
   const int T1 = l1 <= 32 ? 2 : (l1 <= 64 ? 4 : 8);
   const int TALL = T1 * PARTS;
   int wide = 0;                                       // widest later layer that has to fit TH tiles
-  for (int j = 1; j < NL; ++j)
-    if (j < NL - 1 || NL == 2) wide = std::max(wide, a.wout[j]);
   const int l_out = a.wout[NL - 1];
-  if (NL > 2 && l_out > 16) return -1;
+  for (int j = 1; j < NL; ++j)
+    if (j < NL - 1 || NL == 2 || l_out > 16) wide = std::max(wide, a.wout[j]);   // (an output layer of <= 16 is its own tile)
   if (NL == 2 && l_out <= 4) return -1;               // the row-batch kernels are at least as fast there
   if (wide > 128) return -1;
   const int TH = wide <= 16 ? 1 : (wide <= 32 ? 2 : (wide <= 64 ? 4 : 8));
@@ -40,7 +39,7 @@ int try_fused_deep(const PredictArgs& a, hipStream_t s) {
   L.b1 = off; off += 16 * TALL;
   for (int j = 1; j < NL; ++j) {
     const int tin = j == 1 ? TALL : TH;
-    const int tout = j == NL - 1 ? (NL == 2 ? TH : 1) : TH;
+    const int tout = (j == NL - 1 && NL > 2 && l_out <= 16) ? 1 : TH;
     L.w[j - 1] = off; off += tout * tin * 256;
     L.b[j - 1] = off; off += 16 * tout;
   }

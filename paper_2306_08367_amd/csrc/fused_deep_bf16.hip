@@ -122,8 +122,7 @@ __device__ __forceinline__ void stage_weights(const PredictArgs& a, int layer, b
 }
 
 // KB: l_1 <= 32 KB (a multiple of 8; lanes whose units lie past l_1 idle).  TH: later hidden layers (and, with two layers, the output) are at most 16 TH wide.
-// NL: number of layers, 2, 3, or 4 for "four or more" (the count is then read at run time); with
-// three or more layers the output is at most 16 wide.
+// NL: number of layers, 2, 3, or 4 for "four or more" (the count is then read at run time).
 template <int KB, int TH, int NL>
 __global__ __launch_bounds__(DBF_THREADS) void fused_deep_bf16_kernel(PredictArgs a, DeepBfLds L) {
   constexpr int M = (TH + 1) / 2;                       // 32-input chunks of a later hidden layer
@@ -134,7 +133,7 @@ __global__ __launch_bounds__(DBF_THREADS) void fused_deep_bf16_kernel(PredictArg
   const int nl = NL == 4 ? a.n_layers : NL;
   stage_weights(a, 1, true, KB, TH, reinterpret_cast<v4u*>(smem + L.w[0]), reinterpret_cast<float*>(smem + L.b[0]));
   for (int layer = 2; layer < nl; ++layer)
-    stage_weights(a, layer, false, M, layer == nl - 1 ? TLAST : TH, reinterpret_cast<v4u*>(smem + L.w[layer - 1]),
+    stage_weights(a, layer, false, M, (layer == nl - 1 && a.wout[nl - 1] <= 16) ? 1 : TH, reinterpret_cast<v4u*>(smem + L.w[layer - 1]),
                   reinterpret_cast<float*>(smem + L.b[layer - 1]));
   __syncthreads();
 
@@ -228,9 +227,17 @@ __global__ __launch_bounds__(DBF_THREADS) void fused_deep_bf16_kernel(PredictArg
           next_operands<TH>(h3, hb2, hl2);
         }
       }
-      v4f y[1];
-      dense_layer<M, 1>(hb2, hl2, reinterpret_cast<const v4u*>(smem + L.w[nl - 2]), reinterpret_cast<const float*>(smem + L.b[nl - 2]), lane, y);
-      store_rows<1>(a, y, row, live, g, l_out);
+      const v4u* wlast = reinterpret_cast<const v4u*>(smem + L.w[nl - 2]);
+      const float* blast = reinterpret_cast<const float*>(smem + L.b[nl - 2]);
+      if (l_out <= 16) {
+        v4f y[1];
+        dense_layer<M, 1>(hb2, hl2, wlast, blast, lane, y);
+        store_rows<1>(a, y, row, live, g, l_out);
+      } else {
+        v4f y[TH];
+        dense_layer<M, TH>(hb2, hl2, wlast, blast, lane, y);
+        store_rows<TH>(a, y, row, live, g, l_out);
+      }
     }
   }
 }
@@ -249,10 +256,9 @@ int try_fused_deep_bf16(const PredictArgs& a, hipStream_t s) {
     if (!aligned(a.P[k], 16) || a.ldp[k] % 8) return -1;
   const int l_out = a.wout[NL - 1];
   if (NL == 2 && l_out <= 16) return -1;              // the one-tile bf16 kernel covers these
-  if (NL > 2 && l_out > 16) return -1;
   int wide = 0;
   for (int j = 1; j < NL; ++j)
-    if (j < NL - 1 || NL == 2) wide = std::max(wide, a.wout[j]);
+    if (j < NL - 1 || NL == 2 || l_out > 16) wide = std::max(wide, a.wout[j]);   // (an output layer of <= 16 is its own tile)
   if (wide > 256) return -1;
   const int TH = wide <= 16 ? 1 : (wide <= 32 ? 2 : (wide <= 64 ? 4 : (wide <= 128 ? 8 : 16)));
   const int M = (TH + 1) / 2;
@@ -261,7 +267,7 @@ int try_fused_deep_bf16(const PredictArgs& a, hipStream_t s) {
   int off = 0;
   for (int j = 1; j < NL; ++j) {
     const int chunks = j == 1 ? KB : M;
-    const int tout = j == NL - 1 ? (NL == 2 ? TH : 1) : TH;
+    const int tout = (j == NL - 1 && NL > 2 && l_out <= 16) ? 1 : TH;
     L.w[j - 1] = off; off += tout * chunks * 64 * 16;
     L.b[j - 1] = off; off += 16 * tout * 4;
   }

@@ -128,6 +128,10 @@ SHAPES = [
     ("deep_64_64_1_cf20", 3_003, 20, (100, 200, 50), (8, 8, 8), (64, 64, 1), True),
     ("deep_128_24_cf64_k1", 1_777, 64, (90,), (12,), (128, 24), False),
     ("deep_32_32_3_cf37", 2_222, 37, (60, 70), (5, 9), (32, 32, 3), True),
+    # more than 16 outputs after three or four layers
+    ("deep_64_32_64", 2_345, 4, (100, 200, 50), (16, 16, 8), (64, 32, 64), True),
+    ("deep_128_16_100_k2", 1_501, 0, (100, 200), (16, 16), (128, 16, 100), False),
+    ("deep_32_48_24_40", 2_222, 3, (60, 70), (5, 9), (32, 48, 24, 40), True),
     # five to eight layers
     ("deep_six_layers", 2_345, 4, (100, 200, 50), (16, 16, 8), (64, 48, 32, 32, 16, 3), True),
     ("deep_eight_layers_256", 1_501, 0, (100, 200), (16, 16), (256, 24, 20, 16, 12, 10, 8, 1), True),
@@ -301,6 +305,8 @@ BF16_MFMA_SHAPES = [
     ("bf16_deep_8_8_8", 999, (33,), (7,), (8, 8, 8), True),
     ("bf16_deep_five_layers", 2_049, (100, 200, 50), (16, 16, 8), (128, 64, 64, 32, 2), True, 4),
     ("bf16_deep_64_32_1_cf40", 1_501, (100, 200), (16, 16), (64, 32, 1), True, 40),
+    ("bf16_deep_64_32_64", 2_049, (100, 200, 50), (16, 16, 8), (64, 32, 64), True, 4),
+    ("bf16_deep_256_64_200", 1_025, (90, 70), (12, 12), (256, 64, 200), False),
 ]
 
 
