@@ -417,9 +417,20 @@ typedef unsigned long long u64;
 // nodes, eight loads in flight each); then every thread compares the 64 table bytes of its rows with
 // those counts, four bytes per operation, and packs the 64 outcomes into the mask word of its row.
 constexpr int CMP_ROWS = 4;      // rows per thread
-__global__ __launch_bounds__(256) void tree_compress_kernel(TreeArgs t, const uint8_t* __restrict__ table, int64_t rows,
-                                                            int32_t col_off, int32_t c, u64* __restrict__ masks,
-                                                            int32_t words) {
+// All dimension tables in one launch: blockIdx.z selects the table, workgroups past its rows leave at once.
+struct CompressArgs {
+  const uint8_t* table[LQ_MAX_DIMS];
+  u64* masks[LQ_MAX_DIMS];
+  int64_t rows[LQ_MAX_DIMS];
+  int32_t col_off[LQ_MAX_DIMS], cols[LQ_MAX_DIMS];
+};
+__global__ __launch_bounds__(256) void tree_compress_kernel(TreeArgs t, CompressArgs ca, int32_t words) {
+  const int dim = blockIdx.z;
+  const int64_t rows = ca.rows[dim];
+  if (static_cast<int64_t>(blockIdx.x) * CMP_ROWS * 256 >= rows) return;
+  const uint8_t* __restrict__ table = ca.table[dim];
+  u64* __restrict__ masks = ca.masks[dim];
+  const int32_t col_off = ca.col_off[dim], c = ca.cols[dim];
   __shared__ int part[4][64];
   __shared__ unsigned int own_dw[16];
   const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6, w = blockIdx.y;
@@ -943,20 +954,26 @@ int lq_tree_compress_tables(const lq_star* star, const lq_tree* tree, const void
   if (star->n_dims > 0 && (!tables || !masks || !star->dims)) return fail(LQ_ERR_NULL, "tables, masks or star->dims is NULL");
   const int32_t words = static_cast<int32_t>(lq_tree_mask_words(t.l));
   hipStream_t s = static_cast<hipStream_t>(hip_stream);
+  if (star->n_dims == 0) return LQ_OK;
+  CompressArgs ca{};
   int32_t off = 0;
+  int64_t max_rows = 0;
   for (int k = 0; k < star->n_dims; ++k) {
     const lq_mat& d = star->dims[k];
     if (d.rows < 1 || d.cols < 1) return fail(LQ_ERR_SHAPE, "dims[%d] is malformed", k);
     if (!tables[k] || !masks[k] || !aligned(masks[k], 8) || !aligned(tables[k], 16))
       return fail(LQ_ERR_NULL, "tables[%d] or masks[%d] is NULL or misaligned", k, k);
-    const int64_t blocks = (d.rows + 256 * CMP_ROWS - 1) / (256 * CMP_ROWS);
-    if (blocks > 0x7fffffffLL) return fail(LQ_ERR_UNSUPPORTED, "too many rows for one launch");
-    hipLaunchKernelGGL(tree_compress_kernel, dim3(static_cast<unsigned>(blocks), static_cast<unsigned>(words)), dim3(256), 0, s,
-                       t, static_cast<const uint8_t*>(tables[k]), d.rows, off, d.cols,
-                       reinterpret_cast<u64*>(masks[k]), words);
-    LQ_LAUNCH_CHECK("tree_compress_kernel");
+    ca.table[k] = static_cast<const uint8_t*>(tables[k]);
+    ca.masks[k] = reinterpret_cast<u64*>(masks[k]);
+    ca.rows[k] = d.rows; ca.col_off[k] = off; ca.cols[k] = d.cols;
+    max_rows = std::max<int64_t>(max_rows, d.rows);
     off += d.cols;
   }
+  const int64_t blocks = (max_rows + 256 * CMP_ROWS - 1) / (256 * CMP_ROWS);
+  if (blocks > 0x7fffffffLL || words > 65535) return fail(LQ_ERR_UNSUPPORTED, "too many rows or leaves for one launch");
+  hipLaunchKernelGGL(tree_compress_kernel, dim3(static_cast<unsigned>(blocks), static_cast<unsigned>(words),
+                                                static_cast<unsigned>(star->n_dims)), dim3(256), 0, s, t, ca, words);
+  LQ_LAUNCH_CHECK("tree_compress_kernel");
   return LQ_OK;
 }
 
