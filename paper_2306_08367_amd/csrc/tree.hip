@@ -69,11 +69,22 @@ __global__ __launch_bounds__(256) void tree_project_kernel(TreeArgs t, const flo
 // nodes into one word; lane j then holds leaf j and counts the agreements with two popcounts per
 // word against the +1 / -1 node masks of its path, which it built once from its column of H.
 // r * (p + l) / 64 wavefront steps instead of r * l * p thread steps.
+// All dimension tables go out in one launch: blockIdx.z selects the table.
+struct ProjectArgs {
+  const float* D[LQ_MAX_DIMS];
+  uint8_t* out[LQ_MAX_DIMS];
+  int64_t ldd[LQ_MAX_DIMS], rows[LQ_MAX_DIMS];
+  int32_t col_off[LQ_MAX_DIMS], cols[LQ_MAX_DIMS];
+};
 template <int W>
-__global__ __launch_bounds__(256) void tree_project_bits_kernel(TreeArgs t, const float* __restrict__ D,
-                                                                int64_t ldd, int64_t rows, int32_t col_off,
-                                                                int32_t c, uint8_t* __restrict__ out) {
+__global__ __launch_bounds__(256) void tree_project_bits_kernel(TreeArgs t, ProjectArgs pa) {
   typedef unsigned long long u64;
+  const int dim = blockIdx.z;
+  const float* __restrict__ D = pa.D[dim];
+  uint8_t* __restrict__ out = pa.out[dim];
+  const int64_t ldd = pa.ldd[dim], rows = pa.rows[dim];
+  const int32_t col_off = pa.col_off[dim], c = pa.cols[dim];
+  if (static_cast<int64_t>(blockIdx.x) * 16 >= rows) return;      // (a workgroup starts at row 16 blockIdx.x)
   const int lane = threadIdx.x & 63;
   const int64_t wave = static_cast<int64_t>(blockIdx.x) * 4 + (threadIdx.x >> 6);
   const int64_t nwaves = static_cast<int64_t>(gridDim.x) * 4;
@@ -774,18 +785,8 @@ int lq_tree_project_dims(const lq_star* star, const lq_tree* tree, void* const* 
                          static_cast<uint8_t*>(tables[k]), rpb);
       LQ_LAUNCH_CHECK("tree_project_sparse_kernel");
     } else if (t.p <= 256) {
-      // every wavefront builds the node masks of its 64 leaves once (p loads): give it at least p / 8
-      // rows to spread that over
-      const int64_t rows_per_block = 4 * std::max<int64_t>(4, t.p / 8);
-      const int64_t blocks = std::max<int64_t>(1, std::min<int64_t>((d.rows + rows_per_block - 1) / rows_per_block,
-                                                                    static_cast<int64_t>(num_cus()) * 8));
-      const dim3 grid(static_cast<unsigned>(blocks), static_cast<unsigned>((t.ld + 63) / 64)), block(256);
-      const float* dd = static_cast<const float*>(d.data);
-      uint8_t* tab = static_cast<uint8_t*>(tables[k]);
-      if (t.p <= 64) hipLaunchKernelGGL(tree_project_bits_kernel<1>, grid, block, 0, s, t, dd, d.ld, d.rows, off, d.cols, tab);
-      else if (t.p <= 128) hipLaunchKernelGGL(tree_project_bits_kernel<2>, grid, block, 0, s, t, dd, d.ld, d.rows, off, d.cols, tab);
-      else hipLaunchKernelGGL(tree_project_bits_kernel<4>, grid, block, 0, s, t, dd, d.ld, d.rows, off, d.cols, tab);
-      LQ_LAUNCH_CHECK("tree_project_bits_kernel");
+      off += d.cols;
+      continue;                          // (these go out together, after the loop)
     } else {
       const int64_t total = d.rows * t.ld;
       const int64_t blocks = std::min<int64_t>((total + 255) / 256, static_cast<int64_t>(num_cus()) * 32);
@@ -795,6 +796,28 @@ int lq_tree_project_dims(const lq_star* star, const lq_tree* tree, void* const* 
       LQ_LAUNCH_CHECK("tree_project_kernel");
     }
     off += d.cols;
+  }
+  if (t.p <= 256 && star->n_dims > 0) {
+    // every wavefront builds the node masks of its 64 leaves once (p loads): give it at least p / 8
+    // rows to spread that over
+    ProjectArgs pa{};
+    int32_t o = star->fact.cols;
+    int64_t max_rows = 0;
+    for (int k = 0; k < star->n_dims; ++k) {
+      const lq_mat& d = star->dims[k];
+      pa.D[k] = static_cast<const float*>(d.data); pa.out[k] = static_cast<uint8_t*>(tables[k]);
+      pa.ldd[k] = d.ld; pa.rows[k] = d.rows; pa.col_off[k] = o; pa.cols[k] = d.cols;
+      max_rows = std::max<int64_t>(max_rows, d.rows);
+      o += d.cols;
+    }
+    const int64_t rows_per_block = 4 * std::max<int64_t>(4, t.p / 8);
+    const int64_t blocks = std::max<int64_t>(1, std::min<int64_t>((max_rows + rows_per_block - 1) / rows_per_block,
+                                                                  static_cast<int64_t>(num_cus()) * 8));
+    const dim3 grid(static_cast<unsigned>(blocks), static_cast<unsigned>((t.ld + 63) / 64), static_cast<unsigned>(star->n_dims)), block(256);
+    if (t.p <= 64) hipLaunchKernelGGL(tree_project_bits_kernel<1>, grid, block, 0, s, t, pa);
+    else if (t.p <= 128) hipLaunchKernelGGL(tree_project_bits_kernel<2>, grid, block, 0, s, t, pa);
+    else hipLaunchKernelGGL(tree_project_bits_kernel<4>, grid, block, 0, s, t, pa);
+    LQ_LAUNCH_CHECK("tree_project_bits_kernel");
   }
   return LQ_OK;
 }
