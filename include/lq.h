@@ -300,33 +300,49 @@ int lq_fused_join_tree(const lq_star* star, const lq_tree* tree, const void* con
                        void* ws, size_t ws_bytes, void* hip_stream);
 
 /*
- * Leaf masks: a compressed form of the pre-fused tables of Eq. 2, for stars whose fact table has
- * no columns of its own (the setting of Section 3.3.2: every feature lives in a dimension table).
+ * Leaf masks: a compressed form of the pre-fused tables of Eq. 2 (Section 3.3.2).
  * The agreement count of a dimension for (row r, leaf j) never exceeds the number of nodes that
- * dimension owns on the path to j, and the counts of all dimensions add up to the path length
+ * dimension owns on the path to j, and the counts of all owners add up to the path length
  * exactly when each one reaches that maximum.  Bit j of row r of masks[k] says "entry [r][j] of
  * tables[k] equals the number of nodes dimension k owns on the path to leaf j"; the sum over the
  * dimensions followed by `== h` is then a bitwise AND of one mask row per dimension, and the join
  * stage gathers l / 8 bytes per dimension instead of l.
  *   lq_tree_mask_words(l)   words (uint64) per mask row: ceil(l / 64); bits past l are 0
  *   tables  as written by lq_tree_project_dims;  masks  host array of K device pointers,
- *           r_k * words uint64 each;  star->dims gives r_k and c_k (data is not read), star->fact.cols
- *           must be 0 (LQ_ERR_UNSUPPORTED otherwise)
+ *           r_k * words uint64 each;  star->dims gives r_k and c_k, star->fact.cols the number of
+ *           joined columns before the first dimension's (no data is read through star)
  */
 int64_t lq_tree_mask_words(int32_t n_leaves);
 int lq_tree_compress_tables(const lq_star* star, const lq_tree* tree, const void* const* tables,
                             uint64_t* const* masks, void* hip_stream);
 
 /*
+ * Nodes that test the fact table's own columns (feature < c_f) cannot be folded into a table before
+ * the join.  In the mask form each of them becomes two mask rows - the leaves that stay possible
+ * when its test is true (all whose path does not want it false) and when it is false - and the join
+ * stage evaluates the test on the fact row and ANDs the row that applies: the part of (T F > v) H
+ * that Eq. 2 leaves to the join-computation stage, in the same AND form as the tables.
+ *   lq_tree_fact_mask_bytes(p, l)   size of the device buffer (16-byte aligned) that holds them
+ *   lq_tree_fact_masks              fills it from feature, threshold and H (no fact data is read);
+ *                                   valid for any star with this tree and this c_f
+ */
+int64_t lq_tree_fact_mask_bytes(int32_t n_nodes, int32_t n_leaves);
+int lq_tree_fact_masks(int32_t c_f, const lq_tree* tree, void* fact_masks, void* hip_stream);
+
+/*
  * Join-computation stage of Eq. 2 on the leaf masks: per fact row the AND of one mask row per
- * dimension; leaf = position of its lowest set bit (-1 if it is zero), onehot = its bits as bytes.
- * Results are identical to lq_fused_join_tree.  leaf / onehot as there; star->fact.cols must be 0.
+ * dimension and, when the fact table has columns, of one row per node that tests them; leaf =
+ * position of the lowest set bit (-1 if none is set), onehot = the bits as bytes.
+ * Results are identical to lq_fused_join_tree.  leaf / onehot as there.
+ * fact_masks: the buffer written by lq_tree_fact_masks when star->fact.cols > 0 (star->fact is then
+ * read, f32), ignored otherwise (may be NULL).
  * star->dims is optional: when given, only dims[k].rows is read (the number of rows of masks[k]),
  * and mask tables that fit are kept in LDS for the call (it must then not be smaller than any key).
  * flags must be 0: the call has no workspace, LQ_CHECK_FKS returns LQ_ERR_UNSUPPORTED.
  */
 int lq_fused_join_tree_masks(const lq_star* star, const lq_tree* tree, const uint64_t* const* masks,
-                             int32_t* leaf, uint8_t* onehot, uint32_t flags, void* hip_stream);
+                             const void* fact_masks, int32_t* leaf, uint8_t* onehot, uint32_t flags,
+                             void* hip_stream);
 
 /*
  * Non-fused tree pipeline in the matrix form of Section 3.3.1: T is written to the workspace chunk

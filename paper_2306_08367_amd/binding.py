@@ -138,7 +138,11 @@ def _load():
     lib.lq_tree_mask_words.restype = i64
     lib.lq_tree_compress_tables.argtypes = [ps, pt, ctypes.POINTER(vp), ctypes.POINTER(vp), vp]
     lib.lq_tree_compress_tables.restype = ctypes.c_int
-    lib.lq_fused_join_tree_masks.argtypes = [ps, pt, ctypes.POINTER(vp), vp, vp, u32, vp]
+    lib.lq_tree_fact_mask_bytes.argtypes = [i32, i32]
+    lib.lq_tree_fact_mask_bytes.restype = i64
+    lib.lq_tree_fact_masks.argtypes = [i32, pt, vp, vp]
+    lib.lq_tree_fact_masks.restype = ctypes.c_int
+    lib.lq_fused_join_tree_masks.argtypes = [ps, pt, ctypes.POINTER(vp), vp, vp, vp, u32, vp]
     lib.lq_fused_join_tree_masks.restype = ctypes.c_int
     lib.lq_tree_workspace_bytes.argtypes = [ps, pt, i64]
     lib.lq_tree_workspace_bytes.restype = sz
@@ -449,13 +453,13 @@ def lq_tree_mask_words(n_leaves: int) -> int:
     return int(_lib.lq_tree_mask_words(n_leaves))
 
 
-def lq_tree_compress_tables(dims: Sequence[torch.Tensor], tables, feature, threshold, H, stream=None):
+def lq_tree_compress_tables(dims: Sequence[torch.Tensor], tables, feature, threshold, H, c_f: int = 0, stream=None):
     """Leaf masks (int64 bit patterns [r_k x words] per dimension) of pre-fused tree tables."""
     tree = _tree(feature, threshold, H)
     words = lq_tree_mask_words(tree.n_leaves)
     dev = H.device
     masks = [torch.empty((d.shape[0], words), dtype=torch.int64, device=dev) for d in dims]
-    fact = lq_mat(None, 0, 0, 1, LQ_F32)
+    fact = lq_mat(None, 0, int(c_f), max(int(c_f), 1), LQ_F32)
     dims_arr = _mat_array(dims)
     star = lq_star(0, fact, len(dims), dims_arr, _ptr_array([None] * len(dims)))
     _check(_lib.lq_tree_compress_tables(ctypes.byref(star), ctypes.byref(tree), _ptr_array(tables), _ptr_array(masks),
@@ -463,19 +467,34 @@ def lq_tree_compress_tables(dims: Sequence[torch.Tensor], tables, feature, thres
     return masks
 
 
-def lq_fused_join_tree_masks(fks: Sequence[torch.Tensor], masks, feature, threshold, H, want_leaf: bool = True,
-                             want_onehot: bool = False, flags: int = 0, stream=None):
-    """The join stage on leaf masks: same results as lq_fused_join_tree."""
+def lq_tree_fact_mask_bytes(n_nodes: int, n_leaves: int) -> int:
+    return int(_lib.lq_tree_fact_mask_bytes(n_nodes, n_leaves))
+
+
+def lq_tree_fact_masks(c_f: int, feature, threshold, H, stream=None):
+    """Packed mask rows (opaque uint8 buffer) of the nodes that test the fact table's own columns."""
     tree = _tree(feature, threshold, H)
-    n = _n_of(None, fks)
+    buf = torch.empty((lq_tree_fact_mask_bytes(tree.n_nodes, tree.n_leaves),), dtype=torch.uint8, device=H.device)
+    _check(_lib.lq_tree_fact_masks(int(c_f), ctypes.byref(tree), buf.data_ptr(), _stream(stream)))
+    return buf
+
+
+def lq_fused_join_tree_masks(fks: Sequence[torch.Tensor], masks, feature, threshold, H, want_leaf: bool = True,
+                             want_onehot: bool = False, flags: int = 0, stream=None,
+                             X: Optional[torch.Tensor] = None, fact_masks: Optional[torch.Tensor] = None):
+    """The join stage on leaf masks: same results as lq_fused_join_tree.  X / fact_masks: the fact
+    table's own columns and the buffer of lq_tree_fact_masks, when the tree tests such columns."""
+    tree = _tree(feature, threshold, H)
+    n = _n_of(X, fks)
     dev = H.device
     leaf = torch.empty((n,), dtype=torch.int32, device=dev) if want_leaf else None
     onehot = torch.empty((n, tree.n_leaves), dtype=torch.uint8, device=dev) if want_onehot else None
-    star = _Star(n, None, None, fks)
+    star = _Star(n, X, None, fks)
     # row counts of the mask tables (the library may then keep small tables in LDS); no data pointers
     rows_arr = (lq_mat * max(1, len(masks)))(*[lq_mat(None, int(m.shape[0]), 1, 1, LQ_F32) for m in masks])
     star.c.dims = rows_arr
     _check(_lib.lq_fused_join_tree_masks(ctypes.byref(star.c), ctypes.byref(tree), _ptr_array(masks),
+                                         None if fact_masks is None else fact_masks.data_ptr(),
                                          None if leaf is None else leaf.data_ptr(),
                                          None if onehot is None else onehot.data_ptr(), flags, _stream(stream)))
     return leaf, onehot

@@ -492,6 +492,68 @@ __global__ __launch_bounds__(256) void tree_compress_kernel(TreeArgs t, Compress
   }
 }
 
+// Nodes that test the fact table's own columns have no table to be folded into: their outcome is
+// known only per fact row.  For such a node two mask rows say which leaves stay possible when the
+// test comes out true (every leaf whose path does not need it false) and when it comes out false;
+// the join stage evaluates the node on the fact row and ANDs the row that applies.  The nodes are
+// packed (tree order) into one buffer: count, column and threshold per node, then the mask pairs.
+struct FactSide {
+  const float* X;               // NULL: the fact table has no columns
+  int64_t ldx;
+  int32_t c_f, vec_x;           // vec_x: rows of X can be read as 16-byte pieces
+  const int32_t* cnt;
+  const int32_t* feat;
+  const float* thr;
+  const u64* tf;                // [(node * words + w) * 2 + {0: test true, 1: test false}]
+};
+struct FactBuf { int32_t* cnt; int32_t* feat; float* thr; u64* tf; };
+FactBuf fact_buf(void* p, int32_t n_nodes) {
+  char* b = static_cast<char*>(p);
+  return FactBuf{reinterpret_cast<int32_t*>(b), reinterpret_cast<int32_t*>(b + 16),
+                 reinterpret_cast<float*>(b + 16 + 4 * static_cast<size_t>(n_nodes)),
+                 reinterpret_cast<u64*>(b + round_up(16 + 8 * static_cast<size_t>(n_nodes), 16))};
+}
+
+// Workgroup = 16 consecutive nodes, wavefront = 4 of them, lane = leaf of the current mask word.
+// The position of a fact-owned node in the packed list is the number of such nodes before it.
+__global__ __launch_bounds__(256) void tree_fact_masks_kernel(TreeArgs t, int32_t c_f, int32_t words, FactBuf out) {
+  __shared__ int part[4];
+  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+  const int q_lo = 16 * blockIdx.x;
+  int before = 0;
+  for (int q = threadIdx.x; q < q_lo; q += 256) before += t.feature[q] < c_f ? 1 : 0;
+#pragma unroll
+  for (int m = 32; m; m >>= 1) before += __shfl_xor(before, m, 64);
+  if (lane == 0) part[wave] = before;
+  __syncthreads();
+  const int base = part[0] + part[1] + part[2] + part[3];
+  const bool owned = lane < 16 && q_lo + lane < t.p && t.feature[q_lo + lane] < c_f;
+  const unsigned int chunk = static_cast<unsigned int>(__ballot(owned));     // bit i: node q_lo + i is the fact table's
+  if (blockIdx.x == gridDim.x - 1 && threadIdx.x == 0) *out.cnt = base + __builtin_popcount(chunk);
+  if (((chunk >> (4 * wave)) & 0xfu) == 0u) return;
+  for (int w = 0; w < words; ++w) {
+    const int j = 64 * w + lane;
+    int h[4];
+#pragma unroll
+    for (int e = 0; e < 4; ++e) {
+      const int q = q_lo + 4 * wave + e;
+      h[e] = (q < t.p && j < t.l) ? t.H[static_cast<int64_t>(q) * t.l + j] : 0;
+    }
+#pragma unroll
+    for (int e = 0; e < 4; ++e) {
+      const int i = 4 * wave + e;
+      const u64 when_true = __ballot(j < t.l && h[e] >= 0), when_false = __ballot(j < t.l && h[e] <= 0);
+      if (((chunk >> i) & 1u) && lane == 0) {
+        const int pos = base + __builtin_popcount(chunk & ((1u << i) - 1u));
+        const int64_t o = (static_cast<int64_t>(pos) * words + w) * 2;
+        out.tf[o] = when_true;
+        out.tf[o + 1] = when_false;
+        if (w == 0) { out.feat[pos] = t.feature[q_lo + i]; out.thr[pos] = t.thr[q_lo + i]; }
+      }
+    }
+  }
+}
+
 struct MaskJoinArgs {
   int64_t n;
   int32_t K, l, words;
@@ -500,7 +562,59 @@ struct MaskJoinArgs {
   int32_t* leaf;
   uint8_t* onehot;
   int32_t onehot_vec;       // whole 16-byte stores of one-hot rows are legal (l % 16 == 0, aligned)
+  FactSide f;
 };
+
+// The fact columns of R rows: in registers when there are at most eight of them (the node's column
+// is then picked with selects, the column number being the same for every lane), else re-read per node.
+constexpr int FACT_REG_COLS = 8;
+template <int R>
+struct FactRows {
+  float x[R][FACT_REG_COLS];
+  const float* ptr[R];
+};
+template <int R>
+__device__ __forceinline__ void fact_rows_load(const FactSide& fs, const int64_t (&row)[R], FactRows<R>& fr) {
+  typedef float v4f __attribute__((ext_vector_type(4)));
+#pragma unroll
+  for (int u = 0; u < R; ++u) {
+    fr.ptr[u] = fs.X + row[u] * fs.ldx;
+    if (fs.c_f <= FACT_REG_COLS) {
+      if (fs.vec_x) {
+#pragma unroll
+        for (int c4 = 0; c4 < FACT_REG_COLS / 4; ++c4) {
+          const v4f v = 4 * c4 < fs.c_f ? *reinterpret_cast<const v4f*>(fr.ptr[u] + 4 * c4) : v4f{0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+          for (int d = 0; d < 4; ++d) fr.x[u][4 * c4 + d] = v[d];
+        }
+      } else {
+#pragma unroll
+        for (int c = 0; c < FACT_REG_COLS; ++c) fr.x[u][c] = c < fs.c_f ? fr.ptr[u][c] : 0.f;
+      }
+    }
+  }
+}
+template <int R>
+__device__ __forceinline__ void fact_masks_and(const FactSide& fs, const FactRows<R>& fr, int cnt, int words, int w, u64 (&m)[R]) {
+  for (int q = 0; q < cnt; ++q) {
+    const int f = fs.feat[q];
+    const float v = fs.thr[q];
+    const int64_t o = (static_cast<int64_t>(q) * words + w) * 2;
+    const u64 when_true = fs.tf[o], when_false = fs.tf[o + 1];
+#pragma unroll
+    for (int u = 0; u < R; ++u) {
+      float xv;
+      if (fs.c_f <= FACT_REG_COLS) {
+        xv = fr.x[u][0];
+#pragma unroll
+        for (int c = 1; c < FACT_REG_COLS; ++c) xv = f == c ? fr.x[u][c] : xv;
+      } else {
+        xv = fr.ptr[u][f];
+      }
+      m[u] &= xv > v ? when_true : when_false;
+    }
+  }
+}
 
 // Join stage on the masks.  A thread owns four fact rows (row = 256 wave + 64 u + lane, so that key
 // loads and leaf stores are coalesced) and has all their gathers of one load step in flight at once.
@@ -521,6 +635,15 @@ __global__ __launch_bounds__(256) void fused_tree_mask_kernel(MaskJoinArgs a) {
     const int64_t row = min(row0 + 64 * u + lane, a.n - 1);
 #pragma unroll
     for (int k = 0; k < KK; ++k) key[u][k] = (KT > 0 || k < a.K) ? a.fk[k][row] : 0;
+  }
+  FactRows<R> fr;
+  int fact_nodes = 0;
+  if (a.f.X) {
+    int64_t rows[R];
+#pragma unroll
+    for (int u = 0; u < R; ++u) rows[u] = min(row0 + 64 * u + lane, a.n - 1);
+    fact_rows_load(a.f, rows, fr);
+    fact_nodes = *a.f.cnt;
   }
   int first[R];
   u64 kept[R][WMAX > 0 ? WMAX : 1];
@@ -543,9 +666,17 @@ __global__ __launch_bounds__(256) void fused_tree_mask_kernel(MaskJoinArgs a) {
 #pragma unroll
     for (int e = 0; e < WPL; ++e) {
       const int w = w0 + e;
+      if (fact_nodes > 0) {
+        u64 mm[R];
+#pragma unroll
+        for (int u = 0; u < R; ++u) mm[u] = mv[u][e];
+        fact_masks_and(a.f, fr, fact_nodes, a.words, w, mm);
+#pragma unroll
+        for (int u = 0; u < R; ++u) mv[u][e] = mm[u];
+      }
 #pragma unroll
       for (int u = 0; u < R; ++u) {
-        const u64 m = a.K == 0 ? 0ull : mv[u][e];
+        const u64 m = (a.K == 0 && fact_nodes == 0) ? 0ull : mv[u][e];
         if (first[u] < 0 && m != 0ull) first[u] = 64 * w + __builtin_ctzll(m);
         if constexpr (WMAX > 0) {
 #pragma unroll
@@ -663,6 +794,13 @@ __global__ __launch_bounds__(MLDS_THREADS) void fused_tree_mask_lds_kernel(MaskJ
     const bool more = nbase - R * tid < a.n;             // (uniform over the workgroup)
     v4i nkey[KK];
     load_keys(min(more ? nbase : base, a.n - 1), nkey);   // keys of the next step are in flight during this one
+    FactRows<R> fr;
+    if (a.f.X) {                                          // requested before the mask gathers, used after them
+      int64_t rows[R];
+#pragma unroll
+      for (int u = 0; u < R; ++u) rows[u] = min(base + u, a.n - 1);
+      fact_rows_load(a.f, rows, fr);
+    }
     u64 m[R];
 #pragma unroll
     for (int u = 0; u < R; ++u) m[u] = ~0ull;
@@ -678,6 +816,7 @@ __global__ __launch_bounds__(MLDS_THREADS) void fused_tree_mask_lds_kernel(MaskJ
           for (int u = 0; u < R; ++u) m[u] &= g[key[k][u]];
         }
       }
+    if (a.f.X) fact_masks_and(a.f, fr, *a.f.cnt, 1, 0, m);
     v4i lf;
 #pragma unroll
     for (int u = 0; u < R; ++u) lf[u] = m[u] != 0ull ? __builtin_ctzll(m[u]) : -1;
@@ -973,13 +1112,12 @@ int lq_tree_compress_tables(const lq_star* star, const lq_tree* tree, const void
   int rc = check_star_basic(star, false);
   if (rc) return rc;
   if ((rc = check_tree(tree, &t))) return rc;
-  if (star->fact.cols > 0) return fail(LQ_ERR_UNSUPPORTED, "leaf masks need a fact table without columns of its own");
   if (star->n_dims > 0 && (!tables || !masks || !star->dims)) return fail(LQ_ERR_NULL, "tables, masks or star->dims is NULL");
   const int32_t words = static_cast<int32_t>(lq_tree_mask_words(t.l));
   hipStream_t s = static_cast<hipStream_t>(hip_stream);
   if (star->n_dims == 0) return LQ_OK;
   CompressArgs ca{};
-  int32_t off = 0;
+  int32_t off = star->fact.cols;
   int64_t max_rows = 0;
   for (int k = 0; k < star->n_dims; ++k) {
     const lq_mat& d = star->dims[k];
@@ -1000,8 +1138,29 @@ int lq_tree_compress_tables(const lq_star* star, const lq_tree* tree, const void
   return LQ_OK;
 }
 
+int64_t lq_tree_fact_mask_bytes(int32_t n_nodes, int32_t n_leaves) {
+  if (n_nodes < 1 || n_leaves < 1) return 0;
+  return static_cast<int64_t>(round_up(16 + 8 * static_cast<size_t>(n_nodes), 16)) +
+         static_cast<int64_t>(n_nodes) * lq_tree_mask_words(n_leaves) * 16;
+}
+
+int lq_tree_fact_masks(int32_t c_f, const lq_tree* tree, void* fact_masks, void* hip_stream) {
+  clear_error();
+  TreeArgs t{};
+  int rc = check_tree(tree, &t);
+  if (rc) return rc;
+  if (c_f < 0) return fail(LQ_ERR_SHAPE, "c_f < 0");
+  if (!fact_masks || !aligned(fact_masks, 16)) return fail(LQ_ERR_NULL, "fact_masks is NULL or misaligned");
+  const int32_t words = static_cast<int32_t>(lq_tree_mask_words(t.l));
+  hipLaunchKernelGGL(tree_fact_masks_kernel, dim3(static_cast<unsigned>((t.p + 15) / 16)), dim3(256), 0,
+                     static_cast<hipStream_t>(hip_stream), t, c_f, words, fact_buf(fact_masks, t.p));
+  LQ_LAUNCH_CHECK("tree_fact_masks_kernel");
+  return LQ_OK;
+}
+
 int lq_fused_join_tree_masks(const lq_star* star, const lq_tree* tree, const uint64_t* const* masks,
-                             int32_t* leaf, uint8_t* onehot, uint32_t flags, void* hip_stream) {
+                             const void* fact_masks, int32_t* leaf, uint8_t* onehot, uint32_t flags,
+                             void* hip_stream) {
   clear_error();
   if (flags & LQ_CHECK_FKS)
     return fail(LQ_ERR_UNSUPPORTED, "this call has no workspace for LQ_CHECK_FKS: check the keys with lq_fused_join_tree or map them with the key map");
@@ -1009,7 +1168,6 @@ int lq_fused_join_tree_masks(const lq_star* star, const lq_tree* tree, const uin
   int rc = check_star_basic(star, false);
   if (rc) return rc;
   if ((rc = check_tree(tree, &t))) return rc;
-  if (star->fact.cols > 0) return fail(LQ_ERR_UNSUPPORTED, "leaf masks need a fact table without columns of its own");
   if (star->n_dims > 0 && (!masks || !star->fks)) return fail(LQ_ERR_NULL, "masks or fks is NULL");
   if (!leaf && !onehot) return fail(LQ_ERR_NULL, "neither leaf nor onehot requested");
   if (leaf && !aligned(leaf, 4)) return fail(LQ_ERR_SHAPE, "leaf is misaligned");
@@ -1023,6 +1181,16 @@ int lq_fused_join_tree_masks(const lq_star* star, const lq_tree* tree, const uin
   }
   a.leaf = leaf; a.onehot = onehot;
   a.onehot_vec = onehot && aligned(onehot, 16) && t.l % 16 == 0;
+  if (star->fact.cols > 0) {
+    const lq_mat& x = star->fact;
+    if (!fact_masks || !aligned(fact_masks, 16))
+      return fail(LQ_ERR_NULL, "the fact table has columns: fact_masks (from lq_tree_fact_masks) is NULL or misaligned");
+    if (x.ld < x.cols || (a.n > 0 && (!x.data || !aligned(x.data, 4)))) return fail(LQ_ERR_SHAPE, "fact is malformed");
+    const FactBuf fb = fact_buf(const_cast<void*>(fact_masks), t.p);
+    a.f.X = static_cast<const float*>(x.data); a.f.ldx = x.ld; a.f.c_f = x.cols;
+    a.f.vec_x = (aligned(x.data, 16) && x.ld % 4 == 0 && x.cols % 4 == 0) ? 1 : 0;
+    a.f.cnt = fb.cnt; a.f.feat = fb.feat; a.f.thr = fb.thr; a.f.tf = fb.tf;
+  }
   if (a.n == 0) return LQ_OK;
   hipStream_t s = static_cast<hipStream_t>(hip_stream);
   if (a.words == 1 && !onehot && star->dims && a.K >= 1 && a.K <= 4 && a.n >= (1 << 20)) {

@@ -45,6 +45,11 @@ CASES = [
     ("very_wide_1500", 1_025, 0, (120, 90), (32, 32), 1_500),
     ("wide_600_three_tables", 777, 0, (1_000, 37, 300), (20, 30, 10), 600),
     ("fact_columns", 2_500, 3, (40, 60), (4, 4), 24),
+    ("fact_columns_4_aligned", 5_111, 4, (40, 60, 25), (4, 4, 3), 64),
+    ("fact_columns_8_wide_tree", 3_001, 8, (90, 60), (6, 6), 200),
+    ("fact_columns_12", 2_777, 12, (50,), (8,), 48),
+    ("fact_columns_5_very_wide_tree", 1_333, 5, (70, 30), (10, 10), 700),
+    ("fact_columns_only", 4_321, 6, (), (), 40),
     ("one_row", 1, 0, (5,), (3,), 4),
 ]
 
@@ -74,8 +79,36 @@ def test_tree_paths_match_oracle(lq, case):
     np.testing.assert_array_equal(m_leaf.cpu().numpy(), leaf)
     np.testing.assert_array_equal(m_oh.cpu().numpy(), onehot)
     assert (onehot.sum(axis=1) == 1).all()
-    if c_f == 0:
-        _check_masks(lq, w, tree, tables, Tk, leaf, onehot)
+    _check_masks(lq, w, tree, tables, Tk, leaf, onehot)
+
+
+def _fact_side(lq, w, tree):
+    """Keyword arguments for the join on the masks when the fact table has columns, after checking the
+    packed buffer: count, column, threshold and the two mask rows of every node that tests a fact column
+    (test true: the leaves whose path does not want it false; test false: those that do not want it true)."""
+    if w.c_f == 0:
+        return {}
+    f, t, H = tree.feature.cuda(), tree.threshold.cuda(), tree.H.cuda()
+    buf = lq.lq_tree_fact_masks(w.c_f, f, t, H)
+    torch.cuda.synchronize()
+    Hn = tree.H.numpy().astype(np.int64)
+    feat = tree.feature.numpy()
+    p, leaves = Hn.shape
+    words = lq.lq_tree_mask_words(leaves)
+    assert buf.numel() == lq.lq_tree_fact_mask_bytes(p, leaves)
+    raw = buf.cpu().numpy()
+    nodes = np.flatnonzero(feat < w.c_f)
+    assert int(raw[:4].view(np.int32)[0]) == len(nodes)
+    np.testing.assert_array_equal(raw[16:16 + 4 * p].view(np.int32)[:len(nodes)], feat[nodes])
+    np.testing.assert_array_equal(raw[16 + 4 * p:16 + 8 * p].view(np.float32)[:len(nodes)], tree.threshold.numpy()[nodes])
+    start = (16 + 8 * p + 15) // 16 * 16
+    got = raw[start:start + 16 * words * len(nodes)].view(np.uint64).reshape(len(nodes), words, 2)
+    for which, keep in ((0, Hn[nodes] >= 0), (1, Hn[nodes] <= 0)):
+        padded = np.zeros((len(nodes), words * 64), dtype=np.uint8)
+        padded[:, :leaves] = keep
+        want = np.packbits(padded.reshape(-1, words, 64), axis=2, bitorder="little").view(np.uint64).reshape(-1, words)
+        np.testing.assert_array_equal(got[:, :, which], want)
+    return {"X": w.X, "fact_masks": buf}
 
 
 def _check_masks(lq, w, tree, tables, Tk, leaf, onehot):
@@ -86,11 +119,12 @@ def _check_masks(lq, w, tree, tables, Tk, leaf, onehot):
     feat = tree.feature.numpy()
     leaves = Hn.shape[1]
     words = lq.lq_tree_mask_words(leaves)
-    masks = lq.lq_tree_compress_tables(w.dims, tables, f, t, H)
-    g_leaf, g_oh = lq.lq_fused_join_tree_masks(w.fks, masks, f, t, H, want_onehot=True)
-    g_leaf_only, none = lq.lq_fused_join_tree_masks(w.fks, masks, f, t, H)
+    masks = lq.lq_tree_compress_tables(w.dims, tables, f, t, H, c_f=w.c_f)
+    fact = _fact_side(lq, w, tree)
+    g_leaf, g_oh = lq.lq_fused_join_tree_masks(w.fks, masks, f, t, H, want_onehot=True, **fact)
+    g_leaf_only, none = lq.lq_fused_join_tree_masks(w.fks, masks, f, t, H, **fact)
     torch.cuda.synchronize()
-    off = 0
+    off = w.c_f
     for k, d in enumerate(w.dims):
         own = (feat >= off) & (feat < off + d.shape[1])
         neg = (Hn[own] == -1).sum(axis=0)
@@ -189,3 +223,36 @@ def test_tree_full_size_setting1_shape(lq):
     _, _, want = O.tree_predict(None, sub.dims, sub.fks, tree.feature, tree.threshold, tree.H)
     np.testing.assert_array_equal(leaf[rows.cuda()].cpu().numpy(), want)
     assert len(np.unique(want)) > 20                      # the rows really spread over the leaves
+
+
+@pytest.mark.parametrize("c_f,padded", [(4, False), (5, False), (3, True), (12, True)], ids=["cf4", "cf5", "cf3_strided", "cf12_strided"])
+def test_masks_with_fact_columns_at_a_size_that_keeps_tables_in_lds(lq, c_f, padded):
+    """Above 2^20 fact rows the mask join keeps small tables in LDS; here with nodes on the fact
+    table's own columns as well (register and re-read forms, contiguous and strided X)."""
+    n = (1 << 20) + 4_099
+    w, tree = _case("masks_lds_fact", n, c_f, (3_000, 500, 40_000), (5, 4, 6), 64, WL.SEED0 + 610 + c_f)
+    _, _, leaf = O.tree_predict(w.X, w.dims, w.fks, tree.feature, tree.threshold, tree.H)
+    w = to_dev(w)
+    if padded:                                            # rows of X 4 (c_f + 3) bytes apart: not 16-byte pieces
+        wide = torch.zeros((n, c_f + 3), device="cuda")
+        wide[:, :c_f] = w.X
+        w.X = wide[:, :c_f]
+    f, t, H = tree.feature.cuda(), tree.threshold.cuda(), tree.H.cuda()
+    tables, target = lq.lq_tree_project_dims(w.dims, c_f, f, t, H)
+    masks = lq.lq_tree_compress_tables(w.dims, tables, f, t, H, c_f=c_f)
+    fact = _fact_side(lq, w, tree)
+    got, _ = lq.lq_fused_join_tree_masks(w.fks, masks, f, t, H, **fact)
+    torch.cuda.synchronize()
+    np.testing.assert_array_equal(got.cpu().numpy(), leaf)
+    assert len(np.unique(leaf)) > 20
+
+
+def test_masks_need_the_fact_side_when_the_fact_table_has_columns(lq):
+    w, tree = _case("masks_no_fact_side", 1_000, 2, (30,), (4,), 8, WL.SEED0 + 620)
+    w = to_dev(w)
+    f, t, H = tree.feature.cuda(), tree.threshold.cuda(), tree.H.cuda()
+    tables, _ = lq.lq_tree_project_dims(w.dims, 2, f, t, H)
+    masks = lq.lq_tree_compress_tables(w.dims, tables, f, t, H, c_f=2)
+    with pytest.raises(lq.LQError) as e:
+        lq.lq_fused_join_tree_masks(w.fks, masks, f, t, H, X=w.X)
+    assert e.value.status == "LQ_ERR_NULL"

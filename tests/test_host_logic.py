@@ -178,17 +178,24 @@ def test_tree_entry_points_reject_bad_arguments():
     assert lib.lq_materialized_join_tree(ctypes.byref(star), ctypes.byref(tree), FAKE, None, FAKE, 1024, 0,
                                          None) == 4
     assert lib.lq_tree_workspace_bytes(ctypes.byref(star), ctypes.byref(tree), 256) >= 256 * 5 * 4
-    # leaf masks: word count; a fact table with columns of its own is refused; missing arguments
+    # leaf masks: word count; size of the fact-side buffer (header 16 B, column + threshold per node,
+    # rounded to 16, then two words per node and mask word); missing or misaligned arguments
     assert b.lq_tree_mask_words(1) == 1 and b.lq_tree_mask_words(64) == 1 and b.lq_tree_mask_words(65) == 2
     assert b.lq_tree_mask_words(0) == 0
+    assert b.lq_tree_fact_mask_bytes(3, 4) == 48 + 3 * 16 and b.lq_tree_fact_mask_bytes(63, 65) == 528 + 63 * 32
+    assert b.lq_tree_fact_mask_bytes(0, 4) == 0
+    assert lib.lq_tree_fact_masks(-1, ctypes.byref(tree), FAKE, None) == 2
+    assert lib.lq_tree_fact_masks(2, ctypes.byref(tree), None, None) == 1
+    assert lib.lq_tree_fact_masks(2, ctypes.byref(tree), FAKE + 8, None) == 1
     masks = (ctypes.c_void_p * 1)(FAKE)
-    assert lib.lq_tree_compress_tables(ctypes.byref(star), ctypes.byref(tree), tables, masks, None) == 6
-    assert lib.lq_fused_join_tree_masks(ctypes.byref(star), ctypes.byref(tree), masks, FAKE, None, 0, None) == 6
+    # a fact table with columns of its own needs the fact-side buffer
+    assert lib.lq_fused_join_tree_masks(ctypes.byref(star), ctypes.byref(tree), masks, None, FAKE, None, 0, None) == 1
+    assert lib.lq_fused_join_tree_masks(ctypes.byref(star), ctypes.byref(tree), masks, FAKE + 8, FAKE, None, 0, None) == 1
     star0, _, keep0 = _star_model(b, c_f=0)
     assert lib.lq_tree_compress_tables(ctypes.byref(star0), ctypes.byref(tree), tables, None, None) == 1
-    assert lib.lq_fused_join_tree_masks(ctypes.byref(star0), ctypes.byref(tree), masks, None, None, 0, None) == 1
+    assert lib.lq_fused_join_tree_masks(ctypes.byref(star0), ctypes.byref(tree), masks, None, None, None, 0, None) == 1
     odd = (ctypes.c_void_p * 1)(FAKE + 4)
-    assert lib.lq_fused_join_tree_masks(ctypes.byref(star0), ctypes.byref(tree), odd, FAKE, None, 0, None) == 1
+    assert lib.lq_fused_join_tree_masks(ctypes.byref(star0), ctypes.byref(tree), odd, None, FAKE, None, 0, None) == 1
 
 
 def test_keymap_entry_points_reject_bad_arguments():
