@@ -392,6 +392,25 @@ def main():
                                                          "unit": "GB/s", "frac": kgbps / HBM_PEAK_GBPS,
                                                          "algorithmic_bytes_per_row": 16}}}
         del wt, tables, masks
+        # the same tree size with 8 of the 128 joined columns in the fact table itself: their nodes are
+        # evaluated per fact row in the join stage
+        wf = WL.make_predict("tree_s1_sf8_fact", nt, 8, (80_000, 16_000, 2_555), (40, 40, 40), (1,),
+                             seed=WL.SEED0 + 702, device=dev)
+        tables, target = lq.lq_tree_project_dims(wf.dims, 8, tf, tt, tH)
+        masks = lq.lq_tree_compress_tables(wf.dims, tables, tf, tt, tH, c_f=8)
+        fmask = lq.lq_tree_fact_masks(8, tf, tt, tH)
+        fcnt = int(fmask[:4].view(torch.int32).item())
+        fms, _, _ = time_call(lambda: lq.lq_fused_join_tree(wf.X, wf.fks, tables, target, tf, tt, tH), 5, 1)
+        fkms = graph_time(lambda: lq.lq_fused_join_tree_masks(wf.fks, masks, tf, tt, tH, X=wf.X, fact_masks=fmask))
+        fmms, _, _ = time_call(lambda: lq.lq_materialized_join_tree(wf.X, wf.dims, wf.fks, tf, tt, tH,
+                                                                    chunk_rows=1 << 20), 2, 1)
+        fgbps = 48.0 * nt / (fkms * 1e-3) / 1e9
+        out["fused_tree"]["with_fact_columns"] = {
+            "fact_cols": 8, "nodes_on_fact_cols": fcnt, "byte_tables_ms": fms, "leaf_masks_ms_in_a_graph": fkms,
+            "materialized_ms": fmms, "fused_speedup_join_stage": fmms / fkms,
+            "roofline": {"bound": "hbm", "achieved": fgbps, "peak": HBM_PEAK_GBPS, "unit": "GB/s",
+                         "frac": fgbps / HBM_PEAK_GBPS, "algorithmic_bytes_per_row": 48}}
+        del wf, tables, masks, fmask
 
     # ---------------------------------------------------------------- trees of growing size (only on request)
     # cardinality settings 1 (large dimension tables, sf 4) and 2 (small ones), leaves 8 .. 2,048:

@@ -568,51 +568,69 @@ struct MaskJoinArgs {
 // The fact columns of R rows: in registers when there are at most eight of them (the node's column
 // is then picked with selects, the column number being the same for every lane), else re-read per node.
 constexpr int FACT_REG_COLS = 8;
+typedef float v4f __attribute__((ext_vector_type(4)));
 template <int R>
 struct FactRows {
-  float x[R][FACT_REG_COLS];
+  v4f lo[R], hi[R];             // columns 0..3 and 4..7
   const float* ptr[R];
 };
 template <int R>
 __device__ __forceinline__ void fact_rows_load(const FactSide& fs, const int64_t (&row)[R], FactRows<R>& fr) {
-  typedef float v4f __attribute__((ext_vector_type(4)));
 #pragma unroll
   for (int u = 0; u < R; ++u) {
-    fr.ptr[u] = fs.X + row[u] * fs.ldx;
+    const float* p = fs.X + row[u] * fs.ldx;
+    fr.ptr[u] = p;
+    v4f lo = {0.f, 0.f, 0.f, 0.f}, hi = {0.f, 0.f, 0.f, 0.f};
     if (fs.c_f <= FACT_REG_COLS) {
       if (fs.vec_x) {
-#pragma unroll
-        for (int c4 = 0; c4 < FACT_REG_COLS / 4; ++c4) {
-          const v4f v = 4 * c4 < fs.c_f ? *reinterpret_cast<const v4f*>(fr.ptr[u] + 4 * c4) : v4f{0.f, 0.f, 0.f, 0.f};
-#pragma unroll
-          for (int d = 0; d < 4; ++d) fr.x[u][4 * c4 + d] = v[d];
-        }
+        lo = *reinterpret_cast<const v4f*>(p);
+        if (fs.c_f > 4) hi = *reinterpret_cast<const v4f*>(p + 4);
       } else {
-#pragma unroll
-        for (int c = 0; c < FACT_REG_COLS; ++c) fr.x[u][c] = c < fs.c_f ? fr.ptr[u][c] : 0.f;
+        lo.x = p[0];
+        if (fs.c_f > 1) lo.y = p[1];
+        if (fs.c_f > 2) lo.z = p[2];
+        if (fs.c_f > 3) lo.w = p[3];
+        if (fs.c_f > 4) hi.x = p[4];
+        if (fs.c_f > 5) hi.y = p[5];
+        if (fs.c_f > 6) hi.z = p[6];
+        if (fs.c_f > 7) hi.w = p[7];
       }
     }
+    fr.lo[u] = lo;
+    fr.hi[u] = hi;
+  }
+}
+// One fact-side node on R rows: m &= (x[f] > v) ? when_true : when_false.  f is the same for every
+// lane, so the column is picked by a scalar branch rather than by selects.
+template <int R>
+__device__ __forceinline__ void fact_node_and(const FactSide& fs, const FactRows<R>& fr, int f, float v,
+                                              u64 when_true, u64 when_false, u64 (&m)[R]) {
+  auto run = [&](auto pick) {
+#pragma unroll
+    for (int u = 0; u < R; ++u) m[u] &= pick(u) > v ? when_true : when_false;
+  };
+  if (fs.c_f > FACT_REG_COLS) {
+    run([&](int u) { return fr.ptr[u][f]; });
+    return;
+  }
+  switch (f) {
+    case 0: run([&](int u) { return fr.lo[u].x; }); break;
+    case 1: run([&](int u) { return fr.lo[u].y; }); break;
+    case 2: run([&](int u) { return fr.lo[u].z; }); break;
+    case 3: run([&](int u) { return fr.lo[u].w; }); break;
+    case 4: run([&](int u) { return fr.hi[u].x; }); break;
+    case 5: run([&](int u) { return fr.hi[u].y; }); break;
+    case 6: run([&](int u) { return fr.hi[u].z; }); break;
+    default: run([&](int u) { return fr.hi[u].w; }); break;
   }
 }
 template <int R>
 __device__ __forceinline__ void fact_masks_and(const FactSide& fs, const FactRows<R>& fr, int cnt, int words, int w, u64 (&m)[R]) {
   for (int q = 0; q < cnt; ++q) {
-    const int f = fs.feat[q];
+    const int f = __builtin_amdgcn_readfirstlane(fs.feat[q]);
     const float v = fs.thr[q];
     const int64_t o = (static_cast<int64_t>(q) * words + w) * 2;
-    const u64 when_true = fs.tf[o], when_false = fs.tf[o + 1];
-#pragma unroll
-    for (int u = 0; u < R; ++u) {
-      float xv;
-      if (fs.c_f <= FACT_REG_COLS) {
-        xv = fr.x[u][0];
-#pragma unroll
-        for (int c = 1; c < FACT_REG_COLS; ++c) xv = f == c ? fr.x[u][c] : xv;
-      } else {
-        xv = fr.ptr[u][f];
-      }
-      m[u] &= xv > v ? when_true : when_false;
-    }
+    fact_node_and(fs, fr, f, v, fs.tf[o], fs.tf[o + 1], m);
   }
 }
 
@@ -740,9 +758,11 @@ struct MaskLds {
   int32_t off[LQ_MAX_DIMS];     // position of the table in LDS in words, -1 = stays in memory
   int32_t rows[LQ_MAX_DIMS];
   int32_t vec;                  // key columns and leaf are 16-byte aligned: four rows per load / store
+  int32_t fact_off;             // position of the fact-side nodes in LDS in words (three words per node)
 };
 constexpr int MLDS_THREADS = 1024;
-template <int KT>       // number of dimensions, 1..4
+constexpr int FACT_LDS_NODES = 128;    // fact-side nodes kept in LDS; further ones are read from memory per step
+template <int KT, bool FACT>       // KT: number of dimensions, 1..4; FACT: the fact table has columns
 __global__ __launch_bounds__(MLDS_THREADS) void fused_tree_mask_lds_kernel(MaskJoinArgs a, MaskLds L) {
   constexpr int KK = KT, R = 4;
   typedef u64 u64x2 __attribute__((ext_vector_type(2)));
@@ -767,23 +787,37 @@ __global__ __launch_bounds__(MLDS_THREADS) void fused_tree_mask_lds_kernel(MaskJ
       }
       if (tid == 0 && (L.rows[k] & 1)) tab[L.off[k] + L.rows[k] - 1] = a.M[k][L.rows[k] - 1];
     }
+  int fact_nodes = 0;
+  if constexpr (FACT) {
+    fact_nodes = *a.f.cnt;
+    if (tid < min(fact_nodes, FACT_LDS_NODES)) {
+      tab[L.fact_off + 3 * tid] = static_cast<u64>(static_cast<unsigned int>(a.f.feat[tid])) |
+                                  (static_cast<u64>(__float_as_uint(a.f.thr[tid])) << 32);
+      tab[L.fact_off + 3 * tid + 1] = a.f.tf[2 * tid];
+      tab[L.fact_off + 3 * tid + 2] = a.f.tf[2 * tid + 1];
+    }
+  }
   __syncthreads();
-  // every thread takes four consecutive fact rows per step: one 16-byte load per key column, one
-  // 16-byte store of the four leaves (plain loads: streaming hints made this kernel slower)
+  // Without fact columns every thread takes four consecutive fact rows per step: one 16-byte load per
+  // key column, one 16-byte store of the four leaves (plain loads: streaming hints made this kernel
+  // slower).  With fact columns its rows are 64 apart (row = 256 wavefront + 64 u + lane), so that the
+  // lanes of a wavefront read neighbouring rows of X and every cache line of X is fetched once.
   typedef int v4i __attribute__((ext_vector_type(4)));
+  constexpr int RS = FACT ? 64 : 1;                                   // distance between a thread's rows
   const int64_t step = static_cast<int64_t>(gridDim.x) * MLDS_THREADS * R;
-  int64_t base = static_cast<int64_t>(blockIdx.x) * MLDS_THREADS * R + R * tid;
-  if (base - R * tid >= a.n) return;
+  const int in_block = FACT ? 256 * (tid >> 6) + (tid & 63) : R * tid;
+  int64_t base = static_cast<int64_t>(blockIdx.x) * MLDS_THREADS * R + in_block;
+  if (base - in_block >= a.n) return;
   v4i key[KK];
   auto load_keys = [&](int64_t b, v4i (&out)[KK]) {
 #pragma unroll
     for (int k = 0; k < KK; ++k) {
       out[k] = v4i{0, 0, 0, 0};
       if (KT > 0 || k < a.K) {
-        if (L.vec && b + R <= a.n) out[k] = *reinterpret_cast<const v4i*>(a.fk[k] + b);
+        if (!FACT && L.vec && b + R <= a.n) out[k] = *reinterpret_cast<const v4i*>(a.fk[k] + b);
         else {
 #pragma unroll
-          for (int u = 0; u < R; ++u) out[k][u] = a.fk[k][min(b + u, a.n - 1)];
+          for (int u = 0; u < R; ++u) out[k][u] = a.fk[k][min(b + RS * u, a.n - 1)];
         }
       }
     }
@@ -791,14 +825,14 @@ __global__ __launch_bounds__(MLDS_THREADS) void fused_tree_mask_lds_kernel(MaskJ
   load_keys(min(base, a.n - 1), key);
   for (;;) {
     const int64_t nbase = base + step;
-    const bool more = nbase - R * tid < a.n;             // (uniform over the workgroup)
+    const bool more = nbase - in_block < a.n;            // (uniform over the workgroup)
     v4i nkey[KK];
     load_keys(min(more ? nbase : base, a.n - 1), nkey);   // keys of the next step are in flight during this one
     FactRows<R> fr;
-    if (a.f.X) {                                          // requested before the mask gathers, used after them
+    if (FACT && fact_nodes > 0) {                         // requested before the mask gathers, used after them
       int64_t rows[R];
 #pragma unroll
-      for (int u = 0; u < R; ++u) rows[u] = min(base + u, a.n - 1);
+      for (int u = 0; u < R; ++u) rows[u] = min(base + RS * u, a.n - 1);
       fact_rows_load(a.f, rows, fr);
     }
     u64 m[R];
@@ -816,15 +850,28 @@ __global__ __launch_bounds__(MLDS_THREADS) void fused_tree_mask_lds_kernel(MaskJ
           for (int u = 0; u < R; ++u) m[u] &= g[key[k][u]];
         }
       }
-    if (a.f.X) fact_masks_and(a.f, fr, *a.f.cnt, 1, 0, m);
+    if constexpr (FACT) {
+      for (int q = 0; q < fact_nodes; ++q) {
+        u64 ft, when_true, when_false;
+        if (q < FACT_LDS_NODES) {
+          ft = tab[L.fact_off + 3 * q]; when_true = tab[L.fact_off + 3 * q + 1]; when_false = tab[L.fact_off + 3 * q + 2];
+        } else {
+          ft = static_cast<u64>(static_cast<unsigned int>(a.f.feat[q])) | (static_cast<u64>(__float_as_uint(a.f.thr[q])) << 32);
+          when_true = a.f.tf[2 * q]; when_false = a.f.tf[2 * q + 1];
+        }
+        const int f = __builtin_amdgcn_readfirstlane(static_cast<int>(static_cast<unsigned int>(ft)));
+        const float v = __uint_as_float(static_cast<unsigned int>(ft >> 32));
+        fact_node_and(a.f, fr, f, v, when_true, when_false, m);
+      }
+    }
     v4i lf;
 #pragma unroll
     for (int u = 0; u < R; ++u) lf[u] = m[u] != 0ull ? __builtin_ctzll(m[u]) : -1;
-    if (L.vec && base + R <= a.n) *reinterpret_cast<v4i*>(a.leaf + base) = lf;
+    if (!FACT && L.vec && base + R <= a.n) *reinterpret_cast<v4i*>(a.leaf + base) = lf;
     else {
 #pragma unroll
       for (int u = 0; u < R; ++u)
-        if (base + u < a.n) a.leaf[base + u] = lf[u];
+        if (base + RS * u < a.n) a.leaf[base + RS * u] = lf[u];
     }
     if (!more) break;
     base = nbase;
@@ -1217,18 +1264,24 @@ int lq_fused_join_tree_masks(const lq_star* star, const lq_tree* tree, const uin
       if (used > 0) {
         L.vec = aligned(leaf, 16) ? 1 : 0;
         for (int k = 0; k < a.K; ++k) L.vec = (L.vec && aligned(star->fks[k], 16)) ? 1 : 0;
-        const size_t lds = static_cast<size_t>(used) * 8;
+        L.fact_off = static_cast<int32_t>(used);
+        const size_t lds = (static_cast<size_t>(used) + (a.f.X ? 3 * FACT_LDS_NODES : 0)) * 8;
         const int64_t need = (a.n + MLDS_THREADS * 4 - 1) / (MLDS_THREADS * 4);
         const dim3 grid(static_cast<unsigned>(std::min<int64_t>(need, num_cus()))), block(MLDS_THREADS);
-#define LQ_TML(KT_)                                                                                       \
+#define LQ_TML_F(KT_, F_)                                                                                 \
   do {                                                                                                    \
     if (lds > 64 * 1024)                                                                                  \
-      LQ_HIP_TRY(hipFuncSetAttribute(reinterpret_cast<const void*>(&fused_tree_mask_lds_kernel<KT_>),     \
+      LQ_HIP_TRY(hipFuncSetAttribute(reinterpret_cast<const void*>(&fused_tree_mask_lds_kernel<KT_, F_>), \
                                      hipFuncAttributeMaxDynamicSharedMemorySize, static_cast<int>(lds))); \
-    hipLaunchKernelGGL((fused_tree_mask_lds_kernel<KT_>), grid, block, lds, s, a, L);                     \
+    hipLaunchKernelGGL((fused_tree_mask_lds_kernel<KT_, F_>), grid, block, lds, s, a, L);                 \
+  } while (0)
+#define LQ_TML(KT_)                                                                                       \
+  do {                                                                                                    \
+    if (a.f.X) LQ_TML_F(KT_, true); else LQ_TML_F(KT_, false);                                            \
   } while (0)
         if (a.K == 1) LQ_TML(1); else if (a.K == 2) LQ_TML(2); else if (a.K == 3) LQ_TML(3); else LQ_TML(4);
 #undef LQ_TML
+#undef LQ_TML_F
         LQ_LAUNCH_CHECK("fused_tree_mask_lds_kernel");
         return LQ_OK;
       }
