@@ -317,6 +317,18 @@ int lq_tree_compress_tables(const lq_star* star, const lq_tree* tree, const void
                             uint64_t* const* masks, void* hip_stream);
 
 /*
+ * Incremental pre-fusion of the tree tables: recompute rows [first_row, first_row + n_rows) of
+ * tables[dim] - and of masks[dim], when masks is not NULL - after those rows of dimension `dim`
+ * changed (the pre-fused tables are constants only for a period, Section 3.2; refreshing them is
+ * the cost weighed in the discussion of Q8).  Same result as lq_tree_project_dims followed by
+ * lq_tree_compress_tables, restricted to those rows; target and the fact-side masks depend on the
+ * tree alone and stay as they are.  Only entry `dim` of tables / masks is used.
+ */
+int lq_tree_project_dim_rows(const lq_star* star, const lq_tree* tree, void* const* tables,
+                             uint64_t* const* masks, int32_t dim, int64_t first_row, int64_t n_rows,
+                             void* hip_stream);
+
+/*
  * Nodes that test the fact table's own columns (feature < c_f) cannot be folded into a table before
  * the join.  In the mask form each of them becomes two mask rows - the leaves that stay possible
  * when its test is true (all whose path does not want it false) and when it is false - and the join

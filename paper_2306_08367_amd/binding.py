@@ -138,6 +138,8 @@ def _load():
     lib.lq_tree_mask_words.restype = i64
     lib.lq_tree_compress_tables.argtypes = [ps, pt, ctypes.POINTER(vp), ctypes.POINTER(vp), vp]
     lib.lq_tree_compress_tables.restype = ctypes.c_int
+    lib.lq_tree_project_dim_rows.argtypes = [ps, pt, ctypes.POINTER(vp), ctypes.POINTER(vp), i32, i64, i64, vp]
+    lib.lq_tree_project_dim_rows.restype = ctypes.c_int
     lib.lq_tree_fact_mask_bytes.argtypes = [i32, i32]
     lib.lq_tree_fact_mask_bytes.restype = i64
     lib.lq_tree_fact_masks.argtypes = [i32, pt, vp, vp]
@@ -465,6 +467,18 @@ def lq_tree_compress_tables(dims: Sequence[torch.Tensor], tables, feature, thres
     _check(_lib.lq_tree_compress_tables(ctypes.byref(star), ctypes.byref(tree), _ptr_array(tables), _ptr_array(masks),
                                         _stream(stream)))
     return masks
+
+
+def lq_tree_project_dim_rows(dims: Sequence[torch.Tensor], c_f: int, tables, masks, feature, threshold, H,
+                             dim: int, first_row: int, n_rows: int, stream=None) -> None:
+    """Refresh rows [first_row, first_row + n_rows) of tables[dim] (and of masks[dim] unless masks is None) in place."""
+    tree = _tree(feature, threshold, H)
+    fact = lq_mat(None, 0, int(c_f), max(int(c_f), 1), LQ_F32)
+    dims_arr = _mat_array(dims)
+    star = lq_star(0, fact, len(dims), dims_arr, _ptr_array([None] * len(dims)))
+    _check(_lib.lq_tree_project_dim_rows(ctypes.byref(star), ctypes.byref(tree), _ptr_array(tables),
+                                         None if masks is None else _ptr_array(masks), int(dim), int(first_row),
+                                         int(n_rows), _stream(stream)))
 
 
 def lq_tree_fact_mask_bytes(n_nodes: int, n_leaves: int) -> int:

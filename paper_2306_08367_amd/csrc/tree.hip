@@ -931,6 +931,80 @@ int check_star_basic(const lq_star* star, bool need_dims) {
   return LQ_OK;
 }
 
+// Rows of one dimension table (all of them, or the slice an incremental refresh touches) with the
+// place of their pre-fused rows.
+struct DimSlice {
+  const float* D; int64_t ldd, rows;
+  int32_t col_off, cols;
+  uint8_t* out;
+};
+
+int project_slices(const TreeArgs& t, const DimSlice* sl, int n, hipStream_t s) {
+  if (n == 0) return LQ_OK;
+  if (t.p <= 256) {
+    // every wavefront builds the node masks of its 64 leaves once (p loads): give it at least p / 8
+    // rows to spread that over
+    ProjectArgs pa{};
+    int64_t max_rows = 0;
+    for (int k = 0; k < n; ++k) {
+      pa.D[k] = sl[k].D; pa.out[k] = sl[k].out; pa.ldd[k] = sl[k].ldd; pa.rows[k] = sl[k].rows;
+      pa.col_off[k] = sl[k].col_off; pa.cols[k] = sl[k].cols;
+      max_rows = std::max<int64_t>(max_rows, sl[k].rows);
+    }
+    const int64_t rows_per_block = 4 * std::max<int64_t>(4, t.p / 8);
+    const int64_t blocks = std::max<int64_t>(1, std::min<int64_t>((max_rows + rows_per_block - 1) / rows_per_block,
+                                                                  static_cast<int64_t>(num_cus()) * 8));
+    const dim3 grid(static_cast<unsigned>(blocks), static_cast<unsigned>((t.ld + 63) / 64), static_cast<unsigned>(n)), block(256);
+    if (t.p <= 64) hipLaunchKernelGGL(tree_project_bits_kernel<1>, grid, block, 0, s, t, pa);
+    else if (t.p <= 128) hipLaunchKernelGGL(tree_project_bits_kernel<2>, grid, block, 0, s, t, pa);
+    else hipLaunchKernelGGL(tree_project_bits_kernel<4>, grid, block, 0, s, t, pa);
+    LQ_LAUNCH_CHECK("tree_project_bits_kernel");
+    return LQ_OK;
+  }
+  for (int k = 0; k < n; ++k) {
+    const DimSlice& d = sl[k];
+    if (d.rows == 0) continue;
+    if (t.p <= 0x7fff) {   // beyond 4 mask words per leaf the per-leaf node lists are as fast or faster (measured up to 16 words)
+      const int64_t col_tiles = (t.ld + TP_COLS - 1) / TP_COLS;
+      // enough row slices to fill the GPU, each long enough to amortise building the lists
+      int64_t slices = std::max<int64_t>(1, std::min<int64_t>((static_cast<int64_t>(num_cus()) * 4 + col_tiles - 1) / col_tiles,
+                                                              (d.rows + 255) / 256));
+      slices = std::min<int64_t>(slices, 65535);
+      const int64_t rpb = (d.rows + slices - 1) / slices;
+      hipLaunchKernelGGL(tree_project_sparse_kernel, dim3(static_cast<unsigned>(col_tiles), static_cast<unsigned>(slices)),
+                         dim3(256), 0, s, t, d.D, d.ldd, d.rows, d.col_off, d.cols, d.out, rpb);
+      LQ_LAUNCH_CHECK("tree_project_sparse_kernel");
+    } else {
+      const int64_t total = d.rows * t.ld;
+      const int64_t blocks = std::min<int64_t>((total + 255) / 256, static_cast<int64_t>(num_cus()) * 32);
+      hipLaunchKernelGGL(tree_project_kernel, dim3(static_cast<unsigned>(blocks)), dim3(256), 0, s, t,
+                         d.D, d.ldd, d.rows, d.col_off, d.cols, d.out);
+      LQ_LAUNCH_CHECK("tree_project_kernel");
+    }
+  }
+  return LQ_OK;
+}
+
+// Mask rows of the table rows in sl[k].out (sl[k].D is not read).
+int compress_slices(const TreeArgs& t, const DimSlice* sl, u64* const* masks, int n, hipStream_t s) {
+  if (n == 0) return LQ_OK;
+  const int32_t words = static_cast<int32_t>((static_cast<int64_t>(t.l) + 63) / 64);
+  CompressArgs ca{};
+  int64_t max_rows = 0;
+  for (int k = 0; k < n; ++k) {
+    ca.table[k] = sl[k].out; ca.masks[k] = masks[k];
+    ca.rows[k] = sl[k].rows; ca.col_off[k] = sl[k].col_off; ca.cols[k] = sl[k].cols;
+    max_rows = std::max<int64_t>(max_rows, sl[k].rows);
+  }
+  const int64_t blocks = (max_rows + 256 * CMP_ROWS - 1) / (256 * CMP_ROWS);
+  if (blocks < 1) return LQ_OK;
+  if (blocks > 0x7fffffffLL || words > 65535) return fail(LQ_ERR_UNSUPPORTED, "too many rows or leaves for one launch");
+  hipLaunchKernelGGL(tree_compress_kernel, dim3(static_cast<unsigned>(blocks), static_cast<unsigned>(words),
+                                                static_cast<unsigned>(n)), dim3(256), 0, s, t, ca, words);
+  LQ_LAUNCH_CHECK("tree_compress_kernel");
+  return LQ_OK;
+}
+
 }  // namespace
 }  // namespace lq
 
@@ -956,56 +1030,41 @@ int lq_tree_project_dims(const lq_star* star, const lq_tree* tree, void* const* 
   hipStream_t s = static_cast<hipStream_t>(hip_stream);
   hipLaunchKernelGGL(tree_target_kernel, dim3(static_cast<unsigned>((t.ld + 255) / 256)), dim3(256), 0, s, t, target);
   LQ_LAUNCH_CHECK("tree_target_kernel");
+  DimSlice sl[LQ_MAX_DIMS];
   int32_t off = star->fact.cols;
   for (int k = 0; k < star->n_dims; ++k) {
     const lq_mat& d = star->dims[k];
-    if (t.p > 256 && t.p <= 0x7fff) {   // beyond 4 mask words per leaf the per-leaf node lists are as fast or faster (measured up to 16 words)
-      const int64_t col_tiles = (t.ld + TP_COLS - 1) / TP_COLS;
-      // enough row slices to fill the GPU, each long enough to amortise building the lists
-      int64_t slices = std::max<int64_t>(1, std::min<int64_t>((static_cast<int64_t>(num_cus()) * 4 + col_tiles - 1) / col_tiles,
-                                                              (d.rows + 255) / 256));
-      slices = std::min<int64_t>(slices, 65535);
-      const int64_t rpb = (d.rows + slices - 1) / slices;
-      hipLaunchKernelGGL(tree_project_sparse_kernel, dim3(static_cast<unsigned>(col_tiles), static_cast<unsigned>(slices)),
-                         dim3(256), 0, s, t, static_cast<const float*>(d.data), d.ld, d.rows, off, d.cols,
-                         static_cast<uint8_t*>(tables[k]), rpb);
-      LQ_LAUNCH_CHECK("tree_project_sparse_kernel");
-    } else if (t.p <= 256) {
-      off += d.cols;
-      continue;                          // (these go out together, after the loop)
-    } else {
-      const int64_t total = d.rows * t.ld;
-      const int64_t blocks = std::min<int64_t>((total + 255) / 256, static_cast<int64_t>(num_cus()) * 32);
-      hipLaunchKernelGGL(tree_project_kernel, dim3(static_cast<unsigned>(blocks)), dim3(256), 0, s, t,
-                         static_cast<const float*>(d.data), d.ld, d.rows, off, d.cols,
-                         static_cast<uint8_t*>(tables[k]));
-      LQ_LAUNCH_CHECK("tree_project_kernel");
-    }
+    sl[k] = DimSlice{static_cast<const float*>(d.data), d.ld, d.rows, off, d.cols, static_cast<uint8_t*>(tables[k])};
     off += d.cols;
   }
-  if (t.p <= 256 && star->n_dims > 0) {
-    // every wavefront builds the node masks of its 64 leaves once (p loads): give it at least p / 8
-    // rows to spread that over
-    ProjectArgs pa{};
-    int32_t o = star->fact.cols;
-    int64_t max_rows = 0;
-    for (int k = 0; k < star->n_dims; ++k) {
-      const lq_mat& d = star->dims[k];
-      pa.D[k] = static_cast<const float*>(d.data); pa.out[k] = static_cast<uint8_t*>(tables[k]);
-      pa.ldd[k] = d.ld; pa.rows[k] = d.rows; pa.col_off[k] = o; pa.cols[k] = d.cols;
-      max_rows = std::max<int64_t>(max_rows, d.rows);
-      o += d.cols;
-    }
-    const int64_t rows_per_block = 4 * std::max<int64_t>(4, t.p / 8);
-    const int64_t blocks = std::max<int64_t>(1, std::min<int64_t>((max_rows + rows_per_block - 1) / rows_per_block,
-                                                                  static_cast<int64_t>(num_cus()) * 8));
-    const dim3 grid(static_cast<unsigned>(blocks), static_cast<unsigned>((t.ld + 63) / 64), static_cast<unsigned>(star->n_dims)), block(256);
-    if (t.p <= 64) hipLaunchKernelGGL(tree_project_bits_kernel<1>, grid, block, 0, s, t, pa);
-    else if (t.p <= 128) hipLaunchKernelGGL(tree_project_bits_kernel<2>, grid, block, 0, s, t, pa);
-    else hipLaunchKernelGGL(tree_project_bits_kernel<4>, grid, block, 0, s, t, pa);
-    LQ_LAUNCH_CHECK("tree_project_bits_kernel");
-  }
-  return LQ_OK;
+  return project_slices(t, sl, star->n_dims, s);
+}
+
+int lq_tree_project_dim_rows(const lq_star* star, const lq_tree* tree, void* const* tables, uint64_t* const* masks,
+                             int32_t dim, int64_t first_row, int64_t n_rows, void* hip_stream) {
+  clear_error();
+  TreeArgs t{};
+  int rc = check_star_basic(star, true);
+  if (rc) return rc;
+  if ((rc = check_tree(tree, &t))) return rc;
+  if (dim < 0 || dim >= star->n_dims) return fail(LQ_ERR_SHAPE, "dim outside 0..%d", star->n_dims - 1);
+  const lq_mat& d = star->dims[dim];
+  if (first_row < 0 || n_rows < 0 || first_row > d.rows || n_rows > d.rows - first_row)
+    return fail(LQ_ERR_SHAPE, "rows [%lld, +%lld) outside dims[%d]", static_cast<long long>(first_row),
+                static_cast<long long>(n_rows), dim);
+  if (!tables || !tables[dim] || !aligned(tables[dim], 16)) return fail(LQ_ERR_NULL, "tables[%d] is NULL or not 16-byte aligned", dim);
+  if (masks && (!masks[dim] || !aligned(masks[dim], 8))) return fail(LQ_ERR_NULL, "masks[%d] is NULL or misaligned", dim);
+  if (n_rows == 0) return LQ_OK;
+  int32_t off = star->fact.cols;
+  for (int k = 0; k < dim; ++k) off += star->dims[k].cols;
+  hipStream_t s = static_cast<hipStream_t>(hip_stream);
+  const DimSlice sl{static_cast<const float*>(d.data) + first_row * d.ld, d.ld, n_rows, off, d.cols,
+                    static_cast<uint8_t*>(tables[dim]) + first_row * t.ld};
+  if ((rc = project_slices(t, &sl, 1, s))) return rc;
+  if (!masks) return LQ_OK;
+  const int32_t words = static_cast<int32_t>(lq_tree_mask_words(t.l));
+  u64* m = reinterpret_cast<u64*>(masks[dim]) + first_row * words;
+  return compress_slices(t, &sl, &m, 1, s);
 }
 
 int lq_fused_join_tree(const lq_star* star, const lq_tree* tree, const void* const* tables,
@@ -1160,29 +1219,21 @@ int lq_tree_compress_tables(const lq_star* star, const lq_tree* tree, const void
   if (rc) return rc;
   if ((rc = check_tree(tree, &t))) return rc;
   if (star->n_dims > 0 && (!tables || !masks || !star->dims)) return fail(LQ_ERR_NULL, "tables, masks or star->dims is NULL");
-  const int32_t words = static_cast<int32_t>(lq_tree_mask_words(t.l));
   hipStream_t s = static_cast<hipStream_t>(hip_stream);
   if (star->n_dims == 0) return LQ_OK;
-  CompressArgs ca{};
+  DimSlice sl[LQ_MAX_DIMS];
+  u64* mk[LQ_MAX_DIMS];
   int32_t off = star->fact.cols;
-  int64_t max_rows = 0;
   for (int k = 0; k < star->n_dims; ++k) {
     const lq_mat& d = star->dims[k];
     if (d.rows < 1 || d.cols < 1) return fail(LQ_ERR_SHAPE, "dims[%d] is malformed", k);
     if (!tables[k] || !masks[k] || !aligned(masks[k], 8) || !aligned(tables[k], 16))
       return fail(LQ_ERR_NULL, "tables[%d] or masks[%d] is NULL or misaligned", k, k);
-    ca.table[k] = static_cast<const uint8_t*>(tables[k]);
-    ca.masks[k] = reinterpret_cast<u64*>(masks[k]);
-    ca.rows[k] = d.rows; ca.col_off[k] = off; ca.cols[k] = d.cols;
-    max_rows = std::max<int64_t>(max_rows, d.rows);
+    sl[k] = DimSlice{nullptr, 0, d.rows, off, d.cols, static_cast<uint8_t*>(const_cast<void*>(tables[k]))};
+    mk[k] = reinterpret_cast<u64*>(masks[k]);
     off += d.cols;
   }
-  const int64_t blocks = (max_rows + 256 * CMP_ROWS - 1) / (256 * CMP_ROWS);
-  if (blocks > 0x7fffffffLL || words > 65535) return fail(LQ_ERR_UNSUPPORTED, "too many rows or leaves for one launch");
-  hipLaunchKernelGGL(tree_compress_kernel, dim3(static_cast<unsigned>(blocks), static_cast<unsigned>(words),
-                                                static_cast<unsigned>(star->n_dims)), dim3(256), 0, s, t, ca, words);
-  LQ_LAUNCH_CHECK("tree_compress_kernel");
-  return LQ_OK;
+  return compress_slices(t, sl, mk, star->n_dims, s);
 }
 
 int64_t lq_tree_fact_mask_bytes(int32_t n_nodes, int32_t n_leaves) {

@@ -256,3 +256,48 @@ def test_masks_need_the_fact_side_when_the_fact_table_has_columns(lq):
     with pytest.raises(lq.LQError) as e:
         lq.lq_fused_join_tree_masks(w.fks, masks, f, t, H, X=w.X)
     assert e.value.status == "LQ_ERR_NULL"
+
+
+@pytest.mark.parametrize("leaves,c_f", [(24, 0), (64, 3), (300, 0), (2_000, 2)], ids=["l24", "l64_fact", "l300", "l2000_fact"])
+def test_incremental_refresh_of_tree_tables_and_masks(lq, leaves, c_f):
+    """Section 3.2: the pre-fused tables are constants only until a dimension row changes.  Refreshing a
+    row range must give what a full pre-fusion (the oracle's) gives for the changed table, and must not
+    touch other rows (every pre-fusion kernel: bit-mask form, per-leaf node lists)."""
+    w, tree = _case("tree_refresh", 3_001, c_f, (500, 90), (6, 5), leaves, WL.SEED0 + 640 + leaves)
+    w = to_dev(w)
+    f, t, H = tree.feature.cuda(), tree.threshold.cuda(), tree.H.cuda()
+    tables, target = lq.lq_tree_project_dims(w.dims, c_f, f, t, H)
+    masks = lq.lq_tree_compress_tables(w.dims, tables, f, t, H, c_f=c_f)
+    g = torch.Generator().manual_seed(WL.SEED0 + 641)
+    for dim, first, count in ((0, 37, 101), (1, 0, 90), (0, 499, 1), (1, 45, 0)):
+        w.dims[dim][first:first + count] = torch.randn((count, w.dims[dim].shape[1]), generator=g).cuda()
+        before = [tb.clone() for tb in tables], [m.clone() for m in masks]
+        lq.lq_tree_project_dim_rows(w.dims, c_f, tables, masks, f, t, H, dim, first, count)
+        torch.cuda.synchronize()
+        for k in range(2):                      # rows outside the range: untouched
+            keep = torch.ones(tables[k].shape[0], dtype=torch.bool, device="cuda")
+            if k == dim:
+                keep[first:first + count] = False
+            assert torch.equal(tables[k][keep], before[0][k][keep]) and torch.equal(masks[k][keep], before[1][k][keep])
+    cpu = cpu_list(w.dims)
+    Tk = O.tree_project(cpu, c_f, tree.feature, tree.threshold, tree.H)
+    _, onehot, leaf = O.tree_predict(None if w.X is None else w.X.cpu(), cpu, cpu_list(w.fks), tree.feature, tree.threshold, tree.H)
+    Hn = tree.H.numpy().astype(np.int64)
+    feat = tree.feature.numpy()
+    off = c_f
+    for k, d in enumerate(cpu):
+        own = (feat >= off) & (feat < off + d.shape[1])
+        np.testing.assert_array_equal(tables[k].cpu().numpy()[:, :leaves].astype(np.int64), Tk[k] + (Hn[own] == -1).sum(axis=0))
+        off += d.shape[1]
+    got, _ = lq.lq_fused_join_tree(w.X, w.fks, tables, target, f, t, H)
+    fact = _fact_side(lq, w, tree)
+    got_k, oh_k = lq.lq_fused_join_tree_masks(w.fks, masks, f, t, H, want_onehot=True, **fact)
+    torch.cuda.synchronize()
+    np.testing.assert_array_equal(got.cpu().numpy(), leaf)
+    np.testing.assert_array_equal(got_k.cpu().numpy(), leaf)
+    np.testing.assert_array_equal(oh_k.cpu().numpy(), onehot)
+    # tables only (no masks given)
+    lq.lq_tree_project_dim_rows(w.dims, c_f, tables, None, f, t, H, 0, 10, 20)
+    with pytest.raises(lq.LQError) as e:
+        lq.lq_tree_project_dim_rows(w.dims, c_f, tables, masks, f, t, H, 1, 80, 11)
+    assert e.value.status == "LQ_ERR_SHAPE"

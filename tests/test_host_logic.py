@@ -188,6 +188,14 @@ def test_tree_entry_points_reject_bad_arguments():
     assert lib.lq_tree_fact_masks(2, ctypes.byref(tree), None, None) == 1
     assert lib.lq_tree_fact_masks(2, ctypes.byref(tree), FAKE + 8, None) == 1
     masks = (ctypes.c_void_p * 1)(FAKE)
+    # incremental refresh: dimension and row range are checked against the star (dims[0] has 5 rows)
+    refresh = lambda dim, first, count, tb=tables, mk=masks: lib.lq_tree_project_dim_rows(
+        ctypes.byref(star), ctypes.byref(tree), tb, mk, dim, first, count, None)
+    assert refresh(-1, 0, 1) == 2 and refresh(1, 0, 1) == 2
+    assert refresh(0, 3, 3) == 2 and refresh(0, -1, 2) == 2 and refresh(0, 6, 0) == 2
+    assert refresh(0, 5, 0) == 0                              # an empty range at the end: nothing to do
+    assert refresh(0, 0, 1, tb=(ctypes.c_void_p * 1)(FAKE + 8)) == 1
+    assert refresh(0, 0, 1, mk=(ctypes.c_void_p * 1)(FAKE + 4)) == 1
     # a fact table with columns of its own needs the fact-side buffer
     assert lib.lq_fused_join_tree_masks(ctypes.byref(star), ctypes.byref(tree), masks, None, FAKE, None, 0, None) == 1
     assert lib.lq_fused_join_tree_masks(ctypes.byref(star), ctypes.byref(tree), masks, FAKE + 8, FAKE, None, 0, None) == 1
