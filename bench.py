@@ -84,7 +84,7 @@ def main():
     ap.add_argument("--rows", type=int, default=10_000_000, help="fact rows of the headline workload")
     ap.add_argument("--no-extras", action="store_true", help="skip materialised / group-by / skewed legs")
     ap.add_argument("--no-cpu", action="store_true", help="skip the CPU oracle baseline")
-    ap.add_argument("--only", default="", help="run a single leg for profiling: fused|c1|groupby|groupby16|c4|c5|deep|tree|treesweep|keymap|agg|domain|sweep|sfsweep|materialized|copy")
+    ap.add_argument("--only", default="", help="run a single leg for profiling: fused|c1|linear|groupby|groupby16|c4|c5|deep|tree|treesweep|keymap|agg|domain|sweep|sfsweep|materialized|copy")
     args = ap.parse_args()
     if args.gpus != 1:
         sys.exit("bench.py: this build is single-GPU by design (no collectives, no sharding); "
@@ -229,6 +229,33 @@ def main():
                            "materialized_us": mus * 1e3, "rows_per_s": w1.n / (fus * 1e-3),
                            "note": "280 KB of traffic: bound by launch latency; fused_us is paced by the Python caller, "
                                    "fused_us_in_a_graph by the GPU (32 calls per graph)"}
+
+    # ---------------------------------------------------------------- linear regression at scale (the model of Section 3.2)
+    if (args.only == "" and not args.no_extras) or args.only == "linear":
+        nl = 10_000_000
+        cells = {}
+        for name, rows, cols in (("c2_star", (1_000, 10_000, 100_000), (32, 32, 32)),
+                                 ("dimension_tables_all_in_lds", (1_000, 10_000, 20_000), (32, 32, 32)),
+                                 ("four_tables_ssb_sf1_sizes", (2_556, 30_000, 2_000, 200_000), (8, 8, 8, 8))):
+            wl = WL.make_predict("linear_" + name, nl, 4, rows, cols, (1,), seed=WL.SEED0 + 800, device=dev, bias=True)
+            Pl = lq.lq_project_dims(wl.dims, wl.weights[0], wl.c_f)
+            Yl = torch.empty((nl, 1), dtype=torch.float32, device=dev)
+            pms, _, _ = time_call(lambda: lq.lq_project_dims(wl.dims, wl.weights[0], wl.c_f, P=Pl), 10, 2)
+            fms = graph_time(lambda: lq.lq_fused_join_predict(wl.X, wl.fks, Pl, wl.weights, wl.biases, Y=Yl))
+            chunk = 1 << 21
+            wsl = torch.empty(lq.lq_workspace_bytes(lq.binding.LQ_CALL_MATERIALIZED, wl.k, wl.weights, chunk),
+                              dtype=torch.uint8, device=dev)
+            mms, _, _ = time_call(lambda: lq.lq_materialized_join_predict(wl.X, wl.dims, wl.fks, wl.weights, wl.biases,
+                                                                          Y=Yl, ws=wsl), 3, 1)
+            bpr = 4 * (4 + len(rows) + 1)
+            gbps = bpr * nl / (fms * 1e-3) / 1e9
+            cells[name] = {"dim_rows": list(rows), "joined_cols": wl.k, "fused_ms_in_a_graph": fms, "project_dims_ms": pms,
+                           "rows_per_s": nl / (fms * 1e-3), "materialized_ms": mms, "fused_speedup": mms / (fms + pms),
+                           "roofline": {"bound": "hbm", "achieved": gbps, "peak": HBM_PEAK_GBPS, "unit": "GB/s",
+                                        "frac": gbps / HBM_PEAK_GBPS, "algorithmic_bytes_per_row": bpr}}
+            del wl, Pl, Yl, wsl
+        out["linear_regression"] = {"fact_rows": nl, "fact_cols": 4, "outputs": 1, "cells": cells}
+        torch.cuda.empty_cache()
 
     # ---------------------------------------------------------------- LA group-by (SSB-sf1 shape)
     if (args.only == "" and not args.no_extras) or args.only == "groupby":

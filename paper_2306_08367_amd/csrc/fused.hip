@@ -345,6 +345,7 @@ int try_fused_bf16(const PredictArgs& a, hipStream_t s);
 int try_fused_tile(const PredictArgs& a, hipStream_t s);
 int try_fused_deep(const PredictArgs& a, hipStream_t s);
 int try_fused_deep_bf16(const PredictArgs& a, hipStream_t s);
+int try_fused_lds(const PredictArgs& a, hipStream_t s);
 
 int launch_fused(const PredictArgs& a, hipStream_t s) {
   if (a.n == 0) return LQ_OK;
@@ -357,6 +358,8 @@ int launch_fused(const PredictArgs& a, hipStream_t s) {
   rc = try_fused_bf16(a, s);
   if (rc >= 0) return rc;
   rc = try_fused_deep_bf16(a, s);     // bf16: three or four layers, or a second layer of 17..64 outputs
+  if (rc >= 0) return rc;
+  rc = try_fused_lds(a, s);           // linear models with 1 / 2 / 4 outputs whose small projected tables fit LDS
   if (rc >= 0) return rc;
   rc = try_vec(a, s);
   if (rc >= 0) return rc;

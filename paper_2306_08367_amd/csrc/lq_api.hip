@@ -294,6 +294,7 @@ int lq_fused_join_predict(const lq_star* star, const lq_model* model, const lq_m
     }
     a.P[k] = P[k].data;
     a.ldp[k] = P[k].ld;
+    a.prows[k] = P[k].rows;
     a.fk[k] = star->fks[k];
     rows[k] = P[k].rows;
   }

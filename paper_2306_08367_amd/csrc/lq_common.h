@@ -51,6 +51,7 @@ struct PredictArgs {
   int32_t K;
   const void* P[LQ_MAX_DIMS];      // projected tables [r_k x l_1]
   int64_t ldp[LQ_MAX_DIMS];
+  int64_t prows[LQ_MAX_DIMS];      // r_k
   const int32_t* fk[LQ_MAX_DIMS];
   int32_t n_layers;
   const void* W[LQ_MAX_LAYERS];    // W[0] only rows [0, c_f) are used by the fused kernels

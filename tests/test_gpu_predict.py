@@ -253,6 +253,46 @@ def test_deeper_models_with_strided_inputs(lq, layers, dtype):
         assert (buf._base[:, :pad] == 0).all() and (buf._base[:, pad + layers[0]:] == 0).all()
 
 
+LDS_LINEAR = [
+    # name, c_f, dim_rows, dim_cols, outputs, bias; above 2^20 fact rows the small projected tables of
+    # such models are kept in LDS, larger ones (here: 100,000 / 40,000 rows) are gathered from memory
+    ("l1_c2_star", 4, (1_000, 10_000, 100_000), (32, 32, 32), 1, True),
+    ("l1_four_tables_no_fact_columns", 0, (2_556, 30_000, 2_000, 200), (8, 8, 8, 8), 1, False),
+    ("l1_one_table_cf3", 3, (5_000,), (6,), 1, True),
+    ("l1_cf8", 8, (300, 36_000), (5, 5), 1, True),
+    ("l2_two_tables_cf5", 5, (1_000, 17_000), (16, 16), 2, True),
+    ("l2_four_tables", 4, (100, 200, 300, 40_000), (4, 4, 4, 4), 2, False),
+    ("l4_three_tables", 4, (1_000, 8_000, 100_000), (8, 8, 8), 4, True),
+    ("l4_cf7_one_table_fits_exactly", 7, (9_216, 40_000), (6, 6), 4, True),
+]
+
+
+@pytest.mark.parametrize("shape", LDS_LINEAR, ids=[s[0] for s in LDS_LINEAR])
+def test_linear_models_with_lds_resident_tables(lq, shape):
+    name, c_f, rows, cols, l, bias = shape
+    n = (1 << 20) + 2_777                                 # ends inside a workgroup's last step
+    w = WL.make_predict(name, n, c_f, rows, cols, (l,), seed=WL.SEED0 + 95, bias=bias)
+    want = _oracle(w, nthreads=16)
+    w = to_dev(w)
+    P, Y = _run_fused(lq, w)
+    assert_close(Y, want, TOL_F32, name)
+    _, Yg = _run_fused(lq, w, flags=lq.LQ_FORCE_GENERIC)  # the shape-agnostic kernel on the same inputs
+    assert_close(Yg, want, TOL_F32, name + " (generic kernel)")
+    # operands that are column slices of wider buffers: X and Y keep the kernel (scalar loads / stores),
+    # a projected table with a row stride other than l stays in memory
+    Yw = torch.full((n, l + 3), -1.0, device="cuda")
+    Xs = None
+    if c_f:
+        Xw = torch.zeros((n, c_f + 1), device="cuda"); Xw[:, 1:] = w.X
+        Xs = Xw[:, 1:]
+    buf = torch.zeros((rows[0], 2 * l), device="cuda"); buf[:, l:] = P[0]
+    Ps = [buf[:, l:]] + list(P[1:])
+    lq.lq_fused_join_predict(Xs, w.fks, Ps, w.weights, w.biases, Y=Yw[:, 2:2 + l])
+    torch.cuda.synchronize()
+    assert_close(Yw[:, 2:2 + l], want, TOL_F32, name + " (strided)")
+    assert (Yw[:, :2] == -1).all() and (Yw[:, 2 + l:] == -1).all()
+
+
 def test_bf16_paths(lq):
     for name, c_f, layers in (("bf16_linear", 8, (8,)), ("bf16_mlp", 0, (64, 4)), ("bf16_mlp16", 4, (256, 16))):
         w = WL.make_predict(name, 6_007, c_f, (300, 1_000), (32, 64), layers, seed=WL.SEED0 + 80,
