@@ -4,6 +4,7 @@ evaluates the nodes whose column it owns.  CPU only."""
 import os
 
 import numpy as np
+import torch
 
 from oracle import lq_oracle as O
 from workloads import star as WL
@@ -105,6 +106,43 @@ def test_eq2_partial_tables_add_up_to_the_unfused_result():
             Bf = (X[:, tree.feature.numpy()[own]] > tree.threshold.numpy()[own].astype(np.float64))
             S = S + Bf.astype(np.int64) @ tree.H.numpy()[own].astype(np.int64)
         np.testing.assert_array_equal(S, R)
+
+
+def test_leaf_is_reached_exactly_when_every_owner_agrees_on_all_of_its_path_nodes():
+    """The statement behind the one-bit-per-leaf form of the pre-fused tables.  Agreement count of an
+    owner (a dimension, or the fact table's own columns) for leaf j = its signed partial sum + its number
+    of -1 entries in column j; it never exceeds the number of path nodes that owner has, and the counts
+    of all owners reach the path length (R_j == h_j) iff each one reaches its own maximum.  Checked on
+    the oracle's partial tables and its unfused result, for stars with and without fact columns, and for
+    a matrix H that is not a tree (a leaf nobody reaches)."""
+    for c_f, leaves, seed in ((0, 12, 40), (3, 12, 41), (2, 70, 42), (0, 3, 43)):
+        X, dims, fks = _star(seed, n=400, c_f=c_f)
+        tree = WL.make_tree(c_f + 9, leaves, seed + 100)
+        H = tree.H.numpy().astype(np.int64)
+        if seed == 43:
+            H = np.concatenate([H, np.ones((H.shape[0], 1), dtype=np.int64)], axis=1)   # needs every node true
+        Ht = torch.from_numpy(H.astype(np.int8))
+        R, onehot, _ = O.tree_predict(X, dims, fks, tree.feature, tree.threshold, Ht)
+        Tk = O.tree_project(dims, c_f, tree.feature, tree.threshold, Ht)
+        feat, thr = tree.feature.numpy(), tree.threshold.numpy().astype(np.float64)
+        every_owner_agrees = np.ones_like(onehot, dtype=bool)
+        off = c_f
+        for k, d in enumerate(dims):
+            own = (feat >= off) & (feat < off + d.shape[1])
+            neg, path = (H[own] == -1).sum(axis=0), (H[own] != 0).sum(axis=0)
+            agree = Tk[k] + neg
+            assert (agree >= 0).all() and (agree <= path).all()
+            every_owner_agrees &= (agree == path)[fks[k]]
+            off += d.shape[1]
+        if c_f:
+            # the fact table's own nodes, one at a time: the leaves that stay possible are those whose
+            # path does not want the opposite outcome
+            for q in np.flatnonzero(feat < c_f):
+                bit = X[:, feat[q]] > thr[q]
+                every_owner_agrees &= np.where(bit[:, None], H[q] >= 0, H[q] <= 0)
+        np.testing.assert_array_equal(every_owner_agrees, onehot.astype(bool))
+        if seed == 43:
+            assert onehot[:, -1].sum() < len(onehot)         # the extra column is not always reached
 
 
 def test_literal_per_dimension_predicate_double_counts_with_negative_thresholds():
