@@ -207,7 +207,7 @@ int try_fused_lds(const PredictArgs& a, hipStream_t s) {
     if (!aligned(a.P[k], 4 * L) || a.ldp[k] % L) return -1;
   }
   std::stable_sort(order, order + a.K, [&](int x, int y) { return a.prows[x] < a.prows[y]; });
-  const int64_t budget = (144 * 1024) / 4;                // floats
+  const int64_t budget = (156 * 1024) / 4;                // floats, of the 160 KB of a compute unit
   int64_t used = 0;
   for (int q = 0; q < a.K; ++q) {
     const int k = order[q];

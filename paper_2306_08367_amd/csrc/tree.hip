@@ -1305,7 +1305,7 @@ int lq_fused_join_tree_masks(const lq_star* star, const lq_tree* tree, const uin
     if (ok) {
       std::stable_sort(order, order + a.K, [&](int x, int y) { return L.rows[x] < L.rows[y]; });
       int64_t used = 0;
-      const int64_t budget = (144 * 1024) / 8;
+      const int64_t budget = (156 * 1024) / 8;             // of the 160 KB of a compute unit; the fact-side nodes take 3 KB more
       for (int q = 0; q < a.K; ++q) {
         const int k = order[q];
         if (used + L.rows[k] > budget) break;

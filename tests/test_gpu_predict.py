@@ -263,7 +263,7 @@ LDS_LINEAR = [
     ("l2_two_tables_cf5", 5, (1_000, 17_000), (16, 16), 2, True),
     ("l2_four_tables", 4, (100, 200, 300, 40_000), (4, 4, 4, 4), 2, False),
     ("l4_three_tables", 4, (1_000, 8_000, 100_000), (8, 8, 8), 4, True),
-    ("l4_cf7_one_table_fits_exactly", 7, (9_216, 40_000), (6, 6), 4, True),
+    ("l4_cf7_one_table_fits_exactly", 7, (9_984, 40_000), (6, 6), 4, True),
 ]
 
 
