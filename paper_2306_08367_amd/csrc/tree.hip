@@ -234,9 +234,30 @@ __device__ __forceinline__ unsigned int zero_bytes(unsigned int w) {
 }
 
 // G lanes per fact row; lane c handles 16-leaf chunks c, c + G, ...
+// The nodes that test fact columns are listed once per workgroup (in LDS, in any order), so that the
+// per-row work on them is proportional to their number rather than to the size of the tree.
+constexpr int FT_LIST = 1024;           // listed nodes; a tree with more of them walks all nodes instead
 template <int G>
 __global__ __launch_bounds__(256) void fused_tree_kernel(FusedTreeArgs a) {
   constexpr int RPB = 256 / G;
+  __shared__ int fact_q[FT_LIST];
+  __shared__ int fact_cnt;
+  if (a.has_fact_nodes) {
+    if (threadIdx.x == 0) fact_cnt = 0;
+    __syncthreads();
+    for (int q0 = 0; q0 < a.t.p; q0 += 256) {
+      const int q = q0 + threadIdx.x;
+      const bool mine = q < a.t.p && a.t.feature[q] < a.c_f;
+      const unsigned long long bal = __ballot(mine);
+      int base = 0;
+      if ((threadIdx.x & 63) == 0 && bal) base = atomicAdd(&fact_cnt, __builtin_popcountll(bal));
+      base = __shfl(base, 0, 64);
+      const int pos = base + __builtin_popcountll(bal & ((1ull << (threadIdx.x & 63)) - 1ull));
+      if (mine && pos < FT_LIST) fact_q[pos] = q;
+      __syncthreads();
+    }
+  }
+  const int n_fact = a.has_fact_nodes ? fact_cnt : 0;
   const int sub = threadIdx.x / G, c = threadIdx.x % G;
   const int64_t row = static_cast<int64_t>(blockIdx.x) * RPB + sub;
   const bool live = row < a.n;
@@ -253,7 +274,9 @@ __global__ __launch_bounds__(256) void fused_tree_kernel(FusedTreeArgs a) {
       if (k < a.K) sum += *reinterpret_cast<const v4u*>(a.T[k] + base[k] + 16 * ch);
     if (a.has_fact_nodes) {
       const float* xr = a.X + rr * a.ldx;
-      for (int q = 0; q < a.t.p; ++q) {
+      const bool listed = n_fact <= FT_LIST;
+      for (int i = 0; i < (listed ? n_fact : a.t.p); ++i) {
+        const int q = listed ? fact_q[i] : i;
         const int f = a.t.feature[q];
         if (f >= a.c_f) continue;
         const bool bit = xr[f] > a.t.thr[q];
