@@ -301,3 +301,37 @@ def test_incremental_refresh_of_tree_tables_and_masks(lq, leaves, c_f):
     with pytest.raises(lq.LQError) as e:
         lq.lq_tree_project_dim_rows(w.dims, c_f, tables, masks, f, t, H, 1, 80, 11)
     assert e.value.status == "LQ_ERR_SHAPE"
+
+
+def test_mask_join_with_more_fact_side_nodes_than_the_lds_list_holds(lq):
+    """H need not be a tree.  200 nodes, all on the 8 fact columns and one dimension column, 48 "leaves"
+    that each want 4 nodes: above 2^20 rows the mask join keeps the first 128 fact-side nodes in LDS and
+    reads the others from memory.  All three joins against the oracle on a row sample, and against each
+    other on every row."""
+    n, c_f, p, l = (1 << 20) + 333, 8, 200, 48
+    w = WL.make_predict("masks_many_fact_nodes", n, c_f, (700,), (1,), (1,), seed=WL.SEED0 + 660, device="cuda")
+    g = np.random.default_rng(WL.SEED0 + 661)
+    feature = torch.from_numpy(g.integers(0, c_f + 1, size=p).astype(np.int32))
+    feature[150:] = torch.from_numpy(g.integers(0, c_f, size=p - 150).astype(np.int32))    # the tail: fact columns only
+    thr = torch.from_numpy(g.normal(0.0, 0.7, size=p).astype(np.float32))
+    Hn = np.zeros((p, l), dtype=np.int8)
+    for j in range(l):
+        qs = np.concatenate([g.choice(150, size=2, replace=False), 150 + g.choice(50, size=2, replace=False)])
+        Hn[qs, j] = g.choice([-1, 1], size=4)                                              # two wanted nodes beyond the first 128
+    H = torch.from_numpy(Hn)
+    f, t, Hd = feature.cuda(), thr.cuda(), H.cuda()
+    assert int((feature < c_f).sum()) > 128
+    tables, target = lq.lq_tree_project_dims(w.dims, c_f, f, t, Hd)
+    masks = lq.lq_tree_compress_tables(w.dims, tables, f, t, Hd, c_f=c_f)
+    fmask = lq.lq_tree_fact_masks(c_f, f, t, Hd)
+    leaf_b, _ = lq.lq_fused_join_tree(w.X, w.fks, tables, target, f, t, Hd)
+    leaf_k, oh_k = lq.lq_fused_join_tree_masks(w.fks, masks, f, t, Hd, want_onehot=True, X=w.X, fact_masks=fmask)
+    leaf_l, _ = lq.lq_fused_join_tree_masks(w.fks, masks, f, t, Hd, X=w.X, fact_masks=fmask)
+    torch.cuda.synchronize()
+    assert torch.equal(leaf_b, leaf_k) and torch.equal(leaf_b, leaf_l)
+    rows = WL.sample_rows(n)
+    sub = WL.take_rows(w, rows)
+    _, onehot, want = O.tree_predict(sub.X, sub.dims, sub.fks, feature, thr, H)
+    np.testing.assert_array_equal(leaf_l[rows.cuda()].cpu().numpy(), want)
+    np.testing.assert_array_equal(oh_k[rows.cuda()].cpu().numpy(), onehot)
+    assert (want >= 0).any() and (want == -1).any() and (onehot.sum(axis=1) > 1).any()
