@@ -247,7 +247,7 @@ __global__ __launch_bounds__(256) void fused_tree_kernel(FusedTreeArgs a) {
     __syncthreads();
     for (int q0 = 0; q0 < a.t.p; q0 += 256) {
       const int q = q0 + threadIdx.x;
-      const bool mine = q < a.t.p && a.t.feature[q] < a.c_f;
+      const bool mine = q < a.t.p && static_cast<unsigned int>(a.t.feature[q]) < static_cast<unsigned int>(a.c_f);
       const unsigned long long bal = __ballot(mine);
       int base = 0;
       if ((threadIdx.x & 63) == 0 && bal) base = atomicAdd(&fact_cnt, __builtin_popcountll(bal));
@@ -278,7 +278,7 @@ __global__ __launch_bounds__(256) void fused_tree_kernel(FusedTreeArgs a) {
       for (int i = 0; i < (listed ? n_fact : a.t.p); ++i) {
         const int q = listed ? fact_q[i] : i;
         const int f = a.t.feature[q];
-        if (f >= a.c_f) continue;
+        if (f < 0 || f >= a.c_f) continue;
         const bool bit = xr[f] > a.t.thr[q];
 #pragma unroll
         for (int b = 0; b < 16; ++b) {
@@ -544,13 +544,14 @@ __global__ __launch_bounds__(256) void tree_fact_masks_kernel(TreeArgs t, int32_
   const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
   const int q_lo = 16 * blockIdx.x;
   int before = 0;
-  for (int q = threadIdx.x; q < q_lo; q += 256) before += t.feature[q] < c_f ? 1 : 0;
+  for (int q = threadIdx.x; q < q_lo; q += 256) before += static_cast<unsigned int>(t.feature[q]) < static_cast<unsigned int>(c_f) ? 1 : 0;
 #pragma unroll
   for (int m = 32; m; m >>= 1) before += __shfl_xor(before, m, 64);
   if (lane == 0) part[wave] = before;
   __syncthreads();
   const int base = part[0] + part[1] + part[2] + part[3];
-  const bool owned = lane < 16 && q_lo + lane < t.p && t.feature[q_lo + lane] < c_f;
+  const bool owned = lane < 16 && q_lo + lane < t.p &&
+                     static_cast<unsigned int>(t.feature[q_lo + lane]) < static_cast<unsigned int>(c_f);   // (a negative column belongs to no table)
   const unsigned int chunk = static_cast<unsigned int>(__ballot(owned));     // bit i: node q_lo + i is the fact table's
   if (blockIdx.x == gridDim.x - 1 && threadIdx.x == 0) *out.cnt = base + __builtin_popcount(chunk);
   if (((chunk >> (4 * wave)) & 0xfu) == 0u) return;
