@@ -774,6 +774,57 @@ __global__ __launch_bounds__(256) void fused_tree_mask_kernel(MaskJoinArgs a) {
   }
 }
 
+// Leaf-only join for trees of more than 192 leaves (an even number of mask words, no fact-side nodes).
+// A mask row of `words` words is contiguous (128 bytes for 1,024 leaves), so G = words / 2 lanes
+// (rounded up to a power of two) read it as neighbouring 16-byte pieces: one load instruction then
+// touches 64 / G rows of a table as whole runs instead of 64 unrelated pieces, which is what the
+// address path of the vector memory unit is bound by in the kernel above.  A wavefront owns 64
+// consecutive fact rows: their keys are read once, coalesced (lane = row), and handed to the lane
+// groups through the cross-lane network; in pass t group g works on row (64 / G) t + g.  Each lane
+// ANDs its two words over the tables, finds its lowest set bit, and a minimum over the group gives
+// the leaf.  The gathers of four passes are requested before the first is consumed.
+template <int KT, int G>      // dimensions (1..4, 0 = any number); lanes per fact row (2..64)
+__global__ __launch_bounds__(256) void fused_tree_mask_rows_kernel(MaskJoinArgs a) {
+  constexpr int KK = KT > 0 ? KT : LQ_MAX_DIMS;
+  constexpr int RPP = 64 / G;                 // rows per pass
+  constexpr int PB = G < 4 ? G : 4;           // passes in flight together (G passes cover the 64 rows)
+  typedef u64 u64x2 __attribute__((ext_vector_type(2)));
+  const int lane = threadIdx.x & 63, g = lane / G, c = lane % G;
+  const int64_t wave = static_cast<int64_t>(blockIdx.x) * 4 + (threadIdx.x >> 6);
+  const int64_t row0 = wave * 64;
+  if (row0 >= a.n) return;
+  int key[KK];
+#pragma unroll
+  for (int k = 0; k < KK; ++k) key[k] = (KT > 0 || k < a.K) ? a.fk[k][min(row0 + lane, a.n - 1)] : 0;
+  const bool piece = 2 * c < a.words;         // (lanes past the last pair of words of a row stay idle)
+  for (int t0 = 0; t0 < G; t0 += PB) {
+    u64x2 m[PB];
+#pragma unroll
+    for (int e = 0; e < PB; ++e) {
+      m[e] = u64x2{~0ull, ~0ull};
+      const int src = (t0 + e) * RPP + g;     // the lane that holds this row's keys
+#pragma unroll
+      for (int k = 0; k < KK; ++k)
+        if (KT > 0 || k < a.K) {
+          const int j = __shfl(key[k], src, 64);
+          if (piece) m[e] &= *reinterpret_cast<const u64x2*>(a.M[k] + static_cast<int64_t>(j) * a.words + 2 * c);
+        }
+    }
+#pragma unroll
+    for (int e = 0; e < PB; ++e) {
+      int pos = 0x7fffffff;
+      if (piece && a.K > 0) {
+        if (m[e][0] != 0ull) pos = 128 * c + __builtin_ctzll(m[e][0]);
+        else if (m[e][1] != 0ull) pos = 128 * c + 64 + __builtin_ctzll(m[e][1]);
+      }
+#pragma unroll
+      for (int d = 1; d < G; d <<= 1) pos = min(pos, __shfl_xor(pos, d, 64));
+      const int64_t row = row0 + (t0 + e) * RPP + g;
+      if (c == 0 && row < a.n) a.leaf[row] = pos == 0x7fffffff ? -1 : pos;
+    }
+  }
+}
+
 // The same join for trees of up to 64 leaves (one mask word) and leaf-only output, with the mask
 // tables that fit kept in LDS: one persistent workgroup per compute unit stages them once, then its
 // threads stride over the fact rows, four rows each per step.  Gathers from LDS do not go through the
@@ -1362,12 +1413,36 @@ int lq_fused_join_tree_masks(const lq_star* star, const lq_tree* tree, const uin
       }
     }
   }
+  bool wide_loads = a.words % 2 == 0;
+  for (int k = 0; k < a.K; ++k) wide_loads = wide_loads && aligned(masks[k], 16);
+  if (wide_loads && !onehot && !a.f.X && a.words >= 4 && a.words <= 128) {
+    const int64_t rb = (a.n + 255) / 256;
+    if (rb > 0x7fffffffLL) return fail(LQ_ERR_UNSUPPORTED, "too many rows for one launch");
+    const dim3 rgrid(static_cast<unsigned>(rb)), rblock(256);
+    int G = 2;
+    while (2 * G < a.words) G *= 2;
+#define LQ_TR(KT_, G_) hipLaunchKernelGGL((fused_tree_mask_rows_kernel<KT_, G_>), rgrid, rblock, 0, s, a)
+#define LQ_TR_G(KT_)                                                                                   \
+  do {                                                                                                 \
+    switch (G) {                                                                                       \
+      case 2: LQ_TR(KT_, 2); break;                                                                    \
+      case 4: LQ_TR(KT_, 4); break;                                                                    \
+      case 8: LQ_TR(KT_, 8); break;                                                                    \
+      case 16: LQ_TR(KT_, 16); break;                                                                  \
+      case 32: LQ_TR(KT_, 32); break;                                                                  \
+      default: LQ_TR(KT_, 64); break;                                                                  \
+    }                                                                                                  \
+  } while (0)
+    if (a.K == 1) LQ_TR_G(1); else if (a.K == 2) LQ_TR_G(2); else if (a.K == 3) LQ_TR_G(3); else if (a.K == 4) LQ_TR_G(4); else LQ_TR_G(0);
+#undef LQ_TR_G
+#undef LQ_TR
+    LQ_LAUNCH_CHECK("fused_tree_mask_rows_kernel");
+    return LQ_OK;
+  }
   const int64_t blocks = (a.n + 1023) / 1024;
   if (blocks > 0x7fffffffLL) return fail(LQ_ERR_UNSUPPORTED, "too many rows for one launch");
   const dim3 grid(static_cast<unsigned>(blocks)), block(256);
   const int wmax = (a.onehot_vec && a.words <= 4) ? (a.words <= 1 ? 1 : (a.words <= 2 ? 2 : 4)) : 0;
-  bool wide_loads = a.words % 2 == 0;
-  for (int k = 0; k < a.K; ++k) wide_loads = wide_loads && aligned(masks[k], 16);
 #define LQ_TM(KT_, W_)                                                                                \
   do {                                                                                                \
     if (wide_loads) hipLaunchKernelGGL((fused_tree_mask_kernel<KT_, W_, 2>), grid, block, 0, s, a);   \
