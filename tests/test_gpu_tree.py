@@ -43,6 +43,9 @@ CASES = [
     ("hundred_leaves", 3_333, 0, (64, 64, 64, 64), (5, 5, 5, 5), 100),
     ("wide_256", 2_049, 0, (300, 200), (16, 16), 256),
     ("very_wide_1500", 1_025, 0, (120, 90), (32, 32), 1_500),
+    ("wide_384_six_mask_words", 1_531, 0, (200, 100), (16, 16), 384),
+    ("wide_1024_three_tables", 1_101, 0, (150, 90, 60), (20, 20, 20), 1_024),
+    ("wide_2048_one_table", 515, 0, (333,), (40,), 2_048),
     ("wide_600_three_tables", 777, 0, (1_000, 37, 300), (20, 30, 10), 600),
     ("fact_columns", 2_500, 3, (40, 60), (4, 4), 24),
     ("fact_columns_4_aligned", 5_111, 4, (40, 60, 25), (4, 4, 3), 64),
