@@ -844,6 +844,91 @@ __global__ __launch_bounds__(256) void fused_tree_mask_rows_kernel(MaskJoinArgs 
   }
 }
 
+// The same with nodes on fact-table columns (leaf only, any number of dimensions).  A lane applies
+// every such node to its two words of the row: the node's test is evaluated on the fact row of the
+// lane's group, and the mask pair that applies is ANDed in.  The pairs of the first nodes sit in LDS
+// (32 KB: 128 nodes at 1,024 leaves), those of further nodes are read from memory.
+constexpr int ROWS_FACT_LDS = 32 * 1024;
+template <int G>
+__global__ __launch_bounds__(256) void fused_tree_mask_rows_fact_kernel(MaskJoinArgs a) {
+  constexpr int KK = LQ_MAX_DIMS;
+  constexpr int RPP = 64 / G;
+  constexpr int PB = G < 4 ? G : 4;
+  typedef u64 u64x2 __attribute__((ext_vector_type(2)));
+  __shared__ __align__(16) u64 tf_lds[ROWS_FACT_LDS / 8];
+  __shared__ u64 ft_lds[ROWS_FACT_LDS / 64];      // column and threshold of the nodes in LDS (at least 4 words per row)
+  const int fact_nodes = *a.f.cnt;
+  const int in_lds = min(fact_nodes, ROWS_FACT_LDS / (16 * a.words));
+  for (int i = threadIdx.x; i < in_lds * a.words * 2; i += 256) tf_lds[i] = a.f.tf[i];
+  for (int i = threadIdx.x; i < in_lds; i += 256)
+    ft_lds[i] = static_cast<u64>(static_cast<unsigned int>(a.f.feat[i])) | (static_cast<u64>(__float_as_uint(a.f.thr[i])) << 32);
+  __syncthreads();
+  const int lane = threadIdx.x & 63, g = lane / G, c = lane % G;
+  const int64_t wave = static_cast<int64_t>(blockIdx.x) * 4 + (threadIdx.x >> 6);
+  const int64_t row0 = wave * 64;
+  if (row0 >= a.n) return;
+  int key[KK];
+#pragma unroll
+  for (int k = 0; k < KK; ++k) key[k] = k < a.K ? a.fk[k][min(row0 + lane, a.n - 1)] : 0;
+  const bool piece = 2 * c < a.words;
+  const int wc = piece ? 2 * c : 0;           // (idle lanes follow along on the first words and store nothing)
+  for (int t0 = 0; t0 < G; t0 += PB) {
+    u64 m0[PB], m1[PB];
+    FactRows<PB> fr;
+    int64_t rows[PB];
+#pragma unroll
+    for (int e = 0; e < PB; ++e) rows[e] = min(row0 + (t0 + e) * RPP + g, a.n - 1);
+    fact_rows_load(a.f, rows, fr);
+#pragma unroll
+    for (int e = 0; e < PB; ++e) {
+      u64x2 m = u64x2{~0ull, ~0ull};
+      const int src = (t0 + e) * RPP + g;
+#pragma unroll
+      for (int k = 0; k < KK; ++k)
+        if (k < a.K) {
+          const int j = __shfl(key[k], src, 64);
+          m &= *reinterpret_cast<const u64x2*>(a.M[k] + static_cast<int64_t>(j) * a.words + wc);
+        }
+      m0[e] = m[0]; m1[e] = m[1];
+    }
+    // (the data of node q + 1 is requested before node q is applied)
+    auto node = [&](int q, u64& ft, u64x2& p0, u64x2& p1) {      // {test true, test false} for this lane's two words
+      if (q < in_lds) {
+        ft = ft_lds[q];
+        const u64x2* src = reinterpret_cast<const u64x2*>(tf_lds) + q * a.words + wc;
+        p0 = src[0]; p1 = src[1];
+      } else {
+        ft = static_cast<u64>(static_cast<unsigned int>(a.f.feat[q])) | (static_cast<u64>(__float_as_uint(a.f.thr[q])) << 32);
+        const u64x2* src = reinterpret_cast<const u64x2*>(a.f.tf) + static_cast<int64_t>(q) * a.words + wc;
+        p0 = src[0]; p1 = src[1];
+      }
+    };
+    u64 ft = 0ull, nft = 0ull;
+    u64x2 p0 = {0ull, 0ull}, p1 = {0ull, 0ull}, np0 = {0ull, 0ull}, np1 = {0ull, 0ull};
+    if (fact_nodes > 0) node(0, ft, p0, p1);
+    for (int q = 0; q < fact_nodes; ++q) {
+      if (q + 1 < fact_nodes) node(q + 1, nft, np0, np1);
+      const int f = __builtin_amdgcn_readfirstlane(static_cast<int>(static_cast<unsigned int>(ft)));
+      const float v = __uint_as_float(static_cast<unsigned int>(ft >> 32));
+      fact_node_and(a.f, fr, f, v, p0[0], p0[1], m0);
+      fact_node_and(a.f, fr, f, v, p1[0], p1[1], m1);
+      ft = nft; p0 = np0; p1 = np1;
+    }
+#pragma unroll
+    for (int e = 0; e < PB; ++e) {
+      int pos = 0x7fffffff;
+      if (piece && (a.K > 0 || fact_nodes > 0)) {
+        if (m0[e] != 0ull) pos = 128 * c + __builtin_ctzll(m0[e]);
+        else if (m1[e] != 0ull) pos = 128 * c + 64 + __builtin_ctzll(m1[e]);
+      }
+#pragma unroll
+      for (int d = 1; d < G; d <<= 1) pos = min(pos, __shfl_xor(pos, d, 64));
+      const int64_t row = row0 + (t0 + e) * RPP + g;
+      if (c == 0 && row < a.n) a.leaf[row] = pos == 0x7fffffff ? -1 : pos;
+    }
+  }
+}
+
 // The same join for trees of up to 64 leaves (one mask word) and leaf-only output, with the mask
 // tables that fit kept in LDS: one persistent workgroup per compute unit stages them once, then its
 // threads stride over the fact rows, four rows each per step.  Gathers from LDS do not go through the
@@ -1434,6 +1519,23 @@ int lq_fused_join_tree_masks(const lq_star* star, const lq_tree* tree, const uin
   }
   bool wide_loads = a.words % 2 == 0;
   for (int k = 0; k < a.K; ++k) wide_loads = wide_loads && aligned(masks[k], 16);
+  if (wide_loads && !onehot && a.f.X && a.words >= 4 && a.words <= 128 && aligned(a.f.tf, 16)) {
+    const int64_t rb = (a.n + 255) / 256;
+    if (rb > 0x7fffffffLL) return fail(LQ_ERR_UNSUPPORTED, "too many rows for one launch");
+    const dim3 rgrid(static_cast<unsigned>(rb)), rblock(256);
+    int G = 2;
+    while (2 * G < a.words) G *= 2;
+    switch (G) {
+      case 2: hipLaunchKernelGGL(fused_tree_mask_rows_fact_kernel<2>, rgrid, rblock, 0, s, a); break;
+      case 4: hipLaunchKernelGGL(fused_tree_mask_rows_fact_kernel<4>, rgrid, rblock, 0, s, a); break;
+      case 8: hipLaunchKernelGGL(fused_tree_mask_rows_fact_kernel<8>, rgrid, rblock, 0, s, a); break;
+      case 16: hipLaunchKernelGGL(fused_tree_mask_rows_fact_kernel<16>, rgrid, rblock, 0, s, a); break;
+      case 32: hipLaunchKernelGGL(fused_tree_mask_rows_fact_kernel<32>, rgrid, rblock, 0, s, a); break;
+      default: hipLaunchKernelGGL(fused_tree_mask_rows_fact_kernel<64>, rgrid, rblock, 0, s, a); break;
+    }
+    LQ_LAUNCH_CHECK("fused_tree_mask_rows_fact_kernel");
+    return LQ_OK;
+  }
   // (one-hot rows of up to four words are faster from the kernel below, which writes them 16 bytes per
   // lane through the cross-lane network: 0.14 against 0.30 ms per 2.4e6 rows at 256 leaves)
   if (wide_loads && (!onehot || (a.onehot_vec && a.words > 4)) && !a.f.X && a.words >= 4 && a.words <= 128) {

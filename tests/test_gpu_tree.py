@@ -53,6 +53,9 @@ CASES = [
     ("fact_columns_12", 2_777, 12, (50,), (8,), 48),
     ("fact_columns_5_very_wide_tree", 1_333, 5, (70, 30), (10, 10), 700),
     ("fact_columns_only", 4_321, 6, (), (), 40),
+    ("fact_columns_4_wide_1024", 1_203, 4, (150, 90), (20, 20), 1_024),
+    ("fact_columns_12_wide_384", 1_777, 12, (64, 32, 16), (5, 5, 5), 384),
+    ("fact_columns_only_wide_256", 2_049, 7, (), (), 256),
     ("one_row", 1, 0, (5,), (3,), 4),
 ]
 
