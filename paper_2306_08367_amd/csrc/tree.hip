@@ -312,7 +312,7 @@ __global__ __launch_bounds__(256) void fused_tree_kernel(FusedTreeArgs a) {
   if (a.leaf && live && c == 0) a.leaf[row] = first == 0x7fffffff ? -1 : first;
 }
 
-// The same join stage for trees of up to 256 leaves without fact-table nodes, organised so that a
+// The same join stage for trees of up to 1,024 leaves without fact-table nodes, organised so that a
 // wavefront has many gathers in flight: it owns 64 consecutive fact rows, reads their keys once,
 // coalesced (lane = row), and hands them to the G-lane groups through the cross-lane network; in
 // pass t group g works on row (64 / G) t + g.  The gathers of up to four passes are issued before
@@ -1280,7 +1280,7 @@ int lq_fused_join_tree(const lq_star* star, const lq_tree* tree, const void* con
     if ((rc = tree_check_fks(star, ws, ws_bytes, s))) return rc;
   int G = 1;
   while (G < a.chunks && G < 64) G <<= 1;
-  if (!a.has_fact_nodes && a.chunks <= 16 && (!a.onehot || (a.onehot_vec_ok && a.t.l % 16 == 0))) {
+  if (!a.has_fact_nodes && a.chunks <= 64 && (!a.onehot || (a.onehot_vec_ok && a.t.l % 16 == 0))) {
     const int64_t bblocks = (a.n + 255) / 256;
     if (bblocks > 0x7fffffffLL) return fail(LQ_ERR_UNSUPPORTED, "too many rows for one launch");
     const dim3 grid(static_cast<unsigned>(bblocks)), block(256);
@@ -1292,7 +1292,7 @@ int lq_fused_join_tree(const lq_star* star, const lq_tree* tree, const void* con
     else LQ_TREE_K(GG, 0);                                                          \
     break;
     switch (G) {
-      LQ_TREE_CASE(1) LQ_TREE_CASE(2) LQ_TREE_CASE(4) LQ_TREE_CASE(8) LQ_TREE_CASE(16)
+      LQ_TREE_CASE(1) LQ_TREE_CASE(2) LQ_TREE_CASE(4) LQ_TREE_CASE(8) LQ_TREE_CASE(16) LQ_TREE_CASE(32) LQ_TREE_CASE(64)
     }
 #undef LQ_TREE_CASE
 #undef LQ_TREE_K
