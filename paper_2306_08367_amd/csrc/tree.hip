@@ -154,13 +154,17 @@ __global__ __launch_bounds__(256) void tree_project_bits_kernel(TreeArgs t, Proj
 // unsupported), so a workgroup first turns the H columns of its 64 leaves into per-leaf lists of the
 // nodes this dimension owns (node number, sign bit) in LDS and then walks only those lists for every
 // (dimension row, leaf): r * l * depth / K evaluations instead of r * l * p.
-constexpr int TP_COLS = 64;         // leaves per workgroup
-constexpr int TP_MAXPATH = 256;     // list capacity per leaf
+constexpr int TP_COLS = 32;         // leaves per workgroup
+constexpr int TP_MAXPATH = 255;     // list capacity per leaf (longer paths are unsupported: a byte holds the count)
+// The lists hold, per entry, the column within the dimension table (bit 31: the path wants the test
+// false) and the threshold; entry e of all leaves lies side by side, so the lanes of a wavefront
+// (lane = leaf) read neighbouring LDS words.
 __global__ __launch_bounds__(256) void tree_project_sparse_kernel(TreeArgs t, const float* __restrict__ D,
                                                                   int64_t ldd, int64_t rows, int32_t col_off,
                                                                   int32_t c, uint8_t* __restrict__ out,
                                                                   int64_t rows_per_block) {
-  __shared__ unsigned short list[TP_COLS][TP_MAXPATH];
+  __shared__ unsigned int ent[TP_MAXPATH][TP_COLS];
+  __shared__ float thr_l[TP_MAXPATH][TP_COLS];
   __shared__ int count[TP_COLS];
   const int tid = threadIdx.x;
   const int j0 = blockIdx.x * TP_COLS;
@@ -185,7 +189,10 @@ __global__ __launch_bounds__(256) void tree_project_sparse_kernel(TreeArgs t, co
           const int f = t.feature[q] - col_off;
           if (f < 0 || f >= c) continue;                     // node owned by another table
           const int slot = atomicAdd(&count[j], 1);
-          if (slot < TP_MAXPATH) list[j][slot] = static_cast<unsigned short>(q | (hv[u] < 0 ? 0x8000 : 0));
+          if (slot < TP_MAXPATH) {
+            ent[slot][j] = static_cast<unsigned int>(f) | (hv[u] < 0 ? 0x80000000u : 0u);
+            thr_l[slot][j] = t.thr[q];
+          }
         }
       }
   }
@@ -200,10 +207,9 @@ __global__ __launch_bounds__(256) void tree_project_sparse_kernel(TreeArgs t, co
       const float* dr = D + r * ldd;
       const int n = min(count[j], TP_MAXPATH);
       for (int e = 0; e < n; ++e) {
-        const int v = list[j][e];
-        const int q = v & 0x7fff;
-        const bool bit = dr[t.feature[q] - col_off] > t.thr[q];
-        agree += bit == ((v & 0x8000) == 0);
+        const unsigned int v = ent[e][j];
+        const bool bit = dr[v & 0x7fffffffu] > thr_l[e][j];
+        agree += bit == ((v & 0x80000000u) == 0u);
       }
     }
     out[r * t.ld + j0 + j] = static_cast<uint8_t>(min(agree, 255));
