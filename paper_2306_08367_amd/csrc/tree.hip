@@ -154,7 +154,7 @@ __global__ __launch_bounds__(256) void tree_project_bits_kernel(TreeArgs t, Proj
 // unsupported), so a workgroup first turns the H columns of its 64 leaves into per-leaf lists of the
 // nodes this dimension owns (node number, sign bit) in LDS and then walks only those lists for every
 // (dimension row, leaf): r * l * depth / K evaluations instead of r * l * p.
-constexpr int TP_COLS = 32;         // leaves per workgroup
+constexpr int TP_COLS = 8;          // leaves per workgroup (4: slower on large tables, 32: the lists are built four times as often)
 constexpr int TP_MAXPATH = 255;     // list capacity per leaf (longer paths are unsupported: a byte holds the count)
 // The lists hold, per entry, the column within the dimension table (bit 31: the path wants the test
 // false) and the threshold; entry e of all leaves lies side by side, so the lanes of a wavefront
