@@ -155,7 +155,11 @@ def main():
                          "gather_GBps": gather_bytes / (fused_ms * 1e-3) / 1e9,
                          # counter-measured L2-miss bytes per launch over this run's launch time: what the
                          # fabric (Infinity Cache + HBM) delivered; about 7.4 TB/s is what it sustains here
-                         "fabric_GBps": (measured_traffic("fused_c2") or 0.0) / (fused_ms * 1e-3) / 1e9},
+                         "fabric_GBps": (measured_traffic("fused_c2") or 0.0) / (fused_ms * 1e-3) / 1e9,
+                         # reads out of L2 plus fills into it: with every table L2-resident the same kernel
+                         # reads 21.9 TB/s out of L2 (768 B/row in 0.35 ms), the rate this sum also comes to
+                         "l2_reads_plus_fills_GBps": (gather_bytes + (measured_traffic("fused_c2") or 0.0))
+                                                     / (fused_ms * 1e-3) / 1e9},
             "stages": {"project_dims_ms": proj_ms, "fused_join_predict_ms": fused_ms,
                        "fused_rows_per_s": n / (fused_ms * 1e-3)},
         })
