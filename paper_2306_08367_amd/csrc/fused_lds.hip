@@ -14,7 +14,7 @@ namespace {
 constexpr int FL_THREADS = 1024;
 // rows per thread and step, 64 apart (lanes hold neighbouring rows); fewer for wider rows so that a
 // 1,024-thread workgroup stays within 128 registers per lane
-constexpr int fl_rows(int L) { return L == 1 ? 4 : 2; }
+constexpr int fl_rows(int L, int KT) { return (L == 1 && KT <= 4) ? 4 : 2; }
 constexpr int FL_MAX_CF = 8;            // fact columns (kept in registers)
 
 struct LdsPlan {
@@ -39,9 +39,9 @@ __device__ __forceinline__ void load_row(const float* p, float (&v)[L]) {
   }
 }
 
-template <int L, int KT>      // outputs; number of dimensions, 1..4
+template <int L, int KT>      // outputs; number of dimensions, 1..4 (1..8 at one output)
 __global__ __launch_bounds__(FL_THREADS) void fused_lds_kernel(PredictArgs a, LdsPlan pl) {
-  constexpr int R = fl_rows(L);
+  constexpr int R = fl_rows(L, KT);
   extern __shared__ __align__(16) float tab[];
   const int tid = threadIdx.x;
   for (int k = 0; k < KT; ++k)
@@ -174,16 +174,22 @@ __global__ __launch_bounds__(FL_THREADS) void fused_lds_kernel(PredictArgs a, Ld
 
 template <int L>
 int launch_l(const PredictArgs& a, const LdsPlan& pl, size_t lds, hipStream_t s) {
-  const int64_t need = (a.n + FL_THREADS * fl_rows(L) - 1) / (FL_THREADS * fl_rows(L));
-  const dim3 grid(static_cast<unsigned>(std::min<int64_t>(need, num_cus()))), block(FL_THREADS);
+  const dim3 block(FL_THREADS);
 #define LQ_FL(KT_)                                                                                      \
   do {                                                                                                  \
+    const int64_t need = (a.n + FL_THREADS * fl_rows(L, KT_) - 1) / (FL_THREADS * fl_rows(L, KT_));     \
+    const dim3 grid(static_cast<unsigned>(std::min<int64_t>(need, num_cus())));                         \
     if (lds > 64 * 1024)                                                                                \
       LQ_HIP_TRY(hipFuncSetAttribute(reinterpret_cast<const void*>(&fused_lds_kernel<L, KT_>),          \
                                      hipFuncAttributeMaxDynamicSharedMemorySize, static_cast<int>(lds))); \
     hipLaunchKernelGGL((fused_lds_kernel<L, KT_>), grid, block, lds, s, a, pl);                         \
   } while (0)
-  if (a.K == 1) LQ_FL(1); else if (a.K == 2) LQ_FL(2); else if (a.K == 3) LQ_FL(3); else LQ_FL(4);
+  if (a.K == 1) LQ_FL(1); else if (a.K == 2) LQ_FL(2); else if (a.K == 3) LQ_FL(3); else if (a.K == 4) LQ_FL(4);
+  else if constexpr (L == 1) {            // (five to eight tables: one output only, to stay within the registers)
+    if (a.K == 5) LQ_FL(5); else if (a.K == 6) LQ_FL(6); else if (a.K == 7) LQ_FL(7); else LQ_FL(8);
+  } else {
+    return -1;
+  }
 #undef LQ_FL
   LQ_LAUNCH_CHECK("fused_lds_kernel");
   return LQ_OK;
@@ -194,9 +200,10 @@ int launch_l(const PredictArgs& a, const LdsPlan& pl, size_t lds, hipStream_t s)
 // -1: the shape is not covered here.
 int try_fused_lds(const PredictArgs& a, hipStream_t s) {
   if (a.x_dtype != LQ_F32 || a.p_dtype != LQ_F32 || a.y_dtype != LQ_F32) return -1;
-  if (a.n_layers != 1 || a.K < 1 || a.K > 4 || a.c_f > FL_MAX_CF || a.n < (1 << 20)) return -1;
+  if (a.n_layers != 1 || a.K < 1 || a.K > 8 || a.c_f > FL_MAX_CF || a.n < (1 << 20)) return -1;
   const int L = a.wout[0];
   if (L != 1 && L != 2 && L != 4) return -1;
+  if (a.K > 4 && L != 1) return -1;
   if (!aligned(a.Y, 4) || (a.c_f > 0 && !aligned(a.X, 4))) return -1;
   LdsPlan pl{};
   int order[LQ_MAX_DIMS];

@@ -260,6 +260,8 @@ LDS_LINEAR = [
     ("l1_four_tables_no_fact_columns", 0, (2_556, 30_000, 2_000, 200), (8, 8, 8, 8), 1, False),
     ("l1_one_table_cf3", 3, (5_000,), (6,), 1, True),
     ("l1_cf8", 8, (300, 36_000), (5, 5), 1, True),
+    ("l1_six_tables", 4, (100, 2_000, 300, 5_000, 40, 90_000), (3, 4, 5, 6, 7, 8), 1, True),
+    ("l1_eight_tables_no_fact_columns", 0, (10, 20, 30, 40, 50, 60, 70, 8_000), (2, 2, 2, 2, 2, 2, 2, 2), 1, False),
     ("l2_two_tables_cf5", 5, (1_000, 17_000), (16, 16), 2, True),
     ("l2_four_tables", 4, (100, 200, 300, 40_000), (4, 4, 4, 4), 2, False),
     ("l4_three_tables", 4, (1_000, 8_000, 100_000), (8, 8, 8), 4, True),
