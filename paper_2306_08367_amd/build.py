@@ -27,8 +27,22 @@ def hipcc() -> str:
     return exe
 
 
-def _compile(src: str) -> str:
+def _fresh(obj: str, src: str) -> bool:
+    """True when `obj` is newer than its source and every header it may include."""
+    if not os.path.exists(obj):
+        return False
+    t = os.path.getmtime(obj)
+    deps = [os.path.join(CSRC, src), os.path.abspath(__file__)]
+    deps += [os.path.join(CSRC, f) for f in os.listdir(CSRC) if f.endswith(".h")]
+    inc = os.path.join(ROOT, "include")
+    deps += [os.path.join(inc, f) for f in os.listdir(inc)]
+    return all(os.path.getmtime(d) < t for d in deps)
+
+
+def _compile(src: str, only_changed: bool = False) -> str:
     obj = os.path.join(OBJDIR, os.path.splitext(src)[0] + ".o")
+    if only_changed and _fresh(obj, src):
+        return obj
     cmd = [hipcc(), *FLAGS, "-c", os.path.join(CSRC, src), "-o", obj]
     r = subprocess.run(cmd, capture_output=True, text=True)
     # hipcc's host pass warns that it does not know the packed-fp32 feature: harmless.
@@ -40,11 +54,12 @@ def _compile(src: str) -> str:
     return obj
 
 
-def build(verbose: bool = True) -> str:
-    """Compile every source and link liblq.so; always rebuilds."""
+def build(verbose: bool = True, only_changed: bool = False) -> str:
+    """Compile every source and link liblq.so.  Rebuilds everything unless `only_changed` is set
+    (a developer's shortcut: objects newer than their source and all headers are kept)."""
     os.makedirs(OBJDIR, exist_ok=True)
     with ThreadPoolExecutor(max_workers=min(8, len(SOURCES))) as ex:
-        objs = list(ex.map(_compile, SOURCES))
+        objs = list(ex.map(lambda src: _compile(src, only_changed), SOURCES))
     cmd = [hipcc(), "-shared", "-fPIC", f"--offload-arch={ARCH}", "-o", LIB, *objs]
     r = subprocess.run(cmd, capture_output=True, text=True)
     if r.returncode != 0:
@@ -55,4 +70,4 @@ def build(verbose: bool = True) -> str:
 
 
 if __name__ == "__main__":
-    build()
+    build(only_changed="--changed" in sys.argv[1:])
