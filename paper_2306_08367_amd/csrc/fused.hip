@@ -346,22 +346,25 @@ int try_fused_tile(const PredictArgs& a, hipStream_t s);
 int try_fused_deep(const PredictArgs& a, hipStream_t s);
 int try_fused_deep_bf16(const PredictArgs& a, hipStream_t s);
 int try_fused_lds(const PredictArgs& a, hipStream_t s);
+int try_fused_coltile(const PredictArgs& a, hipStream_t s);
 
 int launch_fused(const PredictArgs& a, hipStream_t s) {
   if (a.n == 0) return LQ_OK;
   int rc = try_rowbatch64(a, s);
   if (rc >= 0) return rc;
-  rc = try_fused_deep(a, s);          // three or four layers, or a second layer of 5..64 outputs
+  rc = try_fused_deep(a, s);          // three to eight layers, or a second layer of 5..128 outputs
   if (rc >= 0) return rc;
   rc = try_rowbatch_wide(a, s);
   if (rc >= 0) return rc;
   rc = try_fused_bf16(a, s);
   if (rc >= 0) return rc;
-  rc = try_fused_deep_bf16(a, s);     // bf16: three or four layers, or a second layer of 17..64 outputs
+  rc = try_fused_deep_bf16(a, s);     // bf16: three to eight layers, or a second layer of 17..256 outputs
   if (rc >= 0) return rc;
   rc = try_fused_lds(a, s);           // linear models with 1 / 2 / 4 outputs whose small projected tables fit LDS
   if (rc >= 0) return rc;
   rc = try_vec(a, s);
+  if (rc >= 0) return rc;
+  rc = try_fused_coltile(a, s);       // first layers wider than 256 (fp32) / 512 (bf16) columns, one or two layers
   if (rc >= 0) return rc;
   rc = try_fused_tile(a, s);
   if (rc >= 0) return rc;
