@@ -143,14 +143,23 @@ int lq_project_dim_rows(const lq_star* star, const lq_model* model, lq_mat* P, i
  *   ratio          = cost_no_fusion / cost_fusion                    (Eq. 3 for equal c_j, K = 3)
  *   cost_prefusion = sum_j r_j c_j l                                 (D_j M_j L, paid per update)
  *   memory_growth  = sum_j r_j l / sum_j r_j c_j                     (> 1 when l exceeds the columns, Q6)
- *   fuse           = 1 when queries_per_update * (cost_no_fusion - cost_fusion) > cost_prefusion
  * bytes_per_row_*  what one fact row moves in this library's kernels (one nonzero per row of I_k).
+ * seconds_*        the time model the decision uses.  The dense model above prices I_k as an n x r_k
+ *                  matrix and ends at "fuse when k > l" (Eq. 3); this library stores I_k as one key per
+ *                  fact row, so the fused join stage stays ahead well below k = l (its gathers come out
+ *                  of the caches while the non-fused pipeline writes T to memory and reads it back).
+ *                  Each pipeline is priced by what it streams, gathers and multiplies per fact row at
+ *                  the rates these kernels sustain on an MI355X (about 5 TB/s streamed, 14 TB/s
+ *                  gathered while the tables fit the Infinity Cache and 3 TB/s in 128-byte lines
+ *                  beyond it, 60 / 400 TFLOP/s fp32 / bf16 in the dense products, 4 us per launch).
+ *   fuse           = 1 when queries_per_update * (seconds_no_fusion - seconds_fused) > seconds_prefusion
  */
 typedef struct {
   double cost_no_fusion, cost_fusion, cost_prefusion;
   double ratio, ratio_leading_term, memory_growth;
   double bytes_per_row_fused, bytes_per_row_no_fusion;
   int32_t fuse;
+  double seconds_fused, seconds_no_fusion, seconds_prefusion;
 } lq_advice;
 int lq_fusion_advice(const lq_star* star, const lq_model* model, double queries_per_update,
                      lq_advice* out);
@@ -205,7 +214,9 @@ int lq_materialized_join_predict(const lq_star* star, const lq_model* model, lq_
  *   sums       int64 [n_measures x G], overwritten;  counts int64 [G] or NULL
  *   ws         lq_groupby_workspace_bytes(..) bytes, 256-byte aligned; holds the encoded side
  *              tables between calls for LQ_REUSE_SIDE_TABLES
- * A code outside [0, group_card[k]) on a surviving row is undefined behaviour.
+ * A code outside [0, group_card[k]) on a dimension row that passes its mask is undefined behaviour
+ * unless LQ_CHECK_FKS is set: the checked call also verifies the codes (r_k reads per dimension)
+ * and returns LQ_ERR_SHAPE for such a code without touching the outputs.
  */
 int lq_masked_groupby_sum(int64_t n_fact, int32_t n_dims, const int32_t* const* fks,
                           const int64_t* dim_rows, const uint8_t* const* dim_mask,

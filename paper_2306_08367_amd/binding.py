@@ -60,7 +60,8 @@ class lq_sort_key(ctypes.Structure):
 class lq_advice(ctypes.Structure):
     _fields_ = [(n, ctypes.c_double) for n in ("cost_no_fusion", "cost_fusion", "cost_prefusion", "ratio",
                                                "ratio_leading_term", "memory_growth", "bytes_per_row_fused",
-                                               "bytes_per_row_no_fusion")] + [("fuse", ctypes.c_int32)]
+                                               "bytes_per_row_no_fusion")] + [("fuse", ctypes.c_int32)] + [
+        (n, ctypes.c_double) for n in ("seconds_fused", "seconds_no_fusion", "seconds_prefusion")]
 
 
 class lq_tree(ctypes.Structure):
@@ -220,6 +221,16 @@ def _stream(stream) -> Optional[int]:
     return int(stream.cuda_stream) or None
 
 
+def _empty(stream, *shape, **kw) -> torch.Tensor:
+    """torch.empty for outputs and workspaces of a call that runs on `stream`.  torch hands a freed block to
+    the next allocation on the stream it was allocated on; when the kernels run on another stream the block is
+    marked as in use there, so that it is not recycled while they still read or write it."""
+    t = torch.empty(*shape, **kw)
+    if stream is not None and t.is_cuda and t.numel() > 0:
+        t.record_stream(stream)
+    return t
+
+
 def _expect(t: torch.Tensor, dtype, what: str):
     if t.dtype != dtype:
         raise TypeError(f"{what} must be {dtype}, got {t.dtype}")
@@ -267,7 +278,7 @@ def lq_project_dims(dims: Sequence[torch.Tensor], W0: torch.Tensor, c_f: int,
     """P_k = D_k times its rows of W0 (pre-fusion stage).  Allocates P unless given."""
     if P is None:
         pd = p_dtype or torch.float32
-        P = [torch.empty((d.shape[0], W0.shape[1]), dtype=pd, device=d.device) for d in dims]
+        P = [_empty(stream, (d.shape[0], W0.shape[1]), dtype=pd, device=d.device) for d in dims]
     fact = lq_mat(None, 0, int(c_f), max(int(c_f), 1), _dtype_code(W0))
     dims_arr = _mat_array(dims)
     star = lq_star(0, fact, len(dims), dims_arr, _ptr_array([None] * len(dims)))
@@ -286,9 +297,9 @@ def lq_fused_join_predict(X: Optional[torch.Tensor], fks: Sequence[torch.Tensor]
     n = _n_of(X, fks)
     dev = weights[0].device
     if Y is None:
-        Y = torch.empty((n, weights[-1].shape[1]), dtype=y_dtype or weights[0].dtype, device=dev)
+        Y = _empty(stream, (n, weights[-1].shape[1]), dtype=y_dtype or weights[0].dtype, device=dev)
     if ws is None and (flags & LQ_CHECK_FKS):
-        ws = torch.empty(256, dtype=torch.uint8, device=dev)
+        ws = _empty(stream, 256, dtype=torch.uint8, device=dev)
     star = _Star(n, X, None, fks)
     model = _Model(weights, biases)
     P_arr = _mat_array(P)
@@ -317,11 +328,11 @@ def lq_materialized_join_predict(X: Optional[torch.Tensor], dims: Sequence[torch
     n = _n_of(X, fks)
     dev = weights[0].device
     if Y is None:
-        Y = torch.empty((n, weights[-1].shape[1]), dtype=y_dtype or weights[0].dtype, device=dev)
+        Y = _empty(stream, (n, weights[-1].shape[1]), dtype=y_dtype or weights[0].dtype, device=dev)
     if ws is None:
         rows = chunk_rows or min(max(n, 256), 1 << 22)
         nbytes = lq_workspace_bytes(LQ_CALL_MATERIALIZED, int(weights[0].shape[0]), weights, rows)
-        ws = torch.empty(nbytes, dtype=torch.uint8, device=dev)
+        ws = _empty(stream, nbytes, dtype=torch.uint8, device=dev)
     star = _Star(n, X, dims, fks)
     model = _Model(weights, biases)
     Ym = _mat(Y)
@@ -373,11 +384,11 @@ def lq_masked_groupby_sum(fks: Sequence[torch.Tensor], dim_rows: Sequence[int],
         if codes[k] is not None:
             G *= int(group_card[k])
     if sums is None:
-        sums = torch.empty((len(measures), G), dtype=torch.int64, device=dev)
+        sums = _empty(stream, (len(measures), G), dtype=torch.int64, device=dev)
     if counts is None and want_counts:
-        counts = torch.empty((G,), dtype=torch.int64, device=dev)
+        counts = _empty(stream, (G,), dtype=torch.int64, device=dev)
     if ws is None:
-        ws = torch.empty(lq_groupby_workspace_bytes(dim_rows, group_card, len(measures)),
+        ws = _empty(stream, lq_groupby_workspace_bytes(dim_rows, group_card, len(measures)),
                          dtype=torch.uint8, device=dev)
     rows = (ctypes.c_int64 * max(1, K))(*[int(r) for r in dim_rows])
     card = (ctypes.c_int32 * max(1, K))(*[int(c) for c in group_card])
@@ -417,8 +428,8 @@ def lq_tree_project_dims(dims: Sequence[torch.Tensor], c_f: int, feature, thresh
     tree = _tree(feature, threshold, H)
     ld = lq_tree_table_ld(tree.n_leaves)
     dev = H.device
-    tables = [torch.empty((d.shape[0], ld), dtype=torch.uint8, device=dev) for d in dims]
-    target = torch.empty((ld,), dtype=torch.uint8, device=dev)
+    tables = [_empty(stream, (d.shape[0], ld), dtype=torch.uint8, device=dev) for d in dims]
+    target = _empty(stream, (ld,), dtype=torch.uint8, device=dev)
     fact = lq_mat(None, 0, int(c_f), max(int(c_f), 1), LQ_F32)
     dims_arr = _mat_array(dims)
     star = lq_star(0, fact, len(dims), dims_arr, _ptr_array([None] * len(dims)))
@@ -435,14 +446,14 @@ def lq_fused_join_tree(X: Optional[torch.Tensor], fks: Sequence[torch.Tensor], t
     tree = _tree(feature, threshold, H)
     n = _n_of(X, fks)
     dev = H.device
-    leaf = torch.empty((n,), dtype=torch.int32, device=dev) if want_leaf else None
-    onehot = torch.empty((n, tree.n_leaves), dtype=torch.uint8, device=dev) if want_onehot else None
+    leaf = _empty(stream, (n,), dtype=torch.int32, device=dev) if want_leaf else None
+    onehot = _empty(stream, (n, tree.n_leaves), dtype=torch.uint8, device=dev) if want_onehot else None
     star = _Star(n, X, None, fks)
     ws = None
     if flags & LQ_CHECK_FKS:
         rows_arr = (lq_mat * max(1, len(tables)))(*[lq_mat(None, int(t.shape[0]), 1, 1, LQ_F32) for t in tables])
         star.c.dims = rows_arr
-        ws = torch.empty(256, dtype=torch.uint8, device=dev)
+        ws = _empty(stream, 256, dtype=torch.uint8, device=dev)
     _check(_lib.lq_fused_join_tree(ctypes.byref(star.c), ctypes.byref(tree), _ptr_array(tables),
                                    target.data_ptr(), None if leaf is None else leaf.data_ptr(),
                                    None if onehot is None else onehot.data_ptr(), flags,
@@ -460,7 +471,7 @@ def lq_tree_compress_tables(dims: Sequence[torch.Tensor], tables, feature, thres
     tree = _tree(feature, threshold, H)
     words = lq_tree_mask_words(tree.n_leaves)
     dev = H.device
-    masks = [torch.empty((d.shape[0], words), dtype=torch.int64, device=dev) for d in dims]
+    masks = [_empty(stream, (d.shape[0], words), dtype=torch.int64, device=dev) for d in dims]
     fact = lq_mat(None, 0, int(c_f), max(int(c_f), 1), LQ_F32)
     dims_arr = _mat_array(dims)
     star = lq_star(0, fact, len(dims), dims_arr, _ptr_array([None] * len(dims)))
@@ -488,7 +499,7 @@ def lq_tree_fact_mask_bytes(n_nodes: int, n_leaves: int) -> int:
 def lq_tree_fact_masks(c_f: int, feature, threshold, H, stream=None):
     """Packed mask rows (opaque uint8 buffer) of the nodes that test the fact table's own columns."""
     tree = _tree(feature, threshold, H)
-    buf = torch.empty((lq_tree_fact_mask_bytes(tree.n_nodes, tree.n_leaves),), dtype=torch.uint8, device=H.device)
+    buf = _empty(stream, (lq_tree_fact_mask_bytes(tree.n_nodes, tree.n_leaves),), dtype=torch.uint8, device=H.device)
     _check(_lib.lq_tree_fact_masks(int(c_f), ctypes.byref(tree), buf.data_ptr(), _stream(stream)))
     return buf
 
@@ -501,8 +512,8 @@ def lq_fused_join_tree_masks(fks: Sequence[torch.Tensor], masks, feature, thresh
     tree = _tree(feature, threshold, H)
     n = _n_of(X, fks)
     dev = H.device
-    leaf = torch.empty((n,), dtype=torch.int32, device=dev) if want_leaf else None
-    onehot = torch.empty((n, tree.n_leaves), dtype=torch.uint8, device=dev) if want_onehot else None
+    leaf = _empty(stream, (n,), dtype=torch.int32, device=dev) if want_leaf else None
+    onehot = _empty(stream, (n, tree.n_leaves), dtype=torch.uint8, device=dev) if want_onehot else None
     star = _Star(n, X, None, fks)
     # row counts of the mask tables (the library may then keep small tables in LDS); no data pointers
     rows_arr = (lq_mat * max(1, len(masks)))(*[lq_mat(None, int(m.shape[0]), 1, 1, LQ_F32) for m in masks])
@@ -522,12 +533,12 @@ def lq_materialized_join_tree(X: Optional[torch.Tensor], dims, fks, feature, thr
     tree = _tree(feature, threshold, H)
     n = _n_of(X, fks)
     dev = H.device
-    leaf = torch.empty((n,), dtype=torch.int32, device=dev) if want_leaf else None
-    onehot = torch.empty((n, tree.n_leaves), dtype=torch.uint8, device=dev) if want_onehot else None
+    leaf = _empty(stream, (n,), dtype=torch.int32, device=dev) if want_leaf else None
+    onehot = _empty(stream, (n, tree.n_leaves), dtype=torch.uint8, device=dev) if want_onehot else None
     star = _Star(n, X, dims, fks)
     if ws is None:
         rows = chunk_rows or min(max(n, 256), 1 << 22)
-        ws = torch.empty(int(_lib.lq_tree_workspace_bytes(ctypes.byref(star.c), ctypes.byref(tree), rows)), dtype=torch.uint8,
+        ws = _empty(stream, int(_lib.lq_tree_workspace_bytes(ctypes.byref(star.c), ctypes.byref(tree), rows)), dtype=torch.uint8,
                          device=dev)
     _check(_lib.lq_materialized_join_tree(ctypes.byref(star.c), ctypes.byref(tree),
                                           None if leaf is None else leaf.data_ptr(),
@@ -546,7 +557,7 @@ def lq_keymap_build(keys: torch.Tensor, max_keys: Optional[int] = None, flags: i
     """Hash map from the key values of a dimension to its row numbers; returns the map buffer."""
     _expect(keys, torch.int32, "dimension key column")
     nbytes = lq_keymap_bytes(max(int(keys.shape[0]), max_keys or 0))
-    table = torch.empty(nbytes, dtype=torch.uint8, device=keys.device)
+    table = _empty(stream, nbytes, dtype=torch.uint8, device=keys.device)
     _check(_lib.lq_keymap_build(table.data_ptr(), nbytes, keys.data_ptr(), int(keys.shape[0]), flags, _stream(stream)))
     return table
 
@@ -562,7 +573,7 @@ def lq_keymap_lookup(table: torch.Tensor, fact_keys: torch.Tensor, fk: Optional[
     """fk[i] = dimension row whose key equals fact_keys[i], -1 where there is none."""
     _expect(fact_keys, torch.int32, "fact key column")
     if fk is None:
-        fk = torch.empty_like(fact_keys)
+        fk = _empty(stream, fact_keys.shape, dtype=fact_keys.dtype, device=fact_keys.device)
     _check(_lib.lq_keymap_lookup(table.data_ptr(), table.numel(), fact_keys.data_ptr(),
                                  int(fact_keys.shape[0]), fk.data_ptr(), _stream(stream)))
     return fk
@@ -576,7 +587,7 @@ def lq_keymap64_build(keys: torch.Tensor, max_keys: Optional[int] = None, flags:
     """Map from the int64 key values of a dimension to its row numbers; returns the map buffer."""
     _expect(keys, torch.int64, "dimension key column")
     nbytes = lq_keymap64_bytes(max(int(keys.shape[0]), max_keys or 0))
-    table = torch.empty(nbytes, dtype=torch.uint8, device=keys.device)
+    table = _empty(stream, nbytes, dtype=torch.uint8, device=keys.device)
     _check(_lib.lq_keymap64_build(table.data_ptr(), nbytes, keys.data_ptr(), int(keys.shape[0]), flags, _stream(stream)))
     return table
 
@@ -592,7 +603,7 @@ def lq_keymap64_lookup(table: torch.Tensor, fact_keys: torch.Tensor, fk: Optiona
     """fk[i] = dimension row whose key equals fact_keys[i] (int64), -1 where there is none."""
     _expect(fact_keys, torch.int64, "fact key column")
     if fk is None:
-        fk = torch.empty(fact_keys.shape, dtype=torch.int32, device=fact_keys.device)
+        fk = _empty(stream, fact_keys.shape, dtype=torch.int32, device=fact_keys.device)
     _check(_lib.lq_keymap64_lookup(table.data_ptr(), table.numel(), fact_keys.data_ptr(),
                                    int(fact_keys.shape[0]), fk.data_ptr(), _stream(stream)))
     return fk
@@ -603,10 +614,10 @@ def lq_compact_matches(fk: torch.Tensor, stream=None):
     only the first nnz entries of rows / cols are meaningful."""
     _expect(fk, torch.int32, "mapped key column")
     n = int(fk.shape[0])
-    rows = torch.empty(n, dtype=torch.int64, device=fk.device)
-    cols = torch.empty(n, dtype=torch.int32, device=fk.device)
-    nnz = torch.empty(1, dtype=torch.int64, device=fk.device)
-    ws = torch.empty(int(_lib.lq_compact_workspace_bytes(n)), dtype=torch.uint8, device=fk.device)
+    rows = _empty(stream, n, dtype=torch.int64, device=fk.device)
+    cols = _empty(stream, n, dtype=torch.int32, device=fk.device)
+    nnz = _empty(stream, 1, dtype=torch.int64, device=fk.device)
+    ws = _empty(stream, int(_lib.lq_compact_workspace_bytes(n)), dtype=torch.uint8, device=fk.device)
     _check(_lib.lq_compact_matches(fk.data_ptr(), n, rows.data_ptr(), cols.data_ptr(), nnz.data_ptr(),
                                    ws.data_ptr(), ws.numel(), _stream(stream)))
     return rows, cols, nnz
@@ -627,9 +638,9 @@ def lq_group_domain(cols: Sequence[torch.Tensor], max_card: int = 65535, stream=
             raise ValueError("attribute columns differ in length")
     rows = int(cols[0].shape[0])
     dev = cols[0].device
-    code = torch.empty(rows, dtype=torch.int32, device=dev)
-    values = torch.empty((int(max_card), len(cols)), dtype=torch.int32, device=dev)
-    ws = torch.empty(lq_group_domain_workspace_bytes(rows), dtype=torch.uint8, device=dev)
+    code = _empty(stream, rows, dtype=torch.int32, device=dev)
+    values = _empty(stream, (int(max_card), len(cols)), dtype=torch.int32, device=dev)
+    ws = _empty(stream, lq_group_domain_workspace_bytes(rows), dtype=torch.uint8, device=dev)
     card = ctypes.c_int32(0)
     _check(_lib.lq_group_domain(rows, len(cols), _ptr_array(cols), int(max_card), code.data_ptr(),
                                 values.data_ptr(), ctypes.byref(card), ws.data_ptr(), ws.numel(), _stream(stream)))
@@ -659,9 +670,9 @@ def lq_order_groups(group_card: Sequence[int], sums: Optional[torch.Tensor], cou
     for q, (kind, index, desc) in enumerate(keys):
         karr[q] = lq_sort_key(int(kind), int(index), int(bool(desc)))
     if order is None:
-        order = torch.empty(G, dtype=torch.int32, device=counts.device)
+        order = _empty(stream, G, dtype=torch.int32, device=counts.device)
     if n_out is None:
-        n_out = torch.empty(1, dtype=torch.int32, device=counts.device)
+        n_out = _empty(stream, 1, dtype=torch.int32, device=counts.device)
     _expect(order, torch.int32, "order")
     _expect(n_out, torch.int32, "n_out")
     if order.numel() < G or n_out.numel() < 1:
@@ -741,12 +752,12 @@ def lq_groupby_agg(fks: Sequence[torch.Tensor], dim_rows: Sequence[int], dim_mas
         ma[m] = lq_measure(_MEASURE_OPS[op], a.data_ptr(), None if b is None else b.data_ptr())
     out = {}
     for name in ("sum", "min", "max"):
-        out[name] = torch.empty((M, G), dtype=torch.int64, device=dev) if name in want else None
-    out["count"] = torch.empty((G,), dtype=torch.int64, device=dev) if "count" in want else None
+        out[name] = _empty(stream, (M, G), dtype=torch.int64, device=dev) if name in want else None
+    out["count"] = _empty(stream, (G,), dtype=torch.int64, device=dev) if "count" in want else None
     rows = (ctypes.c_int64 * max(1, K))(*[int(r) for r in dim_rows])
     card = (ctypes.c_int32 * max(1, K))(*[int(c) for c in group_card])
     if ws is None:
-        ws = torch.empty(int(_lib.lq_groupby_agg_workspace_bytes(K, rows, card, M)), dtype=torch.uint8, device=dev)
+        ws = _empty(stream, int(_lib.lq_groupby_agg_workspace_bytes(K, rows, card, M)), dtype=torch.uint8, device=dev)
     ptr = lambda t: None if t is None else t.data_ptr()
     _check(_lib.lq_groupby_agg(n, K, _ptr_array(fks), rows, _ptr_array(masks), _ptr_array(codes), card,
                                len(preds), pa, M, ma, ptr(out["sum"]), ptr(out["min"]), ptr(out["max"]),

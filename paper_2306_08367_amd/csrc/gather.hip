@@ -90,6 +90,29 @@ __global__ __launch_bounds__(256) void check_fks_kernel(CheckArgs a, int32_t* fl
   if (bad) atomicOr(flag, 1);
 }
 
+// Group codes of the dimension side: bit 1 of the flag is raised for a code outside [0, card) on a
+// dimension row whose mask lets it through (rows that are filtered out are never looked up).
+struct CodeCheckArgs {
+  int32_t K;
+  const uint8_t* mask[LQ_MAX_DIMS];
+  const int32_t* code[LQ_MAX_DIMS];
+  int64_t rows[LQ_MAX_DIMS];
+  int32_t card[LQ_MAX_DIMS];
+};
+
+__global__ __launch_bounds__(256) void check_codes_kernel(CodeCheckArgs a, int32_t* flag) {
+  const int64_t stride = static_cast<int64_t>(gridDim.x) * blockDim.x;
+  int bad = 0;
+  for (int k = 0; k < a.K; ++k) {
+    if (!a.code[k]) continue;
+    for (int64_t j = static_cast<int64_t>(blockIdx.x) * blockDim.x + threadIdx.x; j < a.rows[k]; j += stride) {
+      const int32_t v = a.code[k][j];
+      if ((v < 0 || v >= a.card[k]) && (!a.mask[k] || a.mask[k][j])) bad = 1;
+    }
+  }
+  if (bad) atomicOr(flag, 2);
+}
+
 __global__ __launch_bounds__(256) void zero_flag_kernel(int32_t* flag) {
   if (threadIdx.x == 0 && blockIdx.x == 0) *flag = 0;
 }
@@ -165,6 +188,26 @@ int launch_check_fks(int64_t n, int32_t K, const int32_t* const* fks, const int6
     hipLaunchKernelGGL(check_fks_kernel, dim3(static_cast<unsigned>(blocks)), dim3(256), 0, s, a, d_flag);
     LQ_LAUNCH_CHECK("check_fks_kernel");
   }
+  return LQ_OK;
+}
+
+// Must follow launch_check_fks on the same stream (which clears the flag word).
+int launch_check_codes(int32_t K, const int64_t* rows, const uint8_t* const* mask, const int32_t* const* code,
+                       const int32_t* card, int32_t* d_flag, hipStream_t s) {
+  CodeCheckArgs a{};
+  a.K = K;
+  int64_t most = 0;
+  for (int k = 0; k < K; ++k) {
+    a.mask[k] = mask ? mask[k] : nullptr;
+    a.code[k] = code ? code[k] : nullptr;
+    a.rows[k] = rows[k];
+    a.card[k] = (code && code[k] && card) ? card[k] : 1;
+    if (a.code[k]) most = std::max(most, rows[k]);
+  }
+  if (most == 0) return LQ_OK;
+  const int64_t blocks = std::min<int64_t>((most + 255) / 256, static_cast<int64_t>(num_cus()) * 8);
+  hipLaunchKernelGGL(check_codes_kernel, dim3(static_cast<unsigned>(blocks)), dim3(256), 0, s, a, d_flag);
+  LQ_LAUNCH_CHECK("check_codes_kernel");
   return LQ_OK;
 }
 

@@ -163,11 +163,25 @@ int run_fk_check(int64_t n, int32_t K, const int32_t* const* fks, const int64_t*
 
 // Group-by calls keep the packed side tables at the start of their workspace (and may be asked to
 // reuse them), so the check's flag word goes behind them, into the partial-sum area that the scan
-// overwrites afterwards.
-int check_groupby_fks(int64_t n, int32_t K, const int32_t* const* fks, const int64_t* rows, void* ws,
+// overwrites afterwards.  Besides the keys, the check covers the group codes of the dimension side:
+// a code outside [0, group_card) on a row that passes its mask would address an accumulator that
+// does not exist.
+int check_groupby_fks(int64_t n, int32_t K, const int32_t* const* fks, const int64_t* rows,
+                      const uint8_t* const* mask, const int32_t* const* code, const int32_t* card, void* ws,
                       size_t ws_bytes, hipStream_t s) {
   const size_t off = groupby_tables_bytes(K, rows);
-  return run_fk_check(n, K, fks, rows, true, static_cast<uint8_t*>(ws) + off, ws_bytes - off, s);
+  if (!ws || ws_bytes < off + 256 || !aligned(ws, 256))
+    return fail(LQ_ERR_WORKSPACE, "LQ_CHECK_FKS needs a 256-byte aligned workspace of >= 256 bytes");
+  int32_t* flag = reinterpret_cast<int32_t*>(static_cast<uint8_t*>(ws) + off);
+  int rc = launch_check_fks(n, K, fks, rows, true, flag, s);
+  if (rc) return rc;
+  if ((rc = launch_check_codes(K, rows, mask, code, card, flag, s))) return rc;
+  int32_t h = 0;
+  LQ_HIP_TRY(hipMemcpyAsync(&h, flag, sizeof(h), hipMemcpyDeviceToHost, s));
+  LQ_HIP_TRY(hipStreamSynchronize(s));
+  if (h & 1) return fail(LQ_ERR_FK_RANGE, "a foreign key lies outside its dimension table");
+  if (h & 2) return fail(LQ_ERR_SHAPE, "a group code lies outside [0, group_card) on a dimension row that passes its mask");
+  return LQ_OK;
 }
 
 constexpr uint32_t FLAG_FORCE_GENERIC = 0x100u;   // testing aid, see lq_fused_join_predict
@@ -257,8 +271,40 @@ int lq_fusion_advice(const lq_star* star, const lq_model* model, double queries_
                              es * l * star->n_dims + es * c.l_out;
   out->bytes_per_row_no_fusion = es * (star->fact.cols > 0 ? star->fact.cols : 0) + 4.0 * star->n_dims +
                                  es * (k - (star->fact.cols > 0 ? star->fact.cols : 0)) + 2.0 * es * k + es * c.l_out;
-  const double gain = queries_per_update * (out->cost_no_fusion - out->cost_fusion);
-  out->fuse = gain > out->cost_prefusion ? 1 : 0;
+  // The decision.  The dense model above prices I_k as an n x r_k matrix; here I_k is one key per
+  // fact row, so what decides is what the two pipelines of this library move and multiply per fact
+  // row, at the rates they sustain on an MI355X (measured with this library's own kernels):
+  //   streamed bytes (fact columns, keys, outputs, T written and read back)   ~5 TB/s
+  //   gathered bytes (rows of P_k or D_k; from L2 / the 256 MB Infinity Cache while the tables fit
+  //   in half of it, else whole 128-byte lines from memory)                    ~14 TB/s / ~3 TB/s
+  //   dense products                                                           ~60 TFLOP/s fp32, ~400 bf16
+  //   a kernel launch                                                          ~4 us
+  const double c_f = star->fact.cols > 0 ? star->fact.cols : 0;
+  const double K = star->n_dims;
+  constexpr double STREAM = 5.0e12, CACHE_GATHER = 14.0e12, MEMORY_GATHER = 3.0e12, LAUNCH = 4.0e-6;
+  constexpr double CACHE_BYTES = 128.0 * 1024 * 1024;
+  const double dense = c.dtype == LQ_BF16 ? 400.0e12 : 60.0e12;
+  double later_flops = 0, later_bytes = 0;     // layers after the first: same products in both pipelines,
+  for (int j = 1; j < model->n_layers; ++j) {  // but the non-fused one moves every activation through memory
+    later_flops += 2.0 * static_cast<double>(model->W[j].rows) * model->W[j].cols;
+    later_bytes += 2.0 * es * static_cast<double>(model->W[j].rows);
+  }
+  auto gather_seconds = [&](double row_bytes, double table_bytes) {
+    if (table_bytes <= CACHE_BYTES) return row_bytes / CACHE_GATHER;
+    return std::max(row_bytes, 128.0) / MEMORY_GATHER;
+  };
+  double gather_f = 0, gather_n = 0;           // one row of P_j / of D_j per dimension and fact row
+  for (int j = 0; j < star->n_dims; ++j) {
+    gather_f += gather_seconds(es * l, p_elems * es);
+    gather_n += gather_seconds(es * star->dims[j].cols, dim_elems * es);
+  }
+  const double stream_f = es * c_f + 4.0 * K + es * c.l_out;
+  const double stream_n = es * c_f + 4.0 * K + 2.0 * es * k + later_bytes + es * c.l_out;
+  out->seconds_fused = n * (stream_f / STREAM + gather_f + later_flops / dense) + LAUNCH;
+  out->seconds_no_fusion = n * (stream_n / STREAM + gather_n + (2.0 * k * l + later_flops) / dense) +
+                           (1.0 + model->n_layers) * LAUNCH;
+  out->seconds_prefusion = (dim_elems + p_elems) * es / STREAM + 2.0 * prefuse / dense + LAUNCH;
+  out->fuse = queries_per_update * (out->seconds_no_fusion - out->seconds_fused) > out->seconds_prefusion ? 1 : 0;
   return LQ_OK;
 }
 
@@ -400,13 +446,13 @@ size_t lq_groupby_workspace_bytes(int32_t n_dims, const int64_t* dim_rows, const
   return groupby_ws_bytes(n_dims, dim_rows, G * (n_measures + 1));
 }
 
-int lq_masked_groupby_sum(int64_t n_fact, int32_t n_dims, const int32_t* const* fks,
-                          const int64_t* dim_rows, const uint8_t* const* dim_mask,
-                          const int32_t* const* dim_code, const int32_t* group_card,
-                          const uint8_t* fact_mask, int32_t n_measures,
-                          const int32_t* const* measures, int64_t* sums, int64_t* counts, void* ws,
-                          size_t ws_bytes, uint32_t flags, void* hip_stream) {
-  clear_error();
+// Validation and launch shared by lq_masked_groupby_sum and its allocation-free variant.
+static int groupby_sum_checked(int64_t n_fact, int32_t n_dims, const int32_t* const* fks,
+                               const int64_t* dim_rows, const uint8_t* const* dim_mask,
+                               const int32_t* const* dim_code, const int32_t* group_card,
+                               const uint8_t* fact_mask, int32_t n_measures,
+                               const int32_t* const* measures, int64_t* sums, int64_t* counts, void* ws,
+                               size_t ws_bytes, uint32_t flags, void* hip_stream) {
   if (n_fact < 0) return fail(LQ_ERR_SHAPE, "n_fact < 0");
   if (n_dims < 0 || n_dims > LQ_MAX_DIMS) return fail(LQ_ERR_SHAPE, "n_dims %d outside 0..%d", n_dims, LQ_MAX_DIMS);
   if (n_measures < 1 || n_measures > LQ_MAX_MEASURES)
@@ -442,10 +488,21 @@ int lq_masked_groupby_sum(int64_t n_fact, int32_t n_dims, const int32_t* const* 
   hipStream_t s = static_cast<hipStream_t>(hip_stream);
   int rc;
   if ((flags & LQ_CHECK_FKS) && n_dims > 0 && n_fact > 0)
-    if ((rc = check_groupby_fks(n_fact, n_dims, fks, dim_rows, ws, ws_bytes, s))) return rc;
+    if ((rc = check_groupby_fks(n_fact, n_dims, fks, dim_rows, dim_mask, dim_code, group_card, ws, ws_bytes, s))) return rc;
   return launch_groupby(n_fact, n_dims, fks, dim_rows, dim_mask, dim_code, group_card, fact_mask,
                         n_measures, measures, sums, counts, static_cast<int32_t>(G), ws,
                         (flags & LQ_REUSE_SIDE_TABLES) != 0, s);
+}
+
+int lq_masked_groupby_sum(int64_t n_fact, int32_t n_dims, const int32_t* const* fks,
+                          const int64_t* dim_rows, const uint8_t* const* dim_mask,
+                          const int32_t* const* dim_code, const int32_t* group_card,
+                          const uint8_t* fact_mask, int32_t n_measures,
+                          const int32_t* const* measures, int64_t* sums, int64_t* counts, void* ws,
+                          size_t ws_bytes, uint32_t flags, void* hip_stream) {
+  clear_error();
+  return groupby_sum_checked(n_fact, n_dims, fks, dim_rows, dim_mask, dim_code, group_card, fact_mask,
+                             n_measures, measures, sums, counts, ws, ws_bytes, flags, hip_stream);
 }
 
 size_t lq_groupby_agg_workspace_bytes(int32_t n_dims, const int64_t* dim_rows, const int32_t* group_card,
@@ -506,7 +563,7 @@ int lq_groupby_agg(int64_t n_fact, int32_t n_dims, const int32_t* const* fks, co
   hipStream_t s = static_cast<hipStream_t>(hip_stream);
   int rc;
   if ((flags & LQ_CHECK_FKS) && n_dims > 0 && n_fact > 0)
-    if ((rc = check_groupby_fks(n_fact, n_dims, fks, dim_rows, ws, ws_bytes, s))) return rc;
+    if ((rc = check_groupby_fks(n_fact, n_dims, fks, dim_rows, dim_mask, dim_code, group_card, ws, ws_bytes, s))) return rc;
   return launch_groupby_agg(n_fact, n_dims, fks, dim_rows, dim_mask, dim_code, group_card, n_preds, preds,
                             n_measures, measures, sums, mins, maxs, counts, static_cast<int32_t>(G), ws,
                             (flags & LQ_REUSE_SIDE_TABLES) != 0, s);

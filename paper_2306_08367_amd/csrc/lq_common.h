@@ -76,6 +76,8 @@ int launch_materialize(const lq_star& star, void* T, int64_t ldt, int64_t row0, 
                        hipStream_t s);
 int launch_check_fks(int64_t n, int32_t K, const int32_t* const* fks, const int64_t* rows,
                      bool negative_ok, int32_t* d_flag, hipStream_t s);
+int launch_check_codes(int32_t K, const int64_t* rows, const uint8_t* const* mask, const int32_t* const* code,
+                       const int32_t* card, int32_t* d_flag, hipStream_t s);
 int launch_copy(void* dst, const void* src, size_t bytes, hipStream_t s);
 
 // ---- device side -------------------------------------------------------------------------

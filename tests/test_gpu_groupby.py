@@ -172,6 +172,61 @@ def test_check_fks_flag(lq):
     _gpu(lq, w, flags=lq.LQ_CHECK_FKS)
 
 
+def test_check_flag_also_covers_the_group_codes(lq):
+    """A code outside [0, group_card) on a dimension row that passes its mask would address an accumulator
+    that does not exist: the checked call reports it (outputs untouched); the same code on a row that its
+    mask filters out is never looked up and is fine."""
+    w = _random_groupby(41, 9_000, (50, 60), (5, 6), sel=(1.0,))
+    want_s, want_c = _oracle(w)
+    w = to_dev(w)
+    sums = torch.full((2, 30), 7, dtype=torch.int64, device="cuda")
+    for bad in (6, 1 << 20, -1):
+        code = w.dim_code[1].clone()
+        code[17] = bad
+        w2 = WL.GroupByWorkload("bad", w.n, w.fks, w.dim_rows, w.dim_mask, [w.dim_code[0], code], w.group_card,
+                                w.fact_mask, w.measures)
+        with pytest.raises(lq.LQError) as e:
+            _gpu(lq, w2, sums=sums, flags=lq.LQ_CHECK_FKS)
+        assert e.value.status == "LQ_ERR_SHAPE" and "group code" in str(e.value)
+        torch.cuda.synchronize()
+        assert (sums == 7).all()
+    # the offending row filtered out by its mask: accepted, and the result is the oracle's for that mask
+    mask = w.dim_mask[1].clone()
+    mask[17] = 0
+    code = w.dim_code[1].clone()
+    code[17] = 1 << 20
+    w3 = WL.GroupByWorkload("masked", w.n, w.fks, w.dim_rows, [w.dim_mask[0], mask], [w.dim_code[0], code],
+                            w.group_card, w.fact_mask, w.measures)
+    s, c = _gpu(lq, w3, flags=lq.LQ_CHECK_FKS)
+    code_ok = w.dim_code[1].clone()
+    w4 = WL.GroupByWorkload("masked_ok", w.n, cpu_list(w.fks), w.dim_rows, cpu_list([w.dim_mask[0], mask]),
+                            cpu_list([w.dim_code[0], code_ok]), w.group_card, w.fact_mask.cpu(), cpu_list(w.measures))
+    ws, wc = _oracle(w4)
+    np.testing.assert_array_equal(s, ws)
+    np.testing.assert_array_equal(c, wc)
+
+
+def test_call_on_a_side_stream_keeps_its_temporaries(lq):
+    """The binding allocates the workspace and the outputs itself; the kernels run on the caller's stream.
+    Allocating and overwriting on the default stream right after the call must not hand those blocks out
+    again while the side stream still uses them."""
+    w = WL.c3_groupby(n=2_000_003)
+    want_s, want_c = _oracle(w)
+    w = to_dev(w)
+    torch.cuda.synchronize()
+    side = torch.cuda.Stream()
+    for _ in range(3):
+        s, c = lq.lq_masked_groupby_sum(w.fks, w.dim_rows, w.dim_mask, w.dim_code, w.group_card, w.fact_mask,
+                                        w.measures, stream=side)
+        junk = [torch.full((1 << 18,), -1, dtype=torch.int64, device="cuda") for _ in range(16)]
+        small = [torch.full((175,), -1, dtype=torch.int64, device="cuda") for _ in range(64)]
+        side.synchronize()
+        torch.cuda.synchronize()
+        np.testing.assert_array_equal(s.cpu().numpy(), want_s)
+        np.testing.assert_array_equal(c.cpu().numpy(), want_c)
+        del junk, small
+
+
 def test_reuse_side_tables_skips_the_dimension_pass_and_gives_the_same_result(lq):
     # first call encodes the dimension side into the workspace; the following ones reuse it over
     # other fact rows, another fact mask and other measures

@@ -245,6 +245,29 @@ def test_fusion_advice_is_the_complexity_model_of_the_paper():
     r2 = b.lq_fusion_advice(i, 0, [(r, 32) for r in rows], [64])["ratio"]
     assert r1 > adv["ratio"] > r2 * 0 and r1 > r2
 
+def test_fusion_decision_follows_what_the_kernels_move_not_the_dense_model():
+    """The paper's dense cost ratio falls below 1 as soon as l > k; with one key per fact row the fused
+    join stage of this library is still ahead there (its gathers come out of the caches, the non-fused
+    pipeline writes and re-reads T), so the flag must not be the sign of (ratio - 1)."""
+    b = _binding()
+    rows = (60_000, 8_000, 2_555)
+    for cols, l in (((8, 4, 4), 32), ((8, 4, 4), 64), ((12, 12, 8), 64)):
+        adv = b.lq_fusion_advice(2_400_000, 0, list(zip(rows, cols)), [l], queries_per_update=1.0)
+        assert adv["ratio"] < 1 and adv["fuse"] == 1, (cols, l, adv)
+        assert adv["seconds_no_fusion"] > adv["seconds_fused"] > 0 and adv["seconds_prefusion"] > 0
+        # the decision is exactly the stated inequality, for any update frequency
+        for q in (1e-3, 0.5, 1.0, 100.0):
+            a = b.lq_fusion_advice(2_400_000, 0, list(zip(rows, cols)), [l], queries_per_update=q)
+            assert a["fuse"] == int(q * (a["seconds_no_fusion"] - a["seconds_fused"]) > a["seconds_prefusion"])
+        # dimension tables that change before a single query has run never pay for their pre-fusion
+        assert b.lq_fusion_advice(2_400_000, 0, list(zip(rows, cols)), [l], queries_per_update=1e-3)["fuse"] == 0
+    # more fact rows only scale the per-query terms; more dimension rows only the pre-fusion
+    a1 = b.lq_fusion_advice(1_000_000, 4, [(10_000, 32)] * 3, [64, 1])
+    a2 = b.lq_fusion_advice(2_000_000, 4, [(10_000, 32)] * 3, [64, 1])
+    assert a2["seconds_prefusion"] == a1["seconds_prefusion"] and a2["seconds_fused"] > 1.9 * a1["seconds_fused"] - 1e-5
+    a3 = b.lq_fusion_advice(1_000_000, 4, [(20_000, 32)] * 3, [64, 1])
+    assert a3["seconds_prefusion"] > a1["seconds_prefusion"] and a3["seconds_fused"] == a1["seconds_fused"]
+
 
 def test_groupby_agg_rejects_bad_arguments():
     b = _binding()
