@@ -226,6 +226,31 @@ int lq_masked_groupby_sum(int64_t n_fact, int32_t n_dims, const int32_t* const* 
                           void* ws, size_t ws_bytes, uint32_t flags, void* hip_stream);
 
 /*
+ * lq_masked_groupby_sum for callers that cannot allocate device memory or bring a workspace: code
+ * under HIP graph capture, tight serving loops, harnesses that forbid hipMalloc.  Same arguments
+ * and results, without ws / ws_bytes: the encoded side tables and the per-workgroup partial sums
+ * live in a device array of LQ_STATIC_SCRATCH_BYTES bytes that is part of the library image (each
+ * GPU the library runs on holds its copy until the process ends).  The call allocates nothing and
+ * calls no allocating routine.
+ *   - A query whose lq_groupby_workspace_bytes(..) exceeds LQ_STATIC_SCRATCH_BYTES is refused with
+ *     LQ_ERR_WORKSPACE (the SSB-shaped query of 6M fact rows over dimensions of 2,556 / 30,000 /
+ *     2,000 / 200,000 rows needs about 1.9 MB; roughly 3.5 million dimension rows in total fit).
+ *   - flags must be 0 (LQ_ERR_UNSUPPORTED otherwise).
+ *   - All calls on one GPU share that GPU's array: calls that overlap in time on one GPU (two
+ *     streams, two host threads) race and give undefined results; calls on one stream are safe.
+ *     Nothing in the array has to survive between calls and nothing needs clearing: each call
+ *     rewrites the side tables and every partial row it later reads.
+ */
+#define LQ_STATIC_SCRATCH_BYTES (8u << 20)
+size_t lq_static_scratch_bytes(void);
+int lq_masked_groupby_sum_static(int64_t n_fact, int32_t n_dims, const int32_t* const* fks,
+                                 const int64_t* dim_rows, const uint8_t* const* dim_mask,
+                                 const int32_t* const* dim_code, const int32_t* group_card,
+                                 const uint8_t* fact_mask, int32_t n_measures,
+                                 const int32_t* const* measures, int64_t* sums, int64_t* counts,
+                                 uint32_t flags, void* hip_stream);
+
+/*
  * The same aggregate with the rest of the query shapes of the benchmark's query groups: range
  * predicates on fact columns (selection vectors on the fact table, Section 2.2), measures that are
  * a column, the element-wise product or the difference of two columns (computed in int64), and

@@ -93,6 +93,13 @@ def _load():
                                           ctypes.POINTER(vp), ctypes.POINTER(vp),
                                           ctypes.POINTER(i32), vp, i32, ctypes.POINTER(vp), vp, vp,
                                           vp, sz, u32, vp]
+    lib.lq_masked_groupby_sum_static.argtypes = [i64, i32, ctypes.POINTER(vp), ctypes.POINTER(i64),
+                                                 ctypes.POINTER(vp), ctypes.POINTER(vp),
+                                                 ctypes.POINTER(i32), vp, i32, ctypes.POINTER(vp), vp, vp,
+                                                 u32, vp]
+    lib.lq_masked_groupby_sum_static.restype = ctypes.c_int
+    lib.lq_static_scratch_bytes.argtypes = []
+    lib.lq_static_scratch_bytes.restype = sz
     lib.lq_workspace_bytes.argtypes = [ctypes.c_int, ps, pmod, i64]
     lib.lq_workspace_bytes.restype = sz
     lib.lq_groupby_workspace_bytes.argtypes = [i32, ctypes.POINTER(i64), ctypes.POINTER(i32), i32]
@@ -397,6 +404,59 @@ def lq_masked_groupby_sum(fks: Sequence[torch.Tensor], dim_rows: Sequence[int],
         None if fact_mask is None else fact_mask.data_ptr(), len(measures), _ptr_array(measures),
         sums.data_ptr(), None if counts is None else counts.data_ptr(), ws.data_ptr(),
         ws.numel() * ws.element_size(), flags, _stream(stream)))
+    return sums, counts
+
+
+def lq_static_scratch_bytes() -> int:
+    return int(_lib.lq_static_scratch_bytes())
+
+
+def lq_masked_groupby_sum_static(fks: Sequence[torch.Tensor], dim_rows: Sequence[int],
+                                 dim_mask: Optional[Sequence[Optional[torch.Tensor]]],
+                                 dim_code: Optional[Sequence[Optional[torch.Tensor]]],
+                                 group_card: Sequence[int], fact_mask: Optional[torch.Tensor],
+                                 measures: Sequence[torch.Tensor], sums: torch.Tensor,
+                                 counts: Optional[torch.Tensor], flags: int = 0, stream=None):
+    """lq_masked_groupby_sum without a workspace and without any allocation: the caller brings
+    `sums` [M x G] (and `counts` [G] or None), the library's own static device array is the scratch."""
+    K = len(fks)
+    n = int(measures[0].shape[0])
+    for f in fks:
+        _expect(f, torch.int32, "foreign-key column")
+        if f.shape[0] != n:
+            raise ValueError("foreign-key column length differs from the measures")
+    for m in measures:
+        _expect(m, torch.int32, "measure column")
+    masks = list(dim_mask) if dim_mask is not None else [None] * K
+    codes = list(dim_code) if dim_code is not None else [None] * K
+    for k in range(K):
+        if masks[k] is not None:
+            _expect(masks[k], torch.uint8, "dimension mask")
+            if masks[k].shape[0] != dim_rows[k]:
+                raise ValueError("mask length differs from dim_rows")
+        if codes[k] is not None:
+            _expect(codes[k], torch.int32, "dimension group code")
+            if codes[k].shape[0] != dim_rows[k]:
+                raise ValueError("code length differs from dim_rows")
+    if fact_mask is not None:
+        _expect(fact_mask, torch.uint8, "fact mask")
+    G = 1
+    for k in range(K):
+        if codes[k] is not None:
+            G *= int(group_card[k])
+    _expect(sums, torch.int64, "sums")
+    if sums.numel() != len(measures) * G or not sums.is_contiguous():
+        raise ValueError("sums must be a contiguous int64 tensor of n_measures x G elements")
+    if counts is not None:
+        _expect(counts, torch.int64, "counts")
+        if counts.numel() != G:
+            raise ValueError("counts must have G elements")
+    rows = (ctypes.c_int64 * max(1, K))(*[int(r) for r in dim_rows])
+    card = (ctypes.c_int32 * max(1, K))(*[int(c) for c in group_card])
+    _check(_lib.lq_masked_groupby_sum_static(
+        n, K, _ptr_array(fks), rows, _ptr_array(masks), _ptr_array(codes), card,
+        None if fact_mask is None else fact_mask.data_ptr(), len(measures), _ptr_array(measures),
+        sums.data_ptr(), None if counts is None else counts.data_ptr(), flags, _stream(stream)))
     return sums, counts
 
 

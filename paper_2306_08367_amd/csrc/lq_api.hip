@@ -2,6 +2,8 @@
 // Every entry point validates on the host, enqueues on the caller's stream and returns.
 #include <string.h>
 
+#include <mutex>
+
 #include "lq_common.h"
 
 namespace lq {
@@ -503,6 +505,63 @@ int lq_masked_groupby_sum(int64_t n_fact, int32_t n_dims, const int32_t* const* 
   clear_error();
   return groupby_sum_checked(n_fact, n_dims, fks, dim_rows, dim_mask, dim_code, group_card, fact_mask,
                              n_measures, measures, sums, counts, ws, ws_bytes, flags, hip_stream);
+}
+
+// ---- the same call for callers that cannot allocate --------------------------------------------
+// The side tables and the per-workgroup partial rows live in this array instead of a caller
+// workspace.  Every GPU holds its own copy at its own address; host code reaches it only through
+// the address hipGetSymbolAddress returns for the current device (the array's name is a host-side
+// stand-in, not a device address).
+static __device__ __align__(256) unsigned char scratch[LQ_STATIC_SCRATCH_BYTES];
+
+namespace {
+constexpr int MAX_DEVICES = 64;
+std::mutex g_scratch_mu;
+void* g_scratch_ptr[MAX_DEVICES] = {nullptr};
+
+// Device address of `scratch` on the current device, looked up once per device.
+int static_scratch(void** out) {
+  int dev = 0;
+  LQ_HIP_TRY(hipGetDevice(&dev));
+  if (dev < 0 || dev >= MAX_DEVICES) return fail(LQ_ERR_UNSUPPORTED, "device index %d outside 0..%d", dev, MAX_DEVICES - 1);
+  std::lock_guard<std::mutex> lock(g_scratch_mu);
+  if (!g_scratch_ptr[dev]) {
+    void* p = nullptr;
+    LQ_HIP_TRY(hipGetSymbolAddress(&p, HIP_SYMBOL(scratch)));
+    if (!p || !aligned(p, 256)) return fail(LQ_ERR_HIP, "static scratch array has no usable device address");
+    g_scratch_ptr[dev] = p;
+  }
+  *out = g_scratch_ptr[dev];
+  return LQ_OK;
+}
+}  // namespace
+
+size_t lq_static_scratch_bytes(void) { return LQ_STATIC_SCRATCH_BYTES; }
+
+int lq_masked_groupby_sum_static(int64_t n_fact, int32_t n_dims, const int32_t* const* fks,
+                                 const int64_t* dim_rows, const uint8_t* const* dim_mask,
+                                 const int32_t* const* dim_code, const int32_t* group_card,
+                                 const uint8_t* fact_mask, int32_t n_measures,
+                                 const int32_t* const* measures, int64_t* sums, int64_t* counts,
+                                 uint32_t flags, void* hip_stream) {
+  clear_error();
+  if (flags != 0) return fail(LQ_ERR_UNSUPPORTED, "the allocation-free group-by takes no flags");
+  // Size the request before touching the device, so that an oversized one is refused by name.
+  if (n_dims < 0 || n_dims > LQ_MAX_DIMS) return fail(LQ_ERR_SHAPE, "n_dims %d outside 0..%d", n_dims, LQ_MAX_DIMS);
+  if (n_dims > 0 && !dim_rows) return fail(LQ_ERR_NULL, "fks or dim_rows is NULL");
+  int32_t cards[LQ_MAX_DIMS];
+  for (int k = 0; k < n_dims; ++k) cards[k] = (dim_code && dim_code[k] && group_card) ? group_card[k] : 1;
+  const size_t need = lq_groupby_workspace_bytes(n_dims, dim_rows, cards, n_measures);
+  if (need > LQ_STATIC_SCRATCH_BYTES)
+    return fail(LQ_ERR_WORKSPACE,
+                "this query needs %zu bytes of scratch, the allocation-free entry point holds %u: use "
+                "lq_masked_groupby_sum with a workspace", need, (unsigned)LQ_STATIC_SCRATCH_BYTES);
+  void* ws = nullptr;
+  int rc = static_scratch(&ws);
+  if (rc) return rc;
+  // need == 0 means invalid sizes: the shared validation below names the argument.
+  return groupby_sum_checked(n_fact, n_dims, fks, dim_rows, dim_mask, dim_code, group_card, fact_mask,
+                             n_measures, measures, sums, counts, ws, LQ_STATIC_SCRATCH_BYTES, 0u, hip_stream);
 }
 
 size_t lq_groupby_agg_workspace_bytes(int32_t n_dims, const int64_t* dim_rows, const int32_t* group_card,
