@@ -81,6 +81,7 @@ typedef enum { LQ_F32 = 0, LQ_BF16 = 1 } lq_dtype;
 #define LQ_MAX_DIMS 8
 #define LQ_MAX_LAYERS 8
 #define LQ_MAX_MEASURES 4
+#define LQ_MAX_GROUPS (1 << 30)
 
 /* A row-major matrix on the device. */
 typedef struct {
@@ -207,8 +208,12 @@ int lq_materialized_join_predict(const lq_star* star, const lq_model* model, lq_
  *              entries / NULL array for "no predicate"
  *   dim_code   host array of K device pointers (int32 [r_k] in [0, group_card[k])) or
  *              NULL entries / NULL array for dimensions that do not group
- *   group_card host array of K cardinalities (ignored where dim_code[k] is NULL);
- *              G = product over grouping dimensions, G * (n_measures + 1) <= 8192
+ *   group_card host array of K cardinalities, each 1..65535 (ignored where dim_code[k] is NULL);
+ *              G = product over grouping dimensions <= LQ_MAX_GROUPS.  While G * (n_measures + 1)
+ *              <= 8192 every scan workgroup keeps private accumulators in LDS; above that (the
+ *              multi-column group-by of Section 2.4.2 multiplies cardinalities) the output arrays
+ *              themselves are the accumulators, cleared by the call and updated with device-wide
+ *              64-bit atomics -- same results either way
  *   fact_mask  uint8 [n] or NULL
  *   measures   host array of n_measures (1..LQ_MAX_MEASURES) device pointers, int32 [n]
  *   sums       int64 [n_measures x G], overwritten;  counts int64 [G] or NULL
@@ -260,7 +265,8 @@ int lq_masked_groupby_sum_static(int64_t n_fact, int32_t n_dims, const int32_t* 
  *   measures  host array of n_measures (1..LQ_MAX_MEASURES) expressions over device int32 columns
  *   sums, mins, maxs  int64 [n_measures x G], each may be NULL; groups without rows get 0,
  *             INT64_MAX and INT64_MIN;  counts int64 [G] or NULL
- *   G * (3 * n_measures + 1) <= 8192;  ws: lq_groupby_agg_workspace_bytes(..)
+ *   G <= LQ_MAX_GROUPS (LDS accumulators while G * (3 * n_measures + 1) <= 8192, the output arrays
+ *   themselves beyond that);  ws: lq_groupby_agg_workspace_bytes(..)
  */
 typedef struct { const int32_t* col; int32_t lo; int32_t hi; } lq_range_pred;
 #define LQ_MEASURE_COL 0
@@ -502,7 +508,8 @@ typedef struct {
  * the result is unique.  Group g decomposes as a mixed-radix number over group_card, last column
  * fastest, exactly as the group-by builds it.
  *   group_card  host array of the n_group_cols (0..LQ_MAX_DIMS) cardinalities of the grouping
- *               dimensions, in dimension order; G = their product <= 8192
+ *               dimensions, in dimension order; G = their product <= 8192 (this limit is final: the
+ *               sort runs in one workgroup's LDS; a larger result is ordered by the caller)
  *   sums        device int64 [n_measures x G] (may be NULL if no key uses it); counts device int64 [G]
  *   keys        host array of n_keys (0..4) sort keys
  *   order       device int32 [G]: out, the populated groups in order, then -1s

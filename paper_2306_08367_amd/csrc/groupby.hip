@@ -17,12 +17,15 @@
 //                      global atomics instead costs more than this third launch: a few hundred
 //                      workgroups queueing on the same few cache lines.)
 // Integer addition commutes, so the result is exact and independent of scheduling.
-#include "lq_common.h"
+#include "groupby_fast.h"
 
 namespace lq {
+
+int launch_fast_many(const FastArgs& a, const FastLaunch& L);   // groupby_many.hip
+
 namespace {
 
-typedef int v4i __attribute__((ext_vector_type(4)));
+constexpr int64_t GROUPBY_LDS_ACCUMULATORS = 8192;   // int64 accumulators a scan workgroup keeps in LDS
 
 enum DimKind : int32_t { DK_NONE = 0, DK_BITMAP = 1, DK_BYTE = 2, DK_U16 = 3 };
 
@@ -107,7 +110,6 @@ __global__ __launch_bounds__(256) void pack_kernel(GbArgs a) {
 
 // ---------------------------------------------------------------- scan ------------------
 
-constexpr int SCAN_THREADS = 1024;
 
 // VEC fact rows at once: g[q] becomes the group number of row q, or -1 when the row is filtered
 // out.  Dimensions form the outer loop so that the (wavefront-uniform) choice of side-table format
@@ -280,189 +282,6 @@ __global__ __launch_bounds__(SCAN_THREADS) void scan_kernel(GbArgs a, int64_t pe
 }
 
 
-// ---------------------------------------------------------------- scan, common case -----
-
-// The same scan with everything the generic kernel decides at run time fixed at compile time:
-// no fact mask, 16-byte aligned columns, only byte tables (grouping dimensions, optionally
-// masked) and bitmaps (mask-only dimensions).  The host orders the dimensions into four runs:
-//   NBL byte tables in LDS, NML bitmaps in LDS, NMG bitmaps in memory, NBG byte tables in memory.
-// Tables that do not fit LDS stay in memory (L2) and are only consulted for rows that survived
-// every LDS-resident predicate, so a selective query sends few requests to L2.  Group numbers use
-// per-dimension strides, so the order in which dimensions are visited does not matter.
-struct FastArgs {
-  int64_t n;
-  const int32_t* fk[LQ_MAX_DIMS];    // in the order of the four runs above
-  uint32_t off[LQ_MAX_DIMS];         // byte offset inside the packed buffer
-  int32_t stride[LQ_MAX_DIMS];
-  const int32_t* meas[LQ_MAX_MEASURES];
-  const uint8_t* packed;
-  uint32_t lds_bytes;                // prefix of the packed buffer that is copied into LDS
-  int32_t G;
-  unsigned long long* partial;
-};
-
-template <bool BYTE, bool GUARDED>
-__device__ __forceinline__ void lookup(const uint8_t* t, int32_t j, int32_t stride, bool& alive, int32_t& g) {
-  alive = alive && j >= 0;
-  if (GUARDED && !alive) return;
-  const uint32_t jj = j < 0 ? 0u : static_cast<uint32_t>(j);   // keep the lookup in bounds
-  if (BYTE) {
-    const uint32_t b = t[jj];
-    alive = alive && b != 0xffu;
-    g += static_cast<int32_t>(b) * stride;
-  } else {
-    const uint32_t w = reinterpret_cast<const uint32_t*>(t)[jj >> 5];
-    alive = alive && ((w >> (jj & 31)) & 1u);
-  }
-}
-
-// All dimensions of one fact row.
-template <int NBL, int NML, int NMG, int NBG>
-__device__ __forceinline__ void classify_fast(const FastArgs& a, const uint8_t* tab, const int32_t* j,
-                                              bool& alive, int32_t& g) {
-  constexpr int NL = NBL + NML, ND = NL + NMG + NBG;
-#pragma unroll
-  for (int k = 0; k < ND; ++k) {
-    if (k < NBL) lookup<true, false>(tab + a.off[k], j[k], a.stride[k], alive, g);
-    else if (k < NL) lookup<false, false>(tab + a.off[k], j[k], 0, alive, g);
-    else if (k < NL + NMG) lookup<false, true>(a.packed + a.off[k], j[k], 0, alive, g);
-    else lookup<true, true>(a.packed + a.off[k], j[k], a.stride[k], alive, g);
-  }
-}
-
-template <int NBL, int NML, int NMG, int NBG, int MM>
-__global__ __launch_bounds__(SCAN_THREADS) void scan_fast_kernel(FastArgs a, int64_t per_block) {
-  extern __shared__ __align__(16) uint8_t smem[];
-  constexpr int ND = NBL + NML + NMG + NBG;
-  unsigned long long* acc = reinterpret_cast<unsigned long long*>(smem);
-  const int n_acc = (MM + 1) * a.G;
-  uint8_t* tab = smem + round_up(static_cast<size_t>(n_acc) * 8, 16);
-  const int tid = threadIdx.x;
-
-  const int64_t n_vec = a.n / 4;
-  const int64_t v_begin = static_cast<int64_t>(blockIdx.x) * per_block;
-  const int64_t v_end = min(n_vec, v_begin + per_block);
-  int64_t v = v_begin + tid;
-  v4i cur[ND], nxt[ND];
-  if (v < v_end) {
-#pragma unroll
-    for (int k = 0; k < ND; ++k) cur[k] = __builtin_nontemporal_load(reinterpret_cast<const v4i*>(a.fk[k]) + v);
-  }
-  for (int i = tid; i < n_acc; i += SCAN_THREADS) acc[i] = 0ull;
-  {
-    const uint4* src = reinterpret_cast<const uint4*>(a.packed);
-    uint4* dst = reinterpret_cast<uint4*>(tab);
-    for (uint32_t i = tid; i < a.lds_bytes / 16; i += SCAN_THREADS) dst[i] = src[i];
-  }
-  __syncthreads();
-
-  while (v < v_end) {
-    const int64_t vn = v + SCAN_THREADS;
-    if (vn < v_end) {
-#pragma unroll
-      for (int k = 0; k < ND; ++k) nxt[k] = __builtin_nontemporal_load(reinterpret_cast<const v4i*>(a.fk[k]) + vn);
-    }
-    int32_t g[4];
-    bool alive[4];
-#pragma unroll
-    for (int q = 0; q < 4; ++q) {
-      int32_t j[ND];
-#pragma unroll
-      for (int k = 0; k < ND; ++k) j[k] = cur[k][q];
-      g[q] = 0;
-      alive[q] = true;
-      classify_fast<NBL, NML, NMG, NBG>(a, tab, j, alive[q], g[q]);
-    }
-    if (alive[0] || alive[1] || alive[2] || alive[3]) {
-#pragma unroll
-      for (int m = 0; m < MM; ++m) {
-        const v4i val = *(reinterpret_cast<const v4i*>(a.meas[m]) + v);
-#pragma unroll
-        for (int q = 0; q < 4; ++q)
-          if (alive[q])
-            atomicAdd(&acc[m * a.G + g[q]], static_cast<unsigned long long>(static_cast<long long>(val[q])));
-      }
-#pragma unroll
-      for (int q = 0; q < 4; ++q)
-        if (alive[q]) atomicAdd(&acc[MM * a.G + g[q]], 1ull);
-    }
-#pragma unroll
-    for (int k = 0; k < ND; ++k) cur[k] = nxt[k];
-    v = vn;
-  }
-  // ragged tail (n % 4 rows)
-  if (blockIdx.x == 0) {
-    const int64_t i = n_vec * 4 + tid;
-    if (i < a.n) {
-      int32_t j[ND];
-#pragma unroll
-      for (int k = 0; k < ND; ++k) j[k] = a.fk[k][i];
-      int32_t g = 0;
-      bool alive = true;
-      classify_fast<NBL, NML, NMG, NBG>(a, tab, j, alive, g);
-      if (alive) {
-#pragma unroll
-        for (int m = 0; m < MM; ++m)
-          atomicAdd(&acc[m * a.G + g], static_cast<unsigned long long>(static_cast<long long>(a.meas[m][i])));
-        atomicAdd(&acc[MM * a.G + g], 1ull);
-      }
-    }
-  }
-  __syncthreads();
-  unsigned long long* mine = a.partial + static_cast<size_t>(blockIdx.x) * n_acc;
-  for (int i = tid; i < n_acc; i += SCAN_THREADS) mine[i] = acc[i];
-}
-
-struct FastLaunch { unsigned blocks; size_t lds; int64_t per_block; hipStream_t s; int nbl, nml, nmg, nbg, M; };
-
-template <int NBL, int NML, int NMG, int NBG, int MM>
-int launch_fast_inst(const FastArgs& a, const FastLaunch& L) {
-  if (L.lds > 64 * 1024)
-    LQ_HIP_TRY(hipFuncSetAttribute(reinterpret_cast<const void*>(&scan_fast_kernel<NBL, NML, NMG, NBG, MM>),
-                                   hipFuncAttributeMaxDynamicSharedMemorySize, static_cast<int>(L.lds)));
-  hipLaunchKernelGGL((scan_fast_kernel<NBL, NML, NMG, NBG, MM>), dim3(L.blocks), dim3(SCAN_THREADS), L.lds,
-                     L.s, a, L.per_block);
-  LQ_LAUNCH_CHECK("scan_fast_kernel");
-  return LQ_OK;
-}
-template <int NBL, int NML, int NMG, int NBG>
-int launch_fast_m(const FastArgs& a, const FastLaunch& L) {
-  if constexpr (NBL + NML + NMG + NBG == 0) return -1;
-  else {
-    if (L.M == 1) return launch_fast_inst<NBL, NML, NMG, NBG, 1>(a, L);
-    if (L.M == 2) return launch_fast_inst<NBL, NML, NMG, NBG, 2>(a, L);
-    return -1;
-  }
-}
-template <int NBL, int NML>
-int launch_fast_g(const FastArgs& a, const FastLaunch& L) {
-  if (L.nmg == 0 && L.nbg == 0) return launch_fast_m<NBL, NML, 0, 0>(a, L);
-  if (L.nmg == 1 && L.nbg == 0) return launch_fast_m<NBL, NML, 1, 0>(a, L);
-  if (L.nmg == 0 && L.nbg == 1) return launch_fast_m<NBL, NML, 0, 1>(a, L);
-  if (L.nmg == 1 && L.nbg == 1) return launch_fast_m<NBL, NML, 1, 1>(a, L);
-  return -1;
-}
-template <int NBL>
-int launch_fast_ml(const FastArgs& a, const FastLaunch& L) {
-  switch (L.nml) {
-    case 0: return launch_fast_g<NBL, 0>(a, L);
-    case 1: return launch_fast_g<NBL, 1>(a, L);
-    case 2: return launch_fast_g<NBL, 2>(a, L);
-    case 3: return launch_fast_g<NBL, 3>(a, L);
-    default: return -1;
-  }
-}
-// Returns -1 when there is no instantiation for this mix of dimensions.
-int launch_fast(const FastArgs& a, const FastLaunch& L) {
-  switch (L.nbl) {
-    case 0: return launch_fast_ml<0>(a, L);
-    case 1: return launch_fast_ml<1>(a, L);
-    case 2: return launch_fast_ml<2>(a, L);
-    case 3: return launch_fast_ml<3>(a, L);
-    default: return -1;
-  }
-}
-
 // ---------------------------------------------------------------- fold ------------------
 
 constexpr int FOLD_THREADS = 512;
@@ -509,8 +328,6 @@ struct AggExtra {
   unsigned long long* maxs;
 };
 // Accumulator layout (LDS, partial rows): [sums M x G | counts G | mins M x G | maxs M x G].
-constexpr long long AGG_MIN_INIT = 0x7fffffffffffffffLL;
-constexpr long long AGG_MAX_INIT = -0x7fffffffffffffffLL - 1;
 
 __device__ __forceinline__ long long agg_init(int i, int M, int G) {
   return i < (M + 1) * G ? 0LL : (i < (2 * M + 1) * G ? AGG_MIN_INIT : AGG_MAX_INIT);
@@ -646,6 +463,97 @@ __global__ __launch_bounds__(FOLD_THREADS) void fold_agg_kernel(GbArgs a, AggExt
   }
 }
 
+// The scan of scan_kernel / agg_scan_kernel with the accumulators in memory.  x.n_preds == 0 and
+// op == column give the plain masked group-by sum.
+template <bool LDS_TABLES, int VEC, int KMAX>
+__global__ __launch_bounds__(SCAN_THREADS) void scan_global_kernel(GbArgs a, AggExtra x, GlobalOut o, int64_t per_block,
+                                                                   int vec_ok) {
+  extern __shared__ __align__(16) uint8_t smem[];
+  const int tid = threadIdx.x;
+  if (LDS_TABLES) {
+    const uint4* src = reinterpret_cast<const uint4*>(a.packed);
+    uint4* dst = reinterpret_cast<uint4*>(smem);
+    for (uint32_t i = tid; i < a.packed_bytes / 16; i += SCAN_THREADS) dst[i] = src[i];
+    __syncthreads();
+  }
+  const uint8_t* tab = LDS_TABLES ? smem : a.packed;
+
+  auto load4 = [&](const int32_t* col, int64_t i0, int cnt, int32_t (&out)[VEC]) {
+    if (VEC == 4 && vec_ok && cnt == VEC) {
+      const v4i t = *reinterpret_cast<const v4i*>(col + i0);
+#pragma unroll
+      for (int q = 0; q < VEC; ++q) out[q] = t[q];
+    } else {
+#pragma unroll
+      for (int q = 0; q < VEC; ++q) out[q] = q < cnt ? col[i0 + q] : 0;
+    }
+  };
+
+  const int64_t n_vec = (a.n + VEC - 1) / VEC;
+  const int64_t v_begin = static_cast<int64_t>(blockIdx.x) * per_block;
+  const int64_t v_end = min(n_vec, v_begin + per_block);
+  // every lane of a wavefront takes the same number of steps: the merge is a wavefront operation
+  for (int64_t v0 = v_begin + (tid & ~63); v0 < v_end; v0 += SCAN_THREADS) {
+    const int64_t v = v0 + (tid & 63);
+    const int64_t i0 = v * VEC;
+    const int cnt = v < v_end ? static_cast<int>(min<int64_t>(VEC, a.n - i0)) : 0;
+    int32_t fk[VEC][KMAX];
+    bool pass[VEC];
+#pragma unroll
+    for (int q = 0; q < VEC; ++q) pass[q] = q < cnt;
+#pragma unroll
+    for (int k = 0; k < KMAX; ++k) {
+      int32_t t[VEC];
+#pragma unroll
+      for (int q = 0; q < VEC; ++q) t[q] = -1;
+      if (k < a.K && cnt > 0) load4(a.d[k].fk, i0, cnt, t);
+#pragma unroll
+      for (int q = 0; q < VEC; ++q) fk[q][k] = t[q];
+    }
+    if (a.fact_mask && cnt > 0) {
+#pragma unroll
+      for (int q = 0; q < VEC; ++q) pass[q] = pass[q] && a.fact_mask[i0 + (q < cnt ? q : 0)] != 0;
+    }
+#pragma unroll
+    for (int pq = 0; pq < MAX_PREDS; ++pq)
+      if (pq < x.n_preds && cnt > 0) {
+        int32_t pv[VEC];
+        load4(x.pcol[pq], i0, cnt, pv);
+#pragma unroll
+        for (int q = 0; q < VEC; ++q) pass[q] = pass[q] && pv[q] >= x.lo[pq] && pv[q] <= x.hi[pq];
+      }
+    int32_t g[VEC];
+    classify<VEC, KMAX>(a, tab, fk, g);
+    bool any = false;
+#pragma unroll
+    for (int q = 0; q < VEC; ++q) { pass[q] = pass[q] && g[q] >= 0; any = any || pass[q]; }
+    long long val[VEC][LQ_MAX_MEASURES];
+#pragma unroll
+    for (int q = 0; q < VEC; ++q)
+#pragma unroll
+      for (int m = 0; m < LQ_MAX_MEASURES; ++m) val[q][m] = 0;
+    if (any) {                  // measure columns are only touched where a row survives
+#pragma unroll
+      for (int m = 0; m < LQ_MAX_MEASURES; ++m) {
+        if (m >= a.M) break;
+        int32_t av[VEC], bv[VEC];
+        load4(a.meas[m], i0, cnt, av);
+        if (x.op[m] != 0) load4(x.b[m], i0, cnt, bv);
+#pragma unroll
+        for (int q = 0; q < VEC; ++q) {
+          long long t = av[q];
+          if (x.op[m] == 1) t *= static_cast<long long>(bv[q]);
+          else if (x.op[m] == 2) t -= static_cast<long long>(bv[q]);
+          val[q][m] = t;
+        }
+      }
+    }
+    if (__ballot(any) == 0ull) continue;
+#pragma unroll
+    for (int q = 0; q < VEC; ++q) merge_and_add<LQ_MAX_MEASURES>(pass[q], g[q], val[q], a.M, a.G, o);
+  }
+}
+
 constexpr size_t LDS_BUDGET = 160 * 1024 - 1024;   // gfx950 workgroups may use the whole 160 KB
 
 // Fills kind / off / bytes of every dimension; returns the packed size.  Tables are laid out by
@@ -698,9 +606,70 @@ size_t groupby_tables_bytes(int32_t K, const int64_t* rows) {
   return round_up(t, 256) + 256;
 }
 int groupby_max_workgroups() { return 2 * num_cus(); }
+// Up to GROUPBY_LDS_ACCUMULATORS accumulators live in LDS and every scan workgroup leaves a partial row
+// in the workspace; beyond that the accumulators are the caller's output arrays and the workspace only
+// holds the side tables (plus the check's flag word).
 size_t groupby_ws_bytes(int32_t K, const int64_t* rows, int64_t n_acc) {
+  if (n_acc > GROUPBY_LDS_ACCUMULATORS) return groupby_tables_bytes(K, rows) + 256;
   return groupby_tables_bytes(K, rows) +
          round_up(static_cast<size_t>(groupby_max_workgroups()) * n_acc * 8, 256);
+}
+
+// sums / counts = 0, mins / maxs = neutral elements, for the accumulators-in-memory form.
+static int launch_init_outputs(const GlobalOut& o, int32_t M, int32_t G, hipStream_t s) {
+  const int64_t MG = std::max<int64_t>(static_cast<int64_t>(M) * G, G);
+  const int64_t blocks = std::max<int64_t>(1, std::min<int64_t>((MG + 255) / 256, static_cast<int64_t>(num_cus()) * 8));
+  hipLaunchKernelGGL(init_outputs_kernel, dim3(static_cast<unsigned>(blocks)), dim3(256), 0, s, o, MG, static_cast<int64_t>(G));
+  LQ_LAUNCH_CHECK("init_outputs_kernel");
+  return LQ_OK;
+}
+
+static int launch_pack(const GbArgs& a, hipStream_t s) {
+  size_t work = 1;
+  for (int k = 0; k < a.K; ++k) {
+    const size_t w = a.d[k].kind == DK_BITMAP ? static_cast<size_t>(a.d[k].bytes) * 8   // one lane per row
+                                              : static_cast<size_t>(a.d[k].bytes) / 4;   // one thread per word
+    work = std::max(work, w);
+  }
+  const int64_t blocks = std::min<int64_t>(static_cast<int64_t>((work + 255) / 256), static_cast<int64_t>(num_cus()) * 8);
+  hipLaunchKernelGGL(pack_kernel, dim3(static_cast<unsigned>(std::max<int64_t>(blocks, 1))), dim3(256), 0, s, a);
+  LQ_LAUNCH_CHECK("pack_kernel");
+  return LQ_OK;
+}
+
+// The run-time generic scan with the accumulators in memory (side tables all in LDS or all in memory).
+static int launch_scan_global(const GbArgs& a, const AggExtra& x, const GlobalOut& o, size_t lds_prefix, bool vec_ok,
+                              hipStream_t s) {
+  const int cus = num_cus();
+  const int vec = vec_ok ? 4 : 1;
+  const int64_t n_vec = (a.n + vec - 1) / vec;
+  const bool lds_tables = lds_prefix == a.packed_bytes;
+  const size_t lds = lds_tables ? a.packed_bytes : 0;
+  const int per_cu = lds * 2 <= 160 * 1024 ? 2 : 1;
+  int64_t b = std::max<int64_t>(1, std::min<int64_t>((n_vec + SCAN_THREADS - 1) / SCAN_THREADS, static_cast<int64_t>(cus) * per_cu));
+  int64_t pb = (n_vec + b - 1) / b;
+  pb = std::max<int64_t>(SCAN_THREADS, (pb + SCAN_THREADS - 1) / SCAN_THREADS * SCAN_THREADS);
+  b = std::max<int64_t>(1, (n_vec + pb - 1) / pb);
+  const unsigned blocks = static_cast<unsigned>(b);
+  const int kmax = a.K <= 2 ? 2 : (a.K <= 4 ? 4 : 8);
+#define LQ_SCANG(LT, V, KM)                                                                             \
+  do {                                                                                                  \
+    if (lds > 64 * 1024)                                                                                \
+      LQ_HIP_TRY(hipFuncSetAttribute(reinterpret_cast<const void*>(&scan_global_kernel<LT, V, KM>),     \
+                                     hipFuncAttributeMaxDynamicSharedMemorySize, static_cast<int>(lds))); \
+    hipLaunchKernelGGL((scan_global_kernel<LT, V, KM>), dim3(blocks), dim3(SCAN_THREADS), lds, s, a, x, o, pb, \
+                       vec_ok ? 1 : 0);                                                                 \
+  } while (0)
+#define LQ_SCANG_K(LT, V)                                                                               \
+  do {                                                                                                  \
+    if (kmax == 2) LQ_SCANG(LT, V, 2); else if (kmax == 4) LQ_SCANG(LT, V, 4); else LQ_SCANG(LT, V, 8); \
+  } while (0)
+  if (lds_tables) { if (vec == 4) LQ_SCANG_K(true, 4); else LQ_SCANG_K(true, 1); }
+  else            { if (vec == 4) LQ_SCANG_K(false, 4); else LQ_SCANG_K(false, 1); }
+#undef LQ_SCANG_K
+#undef LQ_SCANG
+  LQ_LAUNCH_CHECK("scan_global_kernel");
+  return LQ_OK;
 }
 
 int launch_groupby(int64_t n, int32_t K, const int32_t* const* fks, const int64_t* rows,
@@ -731,7 +700,9 @@ int launch_groupby(int64_t n, int32_t K, const int32_t* const* fks, const int64_
       if (grouping) stride *= card[k];
     }
   }
-  const int n_acc = (M + 1) * G;
+  // More accumulators than a workgroup keeps in LDS: the caller's arrays accumulate (no partial rows, no fold).
+  const bool gacc = static_cast<int64_t>(M + 1) * G > GROUPBY_LDS_ACCUMULATORS;
+  const int n_acc = gacc ? 0 : (M + 1) * G;
   const size_t acc_bytes = round_up(static_cast<size_t>(n_acc) * 8, 16);
   size_t lds_prefix = 0;
   const size_t packed = plan_tables(K, rows, mask, code, card, a.d, LDS_BUDGET - acc_bytes, &lds_prefix);
@@ -739,19 +710,13 @@ int launch_groupby(int64_t n, int32_t K, const int32_t* const* fks, const int64_
   a.packed_bytes = static_cast<uint32_t>(packed);
 
   const int cus = num_cus();
-  if (!reuse_tables) {
-    size_t work = 1;
-    for (int k = 0; k < K; ++k) {
-      const size_t w = a.d[k].kind == DK_BITMAP ? static_cast<size_t>(a.d[k].bytes) * 8   // one lane per row
-                                                : static_cast<size_t>(a.d[k].bytes) / 4;   // one thread per word
-      work = std::max(work, w);
-    }
-    const int64_t blocks = std::min<int64_t>(static_cast<int64_t>((work + 255) / 256), cus * 8);
-    hipLaunchKernelGGL(pack_kernel, dim3(static_cast<unsigned>(std::max<int64_t>(blocks, 1))), dim3(256), 0, s, a);
-    LQ_LAUNCH_CHECK("pack_kernel");
-  }
+  int rc0;
+  const GlobalOut gout{a.sums, a.counts, nullptr, nullptr};
+  if (gacc && (rc0 = launch_init_outputs(gout, M, G, s))) return rc0;
+  if (!reuse_tables && (n > 0 || !gacc) && (rc0 = launch_pack(a, s))) return rc0;
   const unsigned fold_blocks = static_cast<unsigned>((n_acc + FOLD_ACCS - 1) / FOLD_ACCS);
   if (n == 0) {   // nothing to scan: the fold alone writes the all-zero result
+    if (gacc) return LQ_OK;
     hipLaunchKernelGGL(fold_kernel, dim3(fold_blocks), dim3(FOLD_THREADS), 0, s, a, 0);
     LQ_LAUNCH_CHECK("fold_kernel");
     return LQ_OK;
@@ -793,12 +758,15 @@ int launch_groupby(int64_t n, int32_t K, const int32_t* const* fks, const int64_
       }
     if (ok) {
       f.n = n; f.packed = a.packed; f.lds_bytes = static_cast<uint32_t>(lds_prefix); f.G = G; f.partial = a.partial;
+      f.gsums = gacc ? a.sums : nullptr;
+      f.gcounts = gacc ? a.counts : nullptr;
       for (int m = 0; m < M; ++m) f.meas[m] = meas[m];
       L.lds = acc_bytes + lds_prefix; L.s = s; L.M = M;
       slices(L.lds, &L.blocks, &L.per_block);
-      const int rc = launch_fast(f, L);
+      const int rc = gacc ? launch_fast_many(f, L) : launch_fast<false>(f, L);
       if (rc > 0) return rc;
       if (rc == 0) {
+        if (gacc) return LQ_OK;
         hipLaunchKernelGGL(fold_kernel, dim3(fold_blocks), dim3(FOLD_THREADS), 0, s, a, static_cast<int>(L.blocks));
         LQ_LAUNCH_CHECK("fold_kernel");
         return LQ_OK;
@@ -807,6 +775,11 @@ int launch_groupby(int64_t n, int32_t K, const int32_t* const* fks, const int64_
   }
 
   // Everything else: the run-time generic kernel, side tables all in LDS or all in memory.
+  if (gacc) {
+    AggExtra x{};
+    for (int m = 0; m < M; ++m) x.b[m] = meas[m];
+    return launch_scan_global(a, x, gout, lds_prefix, vec_ok, s);
+  }
   const bool lds_tables = lds_prefix == packed;
   const size_t lds = acc_bytes + (lds_tables ? packed : 0);
   unsigned blocks = 0;
@@ -874,6 +847,18 @@ int launch_groupby_agg(int64_t n, int32_t K, const int32_t* const* fks, const in
   for (int m = 0; m < M; ++m) {
     a.meas[m] = meas[m].a; x.op[m] = meas[m].op; x.b[m] = meas[m].b ? meas[m].b : meas[m].a;
     vec_ok = vec_ok && aligned(a.meas[m], 16) && aligned(x.b[m], 16);
+  }
+  if (static_cast<int64_t>(3 * M + 1) * G > GROUPBY_LDS_ACCUMULATORS) {   // accumulators in memory
+    const GlobalOut o{a.sums, a.counts, reinterpret_cast<long long*>(mins), reinterpret_cast<long long*>(maxs)};
+    size_t prefix = 0;
+    const size_t pk = plan_tables(K, rows, mask, code, card, a.d, LDS_BUDGET, &prefix);
+    if (pk > 0xffffffffull) return fail(LQ_ERR_UNSUPPORTED, "group-by: dimension side tables exceed 4 GiB");
+    a.packed_bytes = static_cast<uint32_t>(pk);
+    int rc0;
+    if ((rc0 = launch_init_outputs(o, M, G, s))) return rc0;
+    if (n == 0) return LQ_OK;
+    if (!reuse_tables && (rc0 = launch_pack(a, s))) return rc0;
+    return launch_scan_global(a, x, o, prefix, vec_ok, s);
   }
   const int n_acc = (3 * M + 1) * G;
   const size_t acc_bytes = round_up(static_cast<size_t>(n_acc) * 8, 16);

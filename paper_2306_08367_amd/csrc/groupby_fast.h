@@ -1,0 +1,378 @@
+// (Internal header: the compile-time specialised fact scan of the group-by, instantiated in groupby.hip with
+// the accumulators in LDS and in groupby_many.hip with the accumulators in memory, so that the two families
+// compile in parallel.)
+#ifndef LQ_GROUPBY_FAST_H_
+#define LQ_GROUPBY_FAST_H_
+#include "lq_common.h"
+
+namespace lq {
+
+constexpr int SCAN_THREADS = 1024;
+
+// The same scan with everything the generic kernel decides at run time fixed at compile time:
+// no fact mask, 16-byte aligned columns, only byte tables (grouping dimensions, optionally
+// masked) and bitmaps (mask-only dimensions).  The host orders the dimensions into four runs:
+//   NBL byte tables in LDS, NML bitmaps in LDS, NMG bitmaps in memory, NBG byte tables in memory.
+// Tables that do not fit LDS stay in memory (L2) and are only consulted for rows that survived
+// every LDS-resident predicate, so a selective query sends few requests to L2.  Group numbers use
+// per-dimension strides, so the order in which dimensions are visited does not matter.
+struct FastArgs {
+  int64_t n;
+  const int32_t* fk[LQ_MAX_DIMS];    // in the order of the four runs above
+  uint32_t off[LQ_MAX_DIMS];         // byte offset inside the packed buffer
+  int32_t stride[LQ_MAX_DIMS];
+  const int32_t* meas[LQ_MAX_MEASURES];
+  const uint8_t* packed;
+  uint32_t lds_bytes;                // prefix of the packed buffer that is copied into LDS
+  int32_t G;
+  unsigned long long* partial;
+  unsigned long long* gsums;         // not NULL: more groups than LDS holds, accumulate into the caller's
+  unsigned long long* gcounts;       // arrays (gcounts may be NULL) instead of LDS + partial rows
+};
+
+struct FastLaunch { unsigned blocks; size_t lds; int64_t per_block; hipStream_t s; int nbl, nml, nmg, nbg, M; };
+
+namespace {
+
+typedef int v4i __attribute__((ext_vector_type(4)));
+
+// Neutral elements of MIN and MAX (what groups without rows keep).
+constexpr long long AGG_MIN_INIT = 0x7fffffffffffffffLL;
+constexpr long long AGG_MAX_INIT = -0x7fffffffffffffffLL - 1;
+
+// ---------------------------------------------------------------- many groups ------------
+//
+// More accumulators than LDS holds (the multi-column group-by of Section 2.4.2 multiplies the
+// cardinalities of its grouping attributes): the accumulators are the caller's own dense arrays in
+// memory, cleared by a first launch, and survivors add into them with device-wide 64-bit atomics; no
+// partial rows, no fold.  Before the atomics the lanes of a wavefront that hit the same group are
+// merged (up to four distinct groups per step; a hot group then costs one atomic per wavefront step
+// instead of one per row), the rest go out one by one.  Integer adds commute: exact whatever the order.
+
+__device__ __forceinline__ long long wave_sum64(long long v) {
+#pragma unroll
+  for (int off = 32; off > 0; off >>= 1) v += __shfl_xor(v, off, 64);
+  return v;
+}
+__device__ __forceinline__ long long wave_min64(long long v) {
+#pragma unroll
+  for (int off = 32; off > 0; off >>= 1) v = min(v, __shfl_xor(v, off, 64));
+  return v;
+}
+__device__ __forceinline__ long long wave_max64(long long v) {
+#pragma unroll
+  for (int off = 32; off > 0; off >>= 1) v = max(v, __shfl_xor(v, off, 64));
+  return v;
+}
+
+struct GlobalOut {
+  unsigned long long* sums;     // [M x G] or NULL
+  unsigned long long* counts;   // [G] or NULL
+  long long* mins;              // [M x G] or NULL
+  long long* maxs;              // [M x G] or NULL
+};
+
+// One row slot of every lane: `alive` lanes add val[0..M) into group g.  Wavefront-uniform control flow.
+template <int MAXM>
+__device__ __forceinline__ void merge_and_add(bool alive, int32_t g, const long long (&val)[MAXM], int M, int32_t G,
+                                              const GlobalOut& o) {
+  const int lane = threadIdx.x & 63;
+  unsigned long long todo = __ballot(alive);
+  for (int round = 0; round < 4 && todo; ++round) {
+    const int leader = __ffsll(static_cast<long long>(todo)) - 1;
+    const int32_t lg = __builtin_amdgcn_readlane(g, leader);
+    const bool mine = alive && g == lg;
+    const unsigned long long same = __ballot(mine);
+    todo &= ~same;
+    if (__popcll(same) < 2) continue;            // a single row: it goes out with the others below
+#pragma unroll
+    for (int m = 0; m < MAXM; ++m) {
+      if (m >= M) break;
+      if (o.sums) {
+        const long long t = wave_sum64(mine ? val[m] : 0LL);
+        if (lane == leader) atomicAdd(&o.sums[static_cast<size_t>(m) * G + lg], static_cast<unsigned long long>(t));
+      }
+      if (o.mins) {
+        const long long t = wave_min64(mine ? val[m] : AGG_MIN_INIT);
+        if (lane == leader) atomicMin(&o.mins[static_cast<size_t>(m) * G + lg], t);
+      }
+      if (o.maxs) {
+        const long long t = wave_max64(mine ? val[m] : AGG_MAX_INIT);
+        if (lane == leader) atomicMax(&o.maxs[static_cast<size_t>(m) * G + lg], t);
+      }
+    }
+    if (o.counts && lane == leader) atomicAdd(&o.counts[lg], static_cast<unsigned long long>(__popcll(same)));
+    alive = alive && !mine;
+  }
+  if (alive) {
+#pragma unroll
+    for (int m = 0; m < MAXM; ++m) {
+      if (m >= M) break;
+      const size_t at = static_cast<size_t>(m) * G + g;
+      if (o.sums) atomicAdd(&o.sums[at], static_cast<unsigned long long>(val[m]));
+      if (o.mins) atomicMin(&o.mins[at], val[m]);
+      if (o.maxs) atomicMax(&o.maxs[at], val[m]);
+    }
+    if (o.counts) atomicAdd(&o.counts[g], 1ull);
+  }
+}
+
+// sums / counts = 0, mins / maxs = their neutral elements (a fill kernel rather than a memset, so that
+// callers may record the call into a HIP graph).
+__global__ __launch_bounds__(256) void init_outputs_kernel(GlobalOut o, int64_t MG, int64_t G) {
+  const int64_t stride = static_cast<int64_t>(gridDim.x) * blockDim.x;
+  for (int64_t i = static_cast<int64_t>(blockIdx.x) * blockDim.x + threadIdx.x; i < MG; i += stride) {
+    if (o.sums) o.sums[i] = 0ull;
+    if (o.mins) o.mins[i] = AGG_MIN_INIT;
+    if (o.maxs) o.maxs[i] = AGG_MAX_INIT;
+    if (o.counts && i < G) o.counts[i] = 0ull;
+  }
+}
+
+
+template <bool BYTE, bool GUARDED>
+__device__ __forceinline__ void lookup(const uint8_t* t, int32_t j, int32_t stride, bool& alive, int32_t& g) {
+  alive = alive && j >= 0;
+  if (GUARDED && !alive) return;
+  const uint32_t jj = j < 0 ? 0u : static_cast<uint32_t>(j);   // keep the lookup in bounds
+  if (BYTE) {
+    const uint32_t b = t[jj];
+    alive = alive && b != 0xffu;
+    g += static_cast<int32_t>(b) * stride;
+  } else {
+    const uint32_t w = reinterpret_cast<const uint32_t*>(t)[jj >> 5];
+    alive = alive && ((w >> (jj & 31)) & 1u);
+  }
+}
+
+// All dimensions of one fact row.
+template <int NBL, int NML, int NMG, int NBG>
+__device__ __forceinline__ void classify_fast(const FastArgs& a, const uint8_t* tab, const int32_t* j,
+                                              bool& alive, int32_t& g) {
+  constexpr int NL = NBL + NML, ND = NL + NMG + NBG;
+#pragma unroll
+  for (int k = 0; k < ND; ++k) {
+    if (k < NBL) lookup<true, false>(tab + a.off[k], j[k], a.stride[k], alive, g);
+    else if (k < NL) lookup<false, false>(tab + a.off[k], j[k], 0, alive, g);
+    else if (k < NL + NMG) lookup<false, true>(a.packed + a.off[k], j[k], 0, alive, g);
+    else lookup<true, true>(a.packed + a.off[k], j[k], a.stride[k], alive, g);
+  }
+}
+
+template <int NBL, int NML, int NMG, int NBG, int MM>
+__global__ __launch_bounds__(SCAN_THREADS) void scan_fast_kernel(FastArgs a, int64_t per_block) {
+  extern __shared__ __align__(16) uint8_t smem[];
+  constexpr int ND = NBL + NML + NMG + NBG;
+  unsigned long long* acc = reinterpret_cast<unsigned long long*>(smem);
+  const int n_acc = (MM + 1) * a.G;
+  uint8_t* tab = smem + round_up(static_cast<size_t>(n_acc) * 8, 16);
+  const int tid = threadIdx.x;
+
+  const int64_t n_vec = a.n / 4;
+  const int64_t v_begin = static_cast<int64_t>(blockIdx.x) * per_block;
+  const int64_t v_end = min(n_vec, v_begin + per_block);
+  int64_t v = v_begin + tid;
+  v4i cur[ND], nxt[ND];
+  if (v < v_end) {
+#pragma unroll
+    for (int k = 0; k < ND; ++k) cur[k] = __builtin_nontemporal_load(reinterpret_cast<const v4i*>(a.fk[k]) + v);
+  }
+  for (int i = tid; i < n_acc; i += SCAN_THREADS) acc[i] = 0ull;
+  {
+    const uint4* src = reinterpret_cast<const uint4*>(a.packed);
+    uint4* dst = reinterpret_cast<uint4*>(tab);
+    for (uint32_t i = tid; i < a.lds_bytes / 16; i += SCAN_THREADS) dst[i] = src[i];
+  }
+  __syncthreads();
+
+  while (v < v_end) {
+    const int64_t vn = v + SCAN_THREADS;
+    if (vn < v_end) {
+#pragma unroll
+      for (int k = 0; k < ND; ++k) nxt[k] = __builtin_nontemporal_load(reinterpret_cast<const v4i*>(a.fk[k]) + vn);
+    }
+    int32_t g[4];
+    bool alive[4];
+#pragma unroll
+    for (int q = 0; q < 4; ++q) {
+      int32_t j[ND];
+#pragma unroll
+      for (int k = 0; k < ND; ++k) j[k] = cur[k][q];
+      g[q] = 0;
+      alive[q] = true;
+      classify_fast<NBL, NML, NMG, NBG>(a, tab, j, alive[q], g[q]);
+    }
+    if (alive[0] || alive[1] || alive[2] || alive[3]) {
+#pragma unroll
+      for (int m = 0; m < MM; ++m) {
+        const v4i val = *(reinterpret_cast<const v4i*>(a.meas[m]) + v);
+#pragma unroll
+        for (int q = 0; q < 4; ++q)
+          if (alive[q])
+            atomicAdd(&acc[m * a.G + g[q]], static_cast<unsigned long long>(static_cast<long long>(val[q])));
+      }
+#pragma unroll
+      for (int q = 0; q < 4; ++q)
+        if (alive[q]) atomicAdd(&acc[MM * a.G + g[q]], 1ull);
+    }
+#pragma unroll
+    for (int k = 0; k < ND; ++k) cur[k] = nxt[k];
+    v = vn;
+  }
+  // ragged tail (n % 4 rows)
+  if (blockIdx.x == 0) {
+    const int64_t i = n_vec * 4 + tid;
+    if (i < a.n) {
+      int32_t j[ND];
+#pragma unroll
+      for (int k = 0; k < ND; ++k) j[k] = a.fk[k][i];
+      int32_t g = 0;
+      bool alive = true;
+      classify_fast<NBL, NML, NMG, NBG>(a, tab, j, alive, g);
+      if (alive) {
+#pragma unroll
+        for (int m = 0; m < MM; ++m)
+          atomicAdd(&acc[m * a.G + g], static_cast<unsigned long long>(static_cast<long long>(a.meas[m][i])));
+        atomicAdd(&acc[MM * a.G + g], 1ull);
+      }
+    }
+  }
+  __syncthreads();
+  unsigned long long* mine = a.partial + static_cast<size_t>(blockIdx.x) * n_acc;
+  for (int i = tid; i < n_acc; i += SCAN_THREADS) mine[i] = acc[i];
+}
+
+
+// The same scan with the accumulators in memory: a.gsums [MM x G] and a.gcounts [G] (or NULL), cleared
+// before the launch.  No partial rows, LDS only holds side tables.
+template <int NBL, int NML, int NMG, int NBG, int MM>
+__global__ __launch_bounds__(SCAN_THREADS) void scan_fast_mem_kernel(FastArgs a, int64_t per_block) {
+  extern __shared__ __align__(16) uint8_t smem[];
+  constexpr int ND = NBL + NML + NMG + NBG;
+  uint8_t* tab = smem;
+  const int tid = threadIdx.x;
+  const GlobalOut gout{a.gsums, a.gcounts, nullptr, nullptr};
+
+  const int64_t n_vec = a.n / 4;
+  const int64_t v_begin = static_cast<int64_t>(blockIdx.x) * per_block;
+  const int64_t v_end = min(n_vec, v_begin + per_block);
+  int64_t v = v_begin + tid;
+  const v4i none = {-1, -1, -1, -1};
+  v4i cur[ND], nxt[ND];
+#pragma unroll
+  for (int k = 0; k < ND; ++k)
+    cur[k] = v < v_end ? __builtin_nontemporal_load(reinterpret_cast<const v4i*>(a.fk[k]) + v) : none;
+  {
+    const uint4* src = reinterpret_cast<const uint4*>(a.packed);
+    uint4* dst = reinterpret_cast<uint4*>(tab);
+    for (uint32_t i = tid; i < a.lds_bytes / 16; i += SCAN_THREADS) dst[i] = src[i];
+  }
+  __syncthreads();
+
+  // every lane of a wavefront takes the same number of steps (lanes past the end carry keys of -1, "no
+  // match"): merging equal groups before the atomics is a wavefront operation
+  while (v - (tid & 63) < v_end) {
+    const int64_t vn = v + SCAN_THREADS;
+#pragma unroll
+    for (int k = 0; k < ND; ++k)
+      nxt[k] = vn < v_end ? __builtin_nontemporal_load(reinterpret_cast<const v4i*>(a.fk[k]) + vn) : none;
+    int32_t g[4];
+    bool alive[4];
+#pragma unroll
+    for (int q = 0; q < 4; ++q) {
+      int32_t j[ND];
+#pragma unroll
+      for (int k = 0; k < ND; ++k) j[k] = cur[k][q];
+      g[q] = 0;
+      alive[q] = true;
+      classify_fast<NBL, NML, NMG, NBG>(a, tab, j, alive[q], g[q]);
+    }
+    const bool any = alive[0] || alive[1] || alive[2] || alive[3];
+    if (__ballot(any) != 0ull) {
+      long long val[4][MM];
+#pragma unroll
+      for (int m = 0; m < MM; ++m) {   // measure columns are only touched where a lane has a survivor
+        const v4i t = any ? *(reinterpret_cast<const v4i*>(a.meas[m]) + v) : none;
+#pragma unroll
+        for (int q = 0; q < 4; ++q) val[q][m] = t[q];
+      }
+#pragma unroll
+      for (int q = 0; q < 4; ++q) merge_and_add<MM>(alive[q], g[q], val[q], MM, a.G, gout);
+    }
+#pragma unroll
+    for (int k = 0; k < ND; ++k) cur[k] = nxt[k];
+    v = vn;
+  }
+  // ragged tail (n % 4 rows): one row per lane, straight to memory
+  if (blockIdx.x == 0) {
+    const int64_t i = n_vec * 4 + tid;
+    if (i < a.n) {
+      int32_t j[ND];
+#pragma unroll
+      for (int k = 0; k < ND; ++k) j[k] = a.fk[k][i];
+      int32_t g = 0;
+      bool alive = true;
+      classify_fast<NBL, NML, NMG, NBG>(a, tab, j, alive, g);
+      if (alive) {
+#pragma unroll
+        for (int m = 0; m < MM; ++m)
+          atomicAdd(&a.gsums[static_cast<size_t>(m) * a.G + g], static_cast<unsigned long long>(static_cast<long long>(a.meas[m][i])));
+        if (a.gcounts) atomicAdd(&a.gcounts[g], 1ull);
+      }
+    }
+  }
+}
+
+template <bool MEM, int NBL, int NML, int NMG, int NBG, int MM>
+int launch_fast_inst(const FastArgs& a, const FastLaunch& L) {
+  auto kernel = MEM ? &scan_fast_mem_kernel<NBL, NML, NMG, NBG, MM> : &scan_fast_kernel<NBL, NML, NMG, NBG, MM>;
+  if (L.lds > 64 * 1024)
+    LQ_HIP_TRY(hipFuncSetAttribute(reinterpret_cast<const void*>(kernel),
+                                   hipFuncAttributeMaxDynamicSharedMemorySize, static_cast<int>(L.lds)));
+  hipLaunchKernelGGL(kernel, dim3(L.blocks), dim3(SCAN_THREADS), L.lds, L.s, a, L.per_block);
+  LQ_LAUNCH_CHECK("scan_fast_kernel");
+  return LQ_OK;
+}
+template <bool MEM, int NBL, int NML, int NMG, int NBG>
+int launch_fast_m(const FastArgs& a, const FastLaunch& L) {
+  // (more than 8,192 accumulators need at least two grouping dimensions of up to 255 values each)
+  if constexpr (NBL + NML + NMG + NBG == 0 || (MEM && NBL + NBG < 2)) return -1;
+  else {
+    if (L.M == 1) return launch_fast_inst<MEM, NBL, NML, NMG, NBG, 1>(a, L);
+    if (L.M == 2) return launch_fast_inst<MEM, NBL, NML, NMG, NBG, 2>(a, L);
+    return -1;
+  }
+}
+template <bool MEM, int NBL, int NML>
+int launch_fast_g(const FastArgs& a, const FastLaunch& L) {
+  if (L.nmg == 0 && L.nbg == 0) return launch_fast_m<MEM, NBL, NML, 0, 0>(a, L);
+  if (L.nmg == 1 && L.nbg == 0) return launch_fast_m<MEM, NBL, NML, 1, 0>(a, L);
+  if (L.nmg == 0 && L.nbg == 1) return launch_fast_m<MEM, NBL, NML, 0, 1>(a, L);
+  if (L.nmg == 1 && L.nbg == 1) return launch_fast_m<MEM, NBL, NML, 1, 1>(a, L);
+  return -1;
+}
+template <bool MEM, int NBL>
+int launch_fast_ml(const FastArgs& a, const FastLaunch& L) {
+  switch (L.nml) {
+    case 0: return launch_fast_g<MEM, NBL, 0>(a, L);
+    case 1: return launch_fast_g<MEM, NBL, 1>(a, L);
+    case 2: return launch_fast_g<MEM, NBL, 2>(a, L);
+    case 3: return launch_fast_g<MEM, NBL, 3>(a, L);
+    default: return -1;
+  }
+}
+// Returns -1 when there is no instantiation for this mix of dimensions.
+template <bool MEM>
+int launch_fast(const FastArgs& a, const FastLaunch& L) {
+  switch (L.nbl) {
+    case 0: return launch_fast_ml<MEM, 0>(a, L);
+    case 1: return launch_fast_ml<MEM, 1>(a, L);
+    case 2: return launch_fast_ml<MEM, 2>(a, L);
+    case 3: return launch_fast_ml<MEM, 3>(a, L);
+    default: return -1;
+  }
+}
+
+}  // namespace
+}  // namespace lq
+#endif  // LQ_GROUPBY_FAST_H_

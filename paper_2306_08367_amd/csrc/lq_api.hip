@@ -442,7 +442,7 @@ size_t lq_groupby_workspace_bytes(int32_t n_dims, const int64_t* dim_rows, const
     if (group_card) {
       if (group_card[k] < 1 || group_card[k] > 65535) return 0;
       G *= group_card[k];
-      if (G > 8192) return 0;
+      if (G > LQ_MAX_GROUPS) return 0;
     }
   }
   return groupby_ws_bytes(n_dims, dim_rows, G * (n_measures + 1));
@@ -473,13 +473,11 @@ static int groupby_sum_checked(int64_t n_fact, int32_t n_dims, const int32_t* co
         return fail(LQ_ERR_SHAPE, "group_card[%d] = %d outside 1..65535", k, group_card[k]);
       if (!aligned(dim_code[k], 4)) return fail(LQ_ERR_SHAPE, "dim_code[%d] is not 4-byte aligned", k);
       G *= group_card[k];
-      if (G > 8192) return fail(LQ_ERR_UNSUPPORTED, "more than 8192 groups");
+      if (G > LQ_MAX_GROUPS) return fail(LQ_ERR_UNSUPPORTED, "more than 2^30 groups");
     }
     if (dim_rows[k] == 0 && n_fact > 0 && ((dim_code && dim_code[k]) || (dim_mask && dim_mask[k])))
       return fail(LQ_ERR_SHAPE, "dimension %d has no rows", k);
   }
-  if (G * (n_measures + 1) > 8192)
-    return fail(LQ_ERR_UNSUPPORTED, "groups x (measures + 1) = %lld exceeds 8192", (long long)(G * (n_measures + 1)));
   for (int m = 0; m < n_measures; ++m) {
     if (n_fact > 0 && !measures[m]) return fail(LQ_ERR_NULL, "measures[%d] is NULL", m);
     if (!aligned(measures[m], 4)) return fail(LQ_ERR_SHAPE, "measures[%d] is not 4-byte aligned", m);
@@ -574,7 +572,7 @@ size_t lq_groupby_agg_workspace_bytes(int32_t n_dims, const int64_t* dim_rows, c
     if (group_card) {
       if (group_card[k] < 1 || group_card[k] > 65535) return 0;
       G *= group_card[k];
-      if (G > 8192) return 0;
+      if (G > LQ_MAX_GROUPS) return 0;
     }
   }
   return groupby_ws_bytes(n_dims, dim_rows, G * (3 * n_measures + 1));
@@ -604,12 +602,11 @@ int lq_groupby_agg(int64_t n_fact, int32_t n_dims, const int32_t* const* fks, co
       if (!group_card) return fail(LQ_ERR_NULL, "group_card is NULL");
       if (group_card[k] < 1 || group_card[k] > 65535) return fail(LQ_ERR_SHAPE, "group_card[%d] outside 1..65535", k);
       G *= group_card[k];
-      if (G > 8192) return fail(LQ_ERR_UNSUPPORTED, "more than 8192 groups");
+      if (G > LQ_MAX_GROUPS) return fail(LQ_ERR_UNSUPPORTED, "more than 2^30 groups");
     }
     if (dim_rows[k] == 0 && n_fact > 0 && ((dim_code && dim_code[k]) || (dim_mask && dim_mask[k])))
       return fail(LQ_ERR_SHAPE, "dimension %d has no rows", k);
   }
-  if (G * (3 * n_measures + 1) > 8192) return fail(LQ_ERR_UNSUPPORTED, "groups x (3 measures + 1) exceeds 8192");
   for (int m = 0; m < n_measures; ++m) {
     if (measures[m].op < 0 || measures[m].op > 2) return fail(LQ_ERR_SHAPE, "measures[%d].op is unknown", m);
     if (n_fact > 0 && (!measures[m].a || (measures[m].op != 0 && !measures[m].b))) return fail(LQ_ERR_NULL, "measures[%d] lacks a column", m);

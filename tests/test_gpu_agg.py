@@ -77,3 +77,19 @@ def test_tables_too_large_for_lds_and_optional_outputs(lq):
     assert got["min"] is None and got["max"] is None
     np.testing.assert_array_equal(got["sum"].cpu().numpy(), want[0])
     np.testing.assert_array_equal(got["count"].cpu().numpy(), want[3])
+
+
+def test_more_groups_than_lds_accumulators(lq):
+    """25 x 25 x 250 groups with SUM / MIN / MAX / COUNT of a product and a difference: the outputs
+    themselves accumulate (device-wide atomics), empty groups keep 0 / INT64_MAX / INT64_MIN."""
+    fks, rows, masks, codes, card, c = _case(60, 700_001, (2_556, 30_000, 2_000, 200_000), (25, 25, 250, 1))
+    want = _check(lq, fks, rows, masks, codes, card, [(c["qty"], 1, 40)],
+                  [("mul", c["price"], c["disc"]), ("sub", c["price"], c["cost"])])
+    empty = want[3] == 0
+    assert empty.any() and (want[1][:, empty] == np.iinfo(np.int64).max).all() and (want[2][:, empty] == np.iinfo(np.int64).min).all()
+
+
+def test_many_groups_full_range_values_and_one_hot_group(lq):
+    fks, rows, masks, codes, card, c = _case(61, 400_003, (300, 301), (300, 301), big=True)
+    fks[0][:] = 7                                  # one dimension row for everyone: 301 populated groups of 90,300
+    _check(lq, fks, rows, masks, codes, card, [], [("mul", c["price"], c["cost"]), ("col", c["price"], None)])

@@ -111,12 +111,17 @@ def test_three_grouping_dimensions_and_wide_codes(lq):
     _check(lq, _random_groupby(36, 60_000, (40, 30, 8), (10, 10, 8), n_measures=4))
 
 
-def test_largest_supported_group_count(lq):
-    # 64 x 64 = 4,096 groups with one measure: (M + 1) * G = 8,192 accumulators, the documented limit
+def test_both_sides_of_the_lds_accumulator_limit(lq):
+    # 64 x 64 = 4,096 groups with one measure: (M + 1) * G = 8,192 accumulators, the most a workgroup keeps
+    # in LDS; with two measures the same groups need 12,288 and the output arrays accumulate instead
     _check(lq, _random_groupby(43, 300_001, (500, 700, 20), (64, 64, 1), n_measures=1))
-    w = to_dev(_random_groupby(44, 1_000, (500, 700), (64, 64), n_measures=2))
-    with pytest.raises(lq.LQError) as e:
-        _gpu(lq, w)
+    _check(lq, _random_groupby(44, 300_001, (500, 700, 20), (64, 64, 1), n_measures=2))
+    w = to_dev(_random_groupby(44, 1_000, (500, 700), (65_535, 65_535), n_measures=2))
+    with pytest.raises(lq.LQError) as e:                     # more than 2^30 groups
+        lq.lq_masked_groupby_sum(w.fks, w.dim_rows, w.dim_mask, w.dim_code, w.group_card, w.fact_mask, w.measures,
+                                 sums=torch.empty((2, 1), dtype=torch.int64, device="cuda"),
+                                 counts=torch.empty((1,), dtype=torch.int64, device="cuda"),
+                                 ws=torch.empty(1 << 20, dtype=torch.uint8, device="cuda"))
     assert e.value.status == "LQ_ERR_UNSUPPORTED"
 
 
@@ -250,3 +255,83 @@ def test_reuse_side_tables_skips_the_dimension_pass_and_gives_the_same_result(lq
     s, c = _gpu(lq, w2, ws=ws, flags=lq.LQ_REUSE_SIDE_TABLES)
     np.testing.assert_array_equal(s, ws2)
     np.testing.assert_array_equal(c, wc2)
+
+
+# ---------------------------------------------------------------- more groups than LDS accumulators
+# The multi-column group-by of Section 2.4.2 multiplies the cardinalities of its grouping attributes:
+# above 8,192 accumulators the output arrays themselves accumulate (device-wide atomics).
+
+def _many_groups(seed, n, rows, card, n_measures, sel=None, fact_mask=False, hot=False, neg=False):
+    r = np.random.default_rng(seed)
+    K = len(rows)
+    fks = [torch.from_numpy(r.integers(0, a, size=n).astype(np.int32)) for a in rows]
+    if hot and n:        # most fact rows point at the same few dimension rows: many lanes hit one group
+        for f, a in zip(fks, rows):
+            f[torch.from_numpy(r.random(n) < 0.7)] = int(r.integers(0, a))
+    if neg and n:
+        fks[K - 1][torch.from_numpy(r.integers(0, n, size=max(1, n // 50)))] = -1
+    codes = [torch.from_numpy(r.integers(0, card[k], size=rows[k]).astype(np.int32)) if card[k] > 1 else None
+             for k in range(K)]
+    masks = [None if sel is None or sel[k] is None else torch.from_numpy((r.random(rows[k]) < sel[k]).astype(np.uint8))
+             for k in range(K)]
+    meas = [torch.from_numpy(r.integers(-100_000, 100_001, size=n).astype(np.int32)) for _ in range(n_measures)]
+    fm = torch.from_numpy((r.random(n) < 0.9).astype(np.uint8)) if fact_mask else None
+    return WL.GroupByWorkload("many_groups", n, fks, list(rows), masks, codes, list(card), fm, meas)
+
+
+@pytest.mark.parametrize("n_measures", [1, 4])
+def test_three_grouping_attributes_25_25_250(lq, n_measures):
+    # 156,250 groups; the fourth dimension only filters (about 2.4 % of the fact rows survive)
+    w = _many_groups(300 + n_measures, 1_500_003, (2_556, 30_000, 2_000, 200_000), (25, 25, 250, 1), n_measures,
+                     sel=(None, 0.2, None, 0.12))
+    w, ws, wc = _check(lq, w)
+    assert ws.shape == (n_measures, 156_250) and 10_000 < (wc > 0).sum() < 156_250      # most groups stay empty
+
+
+@pytest.mark.parametrize("n_measures", [1, 4])
+def test_one_million_groups_every_row_survives(lq, n_measures):
+    # 1000 x 1000 groups (16-bit codes), no predicate: 2M atomics per measure, every group about twice
+    w = _many_groups(310 + n_measures, 2_000_001, (5_000, 70_000), (1_000, 1_000), n_measures)
+    w, ws, wc = _check(lq, w)
+    assert wc.sum() == w.n and (wc > 0).sum() > 800_000
+
+
+def test_many_groups_with_a_few_hot_ones(lq):
+    # 70 % of the rows fall into one group: the lanes of a wavefront are merged before the atomic
+    w = _many_groups(320, 3_000_017, (300, 300), (300, 300), 2, hot=True, fact_mask=True)
+    w, ws, wc = _check(lq, w)
+    assert wc.max() > 0.4 * wc.sum()
+
+
+@pytest.mark.parametrize("n", [0, 1, 5, 63, 64, 65, 1_023, 4_099])
+def test_many_groups_ragged_sizes_negative_keys_fact_mask(lq, n):
+    _check(lq, _many_groups(330 + n, n, (70, 110, 50, 13), (30, 40, 9, 1), 2, sel=(None, 0.8, 0.5, 0.6),
+                            fact_mask=True, neg=True))
+
+
+def test_many_groups_unaligned_columns_counts_optional_and_flags(lq):
+    w = _many_groups(340, 300_001, (700, 1_100, 40_000), (100, 120, 1), 1, sel=(None, None, 0.5))
+    ws_, wc_ = _oracle(w)
+    w = to_dev(w)
+    # columns that start 4 bytes past a 16-byte boundary: the one-row-per-lane form of the scan
+    off = lambda t: torch.cat([torch.zeros(1, dtype=t.dtype, device="cuda"), t])[1:]
+    w.fks = [off(f) for f in w.fks]
+    w.measures = [off(m) for m in w.measures]
+    s, c = _gpu(lq, w)
+    np.testing.assert_array_equal(s, ws_)
+    np.testing.assert_array_equal(c, wc_)
+    sums = torch.full((1, 12_000), 99, dtype=torch.int64, device="cuda")
+    s, c = _gpu(lq, w, sums=sums, want_counts=False)
+    assert c is None
+    np.testing.assert_array_equal(s, ws_)
+    # checked call, then the same query again on the encoded side tables
+    ws = torch.empty(lq.lq_groupby_workspace_bytes(w.dim_rows, w.group_card, 1), dtype=torch.uint8, device="cuda")
+    s, c = _gpu(lq, w, ws=ws, flags=lq.LQ_CHECK_FKS)
+    np.testing.assert_array_equal(s, ws_)
+    s, c = _gpu(lq, w, ws=ws, flags=lq.LQ_REUSE_SIDE_TABLES)
+    np.testing.assert_array_equal(s, ws_)
+    np.testing.assert_array_equal(c, wc_)
+    w.fks[0][123] = 700
+    with pytest.raises(lq.LQError) as e:
+        _gpu(lq, w, ws=ws, flags=lq.LQ_CHECK_FKS)
+    assert e.value.status == "LQ_ERR_FK_RANGE"

@@ -135,7 +135,10 @@ def test_groupby_rejects_bad_arguments():
     def call(card, n_meas=1, ws=FAKE, ws_bytes=1 << 20, sums=FAKE, K=2):
         return lib.lq_masked_groupby_sum(100, K, fks, rows, None, codes, (i32 * 2)(*card), None,
                                          n_meas, meas, sums, None, ws, ws_bytes, 0, None)
-    assert call((100, 100)) == 6                              # 10,000 groups > 8192
+    assert call((65_535, 65_535)) == 6                        # more than 2^30 groups
+    assert b.lq_groupby_workspace_bytes([10, 20], [65_535, 65_535], 1) == 0
+    # above 8,192 accumulators the outputs themselves accumulate: the workspace only holds the side tables
+    assert 0 < b.lq_groupby_workspace_bytes([10, 20], [100, 100], 1) < b.lq_groupby_workspace_bytes([10, 20], [60, 60], 1)
     assert call((0, 5)) == 2
     assert call((5, 5), n_meas=0) == 2
     assert call((5, 5), n_meas=5) == 2
