@@ -527,6 +527,26 @@ int lq_order_groups(int32_t n_group_cols, const int32_t* group_card, int32_t n_m
  */
 int lq_stream_copy(void* dst, const void* src, size_t bytes, void* hip_stream);
 
+/*
+ * Two more yardsticks (not part of the method either): what the GPU delivers for the access patterns of the
+ * join stage, with none of its arithmetic.  Nothing is written; `sink` is 16 bytes of device memory that the
+ * kernels only name.
+ *   lq_yardstick_read    reads `bytes` bytes (multiple of 16, 16-byte aligned) `repeats` times in one launch:
+ *                        a buffer that fits the Infinity Cache gives that cache's read rate, a large one HBM's
+ *   lq_yardstick_stream  the same reads and, in the same launch, wbytes bytes of zeros written to wbuf: a pure
+ *                        stream with the read : write mix of a kernel under study
+ *   lq_yardstick_gather  n_gathers random row reads from a table of `rows` rows of row_bytes bytes each (a
+ *                        power of two, 16 .. 1024; a row is fetched by adjacent lanes as one contiguous run,
+ *                        eight rows in flight per lane).  keys == NULL: row numbers are hashed from the
+ *                        gather's index and `seed` (uniform; no other memory traffic); otherwise
+ *                        keys[0 .. n_gathers) are the row numbers (their 4 bytes per gather are streamed)
+ */
+int lq_yardstick_read(const void* buf, size_t bytes, int32_t repeats, void* sink, void* hip_stream);
+int lq_yardstick_stream(const void* buf, size_t bytes, int32_t repeats, void* wbuf, size_t wbytes, void* sink,
+                        void* hip_stream);
+int lq_yardstick_gather(const void* table, int64_t rows, int32_t row_bytes, int64_t n_gathers,
+                        const int32_t* keys, uint32_t seed, void* sink, void* hip_stream);
+
 /* Description of the last error on this host thread ("" if none). */
 const char* lq_last_error(void);
 

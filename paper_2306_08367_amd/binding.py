@@ -105,6 +105,12 @@ def _load():
     lib.lq_groupby_workspace_bytes.argtypes = [i32, ctypes.POINTER(i64), ctypes.POINTER(i32), i32]
     lib.lq_groupby_workspace_bytes.restype = sz
     lib.lq_stream_copy.argtypes = [vp, vp, sz, vp]
+    lib.lq_yardstick_read.argtypes = [vp, sz, i32, vp, vp]
+    lib.lq_yardstick_read.restype = ctypes.c_int
+    lib.lq_yardstick_stream.argtypes = [vp, sz, i32, vp, sz, vp, vp]
+    lib.lq_yardstick_stream.restype = ctypes.c_int
+    lib.lq_yardstick_gather.argtypes = [vp, i64, i32, i64, vp, u32, vp, vp]
+    lib.lq_yardstick_gather.restype = ctypes.c_int
     lib.lq_groupby_agg.argtypes = [i64, i32, ctypes.POINTER(vp), ctypes.POINTER(i64), ctypes.POINTER(vp),
                                    ctypes.POINTER(vp), ctypes.POINTER(i32), i32, ctypes.POINTER(lq_range_pred),
                                    i32, ctypes.POINTER(lq_measure), vp, vp, vp, vp, vp, sz, u32, vp]
@@ -465,6 +471,31 @@ def lq_stream_copy(dst: torch.Tensor, src: torch.Tensor, stream=None) -> None:
     if dst.numel() * dst.element_size() < nbytes:
         raise ValueError("destination smaller than source")
     _check(_lib.lq_stream_copy(dst.data_ptr(), src.data_ptr(), nbytes, _stream(stream)))
+
+
+def lq_yardstick_read(buf: torch.Tensor, repeats: int, sink: torch.Tensor, stream=None) -> None:
+    """Reads `buf` `repeats` times in one launch (bandwidth yardstick; nothing is written)."""
+    _check(_lib.lq_yardstick_read(buf.data_ptr(), buf.numel() * buf.element_size(), int(repeats), sink.data_ptr(),
+                                  _stream(stream)))
+
+
+def lq_yardstick_stream(buf: torch.Tensor, repeats: int, wbuf: torch.Tensor, sink: torch.Tensor, stream=None) -> None:
+    """Reads `buf` `repeats` times and overwrites `wbuf` with zeros, in one launch (stream yardstick)."""
+    _check(_lib.lq_yardstick_stream(buf.data_ptr(), buf.numel() * buf.element_size(), int(repeats), wbuf.data_ptr(),
+                                    wbuf.numel() * wbuf.element_size(), sink.data_ptr(), _stream(stream)))
+
+
+def lq_yardstick_gather(table: torch.Tensor, row_bytes: int, n_gathers: int, sink: torch.Tensor,
+                        keys: Optional[torch.Tensor] = None, seed: int = 1, stream=None) -> None:
+    """n_gathers random reads of row_bytes-byte rows of `table` (gather yardstick; nothing is written)."""
+    rows = table.numel() * table.element_size() // int(row_bytes)
+    if keys is not None:
+        _expect(keys, torch.int32, "keys")
+        if keys.numel() < n_gathers:
+            raise ValueError("fewer keys than gathers")
+    _check(_lib.lq_yardstick_gather(table.data_ptr(), rows, int(row_bytes), int(n_gathers),
+                                    None if keys is None else keys.data_ptr(), int(seed) & 0xffffffff, sink.data_ptr(),
+                                    _stream(stream)))
 
 
 # ---------------------------------------------------------------- decision trees --------------
