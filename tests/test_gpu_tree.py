@@ -341,3 +341,34 @@ def test_mask_join_with_more_fact_side_nodes_than_the_lds_list_holds(lq):
     np.testing.assert_array_equal(leaf_l[rows.cuda()].cpu().numpy(), want)
     np.testing.assert_array_equal(oh_k[rows.cuda()].cpu().numpy(), onehot)
     assert (want >= 0).any() and (want == -1).any() and (onehot.sum(axis=1) > 1).any()
+
+
+def test_more_than_32767_nodes_most_of_them_on_no_path(lq):
+    """The matrix form allows nodes that lie on no leaf's path (all-zero rows of H).  Past 32,767 nodes the
+    pre-fusion walks the columns of H directly instead of building per-leaf node lists."""
+    w, tree = _case("many_nodes", 1_003, 0, (40, 50), (6, 6), 12, WL.SEED0 + 610)
+    p, l = tree.H.shape
+    extra = 33_000 - p
+    r = np.random.default_rng(610)
+    feature = torch.cat([tree.feature, torch.from_numpy(r.integers(0, 12, size=extra).astype(np.int32))])
+    thr = torch.cat([tree.threshold, torch.from_numpy(r.normal(size=extra).astype(np.float32))])
+    H = torch.cat([tree.H, torch.zeros((extra, l), dtype=torch.int8)])
+    perm = torch.from_numpy(r.permutation(33_000))              # the tree's own nodes end up anywhere
+    feature, thr, H = feature[perm].contiguous(), thr[perm].contiguous(), H[perm].contiguous()
+    _, onehot, leaf = O.tree_predict(w.X, w.dims, w.fks, feature, thr, H)
+    assert (leaf >= 0).all()
+    w = to_dev(w)
+    f, t, Hd = feature.cuda(), thr.cuda(), H.cuda()
+    tables, target = lq.lq_tree_project_dims(w.dims, 0, f, t, Hd)
+    g_leaf, g_oh = lq.lq_fused_join_tree(None, w.fks, tables, target, f, t, Hd, want_onehot=True)
+    torch.cuda.synchronize()
+    np.testing.assert_array_equal(g_leaf.cpu().numpy(), leaf)
+    np.testing.assert_array_equal(g_oh.cpu().numpy(), onehot)
+    # the tables themselves: agreement counts = the oracle's signed partial sums + the table's own -1 entries per leaf
+    Pw = O.tree_project([d.cpu() for d in w.dims], 0, feature, thr, H)
+    Hn, feat, off = H.numpy().astype(np.int64), feature.numpy(), 0
+    for k, d in enumerate(w.dims):
+        own = (feat >= off) & (feat < off + d.shape[1])
+        neg = (Hn[own] == -1).sum(axis=0)
+        np.testing.assert_array_equal(tables[k][:, :l].cpu().numpy().astype(np.int64), Pw[k] + neg)
+        off += d.shape[1]
