@@ -259,7 +259,7 @@ int lq_masked_groupby_sum_static(int64_t n_fact, int32_t n_dims, const int32_t* 
  * The same aggregate with the rest of the query shapes of the benchmark's query groups: range
  * predicates on fact columns (selection vectors on the fact table, Section 2.2), measures that are
  * a column, the element-wise product or the difference of two columns (computed in int64), and
- * SUM / MIN / MAX / COUNT per group.  AVG is sums / counts.  Arguments as for
+ * SUM / MIN / MAX / COUNT per group (AVG: lq_group_avg on the sums and counts).  Arguments as for
  * lq_masked_groupby_sum, plus:
  *   preds     host array of n_preds (0..4) predicates: keep row i iff lo <= col[i] <= hi
  *   measures  host array of n_measures (1..LQ_MAX_MEASURES) expressions over device int32 columns
@@ -281,6 +281,16 @@ int lq_groupby_agg(int64_t n_fact, int32_t n_dims, const int32_t* const* fks, co
                    void* hip_stream);
 size_t lq_groupby_agg_workspace_bytes(int32_t n_dims, const int64_t* dim_rows,
                                       const int32_t* group_card, int32_t n_measures);
+
+/*
+ * AVG per group from the SUM and COUNT results of lq_masked_groupby_sum / lq_groupby_agg on the same stream
+ * (the aggregation functions applied after the group-mapping product, Section 2.4):
+ *   avgs[m][g] = sums[m][g] / counts[g] in fp64 (both converted to double, one division, so exact to the last
+ *   bit whenever |sum| < 2^53), NaN for a group without rows.
+ *   sums device int64 [n_measures x n_groups], counts device int64 [n_groups], avgs device double, same shape as sums
+ */
+int lq_group_avg(int32_t n_measures, int64_t n_groups, const int64_t* sums, const int64_t* counts, double* avgs,
+                 void* hip_stream);
 
 /* Workspace sizes in bytes (0 on invalid arguments).  For the group-by, group_card[k] must be
  * 1 for dimensions that do not group (group_card may be NULL when none does); the size depends

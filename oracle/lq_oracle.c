@@ -45,6 +45,7 @@
  * rows are independent in the predict path, and the group-by merges
  * per-thread int64 accumulators in thread order (integers: exact).
  */
+#include <math.h>
 #include <stdint.h>
 #include <stdlib.h>
 #include <string.h>
@@ -380,4 +381,15 @@ int lqo_groupby_agg(int64_t n, int32_t K, const int32_t* const* fk, const uint8_
     if (counts) counts[g] += 1;
   }
   return 0;
+}
+
+/* ------------------------------------------------------------------------------------------
+ * AVG per group from the SUM and COUNT of the same query (the aggregation functions of Section 2.4):
+ *   avgs[m][g] = sums[m][g] / counts[g] in fp64 (both operands converted to double, one division),
+ *   NaN for a group without rows (SQL: no such group, or NULL).
+ * ------------------------------------------------------------------------------------------ */
+void lqo_group_avg(int64_t n_meas, int64_t G, const int64_t* sums, const int64_t* counts, double* avgs) {
+  for (int64_t m = 0; m < n_meas; ++m)
+    for (int64_t g = 0; g < G; ++g)
+      avgs[m * G + g] = counts[g] > 0 ? (double)sums[m * G + g] / (double)counts[g] : NAN;
 }

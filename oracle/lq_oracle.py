@@ -321,3 +321,14 @@ def groupby_agg(fks, dim_rows, dim_mask, dim_code, group_card, preds, measures):
     if rc != 0:
         raise ValueError("group code outside [0, cardinality)")
     return sums, mins, maxs, counts
+
+
+def group_avg(sums, counts) -> np.ndarray:
+    """AVG per group = SUM / COUNT in fp64 ([M x G] from sums [M x G] and counts [G]); NaN where a group has no rows."""
+    lib = _load()
+    sums = np.ascontiguousarray(np.asarray(sums, dtype=np.int64))
+    counts = np.ascontiguousarray(np.asarray(counts, dtype=np.int64))
+    M, G = sums.shape
+    avgs = np.empty((M, G), dtype=np.float64)
+    lib.lqo_group_avg(ctypes.c_int64(M), ctypes.c_int64(G), _pd(sums), _pd(counts), _pd(avgs))
+    return avgs

@@ -105,6 +105,8 @@ def _load():
     lib.lq_groupby_workspace_bytes.argtypes = [i32, ctypes.POINTER(i64), ctypes.POINTER(i32), i32]
     lib.lq_groupby_workspace_bytes.restype = sz
     lib.lq_stream_copy.argtypes = [vp, vp, sz, vp]
+    lib.lq_group_avg.argtypes = [i32, i64, vp, vp, vp, vp]
+    lib.lq_group_avg.restype = ctypes.c_int
     lib.lq_yardstick_read.argtypes = [vp, sz, i32, vp, vp]
     lib.lq_yardstick_read.restype = ctypes.c_int
     lib.lq_yardstick_stream.argtypes = [vp, sz, i32, vp, sz, vp, vp]
@@ -464,6 +466,22 @@ def lq_masked_groupby_sum_static(fks: Sequence[torch.Tensor], dim_rows: Sequence
         None if fact_mask is None else fact_mask.data_ptr(), len(measures), _ptr_array(measures),
         sums.data_ptr(), None if counts is None else counts.data_ptr(), flags, _stream(stream)))
     return sums, counts
+
+
+def lq_group_avg(sums: torch.Tensor, counts: torch.Tensor, avgs: Optional[torch.Tensor] = None, stream=None) -> torch.Tensor:
+    """AVG per group = sums / counts in fp64 ([M x G]); NaN where a group has no rows."""
+    _expect(sums, torch.int64, "sums")
+    _expect(counts, torch.int64, "counts")
+    if sums.dim() != 2 or sums.shape[1] != counts.shape[0] or not sums.is_contiguous():
+        raise ValueError("sums must be a contiguous [n_measures x G] tensor and counts [G]")
+    if avgs is None:
+        avgs = _empty(stream, sums.shape, dtype=torch.float64, device=sums.device)
+    _expect(avgs, torch.float64, "avgs")
+    if avgs.shape != sums.shape or not avgs.is_contiguous():
+        raise ValueError("avgs must be contiguous and shaped like sums")
+    _check(_lib.lq_group_avg(int(sums.shape[0]), int(sums.shape[1]), sums.data_ptr(), counts.data_ptr(), avgs.data_ptr(),
+                             _stream(stream)))
+    return avgs
 
 
 def lq_stream_copy(dst: torch.Tensor, src: torch.Tensor, stream=None) -> None:

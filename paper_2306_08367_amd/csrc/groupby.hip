@@ -554,6 +554,16 @@ __global__ __launch_bounds__(SCAN_THREADS) void scan_global_kernel(GbArgs a, Agg
   }
 }
 
+// AVG = SUM / COUNT per group, in fp64 (one correctly rounded division); NaN for a group without rows.
+__global__ __launch_bounds__(256) void group_avg_kernel(const long long* __restrict__ sums, const long long* __restrict__ counts,
+                                                        double* __restrict__ avgs, int64_t MG, int64_t G) {
+  const int64_t stride = static_cast<int64_t>(gridDim.x) * blockDim.x;
+  for (int64_t i = static_cast<int64_t>(blockIdx.x) * blockDim.x + threadIdx.x; i < MG; i += stride) {
+    const long long c = counts[i % G];
+    avgs[i] = c > 0 ? static_cast<double>(sums[i]) / static_cast<double>(c) : __longlong_as_double(0x7ff8000000000000LL);
+  }
+}
+
 constexpr size_t LDS_BUDGET = 160 * 1024 - 1024;   // gfx950 workgroups may use the whole 160 KB
 
 // Fills kind / off / bytes of every dimension; returns the packed size.  Tables are laid out by
@@ -613,6 +623,16 @@ size_t groupby_ws_bytes(int32_t K, const int64_t* rows, int64_t n_acc) {
   if (n_acc > GROUPBY_LDS_ACCUMULATORS) return groupby_tables_bytes(K, rows) + 256;
   return groupby_tables_bytes(K, rows) +
          round_up(static_cast<size_t>(groupby_max_workgroups()) * n_acc * 8, 256);
+}
+
+int launch_group_avg(int32_t M, int64_t G, const int64_t* sums, const int64_t* counts, double* avgs, hipStream_t s) {
+  const int64_t MG = static_cast<int64_t>(M) * G;
+  if (MG == 0) return LQ_OK;
+  const int64_t blocks = std::min<int64_t>((MG + 255) / 256, static_cast<int64_t>(num_cus()) * 8);
+  hipLaunchKernelGGL(group_avg_kernel, dim3(static_cast<unsigned>(blocks)), dim3(256), 0, s,
+                     reinterpret_cast<const long long*>(sums), reinterpret_cast<const long long*>(counts), avgs, MG, G);
+  LQ_LAUNCH_CHECK("group_avg_kernel");
+  return LQ_OK;
 }
 
 // sums / counts = 0, mins / maxs = neutral elements, for the accumulators-in-memory form.

@@ -47,6 +47,7 @@ int launch_groupby_agg(int64_t n, int32_t K, const int32_t* const* fks, const in
                        int64_t* sums, int64_t* mins, int64_t* maxs, int64_t* counts, int32_t G, void* ws,
                        bool reuse_tables, hipStream_t s);
 size_t groupby_tables_bytes(int32_t K, const int64_t* rows);
+int launch_group_avg(int32_t M, int64_t G, const int64_t* sums, const int64_t* counts, double* avgs, hipStream_t s);
 
 namespace {
 
@@ -623,6 +624,17 @@ int lq_groupby_agg(int64_t n_fact, int32_t n_dims, const int32_t* const* fks, co
   return launch_groupby_agg(n_fact, n_dims, fks, dim_rows, dim_mask, dim_code, group_card, n_preds, preds,
                             n_measures, measures, sums, mins, maxs, counts, static_cast<int32_t>(G), ws,
                             (flags & LQ_REUSE_SIDE_TABLES) != 0, s);
+}
+
+int lq_group_avg(int32_t n_measures, int64_t n_groups, const int64_t* sums, const int64_t* counts, double* avgs,
+                 void* hip_stream) {
+  clear_error();
+  if (n_measures < 1 || n_measures > LQ_MAX_MEASURES) return fail(LQ_ERR_SHAPE, "n_measures %d outside 1..%d", n_measures, LQ_MAX_MEASURES);
+  if (n_groups < 0 || n_groups > LQ_MAX_GROUPS) return fail(LQ_ERR_SHAPE, "n_groups outside 0..2^30");
+  if (n_groups == 0) return LQ_OK;
+  if (!sums || !counts || !avgs) return fail(LQ_ERR_NULL, "sums, counts or avgs is NULL");
+  if (!aligned(sums, 8) || !aligned(counts, 8) || !aligned(avgs, 8)) return fail(LQ_ERR_SHAPE, "arrays are not 8-byte aligned");
+  return launch_group_avg(n_measures, n_groups, sums, counts, avgs, static_cast<hipStream_t>(hip_stream));
 }
 
 int lq_stream_copy(void* dst, const void* src, size_t bytes, void* hip_stream) {

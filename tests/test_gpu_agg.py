@@ -93,3 +93,20 @@ def test_many_groups_full_range_values_and_one_hot_group(lq):
     fks, rows, masks, codes, card, c = _case(61, 400_003, (300, 301), (300, 301), big=True)
     fks[0][:] = 7                                  # one dimension row for everyone: 301 populated groups of 90,300
     _check(lq, fks, rows, masks, codes, card, [], [("mul", c["price"], c["cost"]), ("col", c["price"], None)])
+
+
+def test_avg_from_sums_and_counts(lq):
+    """AVG = SUM / COUNT in fp64, bit for bit the oracle's quotient; NaN exactly where a group has no rows; also on
+    the accumulators-in-memory form (more than 8,192 accumulators) and with sums beyond 2^53."""
+    for seed, n, rows, card, big in ((70, 300_001, (7, 40, 13), (7, 5, 1), False), (71, 200_003, (300, 301), (300, 301), True)):
+        fks, rws, masks, codes, cd, c = _case(seed, n, rows, card, big=big)
+        meas = [("mul", c["price"], c["cost"]), ("col", c["qty"], None)]
+        want = O.groupby_agg(fks, rws, masks, codes, cd, [], meas)
+        want_avg = O.group_avg(want[0], want[3])
+        dev = lambda a: None if a is None else torch.from_numpy(a).cuda()
+        got = lq.lq_groupby_agg([dev(f) for f in fks], rws, [dev(m) for m in masks], [dev(x) for x in codes], cd, [],
+                                [(op, dev(a), dev(b)) for op, a, b in meas], want=("sum", "count"))
+        avg = lq.lq_group_avg(got["sum"], got["count"])
+        torch.cuda.synchronize()
+        np.testing.assert_array_equal(avg.cpu().numpy(), want_avg)             # NaN == NaN in this comparison
+        assert np.isnan(want_avg).any() == (want[3] == 0).any()

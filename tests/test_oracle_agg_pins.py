@@ -94,3 +94,35 @@ def test_products_do_not_wrap_at_32_bits():
     assert sums[0, 0] == (2**31 - 1) ** 2 + 2 * (-2**31) * (2**31 - 1)
     assert sums[1, 0] == 0 + (-2**31 - (2**31 - 1)) + (2**31 - 1 + 2**31)
     assert maxs[0, 0] == (2**31 - 1) ** 2 and mins[1, 0] == -2**32 + 1
+
+
+def test_avg_is_the_exact_mean_of_the_group_rounded_once():
+    """AVG against the mean computed exactly (Python fractions over the surviving rows of each group, rounded to
+    fp64 once): sums stay below 2^53, so SUM / COUNT in fp64 is that same correctly rounded quotient; a group
+    without rows gives NaN; hand-worked: values 1, 2, 4 -> 7/3."""
+    from fractions import Fraction
+    r = np.random.default_rng(9)
+    n, rows, card = 5_000, (13, 9), (13, 3)
+    fks = [r.integers(0, a, size=n).astype(np.int32) for a in rows]
+    codes = [r.integers(0, c, size=a).astype(np.int32) for a, c in zip(rows, card)]
+    codes[1][:] = np.arange(9) % 2                                   # code 2 of the second table never occurs
+    masks = [None, (r.random(9) < 0.7).astype(np.uint8)]
+    a, b = r.integers(-10**5, 10**5, size=n).astype(np.int32), r.integers(1, 50, size=n).astype(np.int32)
+    sums, _, _, counts = O.groupby_agg(fks, rows, masks, codes, card, [], [("mul", a, b), ("col", a, None)])
+    avgs = O.group_avg(sums, counts)
+    exact = {}
+    for i in range(n):
+        if not masks[1][fks[1][i]]:
+            continue
+        g = int(codes[0][fks[0][i]]) * 3 + int(codes[1][fks[1][i]])
+        exact.setdefault(g, []).append((int(a[i]) * int(b[i]), int(a[i])))
+    for g in range(39):
+        if g not in exact:
+            assert counts[g] == 0 and np.isnan(avgs[:, g]).all()
+        else:
+            for m in range(2):
+                want = float(Fraction(sum(v[m] for v in exact[g]), len(exact[g])))
+                assert avgs[m, g] == want
+    assert np.isnan(avgs[:, 2::3]).all() and len(exact) >= 10          # code 2 never occurs; many groups do
+    hand = O.group_avg(np.array([[7, -9, 0]]), np.array([3, 2, 0]))
+    assert hand[0, 0] == 7 / 3 and hand[0, 1] == -4.5 and np.isnan(hand[0, 2])
