@@ -22,90 +22,17 @@
 namespace lq {
 
 int launch_fast_many(const FastArgs& a, const FastLaunch& L);   // groupby_many.hip
+int launch_agg_fast(const GbArgs& a, const AggFastArgs& x, const FastLaunch& L, int n_preds, int pack_here);   // groupby_agg_fast.hip
 
 namespace {
 
 constexpr int64_t GROUPBY_LDS_ACCUMULATORS = 8192;   // int64 accumulators a scan workgroup keeps in LDS
 
-enum DimKind : int32_t { DK_NONE = 0, DK_BITMAP = 1, DK_BYTE = 2, DK_U16 = 3 };
-
-struct GbDim {
-  const int32_t* fk;
-  const uint8_t* mask;   // raw, may be NULL
-  const int32_t* code;   // raw, may be NULL
-  int64_t rows;
-  int32_t kind;
-  int32_t card;          // 1 when not grouping
-  int32_t stride;        // weight of this dimension's code in the group number (0 when not grouping)
-  uint32_t off;          // byte offset of the packed table (16-byte aligned)
-  uint32_t bytes;        // packed size, multiple of 16
-  int32_t in_lds;        // 1 when the table is part of the LDS-resident prefix
-};
-
-struct GbArgs {
-  int64_t n;
-  int32_t K;
-  GbDim d[LQ_MAX_DIMS];
-  const uint8_t* fact_mask;
-  int32_t M;
-  const int32_t* meas[LQ_MAX_MEASURES];
-  unsigned long long* sums;    // [M x G]
-  unsigned long long* counts;  // [G] or NULL
-  int32_t G;
-  uint8_t* packed;             // workspace: all packed tables
-  uint32_t packed_bytes;
-  unsigned long long* partial; // workspace: [workgroups x (M+1) x G]
-};
-
 // ---------------------------------------------------------------- pack ------------------
 
-// Work is cut into 256-thread units: unit u of dimension k covers 64*4 = 256 ... see unit_count().
-// BITMAP: a wavefront turns 64 mask bytes into one 64-bit ballot word per step.
-// BYTE / U16: one thread builds 4 consecutive entries and stores them as one word (pair).
 __global__ __launch_bounds__(256) void pack_kernel(GbArgs a) {
-  const int64_t gtid = static_cast<int64_t>(blockIdx.x) * blockDim.x + threadIdx.x;
-  const int64_t gstride = static_cast<int64_t>(gridDim.x) * blockDim.x;
-  const int lane = threadIdx.x & 63;
-  const int64_t gwave = gtid >> 6, nwave = gstride >> 6;
-  for (int k = 0; k < a.K; ++k) {
-    const GbDim& d = a.d[k];
-    if (d.kind == DK_BITMAP) {
-      unsigned long long* out = reinterpret_cast<unsigned long long*>(a.packed + d.off);
-      const int64_t steps = d.bytes / 8;               // 64 rows per step
-      for (int64_t q = gwave; q < steps; q += nwave) {
-        const int64_t j = q * 64 + lane;
-        const bool on = j < d.rows && d.mask[j] != 0;
-        const unsigned long long bits = __ballot(on);
-        if (lane == 0) out[q] = bits;
-      }
-    } else if (d.kind == DK_BYTE) {
-      uint32_t* out = reinterpret_cast<uint32_t*>(a.packed + d.off);
-      for (int64_t q = gtid; q < d.bytes / 4; q += gstride) {
-        uint32_t w = 0;
-#pragma unroll
-        for (int b = 0; b < 4; ++b) {
-          const int64_t j = q * 4 + b;
-          uint32_t v = 0xffu;
-          if (j < d.rows && (!d.mask || d.mask[j])) v = d.code ? static_cast<uint32_t>(d.code[j]) & 0xffu : 0u;
-          w |= v << (8 * b);
-        }
-        out[q] = w;
-      }
-    } else if (d.kind == DK_U16) {
-      uint32_t* out = reinterpret_cast<uint32_t*>(a.packed + d.off);
-      for (int64_t q = gtid; q < d.bytes / 4; q += gstride) {
-        uint32_t w = 0;
-#pragma unroll
-        for (int b = 0; b < 2; ++b) {
-          const int64_t j = q * 2 + b;
-          uint32_t v = 0xffffu;
-          if (j < d.rows && (!d.mask || d.mask[j])) v = static_cast<uint32_t>(d.code[j]) & 0xffffu;
-          w |= v << (16 * b);
-        }
-        out[q] = w;
-      }
-    }
-  }
+  pack_tables(a, a.packed, static_cast<int64_t>(blockIdx.x) * blockDim.x + threadIdx.x,
+              static_cast<int64_t>(gridDim.x) * blockDim.x);
 }
 
 // ---------------------------------------------------------------- scan ------------------
@@ -287,7 +214,6 @@ __global__ __launch_bounds__(SCAN_THREADS) void scan_kernel(GbArgs a, int64_t pe
 constexpr int FOLD_THREADS = 512;
 constexpr int FOLD_PARTS = 64;                       // threads sharing one accumulator
 constexpr int FOLD_ACCS = FOLD_THREADS / FOLD_PARTS; // accumulators per workgroup
-static_assert((FOLD_PARTS - 1) % 9 == 0, "fold_agg_kernel combines the partial rows nine at a time");
 
 // sums / counts [i] = sum over workgroups b of partial[b][i].  Eight consecutive accumulators per
 // workgroup, each summed by 64 threads striding over the partial rows, then combined in LDS.
@@ -312,6 +238,48 @@ __global__ __launch_bounds__(FOLD_THREADS) void fold_kernel(GbArgs a, int rows_w
   }
 }
 
+// The same fold for results of up to a thousand accumulators (175 groups x (SUM, COUNT) is typical): one
+// wavefront per accumulator, lane l adds partial rows l, l + 64, .. with all its loads in flight, then the
+// lanes are added through the cross-lane network.  Fewer dependent steps than the two-level form above,
+// which in turn touches eight times fewer cache lines per load and stays the form for large results.
+constexpr int FOLD_WAVE_THREADS = 256;
+constexpr int FOLD_WAVE_MAX_ACC = 1024;
+__global__ __launch_bounds__(FOLD_WAVE_THREADS) void fold_wave_kernel(GbArgs a, int rows_written) {
+  const int n_acc = (a.M + 1) * a.G;
+  const int lane = threadIdx.x & 63;
+  const int i = blockIdx.x * (FOLD_WAVE_THREADS / 64) + (threadIdx.x >> 6);
+  if (i >= n_acc) return;
+  unsigned long long t = 0ull;
+  for (int b0 = lane; b0 < rows_written; b0 += 8 * 64) {
+    unsigned long long v[8];
+#pragma unroll
+    for (int u = 0; u < 8; ++u) {
+      const int b = b0 + u * 64;
+      v[u] = b < rows_written ? a.partial[static_cast<size_t>(b) * n_acc + i] : 0ull;
+    }
+#pragma unroll
+    for (int u = 0; u < 8; ++u) t += v[u];
+  }
+  const unsigned long long tot = static_cast<unsigned long long>(wave_sum64(static_cast<long long>(t)));
+  if (lane == 0) {
+    if (i < a.M * a.G) a.sums[i] = tot;
+    else if (a.counts) a.counts[i - a.M * a.G] = tot;
+  }
+}
+
+// Launches whichever fold suits the number of accumulators.
+static int launch_fold(const GbArgs& a, int rows_written, hipStream_t s) {
+  const int n_acc = (a.M + 1) * a.G;
+  if (n_acc <= FOLD_WAVE_MAX_ACC) {
+    const unsigned blocks = static_cast<unsigned>((n_acc + FOLD_WAVE_THREADS / 64 - 1) / (FOLD_WAVE_THREADS / 64));
+    hipLaunchKernelGGL(fold_wave_kernel, dim3(blocks), dim3(FOLD_WAVE_THREADS), 0, s, a, rows_written);
+  } else {
+    const unsigned blocks = static_cast<unsigned>((n_acc + FOLD_ACCS - 1) / FOLD_ACCS);
+    hipLaunchKernelGGL(fold_kernel, dim3(blocks), dim3(FOLD_THREADS), 0, s, a, rows_written);
+  }
+  LQ_LAUNCH_CHECK("fold_kernel");
+  return LQ_OK;
+}
 
 // ---------------------------------------------------------------- wider aggregate ----------
 
@@ -334,7 +302,10 @@ __device__ __forceinline__ long long agg_init(int i, int M, int G) {
 }
 
 template <bool LDS_TABLES, int VEC, int KMAX>
-__global__ __launch_bounds__(SCAN_THREADS) void agg_scan_kernel(GbArgs a, AggExtra x, int64_t per_block, int vec_ok) {
+// pack_here: the dimension tables are so small that every workgroup encodes its own copy of the side tables
+// straight into LDS from the raw mask / code arrays (no separate launch); workgroup 0 also leaves them in the
+// workspace, where a later call that reuses the side tables expects them.
+__global__ __launch_bounds__(SCAN_THREADS) void agg_scan_kernel(GbArgs a, AggExtra x, int64_t per_block, int vec_ok, int pack_here) {
   extern __shared__ __align__(16) uint8_t smem[];
   long long* acc = reinterpret_cast<long long*>(smem);
   const int MG = a.M * a.G;
@@ -343,9 +314,19 @@ __global__ __launch_bounds__(SCAN_THREADS) void agg_scan_kernel(GbArgs a, AggExt
   const int tid = threadIdx.x;
   for (int i = tid; i < n_acc; i += SCAN_THREADS) acc[i] = agg_init(i, a.M, a.G);
   if (LDS_TABLES) {
-    const uint4* src = reinterpret_cast<const uint4*>(a.packed);
-    uint4* dst = reinterpret_cast<uint4*>(tab_lds);
-    for (uint32_t i = tid; i < a.packed_bytes / 16; i += SCAN_THREADS) dst[i] = src[i];
+    if (pack_here) {
+      pack_tables(a, tab_lds, tid, SCAN_THREADS);
+      if (blockIdx.x == 0) {
+        __syncthreads();
+        uint4* dst = reinterpret_cast<uint4*>(a.packed);
+        const uint4* src = reinterpret_cast<const uint4*>(tab_lds);
+        for (uint32_t i = tid; i < a.packed_bytes / 16; i += SCAN_THREADS) dst[i] = src[i];
+      }
+    } else {
+      const uint4* src = reinterpret_cast<const uint4*>(a.packed);
+      uint4* dst = reinterpret_cast<uint4*>(tab_lds);
+      for (uint32_t i = tid; i < a.packed_bytes / 16; i += SCAN_THREADS) dst[i] = src[i];
+    }
   }
   __syncthreads();
   const uint8_t* tab = LDS_TABLES ? tab_lds : a.packed;
@@ -423,38 +404,31 @@ __global__ __launch_bounds__(SCAN_THREADS) void agg_scan_kernel(GbArgs a, AggExt
   for (int i = tid; i < n_acc; i += SCAN_THREADS) mine[i] = acc[i];
 }
 
-// Fold of the wider aggregate: add, min or max depending on the segment the accumulator is in.
-__global__ __launch_bounds__(FOLD_THREADS) void fold_agg_kernel(GbArgs a, AggExtra x, int rows_written) {
-  __shared__ long long part[FOLD_PARTS][FOLD_ACCS];
+// Fold of the wider aggregate: add, min or max depending on the segment the accumulator is in.  One
+// wavefront per accumulator: lane l combines partial rows l, l + 64, .. (all its loads requested before the
+// first is used), then the 64 lanes are combined through the cross-lane network.
+constexpr int FOLD_AGG_THREADS = 256;
+__global__ __launch_bounds__(FOLD_AGG_THREADS) void fold_agg_kernel(GbArgs a, AggExtra x, int rows_written) {
   const int n_acc = (3 * a.M + 1) * a.G;
-  const int il = threadIdx.x % FOLD_ACCS, p = threadIdx.x / FOLD_ACCS;
-  const int i = blockIdx.x * FOLD_ACCS + il;
+  const int lane = threadIdx.x & 63;
+  const int i = blockIdx.x * (FOLD_AGG_THREADS / 64) + (threadIdx.x >> 6);
+  if (i >= n_acc) return;
   const int seg = i < (a.M + 1) * a.G ? 0 : (i < (2 * a.M + 1) * a.G ? 1 : 2);
-  long long t = i < n_acc ? agg_init(i, a.M, a.G) : 0;
+  const long long neutral = agg_init(i, a.M, a.G);
+  long long t = neutral;
   const long long* partial = reinterpret_cast<const long long*>(a.partial);
-  if (i < n_acc)
-    for (int b0 = p; b0 < rows_written; b0 += 8 * FOLD_PARTS) {   // eight loads in flight per thread
-      long long v[8];
+  for (int b0 = lane; b0 < rows_written; b0 += 8 * 64) {
+    long long v[8];
 #pragma unroll
-      for (int u = 0; u < 8; ++u) {
-        const int b = b0 + u * FOLD_PARTS;
-        v[u] = b < rows_written ? partial[static_cast<size_t>(b) * n_acc + i] : agg_init(i, a.M, a.G);
-      }
-#pragma unroll
-      for (int u = 0; u < 8; ++u) t = seg == 0 ? t + v[u] : (seg == 1 ? min(t, v[u]) : max(t, v[u]));
+    for (int u = 0; u < 8; ++u) {
+      const int b = b0 + u * 64;
+      v[u] = b < rows_written ? partial[static_cast<size_t>(b) * n_acc + i] : neutral;
     }
-  part[p][il] = t;
-  __syncthreads();
-  if (threadIdx.x < FOLD_ACCS && i < n_acc) {
-    long long tot = part[0][il];
 #pragma unroll
-    for (int q0 = 1; q0 < FOLD_PARTS; q0 += 9) {               // 63 = 7 x 9 LDS reads, nine in flight
-      long long v[9];
-#pragma unroll
-      for (int u = 0; u < 9; ++u) v[u] = part[q0 + u][il];
-#pragma unroll
-      for (int u = 0; u < 9; ++u) tot = seg == 0 ? tot + v[u] : (seg == 1 ? min(tot, v[u]) : max(tot, v[u]));
-    }
+    for (int u = 0; u < 8; ++u) t = seg == 0 ? t + v[u] : (seg == 1 ? min(t, v[u]) : max(t, v[u]));
+  }
+  const long long tot = seg == 0 ? wave_sum64(t) : (seg == 1 ? wave_min64(t) : wave_max64(t));
+  if (lane == 0) {
     const int MG = a.M * a.G;
     if (i < MG) { if (a.sums) a.sums[i] = static_cast<unsigned long long>(tot); }
     else if (i < MG + a.G) { if (a.counts) a.counts[i - MG] = static_cast<unsigned long long>(tot); }
@@ -734,12 +708,9 @@ int launch_groupby(int64_t n, int32_t K, const int32_t* const* fks, const int64_
   const GlobalOut gout{a.sums, a.counts, nullptr, nullptr};
   if (gacc && (rc0 = launch_init_outputs(gout, M, G, s))) return rc0;
   if (!reuse_tables && (n > 0 || !gacc) && (rc0 = launch_pack(a, s))) return rc0;
-  const unsigned fold_blocks = static_cast<unsigned>((n_acc + FOLD_ACCS - 1) / FOLD_ACCS);
   if (n == 0) {   // nothing to scan: the fold alone writes the all-zero result
     if (gacc) return LQ_OK;
-    hipLaunchKernelGGL(fold_kernel, dim3(fold_blocks), dim3(FOLD_THREADS), 0, s, a, 0);
-    LQ_LAUNCH_CHECK("fold_kernel");
-    return LQ_OK;
+    return launch_fold(a, 0, s);
   }
 
   const int vec = vec_ok ? 4 : 1;
@@ -787,9 +758,7 @@ int launch_groupby(int64_t n, int32_t K, const int32_t* const* fks, const int64_
       if (rc > 0) return rc;
       if (rc == 0) {
         if (gacc) return LQ_OK;
-        hipLaunchKernelGGL(fold_kernel, dim3(fold_blocks), dim3(FOLD_THREADS), 0, s, a, static_cast<int>(L.blocks));
-        LQ_LAUNCH_CHECK("fold_kernel");
-        return LQ_OK;
+        return launch_fold(a, static_cast<int>(L.blocks), s);
       }
     }
   }
@@ -825,9 +794,7 @@ int launch_groupby(int64_t n, int32_t K, const int32_t* const* fks, const int64_
 #undef LQ_SCAN_K
 #undef LQ_SCAN
   LQ_LAUNCH_CHECK("scan_kernel");
-  hipLaunchKernelGGL(fold_kernel, dim3(fold_blocks), dim3(FOLD_THREADS), 0, s, a, static_cast<int>(blocks));
-  LQ_LAUNCH_CHECK("fold_kernel");
-  return LQ_OK;
+  return launch_fold(a, static_cast<int>(blocks), s);
 }
 
 
@@ -887,17 +854,17 @@ int launch_groupby_agg(int64_t n, int32_t K, const int32_t* const* fks, const in
   if (packed > 0xffffffffull) return fail(LQ_ERR_UNSUPPORTED, "group-by: dimension side tables exceed 4 GiB");
   a.packed_bytes = static_cast<uint32_t>(packed);
   const int cus = num_cus();
-  if (!reuse_tables) {
-    size_t work = 1;
-    for (int k = 0; k < K; ++k) {
-      const size_t w = a.d[k].kind == DK_BITMAP ? static_cast<size_t>(a.d[k].bytes) * 8 : static_cast<size_t>(a.d[k].bytes) / 4;
-      work = std::max(work, w);
-    }
-    const int64_t blocks = std::min<int64_t>(static_cast<int64_t>((work + 255) / 256), cus * 8);
-    hipLaunchKernelGGL(pack_kernel, dim3(static_cast<unsigned>(std::max<int64_t>(blocks, 1))), dim3(256), 0, s, a);
-    LQ_LAUNCH_CHECK("pack_kernel");
+  // Small dimension tables (up to 16 KB of masks and codes in all, LDS-resident once encoded): every scan
+  // workgroup encodes them itself, which saves the separate launch.
+  size_t raw_bytes = 0;
+  for (int k = 0; k < K; ++k)
+    raw_bytes += static_cast<size_t>(rows[k]) * ((a.d[k].mask ? 1 : 0) + (a.d[k].code ? 4 : 0));
+  const bool pack_here = !reuse_tables && n > 0 && lds_prefix == packed && raw_bytes <= 16 * 1024;
+  if (!reuse_tables && !pack_here) {
+    const int rc0 = launch_pack(a, s);
+    if (rc0) return rc0;
   }
-  const unsigned fold_blocks = static_cast<unsigned>((n_acc + FOLD_ACCS - 1) / FOLD_ACCS);
+  const unsigned fold_blocks = static_cast<unsigned>((n_acc + FOLD_AGG_THREADS / 64 - 1) / (FOLD_AGG_THREADS / 64));
   unsigned blocks = 0;
   if (n > 0) {
     constexpr int VEC = 4;
@@ -911,20 +878,51 @@ int launch_groupby_agg(int64_t n, int32_t K, const int32_t* const* fks, const in
     pb = std::max<int64_t>(SCAN_THREADS, (pb + SCAN_THREADS - 1) / SCAN_THREADS * SCAN_THREADS);
     b = std::max<int64_t>(1, (n_vec + pb - 1) / pb);
     blocks = static_cast<unsigned>(b);
+    // Common shapes: one measure, up to two predicates, every side table a byte table or a bitmap in LDS.
+    if (M == 1 && n_preds <= 2 && vec_ok && lds_tables && K >= 1) {
+      AggFastArgs fx{};
+      FastLaunch L{};
+      bool ok = true;
+      int slot = 0;
+      for (int run = 0; run < 2 && ok; ++run)          // byte tables first, then bitmaps
+        for (int k = 0; k < K; ++k) {
+          const int kind = a.d[k].kind;
+          if (kind != DK_BYTE && kind != DK_BITMAP) { ok = false; break; }
+          if (kind != (run == 0 ? DK_BYTE : DK_BITMAP)) continue;
+          fx.f.fk[slot] = a.d[k].fk; fx.f.off[slot] = a.d[k].off; fx.f.stride[slot] = a.d[k].stride;
+          ++slot;
+          if (run == 0) ++L.nbl; else ++L.nml;
+        }
+      if (ok) {
+        fx.f.n = n; fx.f.packed = a.packed; fx.f.lds_bytes = static_cast<uint32_t>(packed); fx.f.G = G; fx.f.partial = a.partial;
+        fx.f.meas[0] = a.meas[0];
+        fx.b = x.b[0]; fx.op = x.op[0];
+        for (int q = 0; q < n_preds; ++q) { fx.pcol[q] = x.pcol[q]; fx.lo[q] = x.lo[q]; fx.hi[q] = x.hi[q]; }
+        fx.minmax = (mins || maxs) ? 1 : 0;
+        L.lds = lds; L.s = s; L.M = 1; L.blocks = blocks; L.per_block = pb;
+        const int rc = launch_agg_fast(a, fx, L, n_preds, pack_here ? 1 : 0);
+        if (rc > 0) return rc;
+        if (rc == 0) {
+          hipLaunchKernelGGL(fold_agg_kernel, dim3(fold_blocks), dim3(FOLD_AGG_THREADS), 0, s, a, x, static_cast<int>(blocks));
+          LQ_LAUNCH_CHECK("fold_agg_kernel");
+          return LQ_OK;
+        }
+      }
+    }
 #define LQ_AGG(LT, KM)                                                                           \
   do {                                                                                           \
     if (lds > 64 * 1024)                                                                         \
       LQ_HIP_TRY(hipFuncSetAttribute(reinterpret_cast<const void*>(&agg_scan_kernel<LT, 4, KM>), \
                                      hipFuncAttributeMaxDynamicSharedMemorySize, static_cast<int>(lds))); \
     hipLaunchKernelGGL((agg_scan_kernel<LT, 4, KM>), dim3(blocks), dim3(SCAN_THREADS), lds, s, a, x, pb, \
-                       vec_ok ? 1 : 0);                                                          \
+                       vec_ok ? 1 : 0, pack_here ? 1 : 0);                                       \
   } while (0)
     if (lds_tables) { if (K <= 2) LQ_AGG(true, 2); else if (K <= 4) LQ_AGG(true, 4); else LQ_AGG(true, 8); }
     else            { if (K <= 2) LQ_AGG(false, 2); else if (K <= 4) LQ_AGG(false, 4); else LQ_AGG(false, 8); }
 #undef LQ_AGG
     LQ_LAUNCH_CHECK("agg_scan_kernel");
   }
-  hipLaunchKernelGGL(fold_agg_kernel, dim3(fold_blocks), dim3(FOLD_THREADS), 0, s, a, x, static_cast<int>(blocks));
+  hipLaunchKernelGGL(fold_agg_kernel, dim3(fold_blocks), dim3(FOLD_AGG_THREADS), 0, s, a, x, static_cast<int>(blocks));
   LQ_LAUNCH_CHECK("fold_agg_kernel");
   return LQ_OK;
 }

@@ -9,6 +9,38 @@ namespace lq {
 
 constexpr int SCAN_THREADS = 1024;
 
+// The dimension side of a group-by call.
+enum DimKind : int32_t { DK_NONE = 0, DK_BITMAP = 1, DK_BYTE = 2, DK_U16 = 3 };
+
+struct GbDim {
+  const int32_t* fk;
+  const uint8_t* mask;   // raw, may be NULL
+  const int32_t* code;   // raw, may be NULL
+  int64_t rows;
+  int32_t kind;
+  int32_t card;          // 1 when not grouping
+  int32_t stride;        // weight of this dimension's code in the group number (0 when not grouping)
+  uint32_t off;          // byte offset of the packed table (16-byte aligned)
+  uint32_t bytes;        // packed size, multiple of 16
+  int32_t in_lds;        // 1 when the table is part of the LDS-resident prefix
+};
+
+struct GbArgs {
+  int64_t n;
+  int32_t K;
+  GbDim d[LQ_MAX_DIMS];
+  const uint8_t* fact_mask;
+  int32_t M;
+  const int32_t* meas[LQ_MAX_MEASURES];
+  unsigned long long* sums;    // [M x G]
+  unsigned long long* counts;  // [G] or NULL
+  int32_t G;
+  uint8_t* packed;             // workspace: all packed tables
+  uint32_t packed_bytes;
+  unsigned long long* partial; // workspace: [workgroups x (M+1) x G]
+};
+
+
 // The same scan with everything the generic kernel decides at run time fixed at compile time:
 // no fact mask, 16-byte aligned columns, only byte tables (grouping dimensions, optionally
 // masked) and bitmaps (mask-only dimensions).  The host orders the dimensions into four runs:
@@ -30,11 +62,71 @@ struct FastArgs {
   unsigned long long* gcounts;       // arrays (gcounts may be NULL) instead of LDS + partial rows
 };
 
+// The wider aggregate on the specialised scan: one measure (a column, or the product / difference of two),
+// up to two fact-side range predicates, every side table in LDS.
+struct AggFastArgs {
+  FastArgs f;                 // f.meas[0] is the measure's first column; f.partial rows hold [sum | count | min | max] x G
+  const int32_t* b;           // second column of the measure (op != 0)
+  int32_t op;                 // 0 column, 1 product, 2 difference
+  const int32_t* pcol[2];
+  int32_t lo[2], hi[2];
+  int32_t minmax;             // MIN / MAX wanted (otherwise their accumulators keep the neutral elements)
+};
+
 struct FastLaunch { unsigned blocks; size_t lds; int64_t per_block; hipStream_t s; int nbl, nml, nmg, nbg, M; };
 
 namespace {
 
 typedef int v4i __attribute__((ext_vector_type(4)));
+
+// Encodes every dimension's side table into `dst` (memory, or a workgroup's LDS): thread gtid of gstride
+// (gstride a multiple of 64, whole wavefronts take part).
+// BITMAP: a wavefront turns 64 mask bytes into one 64-bit ballot word per step.
+// BYTE / U16: one thread builds 4 (2) consecutive entries and stores them as one word.
+__device__ __forceinline__ void pack_tables(const GbArgs& a, uint8_t* dst, int64_t gtid, int64_t gstride) {
+  const int lane = threadIdx.x & 63;
+  const int64_t gwave = gtid >> 6, nwave = gstride >> 6;
+  for (int k = 0; k < a.K; ++k) {
+    const GbDim& d = a.d[k];
+    if (d.kind == DK_BITMAP) {
+      unsigned long long* out = reinterpret_cast<unsigned long long*>(dst + d.off);
+      const int64_t steps = d.bytes / 8;               // 64 rows per step
+      for (int64_t q = gwave; q < steps; q += nwave) {
+        const int64_t j = q * 64 + lane;
+        const bool on = j < d.rows && d.mask[j] != 0;
+        const unsigned long long bits = __ballot(on);
+        if (lane == 0) out[q] = bits;
+      }
+    } else if (d.kind == DK_BYTE) {
+      uint32_t* out = reinterpret_cast<uint32_t*>(dst + d.off);
+      for (int64_t q = gtid; q < d.bytes / 4; q += gstride) {
+        uint32_t w = 0;
+#pragma unroll
+        for (int b = 0; b < 4; ++b) {
+          const int64_t j = q * 4 + b;
+          uint32_t v = 0xffu;
+          if (j < d.rows && (!d.mask || d.mask[j])) v = d.code ? static_cast<uint32_t>(d.code[j]) & 0xffu : 0u;
+          w |= v << (8 * b);
+        }
+        out[q] = w;
+      }
+    } else if (d.kind == DK_U16) {
+      uint32_t* out = reinterpret_cast<uint32_t*>(dst + d.off);
+      for (int64_t q = gtid; q < d.bytes / 4; q += gstride) {
+        uint32_t w = 0;
+#pragma unroll
+        for (int b = 0; b < 2; ++b) {
+          const int64_t j = q * 2 + b;
+          uint32_t v = 0xffffu;
+          if (j < d.rows && (!d.mask || d.mask[j])) v = static_cast<uint32_t>(d.code[j]) & 0xffffu;
+          w |= v << (16 * b);
+        }
+        out[q] = w;
+      }
+    }
+  }
+}
+
 
 // Neutral elements of MIN and MAX (what groups without rows keep).
 constexpr long long AGG_MIN_INIT = 0x7fffffffffffffffLL;
@@ -185,6 +277,22 @@ __global__ __launch_bounds__(SCAN_THREADS) void scan_fast_kernel(FastArgs a, int
   }
   __syncthreads();
 
+  // The measure columns of a step are requested when its survivors are known and added one step later, so
+  // that their latency passes under the next step's keys instead of ending every step.
+  uint32_t pending = 0;         // bit q: row q of the previous step survived
+  int32_t pg[4] = {0, 0, 0, 0};
+  v4i pval[MM];
+  auto flush = [&]() {
+#pragma unroll
+    for (int m = 0; m < MM; ++m)
+#pragma unroll
+      for (int q = 0; q < 4; ++q)
+        if (pending & (1u << q))
+          atomicAdd(&acc[m * a.G + pg[q]], static_cast<unsigned long long>(static_cast<long long>(pval[m][q])));
+#pragma unroll
+    for (int q = 0; q < 4; ++q)
+      if (pending & (1u << q)) atomicAdd(&acc[MM * a.G + pg[q]], 1ull);
+  };
   while (v < v_end) {
     const int64_t vn = v + SCAN_THREADS;
     if (vn < v_end) {
@@ -192,33 +300,30 @@ __global__ __launch_bounds__(SCAN_THREADS) void scan_fast_kernel(FastArgs a, int
       for (int k = 0; k < ND; ++k) nxt[k] = __builtin_nontemporal_load(reinterpret_cast<const v4i*>(a.fk[k]) + vn);
     }
     int32_t g[4];
-    bool alive[4];
+    uint32_t alive_bits = 0;
 #pragma unroll
     for (int q = 0; q < 4; ++q) {
       int32_t j[ND];
 #pragma unroll
       for (int k = 0; k < ND; ++k) j[k] = cur[k][q];
       g[q] = 0;
-      alive[q] = true;
-      classify_fast<NBL, NML, NMG, NBG>(a, tab, j, alive[q], g[q]);
+      bool alive = true;
+      classify_fast<NBL, NML, NMG, NBG>(a, tab, j, alive, g[q]);
+      alive_bits |= alive ? (1u << q) : 0u;
     }
-    if (alive[0] || alive[1] || alive[2] || alive[3]) {
+    if (pending) flush();
+    pending = alive_bits;
+    if (pending) {
 #pragma unroll
-      for (int m = 0; m < MM; ++m) {
-        const v4i val = *(reinterpret_cast<const v4i*>(a.meas[m]) + v);
+      for (int q = 0; q < 4; ++q) pg[q] = g[q];
 #pragma unroll
-        for (int q = 0; q < 4; ++q)
-          if (alive[q])
-            atomicAdd(&acc[m * a.G + g[q]], static_cast<unsigned long long>(static_cast<long long>(val[q])));
-      }
-#pragma unroll
-      for (int q = 0; q < 4; ++q)
-        if (alive[q]) atomicAdd(&acc[MM * a.G + g[q]], 1ull);
+      for (int m = 0; m < MM; ++m) pval[m] = *(reinterpret_cast<const v4i*>(a.meas[m]) + v);
     }
 #pragma unroll
     for (int k = 0; k < ND; ++k) cur[k] = nxt[k];
     v = vn;
   }
+  if (pending) flush();
   // ragged tail (n % 4 rows)
   if (blockIdx.x == 0) {
     const int64_t i = n_vec * 4 + tid;
