@@ -11,7 +11,13 @@ namespace lq {
 namespace {
 
 // Accumulators (LDS, partial rows): [sum G | count G | min G | max G].
-template <int NBL, int NML, int NP>
+// DEFER: the measure columns of a step are requested when its survivors are known and added one step later, so
+// that their latency passes under the next step's keys instead of ending every step.  It shortens a thread's
+// critical path by one memory latency per step, which is what a scan of a few steps per thread is made of
+// (6e6 rows: 3 steps, 22.9 -> 18.5 us); over many steps the other wavefronts cover that latency anyway and the
+// later, second divergent region costs throughput (the same change made the plain group-by 11 % slower at 9.6e7
+// rows), so long scans consume their measures at once.
+template <int NBL, int NML, int NP, bool DEFER>
 __global__ __launch_bounds__(SCAN_THREADS) void agg_fast_kernel(GbArgs a, AggFastArgs x, int64_t per_block, int pack_here) {
   extern __shared__ __align__(16) uint8_t smem[];
   constexpr int ND = NBL + NML, NC = ND + NP;
@@ -62,9 +68,7 @@ __global__ __launch_bounds__(SCAN_THREADS) void agg_fast_kernel(GbArgs a, AggFas
     }
   };
 
-  // The measure columns of a step are requested when its survivors are known and added one step later, so
-  // that their latency passes under the next step's keys instead of ending every step.
-  uint32_t pending = 0;         // bit q: row q of the previous step survived
+  uint32_t pending = 0;         // bit q: row q of the previous step survived (DEFER)
   int32_t pg[4] = {0, 0, 0, 0};
   v4i pav = {0, 0, 0, 0}, pbv = {0, 0, 0, 0};
   auto flush = [&]() {
@@ -92,7 +96,7 @@ __global__ __launch_bounds__(SCAN_THREADS) void agg_fast_kernel(GbArgs a, AggFas
       classify_fast<NBL, NML, 0, 0>(f, tab, j, alive, g[q]);
       alive_bits |= alive ? (1u << q) : 0u;
     }
-    if (pending) flush();
+    if (DEFER && pending) flush();
     pending = alive_bits;
     if (pending) {
 #pragma unroll
@@ -100,12 +104,13 @@ __global__ __launch_bounds__(SCAN_THREADS) void agg_fast_kernel(GbArgs a, AggFas
       pav = *(reinterpret_cast<const v4i*>(f.meas[0]) + v);
       pbv = pav;
       if (x.op != 0) pbv = *(reinterpret_cast<const v4i*>(x.b) + v);
+      if (!DEFER) flush();
     }
 #pragma unroll
     for (int c = 0; c < NC; ++c) cur[c] = nxt[c];
     v = vn;
   }
-  if (pending) flush();
+  if (DEFER && pending) flush();
   // ragged tail (n % 4 rows)
   if (blockIdx.x == 0) {
     const int64_t i = n_vec * 4 + tid;
@@ -128,10 +133,12 @@ __global__ __launch_bounds__(SCAN_THREADS) void agg_fast_kernel(GbArgs a, AggFas
 
 template <int NBL, int NML, int NP>
 int agg_fast_inst(const GbArgs& a, const AggFastArgs& x, const FastLaunch& L, int pack_here) {
+  const bool defer = L.per_block <= 8 * SCAN_THREADS;          // at most eight steps per thread
+  auto kernel = defer ? &agg_fast_kernel<NBL, NML, NP, true> : &agg_fast_kernel<NBL, NML, NP, false>;
   if (L.lds > 64 * 1024)
-    LQ_HIP_TRY(hipFuncSetAttribute(reinterpret_cast<const void*>(&agg_fast_kernel<NBL, NML, NP>),
+    LQ_HIP_TRY(hipFuncSetAttribute(reinterpret_cast<const void*>(kernel),
                                    hipFuncAttributeMaxDynamicSharedMemorySize, static_cast<int>(L.lds)));
-  hipLaunchKernelGGL((agg_fast_kernel<NBL, NML, NP>), dim3(L.blocks), dim3(SCAN_THREADS), L.lds, L.s, a, x, L.per_block, pack_here);
+  hipLaunchKernelGGL(kernel, dim3(L.blocks), dim3(SCAN_THREADS), L.lds, L.s, a, x, L.per_block, pack_here);
   LQ_LAUNCH_CHECK("agg_fast_kernel");
   return LQ_OK;
 }

@@ -277,22 +277,6 @@ __global__ __launch_bounds__(SCAN_THREADS) void scan_fast_kernel(FastArgs a, int
   }
   __syncthreads();
 
-  // The measure columns of a step are requested when its survivors are known and added one step later, so
-  // that their latency passes under the next step's keys instead of ending every step.
-  uint32_t pending = 0;         // bit q: row q of the previous step survived
-  int32_t pg[4] = {0, 0, 0, 0};
-  v4i pval[MM];
-  auto flush = [&]() {
-#pragma unroll
-    for (int m = 0; m < MM; ++m)
-#pragma unroll
-      for (int q = 0; q < 4; ++q)
-        if (pending & (1u << q))
-          atomicAdd(&acc[m * a.G + pg[q]], static_cast<unsigned long long>(static_cast<long long>(pval[m][q])));
-#pragma unroll
-    for (int q = 0; q < 4; ++q)
-      if (pending & (1u << q)) atomicAdd(&acc[MM * a.G + pg[q]], 1ull);
-  };
   while (v < v_end) {
     const int64_t vn = v + SCAN_THREADS;
     if (vn < v_end) {
@@ -300,30 +284,33 @@ __global__ __launch_bounds__(SCAN_THREADS) void scan_fast_kernel(FastArgs a, int
       for (int k = 0; k < ND; ++k) nxt[k] = __builtin_nontemporal_load(reinterpret_cast<const v4i*>(a.fk[k]) + vn);
     }
     int32_t g[4];
-    uint32_t alive_bits = 0;
+    bool alive[4];
 #pragma unroll
     for (int q = 0; q < 4; ++q) {
       int32_t j[ND];
 #pragma unroll
       for (int k = 0; k < ND; ++k) j[k] = cur[k][q];
       g[q] = 0;
-      bool alive = true;
-      classify_fast<NBL, NML, NMG, NBG>(a, tab, j, alive, g[q]);
-      alive_bits |= alive ? (1u << q) : 0u;
+      alive[q] = true;
+      classify_fast<NBL, NML, NMG, NBG>(a, tab, j, alive[q], g[q]);
     }
-    if (pending) flush();
-    pending = alive_bits;
-    if (pending) {
+    if (alive[0] || alive[1] || alive[2] || alive[3]) {
 #pragma unroll
-      for (int q = 0; q < 4; ++q) pg[q] = g[q];
+      for (int m = 0; m < MM; ++m) {
+        const v4i val = *(reinterpret_cast<const v4i*>(a.meas[m]) + v);
 #pragma unroll
-      for (int m = 0; m < MM; ++m) pval[m] = *(reinterpret_cast<const v4i*>(a.meas[m]) + v);
+        for (int q = 0; q < 4; ++q)
+          if (alive[q])
+            atomicAdd(&acc[m * a.G + g[q]], static_cast<unsigned long long>(static_cast<long long>(val[q])));
+      }
+#pragma unroll
+      for (int q = 0; q < 4; ++q)
+        if (alive[q]) atomicAdd(&acc[MM * a.G + g[q]], 1ull);
     }
 #pragma unroll
     for (int k = 0; k < ND; ++k) cur[k] = nxt[k];
     v = vn;
   }
-  if (pending) flush();
   // ragged tail (n % 4 rows)
   if (blockIdx.x == 0) {
     const int64_t i = n_vec * 4 + tid;

@@ -110,3 +110,10 @@ def test_avg_from_sums_and_counts(lq):
         torch.cuda.synchronize()
         np.testing.assert_array_equal(avg.cpu().numpy(), want_avg)             # NaN == NaN in this comparison
         assert np.isnan(want_avg).any() == (want[3] == 0).any()
+
+
+def test_long_scan_of_the_specialised_aggregate(lq):
+    """More than eight steps per thread (over 16.8M fact rows): the specialised scan then consumes its measure
+    columns at once instead of one step late; two joins, two predicates, a product, ragged row count."""
+    fks, rows, masks, codes, card, c = _case(80, 20_000_003, (2_556, 300), (7, 1))
+    _check(lq, fks, rows, masks, codes, card, [(c["disc"], 1, 3), (c["qty"], 1, 24)], [("mul", c["price"], c["disc"])])
