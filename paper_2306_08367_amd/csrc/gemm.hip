@@ -61,11 +61,21 @@ template <> struct Tile<bf16_t> {
   static constexpr int VEC = 8;
 };
 
+struct __attribute__((packed, aligned(4))) Words4 { unsigned int x, y, z, w; };
+
 // 16 bytes starting at p, of which only the first `valid` elements exist (others read as zero).
 template <typename T>
 __device__ __forceinline__ v4u load_chunk(const T* p, int valid, bool vec_ok) {
   constexpr int VEC = Tile<T>::VEC;
   if (valid >= VEC && vec_ok) return *reinterpret_cast<const v4u*>(p);
+  if constexpr (sizeof(T) == 4) {
+    // Rows whose stride is not a multiple of four floats (a table with 683 columns): still one 16-byte
+    // load, declared with the 4-byte alignment the pointer has.
+    if (valid >= VEC) {
+      const Words4 t = *reinterpret_cast<const Words4*>(p);
+      return v4u{t.x, t.y, t.z, t.w};
+    }
+  }
   v4u r = {0u, 0u, 0u, 0u};
   if (valid <= 0) return r;
   if constexpr (sizeof(T) == 4) {
