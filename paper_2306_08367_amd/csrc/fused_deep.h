@@ -43,23 +43,32 @@ constexpr int DEEP_WAVES = DEEP_THREADS / 64;
 
 
 // out^T += W^T h^T for TIN input tiles (tiles kt0 .. kt0 + TIN - 1 of a layer of TIN_ALL input
-// tiles); w points into LDS.  The 16x16 weight tiles are taken in the order (kt, ot) and requested
-// two tiles ahead of the products that use them, so that the matrix cores do not wait for LDS.
+// tiles); w points into LDS.  The 16x16 weight tiles are taken in the order (kt, ot), IL output tiles
+// at a time whose products alternate (consecutive matrix instructions then write different
+// accumulators), and are requested one group ahead of the products that use them, so that the matrix
+// cores wait neither for LDS nor for the previous product of the same accumulator.
 template <int TIN, int TOUT, int TIN_ALL>
 __device__ __forceinline__ void dense_accumulate(const v4f (&h)[TIN], const float* w, int kt0, int lane, v4f (&out)[TOUT]) {
-  constexpr int NB = TIN * TOUT, AHEAD = 2;
+  constexpr int IL = TOUT % 2 == 0 ? 2 : 1;
+  constexpr int NG = TIN * TOUT / IL;                                   // groups of IL tiles
   const v4f* wl = reinterpret_cast<const v4f*>(w) + kt0 * 64 + lane;   // tile (ot, kt) at wl[(ot TIN_ALL + kt) 64]
-  v4f wv[AHEAD + 1];
+  v4f wv[2][IL];
 #pragma unroll
-  for (int b = 0; b < AHEAD && b < NB; ++b) wv[b] = wl[((b % TOUT) * TIN_ALL + b / TOUT) * 64];
+  for (int i = 0; i < IL; ++i) wv[0][i] = wl[(i * TIN_ALL + 0) * 64];
 #pragma unroll
-  for (int b = 0; b < NB; ++b) {
-    const int kt = b / TOUT, ot = b % TOUT;
-    if (b + AHEAD < NB) wv[(b + AHEAD) % (AHEAD + 1)] = wl[(((b + AHEAD) % TOUT) * TIN_ALL + (b + AHEAD) / TOUT) * 64];
+  for (int gi = 0; gi < NG; ++gi) {
+    const int kt = gi / (TOUT / IL), ot0 = (gi % (TOUT / IL)) * IL;
+    if (gi + 1 < NG) {
+      const int kn = (gi + 1) / (TOUT / IL), on = ((gi + 1) % (TOUT / IL)) * IL;
+#pragma unroll
+      for (int i = 0; i < IL; ++i) wv[(gi + 1) & 1][i] = wl[((on + i) * TIN_ALL + kn) * 64];
+    }
     __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
     for (int v = 0; v < 4; ++v)
-      out[ot] = __builtin_amdgcn_mfma_f32_16x16x4f32(wv[b % (AHEAD + 1)][v], h[kt][v], out[ot], 0, 0, 0);
+#pragma unroll
+      for (int i = 0; i < IL; ++i)
+        out[ot0 + i] = __builtin_amdgcn_mfma_f32_16x16x4f32(wv[gi & 1][i][v], h[kt][v], out[ot0 + i], 0, 0, 0);
     __builtin_amdgcn_sched_barrier(0);
   }
 }
@@ -165,31 +174,50 @@ __global__ __launch_bounds__(DEEP_THREADS) void fused_deep_kernel(PredictArgs a,
   constexpr int LPR = 4 * T1, RPI = 64 / LPR, LD = 16 * T1 + 4;   // LD staggers rows over the LDS banks
   const int gsub = lane / LPR, gc = lane % LPR;
   float* tile = lds + L.total + wave * 16 * LD;
+  for (int i = lane; i < 16 * LD; i += 64) tile[i] = 0.f;
+  // A piece of the summed rows goes to the tile; a lane past the end of a row leaves the tile's zero in
+  // place (one column part) or writes a zero over what the previous part left there (two parts).
+  auto store_piece = [&](float* dst, v4f sum, bool live) {
+    if constexpr (PARTS > 1) {
+      *reinterpret_cast<v4f*>(dst) = live ? sum : v4f{0.f, 0.f, 0.f, 0.f};
+    } else {
+      if (live) *reinterpret_cast<v4f*>(dst) = sum;
+    }
+  };
   auto clamp_row = [&](int64_t st) { return min<int64_t>(min<int64_t>(st, n_steps - 1) * 16 + r16, a.n - 1); };
-  int key0[KMAX];          // keys of this step (only live when later parts still need them: PARTS > 1)
-  int key1[KMAX];          // keys of the step after this one (lane l: row l % 16)
+  // Keys are kept as the offset of their row in 16-byte pieces, key * (row stride / 4): one 32-bit
+  // product per key where it is loaded, instead of a 64-bit one per gathered piece.
+  uint32_t ld16[KMAX];
+#pragma unroll
+  for (int k = 0; k < KMAX; ++k) ld16[k] = static_cast<uint32_t>(a.ldp[k] >> 2);
+  uint32_t key0[KMAX];     // rows of this step (only live when later parts still need them: PARTS > 1)
+  uint32_t key1[KMAX];     // rows of the step after this one (lane l: row l % 16)
   float xv[4], x1[4];      // fact columns of this step and of the next
   v4f g[KMAX][T1];         // gathered pieces in flight: g[k][u] = row u RPI + gsub, piece gc of one part
-  auto gather = [&](const int (&key)[KMAX], int part) {
+  auto gather = [&](const uint32_t (&key)[KMAX], int part) {
     const int col = part * 16 * T1 + 4 * gc;
-    const bool active = col < l1;          // widths below 16 T1 PARTS: the lanes past the end of a row idle
+    // Widths below 16 T1 PARTS: the lanes past the end of a row re-read its first piece (no branch
+    // around the loads, which would serialise the broadcast-then-load pairs); what they fetch never
+    // reaches the tile, whose columns past the end of a row hold zeros.
+    const uint32_t piece = col < l1 ? col >> 2 : 0;
+    uint32_t at[KMAX][T1];
 #pragma unroll
-    for (int k = 0; k < KMAX; ++k) {
+    for (int k = 0; k < KMAX; ++k)
 #pragma unroll
-      for (int u = 0; u < T1; ++u) {
-        const int kr = __shfl(key[k], u * RPI + gsub);
-        g[k][u] = active ? *reinterpret_cast<const v4f*>(static_cast<const float*>(a.P[k]) + static_cast<int64_t>(kr) * a.ldp[k] + col)
-                         : v4f{0.f, 0.f, 0.f, 0.f};
-      }
-    }
+      for (int u = 0; u < T1; ++u) at[k][u] = static_cast<uint32_t>(__shfl(static_cast<int>(key[k]), u * RPI + gsub)) + piece;
+#pragma unroll
+    for (int k = 0; k < KMAX; ++k)
+#pragma unroll
+      for (int u = 0; u < T1; ++u)
+        g[k][u] = *reinterpret_cast<const v4f*>(static_cast<const char*>(a.P[k]) + (static_cast<uint64_t>(at[k][u]) << 4));
   };
   {
     const int64_t row = clamp_row(step), row1 = clamp_row(step + stride);
-    int key[KMAX];
+    uint32_t key[KMAX];
 #pragma unroll
-    for (int k = 0; k < KMAX; ++k) key[k] = a.fk[k][row];
+    for (int k = 0; k < KMAX; ++k) key[k] = static_cast<uint32_t>(a.fk[k][row]) * ld16[k];
 #pragma unroll
-    for (int k = 0; k < KMAX; ++k) key1[k] = a.fk[k][row1];
+    for (int k = 0; k < KMAX; ++k) key1[k] = static_cast<uint32_t>(a.fk[k][row1]) * ld16[k];
 #pragma unroll
     for (int kc = 0; kc < 4; ++kc) {
       const int q = 4 * kc + q4;
@@ -208,10 +236,10 @@ __global__ __launch_bounds__(DEEP_THREADS) void fused_deep_kernel(PredictArgs a,
     const bool more = step + stride < n_steps;
     // keys and fact columns two steps ahead (rows past the end are clamped: harmless reloads)
     const int64_t row2 = clamp_row(step + 2 * stride);
-    int key2[KMAX];
+    uint32_t key2[KMAX];
     float x2[4];
 #pragma unroll
-    for (int k = 0; k < KMAX; ++k) key2[k] = a.fk[k][row2];
+    for (int k = 0; k < KMAX; ++k) key2[k] = static_cast<uint32_t>(a.fk[k][row2]) * ld16[k];
 #pragma unroll
     for (int kc = 0; kc < 4; ++kc) {
       const int q = 4 * kc + q4;
@@ -233,7 +261,7 @@ __global__ __launch_bounds__(DEEP_THREADS) void fused_deep_kernel(PredictArgs a,
           for (int k = 1; k < KMAX; ++k)
 #pragma unroll
             for (int v = 0; v < 4; ++v) sum[v] += g[k][u][v];
-          *reinterpret_cast<v4f*>(tile + (u * RPI + gsub) * LD + 4 * gc) = sum;
+          store_piece(tile + (u * RPI + gsub) * LD + 4 * gc, sum, part * 16 * T1 + 4 * gc < l1);
         }
         if (part + 1 < PARTS) gather(key0, part + 1); else gather(key1, 0);
       } else {
@@ -250,13 +278,12 @@ __global__ __launch_bounds__(DEEP_THREADS) void fused_deep_kernel(PredictArgs a,
         const int col = part * 16 * T1 + 4 * gc;
         const int64_t myrow = clamp_row(step);
         for (int k = KMAX; k < a.K; ++k) {                   // tables 5..8: key, then gather, inside the step
-          const int kk = a.fk[k][myrow];
+          const uint32_t kk = static_cast<uint32_t>(a.fk[k][myrow]) * static_cast<uint32_t>(a.ldp[k] >> 2);
           v4f e[T1];
 #pragma unroll
           for (int u = 0; u < T1; ++u) {
-            const int kr = __shfl(kk, u * RPI + gsub);
-            e[u] = col < l1 ? *reinterpret_cast<const v4f*>(static_cast<const float*>(a.P[k]) + static_cast<int64_t>(kr) * a.ldp[k] + col)
-                            : v4f{0.f, 0.f, 0.f, 0.f};
+            const uint32_t at = static_cast<uint32_t>(__shfl(static_cast<int>(kk), u * RPI + gsub)) + (col < l1 ? col >> 2 : 0);
+            e[u] = *reinterpret_cast<const v4f*>(static_cast<const char*>(a.P[k]) + (static_cast<uint64_t>(at) << 4));
           }
 #pragma unroll
           for (int u = 0; u < T1; ++u)
@@ -264,7 +291,7 @@ __global__ __launch_bounds__(DEEP_THREADS) void fused_deep_kernel(PredictArgs a,
             for (int v = 0; v < 4; ++v) sum[u][v] += e[u][v];
         }
 #pragma unroll
-        for (int u = 0; u < T1; ++u) *reinterpret_cast<v4f*>(tile + (u * RPI + gsub) * LD + 4 * gc) = sum[u];
+        for (int u = 0; u < T1; ++u) store_piece(tile + (u * RPI + gsub) * LD + 4 * gc, sum[u], col < l1);
       }
 
       // z = x W_f + b_1 (matrix cores) + the gathered sum (back from the tile), ReLU
@@ -352,7 +379,8 @@ __global__ __launch_bounds__(DEEP_THREADS) void fused_deep_kernel(PredictArgs a,
 }
 
 
-// Launches the instantiation for NL_ (2, 3, or 4 = four or more layers).
+// Launches the instantiation for NL_ (2, 3, or 4 = four or more layers) on at most `blocks` workgroups: one
+// resident set of them (every wavefront runs its software pipeline once, none starts late).
 template <int NL_>
 int launch_deep_nl(const PredictArgs& a, const DeepLds& L, size_t lds, int64_t blocks, int vec_y, int T1, int PARTS, int TH,
                    hipStream_t s) {
@@ -361,8 +389,10 @@ int launch_deep_nl(const PredictArgs& a, const DeepLds& L, size_t lds, int64_t b
     if (lds > 64 * 1024)                                                                                    \
       LQ_HIP_TRY(hipFuncSetAttribute(reinterpret_cast<const void*>(&fused_deep_kernel<T1_, PARTS_, TH_, NL_, K_, X_>), \
                                      hipFuncAttributeMaxDynamicSharedMemorySize, static_cast<int>(lds)));   \
-    hipLaunchKernelGGL((fused_deep_kernel<T1_, PARTS_, TH_, NL_, K_, X_>), dim3(static_cast<unsigned>(blocks)), \
-                       dim3(DEEP_THREADS), lds, s, a, L, vec_y);                                            \
+    const int64_t resident = static_cast<int64_t>(num_cus()) *                                              \
+        resident_per_cu(reinterpret_cast<const void*>(&fused_deep_kernel<T1_, PARTS_, TH_, NL_, K_, X_>), DEEP_THREADS, lds); \
+    hipLaunchKernelGGL((fused_deep_kernel<T1_, PARTS_, TH_, NL_, K_, X_>),                                  \
+                       dim3(static_cast<unsigned>(std::min(blocks, resident))), dim3(DEEP_THREADS), lds, s, a, L, vec_y); \
   } while (0)
 #define LQ_DEEP_K(T1_, PARTS_, TH_)                                                                         \
   do {                                                                                                      \

@@ -18,8 +18,10 @@ int try_fused_deep(const PredictArgs& a, hipStream_t s) {
   const int l1 = a.wout[0];
   if (l1 % 4 || l1 < 20 || l1 > 256) return -1;
   if (a.c_f > 64 || a.K < 1 || a.K > LQ_MAX_DIMS) return -1;
-  for (int k = 0; k < a.K; ++k)
+  for (int k = 0; k < a.K; ++k) {
     if (!aligned(a.P[k], 16) || a.ldp[k] % 4) return -1;
+    if (a.prows[k] * (a.ldp[k] / 4) > 0xffffffffLL) return -1;     // the kernel counts 16-byte pieces of a table in 32 bits
+  }
   // 16-unit tiles of the hidden layer, padded to a power of two; above 128 in two column parts
   const int PARTS = l1 > 128 ? 2 : 1;
   const int T1 = l1 <= 32 ? 2 : (l1 <= 64 ? 4 : 8);
@@ -51,8 +53,7 @@ int try_fused_deep(const PredictArgs& a, hipStream_t s) {
   const int vec_y = (l_out % 4 == 0 && a.ldy % 4 == 0 && aligned(a.Y, 16)) ? 1 : 0;
 
   const int64_t n_steps = (a.n + 15) / 16;
-  const int per_cu = static_cast<int>(std::max<size_t>(1, std::min<size_t>(4, (160 * 1024) / std::max<size_t>(lds, 1))));
-  const int64_t blocks = std::min<int64_t>((n_steps + DEEP_WAVES - 1) / DEEP_WAVES, static_cast<int64_t>(num_cus()) * per_cu);
+  const int64_t blocks = (n_steps + DEEP_WAVES - 1) / DEEP_WAVES;    // the launcher caps them at one resident set
   if (blocks <= 0) return LQ_OK;
   if (NL == 2) return launch_deep_nl<2>(a, L, lds, blocks, vec_y, T1, PARTS, TH, s);
   if (NL == 3) return launch_deep_3(a, L, lds, blocks, vec_y, T1, PARTS, TH, s);

@@ -3,6 +3,7 @@
 #include <string.h>
 
 #include <mutex>
+#include <vector>
 
 #include "lq_common.h"
 
@@ -29,6 +30,24 @@ int num_cus() {
     cached[dev] = v;
   }
   return cached[dev];
+}
+
+int resident_per_cu(const void* kernel, int threads, size_t lds) {
+  struct Entry { int dev; const void* kernel; int threads; size_t lds; int value; };
+  static std::mutex mu;
+  static std::vector<Entry> cache;
+  int dev = 0;
+  if (hipGetDevice(&dev) != hipSuccess) dev = 0;
+  std::lock_guard<std::mutex> lock(mu);
+  for (const Entry& e : cache)
+    if (e.dev == dev && e.kernel == kernel && e.threads == threads && e.lds == lds) return e.value;
+  int v = 0;
+  if (hipOccupancyMaxActiveBlocksPerMultiprocessor(&v, kernel, threads, lds) != hipSuccess || v < 1) {
+    (void)hipGetLastError();
+    v = 1;
+  }
+  cache.push_back({dev, kernel, threads, lds, v});
+  return v;
 }
 
 int launch_gemm(const void* A, int64_t lda, const void* B, int64_t ldb, void* C, int64_t ldc,

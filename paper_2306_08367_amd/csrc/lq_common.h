@@ -42,6 +42,12 @@ __host__ __device__ inline size_t round_up(size_t v, size_t a) { return (v + a -
 // Number of compute units of the current device (cached per process).
 int num_cus();
 
+// Workgroups of `kernel` (of `threads` threads and `lds` bytes of dynamic LDS) that one compute unit of the
+// current device holds at a time, by registers, LDS and wave slots; at least 1.  Cached per kernel and
+// LDS size.  Grid-stride kernels size their grid as a whole multiple of this: the workgroups beyond
+// one resident set only start when earlier ones end, at whatever occupancy is then left.
+int resident_per_cu(const void* kernel, int threads, size_t lds);
+
 // Everything a predict kernel needs, passed by value as the kernel argument.
 struct PredictArgs {
   int64_t n;
