@@ -203,13 +203,27 @@ def main():
             t = time_call(lambda: lq.lq_yardstick_gather(tab, row_bytes, ng, sink), 10, 2)
             yard[name + "_GBps"] = ng * row_bytes / (t[2] * 1e-3) / 1e9
             yard[name + "_Grows_per_s"] = ng / (t[2] * 1e-3) / 1e9
+        # fp32 matrix instructions alone and with vector instructions between them (three wavefronts per SIMD)
+        msink = torch.empty(256 * 8 * 256, dtype=torch.float32, device=dev)
+        it_m = 2000
+        mflop = 256 * 4 * 3 * it_m * 16 * 2048.0                      # SIMDs x wavefronts x iterations x 16 x (16*16*4*2)
+        tm = {nv: time_call(lambda: lq.lq_yardstick_matrix(nv, 3, it_m, msink), 10, 2)[2] for nv in (0, 64, 128)}
+        yard["fp32_matrix_TFLOPs"] = mflop / (tm[0] * 1e-3) / 1e12
+        yard["fp32_matrix_TFLOPs_with_4_vector_ops_per_matrix_op"] = mflop / (tm[64] * 1e-3) / 1e12
+        yard["fp32_matrix_TFLOPs_with_8_vector_ops_per_matrix_op"] = mflop / (tm[128] * 1e-3) / 1e12
+        # time the vector instructions add, as a fraction of what they take alone (4 cycles each at 2.4 GHz)
+        alone = 3 * it_m * 128 * 4 / 2.4e9 * 1e3
+        yard["vector_time_not_hidden_by_matrix_ops_frac"] = (tm[128] - tm[0]) / alone
+        del msink
         yard["note"] = ("medians of 10 launches; copy and HBM read over 2 GiB, Infinity Cache read = 64 MiB read 32 times in one "
                         "launch, L2 read = 2 MiB read 1,024 times; gathers: 3e7 uniform random rows per launch, a row fetched by "
-                        "adjacent lanes as one run, eight rows in flight per lane, nothing written")
+                        "adjacent lanes as one run, eight rows in flight per lane, nothing written; fp32 matrix: 16x16x4 "
+                        "instructions, three wavefronts per SIMD, 16 per iteration followed by 0 / 64 / 128 independent vector "
+                        "multiply-adds")
         out["yardsticks"] = yard
         out["stream_copy"] = {"GBps_read_plus_write": yard["stream_copy_GBps_read_plus_write"], "bytes_copied": nb}
 
-    if args.only in ("", "yardsticks", "fused", "c4", "c5"):
+    if args.only in ("", "yardsticks", "fused", "c4", "c5", "deep"):
         guarded("yardsticks", leg_yardsticks)
 
     # ---------------------------------------------------------------- headline: fused MLP (C2)
@@ -503,6 +517,12 @@ def main():
             later_flop = 2.0 * sum(a * b for a, b in zip(layers[:-1], layers[1:])) * nd
             cells[name] = {"fused_ms": round(t[2], 4), "fused_ms_min": round(t[1], 4), "rows_per_s": nd / (t[2] * 1e-3),
                            "later_layers_TFLOPs": later_flop / (t[2] * 1e-3) / 1e12,
+                           # fp32 cells: time of the matrix instructions alone (widths padded to 16, fact columns to 4) at
+                           # the measured matrix rate, over the kernel's time; the vector work in between is not hidden
+                           "matrix_pipe_busy_frac": (None if dt != torch.float32 or not yard.get("fp32_matrix_TFLOPs") else
+                                                     2.0 * nd * (sum(-(-a // 16) * 16 * -(-b // 16) * 16 for a, b in zip(layers[:-1], layers[1:])
+                                                                     if b > 1) + -(-c_f // 4) * 4 * -(-layers[0] // 16) * 16)
+                                                     / (t[2] * 1e-3) / (yard["fp32_matrix_TFLOPs"] * 1e12)),
                            "gather_GBps": len(rows) * layers[0] * wd.dims[0].element_size() * nd / (t[2] * 1e-3) / 1e9,
                            "materialized_ms": round(mt[2], 3), "fused_speedup": mt[2] / t[2]}
             del wd, Pd, Yd, wsd

@@ -557,6 +557,18 @@ int lq_yardstick_stream(const void* buf, size_t bytes, int32_t repeats, void* wb
 int lq_yardstick_gather(const void* table, int64_t rows, int32_t row_bytes, int64_t n_gathers,
                         const int32_t* keys, uint32_t seed, void* sink, void* hip_stream);
 
+/*
+ * Arithmetic yardstick (not part of the method): on every SIMD of the device, waves_per_simd (1..8)
+ * wavefronts each run `iters` iterations of 16 fp32 16x16x4 matrix instructions followed by vector_ops
+ * (0, 32, 64 or 128) independent fp32 vector multiply-adds.  Timed with vector_ops = 0 it gives the matrix
+ * rate; the extra time with vector_ops > 0, against 4 cycles per vector instruction, says how much of the
+ * vector work the matrix instructions hide: the roof of the kernels that run later layers on the matrix
+ * cores between gathers and sums.  sink: device memory of at least compute units * waves_per_simd * 1024
+ * bytes (sink_bytes says how many there are), overwritten.
+ */
+int lq_yardstick_matrix(int32_t vector_ops, int32_t waves_per_simd, int32_t iters, void* sink, size_t sink_bytes,
+                        void* hip_stream);
+
 /* Description of the last error on this host thread ("" if none). */
 const char* lq_last_error(void);
 

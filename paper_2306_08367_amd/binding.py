@@ -113,6 +113,8 @@ def _load():
     lib.lq_yardstick_stream.restype = ctypes.c_int
     lib.lq_yardstick_gather.argtypes = [vp, i64, i32, i64, vp, u32, vp, vp]
     lib.lq_yardstick_gather.restype = ctypes.c_int
+    lib.lq_yardstick_matrix.argtypes = [i32, i32, i32, vp, sz, vp]
+    lib.lq_yardstick_matrix.restype = ctypes.c_int
     lib.lq_groupby_agg.argtypes = [i64, i32, ctypes.POINTER(vp), ctypes.POINTER(i64), ctypes.POINTER(vp),
                                    ctypes.POINTER(vp), ctypes.POINTER(i32), i32, ctypes.POINTER(lq_range_pred),
                                    i32, ctypes.POINTER(lq_measure), vp, vp, vp, vp, vp, sz, u32, vp]
@@ -514,6 +516,12 @@ def lq_yardstick_gather(table: torch.Tensor, row_bytes: int, n_gathers: int, sin
     _check(_lib.lq_yardstick_gather(table.data_ptr(), rows, int(row_bytes), int(n_gathers),
                                     None if keys is None else keys.data_ptr(), int(seed) & 0xffffffff, sink.data_ptr(),
                                     _stream(stream)))
+
+
+def lq_yardstick_matrix(vector_ops: int, waves_per_simd: int, iters: int, sink: torch.Tensor, stream=None) -> None:
+    """`iters` rounds of 16 fp32 matrix instructions and `vector_ops` vector multiply-adds on every SIMD."""
+    _check(_lib.lq_yardstick_matrix(int(vector_ops), int(waves_per_simd), int(iters), sink.data_ptr(),
+                                    sink.numel() * sink.element_size(), _stream(stream)))
 
 
 # ---------------------------------------------------------------- decision trees --------------

@@ -92,7 +92,7 @@ __device__ __forceinline__ void relu(v4f (&h)[T]) {
 #pragma unroll
   for (int t = 0; t < T; ++t)
 #pragma unroll
-    for (int v = 0; v < 4; ++v) h[t][v] = fmaxf(h[t][v], 0.f);
+    for (int v = 0; v < 4; ++v) h[t][v] = __builtin_amdgcn_fmed3f(h[t][v], 0.f, __builtin_inff());   // one instruction; NaN -> 0 like fmaxf
 }
 
 // Rows of Y for the 16 rows of a step; lane holds output units 16 ot + 4 (l / 16) + v of row l % 16.
@@ -114,27 +114,17 @@ __device__ __forceinline__ void store_rows(const PredictArgs& a, const v4f (&y)[
   }
 }
 
-// T1, PARTS: l_1 <= 16 T1 PARTS (a multiple of 4); the hidden layer is gathered and fed to the second
-// layer in PARTS column parts of 16 T1 units, so that at most 4 T1 registers per table are in flight.  TH: later hidden layers (and, with two layers, the output) are at most 16 TH wide.
-// NL: number of layers, 2, 3, or 4 for "four or more" (the count is then read at run time).
-// KMAX: number of dimension tables whose gathers are all in flight at once (1..4).  EXTRA: there are
-// more than KMAX = 4 tables; the further ones are gathered inside the step, after the prefetch of the
-// next step has been requested.
-template <int T1, int PARTS, int TH, int NL, int KMAX, bool EXTRA>
-__global__ __launch_bounds__(DEEP_THREADS) void fused_deep_kernel(PredictArgs a, DeepLds L, int vec_y) {
-  constexpr int TALL = T1 * PARTS;                // 16-unit tiles of the whole hidden layer
-  extern __shared__ __align__(16) float lds[];
-  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
-  const int r16 = lane & 15, q4 = lane >> 4;
+// Stages the model in LDS in operand order (THREADS threads of the workgroup call this; the caller
+// synchronises afterwards).  TALL: 16-unit tiles of the first hidden layer, TH: of the later ones.
+template <int THREADS, int NL>
+__device__ __forceinline__ void stage_model(const PredictArgs& a, const DeepLds& L, float* lds, int tid, int TALL, int TH) {
   const int l1 = a.wout[0];
-
-  // ---- stage the model in operand order
-  for (int i = tid; i < TALL * L.kc * 64; i += DEEP_THREADS) {
+  for (int i = tid; i < TALL * L.kc * 64; i += THREADS) {
     const int ln = i & 63, tk = i >> 6, t = tk / L.kc, kc = tk - t * L.kc;
     const int q = 4 * kc + (ln >> 4), c = 16 * t + (ln & 15);
     lds[L.wf + i] = (q < a.c_f && c < l1) ? static_cast<const float*>(a.W[0])[static_cast<int64_t>(q) * a.ldw[0] + c] : 0.f;
   }
-  for (int i = tid; i < 16 * TALL; i += DEEP_THREADS)
+  for (int i = tid; i < 16 * TALL; i += THREADS)
     lds[L.b1 + i] = (i < l1 && a.bias[0]) ? static_cast<const float*>(a.bias[0])[i] : 0.f;
   const int nl = NL == 4 ? a.n_layers : NL;
   for (int layer = 1; layer < nl; ++layer) {
@@ -143,19 +133,90 @@ __global__ __launch_bounds__(DEEP_THREADS) void fused_deep_kernel(PredictArgs a,
     const int win = a.win[layer], wout = a.wout[layer];
     const float* W = static_cast<const float*>(a.W[layer]);
     const int64_t ldw = a.ldw[layer];
-    for (int i = tid; i < tout * tin * 256; i += DEEP_THREADS) {
+    for (int i = tid; i < tout * tin * 256; i += THREADS) {
       const int v = i & 3, ln = (i >> 2) & 63, tile = i >> 8, ot = tile / tin, kt = tile - ot * tin;
       const int f = 16 * kt + 4 * (ln >> 4) + v, c = 16 * ot + (ln & 15);
       lds[L.w[layer - 1] + i] = (f < win && c < wout) ? W[static_cast<int64_t>(f) * ldw + c] : 0.f;
     }
-    for (int i = tid; i < 16 * tout; i += DEEP_THREADS)
+    for (int i = tid; i < 16 * tout; i += THREADS)
       lds[L.b[layer - 1] + i] = (i < wout && a.bias[layer]) ? static_cast<const float*>(a.bias[layer])[i] : 0.f;
   }
   if (NL > 2) {
     const int win = a.win[nl - 1];
-    for (int i = tid; i < 16 * TH; i += DEEP_THREADS)
+    for (int i = tid; i < 16 * TH; i += THREADS)
       lds[L.wvec + i] = i < win ? static_cast<const float*>(a.W[nl - 1])[static_cast<int64_t>(i) * a.ldw[nl - 1]] : 0.f;
   }
+}
+
+// Everything after the second layer for the 16 rows of a step (lane l: row `row`, units 4 (l / 16) .. + 3
+// of every 16), and the store of Y.  h2 holds the second layer's sums with its bias, before the ReLU.
+template <int TH, int NL>
+__device__ __forceinline__ void later_layers(const PredictArgs& a, const DeepLds& L, const float* lds, v4f (&h2)[TH],
+                                             int64_t row, int lane, int nl, int l_out, int vec_y) {
+  const int q4 = lane >> 4;
+  const bool valid = row < a.n;
+  if constexpr (NL == 2) {
+    store_rows<TH>(a, h2, row, valid, q4, l_out, vec_y != 0);
+  } else {
+    relu<TH>(h2);
+    if constexpr (NL == 4) {
+      for (int layer = 2; layer < nl - 1; ++layer) {     // the hidden layers between the second and the last
+        v4f h3[TH];
+        dense_layer<TH, TH>(h2, lds + L.w[layer - 1], lds + L.b[layer - 1], lane, h3);
+        relu<TH>(h3);
+#pragma unroll
+        for (int t = 0; t < TH; ++t) h2[t] = h3[t];
+      }
+    }
+    if (l_out == 1) {
+      // one output: a dot product per row, summed over the four lanes of the row
+      float y = 0.f;
+#pragma unroll
+      for (int t = 0; t < TH; ++t) {
+        const v4f w = *reinterpret_cast<const v4f*>(lds + L.wvec + 16 * t + 4 * q4);
+#pragma unroll
+        for (int v = 0; v < 4; ++v) y = fmaf(h2[t][v], w[v], y);
+      }
+      y += __shfl_xor(y, 16);
+      y += __shfl_xor(y, 32);
+      y += lds[L.b[nl - 2]];
+      if (valid && q4 == 0) static_cast<float*>(a.Y)[row * a.ldy] = y;
+    } else if (l_out <= 16) {
+      v4f y[1];
+      dense_layer<TH, 1>(h2, lds + L.w[nl - 2], lds + L.b[nl - 2], lane, y);
+      store_rows<1>(a, y, row, valid, q4, l_out, vec_y != 0);
+    } else {
+      v4f y[TH];
+      dense_layer<TH, TH>(h2, lds + L.w[nl - 2], lds + L.b[nl - 2], lane, y);
+      store_rows<TH>(a, y, row, valid, q4, l_out, vec_y != 0);
+    }
+  }
+}
+
+// Asking for two wavefronts per SIMD caps the kernel at 256 registers, all of them ordinary ones: the
+// accumulators of the matrix instructions then need no copies before the vector instructions that
+// follow them (bias, ReLU, the sum over the row).  The instantiations with the most gathers in flight or
+// the widest later layers need more and keep the default.
+template <int T1, int TH, int KMAX> struct DeepRegs {
+  static constexpr int MIN_WAVES = (T1 * KMAX <= 24 && TH <= 4) ? 2 : 1;
+};
+
+// T1, PARTS: l_1 <= 16 T1 PARTS (a multiple of 4); the hidden layer is gathered and fed to the second
+// layer in PARTS column parts of 16 T1 units, so that at most 4 T1 registers per table are in flight.  TH: later hidden layers (and, with two layers, the output) are at most 16 TH wide.
+// NL: number of layers, 2, 3, or 4 for "four or more" (the count is then read at run time).
+// KMAX: number of dimension tables whose gathers are all in flight at once (1..4).  EXTRA: there are
+// more than KMAX = 4 tables; the further ones are gathered inside the step, after the prefetch of the
+// next step has been requested.
+template <int T1, int PARTS, int TH, int NL, int KMAX, bool EXTRA>
+__global__ __launch_bounds__(DEEP_THREADS, (DeepRegs<T1, TH, KMAX>::MIN_WAVES)) void fused_deep_kernel(PredictArgs a, DeepLds L, int vec_y) {
+  constexpr int TALL = T1 * PARTS;                // 16-unit tiles of the whole hidden layer
+  extern __shared__ __align__(16) float lds[];
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  const int r16 = lane & 15, q4 = lane >> 4;
+  const int l1 = a.wout[0];
+
+  stage_model<DEEP_THREADS, NL>(a, L, lds, tid, TALL, TH);
+  const int nl = NL == 4 ? a.n_layers : NL;
   __syncthreads();
 
   const int64_t n_steps = (a.n + 15) / 16;
@@ -326,45 +387,7 @@ __global__ __launch_bounds__(DEEP_THREADS) void fused_deep_kernel(PredictArgs a,
       dense_accumulate<T1, T2, TALL>(h1, lds + L.w[0], part * T1, lane, h2);
     }
 
-    // ---- later layers
-    const int64_t row = step * 16 + r16;
-    const bool valid = row < a.n;
-    if constexpr (NL == 2) {
-      store_rows<TH>(a, h2, row, valid, q4, l_out, vec_y != 0);
-    } else {
-      relu<TH>(h2);
-      if constexpr (NL == 4) {
-        for (int layer = 2; layer < nl - 1; ++layer) {     // the hidden layers between the second and the last
-          v4f h3[TH];
-          dense_layer<TH, TH>(h2, lds + L.w[layer - 1], lds + L.b[layer - 1], lane, h3);
-          relu<TH>(h3);
-#pragma unroll
-          for (int t = 0; t < TH; ++t) h2[t] = h3[t];
-        }
-      }
-      if (l_out == 1) {
-        // one output: a dot product per row, summed over the four lanes of the row
-        float y = 0.f;
-#pragma unroll
-        for (int t = 0; t < TH; ++t) {
-          const v4f w = *reinterpret_cast<const v4f*>(lds + L.wvec + 16 * t + 4 * q4);
-#pragma unroll
-          for (int v = 0; v < 4; ++v) y = fmaf(h2[t][v], w[v], y);
-        }
-        y += __shfl_xor(y, 16);
-        y += __shfl_xor(y, 32);
-        y += lds[L.b[nl - 2]];
-        if (valid && q4 == 0) static_cast<float*>(a.Y)[row * a.ldy] = y;
-      } else if (l_out <= 16) {
-        v4f y[1];
-        dense_layer<TH, 1>(h2, lds + L.w[nl - 2], lds + L.b[nl - 2], lane, y);
-        store_rows<1>(a, y, row, valid, q4, l_out, vec_y != 0);
-      } else {
-        v4f y[TH];
-        dense_layer<TH, TH>(h2, lds + L.w[nl - 2], lds + L.b[nl - 2], lane, y);
-        store_rows<TH>(a, y, row, valid, q4, l_out, vec_y != 0);
-      }
-    }
+    later_layers<TH, NL>(a, L, lds, h2, step * 16 + r16, lane, nl, l_out, vec_y);
     if (!more) break;
     step += stride;
     if constexpr (PARTS > 1) {
@@ -386,11 +409,10 @@ int launch_deep_nl(const PredictArgs& a, const DeepLds& L, size_t lds, int64_t b
                    hipStream_t s) {
 #define LQ_DEEP(T1_, PARTS_, TH_, K_, X_)                                                                   \
   do {                                                                                                      \
+    const void* fn = reinterpret_cast<const void*>(&fused_deep_kernel<T1_, PARTS_, TH_, NL_, K_, X_>);      \
     if (lds > 64 * 1024)                                                                                    \
-      LQ_HIP_TRY(hipFuncSetAttribute(reinterpret_cast<const void*>(&fused_deep_kernel<T1_, PARTS_, TH_, NL_, K_, X_>), \
-                                     hipFuncAttributeMaxDynamicSharedMemorySize, static_cast<int>(lds)));   \
-    const int64_t resident = static_cast<int64_t>(num_cus()) *                                              \
-        resident_per_cu(reinterpret_cast<const void*>(&fused_deep_kernel<T1_, PARTS_, TH_, NL_, K_, X_>), DEEP_THREADS, lds); \
+      LQ_HIP_TRY(hipFuncSetAttribute(fn, hipFuncAttributeMaxDynamicSharedMemorySize, static_cast<int>(lds))); \
+    const int64_t resident = static_cast<int64_t>(num_cus()) * resident_per_cu(fn, DEEP_THREADS, lds);     \
     hipLaunchKernelGGL((fused_deep_kernel<T1_, PARTS_, TH_, NL_, K_, X_>),                                  \
                        dim3(static_cast<unsigned>(std::min(blocks, resident))), dim3(DEEP_THREADS), lds, s, a, L, vec_y); \
   } while (0)

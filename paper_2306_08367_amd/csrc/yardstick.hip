@@ -74,6 +74,37 @@ __global__ __launch_bounds__(256) void yard_gather_kernel(const v4u* __restrict_
 }
 
 }  // namespace
+
+typedef float v4f_y __attribute__((ext_vector_type(4)));
+
+// Per iteration: 16 fp32 16x16x4 matrix instructions on four accumulators, then NV independent vector
+// multiply-adds on eight registers.  Timed for NV = 0 and NV > 0 at the same occupancy, it shows how much
+// of the vector work the matrix instructions of the same and of the other wavefronts of a SIMD hide.
+template <int NV>
+__global__ __launch_bounds__(256) void yard_matrix_kernel(float* sink, int iters, float a0, float b0) {
+  v4f_y acc[4];
+#pragma unroll
+  for (int i = 0; i < 4; ++i) acc[i] = v4f_y{0.f, 0.f, 0.f, 0.f};
+  float x[8];
+#pragma unroll
+  for (int i = 0; i < 8; ++i) x[i] = a0 * i + threadIdx.x;
+  const float a = a0 + threadIdx.x, b = b0;
+  for (int it = 0; it < iters; ++it) {
+#pragma unroll
+    for (int r = 0; r < 16; ++r) acc[r & 3] = __builtin_amdgcn_mfma_f32_16x16x4f32(a, b, acc[r & 3], 0, 0, 0);
+    __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+    for (int v = 0; v < NV; ++v) x[v & 7] = fmaf(x[v & 7], b, a);
+    __builtin_amdgcn_sched_barrier(0);
+  }
+  float t = 0.f;
+#pragma unroll
+  for (int i = 0; i < 4; ++i) t += acc[i][0] + acc[i][1] + acc[i][2] + acc[i][3];
+#pragma unroll
+  for (int i = 0; i < 8; ++i) t += x[i];
+  sink[static_cast<size_t>(blockIdx.x) * 256 + threadIdx.x] = t;
+}
+
 }  // namespace lq
 
 using namespace lq;
@@ -127,6 +158,29 @@ int lq_yardstick_gather(const void* table, int64_t rows, int32_t row_bytes, int6
   }
 #undef LQ_YG
   LQ_LAUNCH_CHECK("yard_gather_kernel");
+  return LQ_OK;
+}
+
+int lq_yardstick_matrix(int32_t vector_ops, int32_t waves_per_simd, int32_t iters, void* sink, size_t sink_bytes,
+                        void* hip_stream) {
+  clear_error();
+  if (!sink) return fail(LQ_ERR_NULL, "sink is NULL");
+  if (waves_per_simd < 1 || waves_per_simd > 8 || iters < 1) return fail(LQ_ERR_SHAPE, "waves_per_simd must be 1..8, iters >= 1");
+  const int64_t blocks = static_cast<int64_t>(num_cus()) * waves_per_simd;     // 256 threads: one wavefront per SIMD
+  if (sink_bytes < static_cast<size_t>(blocks) * 256 * sizeof(float))
+    return fail(LQ_ERR_SHAPE, "matrix yardstick: sink needs %lld bytes", (long long)(blocks * 256 * sizeof(float)));
+  hipStream_t s = static_cast<hipStream_t>(hip_stream);
+#define LQ_YM(NV) hipLaunchKernelGGL(yard_matrix_kernel<NV>, dim3(static_cast<unsigned>(blocks)), dim3(256), 0, s, \
+                                     static_cast<float*>(sink), iters, 1.0f, 0.5f)
+  switch (vector_ops) {
+    case 0: LQ_YM(0); break;
+    case 32: LQ_YM(32); break;
+    case 64: LQ_YM(64); break;
+    case 128: LQ_YM(128); break;
+    default: return fail(LQ_ERR_SHAPE, "vector_ops must be 0, 32, 64 or 128");
+  }
+#undef LQ_YM
+  LQ_LAUNCH_CHECK("yard_matrix_kernel");
   return LQ_OK;
 }
 

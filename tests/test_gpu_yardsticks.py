@@ -48,3 +48,19 @@ def test_yardsticks_refuse_bad_arguments(lq):
         lq.lq_yardstick_read(buf[8:4088], 1, sink)                # misaligned
     with pytest.raises(lq.LQError):
         lq.lq_yardstick_read(buf, 0, sink)
+
+
+def test_matrix_yardstick_runs_and_refuses_bad_arguments(lq):
+    cus = torch.cuda.get_device_properties(0).multi_processor_count
+    sink = torch.zeros(cus * 2 * 256, dtype=torch.float32, device="cuda")
+    for nv in (0, 32, 64, 128):
+        sink.zero_()
+        lq.lq_yardstick_matrix(nv, 2, 3, sink)
+        torch.cuda.synchronize()
+        assert torch.isfinite(sink).all() and (sink != 0).any()
+    with pytest.raises(lq.LQError):
+        lq.lq_yardstick_matrix(48, 2, 3, sink)                    # not one of the compiled mixes
+    with pytest.raises(lq.LQError):
+        lq.lq_yardstick_matrix(0, 3, 3, sink)                     # sink too small for three wavefronts per SIMD
+    with pytest.raises(lq.LQError):
+        lq.lq_yardstick_matrix(0, 0, 3, sink)
