@@ -124,8 +124,7 @@ template <> struct Chunk<bf16_t, 8> {
     uint32_t w[4];
 #pragma unroll
     for (int q = 0; q < 4; ++q)
-      w[q] = static_cast<uint32_t>(f32_to_bf16(v[2 * q])) |
-             (static_cast<uint32_t>(f32_to_bf16(v[2 * q + 1])) << 16);
+      w[q] = f32x2_to_bf16x2(v[2 * q], v[2 * q + 1]);
     *reinterpret_cast<uint4*>(p) = make_uint4(w[0], w[1], w[2], w[3]);
   }
 };

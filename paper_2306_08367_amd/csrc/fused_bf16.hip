@@ -26,7 +26,7 @@ __device__ __forceinline__ void unpack_add(const v4u& w, float (&acc)[8]) {
   }
 }
 __device__ __forceinline__ unsigned int pack2(float lo, float hi) {
-  return static_cast<unsigned int>(f32_to_bf16(lo)) | (static_cast<unsigned int>(f32_to_bf16(hi)) << 16);
+  return f32x2_to_bf16x2(lo, hi);
 }
 
 // KB = l_1 / 32.  NL = 1: Y = z (TY = bf16 or float).  NL = 2: Y = W_2^T relu(z) + b_2, l_2 <= 16.

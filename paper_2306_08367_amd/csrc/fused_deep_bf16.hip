@@ -40,18 +40,15 @@ __device__ __forceinline__ void unpack_add(const v4u& w, float (&acc)[8]) {
     acc[2 * q + 1] += __uint_as_float(w[q] & 0xffff0000u);
   }
 }
-__device__ __forceinline__ unsigned int pack2(float lo, float hi) {
-  return static_cast<unsigned int>(f32_to_bf16(lo)) | (static_cast<unsigned int>(f32_to_bf16(hi)) << 16);
-}
+__device__ __forceinline__ unsigned int pack2(float lo, float hi) { return f32x2_to_bf16x2(lo, hi); }
 // ReLU of two activations, each split into a bf16 head and a bf16 tail (x = head + tail up to 2^-17
 // relative): feeding both to the matrix cores keeps the activations at about fp32 precision although
 // the instruction takes bf16 operands (the weights are bf16 values to begin with, so exact).
 struct HeadTail { unsigned int head, tail; };
 __device__ __forceinline__ HeadTail split2_relu(float x0, float x1) {
   x0 = fmaxf(x0, 0.f); x1 = fmaxf(x1, 0.f);
-  const bf16_t h0 = f32_to_bf16(x0), h1 = f32_to_bf16(x1);
-  return {static_cast<unsigned int>(h0) | (static_cast<unsigned int>(h1) << 16),
-          pack2(x0 - bf16_to_f32(h0), x1 - bf16_to_f32(h1))};
+  const unsigned int head = pack2(x0, x1);
+  return {head, pack2(x0 - __uint_as_float(head << 16), x1 - __uint_as_float(head & 0xffff0000u))};
 }
 
 // out^T = W^T h^T + b: CH chunks of 32 inputs (B operands: heads hb and tails hl), TOUT tiles of 16 outputs.
@@ -124,7 +121,7 @@ __device__ __forceinline__ void stage_weights(const PredictArgs& a, int layer, b
 // KB: l_1 <= 32 KB (a multiple of 8; lanes whose units lie past l_1 idle).  TH: later hidden layers (and, with two layers, the output) are at most 16 TH wide.
 // NL: number of layers, 2, 3, or 4 for "four or more" (the count is then read at run time).
 template <int KB, int TH, int NL>
-__global__ __launch_bounds__(DBF_THREADS) void fused_deep_bf16_kernel(PredictArgs a, DeepBfLds L) {
+__global__ __launch_bounds__(DBF_THREADS, (TH <= 8 ? 2 : 1)) void fused_deep_bf16_kernel(PredictArgs a, DeepBfLds L) {
   constexpr int M = (TH + 1) / 2;                       // 32-input chunks of a later hidden layer
   constexpr int TLAST = NL == 2 ? TH : 1;
   extern __shared__ __align__(16) unsigned char smem[];
@@ -143,6 +140,27 @@ __global__ __launch_bounds__(DBF_THREADS) void fused_deep_bf16_kernel(PredictArg
   const int l_out = a.wout[nl - 1], l1 = a.wout[0];
   const bool w0_vec = (reinterpret_cast<uintptr_t>(a.W[0]) & 15) == 0 && a.ldw[0] % 8 == 0;
 
+  // Gathers: the row of table k + 1 is requested before the row of table k is added up, so one row is
+  // always in flight (lanes whose units lie past l_1 re-read the first piece of the row and add
+  // nothing).  The first table of the next pass is requested before the matrix work of this pass, its
+  // keys at the top of this pass.
+  int key[LQ_MAX_DIMS];
+  v4u w[2][KB];
+  auto load_keys = [&](int64_t r, int (&kk)[LQ_MAX_DIMS]) {
+#pragma unroll
+    for (int k = 0; k < LQ_MAX_DIMS; ++k) kk[k] = k < a.K ? a.fk[k][r] : 0;
+  };
+  auto request = [&](int k, int f, v4u (&dst)[KB]) {
+    const char* p = static_cast<const char*>(a.P[k]) +
+                    (static_cast<uint64_t>(static_cast<uint32_t>(f) * static_cast<uint32_t>(a.ldp[k] >> 3)) << 4);
+#pragma unroll
+    for (int kb = 0; kb < KB; ++kb) dst[kb] = *reinterpret_cast<const v4u*>(p + (32 * kb + 8 * g < l1 ? 64 * kb + 16 * g : 0));
+  };
+  if (wave < npass) {
+    load_keys(min<int64_t>(wave * 16 + j, a.n - 1), key);
+    request(0, key[0], w[0]);
+  }
+
   for (int64_t pass = wave; pass < npass; pass += nwaves) {
     // The staged model is read from LDS where it is used (otherwise the reads are hoisted out of
     // the loop and the weights take every register there is).
@@ -150,6 +168,9 @@ __global__ __launch_bounds__(DBF_THREADS) void fused_deep_bf16_kernel(PredictArg
     const int64_t row = pass * 16 + j;
     const bool live = row < a.n;
     const int64_t rr = live ? row : a.n - 1;
+    const bool more = pass + nwaves < npass;
+    int keyn[LQ_MAX_DIMS];
+    load_keys(min<int64_t>((more ? pass + nwaves : pass) * 16 + j, a.n - 1), keyn);
 
     // ---- layer 1: z = x W_f + sum_k P_k[fk_k] + b_1 in fp32, lane (g, j) owns units 32 kb + 8 g + t
     float acc[KB][8];
@@ -190,15 +211,17 @@ __global__ __launch_bounds__(DBF_THREADS) void fused_deep_bf16_kernel(PredictArg
         }
       }
     }
-    for (int k = 0; k < a.K; ++k) {
-      const int64_t f = a.fk[k][rr];
-      const bf16_t* p = static_cast<const bf16_t*>(a.P[k]) + f * a.ldp[k] + 8 * g;
-      v4u w[KB];
 #pragma unroll
-      for (int kb = 0; kb < KB; ++kb) w[kb] = 32 * kb + 8 * g < l1 ? *reinterpret_cast<const v4u*>(p + 32 * kb) : v4u{0u, 0u, 0u, 0u};
+    for (int k = 0; k < LQ_MAX_DIMS; ++k) {
+      if (k >= a.K) break;
+      if (k + 1 < a.K) request(k + 1, key[(k + 1) % LQ_MAX_DIMS], w[(k + 1) & 1]);
 #pragma unroll
-      for (int kb = 0; kb < KB; ++kb) unpack_add(w[kb], acc[kb]);
+      for (int kb = 0; kb < KB; ++kb)
+        if (32 * kb + 8 * g < l1) unpack_add(w[k & 1][kb], acc[kb]);
     }
+    if (more) request(0, keyn[0], w[0]);
+#pragma unroll
+    for (int k = 0; k < LQ_MAX_DIMS; ++k) key[k] = keyn[k];
     // the wide first hidden layer is rounded to bf16 once (rounding errors of many units average out),
     // as in the one-tile bf16 kernel; the few activations of the later layers are fed head and tail
     v4u hb[KB];
@@ -252,8 +275,10 @@ int try_fused_deep_bf16(const PredictArgs& a, hipStream_t s) {
   const int l1 = a.wout[0];
   if (l1 % 8 || l1 > 256) return -1;
   const int KB = l1 <= 32 ? 1 : (l1 <= 64 ? 2 : (l1 <= 128 ? 4 : 8));   // 32-unit blocks, padded to a power of two
-  for (int k = 0; k < a.K; ++k)
+  for (int k = 0; k < a.K; ++k) {
     if (!aligned(a.P[k], 16) || a.ldp[k] % 8) return -1;
+    if (a.prows[k] * (a.ldp[k] / 8) > 0xffffffffLL) return -1;     // the kernel counts 16-byte pieces of a table in 32 bits
+  }
   const int l_out = a.wout[NL - 1];
   if (NL == 2 && l_out <= 16) return -1;              // the one-tile bf16 kernel covers these
   int wide = 0;
@@ -276,14 +301,15 @@ int try_fused_deep_bf16(const PredictArgs& a, hipStream_t s) {
   if (lds > 150 * 1024) return -1;
 
   const int64_t npass = (a.n + 15) / 16;
-  const int64_t blocks = std::min<int64_t>((npass + 3) / 4, static_cast<int64_t>(num_cus()) * 8);
+  const int64_t blocks = (npass + 3) / 4;             // capped below at one resident set: every wavefront stages once
   if (blocks <= 0) return LQ_OK;
 #define LQ_DBF(KB_, TH_, NL_)                                                                           \
   do {                                                                                                  \
+    const void* fn = reinterpret_cast<const void*>(&fused_deep_bf16_kernel<KB_, TH_, NL_>);              \
     if (lds > 64 * 1024)                                                                                \
-      LQ_HIP_TRY(hipFuncSetAttribute(reinterpret_cast<const void*>(&fused_deep_bf16_kernel<KB_, TH_, NL_>), \
-                                     hipFuncAttributeMaxDynamicSharedMemorySize, static_cast<int>(lds))); \
-    hipLaunchKernelGGL((fused_deep_bf16_kernel<KB_, TH_, NL_>), dim3(static_cast<unsigned>(blocks)),     \
+      LQ_HIP_TRY(hipFuncSetAttribute(fn, hipFuncAttributeMaxDynamicSharedMemorySize, static_cast<int>(lds))); \
+    const int64_t resident = static_cast<int64_t>(num_cus()) * resident_per_cu(fn, DBF_THREADS, lds);   \
+    hipLaunchKernelGGL((fused_deep_bf16_kernel<KB_, TH_, NL_>), dim3(static_cast<unsigned>(std::min(blocks, resident))), \
                        dim3(DBF_THREADS), lds, s, a, L);                                                \
   } while (0)
 #define LQ_DBF_KB(TH_, NL_)                                                                             \

@@ -54,7 +54,7 @@ template <> struct Piece<bf16_t> {
     v4u o;
 #pragma unroll
     for (int q = 0; q < 4; ++q)
-      o[q] = static_cast<unsigned int>(f32_to_bf16(z[2 * q])) | (static_cast<unsigned int>(f32_to_bf16(z[2 * q + 1])) << 16);
+      o[q] = f32x2_to_bf16x2(z[2 * q], z[2 * q + 1]);
     return o;
   }
 };
@@ -262,8 +262,7 @@ void fused_rowbatch_wide_kernel(PredictArgs a) {
                 *reinterpret_cast<v4f*>(yr + 4 * q) = v4f{o4[0], o4[1], o4[2], o4[3]};
               } else {
                 *reinterpret_cast<v2u*>(yr + 4 * q) =
-                    v2u{static_cast<unsigned int>(f32_to_bf16(o4[0])) | (static_cast<unsigned int>(f32_to_bf16(o4[1])) << 16),
-                        static_cast<unsigned int>(f32_to_bf16(o4[2])) | (static_cast<unsigned int>(f32_to_bf16(o4[3])) << 16)};
+                    v2u{f32x2_to_bf16x2(o4[0], o4[1]), f32x2_to_bf16x2(o4[2], o4[3])};
               }
             }
         } else {

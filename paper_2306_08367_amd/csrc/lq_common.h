@@ -96,11 +96,15 @@ __device__ __forceinline__ float bf16_to_f32(bf16_t v) {
 }
 
 // Round to nearest even; NaN stays NaN (quiet).
+typedef __bf16 lq_bf16x2 __attribute__((ext_vector_type(2)));
+typedef float lq_f32x2 __attribute__((ext_vector_type(2)));
+// Two floats rounded to bf16 (to nearest, ties to even; NaN stays NaN), `lo` in bits 0..15 of the result:
+// the hardware's packed conversion, one instruction.
+__device__ __forceinline__ unsigned int f32x2_to_bf16x2(float lo, float hi) {
+  return __builtin_bit_cast(unsigned int, __builtin_convertvector((lq_f32x2){lo, hi}, lq_bf16x2));
+}
 __device__ __forceinline__ bf16_t f32_to_bf16(float f) {
-  uint32_t u = __float_as_uint(f);
-  if ((u & 0x7fffffffu) > 0x7f800000u) return static_cast<bf16_t>((u >> 16) | 0x0040u);
-  u += 0x7fffu + ((u >> 16) & 1u);
-  return static_cast<bf16_t>(u >> 16);
+  return static_cast<bf16_t>(f32x2_to_bf16x2(f, 0.f) & 0xffffu);
 }
 
 template <typename T> struct Elem;
