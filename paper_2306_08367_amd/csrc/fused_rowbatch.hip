@@ -56,14 +56,23 @@ __device__ __forceinline__ void load_rows(const PredictArgs& a, int64_t rr, RowR
   for (int q = 0; q < CFC; ++q) r.x[q] = __builtin_nontemporal_load(reinterpret_cast<const v4f*>(xr) + q);
 }
 
+// Keys become byte offsets of their rows once per batch (one 32-bit product per key: the host has
+// checked that every projected table is smaller than 4 GiB), so that a gather costs a broadcast and one
+// add on top of its load instead of a 64-bit multiply-add.
+template <int K, int CFC>
+__device__ __forceinline__ void keys_to_offsets(const PredictArgs& a, RowRegs<K, CFC>& r) {
+#pragma unroll
+  for (int k = 0; k < K; ++k)
+    r.fk[k] = static_cast<int>(static_cast<uint32_t>(r.fk[k]) * (static_cast<uint32_t>(a.ldp[k]) * 4u));
+}
+
 template <int T, int K, int CFC>
 __device__ __forceinline__ void issue_pass(const PredictArgs& a, int c, const RowRegs<K, CFC>& r,
                                            v4f (&p)[K > 0 ? K : 1]) {
 #pragma unroll
   for (int k = 0; k < K; ++k) {
-    const int j = dppi<DPP_ROW_BCAST0 + T>(r.fk[k]);
-    p[k] = *reinterpret_cast<const v4f*>(static_cast<const float*>(a.P[k]) +
-                                         static_cast<int64_t>(j) * a.ldp[k] + 4 * c);
+    const uint32_t at = static_cast<uint32_t>(dppi<DPP_ROW_BCAST0 + T>(r.fk[k])) + 16u * static_cast<uint32_t>(c);
+    p[k] = *reinterpret_cast<const v4f*>(static_cast<const char*>(a.P[k]) + at);
   }
 }
 template <int GRP, int K, int CFC>
@@ -175,6 +184,7 @@ void fused_rowbatch64_kernel(PredictArgs a) {
   int64_t row = b * 64 + lane;
   RowRegs<K, CFC> cur, nxt;
   load_rows<K, CFC>(a, row < a.n ? row : a.n - 1, cur);
+  keys_to_offsets<K, CFC>(a, cur);
   Gathered<K> ga, gb;
   issue_group<0, K, CFC>(a, c, cur, ga);
   for (;;) {
@@ -192,6 +202,7 @@ void fused_rowbatch64_kernel(PredictArgs a) {
     compute_group<1, K, CFC, NL, L2>(a, c, row0, s, cur, gb, w, yk);
     issue_group<3, K, CFC>(a, c, cur, gb);
     compute_group<2, K, CFC, NL, L2>(a, c, row0, s, cur, ga, w, yk);
+    keys_to_offsets<K, CFC>(a, nxt);
     issue_group<0, K, CFC>(a, c, nxt, ga);   // first group of the next batch (a repeat of valid rows at the end)
     compute_group<3, K, CFC, NL, L2>(a, c, row0, s, cur, gb, w, yk);
     if constexpr (NL == 2) {
@@ -252,8 +263,10 @@ int try_rowbatch64(const PredictArgs& a, hipStream_t s) {
   if (a.x_dtype != LQ_F32 || a.p_dtype != LQ_F32 || a.y_dtype != LQ_F32) return -1;
   if (a.wout[0] != 64 || a.n_layers > 2 || a.K < 1 || a.K > 4) return -1;
   if (a.n < 256) return -1;   // too few 64-row batches to matter; the simpler kernel handles it
-  for (int k = 0; k < a.K; ++k)
+  for (int k = 0; k < a.K; ++k) {
     if (!aligned(a.P[k], 16) || a.ldp[k] % 4) return -1;
+    if (a.prows[k] * a.ldp[k] * 4 > 0xffffffffLL) return -1;     // the kernel keeps byte offsets into a table in 32 bits
+  }
   if (a.c_f > 0 && (!aligned(a.X, 16) || a.ldx % 4)) return -1;
   if (a.n_layers == 1 && (!aligned(a.Y, 16) || a.ldy % 4)) return -1;
   switch (a.K) {

@@ -111,6 +111,16 @@ __device__ __forceinline__ void load_rows(const PredictArgs& a, int64_t rr, bool
   }
 }
 
+// Keys become byte offsets of their rows once per batch (one 32-bit product per key: the host has
+// checked that every projected table is smaller than 4 GiB), so that a gather costs a broadcast and one
+// add on top of its load instead of a 64-bit multiply-add.
+template <typename T, int K, int CFC>
+__device__ __forceinline__ void keys_to_offsets(const PredictArgs& a, WRow<K, CFC>& r) {
+#pragma unroll
+  for (int k = 0; k < K; ++k)
+    r.fk[k] = static_cast<int>(static_cast<uint32_t>(r.fk[k]) * (static_cast<uint32_t>(a.ldp[k]) * static_cast<uint32_t>(sizeof(T))));
+}
+
 // Gathers of passes PG grp .. PG grp + PG - 1.
 template <typename T, int LPR, int K, int CFC, int PG>
 __device__ __forceinline__ void issue_group(const PredictArgs& a, int c, bool active, int group_base, int grp,
@@ -119,11 +129,9 @@ __device__ __forceinline__ void issue_group(const PredictArgs& a, int c, bool ac
   for (int u = 0; u < PG; ++u)
 #pragma unroll
     for (int k = 0; k < K; ++k) {
-      const int j = from_lane<LPR>(r.fk[k], PG * grp + u, group_base);
+      const uint32_t at = static_cast<uint32_t>(from_lane<LPR>(r.fk[k], PG * grp + u, group_base)) + 16u * static_cast<uint32_t>(c);
       g.p[u][k] = v4u{0u, 0u, 0u, 0u};
-      if (active)
-        g.p[u][k] = *reinterpret_cast<const v4u*>(static_cast<const T*>(a.P[k]) + static_cast<int64_t>(j) * a.ldp[k] +
-                                                  Piece<T>::COLS * c);
+      if (active) g.p[u][k] = *reinterpret_cast<const v4u*>(static_cast<const char*>(a.P[k]) + at);
     }
 }
 
@@ -230,6 +238,7 @@ void fused_rowbatch_wide_kernel(PredictArgs a) {
   int64_t row = b * 64 + lane;
   WRow<K, CFC> cur, nxt;
   load_rows<T, K, CFC>(a, row < a.n ? row : a.n - 1, x_vec, cur);
+  keys_to_offsets<T, K, CFC>(a, cur);
   WGather<K, PG> ga, gb;
   issue_group<T, LPR, K, CFC, PG>(a, c, active, group_base, 0, cur, ga);
   for (;;) {
@@ -246,7 +255,10 @@ void fused_rowbatch_wide_kernel(PredictArgs a) {
       issue_group<T, LPR, K, CFC, PG>(a, c, active, group_base, grp + 1, cur, gb);
       compute_group<T, LPR, K, CFC, NL, L2P, PG>(a, c, active, group_base, grp, row0, cur, ga, w, yk);
       if (grp + 2 < NG) issue_group<T, LPR, K, CFC, PG>(a, c, active, group_base, grp + 2, cur, ga);
-      else issue_group<T, LPR, K, CFC, PG>(a, c, active, group_base, 0, nxt, ga);   // first group of the next batch (valid rows repeated at the end)
+      else {                                       // first group of the next batch (valid rows repeated at the end)
+        keys_to_offsets<T, K, CFC>(a, nxt);
+        issue_group<T, LPR, K, CFC, PG>(a, c, active, group_base, 0, nxt, ga);
+      }
       compute_group<T, LPR, K, CFC, NL, L2P, PG>(a, c, active, group_base, grp + 1, row0, cur, gb, w, yk);
     }
     if constexpr (NL == 2) {

@@ -13,8 +13,10 @@ int try_rowbatch_wide(const PredictArgs& a, hipStream_t s) {
   if (a.n_layers > 2 || a.n < 256) return -1;
   if (a.x_dtype == LQ_BF16 && a.p_dtype == LQ_BF16 && a.y_dtype == LQ_BF16) return try_rowbatch_wide_bf16(a, s);
   if (a.x_dtype != LQ_F32 || a.p_dtype != LQ_F32 || a.y_dtype != LQ_F32) return -1;
-  for (int k = 0; k < a.K; ++k)
+  for (int k = 0; k < a.K; ++k) {
     if (!aligned(a.P[k], 16) || a.ldp[k] % 4) return -1;
+    if (a.prows[k] * a.ldp[k] * 4 > 0xffffffffLL) return -1;     // the kernels keep byte offsets into a table in 32 bits
+  }
   if (a.n_layers == 1 && (!aligned(a.Y, 16) || a.ldy % 4)) return -1;
   const int l1 = a.wout[0];
   if (l1 % 4 || l1 > 256 || l1 <= 16) return -1;        // (up to 16: one row per 1..4 lanes, the lane-group kernel)

@@ -8,8 +8,10 @@ namespace lq {
 // n and the layer count are checked by the caller (try_rowbatch_wide).
 int try_rowbatch_wide_bf16(const PredictArgs& a, hipStream_t s) {
   if (a.K == 4 && a.c_f > 4) return -1;      // (would not fit the register file without spilling)
-  for (int k = 0; k < a.K; ++k)
+  for (int k = 0; k < a.K; ++k) {
     if (!aligned(a.P[k], 16) || a.ldp[k] % 8) return -1;
+    if (a.prows[k] * a.ldp[k] * 2 > 0xffffffffLL) return -1;     // the kernels keep byte offsets into a table in 32 bits
+  }
   if (a.n_layers == 1 && (!aligned(a.Y, 16) || a.ldy % 8)) return -1;
   const int l1 = a.wout[0];
   if (l1 % 8 || l1 > 512 || l1 <= 32) return -1;
