@@ -144,3 +144,29 @@ def test_fused_tree_over_more_than_2e31_rows(lq):
     leaf_k, _ = lq.lq_fused_join_tree_masks(fks, masks, f, t, H)
     torch.cuda.synchronize()
     assert torch.equal(leaf_k, leaf)
+
+
+@pytest.mark.parametrize("shape", [
+    # name, dimension rows (the last table's projected rows pass 4 GiB), columns, layers, dtype
+    ("mlp_64_1_f32", (1_000, (1 << 24) + 5), (8, 2), (64, 1), torch.float32),          # 256-byte projected rows
+    ("mlp_128_4_f32", ((1 << 23) + 5,), (3,), (128, 4), torch.float32),                 # 512-byte projected rows
+    ("mlp_64_64_1_f32", (1_000, (1 << 24) + 5), (8, 2), (64, 64, 1), torch.float32),    # matrix-core kernel: 2^28 pieces
+    ("mlp_256_2_bf16", ((1 << 23) + 5, 500), (2, 6), (256, 2), torch.bfloat16),         # 512-byte bf16 rows
+], ids=lambda s: s[0])
+def test_projected_tables_of_4_gib_and_more(lq, shape):
+    """A projected table whose byte size passes 2^32: the kernels that keep 32-bit byte offsets into a table
+    must stand aside, and whichever kernel runs must address the far end of the table correctly.  Half of the
+    fact rows point into the last 1,000 rows of the big table."""
+    name, rows, cols, layers, dt = shape
+    n = 20_011
+    w = WL.make_predict(name, n, 4, rows, cols, layers, seed=WL.SEED0 + 950, device="cuda", dtype=dt,
+                        w_sigma=[0.3] + [1.0 / np.sqrt(a) for a in layers[:-1]], bias=True)
+    big = int(np.argmax(rows))
+    far = torch.arange(n, device="cuda") % 2 == 0
+    w.fks[big][far] = (rows[big] - 1 - torch.randint(0, 1_000, (int(far.sum()),), device="cuda")).to(torch.int32)
+    P = lq.lq_project_dims(w.dims, w.weights[0], w.c_f, p_dtype=dt)
+    assert P[big].numel() * P[big].element_size() >= 2 ** 32
+    Y = lq.lq_fused_join_predict(w.X, w.fks, P, w.weights, w.biases, y_dtype=torch.float32)
+    torch.cuda.synchronize()
+    want = O.join_predict(w.X.cpu(), cpu_list(w.dims), cpu_list(w.fks), cpu_list(w.weights), cpu_list(w.biases), nthreads=16)
+    assert_close(Y, want, TOL_BF16 if dt == torch.bfloat16 else TOL_F32, f"{name}: projected table of {P[big].numel() * P[big].element_size()} bytes")
