@@ -337,12 +337,17 @@ def main():
         ft = time_call(lambda: lq.lq_fused_join_predict(w1.X, w1.fks, P1, w1.weights, None, Y=Y1), 50, 5)
         mt = time_call(lambda: lq.lq_materialized_join_predict(w1.X, w1.dims, w1.fks, w1.weights, None, Y=Y1, ws=ws1), 50, 5)
         gus = graph_time(lambda: lq.lq_fused_join_predict(w1.X, w1.fks, P1, w1.weights, None, Y=Y1), reps=32, iters=20, warmup=3)
+        gpus = graph_time(lambda: lq.lq_project_dims(w1.dims, w1.weights[0], w1.c_f, P=P1), reps=32, iters=20, warmup=3)
+        gmus = graph_time(lambda: lq.lq_materialized_join_predict(w1.X, w1.dims, w1.fks, w1.weights, None, Y=Y1, ws=ws1),
+                          reps=32, iters=20, warmup=3)
         out["fused_c1"] = {"fact_rows": w1.n, "fused_us": ft[0] * 1e3, "fused_us_median": ft[2] * 1e3, "fused_us_min": ft[1] * 1e3,
-                           "fused_us_in_a_graph": gus * 1e3, "project_dims_us": pt[2] * 1e3,
-                           "materialized_us": mt[2] * 1e3, "rows_per_s": w1.n / (gus * 1e-3),
-                           "fused_speedup": mt[2] / (ft[2] + pt[2]),
-                           "note": "280 KB of traffic: bound by launch latency; fused_us is paced by the Python caller, "
-                                   "fused_us_in_a_graph (and rows_per_s) by the GPU (32 calls per graph)"}
+                           "fused_us_in_a_graph": gus * 1e3, "project_dims_us": pt[2] * 1e3, "project_dims_us_in_a_graph": gpus * 1e3,
+                           "materialized_us": mt[2] * 1e3, "materialized_us_in_a_graph": gmus * 1e3, "rows_per_s": w1.n / (gus * 1e-3),
+                           "fused_speedup": gmus / (gus + gpus), "fused_speedup_join_stage_alone": gmus / gus,
+                           "fused_speedup_at_the_python_callers_pace": mt[2] / (ft[2] + pt[2]),
+                           "note": "280 KB of traffic: bound by launch latency; the *_us figures are paced by the Python caller "
+                                   "(one call every 15-20 us whatever it launches), the *_in_a_graph ones, rows_per_s and "
+                                   "fused_speedup by the GPU (32 calls per graph)"}
         if do_cpu:
             out["fused_c1"]["cpu"] = cpu_predict(w1, w1.n, w1.n)
     if want("c1"):
