@@ -396,12 +396,16 @@ def main():
         t = time_call(gb, 60, 6)
         rt = time_call(lambda: gb(lq.LQ_REUSE_SIDE_TABLES), 60, 6)       # dimension side already encoded in ws
         survivors = int(counts.sum().item())
+        # the same calls recorded in a HIP graph (12 per graph, two turns over the copies): no gaps between the launches
+        gt = graph_time(gb, reps=2 * copies, iters=20, warmup=3)
+        grt = graph_time(lambda: gb(lq.LQ_REUSE_SIDE_TABLES), reps=2 * copies, iters=20, warmup=3)
         # floor of this call shape on this machine: one launch that only reads the 96 MB of key columns
         sink = torch.zeros(4, dtype=torch.int32, device=dev)
         keys = torch.cat([f.view(torch.uint8) for f in cols[0][0]])
         ft = time_call(lambda: lq.lq_yardstick_read(keys, 1, sink), 30, 5)
         out["groupby_c3"] = {"rows_per_s": g.n / (t[2] * 1e-3), "fact_rows": g.n, "groups": g.G, "surviving_rows": survivors,
                              **tstats(t), **tstats(rt, "reuse_side_tables_"),
+                             "ms_in_a_graph": gt, "reuse_side_tables_ms_in_a_graph": grt,
                              "launches_per_call": 3, "read_only_sweep_of_the_key_columns_ms": ft[2],
                              "roofline": hbm_roofline(20, g.n, t[2], traffic=measured_traffic("groupby_c3"),
                                                       frac_reuse_side_tables=20.0 * g.n / (rt[2] * 1e-3) / 1e9 / HBM_PEAK_GBPS,
