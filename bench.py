@@ -318,7 +318,13 @@ def main():
         ws = torch.empty(lq.lq_workspace_bytes(MAT, w.k, w.weights, chunk), dtype=torch.uint8, device=dev)
         Ym = torch.empty_like(Y)
         t = time_call(lambda: lq.lq_materialized_join_predict(w.X, w.dims, w.fks, w.weights, w.biases, Y=Ym, ws=ws), 5, 1)
-        out["materialized"] = {"rows_per_s": n / (t[0] * 1e-3), "chunk_rows": chunk, **tstats(t)}
+        # per row: X and keys in, the joined tuple T written and read back, the hidden layer written and read back, Y out
+        l1m = int(w.weights[0].shape[1])
+        bpr = 4 * (w.c_f + len(w.fks)) + 2 * 4 * w.k + 2 * 4 * l1m + 4 * int(w.weights[-1].shape[1])
+        out["materialized"] = {"rows_per_s": n / (t[0] * 1e-3), "chunk_rows": chunk, **tstats(t),
+                               "roofline": hbm_roofline(bpr, n, t[2], note="non-fused pipeline: materialise T, dense first layer, "
+                                                        "second layer; HBM bytes per row as listed in the source; its dense first "
+                                                        "layer also stands at the fp32 matrix rate")}
         if "stages" in out:
             out["materialized"]["fused_speedup"] = t[2] / (out["stages"]["fused_join_predict_ms_median"]
                                                           + out["stages"]["project_dims_ms_median"])
