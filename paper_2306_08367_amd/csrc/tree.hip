@@ -29,13 +29,34 @@ struct TreeArgs {
 
 // ---------------------------------------------------------------- pre-fusion --------------
 
-__global__ __launch_bounds__(256) void tree_target_kernel(TreeArgs t, uint8_t* target) {
-  const int j = blockIdx.x * blockDim.x + threadIdx.x;
-  if (j >= t.ld) return;
-  if (j >= t.l) { target[j] = 0xff; return; }
+// target[j] = number of nonzeros in column j of H (the length of leaf j's path).  A workgroup takes 64
+// leaves; its 16 wavefronts each count every 16th node (adjacent lanes read adjacent bytes of a row of
+// H) and the partial counts meet in LDS.
+constexpr int TT_THREADS = 1024;
+__global__ __launch_bounds__(TT_THREADS) void tree_target_kernel(TreeArgs t, uint8_t* target) {
+  __shared__ int part[TT_THREADS / 64][64];
+  const int lane = threadIdx.x & 63, slice = threadIdx.x >> 6;
+  const int j = blockIdx.x * 64 + lane;
   int cnt = 0;
-  for (int q = 0; q < t.p; ++q) cnt += t.H[static_cast<int64_t>(q) * t.l + j] != 0;
-  target[j] = static_cast<uint8_t>(min(cnt, 255));
+  if (j < t.l) {
+    int q = slice;
+    for (; q + 7 * (TT_THREADS / 64) < t.p; q += 8 * (TT_THREADS / 64)) {      // eight rows of H requested at a time
+      int8_t hv[8];
+#pragma unroll
+      for (int u = 0; u < 8; ++u) hv[u] = t.H[static_cast<int64_t>(q + u * (TT_THREADS / 64)) * t.l + j];
+#pragma unroll
+      for (int u = 0; u < 8; ++u) cnt += hv[u] != 0;
+    }
+    for (; q < t.p; q += TT_THREADS / 64) cnt += t.H[static_cast<int64_t>(q) * t.l + j] != 0;
+  }
+  part[slice][lane] = cnt;
+  __syncthreads();
+  if (slice == 0 && j < t.ld) {
+    int total = 0;
+#pragma unroll
+    for (int w = 0; w < TT_THREADS / 64; ++w) total += part[w][lane];
+    target[j] = j < t.l ? static_cast<uint8_t>(min(total, 255)) : 0xff;
+  }
 }
 
 // One thread per (dimension row, leaf), leaves fastest.  col_off / c: the dimension's columns in T.
@@ -159,33 +180,39 @@ constexpr int TP_MAXPATH = 255;     // list capacity per leaf (longer paths are 
 // The lists hold, per entry, the column within the dimension table (bit 31: the path wants the test
 // false) and the threshold; entry e of all leaves lies side by side, so the lanes of a wavefront
 // (lane = leaf) read neighbouring LDS words.
-__global__ __launch_bounds__(256) void tree_project_sparse_kernel(TreeArgs t, const float* __restrict__ D,
-                                                                  int64_t ldd, int64_t rows, int32_t col_off,
-                                                                  int32_t c, uint8_t* __restrict__ out,
-                                                                  int64_t rows_per_block) {
+constexpr int TPS_THREADS = 1024;   // a large workgroup builds its lists in two rounds of loads and then has 16 wavefronts of row work
+__global__ __launch_bounds__(TPS_THREADS) void tree_project_sparse_kernel(TreeArgs t, const float* __restrict__ D,
+                                                                          int64_t ldd, int64_t rows, int32_t col_off,
+                                                                          int32_t c, uint8_t* __restrict__ out,
+                                                                          int64_t rows_per_block, int32_t col_tiles) {
   __shared__ unsigned int ent[TP_MAXPATH][TP_COLS];
   __shared__ float thr_l[TP_MAXPATH][TP_COLS];
   __shared__ int count[TP_COLS];
   const int tid = threadIdx.x;
-  const int j0 = blockIdx.x * TP_COLS;
+  // Workgroups are dealt to the eight XCDs in turn (blockIdx.x % 8).  The 16 column tiles that share a
+  // 128-byte line of an output row should meet in one L2, so each XCD takes a contiguous eighth of the tiles.
+  int tile = blockIdx.x;
+  if (col_tiles % 8 == 0) tile = (blockIdx.x % 8) * (col_tiles / 8) + blockIdx.x / 8;
+  const int j0 = tile * TP_COLS;
   const int64_t r0 = static_cast<int64_t>(blockIdx.y) * rows_per_block;
   const int64_t r1 = min(rows, r0 + rows_per_block);
   if (tid < TP_COLS) count[tid] = 0;
   __syncthreads();
   {
+    constexpr int QS = TPS_THREADS / TP_COLS;             // nodes covered by one round of the workgroup
     const int j = tid % TP_COLS;
     if (j0 + j < t.l)
-      for (int q0 = tid / TP_COLS; q0 < t.p; q0 += 8 * (256 / TP_COLS)) {   // eight entries of H requested at a time
+      for (int q0 = tid / TP_COLS; q0 < t.p; q0 += 8 * QS) {   // eight entries of H requested at a time
         int hv[8];
 #pragma unroll
         for (int u = 0; u < 8; ++u) {
-          const int q = q0 + u * (256 / TP_COLS);
+          const int q = q0 + u * QS;
           hv[u] = q < t.p ? t.H[static_cast<int64_t>(q) * t.l + j0 + j] : 0;
         }
 #pragma unroll
         for (int u = 0; u < 8; ++u) {
           if (hv[u] == 0) continue;
-          const int q = q0 + u * (256 / TP_COLS);
+          const int q = q0 + u * QS;
           const int f = t.feature[q] - col_off;
           if (f < 0 || f >= c) continue;                     // node owned by another table
           const int slot = atomicAdd(&count[j], 1);
@@ -198,7 +225,7 @@ __global__ __launch_bounds__(256) void tree_project_sparse_kernel(TreeArgs t, co
   }
   __syncthreads();
   const int64_t total = (r1 - r0) * TP_COLS;
-  for (int64_t idx = tid; idx < total; idx += 256) {
+  for (int64_t idx = tid; idx < total; idx += TPS_THREADS) {
     const int64_t r = r0 + idx / TP_COLS;
     const int j = static_cast<int>(idx % TP_COLS);
     if (j0 + j >= t.ld) continue;
@@ -1152,12 +1179,13 @@ int project_slices(const TreeArgs& t, const DimSlice* sl, int n, hipStream_t s) 
     if (t.p <= 0x7fff) {   // beyond 4 mask words per leaf the per-leaf node lists are as fast or faster (measured up to 16 words)
       const int64_t col_tiles = (t.ld + TP_COLS - 1) / TP_COLS;
       // enough row slices to fill the GPU, each long enough to amortise building the lists
-      int64_t slices = std::max<int64_t>(1, std::min<int64_t>((static_cast<int64_t>(num_cus()) * 4 + col_tiles - 1) / col_tiles,
+      int64_t slices = std::max<int64_t>(1, std::min<int64_t>((static_cast<int64_t>(num_cus()) * 2 + col_tiles - 1) / col_tiles,
                                                               (d.rows + 255) / 256));
       slices = std::min<int64_t>(slices, 65535);
       const int64_t rpb = (d.rows + slices - 1) / slices;
       hipLaunchKernelGGL(tree_project_sparse_kernel, dim3(static_cast<unsigned>(col_tiles), static_cast<unsigned>(slices)),
-                         dim3(256), 0, s, t, d.D, d.ldd, d.rows, d.col_off, d.cols, d.out, rpb);
+                         dim3(TPS_THREADS), 0, s, t, d.D, d.ldd, d.rows, d.col_off, d.cols, d.out, rpb,
+                         static_cast<int32_t>(col_tiles));
       LQ_LAUNCH_CHECK("tree_project_sparse_kernel");
     } else {
       const int64_t total = d.rows * t.ld;
@@ -1213,7 +1241,7 @@ int lq_tree_project_dims(const lq_star* star, const lq_tree* tree, void* const* 
   for (int k = 0; k < star->n_dims; ++k)
     if (!tables[k] || !aligned(tables[k], 16)) return fail(LQ_ERR_NULL, "tables[%d] is NULL or not 16-byte aligned", k);
   hipStream_t s = static_cast<hipStream_t>(hip_stream);
-  hipLaunchKernelGGL(tree_target_kernel, dim3(static_cast<unsigned>((t.ld + 255) / 256)), dim3(256), 0, s, t, target);
+  hipLaunchKernelGGL(tree_target_kernel, dim3(static_cast<unsigned>((t.ld + 63) / 64)), dim3(TT_THREADS), 0, s, t, target);
   LQ_LAUNCH_CHECK("tree_target_kernel");
   DimSlice sl[LQ_MAX_DIMS];
   int32_t off = star->fact.cols;
