@@ -447,3 +447,25 @@ def test_incremental_prefusion_refreshes_only_the_given_rows(lq):
         assert_close(P[1], Pw[1], TOL_F32, "refreshed table")
         with pytest.raises(lq.LQError):
             lq.lq_project_dim_rows(w.dims, w.weights[0], w.c_f, P, 1, rows[1] - 5, 6)
+
+
+@pytest.mark.parametrize("shape", [
+    # name, fact rows, fact columns, dimension rows, dimension columns, layers, bias
+    ("tall_k100_64_1", 300_007, 4, (1_000, 10_000, 500), (32, 32, 32), (64, 1), True),
+    ("tall_k37_40", 280_001, 5, (300, 200), (16, 16), (40,), False),          # k and the width not multiples of 4
+    ("tall_k255_17_3", 270_013, 0, (400, 300, 200), (85, 85, 85), (17, 3), True),
+], ids=lambda s: s[0])
+def test_non_fused_first_layer_over_many_rows(lq, shape):
+    """The non-fused pipeline with all rows in one chunk (a few hundred thousand rows, at most 64 columns, short k:
+    thousands of tiles of the dense first layer in one launch); compared with the oracle on a row sample that holds
+    both ends and a stride through the middle."""
+    name, n, c_f, rows, cols, layers, bias = shape
+    w = WL.make_predict(name, n, c_f, rows, cols, layers, seed=WL.SEED0 + 700 + len(name), device="cuda",
+                        w_sigma=[1.0 / np.sqrt(c_f + sum(cols))] + [1.0 / np.sqrt(a) for a in layers[:-1]], bias=bias)
+    Ym = lq.lq_materialized_join_predict(w.X, w.dims, w.fks, w.weights, w.biases, chunk_rows=n)
+    torch.cuda.synchronize()
+    sample = torch.cat([torch.arange(0, 4_096), torch.arange(4_096, n - 4_096, 257), torch.arange(n - 4_096, n)])
+    sub = WL.take_rows(w, sample.to("cuda"))
+    want = O.join_predict(None if sub.X is None else sub.X.cpu(), cpu_list(sub.dims), cpu_list(sub.fks), cpu_list(sub.weights),
+                          cpu_list(sub.biases), nthreads=16)
+    assert_close(Ym[sample.to("cuda")], want, TOL_F32, f"{name}: non-fused, one chunk")
