@@ -67,6 +67,33 @@ def test_random_stars_and_models(lq):
             assert_close(Ym, want, tol, f"non-fused, {desc}")
 
 
+def test_random_deeper_models(lq):
+    """fp32 models of two to six layers with first layers of 20 .. 256 columns on one to eight tables: the shapes of the
+    matrix-core kernel (one or two column parts, one to four tables prefetched and up to four more gathered inside
+    the step, up to 64 fact columns, later layers up to 128 wide)."""
+    first = [20, 24, 32, 36, 48, 64, 72, 100, 128, 132, 200, 256]
+    later = [1, 2, 3, 4, 5, 8, 16, 17, 24, 33, 48, 64, 100, 128]
+    for seed in _seeds(7, 400):
+        r = np.random.default_rng(seed)
+        K = int(r.integers(1, 9))
+        c_f = int(r.choice([0, 0, 1, 3, 4, 5, 8, 9, 12, 16, 20, 33, 64]))
+        rows = [int(r.integers(1, 400)) for _ in range(K)]
+        cols = [int(r.integers(1, 12)) for _ in range(K)]
+        nl = int(r.integers(2, 7))
+        layers = [int(r.choice(first))] + [int(r.choice(later)) for _ in range(nl - 1)]
+        n = int(r.choice([1, 15, 16, 17, 63, 64, 65, 255, 1000, 4097]))
+        k = c_f + sum(cols)
+        sig = [1.0 / np.sqrt(max(k, 1))] + [1.4 / np.sqrt(a) for a in layers[:-1]]
+        desc = f"seed={seed} n={n} c_f={c_f} rows={rows} cols={cols} layers={layers}"
+        w = WL.make_predict("random_deep", n, c_f, rows, cols, layers, seed=seed, w_sigma=sig, bias=bool(r.integers(0, 2)))
+        want = O.join_predict(w.X, w.dims, w.fks, w.weights, w.biases, nthreads=8)
+        w = to_dev(w)
+        P = lq.lq_project_dims(w.dims, w.weights[0], w.c_f)
+        Y = lq.lq_fused_join_predict(w.X, w.fks, P, w.weights, w.biases)
+        torch.cuda.synchronize()
+        assert_close(Y, want, TOL_F32, f"fused, {desc}")
+
+
 def test_random_models_on_one_or_two_fact_rows_are_exact_on_small_integers(lq):
     for seed in _seeds(7, 100):
         r = np.random.default_rng(seed)
