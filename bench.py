@@ -14,7 +14,7 @@ Prints ONE JSON line.  Besides the contract fields it carries
                   gathers: the measured roofs the per-configuration cells are quoted against
   one cell per configuration / leg (each event-timed on the launch stream: mean, median and min; the
   non-fused pipeline beside the fused one; the CPU oracle at 1 thread and at all threads under "cpu")
-  summary       - last key: the five named configurations in a few numbers each
+  summary       - right after the contract's keys: the five named configurations in a few numbers each
 """
 from __future__ import annotations
 
@@ -833,7 +833,13 @@ def main():
             "host_threads_used_by_the_oracle": cpu_threads() if do_cpu else None,
         }
 
-    print(json.dumps(out))
+    # the contract's keys and the per-configuration summary first (a reader that keeps only the head of the line still
+    # has every headline figure), the detailed cells after them
+    head = ("metric", "value", "unit", "n_gpus", "steps", "warmup", "ms_per_step", "higher_is_better", "scaling", "vs_baseline",
+            "dtype", "data", "config", "roofline", "cpu_baseline", "summary")
+    ordered = {k: out[k] for k in head if k in out}
+    ordered.update({k: v for k, v in out.items() if k not in ordered})
+    print(json.dumps(ordered))
 
 
 if __name__ == "__main__":
