@@ -430,7 +430,7 @@ def main():
         nm = 6_000_000
         cells = {}
         for name, rows, card, sel in (("three_attributes_25x25x250_selective", (2_556, 30_000, 2_000, 200_000), (25, 25, 250, 1), (None, 0.2, None, 0.12)),
-                                      ("three_attributes_25x25x250_all_rows", (2_556, 30_000, 2_000, 200_000), (25, 25, 250, 1), None),
+                                      ("three_attributes_25x25x250_all_rows", (2_556, 30_000, 2_000, 200_000), (25, 25, 250, 1), (None, None, None, 1.0)),
                                       ("two_attributes_250x250_selective", (2_556, 30_000, 2_000, 200_000), (250, 250, 1, 1), (None, None, 0.2, 0.12))):
             gen = torch.Generator(device=dev); gen.manual_seed(WL.SEED0 + 970)
             fks = [torch.randint(0, r, (nm,), generator=gen, device=dev, dtype=torch.int32) for r in rows]
@@ -439,16 +439,22 @@ def main():
                      for k in range(len(rows))]
             meas = [torch.randint(1, 100_001, (nm,), generator=gen, device=dev, dtype=torch.int32)]
             G = math.prod(card)
-            ws = torch.empty(lq.lq_groupby_workspace_bytes(rows, card, 1), dtype=torch.uint8, device=dev)
+            small = lq.lq_groupby_workspace_bytes(rows, card, 1)
+            big = lq.lq_groupby_bucket_workspace_bytes(nm, rows, card, 1)
+            ws = torch.empty(max(small, big), dtype=torch.uint8, device=dev)
             sums = torch.empty((1, G), dtype=torch.int64, device=dev)
             counts = torch.empty((G,), dtype=torch.int64, device=dev)
             t = time_call(lambda: lq.lq_masked_groupby_sum(fks, rows, masks, codes, card, None, meas, sums=sums, counts=counts, ws=ws), 20, 3)
+            at = time_call(lambda: lq.lq_masked_groupby_sum(fks, rows, masks, codes, card, None, meas, sums=sums, counts=counts,
+                                                            ws=ws[:small]), 20, 3)
             cells[name] = {"groups": G, "surviving_rows": int(counts.sum().item()), "rows_per_s": nm / (t[2] * 1e-3), **tstats(t),
+                           "through_atomics_ms": at[2], "workspace_MB": max(small, big) / 1e6, "workspace_for_atomics_MB": small / 1e6,
                            "roofline": hbm_roofline(20, nm, t[2])}
         out["groupby_many_groups"] = {"fact_rows": nm, "cells": cells,
-                                      "note": "above 8,192 accumulators the output arrays accumulate through device-wide 64-bit atomics "
-                                              "(about 2.3e10 per second on this GPU): selective queries stay near the LDS form, "
-                                              "queries where every row survives are bound by the atomics"}
+                                      "note": "above 8,192 accumulators: with the large workspace survivors are sorted into buckets of "
+                                              "neighbouring groups and each bucket is added up in LDS by the workgroup that owns it "
+                                              "(ms); with the small one the output arrays accumulate through device-wide 64-bit atomics, "
+                                              "about 2.3e10 per second on this GPU (through_atomics_ms)"}
     if want("groupby_many"):
         guarded("groupby_many_groups", leg_groupby_many)
 

@@ -213,7 +213,10 @@ int lq_materialized_join_predict(const lq_star* star, const lq_model* model, lq_
  *              <= 8192 every scan workgroup keeps private accumulators in LDS; above that (the
  *              multi-column group-by of Section 2.4.2 multiplies cardinalities) the output arrays
  *              themselves are the accumulators, cleared by the call and updated with device-wide
- *              64-bit atomics -- same results either way
+ *              64-bit atomics, or - when ws_bytes is at least lq_groupby_bucket_workspace_bytes(..) -
+ *              the surviving rows are first sorted into buckets of neighbouring groups in the workspace
+ *              and each bucket is then added up in LDS by the one workgroup that owns its groups
+ *              (several times faster when many rows survive) -- same results every way
  *   fact_mask  uint8 [n] or NULL
  *   measures   host array of n_measures (1..LQ_MAX_MEASURES) device pointers, int32 [n]
  *   sums       int64 [n_measures x G], overwritten;  counts int64 [G] or NULL
@@ -299,6 +302,12 @@ size_t lq_workspace_bytes(int which_call, const lq_star* star, const lq_model* m
                           int64_t chunk_rows);
 size_t lq_groupby_workspace_bytes(int32_t n_dims, const int64_t* dim_rows,
                                   const int32_t* group_card, int32_t n_measures);
+/* Workspace with which lq_masked_groupby_sum over n_fact rows and more than 8,192 accumulators takes the
+ * bucketed form (see group_card above): the size above plus two slots of 4 (1 + n_measures) bytes per fact
+ * row and a little per bucket.  0 when that form does not apply (8,192 accumulators or fewer, more than two
+ * measures, 2^31 rows or more, more than 8,192 buckets); the call then works with the smaller workspace. */
+size_t lq_groupby_bucket_workspace_bytes(int64_t n_fact, int32_t n_dims, const int64_t* dim_rows,
+                                         const int32_t* group_card, int32_t n_measures);
 
 /* ---------------------------------------------------------------------------------------
  * Decision trees (Section 3.3).  The tree is given in the matrix form of Section 3.3.1:

@@ -7,7 +7,7 @@ into its C interface.  There is no fallback: without the library, importing
 """
 from .binding import (  # noqa: F401
     LQ_CHECK_FKS, LQ_REUSE_SIDE_TABLES, LQ_FORCE_GENERIC, LQ_FORCE_TILE, LQError, lib_path, lq_fused_join_predict,
-    lq_groupby_workspace_bytes, lq_last_error, lq_masked_groupby_sum,
+    lq_groupby_workspace_bytes, lq_groupby_bucket_workspace_bytes, lq_last_error, lq_masked_groupby_sum,
     lq_materialized_join_predict, lq_project_dims, lq_stream_copy, lq_version,
     lq_workspace_bytes, lq_tree_table_ld, lq_tree_project_dims, lq_fused_join_tree,
     lq_materialized_join_tree, lq_tree_mask_words, lq_tree_compress_tables, lq_tree_project_dim_rows, lq_tree_fact_mask_bytes, lq_tree_fact_masks, lq_fused_join_tree_masks, LQ_CHECK_KEYS, lq_keymap_bytes, lq_keymap_build, lq_keymap_insert,

@@ -104,6 +104,8 @@ def _load():
     lib.lq_workspace_bytes.restype = sz
     lib.lq_groupby_workspace_bytes.argtypes = [i32, ctypes.POINTER(i64), ctypes.POINTER(i32), i32]
     lib.lq_groupby_workspace_bytes.restype = sz
+    lib.lq_groupby_bucket_workspace_bytes.argtypes = [i64, i32, ctypes.POINTER(i64), ctypes.POINTER(i32), i32]
+    lib.lq_groupby_bucket_workspace_bytes.restype = sz
     lib.lq_stream_copy.argtypes = [vp, vp, sz, vp]
     lib.lq_group_avg.argtypes = [i32, i64, vp, vp, vp, vp]
     lib.lq_group_avg.restype = ctypes.c_int
@@ -366,6 +368,14 @@ def lq_groupby_workspace_bytes(dim_rows: Sequence[int], group_card: Sequence[int
     return int(_lib.lq_groupby_workspace_bytes(K, rows, card, n_measures))
 
 
+def lq_groupby_bucket_workspace_bytes(n_fact: int, dim_rows: Sequence[int], group_card: Sequence[int], n_measures: int) -> int:
+    """Workspace that lets a group-by over more than 8,192 accumulators take the bucketed form (0: does not apply)."""
+    K = len(dim_rows)
+    rows = (ctypes.c_int64 * max(1, K))(*[int(r) for r in dim_rows])
+    card = (ctypes.c_int32 * max(1, K))(*[int(c) for c in group_card])
+    return int(_lib.lq_groupby_bucket_workspace_bytes(int(n_fact), K, rows, card, n_measures))
+
+
 def lq_masked_groupby_sum(fks: Sequence[torch.Tensor], dim_rows: Sequence[int],
                           dim_mask: Optional[Sequence[Optional[torch.Tensor]]],
                           dim_code: Optional[Sequence[Optional[torch.Tensor]]],
@@ -405,8 +415,10 @@ def lq_masked_groupby_sum(fks: Sequence[torch.Tensor], dim_rows: Sequence[int],
     if counts is None and want_counts:
         counts = _empty(stream, (G,), dtype=torch.int64, device=dev)
     if ws is None:
-        ws = _empty(stream, lq_groupby_workspace_bytes(dim_rows, group_card, len(measures)),
-                         dtype=torch.uint8, device=dev)
+        eff_card = [int(group_card[k]) if codes[k] is not None else 1 for k in range(K)]
+        ws = _empty(stream, max(lq_groupby_workspace_bytes(dim_rows, group_card, len(measures)),
+                                lq_groupby_bucket_workspace_bytes(n, dim_rows, eff_card, len(measures))),
+                    dtype=torch.uint8, device=dev)
     rows = (ctypes.c_int64 * max(1, K))(*[int(r) for r in dim_rows])
     card = (ctypes.c_int32 * max(1, K))(*[int(c) for c in group_card])
     _check(_lib.lq_masked_groupby_sum(

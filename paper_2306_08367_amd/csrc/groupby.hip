@@ -21,7 +21,8 @@
 
 namespace lq {
 
-int launch_fast_many(const FastArgs& a, const FastLaunch& L);   // groupby_many.hip
+int launch_fast_many(const FastArgs& a, const FastLaunch& L);     // groupby_many.hip
+int launch_fast_bucket(const FastArgs& a, const FastLaunch& L);   // groupby_many.hip
 int launch_agg_fast(const GbArgs& a, const AggFastArgs& x, const FastLaunch& L, int n_preds, int pack_here);   // groupby_agg_fast.hip
 
 namespace {
@@ -599,6 +600,34 @@ size_t groupby_ws_bytes(int32_t K, const int64_t* rows, int64_t n_acc) {
          round_up(static_cast<size_t>(groupby_max_workgroups()) * n_acc * 8, 256);
 }
 
+// Geometry of the bucketed many-groups form for n fact rows: false when it does not apply.
+//   shift   a bucket covers 1 << shift neighbouring groups, whose (M + 1) accumulators each fit LDS
+//   buckets at least 256 where G allows (one workgroup per bucket in the second pass), at most 8,192
+//   cap     slots per bucket: twice the even share plus 1,024 (a bucket that overflows sends the rest through atomics)
+bool bucket_plan(int64_t n, int64_t G, int32_t M, BucketArgs* b, size_t* bytes) {
+  if (M < 1 || M > 2 || n < 1 || n > 0x7fffffffLL) return false;           // (the specialised scans take one or two measures)
+  if ((M + 1) * G <= GROUPBY_LDS_ACCUMULATORS) return false;
+  int shift = 0;
+  while ((int64_t{2} << shift) * (M + 1) <= GROUPBY_LDS_ACCUMULATORS && (int64_t{2} << shift) * 256 <= G) ++shift;
+  const int64_t buckets = (G + (int64_t{1} << shift) - 1) >> shift;
+  if (buckets > 8192) return false;
+  const int64_t cap = 2 * ((n + buckets - 1) / buckets) + 1024;
+  if (cap > 0x7fffffffLL) return false;
+  b->shift = shift;
+  b->buckets = static_cast<int32_t>(buckets);
+  b->cap = static_cast<uint32_t>(cap);
+  *bytes = round_up(static_cast<size_t>(buckets) * 4, 256) + static_cast<size_t>(buckets) * cap * (1 + M) * 4;
+  return true;
+}
+
+// Workspace that lets a group-by of n rows over more than 8,192 accumulators take the bucketed form (0: it does not apply).
+size_t groupby_bucket_ws_bytes(int64_t n, int32_t K, const int64_t* rows, int64_t G, int32_t M) {
+  BucketArgs b{};
+  size_t extra = 0;
+  if (!bucket_plan(n, G, M, &b, &extra)) return 0;
+  return round_up(groupby_ws_bytes(K, rows, G * (M + 1)), 256) + extra;
+}
+
 int launch_group_avg(int32_t M, int64_t G, const int64_t* sums, const int64_t* counts, double* avgs, hipStream_t s) {
   const int64_t MG = static_cast<int64_t>(M) * G;
   if (MG == 0) return LQ_OK;
@@ -610,10 +639,12 @@ int launch_group_avg(int32_t M, int64_t G, const int64_t* sums, const int64_t* c
 }
 
 // sums / counts = 0, mins / maxs = neutral elements, for the accumulators-in-memory form.
-static int launch_init_outputs(const GlobalOut& o, int32_t M, int32_t G, hipStream_t s) {
+static int launch_init_outputs(const GlobalOut& o, int32_t M, int32_t G, hipStream_t s, unsigned int* words = nullptr,
+                               int64_t n_words = 0) {
   const int64_t MG = std::max<int64_t>(static_cast<int64_t>(M) * G, G);
   const int64_t blocks = std::max<int64_t>(1, std::min<int64_t>((MG + 255) / 256, static_cast<int64_t>(num_cus()) * 8));
-  hipLaunchKernelGGL(init_outputs_kernel, dim3(static_cast<unsigned>(blocks)), dim3(256), 0, s, o, MG, static_cast<int64_t>(G));
+  hipLaunchKernelGGL(init_outputs_kernel, dim3(static_cast<unsigned>(blocks)), dim3(256), 0, s, o, MG, static_cast<int64_t>(G),
+                     words, n_words);
   LQ_LAUNCH_CHECK("init_outputs_kernel");
   return LQ_OK;
 }
@@ -669,7 +700,7 @@ static int launch_scan_global(const GbArgs& a, const AggExtra& x, const GlobalOu
 int launch_groupby(int64_t n, int32_t K, const int32_t* const* fks, const int64_t* rows,
                    const uint8_t* const* mask, const int32_t* const* code, const int32_t* card,
                    const uint8_t* fact_mask, int32_t M, const int32_t* const* meas, int64_t* sums,
-                   int64_t* counts, int32_t G, void* ws, bool reuse_tables, hipStream_t s) {
+                   int64_t* counts, int32_t G, void* ws, size_t ws_bytes, bool reuse_tables, hipStream_t s) {
   GbArgs a{};
   a.n = n; a.K = K; a.fact_mask = fact_mask; a.M = M; a.G = G;
   a.sums = reinterpret_cast<unsigned long long*>(sums);
@@ -706,7 +737,22 @@ int launch_groupby(int64_t n, int32_t K, const int32_t* const* fks, const int64_
   const int cus = num_cus();
   int rc0;
   const GlobalOut gout{a.sums, a.counts, nullptr, nullptr};
-  if (gacc && (rc0 = launch_init_outputs(gout, M, G, s))) return rc0;
+  // many groups: through buckets when the specialised scan applies and the caller's workspace has room for them
+  // (their counters are cleared with the outputs), else through atomics
+  BucketArgs bucket{};
+  bool want_buckets = false;
+  if (gacc && vec_ok && !fact_mask && n > 0) {
+    size_t extra = 0;
+    const size_t base = round_up(groupby_ws_bytes(K, rows, static_cast<int64_t>(M + 1) * G), 256);
+    if (bucket_plan(n, G, M, &bucket, &extra) && ws_bytes >= base + extra &&
+        round_up(lds_prefix, 16) + static_cast<size_t>(bucket.buckets) * 8 <= LDS_BUDGET) {
+      want_buckets = true;
+      bucket.gcount = reinterpret_cast<unsigned int*>(static_cast<uint8_t*>(ws) + base);
+      bucket.pairs = reinterpret_cast<uint32_t*>(static_cast<uint8_t*>(ws) + base + round_up(static_cast<size_t>(bucket.buckets) * 4, 256));
+    }
+  }
+  if (gacc && (rc0 = launch_init_outputs(gout, M, G, s, want_buckets ? bucket.gcount : nullptr, want_buckets ? bucket.buckets : 0)))
+    return rc0;
   if (!reuse_tables && (n > 0 || !gacc) && (rc0 = launch_pack(a, s))) return rc0;
   if (n == 0) {   // nothing to scan: the fold alone writes the all-zero result
     if (gacc) return LQ_OK;
@@ -753,8 +799,18 @@ int launch_groupby(int64_t n, int32_t K, const int32_t* const* fks, const int64_
       f.gcounts = gacc ? a.counts : nullptr;
       for (int m = 0; m < M; ++m) f.meas[m] = meas[m];
       L.lds = acc_bytes + lds_prefix; L.s = s; L.M = M;
+      const bool buckets = want_buckets;
+      if (buckets) {
+        L.bucket = bucket;
+        L.lds = round_up(lds_prefix, 16) + static_cast<size_t>(bucket.buckets) * 8;
+      }
       slices(L.lds, &L.blocks, &L.per_block);
-      const int rc = gacc ? launch_fast_many(f, L) : launch_fast<false>(f, L);
+      int rc = gacc ? (buckets ? launch_fast_bucket(f, L) : launch_fast_many(f, L)) : launch_fast<0>(f, L);
+      if (rc == -1 && buckets) {                     // no bucketed instantiation for this mix: the atomic form
+        L.lds = acc_bytes + lds_prefix;
+        slices(L.lds, &L.blocks, &L.per_block);
+        rc = launch_fast_many(f, L);
+      }
       if (rc > 0) return rc;
       if (rc == 0) {
         if (gacc) return LQ_OK;

@@ -73,7 +73,19 @@ struct AggFastArgs {
   int32_t minmax;             // MIN / MAX wanted (otherwise their accumulators keep the neutral elements)
 };
 
-struct FastLaunch { unsigned blocks; size_t lds; int64_t per_block; hipStream_t s; int nbl, nml, nmg, nbg, M; };
+// Many groups, second form: survivors are first sorted into buckets of neighbouring groups (a bucket's
+// accumulators fit LDS), then one workgroup per bucket adds its bucket up in LDS and is the only writer of
+// its groups.  A survivor costs one LDS atomic and one 8- or 12-byte store instead of two or three device-wide
+// atomics; what does not fit a bucket's slots (skewed groups) goes the atomic way.
+struct BucketArgs {
+  unsigned int* gcount;      // [buckets] survivors sent to each bucket so far (may pass `cap`: the excess took the atomics)
+  uint32_t* pairs;           // [buckets][cap][1 + measures]: group number inside the bucket, then the measures
+  int32_t buckets;
+  int32_t shift;             // bucket = group >> shift
+  uint32_t cap;              // slots per bucket
+};
+
+struct FastLaunch { unsigned blocks; size_t lds; int64_t per_block; hipStream_t s; int nbl, nml, nmg, nbg, M; BucketArgs bucket; };
 
 namespace {
 
@@ -211,8 +223,10 @@ __device__ __forceinline__ void merge_and_add(bool alive, int32_t g, const long 
 
 // sums / counts = 0, mins / maxs = their neutral elements (a fill kernel rather than a memset, so that
 // callers may record the call into a HIP graph).
-__global__ __launch_bounds__(256) void init_outputs_kernel(GlobalOut o, int64_t MG, int64_t G) {
+// `words` (may be NULL): n_words 32-bit counters cleared by the same launch (the bucket counters).
+__global__ __launch_bounds__(256) void init_outputs_kernel(GlobalOut o, int64_t MG, int64_t G, unsigned int* words, int64_t n_words) {
   const int64_t stride = static_cast<int64_t>(gridDim.x) * blockDim.x;
+  for (int64_t i = static_cast<int64_t>(blockIdx.x) * blockDim.x + threadIdx.x; i < n_words; i += stride) words[i] = 0u;
   for (int64_t i = static_cast<int64_t>(blockIdx.x) * blockDim.x + threadIdx.x; i < MG; i += stride) {
     if (o.sums) o.sums[i] = 0ull;
     if (o.mins) o.mins[i] = AGG_MIN_INIT;
@@ -415,52 +429,237 @@ __global__ __launch_bounds__(SCAN_THREADS) void scan_fast_mem_kernel(FastArgs a,
   }
 }
 
-template <bool MEM, int NBL, int NML, int NMG, int NBG, int MM>
-int launch_fast_inst(const FastArgs& a, const FastLaunch& L) {
-  auto kernel = MEM ? &scan_fast_mem_kernel<NBL, NML, NMG, NBG, MM> : &scan_fast_kernel<NBL, NML, NMG, NBG, MM>;
-  if (L.lds > 64 * 1024)
-    LQ_HIP_TRY(hipFuncSetAttribute(reinterpret_cast<const void*>(kernel),
-                                   hipFuncAttributeMaxDynamicSharedMemorySize, static_cast<int>(L.lds)));
-  hipLaunchKernelGGL(kernel, dim3(L.blocks), dim3(SCAN_THREADS), L.lds, L.s, a, L.per_block);
-  LQ_LAUNCH_CHECK("scan_fast_kernel");
-  return LQ_OK;
+// First pass of the bucketed form.  Per round of the workgroup (up to 8 rows per thread): every survivor takes a
+// rank inside its bucket from an LDS counter; one thread per bucket with survivors reserves that many slots
+// of the bucket with one device-wide atomic; the survivors are then written to their slots.  Every thread
+// of the workgroup takes the same number of steps (the barriers are inside the loop); lanes past the end
+// carry keys of -1.  gcount is zero and the outputs are cleared before the launch.
+template <int NBL, int NML, int NMG, int NBG, int MM>
+__global__ __launch_bounds__(SCAN_THREADS) void scan_fast_bucket_kernel(FastArgs a, BucketArgs b, int64_t per_block) {
+  extern __shared__ __align__(16) uint8_t smem[];
+  constexpr int ND = NBL + NML + NMG + NBG;
+  uint8_t* tab = smem;
+  unsigned int* lcount = reinterpret_cast<unsigned int*>(smem + round_up(static_cast<size_t>(a.lds_bytes), 16));
+  unsigned int* lbase = lcount + b.buckets;
+  const int tid = threadIdx.x;
+  const GlobalOut gout{a.gsums, a.gcounts, nullptr, nullptr};
+
+  const int64_t n_vec = a.n / 4;
+  const int64_t v_begin = static_cast<int64_t>(blockIdx.x) * per_block;
+  const int64_t v_end = min(n_vec, v_begin + per_block);
+  const int64_t steps = v_begin < v_end ? (v_end - v_begin + SCAN_THREADS - 1) / SCAN_THREADS : 0;
+  int64_t v = v_begin + tid;
+  const v4i none = {-1, -1, -1, -1};
+  v4i cur[ND], nxt[ND];
+#pragma unroll
+  for (int k = 0; k < ND; ++k)
+    cur[k] = v < v_end ? __builtin_nontemporal_load(reinterpret_cast<const v4i*>(a.fk[k]) + v) : none;
+  {
+    const uint4* src = reinterpret_cast<const uint4*>(a.packed);
+    uint4* dst = reinterpret_cast<uint4*>(tab);
+    for (uint32_t i = tid; i < a.lds_bytes / 16; i += SCAN_THREADS) dst[i] = src[i];
+  }
+  for (int i = tid; i < b.buckets; i += SCAN_THREADS) lcount[i] = 0u;
+  __syncthreads();
+
+  // A round is up to NS steps (4 NS rows per thread): their survivors stay in registers until the round's
+  // slots are reserved, so that the two barriers and the reservation are paid once per 4 NS rows.
+  constexpr int NS = 2;
+  for (int64_t st0 = 0; st0 < steps; st0 += NS) {
+    int32_t g[NS][4];
+    int32_t val[NS][4][MM];
+    unsigned int rank[NS][4];
+    unsigned int alive_bits = 0u;                   // bit 4 s + q: row q of step s survives
+#pragma unroll
+    for (int s = 0; s < NS; ++s) {
+      if (st0 + s < steps) {                        // (the same for the whole workgroup)
+        const int64_t vn = v + SCAN_THREADS;
+#pragma unroll
+        for (int k = 0; k < ND; ++k)
+          nxt[k] = vn < v_end ? __builtin_nontemporal_load(reinterpret_cast<const v4i*>(a.fk[k]) + vn) : none;
+        bool alive[4];
+#pragma unroll
+        for (int q = 0; q < 4; ++q) {
+          int32_t j[ND];
+#pragma unroll
+          for (int k = 0; k < ND; ++k) j[k] = cur[k][q];
+          g[s][q] = 0;
+          alive[q] = true;
+          classify_fast<NBL, NML, NMG, NBG>(a, tab, j, alive[q], g[s][q]);
+        }
+        const bool any = alive[0] || alive[1] || alive[2] || alive[3];
+#pragma unroll
+        for (int m = 0; m < MM; ++m) {              // measure columns are only touched where a lane has a survivor
+          const v4i t = any ? *(reinterpret_cast<const v4i*>(a.meas[m]) + v) : none;
+#pragma unroll
+          for (int q = 0; q < 4; ++q) val[s][q][m] = t[q];
+        }
+#pragma unroll
+        for (int q = 0; q < 4; ++q) {
+          rank[s][q] = alive[q] ? atomicAdd(&lcount[g[s][q] >> b.shift], 1u) : 0u;
+          alive_bits |= alive[q] ? 1u << (4 * s + q) : 0u;
+        }
+#pragma unroll
+        for (int k = 0; k < ND; ++k) cur[k] = nxt[k];
+        v = vn;
+      }
+    }
+    __syncthreads();
+    for (int i = tid; i < b.buckets; i += SCAN_THREADS) {
+      const unsigned int c = lcount[i];
+      if (c) { lbase[i] = atomicAdd(&b.gcount[i], c); lcount[i] = 0u; }
+    }
+    __syncthreads();
+#pragma unroll
+    for (int s = 0; s < NS; ++s)
+#pragma unroll
+      for (int q = 0; q < 4; ++q) {
+        bool over = false;
+        if ((alive_bits >> (4 * s + q)) & 1u) {
+          const int bk = g[s][q] >> b.shift;
+          const unsigned int pos = lbase[bk] + rank[s][q];
+          if (pos < b.cap) {
+            uint32_t* dst = b.pairs + (static_cast<size_t>(bk) * b.cap + pos) * (1 + MM);
+            dst[0] = static_cast<uint32_t>(g[s][q] & ((1 << b.shift) - 1));
+#pragma unroll
+            for (int m = 0; m < MM; ++m) dst[1 + m] = static_cast<uint32_t>(val[s][q][m]);
+          } else {
+            over = true;
+          }
+        }
+        if (__ballot(over) != 0ull) {                // rare: a bucket is full, the rest of it takes the atomics
+          long long wide[MM];
+#pragma unroll
+          for (int m = 0; m < MM; ++m) wide[m] = val[s][q][m];
+          merge_and_add<MM>(over, g[s][q], wide, MM, a.G, gout);
+        }
+      }
+  }
+  // ragged tail (n % 4 rows): one row per lane, straight to memory
+  if (blockIdx.x == 0) {
+    const int64_t i = n_vec * 4 + tid;
+    if (i < a.n) {
+      int32_t j[ND];
+#pragma unroll
+      for (int k = 0; k < ND; ++k) j[k] = a.fk[k][i];
+      int32_t g = 0;
+      bool alive = true;
+      classify_fast<NBL, NML, NMG, NBG>(a, tab, j, alive, g);
+      if (alive) {
+#pragma unroll
+        for (int m = 0; m < MM; ++m)
+          atomicAdd(&a.gsums[static_cast<size_t>(m) * a.G + g], static_cast<unsigned long long>(static_cast<long long>(a.meas[m][i])));
+        if (a.gcounts) atomicAdd(&a.gcounts[g], 1ull);
+      }
+    }
+  }
 }
-template <bool MEM, int NBL, int NML, int NMG, int NBG>
+
+// Second pass: workgroup `bucket` adds the bucket's survivors up in LDS and then adds its accumulators to the
+// groups it alone owns (plain read-modify-write: the atomics of the first pass are complete).
+constexpr int BUCKET_FOLD_THREADS = 1024;
+template <int MM>
+__global__ __launch_bounds__(BUCKET_FOLD_THREADS) void bucket_fold_kernel(BucketArgs b, unsigned long long* sums,
+                                                                          unsigned long long* counts, int32_t G) {
+  extern __shared__ __align__(16) unsigned long long bacc[];     // [MM + 1][groups of a bucket]
+  const int R = 1 << b.shift;
+  const int bucket = blockIdx.x;
+  const unsigned int cnt = min(b.gcount[bucket], b.cap);
+  if (cnt == 0u) return;                                         // (the same for the whole workgroup)
+  for (int i = threadIdx.x; i < (MM + 1) * R; i += BUCKET_FOLD_THREADS) bacc[i] = 0ull;
+  __syncthreads();
+  const uint32_t* p = b.pairs + static_cast<size_t>(bucket) * b.cap * (1 + MM);
+  for (unsigned int i = threadIdx.x; i < cnt; i += BUCKET_FOLD_THREADS) {
+    const uint32_t* e = p + static_cast<size_t>(i) * (1 + MM);
+    const uint32_t gl = e[0];
+#pragma unroll
+    for (int m = 0; m < MM; ++m)
+      atomicAdd(&bacc[m * R + gl], static_cast<unsigned long long>(static_cast<long long>(static_cast<int32_t>(e[1 + m]))));
+    atomicAdd(&bacc[MM * R + gl], 1ull);
+  }
+  __syncthreads();
+  for (int i = threadIdx.x; i < R; i += BUCKET_FOLD_THREADS) {
+    const int64_t g = static_cast<int64_t>(bucket) * R + i;
+    if (g >= G) break;
+    const unsigned long long c = bacc[MM * R + i];
+    if (c == 0ull) continue;
+#pragma unroll
+    for (int m = 0; m < MM; ++m) sums[static_cast<size_t>(m) * G + g] += bacc[m * R + i];
+    if (counts) counts[g] += c;
+  }
+}
+
+template <int MODE, int NBL, int NML, int NMG, int NBG, int MM>
+int launch_fast_inst(const FastArgs& a, const FastLaunch& L) {
+  if constexpr (MODE == 2) {
+    auto kernel = &scan_fast_bucket_kernel<NBL, NML, NMG, NBG, MM>;
+    if (L.lds > 64 * 1024)
+      LQ_HIP_TRY(hipFuncSetAttribute(reinterpret_cast<const void*>(kernel),
+                                     hipFuncAttributeMaxDynamicSharedMemorySize, static_cast<int>(L.lds)));
+    // one resident set of workgroups (this kernel's registers allow fewer per compute unit than its LDS does)
+    const int64_t resident = static_cast<int64_t>(num_cus()) * resident_per_cu(reinterpret_cast<const void*>(kernel), SCAN_THREADS, L.lds);
+    const int64_t n_vec = a.n / 4;
+    int64_t blocks = std::max<int64_t>(1, std::min<int64_t>(L.blocks, resident));
+    int64_t per_block = (n_vec + blocks - 1) / blocks;
+    per_block = std::max<int64_t>(SCAN_THREADS, (per_block + SCAN_THREADS - 1) / SCAN_THREADS * SCAN_THREADS);
+    blocks = std::max<int64_t>(1, (n_vec + per_block - 1) / per_block);
+    hipLaunchKernelGGL(kernel, dim3(static_cast<unsigned>(blocks)), dim3(SCAN_THREADS), L.lds, L.s, a, L.bucket, per_block);
+    LQ_LAUNCH_CHECK("scan_fast_bucket_kernel");
+    const size_t fold_lds = static_cast<size_t>(MM + 1) * (size_t{1} << L.bucket.shift) * 8;
+    if (fold_lds > 64 * 1024)
+      LQ_HIP_TRY(hipFuncSetAttribute(reinterpret_cast<const void*>(&bucket_fold_kernel<MM>),
+                                     hipFuncAttributeMaxDynamicSharedMemorySize, static_cast<int>(fold_lds)));
+    hipLaunchKernelGGL((bucket_fold_kernel<MM>), dim3(static_cast<unsigned>(L.bucket.buckets)), dim3(BUCKET_FOLD_THREADS),
+                       fold_lds, L.s, L.bucket, a.gsums, a.gcounts, a.G);
+    LQ_LAUNCH_CHECK("bucket_fold_kernel");
+    return LQ_OK;
+  } else {
+    auto kernel = MODE == 1 ? &scan_fast_mem_kernel<NBL, NML, NMG, NBG, MM> : &scan_fast_kernel<NBL, NML, NMG, NBG, MM>;
+    if (L.lds > 64 * 1024)
+      LQ_HIP_TRY(hipFuncSetAttribute(reinterpret_cast<const void*>(kernel),
+                                     hipFuncAttributeMaxDynamicSharedMemorySize, static_cast<int>(L.lds)));
+    hipLaunchKernelGGL(kernel, dim3(L.blocks), dim3(SCAN_THREADS), L.lds, L.s, a, L.per_block);
+    LQ_LAUNCH_CHECK("scan_fast_kernel");
+    return LQ_OK;
+  }
+}
+template <int MODE, int NBL, int NML, int NMG, int NBG>
 int launch_fast_m(const FastArgs& a, const FastLaunch& L) {
   // (more than 8,192 accumulators need at least two grouping dimensions of up to 255 values each)
-  if constexpr (NBL + NML + NMG + NBG == 0 || (MEM && NBL + NBG < 2)) return -1;
+  if constexpr (NBL + NML + NMG + NBG == 0 || (MODE != 0 && NBL + NBG < 2)) return -1;
   else {
-    if (L.M == 1) return launch_fast_inst<MEM, NBL, NML, NMG, NBG, 1>(a, L);
-    if (L.M == 2) return launch_fast_inst<MEM, NBL, NML, NMG, NBG, 2>(a, L);
+    if (L.M == 1) return launch_fast_inst<MODE, NBL, NML, NMG, NBG, 1>(a, L);
+    if (L.M == 2) return launch_fast_inst<MODE, NBL, NML, NMG, NBG, 2>(a, L);
     return -1;
   }
 }
-template <bool MEM, int NBL, int NML>
+template <int MODE, int NBL, int NML>
 int launch_fast_g(const FastArgs& a, const FastLaunch& L) {
-  if (L.nmg == 0 && L.nbg == 0) return launch_fast_m<MEM, NBL, NML, 0, 0>(a, L);
-  if (L.nmg == 1 && L.nbg == 0) return launch_fast_m<MEM, NBL, NML, 1, 0>(a, L);
-  if (L.nmg == 0 && L.nbg == 1) return launch_fast_m<MEM, NBL, NML, 0, 1>(a, L);
-  if (L.nmg == 1 && L.nbg == 1) return launch_fast_m<MEM, NBL, NML, 1, 1>(a, L);
+  if (L.nmg == 0 && L.nbg == 0) return launch_fast_m<MODE, NBL, NML, 0, 0>(a, L);
+  if (L.nmg == 1 && L.nbg == 0) return launch_fast_m<MODE, NBL, NML, 1, 0>(a, L);
+  if (L.nmg == 0 && L.nbg == 1) return launch_fast_m<MODE, NBL, NML, 0, 1>(a, L);
+  if (L.nmg == 1 && L.nbg == 1) return launch_fast_m<MODE, NBL, NML, 1, 1>(a, L);
   return -1;
 }
-template <bool MEM, int NBL>
+template <int MODE, int NBL>
 int launch_fast_ml(const FastArgs& a, const FastLaunch& L) {
   switch (L.nml) {
-    case 0: return launch_fast_g<MEM, NBL, 0>(a, L);
-    case 1: return launch_fast_g<MEM, NBL, 1>(a, L);
-    case 2: return launch_fast_g<MEM, NBL, 2>(a, L);
-    case 3: return launch_fast_g<MEM, NBL, 3>(a, L);
+    case 0: return launch_fast_g<MODE, NBL, 0>(a, L);
+    case 1: return launch_fast_g<MODE, NBL, 1>(a, L);
+    case 2: return launch_fast_g<MODE, NBL, 2>(a, L);
+    case 3: return launch_fast_g<MODE, NBL, 3>(a, L);
     default: return -1;
   }
 }
 // Returns -1 when there is no instantiation for this mix of dimensions.
-template <bool MEM>
+// MODE: 0 accumulators in LDS, 1 in memory through atomics, 2 in memory through buckets.
+template <int MODE>
 int launch_fast(const FastArgs& a, const FastLaunch& L) {
   switch (L.nbl) {
-    case 0: return launch_fast_ml<MEM, 0>(a, L);
-    case 1: return launch_fast_ml<MEM, 1>(a, L);
-    case 2: return launch_fast_ml<MEM, 2>(a, L);
-    case 3: return launch_fast_ml<MEM, 3>(a, L);
+    case 0: return launch_fast_ml<MODE, 0>(a, L);
+    case 1: return launch_fast_ml<MODE, 1>(a, L);
+    case 2: return launch_fast_ml<MODE, 2>(a, L);
+    case 3: return launch_fast_ml<MODE, 3>(a, L);
     default: return -1;
   }
 }

@@ -58,8 +58,9 @@ int launch_fused_tile(const PredictArgs& a, hipStream_t s);
 int launch_groupby(int64_t n, int32_t K, const int32_t* const* fks, const int64_t* rows,
                    const uint8_t* const* mask, const int32_t* const* code, const int32_t* card,
                    const uint8_t* fact_mask, int32_t M, const int32_t* const* meas, int64_t* sums,
-                   int64_t* counts, int32_t G, void* ws, bool reuse_tables, hipStream_t s);
+                   int64_t* counts, int32_t G, void* ws, size_t ws_bytes, bool reuse_tables, hipStream_t s);
 size_t groupby_ws_bytes(int32_t K, const int64_t* rows, int64_t n_acc);
+size_t groupby_bucket_ws_bytes(int64_t n, int32_t K, const int64_t* rows, int64_t G, int32_t M);
 int launch_groupby_agg(int64_t n, int32_t K, const int32_t* const* fks, const int64_t* rows,
                        const uint8_t* const* mask, const int32_t* const* code, const int32_t* card,
                        int32_t n_preds, const lq_range_pred* preds, int32_t M, const lq_measure* meas,
@@ -468,6 +469,19 @@ size_t lq_groupby_workspace_bytes(int32_t n_dims, const int64_t* dim_rows, const
   return groupby_ws_bytes(n_dims, dim_rows, G * (n_measures + 1));
 }
 
+size_t lq_groupby_bucket_workspace_bytes(int64_t n_fact, int32_t n_dims, const int64_t* dim_rows, const int32_t* group_card,
+                                         int32_t n_measures) {
+  if (n_dims < 0 || n_dims > LQ_MAX_DIMS || (n_dims > 0 && !dim_rows) || !group_card) return 0;
+  if (n_measures < 1 || n_measures > LQ_MAX_MEASURES) return 0;
+  int64_t G = 1;
+  for (int k = 0; k < n_dims; ++k) {
+    if (dim_rows[k] < 0 || group_card[k] < 1 || group_card[k] > 65535) return 0;
+    G *= group_card[k];
+    if (G > LQ_MAX_GROUPS) return 0;
+  }
+  return groupby_bucket_ws_bytes(n_fact, n_dims, dim_rows, G, n_measures);
+}
+
 // Validation and launch shared by lq_masked_groupby_sum and its allocation-free variant.
 static int groupby_sum_checked(int64_t n_fact, int32_t n_dims, const int32_t* const* fks,
                                const int64_t* dim_rows, const uint8_t* const* dim_mask,
@@ -510,7 +524,7 @@ static int groupby_sum_checked(int64_t n_fact, int32_t n_dims, const int32_t* co
   if ((flags & LQ_CHECK_FKS) && n_dims > 0 && n_fact > 0)
     if ((rc = check_groupby_fks(n_fact, n_dims, fks, dim_rows, dim_mask, dim_code, group_card, ws, ws_bytes, s))) return rc;
   return launch_groupby(n_fact, n_dims, fks, dim_rows, dim_mask, dim_code, group_card, fact_mask,
-                        n_measures, measures, sums, counts, static_cast<int32_t>(G), ws,
+                        n_measures, measures, sums, counts, static_cast<int32_t>(G), ws, ws_bytes,
                         (flags & LQ_REUSE_SIDE_TABLES) != 0, s);
 }
 

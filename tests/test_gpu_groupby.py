@@ -346,3 +346,26 @@ def test_many_groups_on_the_specialised_scan(lq, rows, card, sel, n_measures):
     # aligned columns, no fact mask, byte codes and bitmaps, one or two measures: the compile-time specialised scan
     w = _many_groups(350 + len(rows) + n_measures, 777_777, rows, card, n_measures, sel=sel, neg=True)
     _check(lq, w)
+
+
+def test_many_groups_through_buckets_and_through_atomics(lq):
+    """The two forms of the many-groups group-by on the same query: with the small workspace the survivors go through
+    device-wide atomics, with lq_groupby_bucket_workspace_bytes they are sorted into buckets first; both equal the oracle.
+    Also with most rows in a few groups (a bucket runs out of slots and the rest takes the atomics) and with a workspace
+    one byte short of the bucketed form."""
+    for seed, hot, nm in ((350, False, 1), (351, True, 2), (352, False, 2)):
+        w = _many_groups(seed, 2_000_003, (300, 280, 5_000), (300, 280, 1), nm, sel=(None, None, 0.7), hot=hot)
+        ws_, wc_ = _oracle(w)
+        w = to_dev(w)
+        small = lq.lq_groupby_workspace_bytes(w.dim_rows, w.group_card, nm)
+        big = lq.lq_groupby_bucket_workspace_bytes(w.n, w.dim_rows, w.group_card, nm)
+        assert big > small + 2 * 4 * (1 + nm) * w.n
+        for size in (small, big - 1, big):
+            ws = torch.empty(size, dtype=torch.uint8, device="cuda")
+            s, c = _gpu(lq, w, ws=ws)
+            np.testing.assert_array_equal(s, ws_, err_msg=f"seed {seed}, workspace {size}")
+            np.testing.assert_array_equal(c, wc_, err_msg=f"seed {seed}, workspace {size}")
+    # the bucketed form does not apply: few accumulators, three measures
+    assert lq.lq_groupby_bucket_workspace_bytes(1_000_000, [300, 280], [30, 28], 1) == 0
+    assert lq.lq_groupby_bucket_workspace_bytes(1_000_000, [300, 280], [300, 280], 3) == 0
+    assert lq.lq_groupby_bucket_workspace_bytes(0, [300, 280], [300, 280], 1) == 0
