@@ -369,3 +369,33 @@ def test_many_groups_through_buckets_and_through_atomics(lq):
     assert lq.lq_groupby_bucket_workspace_bytes(1_000_000, [300, 280], [30, 28], 1) == 0
     assert lq.lq_groupby_bucket_workspace_bytes(1_000_000, [300, 280], [300, 280], 3) == 0
     assert lq.lq_groupby_bucket_workspace_bytes(0, [300, 280], [300, 280], 1) == 0
+
+
+@pytest.mark.parametrize("n", [1, 5, 1_023, 4_099, 70_001])
+def test_bucketed_many_groups_ragged_sizes_and_negative_keys(lq, n):
+    # no fact mask, aligned columns: the specialised scan, with the default (large) workspace the bucketed form
+    _check(lq, _many_groups(360 + n, n, (70, 110, 50, 130), (70, 110, 3, 1), 2, sel=(None, 0.8, 0.5, 0.6), neg=True))
+
+
+@pytest.mark.parametrize("card,n_measures", [
+    ((91, 91), 1),                  # 8,281 groups: just past the LDS limit at one measure, buckets of 32 groups
+    ((65, 64), 2),                  # 4,160 groups x 3 accumulators: buckets of 16
+    ((200, 173, 87), 1),            # 3.0e6 groups, not a multiple of the bucket size (4,096 groups each)
+    ((255, 255, 255), 2),           # 1.66e7 groups: 8,097 buckets of 2,048, close to the most the form takes
+    ((255, 255, 255, 3), 1),        # 5.0e7 groups: more buckets than the form takes, the atomic form runs
+], ids=["8281x1", "4160x2", "3.0e6x1", "1.66e7x2", "5.0e7x1"])
+def test_bucketed_many_groups_bucket_geometries(lq, card, n_measures):
+    # (grouping attributes of at most 255 values each: the side tables the specialised scan takes)
+    rows = tuple(c + 5 for c in card) + (40,)
+    w = _many_groups(370 + card[0] + len(card), 200_003, rows, tuple(card) + (1,), n_measures,
+                     sel=(None,) * len(card) + (0.9,))
+    _check(lq, w)
+
+
+def test_bucketed_many_groups_all_rows_in_one_group(lq):
+    # every row in one group: its bucket fills up and the rest goes through the merged atomics
+    w = _many_groups(380, 1_000_003, (300, 300), (300, 300), 1)
+    for f in w.fks:
+        f[:] = 7
+    w, ws, wc = _check(lq, w)
+    assert (wc > 0).sum() == 1 and wc.max() == 1_000_003
