@@ -520,9 +520,17 @@ __global__ __launch_bounds__(SCAN_THREADS) void scan_fast_bucket_kernel(FastArgs
           const unsigned int pos = lbase[bk] + rank[s][q];
           if (pos < b.cap) {
             uint32_t* dst = b.pairs + (static_cast<size_t>(bk) * b.cap + pos) * (1 + MM);
-            dst[0] = static_cast<uint32_t>(g[s][q] & ((1 << b.shift) - 1));
+            const uint32_t gl = static_cast<uint32_t>(g[s][q] & ((1 << b.shift) - 1));
+            // (ordinary stores: the runs of a bucket are completed in L2 by later rounds and other workgroups;
+            // streaming stores send every 8-byte piece to memory on its own and were measured 3.6x slower)
+            if constexpr (MM == 1) {             // one 8-byte store (slots of two words are 8-byte aligned)
+              typedef unsigned int v2u __attribute__((ext_vector_type(2)));
+              *reinterpret_cast<v2u*>(dst) = v2u{gl, static_cast<uint32_t>(val[s][q][0])};
+            } else {
+              dst[0] = gl;
 #pragma unroll
-            for (int m = 0; m < MM; ++m) dst[1 + m] = static_cast<uint32_t>(val[s][q][m]);
+              for (int m = 0; m < MM; ++m) dst[1 + m] = static_cast<uint32_t>(val[s][q][m]);
+            }
           } else {
             over = true;
           }
