@@ -431,7 +431,9 @@ def main():
         cells = {}
         for name, rows, card, sel in (("three_attributes_25x25x250_selective", (2_556, 30_000, 2_000, 200_000), (25, 25, 250, 1), (None, 0.2, None, 0.12)),
                                       ("three_attributes_25x25x250_all_rows", (2_556, 30_000, 2_000, 200_000), (25, 25, 250, 1), (None, None, None, 1.0)),
-                                      ("two_attributes_250x250_selective", (2_556, 30_000, 2_000, 200_000), (250, 250, 1, 1), (None, None, 0.2, 0.12))):
+                                      ("two_attributes_250x250_selective", (2_556, 30_000, 2_000, 200_000), (250, 250, 1, 1), (None, None, 0.2, 0.12)),
+                                      # year x brand with a filter on the supplier side: a grouping attribute of 1,000 values
+                                      ("year_x_1000_brands_one_supplier_region", (2_556, 30_000, 2_000, 200_000), (7, 1, 1, 1_000), (None, 1.0, 0.2, None))):
             gen = torch.Generator(device=dev); gen.manual_seed(WL.SEED0 + 970)
             fks = [torch.randint(0, r, (nm,), generator=gen, device=dev, dtype=torch.int32) for r in rows]
             codes = [torch.randint(0, c, (r,), generator=gen, device=dev, dtype=torch.int32) if c > 1 else None for r, c in zip(rows, card)]

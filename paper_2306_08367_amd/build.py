@@ -12,7 +12,7 @@ ROOT = os.path.dirname(HERE)
 CSRC = os.path.join(HERE, "csrc")
 LIB = os.path.join(HERE, "liblq.so")
 OBJDIR = os.path.join(HERE, "_build")
-SOURCES = ["lq_api.hip", "gemm.hip", "fused.hip", "fused_rowbatch.hip", "fused_rowbatch_wide_a.hip", "fused_rowbatch_wide_b.hip", "fused_rowbatch_wide_c.hip", "fused_rowbatch_wide_d.hip", "fused_coltile_a.hip", "fused_coltile_b.hip", "fused_coltile_c.hip", "fused_bf16.hip", "fused_tile.hip", "fused_deep.hip", "fused_deep_b.hip", "fused_deep_c.hip", "fused_deep_bf16.hip", "fused_lds.hip", "gather.hip", "yardstick.hip", "groupby.hip", "groupby_many.hip", "groupby_agg_fast.hip", "tree.hip", "keymap.hip", "keymap64.hip", "domain.hip"]
+SOURCES = ["lq_api.hip", "gemm.hip", "fused.hip", "fused_rowbatch.hip", "fused_rowbatch_wide_a.hip", "fused_rowbatch_wide_b.hip", "fused_rowbatch_wide_c.hip", "fused_rowbatch_wide_d.hip", "fused_coltile_a.hip", "fused_coltile_b.hip", "fused_coltile_c.hip", "fused_bf16.hip", "fused_tile.hip", "fused_deep.hip", "fused_deep_b.hip", "fused_deep_c.hip", "fused_deep_bf16.hip", "fused_lds.hip", "gather.hip", "yardstick.hip", "groupby.hip", "groupby_many.hip", "groupby_wide.hip", "groupby_agg_fast.hip", "tree.hip", "keymap.hip", "keymap64.hip", "domain.hip"]
 ARCH = "gfx950"
 # Packed-fp32 instruction selection is switched off for all device code.
 FLAGS = ["-O3", "-std=c++17", "-fPIC", f"--offload-arch={ARCH}", "-Wall", "-Wno-unused-function",

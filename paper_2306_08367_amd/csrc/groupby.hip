@@ -23,6 +23,7 @@ namespace lq {
 
 int launch_fast_many(const FastArgs& a, const FastLaunch& L);     // groupby_many.hip
 int launch_fast_bucket(const FastArgs& a, const FastLaunch& L);   // groupby_many.hip
+int launch_fast_wide(const FastArgs& a, const FastLaunch& L, int mode);   // groupby_wide.hip (0 LDS, 1 atomics, 2 buckets)
 int launch_agg_fast(const GbArgs& a, const AggFastArgs& x, const FastLaunch& L, int n_preds, int pack_here);   // groupby_agg_fast.hip
 
 namespace {
@@ -784,12 +785,13 @@ int launch_groupby(int64_t n, int32_t K, const int32_t* const* fks, const int64_
     // runs: byte in LDS, bitmap in LDS, bitmap in memory, byte in memory
     for (int run = 0; run < 4 && ok; ++run)
       for (int k = 0; k < K; ++k) {
-        const int kind = a.d[k].kind;
+        const bool wide = a.d[k].kind == DK_U16;               // a code table of 16-bit entries rides with the byte tables
+        const int kind = wide ? static_cast<int>(DK_BYTE) : a.d[k].kind;
         if (kind != DK_BYTE && kind != DK_BITMAP) { ok = false; break; }
         const int want_kind = (run == 0 || run == 3) ? DK_BYTE : DK_BITMAP;
         const int want_lds = run < 2 ? 1 : 0;
         if (kind != want_kind || a.d[k].in_lds != want_lds) continue;
-        f.fk[slot] = a.d[k].fk; f.off[slot] = a.d[k].off; f.stride[slot] = a.d[k].stride;
+        f.fk[slot] = a.d[k].fk; f.off[slot] = a.d[k].off; f.stride[slot] = a.d[k].stride; f.wide[slot] = wide ? 1 : 0;
         ++slot;
         if (run == 0) ++L.nbl; else if (run == 1) ++L.nml; else if (run == 2) ++L.nmg; else ++L.nbg;
       }
@@ -805,11 +807,17 @@ int launch_groupby(int64_t n, int32_t K, const int32_t* const* fks, const int64_
         L.lds = round_up(lds_prefix, 16) + static_cast<size_t>(bucket.buckets) * 8;
       }
       slices(L.lds, &L.blocks, &L.per_block);
-      int rc = gacc ? (buckets ? launch_fast_bucket(f, L) : launch_fast_many(f, L)) : launch_fast<0>(f, L);
+      bool any_wide = false;
+      for (int k = 0; k < slot; ++k) any_wide = any_wide || f.wide[k];
+      auto run = [&](int mode) {
+        if (any_wide) return launch_fast_wide(f, L, mode);
+        return mode == 0 ? launch_fast<0>(f, L) : (mode == 1 ? launch_fast_many(f, L) : launch_fast_bucket(f, L));
+      };
+      int rc = run(gacc ? (buckets ? 2 : 1) : 0);
       if (rc == -1 && buckets) {                     // no bucketed instantiation for this mix: the atomic form
         L.lds = acc_bytes + lds_prefix;
         slices(L.lds, &L.blocks, &L.per_block);
-        rc = launch_fast_many(f, L);
+        rc = run(1);
       }
       if (rc > 0) return rc;
       if (rc == 0) {

@@ -53,6 +53,7 @@ struct FastArgs {
   const int32_t* fk[LQ_MAX_DIMS];    // in the order of the four runs above
   uint32_t off[LQ_MAX_DIMS];         // byte offset inside the packed buffer
   int32_t stride[LQ_MAX_DIMS];
+  uint8_t wide[LQ_MAX_DIMS];         // 1: the code table has 16-bit entries (more than 255 values), else bytes
   const int32_t* meas[LQ_MAX_MEASURES];
   const uint8_t* packed;
   uint32_t lds_bytes;                // prefix of the packed buffer that is copied into LDS
@@ -236,14 +237,23 @@ __global__ __launch_bounds__(256) void init_outputs_kernel(GlobalOut o, int64_t 
 }
 
 
-template <bool BYTE, bool GUARDED>
-__device__ __forceinline__ void lookup(const uint8_t* t, int32_t j, int32_t stride, bool& alive, int32_t& g) {
+// BYTE: a code table (entries of one byte, or of two when `wide`; all ones = filtered out), else a bitmap.
+// WIDE: some code table of the call has 16-bit entries (decided per kernel instantiation, so that calls with byte
+// tables only do not pay for the test).
+template <bool BYTE, bool GUARDED, bool WIDE>
+__device__ __forceinline__ void lookup(const uint8_t* t, int32_t j, int32_t stride, bool wide, bool& alive, int32_t& g) {
   alive = alive && j >= 0;
   if (GUARDED && !alive) return;
   const uint32_t jj = j < 0 ? 0u : static_cast<uint32_t>(j);   // keep the lookup in bounds
   if (BYTE) {
-    const uint32_t b = t[jj];
-    alive = alive && b != 0xffu;
+    uint32_t b;
+    if (WIDE && wide) {                                        // (the same for every lane: a property of the table)
+      b = reinterpret_cast<const uint16_t*>(t)[jj];
+      alive = alive && b != 0xffffu;
+    } else {
+      b = t[jj];
+      alive = alive && b != 0xffu;
+    }
     g += static_cast<int32_t>(b) * stride;
   } else {
     const uint32_t w = reinterpret_cast<const uint32_t*>(t)[jj >> 5];
@@ -252,20 +262,20 @@ __device__ __forceinline__ void lookup(const uint8_t* t, int32_t j, int32_t stri
 }
 
 // All dimensions of one fact row.
-template <int NBL, int NML, int NMG, int NBG>
+template <int NBL, int NML, int NMG, int NBG, bool WIDE = false>
 __device__ __forceinline__ void classify_fast(const FastArgs& a, const uint8_t* tab, const int32_t* j,
                                               bool& alive, int32_t& g) {
   constexpr int NL = NBL + NML, ND = NL + NMG + NBG;
 #pragma unroll
   for (int k = 0; k < ND; ++k) {
-    if (k < NBL) lookup<true, false>(tab + a.off[k], j[k], a.stride[k], alive, g);
-    else if (k < NL) lookup<false, false>(tab + a.off[k], j[k], 0, alive, g);
-    else if (k < NL + NMG) lookup<false, true>(a.packed + a.off[k], j[k], 0, alive, g);
-    else lookup<true, true>(a.packed + a.off[k], j[k], a.stride[k], alive, g);
+    if (k < NBL) lookup<true, false, WIDE>(tab + a.off[k], j[k], a.stride[k], a.wide[k] != 0, alive, g);
+    else if (k < NL) lookup<false, false, false>(tab + a.off[k], j[k], 0, false, alive, g);
+    else if (k < NL + NMG) lookup<false, true, false>(a.packed + a.off[k], j[k], 0, false, alive, g);
+    else lookup<true, true, WIDE>(a.packed + a.off[k], j[k], a.stride[k], a.wide[k] != 0, alive, g);
   }
 }
 
-template <int NBL, int NML, int NMG, int NBG, int MM>
+template <int NBL, int NML, int NMG, int NBG, int MM, bool WIDE>
 __global__ __launch_bounds__(SCAN_THREADS) void scan_fast_kernel(FastArgs a, int64_t per_block) {
   extern __shared__ __align__(16) uint8_t smem[];
   constexpr int ND = NBL + NML + NMG + NBG;
@@ -306,7 +316,7 @@ __global__ __launch_bounds__(SCAN_THREADS) void scan_fast_kernel(FastArgs a, int
       for (int k = 0; k < ND; ++k) j[k] = cur[k][q];
       g[q] = 0;
       alive[q] = true;
-      classify_fast<NBL, NML, NMG, NBG>(a, tab, j, alive[q], g[q]);
+      classify_fast<NBL, NML, NMG, NBG, WIDE>(a, tab, j, alive[q], g[q]);
     }
     if (alive[0] || alive[1] || alive[2] || alive[3]) {
 #pragma unroll
@@ -334,7 +344,7 @@ __global__ __launch_bounds__(SCAN_THREADS) void scan_fast_kernel(FastArgs a, int
       for (int k = 0; k < ND; ++k) j[k] = a.fk[k][i];
       int32_t g = 0;
       bool alive = true;
-      classify_fast<NBL, NML, NMG, NBG>(a, tab, j, alive, g);
+      classify_fast<NBL, NML, NMG, NBG, WIDE>(a, tab, j, alive, g);
       if (alive) {
 #pragma unroll
         for (int m = 0; m < MM; ++m)
@@ -351,7 +361,7 @@ __global__ __launch_bounds__(SCAN_THREADS) void scan_fast_kernel(FastArgs a, int
 
 // The same scan with the accumulators in memory: a.gsums [MM x G] and a.gcounts [G] (or NULL), cleared
 // before the launch.  No partial rows, LDS only holds side tables.
-template <int NBL, int NML, int NMG, int NBG, int MM>
+template <int NBL, int NML, int NMG, int NBG, int MM, bool WIDE>
 __global__ __launch_bounds__(SCAN_THREADS) void scan_fast_mem_kernel(FastArgs a, int64_t per_block) {
   extern __shared__ __align__(16) uint8_t smem[];
   constexpr int ND = NBL + NML + NMG + NBG;
@@ -391,7 +401,7 @@ __global__ __launch_bounds__(SCAN_THREADS) void scan_fast_mem_kernel(FastArgs a,
       for (int k = 0; k < ND; ++k) j[k] = cur[k][q];
       g[q] = 0;
       alive[q] = true;
-      classify_fast<NBL, NML, NMG, NBG>(a, tab, j, alive[q], g[q]);
+      classify_fast<NBL, NML, NMG, NBG, WIDE>(a, tab, j, alive[q], g[q]);
     }
     const bool any = alive[0] || alive[1] || alive[2] || alive[3];
     if (__ballot(any) != 0ull) {
@@ -418,7 +428,7 @@ __global__ __launch_bounds__(SCAN_THREADS) void scan_fast_mem_kernel(FastArgs a,
       for (int k = 0; k < ND; ++k) j[k] = a.fk[k][i];
       int32_t g = 0;
       bool alive = true;
-      classify_fast<NBL, NML, NMG, NBG>(a, tab, j, alive, g);
+      classify_fast<NBL, NML, NMG, NBG, WIDE>(a, tab, j, alive, g);
       if (alive) {
 #pragma unroll
         for (int m = 0; m < MM; ++m)
@@ -434,7 +444,7 @@ __global__ __launch_bounds__(SCAN_THREADS) void scan_fast_mem_kernel(FastArgs a,
 // of the bucket with one device-wide atomic; the survivors are then written to their slots.  Every thread
 // of the workgroup takes the same number of steps (the barriers are inside the loop); lanes past the end
 // carry keys of -1.  gcount is zero and the outputs are cleared before the launch.
-template <int NBL, int NML, int NMG, int NBG, int MM>
+template <int NBL, int NML, int NMG, int NBG, int MM, bool WIDE>
 __global__ __launch_bounds__(SCAN_THREADS) void scan_fast_bucket_kernel(FastArgs a, BucketArgs b, int64_t per_block) {
   extern __shared__ __align__(16) uint8_t smem[];
   constexpr int ND = NBL + NML + NMG + NBG;
@@ -485,7 +495,7 @@ __global__ __launch_bounds__(SCAN_THREADS) void scan_fast_bucket_kernel(FastArgs
           for (int k = 0; k < ND; ++k) j[k] = cur[k][q];
           g[s][q] = 0;
           alive[q] = true;
-          classify_fast<NBL, NML, NMG, NBG>(a, tab, j, alive[q], g[s][q]);
+          classify_fast<NBL, NML, NMG, NBG, WIDE>(a, tab, j, alive[q], g[s][q]);
         }
         const bool any = alive[0] || alive[1] || alive[2] || alive[3];
 #pragma unroll
@@ -552,7 +562,7 @@ __global__ __launch_bounds__(SCAN_THREADS) void scan_fast_bucket_kernel(FastArgs
       for (int k = 0; k < ND; ++k) j[k] = a.fk[k][i];
       int32_t g = 0;
       bool alive = true;
-      classify_fast<NBL, NML, NMG, NBG>(a, tab, j, alive, g);
+      classify_fast<NBL, NML, NMG, NBG, WIDE>(a, tab, j, alive, g);
       if (alive) {
 #pragma unroll
         for (int m = 0; m < MM; ++m)
@@ -597,10 +607,10 @@ __global__ __launch_bounds__(BUCKET_FOLD_THREADS) void bucket_fold_kernel(Bucket
   }
 }
 
-template <int MODE, int NBL, int NML, int NMG, int NBG, int MM>
+template <int MODE, bool WIDE, int NBL, int NML, int NMG, int NBG, int MM>
 int launch_fast_inst(const FastArgs& a, const FastLaunch& L) {
   if constexpr (MODE == 2) {
-    auto kernel = &scan_fast_bucket_kernel<NBL, NML, NMG, NBG, MM>;
+    auto kernel = &scan_fast_bucket_kernel<NBL, NML, NMG, NBG, MM, WIDE>;
     if (L.lds > 64 * 1024)
       LQ_HIP_TRY(hipFuncSetAttribute(reinterpret_cast<const void*>(kernel),
                                      hipFuncAttributeMaxDynamicSharedMemorySize, static_cast<int>(L.lds)));
@@ -622,7 +632,7 @@ int launch_fast_inst(const FastArgs& a, const FastLaunch& L) {
     LQ_LAUNCH_CHECK("bucket_fold_kernel");
     return LQ_OK;
   } else {
-    auto kernel = MODE == 1 ? &scan_fast_mem_kernel<NBL, NML, NMG, NBG, MM> : &scan_fast_kernel<NBL, NML, NMG, NBG, MM>;
+    auto kernel = MODE == 1 ? &scan_fast_mem_kernel<NBL, NML, NMG, NBG, MM, WIDE> : &scan_fast_kernel<NBL, NML, NMG, NBG, MM, WIDE>;
     if (L.lds > 64 * 1024)
       LQ_HIP_TRY(hipFuncSetAttribute(reinterpret_cast<const void*>(kernel),
                                      hipFuncAttributeMaxDynamicSharedMemorySize, static_cast<int>(L.lds)));
@@ -631,43 +641,44 @@ int launch_fast_inst(const FastArgs& a, const FastLaunch& L) {
     return LQ_OK;
   }
 }
-template <int MODE, int NBL, int NML, int NMG, int NBG>
+template <int MODE, bool WIDE, int NBL, int NML, int NMG, int NBG>
 int launch_fast_m(const FastArgs& a, const FastLaunch& L) {
   // (more than 8,192 accumulators need at least two grouping dimensions of up to 255 values each)
   if constexpr (NBL + NML + NMG + NBG == 0 || (MODE != 0 && NBL + NBG < 2)) return -1;
   else {
-    if (L.M == 1) return launch_fast_inst<MODE, NBL, NML, NMG, NBG, 1>(a, L);
-    if (L.M == 2) return launch_fast_inst<MODE, NBL, NML, NMG, NBG, 2>(a, L);
+    if (L.M == 1) return launch_fast_inst<MODE, WIDE, NBL, NML, NMG, NBG, 1>(a, L);
+    if (L.M == 2) return launch_fast_inst<MODE, WIDE, NBL, NML, NMG, NBG, 2>(a, L);
     return -1;
   }
 }
-template <int MODE, int NBL, int NML>
+template <int MODE, bool WIDE, int NBL, int NML>
 int launch_fast_g(const FastArgs& a, const FastLaunch& L) {
-  if (L.nmg == 0 && L.nbg == 0) return launch_fast_m<MODE, NBL, NML, 0, 0>(a, L);
-  if (L.nmg == 1 && L.nbg == 0) return launch_fast_m<MODE, NBL, NML, 1, 0>(a, L);
-  if (L.nmg == 0 && L.nbg == 1) return launch_fast_m<MODE, NBL, NML, 0, 1>(a, L);
-  if (L.nmg == 1 && L.nbg == 1) return launch_fast_m<MODE, NBL, NML, 1, 1>(a, L);
+  if (L.nmg == 0 && L.nbg == 0) return launch_fast_m<MODE, WIDE, NBL, NML, 0, 0>(a, L);
+  if (L.nmg == 1 && L.nbg == 0) return launch_fast_m<MODE, WIDE, NBL, NML, 1, 0>(a, L);
+  if (L.nmg == 0 && L.nbg == 1) return launch_fast_m<MODE, WIDE, NBL, NML, 0, 1>(a, L);
+  if (L.nmg == 1 && L.nbg == 1) return launch_fast_m<MODE, WIDE, NBL, NML, 1, 1>(a, L);
   return -1;
 }
-template <int MODE, int NBL>
+template <int MODE, bool WIDE, int NBL>
 int launch_fast_ml(const FastArgs& a, const FastLaunch& L) {
   switch (L.nml) {
-    case 0: return launch_fast_g<MODE, NBL, 0>(a, L);
-    case 1: return launch_fast_g<MODE, NBL, 1>(a, L);
-    case 2: return launch_fast_g<MODE, NBL, 2>(a, L);
-    case 3: return launch_fast_g<MODE, NBL, 3>(a, L);
+    case 0: return launch_fast_g<MODE, WIDE, NBL, 0>(a, L);
+    case 1: return launch_fast_g<MODE, WIDE, NBL, 1>(a, L);
+    case 2: return launch_fast_g<MODE, WIDE, NBL, 2>(a, L);
+    case 3: return launch_fast_g<MODE, WIDE, NBL, 3>(a, L);
     default: return -1;
   }
 }
 // Returns -1 when there is no instantiation for this mix of dimensions.
 // MODE: 0 accumulators in LDS, 1 in memory through atomics, 2 in memory through buckets.
-template <int MODE>
+// WIDE: instantiations that also take code tables of 16-bit entries (compiled in a source of their own).
+template <int MODE, bool WIDE = false>
 int launch_fast(const FastArgs& a, const FastLaunch& L) {
   switch (L.nbl) {
-    case 0: return launch_fast_ml<MODE, 0>(a, L);
-    case 1: return launch_fast_ml<MODE, 1>(a, L);
-    case 2: return launch_fast_ml<MODE, 2>(a, L);
-    case 3: return launch_fast_ml<MODE, 3>(a, L);
+    case 0: return launch_fast_ml<MODE, WIDE, 0>(a, L);
+    case 1: return launch_fast_ml<MODE, WIDE, 1>(a, L);
+    case 2: return launch_fast_ml<MODE, WIDE, 2>(a, L);
+    case 3: return launch_fast_ml<MODE, WIDE, 3>(a, L);
     default: return -1;
   }
 }

@@ -400,3 +400,23 @@ def test_bucketed_many_groups_all_rows_in_one_group(lq):
         f[:] = 7
     w, ws, wc = _check(lq, w)
     assert (wc > 0).sum() == 1 and wc.max() == 1_000_003
+
+
+@pytest.mark.parametrize("card,n_measures,sel", [
+    ((300, 9), 2, (None, None, 0.5)),            # 2,700 groups x 3 accumulators: LDS form with a 16-bit code table
+    ((1_000, 7), 1, (None, None, 0.3)),          # 7,000 groups x 2: past the LDS limit (a brand x year query)
+    ((1_000, 250), 2, (0.9, None, None)),        # 250,000 groups, two measures, a masked grouping table
+    ((40_000, 3), 1, (None, None, None)),        # a 16-bit table too large for LDS, every row survives
+], ids=["lds_2700x3", "7000x2", "250000x3", "table_in_memory"])
+def test_grouping_attributes_of_more_than_255_values_on_the_specialised_scan(lq, card, n_measures, sel):
+    """Code tables of 16-bit entries on the specialised scan (no fact mask, aligned columns), in its LDS form, through
+    atomics (small workspace) and through buckets (default workspace)."""
+    rows = (card[0] + 17, card[1] + 3, 900)
+    w = _many_groups(390 + card[0] % 97, 300_007, rows, tuple(card) + (1,), n_measures, sel=sel, neg=True)
+    ws_, wc_ = _oracle(w)
+    w = to_dev(w)
+    small = torch.empty(lq.lq_groupby_workspace_bytes(w.dim_rows, w.group_card, n_measures), dtype=torch.uint8, device="cuda")
+    for kw in ({}, {"ws": small}):
+        s, c = _gpu(lq, w, **kw)
+        np.testing.assert_array_equal(s, ws_)
+        np.testing.assert_array_equal(c, wc_)
