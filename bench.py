@@ -223,7 +223,7 @@ def main():
         out["yardsticks"] = yard
         out["stream_copy"] = {"GBps_read_plus_write": yard["stream_copy_GBps_read_plus_write"], "bytes_copied": nb}
 
-    if args.only in ("", "yardsticks", "fused", "c4", "c5", "deep"):
+    if args.only in ("", "yardsticks", "fused", "c4", "c5", "deep", "keymap"):
         guarded("yardsticks", leg_yardsticks)
 
     # ---------------------------------------------------------------- headline: fused MLP (C2)
@@ -678,6 +678,15 @@ def main():
         out["keymap_ssb_sf1"] = {"fact_rows": nk, "rows_per_s_all_4_columns": nk / (tot_ms * 1e-3),
                                  "dense_keys_rows_per_s_all_4_columns": nk / (tot_dense * 1e-3), "per_dimension": res,
                                  "roofline": hbm_roofline(8, 4 * nk, tot_ms)}
+        gy = yard.get("gather_16B_rows_of_2MB_Grows_per_s")
+        if gy:
+            # a hashed lookup is at least one random 8-byte read of a table that sits in L2: the rate of the bare gather
+            # yardstick (16-byte rows of a 2 MB table) is its roof, the 8 bytes per key streamed in and out are not
+            big = res["200000"]["lookup_ms"]
+            out["keymap_ssb_sf1"]["hashed_lookups_frac_of_gather_yardstick"] = (nk / (big * 1e-3) / 1e9) / gy
+            out["keymap_ssb_sf1"]["note"] = ("hashed_lookups_frac_of_gather_yardstick: keys per second into the 200,000-key map "
+                                             "(3.2 MB of slots at load factor 1/2, 1.5 probes on average) over random 16-byte "
+                                             "reads per second from a 2 MB table")
     if want("keymap"):
         guarded("keymap_ssb_sf1", leg_keymap)
 
