@@ -214,7 +214,7 @@ def _mat(t: Optional[torch.Tensor], rows: int = 0, cols: int = 0, dtype: int = L
     s0, s1 = t.stride()
     if c > 1 and s1 != 1:
         raise ValueError("matrix columns must be contiguous (row-major)")
-    ld = s0 if r > 1 else max(c, 1)
+    ld = s0 if (r > 1 or s0 >= c) else max(c, 1)
     if r > 1 and ld < c:
         raise ValueError("row stride smaller than the row")
     return lq_mat(t.data_ptr(), r, c, ld, _dtype_code(t))
@@ -296,8 +296,13 @@ def lq_project_dims(dims: Sequence[torch.Tensor], W0: torch.Tensor, c_f: int,
                     stream=None) -> List[torch.Tensor]:
     """P_k = D_k times its rows of W0 (pre-fusion stage).  Allocates P unless given."""
     if P is None:
+        # rows start 16 bytes apart at the least (the stride is padded to 4 floats / 8 bf16 values): the fast kernels of
+        # the join stage then take any hidden width, the padding is never read as data
         pd = p_dtype or torch.float32
-        P = [_empty(stream, (d.shape[0], W0.shape[1]), dtype=pd, device=d.device) for d in dims]
+        per16 = 4 if pd == torch.float32 else 8
+        l1 = int(W0.shape[1])
+        ld = (l1 + per16 - 1) // per16 * per16
+        P = [_empty(stream, (d.shape[0], ld), dtype=pd, device=d.device)[:, :l1] for d in dims]
     fact = lq_mat(None, 0, int(c_f), max(int(c_f), 1), _dtype_code(W0))
     dims_arr = _mat_array(dims)
     star = lq_star(0, fact, len(dims), dims_arr, _ptr_array([None] * len(dims)))

@@ -238,7 +238,13 @@ __global__ __launch_bounds__(DEEP_THREADS, (DeepRegs<T1, TH, KMAX>::MIN_WAVES)) 
   for (int i = lane; i < 16 * LD; i += 64) tile[i] = 0.f;
   // A piece of the summed rows goes to the tile; a lane past the end of a row leaves the tile's zero in
   // place (one column part) or writes a zero over what the previous part left there (two parts).
-  auto store_piece = [&](float* dst, v4f sum, bool live) {
+  // (live: the piece starts inside the row.  A hidden width that is not a multiple of four: the row's last piece
+  // ends in the padding of the row stride, whose contents are not ours; those elements count as zero.)
+  auto store_piece = [&](float* dst, v4f sum, bool live, int col) {
+    if (l1 % 4 != 0) {
+#pragma unroll
+      for (int v = 0; v < 4; ++v) sum[v] = col + v < l1 ? sum[v] : 0.f;
+    }
     if constexpr (PARTS > 1) {
       *reinterpret_cast<v4f*>(dst) = live ? sum : v4f{0.f, 0.f, 0.f, 0.f};
     } else {
@@ -322,7 +328,7 @@ __global__ __launch_bounds__(DEEP_THREADS, (DeepRegs<T1, TH, KMAX>::MIN_WAVES)) 
           for (int k = 1; k < KMAX; ++k)
 #pragma unroll
             for (int v = 0; v < 4; ++v) sum[v] += g[k][u][v];
-          store_piece(tile + (u * RPI + gsub) * LD + 4 * gc, sum, part * 16 * T1 + 4 * gc < l1);
+          store_piece(tile + (u * RPI + gsub) * LD + 4 * gc, sum, part * 16 * T1 + 4 * gc < l1, part * 16 * T1 + 4 * gc);
         }
         if (part + 1 < PARTS) gather(key0, part + 1); else gather(key1, 0);
       } else {
@@ -352,7 +358,7 @@ __global__ __launch_bounds__(DEEP_THREADS, (DeepRegs<T1, TH, KMAX>::MIN_WAVES)) 
             for (int v = 0; v < 4; ++v) sum[u][v] += e[u][v];
         }
 #pragma unroll
-        for (int u = 0; u < T1; ++u) store_piece(tile + (u * RPI + gsub) * LD + 4 * gc, sum[u], col < l1);
+        for (int u = 0; u < T1; ++u) store_piece(tile + (u * RPI + gsub) * LD + 4 * gc, sum[u], col < l1, col);
       }
 
       // z = x W_f + b_1 (matrix cores) + the gathered sum (back from the tile), ReLU

@@ -144,8 +144,8 @@ template <int COLS, int CFC, int L2P> struct WConsts {
 };
 
 template <typename T, int LPR, int K, int CFC, int NL, int L2P, int PG>
-__device__ __forceinline__ void compute_group(const PredictArgs& a, int c, bool active, int group_base, int grp, int64_t row0,
-                                              const WRow<K, CFC>& r, const WGather<K, PG>& g,
+__device__ __forceinline__ void compute_group(const PredictArgs& a, int c, bool active, int nvalid, bool y_piece, int group_base,
+                                              int grp, int64_t row0, const WRow<K, CFC>& r, const WGather<K, PG>& g,
                                               const WConsts<Piece<T>::COLS, CFC, L2P>& w, float (&ykeep)[L2P]) {
   constexpr int COLS = Piece<T>::COLS;
 #pragma unroll
@@ -164,10 +164,24 @@ __device__ __forceinline__ void compute_group(const PredictArgs& a, int c, bool 
       }
 #pragma unroll
     for (int k = 0; k < K; ++k) Piece<T>::add(g.p[u][k], z);
+    // a hidden width that is not a multiple of COLS: the last piece of a row ends in the padding of the row
+    // stride, whose contents are not ours; those elements count as zero
+    if (a.wout[0] % COLS != 0) {
+#pragma unroll
+      for (int v = 0; v < COLS; ++v) z[v] = v < nvalid ? z[v] : 0.f;
+    }
     if constexpr (NL == 1) {
       const int64_t row = row0 + group_base + t;
-      if (row < a.n && active)
-        __builtin_nontemporal_store(Piece<T>::pack(z), reinterpret_cast<v4u*>(static_cast<T*>(a.Y) + row * a.ldy + COLS * c));
+      if (row < a.n && active) {
+        T* yr = static_cast<T*>(a.Y) + row * a.ldy + COLS * c;
+        if (y_piece) {
+          __builtin_nontemporal_store(Piece<T>::pack(z), reinterpret_cast<v4u*>(yr));
+        } else {                       // Y rows that are not 16-byte aligned, or a partial last piece
+#pragma unroll
+          for (int v = 0; v < COLS; ++v)
+            if (v < nvalid) Elem<T>::store(yr + v, z[v]);
+        }
+      }
     } else {
       float y[L2P];
 #pragma unroll
@@ -210,6 +224,9 @@ void fused_rowbatch_wide_kernel(PredictArgs a) {
   if (wave >= nb) return;
   const int l2 = NL == 2 ? a.wout[1] : 0;
   const bool active = COLS * c < a.wout[0];   // lanes beyond the hidden width idle (widths that are not COLS x a power of two)
+  const int nvalid = min(COLS, max(0, a.wout[0] - COLS * c));      // columns of this lane's piece that exist
+  // (linear models) whole 16-byte pieces of Y: aligned rows and no partial piece in this lane
+  const bool y_piece = a.ldy % COLS == 0 && (reinterpret_cast<uintptr_t>(a.Y) & 15) == 0 && nvalid == COLS;
   const bool x_vec = a.c_f == 4 * CFC && a.ldx % 4 == 0 && (reinterpret_cast<uintptr_t>(a.X) & (4 * sizeof(T) - 1)) == 0;
   const bool y_vec = l2 % 4 == 0 && a.ldy % 4 == 0 && (reinterpret_cast<uintptr_t>(a.Y) & 15) == 0;
 
@@ -220,16 +237,16 @@ void fused_rowbatch_wide_kernel(PredictArgs a) {
     for (int q = 0; q < CFC * 4; ++q)
 #pragma unroll
       for (int v = 0; v < COLS; ++v)
-        w.wf[q][v] = (q < a.c_f && active) ? Elem<T>::load(W0 + static_cast<int64_t>(q) * a.ldw[0] + COLS * c + v) : 0.f;
+        w.wf[q][v] = (q < a.c_f && v < nvalid) ? Elem<T>::load(W0 + static_cast<int64_t>(q) * a.ldw[0] + COLS * c + v) : 0.f;
 #pragma unroll
     for (int v = 0; v < COLS; ++v)
-      w.b1[v] = (a.bias[0] && active) ? Elem<T>::load(static_cast<const T*>(a.bias[0]) + COLS * c + v) : 0.f;
+      w.b1[v] = (a.bias[0] && v < nvalid) ? Elem<T>::load(static_cast<const T*>(a.bias[0]) + COLS * c + v) : 0.f;
 #pragma unroll
     for (int o = 0; o < L2P; ++o) {
-      const bool real = NL == 2 && o < l2 && active;
+      const bool real = NL == 2 && o < l2;
 #pragma unroll
       for (int v = 0; v < COLS; ++v)
-        w.w2[v][o] = real ? Elem<T>::load(static_cast<const T*>(a.W[1]) + static_cast<int64_t>(COLS * c + v) * a.ldw[1] + o) : 0.f;
+        w.w2[v][o] = (real && v < nvalid) ? Elem<T>::load(static_cast<const T*>(a.W[1]) + static_cast<int64_t>(COLS * c + v) * a.ldw[1] + o) : 0.f;
       w.b2[o] = (NL == 2 && o < l2 && a.bias[1]) ? Elem<T>::load(static_cast<const T*>(a.bias[1]) + o) : 0.f;
     }
   }
@@ -253,13 +270,13 @@ void fused_rowbatch_wide_kernel(PredictArgs a) {
 #pragma unroll 1
     for (int grp = 0; grp < NG; grp += 2) {
       issue_group<T, LPR, K, CFC, PG>(a, c, active, group_base, grp + 1, cur, gb);
-      compute_group<T, LPR, K, CFC, NL, L2P, PG>(a, c, active, group_base, grp, row0, cur, ga, w, yk);
+      compute_group<T, LPR, K, CFC, NL, L2P, PG>(a, c, active, nvalid, y_piece, group_base, grp, row0, cur, ga, w, yk);
       if (grp + 2 < NG) issue_group<T, LPR, K, CFC, PG>(a, c, active, group_base, grp + 2, cur, ga);
       else {                                       // first group of the next batch (valid rows repeated at the end)
         keys_to_offsets<T, K, CFC>(a, nxt);
         issue_group<T, LPR, K, CFC, PG>(a, c, active, group_base, 0, nxt, ga);
       }
-      compute_group<T, LPR, K, CFC, NL, L2P, PG>(a, c, active, group_base, grp + 1, row0, cur, gb, w, yk);
+      compute_group<T, LPR, K, CFC, NL, L2P, PG>(a, c, active, nvalid, y_piece, group_base, grp + 1, row0, cur, gb, w, yk);
     }
     if constexpr (NL == 2) {
       if (row < a.n) {

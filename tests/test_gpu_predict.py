@@ -469,3 +469,51 @@ def test_non_fused_first_layer_over_many_rows(lq, shape):
     want = O.join_predict(None if sub.X is None else sub.X.cpu(), cpu_list(sub.dims), cpu_list(sub.fks), cpu_list(sub.weights),
                           cpu_list(sub.biases), nthreads=16)
     assert_close(Ym[sample.to("cuda")], want, TOL_F32, f"{name}: non-fused, one chunk")
+
+
+@pytest.mark.parametrize("shape", [
+    # name, fact rows, fact columns, dimension rows, dimension columns, layers, bias
+    ("w50_1", 20_011, 4, (300, 200, 100), (8, 8, 8), (50, 1), True),
+    ("w30_4", 4_099, 3, (300, 200), (8, 8), (30, 4), False),
+    ("w102_1_k5", 3_001, 0, (50, 60, 70, 80, 90), (4, 4, 4, 4, 4), (102, 1), True),
+    ("w50_linear", 20_011, 4, (300, 200, 100), (8, 8, 8), (50,), True),
+    ("w22_linear_one_row_table", 1_025, 0, (1, 40), (8, 8), (22,), False),
+    ("w250_13", 2_049, 8, (300, 200), (8, 8), (250, 13), True),
+    ("w50_10", 20_011, 4, (300, 200, 100), (8, 8, 8), (50, 10), True),        # matrix-core kernel
+    ("w50_30_1", 20_011, 4, (300, 200, 100), (8, 8, 8), (50, 30, 1), True),
+    ("w130_64_7_k6", 3_003, 5, (30, 40, 50, 60, 70, 80), (4, 4, 4, 4, 4, 4), (130, 64, 7), False),   # two column parts, six tables
+    ("w254_100", 1_111, 0, (100,), (16,), (254, 100), True),
+], ids=lambda s: s[0])
+def test_hidden_widths_that_are_not_multiples_of_four(lq, shape):
+    """fp32 first layers of any width: with the row stride of the projected tables padded to four floats (what the
+    binding allocates) the row-batch and matrix-core kernels take them, the last 16-byte piece of a row ending in the
+    padding, which is filled with NaN here and must not reach the result; with contiguous tables (rows not 16-byte
+    aligned) the general kernels run.  Both against the oracle."""
+    name, n, c_f, rows, cols, layers, bias = shape
+    k = c_f + sum(cols)
+    w = WL.make_predict(name, n, c_f, rows, cols, layers, seed=WL.SEED0 + 800 + len(name), device="cuda",
+                        w_sigma=[1.0 / np.sqrt(k)] + [1.0 / np.sqrt(a) for a in layers[:-1]], bias=bias)
+    want = _oracle(w)
+    l1 = layers[0]
+    ld = (l1 + 3) // 4 * 4
+    padded = []
+    for d in w.dims:
+        buf = torch.full((d.shape[0], ld), float("nan"), device="cuda")
+        padded.append(buf[:, :l1])
+    lq.lq_project_dims(w.dims, w.weights[0], w.c_f, P=padded)
+    Y = lq.lq_fused_join_predict(w.X, w.fks, padded, w.weights, w.biases)
+    torch.cuda.synchronize()
+    assert_close(Y, want, TOL_F32, f"{name}: padded row stride")
+    for buf in padded:                                   # the padding is untouched
+        assert torch.isnan(buf.as_strided((buf.shape[0], ld - l1), (ld, 1), buf.storage_offset() + l1)).all()
+    P = [torch.empty((d.shape[0], l1), device="cuda") for d in w.dims]
+    lq.lq_project_dims(w.dims, w.weights[0], w.c_f, P=P)
+    Yc = lq.lq_fused_join_predict(w.X, w.fks, P, w.weights, w.biases)
+    torch.cuda.synchronize()
+    assert_close(Yc, want, TOL_F32, f"{name}: contiguous tables")
+    if len(layers) == 1:                                 # a linear model into a column slice of a wider, misaligned buffer
+        Yw = torch.full((n, l1 + 3), -7.0, device="cuda")
+        lq.lq_fused_join_predict(w.X, w.fks, padded, w.weights, w.biases, Y=Yw[:, 1:1 + l1])
+        torch.cuda.synchronize()
+        assert_close(Yw[:, 1:1 + l1], want, TOL_F32, f"{name}: misaligned Y")
+        assert (Yw[:, 0] == -7).all() and (Yw[:, 1 + l1:] == -7).all()
