@@ -90,6 +90,9 @@ __global__ __launch_bounds__(CT_THREADS) void fused_coltile_kernel(PredictArgs a
     for (int tile = w; tile < tiles; tile += NW) {
       const int col = tile * TILE + COLS * lane;
       const bool active = col < l1;
+      const int nvalid = min(COLS, max(0, l1 - col));          // columns of this lane's piece that exist
+      // (linear models) a whole 16-byte piece of Y: aligned rows and no partial piece in this lane
+      const bool y_piece = a.ldy % COLS == 0 && (reinterpret_cast<uintptr_t>(a.Y) & 15) == 0 && nvalid == COLS;
       if (tile != loaded_tile) {      // a wavefront with one tile keeps its weights for the whole launch
         loaded_tile = tile;
         const T* W0 = static_cast<const T*>(a.W[0]);
@@ -97,16 +100,16 @@ __global__ __launch_bounds__(CT_THREADS) void fused_coltile_kernel(PredictArgs a
         for (int q = 0; q < CFC * 4; ++q)
 #pragma unroll
           for (int v = 0; v < COLS; ++v)
-            cw.wf[q][v] = (q < a.c_f && active) ? Elem<T>::load(W0 + static_cast<int64_t>(q) * a.ldw[0] + col + v) : 0.f;
+            cw.wf[q][v] = (q < a.c_f && v < nvalid) ? Elem<T>::load(W0 + static_cast<int64_t>(q) * a.ldw[0] + col + v) : 0.f;
 #pragma unroll
         for (int v = 0; v < COLS; ++v)
-          cw.b1[v] = (a.bias[0] && active) ? Elem<T>::load(static_cast<const T*>(a.bias[0]) + col + v) : 0.f;
+          cw.b1[v] = (a.bias[0] && v < nvalid) ? Elem<T>::load(static_cast<const T*>(a.bias[0]) + col + v) : 0.f;
 #pragma unroll
         for (int o = 0; o < L2P; ++o) {
-          const bool real = NL == 2 && o < l2 && active;
+          const bool real = NL == 2 && o < l2;
 #pragma unroll
           for (int v = 0; v < COLS; ++v)
-            cw.w2[v][o] = real ? Elem<T>::load(static_cast<const T*>(a.W[1]) + static_cast<int64_t>(col + v) * a.ldw[1] + o) : 0.f;
+            cw.w2[v][o] = (real && v < nvalid) ? Elem<T>::load(static_cast<const T*>(a.W[1]) + static_cast<int64_t>(col + v) * a.ldw[1] + o) : 0.f;
         }
       }
       const T* pb[K];
@@ -130,10 +133,24 @@ __global__ __launch_bounds__(CT_THREADS) void fused_coltile_kernel(PredictArgs a
             }
 #pragma unroll
           for (int k = 0; k < K; ++k) Piece<T>::add(g.p[u][k], z);
+          // a width that is not a multiple of COLS: the last piece of a row ends in the padding of the row stride,
+          // whose contents are not ours; those elements count as zero
+          if (l1 % COLS != 0) {
+#pragma unroll
+            for (int v = 0; v < COLS; ++v) z[v] = v < nvalid ? z[v] : 0.f;
+          }
           if constexpr (NL == 1) {
             const int64_t row = row0 + t;
-            if (row < a.n && active)
-              __builtin_nontemporal_store(Piece<T>::pack(z), reinterpret_cast<v4u*>(static_cast<T*>(a.Y) + row * a.ldy + col));
+            if (row < a.n && active) {
+              T* yr = static_cast<T*>(a.Y) + row * a.ldy + col;
+              if (y_piece) {
+                __builtin_nontemporal_store(Piece<T>::pack(z), reinterpret_cast<v4u*>(yr));
+              } else {                 // Y rows that are not 16-byte aligned, or a partial last piece
+#pragma unroll
+                for (int v = 0; v < COLS; ++v)
+                  if (v < nvalid) Elem<T>::store(yr + v, z[v]);
+              }
+            }
           } else {
             float y[L2P];
 #pragma unroll
@@ -245,14 +262,13 @@ int ct_pick_many_dims(const PredictArgs& a, hipStream_t s) {
 }
 
 // Shapes the column-tiled kernel takes, whatever the element type: one or two layers, all operands of
-// one type, whole 16-byte pieces everywhere.
+// one type, projected tables whose rows start 16 bytes apart.
 inline bool ct_shape_ok(const PredictArgs& a, int cols) {
   if (a.n_layers > 2 || a.K < 1 || a.c_f > 8) return false;
   if (a.x_dtype != a.p_dtype || a.x_dtype != a.y_dtype) return false;
-  if (a.wout[0] % cols) return false;
+  // (any width: a row's last 16-byte piece may end in the padding of the row stride; a linear model's Y may have any alignment)
   for (int k = 0; k < a.K; ++k)
     if (!aligned(a.P[k], 16) || a.ldp[k] % cols) return false;
-  if (a.n_layers == 1 && (!aligned(a.Y, 16) || a.ldy % cols)) return false;
   return true;
 }
 

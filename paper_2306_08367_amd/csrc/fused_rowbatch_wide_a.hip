@@ -20,7 +20,7 @@ int try_rowbatch_wide(const PredictArgs& a, hipStream_t s) {
   // (any hidden width: the last 16-byte piece of a row may end in the padding of the row stride, which is a multiple
   // of four floats; a linear model's Y may have any alignment)
   const int l1 = a.wout[0];
-  if (l1 > 256 || l1 <= 16) return -1;                  // (up to 16: one row per 1..4 lanes, the lane-group kernel)
+  if (l1 > 256 || l1 < 12) return -1;                   // (below 12: one row per 1..3 lanes, the lane-group kernel)
   if (a.K > 4) return try_rowbatch_wide_f32_many_dims(a, s);
   if (l1 <= 32) return pick_k<float, 8, 16>(a, s);      // lanes beyond l_1 / 4 idle
   if (l1 <= 64) return pick_k<float, 16, 16>(a, s);     // (64 with 0 / 4 / 8 aligned fact columns and 1 / 2 / 4 outputs: the unrolled kernel, tried first)

@@ -12,9 +12,10 @@ int try_rowbatch_wide_bf16(const PredictArgs& a, hipStream_t s) {
     if (!aligned(a.P[k], 16) || a.ldp[k] % 8) return -1;
     if (a.prows[k] * a.ldp[k] * 2 > 0xffffffffLL) return -1;     // the kernels keep byte offsets into a table in 32 bits
   }
-  if (a.n_layers == 1 && (!aligned(a.Y, 16) || a.ldy % 8)) return -1;
+  // (any hidden width: the last 16-byte piece of a row may end in the padding of the row stride, which is a multiple
+  // of eight values; a linear model's Y may have any alignment)
   const int l1 = a.wout[0];
-  if (l1 % 8 || l1 > 512 || l1 <= 32) return -1;
+  if (l1 > 512 || l1 <= 32) return -1;
   if (l1 <= 64) return pick_k<bf16_t, 8, 4>(a, s);      // lanes beyond l_1 / 8 idle
   if (l1 <= 128) return pick_k<bf16_t, 16, 4>(a, s);
   if (l1 <= 256) return pick_k<bf16_t, 32, 4>(a, s);

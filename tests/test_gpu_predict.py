@@ -483,6 +483,11 @@ def test_non_fused_first_layer_over_many_rows(lq, shape):
     ("w50_30_1", 20_011, 4, (300, 200, 100), (8, 8, 8), (50, 30, 1), True),
     ("w130_64_7_k6", 3_003, 5, (30, 40, 50, 60, 70, 80), (4, 4, 4, 4, 4, 4), (130, 64, 7), False),   # two column parts, six tables
     ("w254_100", 1_111, 0, (100,), (16,), (254, 100), True),
+    ("w262_1", 2_049, 4, (300, 200), (8, 8), (262, 1), True),                 # column-tiled kernel
+    ("w1001_linear", 1_025, 0, (100, 50), (8, 8), (1_001,), False),
+    ("w770_7_k5", 777, 3, (30, 40, 50, 60, 70), (4, 4, 4, 4, 4), (770, 1), True),
+    ("w13_1", 20_011, 4, (300, 200, 100), (8, 8, 8), (13, 1), True),          # 12..16 columns: the row-batch kernel too
+    ("w16_2", 20_011, 0, (300, 200), (8, 8), (16, 2), False),
 ], ids=lambda s: s[0])
 def test_hidden_widths_that_are_not_multiples_of_four(lq, shape):
     """fp32 first layers of any width: with the row stride of the projected tables padded to four floats (what the
@@ -517,3 +522,33 @@ def test_hidden_widths_that_are_not_multiples_of_four(lq, shape):
         torch.cuda.synchronize()
         assert_close(Yw[:, 1:1 + l1], want, TOL_F32, f"{name}: misaligned Y")
         assert (Yw[:, 0] == -7).all() and (Yw[:, 1 + l1:] == -7).all()
+
+
+@pytest.mark.parametrize("shape", [
+    ("bf16_w44_1", 4_099, 4, (300, 200, 100), (8, 8, 8), (44, 1), True),
+    ("bf16_w100_4", 4_099, 0, (300, 200), (8, 8), (100, 4), False),
+    ("bf16_w100_linear", 2_049, 4, (300, 200), (8, 8), (100,), True),
+    ("bf16_w500_2", 1_025, 8, (100, 50), (8, 8), (500, 2), True),
+    ("bf16_w1001_1", 1_025, 0, (100, 50), (8, 8), (1_001, 1), True),          # column-tiled kernel
+], ids=lambda s: s[0])
+def test_bf16_hidden_widths_that_are_not_multiples_of_eight(lq, shape):
+    """The same for bf16 models (16-byte pieces of eight values): row stride padded to eight values, the padding filled
+    with NaN; then contiguous tables (general kernels).  Y in bf16 and in fp32."""
+    name, n, c_f, rows, cols, layers, bias = shape
+    k = c_f + sum(cols)
+    w = WL.make_predict(name, n, c_f, rows, cols, layers, seed=WL.SEED0 + 850 + len(name), device="cuda", dtype=torch.bfloat16,
+                        w_sigma=[1.0 / np.sqrt(k)] + [1.0 / np.sqrt(a) for a in layers[:-1]], bias=bias)
+    want = _oracle(w)
+    l1 = layers[0]
+    ld = (l1 + 7) // 8 * 8
+    padded = [torch.full((d.shape[0], ld), float("nan"), device="cuda", dtype=torch.bfloat16)[:, :l1] for d in w.dims]
+    lq.lq_project_dims(w.dims, w.weights[0], w.c_f, P=padded)
+    for yd in (torch.bfloat16, torch.float32):
+        Y = lq.lq_fused_join_predict(w.X, w.fks, padded, w.weights, w.biases, y_dtype=yd)
+        torch.cuda.synchronize()
+        assert_close(Y, want, TOL_BF16, f"{name}: padded row stride, Y {yd}")
+    P = [torch.empty((d.shape[0], l1), device="cuda", dtype=torch.bfloat16) for d in w.dims]
+    lq.lq_project_dims(w.dims, w.weights[0], w.c_f, P=P)
+    Yc = lq.lq_fused_join_predict(w.X, w.fks, P, w.weights, w.biases, y_dtype=torch.float32)
+    torch.cuda.synchronize()
+    assert_close(Yc, want, TOL_BF16, f"{name}: contiguous tables")
