@@ -30,7 +30,11 @@ int try_fused_deep(const PredictArgs& a, hipStream_t s) {
   const int l_out = a.wout[NL - 1];
   for (int j = 1; j < NL; ++j)
     if (j < NL - 1 || NL == 2 || l_out > 16) wide = std::max(wide, a.wout[j]);   // (an output layer of <= 16 is its own tile)
-  if (NL == 2 && l_out <= 4) return -1;               // the row-batch kernels are at least as fast there
+  // One to four outputs: the row-batch kernels are at least as fast while the fact table brings few columns of its
+  // own; with more of them x W_f is better off on the matrix cores (measured per 4e6 rows on a three-table star,
+  // row-batch -> this kernel: 64->1 with 12 fact columns 0.36 -> 0.28 ms, 64->4 0.55 -> 0.27, 128->4 0.90 -> 0.52,
+  // 64->1 with 20 (beyond the row-batch kernels' 16) 1.10 -> 0.34; 32->1 with 8: 0.12 against 0.14, stays there).
+  if (NL == 2 && l_out <= 4 && !(a.c_f > 8 || (a.c_f > 4 && l1 >= 64))) return -1;
   if (wide > 128) return -1;
   const int TH = wide <= 16 ? 1 : (wide <= 32 ? 2 : (wide <= 64 ? 4 : 8));
 
