@@ -176,8 +176,8 @@ int lq_fusion_advice(const lq_star* star, const lq_model* model, double queries_
  *       kernels need every P[k] 16-byte aligned with a row stride that is a multiple of 16 bytes (4 floats / 8 bf16
  *       values).  For fp32 models that is all: a hidden width that is not a multiple of 4 then runs as fast as its
  *       neighbours, the last 16-byte piece of a row ends in the stride's padding, whose contents are never used (so
- *       allocate [r_k x round_up(l_1, 4)] and pass cols = l_1, ld = round_up(l_1, 4)); bf16 widths that are not
- *       multiples of 8 take the general kernels
+ *       allocate [r_k x round_up(l_1, 4)] and pass cols = l_1, ld = round_up(l_1, 4)); for bf16 models the same
+ *       holds with multiples of 8 values when the model is linear or has one more layer of up to 4 outputs
  *   Y   [n x l_out], dtype f32 or bf16 (bf16 only for bf16 models), overwritten
  *   ws  workspace of lq_workspace_bytes(LQ_CALL_FUSED, ..) bytes, 256-byte
  *       aligned; only used with LQ_CHECK_FKS (may be NULL otherwise)
