@@ -275,6 +275,10 @@ int lq_masked_groupby_sum_static(int64_t n_fact, int32_t n_dims, const int32_t* 
  *             INT64_MAX and INT64_MIN;  counts int64 [G] or NULL
  *   G <= LQ_MAX_GROUPS (LDS accumulators while G * (3 * n_measures + 1) <= 8192, the output arrays
  *   themselves beyond that);  ws: lq_groupby_agg_workspace_bytes(..)
+ * A call without fact predicates that wants sums and counts only, of one column, two columns or one difference of
+ * two columns, over more than 8,192 accumulators, is the plain group-by: given a workspace of
+ * lq_groupby_agg_bucket_workspace_bytes(..) bytes (0: does not apply) it runs that call's bucketed form (SUM(a - b)
+ * as SUM(a) - SUM(b), exact in int64) -- same results, several times faster when many rows survive.
  */
 typedef struct { const int32_t* col; int32_t lo; int32_t hi; } lq_range_pred;
 #define LQ_MEASURE_COL 0
@@ -289,6 +293,9 @@ int lq_groupby_agg(int64_t n_fact, int32_t n_dims, const int32_t* const* fks, co
                    void* hip_stream);
 size_t lq_groupby_agg_workspace_bytes(int32_t n_dims, const int64_t* dim_rows,
                                       const int32_t* group_card, int32_t n_measures);
+size_t lq_groupby_agg_bucket_workspace_bytes(int64_t n_fact, int32_t n_dims, const int64_t* dim_rows,
+                                             const int32_t* group_card, int32_t n_measures,
+                                             const lq_measure* measures);
 
 /*
  * AVG per group from the SUM and COUNT results of lq_masked_groupby_sum / lq_groupby_agg on the same stream

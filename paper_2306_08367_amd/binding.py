@@ -123,6 +123,8 @@ def _load():
     lib.lq_groupby_agg.restype = ctypes.c_int
     lib.lq_groupby_agg_workspace_bytes.argtypes = [i32, ctypes.POINTER(i64), ctypes.POINTER(i32), i32]
     lib.lq_groupby_agg_workspace_bytes.restype = sz
+    lib.lq_groupby_agg_bucket_workspace_bytes.argtypes = [i64, i32, ctypes.POINTER(i64), ctypes.POINTER(i32), i32, vp]
+    lib.lq_groupby_agg_bucket_workspace_bytes.restype = sz
     lib.lq_project_dim_rows.argtypes = [ps, pmod, pm, i32, i64, i64, vp]
     lib.lq_project_dim_rows.restype = ctypes.c_int
     lib.lq_fusion_advice.argtypes = [ps, pmod, ctypes.c_double, ctypes.POINTER(lq_advice)]
@@ -891,7 +893,11 @@ def lq_groupby_agg(fks: Sequence[torch.Tensor], dim_rows: Sequence[int], dim_mas
     rows = (ctypes.c_int64 * max(1, K))(*[int(r) for r in dim_rows])
     card = (ctypes.c_int32 * max(1, K))(*[int(c) for c in group_card])
     if ws is None:
-        ws = _empty(stream, int(_lib.lq_groupby_agg_workspace_bytes(K, rows, card, M)), dtype=torch.uint8, device=dev)
+        need = int(_lib.lq_groupby_agg_workspace_bytes(K, rows, card, M))
+        if not preds and "min" not in want and "max" not in want and "sum" in want:
+            eff = (ctypes.c_int32 * max(1, K))(*[int(group_card[k]) if codes[k] is not None else 1 for k in range(K)])
+            need = max(need, int(_lib.lq_groupby_agg_bucket_workspace_bytes(n, K, rows, eff, M, ctypes.cast(ma, ctypes.c_void_p))))
+        ws = _empty(stream, need, dtype=torch.uint8, device=dev)
     ptr = lambda t: None if t is None else t.data_ptr()
     _check(_lib.lq_groupby_agg(n, K, _ptr_array(fks), rows, _ptr_array(masks), _ptr_array(codes), card,
                                len(preds), pa, M, ma, ptr(out["sum"]), ptr(out["min"]), ptr(out["max"]),

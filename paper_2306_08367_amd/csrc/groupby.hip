@@ -629,6 +629,21 @@ size_t groupby_bucket_ws_bytes(int64_t n, int32_t K, const int64_t* rows, int64_
   return round_up(groupby_ws_bytes(K, rows, G * (M + 1)), 256) + extra;
 }
 
+// sums[g] = two[g] - two[G + g]: SUM(a - b) from SUM(a) and SUM(b), exact in int64.
+__global__ __launch_bounds__(256) void group_diff_kernel(const long long* __restrict__ two, long long* __restrict__ sums, int64_t G) {
+  const int64_t stride = static_cast<int64_t>(gridDim.x) * blockDim.x;
+  for (int64_t g = static_cast<int64_t>(blockIdx.x) * blockDim.x + threadIdx.x; g < G; g += stride) sums[g] = two[g] - two[G + g];
+}
+
+int launch_group_diff(int64_t G, const int64_t* two, int64_t* sums, hipStream_t s) {
+  if (G == 0) return LQ_OK;
+  const int64_t blocks = std::min<int64_t>((G + 255) / 256, static_cast<int64_t>(num_cus()) * 8);
+  hipLaunchKernelGGL(group_diff_kernel, dim3(static_cast<unsigned>(blocks)), dim3(256), 0, s,
+                     reinterpret_cast<const long long*>(two), reinterpret_cast<long long*>(sums), G);
+  LQ_LAUNCH_CHECK("group_diff_kernel");
+  return LQ_OK;
+}
+
 int launch_group_avg(int32_t M, int64_t G, const int64_t* sums, const int64_t* counts, double* avgs, hipStream_t s) {
   const int64_t MG = static_cast<int64_t>(M) * G;
   if (MG == 0) return LQ_OK;

@@ -61,6 +61,7 @@ int launch_groupby(int64_t n, int32_t K, const int32_t* const* fks, const int64_
                    int64_t* counts, int32_t G, void* ws, size_t ws_bytes, bool reuse_tables, hipStream_t s);
 size_t groupby_ws_bytes(int32_t K, const int64_t* rows, int64_t n_acc);
 size_t groupby_bucket_ws_bytes(int64_t n, int32_t K, const int64_t* rows, int64_t G, int32_t M);
+int launch_group_diff(int64_t G, const int64_t* two, int64_t* sums, hipStream_t s);
 int launch_groupby_agg(int64_t n, int32_t K, const int32_t* const* fks, const int64_t* rows,
                        const uint8_t* const* mask, const int32_t* const* code, const int32_t* card,
                        int32_t n_preds, const lq_range_pred* preds, int32_t M, const lq_measure* meas,
@@ -612,6 +613,42 @@ size_t lq_groupby_agg_workspace_bytes(int32_t n_dims, const int64_t* dim_rows, c
   return groupby_ws_bytes(n_dims, dim_rows, G * (3 * n_measures + 1));
 }
 
+// Aggregates that the plain group-by can compute: one measure that is a column or a difference of two, or two
+// columns.  cols: the fact columns to sum; *sub: the result is the first sum minus the second.
+static bool agg_as_plain_sums(int32_t n_measures, const lq_measure* measures, const int32_t** cols, int* n_cols, bool* sub) {
+  *sub = false;
+  *n_cols = 0;
+  if (n_measures == 1 && measures[0].op == 2) {
+    cols[0] = measures[0].a; cols[1] = measures[0].b; *n_cols = 2; *sub = true;
+    return true;
+  }
+  if (n_measures > 2) return false;
+  for (int m = 0; m < n_measures; ++m) {
+    if (measures[m].op != 0) return false;
+    cols[(*n_cols)++] = measures[m].a;
+  }
+  return true;
+}
+
+size_t lq_groupby_agg_bucket_workspace_bytes(int64_t n_fact, int32_t n_dims, const int64_t* dim_rows,
+                                             const int32_t* group_card, int32_t n_measures, const lq_measure* measures) {
+  if (n_dims < 0 || n_dims > LQ_MAX_DIMS || (n_dims > 0 && !dim_rows) || !group_card || !measures) return 0;
+  if (n_measures < 1 || n_measures > LQ_MAX_MEASURES) return 0;
+  const int32_t* cols[2];
+  int n_cols = 0;
+  bool sub = false;
+  if (!agg_as_plain_sums(n_measures, measures, cols, &n_cols, &sub)) return 0;
+  int64_t G = 1;
+  for (int k = 0; k < n_dims; ++k) {
+    if (dim_rows[k] < 0 || group_card[k] < 1 || group_card[k] > 65535) return 0;
+    G *= group_card[k];
+    if (G > LQ_MAX_GROUPS) return 0;
+  }
+  const size_t big = groupby_bucket_ws_bytes(n_fact, n_dims, dim_rows, G, n_cols);
+  if (big == 0) return 0;
+  return round_up(big, 256) + (sub ? static_cast<size_t>(G) * 16 : 0);
+}
+
 int lq_groupby_agg(int64_t n_fact, int32_t n_dims, const int32_t* const* fks, const int64_t* dim_rows,
                    const uint8_t* const* dim_mask, const int32_t* const* dim_code, const int32_t* group_card,
                    int32_t n_preds, const lq_range_pred* preds, int32_t n_measures, const lq_measure* measures,
@@ -654,6 +691,27 @@ int lq_groupby_agg(int64_t n_fact, int32_t n_dims, const int32_t* const* fks, co
   int rc;
   if ((flags & LQ_CHECK_FKS) && n_dims > 0 && n_fact > 0)
     if ((rc = check_groupby_fks(n_fact, n_dims, fks, dim_rows, dim_mask, dim_code, group_card, ws, ws_bytes, s))) return rc;
+  // Sums and counts without fact predicates over more groups than LDS holds, given the large workspace: the plain
+  // group-by computes them in its bucketed form (SUM(a - b) as SUM(a) - SUM(b), exact in int64).
+  if (n_preds == 0 && !mins && !maxs && sums && n_fact > 0) {
+    const int32_t* cols[2];
+    int n_cols = 0;
+    bool sub = false;
+    if (agg_as_plain_sums(n_measures, measures, cols, &n_cols, &sub)) {
+      const size_t big = round_up(groupby_bucket_ws_bytes(n_fact, n_dims, dim_rows, G, n_cols), 256);
+      if (big > 0 && ws_bytes >= big + (sub ? static_cast<size_t>(G) * 16 : 0)) {
+        const bool reuse = (flags & LQ_REUSE_SIDE_TABLES) != 0;
+        if (!sub)
+          return launch_groupby(n_fact, n_dims, fks, dim_rows, dim_mask, dim_code, group_card, nullptr, n_cols, cols, sums,
+                                counts, static_cast<int32_t>(G), ws, big, reuse, s);
+        int64_t* two = reinterpret_cast<int64_t*>(static_cast<uint8_t*>(ws) + big);
+        if ((rc = launch_groupby(n_fact, n_dims, fks, dim_rows, dim_mask, dim_code, group_card, nullptr, 2, cols, two, counts,
+                                 static_cast<int32_t>(G), ws, big, reuse, s)))
+          return rc;
+        return launch_group_diff(G, two, sums, s);
+      }
+    }
+  }
   return launch_groupby_agg(n_fact, n_dims, fks, dim_rows, dim_mask, dim_code, group_card, n_preds, preds,
                             n_measures, measures, sums, mins, maxs, counts, static_cast<int32_t>(G), ws,
                             (flags & LQ_REUSE_SIDE_TABLES) != 0, s);

@@ -117,3 +117,36 @@ def test_long_scan_of_the_specialised_aggregate(lq):
     columns at once instead of one step late; two joins, two predicates, a product, ragged row count."""
     fks, rows, masks, codes, card, c = _case(80, 20_000_003, (2_556, 300), (7, 1))
     _check(lq, fks, rows, masks, codes, card, [(c["disc"], 1, 3), (c["qty"], 1, 24)], [("mul", c["price"], c["disc"])])
+
+
+@pytest.mark.parametrize("ops,want", [
+    ((("sub", 0, 1),), ("sum", "count")),            # SUM(a - b): the profit measure of the fourth query group
+    ((("col", 0, None),), ("sum",)),
+    ((("col", 0, None), ("col", 2, None)), ("sum", "count")),
+], ids=["sub", "col", "two_cols"])
+def test_many_group_sums_without_predicates_take_the_plain_group_by(lq, ops, want):
+    """Sums and counts without fact predicates over more groups than LDS holds: with the default (large) workspace the
+    call runs the plain group-by's bucketed form, with the small one the aggregate's own scan; both equal the oracle."""
+    import ctypes
+    r = np.random.default_rng(77 + len(ops))
+    n = 400_003
+    rows, card = [300, 260, 900], [250, 240, 1]
+    fks = [r.integers(0, a, size=n).astype(np.int32) for a in rows]
+    fks[1][::97] = -1
+    codes = [r.integers(0, card[k], size=rows[k]).astype(np.int32) if card[k] > 1 else None for k in range(3)]
+    masks = [None, None, (r.random(rows[2]) < 0.6).astype(np.uint8)]
+    cols = [r.integers(-50_000, 100_000, size=n).astype(np.int32) for _ in range(3)]
+    meas = [(op, cols[a], None if b is None else cols[b]) for op, a, b in ops]
+    ref = O.groupby_agg(fks, rows, masks, codes, card, [], meas)
+    dev = lambda a: None if a is None else torch.from_numpy(a).cuda()
+    d_fks, d_masks, d_codes = [dev(f) for f in fks], [dev(m) for m in masks], [dev(c) for c in codes]
+    d_meas = [(op, dev(a), dev(b)) for op, a, b in meas]
+    rows_c = (ctypes.c_int64 * 3)(*rows); card_c = (ctypes.c_int32 * 3)(*card)
+    small = torch.empty(int(lq.binding._lib.lq_groupby_agg_workspace_bytes(3, rows_c, card_c, len(meas))), dtype=torch.uint8,
+                        device="cuda")
+    for kw in ({}, {"ws": small}):
+        out = lq.lq_groupby_agg(d_fks, rows, d_masks, d_codes, card, [], d_meas, want=want, **kw)
+        torch.cuda.synchronize()
+        np.testing.assert_array_equal(out["sum"].cpu().numpy(), ref[0])
+        if "count" in want:
+            np.testing.assert_array_equal(out["count"].cpu().numpy(), ref[3])
