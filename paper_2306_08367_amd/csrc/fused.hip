@@ -42,7 +42,7 @@ __global__ __launch_bounds__(GEN_THREADS) void fused_generic_kernel(PredictArgs 
       for (int k = 0; k < a.K; ++k)
         acc += load_as_f32(a.P[k], static_cast<int64_t>(a.fk[k][row]) * a.ldp[k] + j, a.p_dtype);
       if (a.bias[0]) acc += load_as_f32(a.bias[0], j, a.x_dtype);
-      if (last0) store_from_f32(a.Y, row * a.ldy + j, a.y_dtype, acc);
+      if (last0) store_from_f32(a.Y, row * a.ldy + j, a.y_dtype, a.relu_linear ? fmaxf(acc, 0.f) : acc);
       else cur[r * maxw + j] = fmaxf(acc, 0.f);
     }
     for (int layer = 1; layer < a.n_layers; ++layer) {
@@ -261,7 +261,7 @@ int launch_vec_inst(const PredictArgs& a, hipStream_t s) {
   // One pass per workgroup: workgroups then sweep the fact table in launch order, which streams
   // from HBM measurably faster than a strided persistent loop.
   const int64_t blocks = std::min<int64_t>(n_pass, 0x7fffffffLL);
-  if (blocks <= 0) return LQ_OK;
+  if (blocks <= 0 || a.probe) return LQ_OK;
   constexpr bool can_xv = sizeof(TX) == 4 && CF > 0 && CF % 4 == 0;
   if (can_xv && a.c_f == CF && aligned(a.X, 16) && a.ldx % 4 == 0)
     hipLaunchKernelGGL((fused_vec_kernel<TX, TP, TY, VEC, LPR, CF, NL, L2, can_xv>),
@@ -368,6 +368,71 @@ int launch_fused(const PredictArgs& a, hipStream_t s) {
   rc = try_fused_tile(a, s);
   if (rc >= 0) return rc;
   return launch_generic(a, s);
+}
+
+// Does one of the specialised kernels take this shape?  (The per-wavefront tile kernel and the shape-agnostic
+// kernel, which take anything, do not count.)  Nothing is launched.
+bool fused_kernel_covers(const PredictArgs& a0) {
+  PredictArgs a = a0;
+  a.probe = 1;
+  hipStream_t s = nullptr;
+  return try_rowbatch64(a, s) >= 0 || try_fused_deep(a, s) >= 0 || try_rowbatch_wide(a, s) >= 0 || try_fused_bf16(a, s) >= 0 ||
+         try_fused_deep_bf16(a, s) >= 0 || try_fused_lds(a, s) >= 0 || try_vec(a, s) >= 0 || try_fused_coltile(a, s) >= 0;
+}
+
+int launch_gemm(const void* A, int64_t lda, const void* B, int64_t ldb, void* C, int64_t ldc, const void* bias, int64_t M,
+                int32_t N, int32_t Kd, int relu, int32_t in_dtype, int32_t out_dtype, hipStream_t s);
+
+// Workspace bytes per 256 fact rows of the layered form below (two activation buffers as wide as the widest
+// hidden layer, rows 16 bytes apart at the least).
+size_t fused_layered_bytes_per_256(const PredictArgs& a) {
+  const size_t es = dtype_size(a.x_dtype);
+  size_t widest = 0;
+  for (int j = 0; j + 1 < a.n_layers; ++j) widest = std::max(widest, round_up(static_cast<size_t>(a.wout[j]) * es, 16));
+  return 2 * 256 * widest;
+}
+
+// Models that none of the specialised kernels takes (a wide first layer followed by a wide or a third layer, say
+// 1,024 -> 1,024 or 512 -> 64 -> 1): the join stage runs as a linear operator with the ReLU in its store
+// (z = x W_f + sum_k P_k[fk_k] + b_1 written once, in chunks of rows that fit the workspace), the later layers as
+// dense products on the matrix cores.  Still no joined table, and the first layer's k x l_1 product stays pre-fused.
+int launch_fused_layered(const PredictArgs& a, void* ws, size_t ws_bytes, hipStream_t s) {
+  const size_t es = dtype_size(a.x_dtype);
+  const size_t per256 = fused_layered_bytes_per_256(a);
+  int64_t chunk = static_cast<int64_t>(ws_bytes / per256) * 256;
+  chunk = std::min<int64_t>(chunk, static_cast<int64_t>(round_up(static_cast<size_t>(a.n), 256)));
+  if (chunk < 256) return fail(LQ_ERR_WORKSPACE, "workspace too small for one 256-row chunk of the layered form");
+  const size_t half = static_cast<size_t>(chunk) / 256 * (per256 / 2);
+  uint8_t* buf[2] = {static_cast<uint8_t*>(ws), static_cast<uint8_t*>(ws) + half};
+  for (int64_t r0 = 0; r0 < a.n; r0 += chunk) {
+    const int64_t m = std::min<int64_t>(chunk, a.n - r0);
+    PredictArgs f = a;
+    f.n = m;
+    f.X = a.X ? static_cast<const uint8_t*>(a.X) + static_cast<size_t>(r0) * a.ldx * es : nullptr;
+    for (int k = 0; k < a.K; ++k) f.fk[k] = a.fk[k] + r0;
+    f.n_layers = 1;
+    f.relu_linear = 1;
+    f.y_dtype = a.x_dtype;
+    int64_t ld = static_cast<int64_t>(round_up(static_cast<size_t>(a.wout[0]) * es, 16) / es);
+    f.Y = buf[0]; f.ldy = ld;
+    int rc = try_rowbatch_wide(f, s);
+    if (rc < 0) rc = try_fused_coltile(f, s);
+    if (rc < 0) rc = launch_generic(f, s);
+    if (rc) return rc;
+    int cur = 0;
+    for (int j = 1; j < a.n_layers; ++j) {
+      const bool last = j == a.n_layers - 1;
+      void* C = last ? static_cast<void*>(static_cast<uint8_t*>(a.Y) + static_cast<size_t>(r0) * a.ldy * dtype_size(a.y_dtype))
+                     : static_cast<void*>(buf[cur ^ 1]);
+      const int64_t ldc = last ? a.ldy : static_cast<int64_t>(round_up(static_cast<size_t>(a.wout[j]) * es, 16) / es);
+      rc = launch_gemm(buf[cur], ld, a.W[j], a.ldw[j], C, ldc, a.bias[j], m, a.wout[j], a.win[j], last ? 0 : 1, a.x_dtype,
+                       last ? a.y_dtype : a.x_dtype, s);
+      if (rc) return rc;
+      ld = ldc;
+      cur ^= 1;
+    }
+  }
+  return LQ_OK;
 }
 
 // The tile kernel alone (testing / tuning aid), generic kernel if it does not cover the shape.

@@ -151,6 +151,7 @@ int launch_inst(const PredictArgs& a, hipStream_t s) {
   const int64_t npass = (a.n + 15) / 16;
   const int64_t blocks = std::min<int64_t>((npass + 3) / 4, static_cast<int64_t>(num_cus()) * 8);
   const dim3 grid(static_cast<unsigned>(blocks)), block(BF_THREADS);
+  if (a.probe) return LQ_OK;
   if (a.c_f > 0) hipLaunchKernelGGL((fused_bf16_kernel<KB, NL, TY, true>), grid, block, 0, s, a);
   else hipLaunchKernelGGL((fused_bf16_kernel<KB, NL, TY, false>), grid, block, 0, s, a);
   LQ_LAUNCH_CHECK("fused_bf16_kernel");

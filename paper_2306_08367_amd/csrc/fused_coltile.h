@@ -140,6 +140,10 @@ __global__ __launch_bounds__(CT_THREADS) void fused_coltile_kernel(PredictArgs a
             for (int v = 0; v < COLS; ++v) z[v] = v < nvalid ? z[v] : 0.f;
           }
           if constexpr (NL == 1) {
+            if (a.relu_linear) {
+#pragma unroll
+              for (int v = 0; v < COLS; ++v) z[v] = fmaxf(z[v], 0.f);
+            }
             const int64_t row = row0 + t;
             if (row < a.n && active) {
               T* yr = static_cast<T*>(a.Y) + row * a.ldy + col;
@@ -215,6 +219,7 @@ int ct_launch(const PredictArgs& a, hipStream_t s) {
   const int64_t batches = (a.n + RB - 1) / RB;
   const int64_t blocks = std::min<int64_t>(batches, 4LL * num_cus());
   const size_t lds = NL == 2 ? static_cast<size_t>(nw) * RB * L2P * sizeof(float) : 0;
+  if (a.probe) return LQ_OK;
   hipLaunchKernelGGL((fused_coltile_kernel<T, K, CFC, NL, L2P>), dim3(static_cast<unsigned>(blocks)), dim3(nw * 64),
                      lds, s, a, tiles, RB);
   LQ_LAUNCH_CHECK("fused_coltile_kernel");

@@ -58,7 +58,7 @@ int try_fused_deep(const PredictArgs& a, hipStream_t s) {
 
   const int64_t n_steps = (a.n + 15) / 16;
   const int64_t blocks = (n_steps + DEEP_WAVES - 1) / DEEP_WAVES;    // the launcher caps them at one resident set
-  if (blocks <= 0) return LQ_OK;
+  if (blocks <= 0 || a.probe) return LQ_OK;
   if (NL == 2) return launch_deep_nl<2>(a, L, lds, blocks, vec_y, T1, PARTS, TH, s);
   if (NL == 3) return launch_deep_3(a, L, lds, blocks, vec_y, T1, PARTS, TH, s);
   return launch_deep_4(a, L, lds, blocks, vec_y, T1, PARTS, TH, s);

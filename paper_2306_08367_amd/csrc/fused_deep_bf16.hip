@@ -302,7 +302,7 @@ int try_fused_deep_bf16(const PredictArgs& a, hipStream_t s) {
 
   const int64_t npass = (a.n + 15) / 16;
   const int64_t blocks = (npass + 3) / 4;             // capped below at one resident set: every wavefront stages once
-  if (blocks <= 0) return LQ_OK;
+  if (blocks <= 0 || a.probe) return LQ_OK;
 #define LQ_DBF(KB_, TH_, NL_)                                                                           \
   do {                                                                                                  \
     const void* fn = reinterpret_cast<const void*>(&fused_deep_bf16_kernel<KB_, TH_, NL_>);              \

@@ -174,6 +174,7 @@ __global__ __launch_bounds__(FL_THREADS) void fused_lds_kernel(PredictArgs a, Ld
 
 template <int L>
 int launch_l(const PredictArgs& a, const LdsPlan& pl, size_t lds, hipStream_t s) {
+  if (a.probe) return (a.K <= 4 || L == 1) ? LQ_OK : -1;
   const dim3 block(FL_THREADS);
 #define LQ_FL(KT_)                                                                                      \
   do {                                                                                                  \

@@ -229,6 +229,7 @@ template <int K, int CFC, int NL, int L2>
 int launch_inst(const PredictArgs& a, hipStream_t s) {
   const int64_t nb = (a.n + 63) / 64;
   const int64_t blocks = std::min<int64_t>((nb + 3) / 4, static_cast<int64_t>(num_cus()) * ((NL == 2 && L2 > 1) ? 2 : 3));
+  if (a.probe) return LQ_OK;
   hipLaunchKernelGGL((fused_rowbatch64_kernel<K, CFC, NL, L2>), dim3(static_cast<unsigned>(blocks)),
                      dim3(RB_THREADS), 0, s, a);
   LQ_LAUNCH_CHECK("fused_rowbatch64_kernel");

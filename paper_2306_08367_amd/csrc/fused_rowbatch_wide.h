@@ -171,6 +171,10 @@ __device__ __forceinline__ void compute_group(const PredictArgs& a, int c, bool 
       for (int v = 0; v < COLS; ++v) z[v] = v < nvalid ? z[v] : 0.f;
     }
     if constexpr (NL == 1) {
+      if (a.relu_linear) {
+#pragma unroll
+        for (int v = 0; v < COLS; ++v) z[v] = fmaxf(z[v], 0.f);
+      }
       const int64_t row = row0 + group_base + t;
       if (row < a.n && active) {
         T* yr = static_cast<T*>(a.Y) + row * a.ldy + COLS * c;
@@ -312,6 +316,7 @@ template <typename T, int LPR, int K, int CFC, int NL, int L2P>
 int launch_inst(const PredictArgs& a, hipStream_t s) {
   const int64_t nb = (a.n + 63) / 64;
   const int64_t blocks = std::min<int64_t>((nb + 3) / 4, static_cast<int64_t>(num_cus()) * waves_per_simd(Piece<T>::COLS, K, CFC, L2P));
+  if (a.probe) return LQ_OK;
   hipLaunchKernelGGL((fused_rowbatch_wide_kernel<T, LPR, K, CFC, NL, L2P>), dim3(static_cast<unsigned>(blocks)),
                      dim3(RBW_THREADS), 0, s, a);
   LQ_LAUNCH_CHECK("fused_rowbatch_wide_kernel");

@@ -54,6 +54,9 @@ int launch_gemm(const void* A, int64_t lda, const void* B, int64_t ldb, void* C,
                 const void* bias, int64_t M, int32_t N, int32_t Kd, int relu, int32_t in_dtype,
                 int32_t out_dtype, hipStream_t s);
 int launch_fused_generic(const PredictArgs& a, hipStream_t s);
+bool fused_kernel_covers(const PredictArgs& a);
+size_t fused_layered_bytes_per_256(const PredictArgs& a);
+int launch_fused_layered(const PredictArgs& a, void* ws, size_t ws_bytes, hipStream_t s);
 int launch_fused_tile(const PredictArgs& a, hipStream_t s);
 int launch_groupby(int64_t n, int32_t K, const int32_t* const* fks, const int64_t* rows,
                    const uint8_t* const* mask, const int32_t* const* code, const int32_t* card,
@@ -380,12 +383,27 @@ int lq_fused_join_predict(const lq_star* star, const lq_model* model, const lq_m
     if ((rc = run_fk_check(a.n, a.K, star->fks, rows, false, ws, ws_bytes, s))) return rc;
   if (flags & FLAG_FORCE_GENERIC) return launch_fused_generic(a, s);
   if (flags & LQ_FORCE_TILE) return launch_fused_tile(a, s);
+  // A model of two or more layers that no specialised kernel takes, and a workspace with room for a chunk of
+  // activations behind its first 256 bytes: the join stage as a linear operator, then dense products.
+  if (a.n_layers >= 2 && a.n > 0 && ws && aligned(ws, 256) && ws_bytes >= 256 + fused_layered_bytes_per_256(a) &&
+      !fused_kernel_covers(a))
+    return launch_fused_layered(a, static_cast<uint8_t*>(ws) + 256, ws_bytes - 256, s);
   return launch_fused(a, s);
 }
 
 size_t lq_workspace_bytes(int which_call, const lq_star* star, const lq_model* model,
                           int64_t chunk_rows) {
-  if (which_call == LQ_CALL_FUSED) return 256;
+  if (which_call == LQ_CALL_FUSED) {
+    // 256 bytes for the checked call; with chunk_rows > 0 and a model of two or more layers also two activation
+    // buffers of that many rows, which the layered form of the join stage uses when no specialised kernel takes
+    // the model (see lq_fused_join_predict)
+    if (chunk_rows < 1 || !model || !model->W || model->n_layers < 2 || model->n_layers > LQ_MAX_LAYERS) return 256;
+    const size_t es = dtype_size(model->W[0].dtype);
+    size_t widest = 0;
+    for (int j = 0; j + 1 < model->n_layers; ++j)
+      widest = std::max(widest, round_up(static_cast<size_t>(model->W[j].cols) * es, 16));
+    return 256 + 2 * round_up(static_cast<size_t>(chunk_rows), 256) * widest;
+  }
   if (which_call != LQ_CALL_MATERIALIZED || !star || !model || !model->W || chunk_rows < 1) return 0;
   if (model->n_layers < 1 || model->n_layers > LQ_MAX_LAYERS) return 0;
   const size_t es = dtype_size(model->W[0].dtype);

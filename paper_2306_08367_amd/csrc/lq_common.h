@@ -70,6 +70,9 @@ struct PredictArgs {
   int32_t x_dtype;  // dtype of X, W, bias
   int32_t p_dtype;
   int32_t y_dtype;
+  int32_t relu_linear;   // a one-layer call stores max(z, 0): the first layer of a model whose later layers run as dense
+                         // products (honoured by the wide row-batch, column-tiled and shape-agnostic kernels only)
+  int32_t probe;         // a specialised kernel that would take the shape returns LQ_OK without launching
 };
 
 // Kernel launchers implemented in the .hip files.  Each returns an lq_status.

@@ -157,3 +157,46 @@ def test_wide_operator_fk_indexing_is_bit_exact(lq):
         Y = lq.lq_fused_join_predict(w.X, w.fks, P, w.weights, w.biases)
         torch.cuda.synchronize()
         np.testing.assert_array_equal(Y.cpu().double().numpy(), want)
+
+
+LAYERED = [
+    # name, n, c_f, dim_rows, k, layers, dtype, bias
+    ("l512_64_1", 3_001, 4, S2_ROWS, 256, (512, 64, 1), torch.float32, True),
+    ("l1024_1024", 1_025, 0, S2_ROWS, 256, (1024, 1024), torch.float32, False),
+    ("l300_64_1", 2_049, 4, (300, 200), 64, (300, 64, 1), torch.float32, True),
+    ("l512_17", 4_099, 8, (300, 200, 100), 96, (512, 17), torch.float32, True),
+    ("l262_40_3_ragged", 777, 3, (30, 20), 32, (262, 40, 3), torch.float32, True),
+    ("l256_300_2_wide_later_layer", 1_111, 4, (100, 200), 32, (256, 300, 2), torch.float32, False),
+    ("l2048_256_one_row", 1, 4, (30, 20), 32, (2048, 256), torch.float32, True),
+    ("bf16_l1024_16", 2_049, 0, (100, 200), 32, (1024, 16), torch.bfloat16, True),
+    ("bf16_l1024_64_1", 1_025, 4, (100, 200), 32, (1024, 64, 1), torch.bfloat16, False),
+]
+
+
+@pytest.mark.parametrize("shape", LAYERED, ids=[s[0] for s in LAYERED])
+def test_wide_models_that_no_fused_kernel_takes(lq, shape):
+    """A wide first layer followed by a wide or a third layer: with a workspace (the binding brings one) the join stage
+    runs as a linear operator with the ReLU in its store and the later layers as dense products, in chunks of rows;
+    without one, and with a workspace of a single 256-row chunk, the same results from the general kernels / from many
+    chunks.  All against the oracle."""
+    name, n, c_f, rows, k, layers, dt, bias = shape
+    cols = _cols(k - c_f, len(rows))
+    w = WL.make_predict(name, n, c_f, rows, cols, layers, seed=WL.SEED0 + 4400 + len(name), dtype=dt,
+                        w_sigma=_sigmas(k, layers), bias=bias)
+    want = _oracle(w)
+    w = to_dev(w)
+    tol = TOL_BF16 if dt == torch.bfloat16 else TOL_F32
+    P = lq.lq_project_dims(w.dims, w.weights[0], w.c_f, p_dtype=dt)
+    Y = lq.lq_fused_join_predict(w.X, w.fks, P, w.weights, w.biases, y_dtype=torch.float32)
+    torch.cuda.synchronize()
+    assert_close(Y, want, tol, f"{name}: default workspace")
+    es = 2 if dt == torch.bfloat16 else 4
+    one_chunk = 256 + 2 * 256 * ((max(layers[:-1]) * es + 15) // 16 * 16)
+    Y1 = lq.lq_fused_join_predict(w.X, w.fks, P, w.weights, w.biases, y_dtype=torch.float32,
+                                  ws=torch.empty(one_chunk, dtype=torch.uint8, device="cuda"))
+    torch.cuda.synchronize()
+    assert_close(Y1, want, tol, f"{name}: chunks of 256 rows")
+    Y0 = lq.lq_fused_join_predict(w.X, w.fks, P, w.weights, w.biases, y_dtype=torch.float32,
+                                  ws=torch.empty(256, dtype=torch.uint8, device="cuda"))
+    torch.cuda.synchronize()
+    assert_close(Y0, want, tol, f"{name}: no room for activations, general kernels")
