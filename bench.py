@@ -142,7 +142,7 @@ def main():
     ap.add_argument("--no-extras", action="store_true", help="only the headline workload and its CPU baseline")
     ap.add_argument("--no-cpu", action="store_true", help="skip every CPU oracle baseline")
     ap.add_argument("--only", default="", help="run a single leg for profiling: fused|yardsticks|c1|linear|groupby|groupby_many|"
-                    "groupby16|c4|c5|deep|tree|treesweep|keymap|agg|domain|sweep|setting2|sfsweep|materialized")
+                    "groupby16|c4|c5|deep|wide_models|tree|treesweep|keymap|agg|domain|sweep|setting2|sfsweep|materialized")
     args = ap.parse_args()
     if args.gpus != 1:
         sys.exit("bench.py: this build is single-GPU by design (no collectives, no sharding); "
@@ -552,6 +552,30 @@ def main():
         out["deeper_models"] = {"fact_rows": nd, "cells": cells}
     if want("deep"):
         guarded("deeper_models", leg_deep)
+
+    # ---------------------------------------------------------------- wide models (layered form: linear join stage + dense layers)
+    def leg_wide_models():
+        nw = 1_000_000
+        cells = {}
+        for name, dt, layers in (("f32_1024_1024", torch.float32, (1024, 1024)), ("f32_512_64_1", torch.float32, (512, 64, 1)),
+                                 ("f32_2048_256", torch.float32, (2048, 256)), ("bf16_1024_64_1", torch.bfloat16, (1024, 64, 1))):
+            ww = WL.make_predict(name, nw, 4, (1_000, 10_000, 100_000), (32, 32, 32), layers, seed=WL.SEED0 + 960, dtype=dt, device=dev,
+                                 w_sigma=[0.05] * len(layers))
+            Pw = lq.lq_project_dims(ww.dims, ww.weights[0], 4, p_dtype=dt)
+            Yw = torch.empty((nw, layers[-1]), dtype=dt, device=dev)
+            ws_l = torch.empty(lq.lq_workspace_bytes(lq.binding.LQ_CALL_FUSED, ww.k, ww.weights, 1 << 17), dtype=torch.uint8, device=dev)
+            t = time_call(lambda: lq.lq_fused_join_predict(ww.X, ww.fks, Pw, ww.weights, None, Y=Yw, ws=ws_l), 5, 1)
+            wsm = torch.empty(lq.lq_workspace_bytes(MAT, ww.k, ww.weights, 1 << 17), dtype=torch.uint8, device=dev)
+            mt = time_call(lambda: lq.lq_materialized_join_predict(ww.X, ww.dims, ww.fks, ww.weights, None, Y=Yw, ws=wsm), 3, 1)
+            later = 2.0 * sum(a * b for a, b in zip(layers[:-1], layers[1:])) * nw
+            cells[name] = {"fused_ms": round(t[2], 3), "rows_per_s": nw / (t[2] * 1e-3), "later_layers_TFLOPs": later / (t[2] * 1e-3) / 1e12,
+                           "materialized_ms": round(mt[2], 3), "fused_speedup": mt[2] / t[2], "workspace_MB": ws_l.numel() / 1e6}
+            del ww, Pw, Yw, ws_l, wsm
+        out["wide_models"] = {"fact_rows": nw, "cells": cells,
+                              "note": "models no fused kernel takes: the join stage as a linear operator with the ReLU in its store, "
+                                      "later layers as dense products, in chunks of 131,072 rows"}
+    if want("wide_models"):
+        guarded("wide_models", leg_wide_models)
 
     # ---------------------------------------------------------------- group-by at 16x the fact rows
     def leg_groupby16():
