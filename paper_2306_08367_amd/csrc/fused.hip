@@ -42,7 +42,10 @@ __global__ __launch_bounds__(GEN_THREADS) void fused_generic_kernel(PredictArgs 
       for (int k = 0; k < a.K; ++k)
         acc += load_as_f32(a.P[k], static_cast<int64_t>(a.fk[k][row]) * a.ldp[k] + j, a.p_dtype);
       if (a.bias[0]) acc += load_as_f32(a.bias[0], j, a.x_dtype);
-      if (last0) store_from_f32(a.Y, row * a.ldy + j, a.y_dtype, a.relu_linear ? fmaxf(acc, 0.f) : acc);
+      if (last0) {
+        if (a.accumulate_y) acc += load_as_f32(a.Y, row * a.ldy + j, a.y_dtype);
+        store_from_f32(a.Y, row * a.ldy + j, a.y_dtype, a.relu_linear ? fmaxf(acc, 0.f) : acc);
+      }
       else cur[r * maxw + j] = fmaxf(acc, 0.f);
     }
     for (int layer = 1; layer < a.n_layers; ++layer) {
@@ -347,6 +350,10 @@ int try_fused_deep_bf16(const PredictArgs& a, hipStream_t s);
 int try_fused_lds(const PredictArgs& a, hipStream_t s);
 int try_fused_coltile(const PredictArgs& a, hipStream_t s);
 
+int launch_linear_stage(const PredictArgs& f, hipStream_t s);
+int launch_gemm(const void* A, int64_t lda, const void* B, int64_t ldb, void* C, int64_t ldc, const void* bias, int64_t M,
+                int32_t N, int32_t Kd, int relu, int32_t in_dtype, int32_t out_dtype, hipStream_t s);
+
 int launch_fused(const PredictArgs& a, hipStream_t s) {
   if (a.n == 0) return LQ_OK;
   int rc = try_rowbatch64(a, s);
@@ -365,6 +372,7 @@ int launch_fused(const PredictArgs& a, hipStream_t s) {
   if (rc >= 0) return rc;
   rc = try_fused_coltile(a, s);       // first layers wider than 256 (fp32) / 512 (bf16) columns, one or two layers
   if (rc >= 0) return rc;
+  if (a.n_layers == 1) return launch_linear_stage(a, s);   // (a wide linear operator with many fact columns)
   rc = try_fused_tile(a, s);
   if (rc >= 0) return rc;
   return launch_generic(a, s);
@@ -392,6 +400,32 @@ size_t fused_layered_bytes_per_256(const PredictArgs& a) {
   return 2 * 256 * widest;
 }
 
+// The join stage as a linear operator (one layer, optionally with the ReLU in its store) on the kernels that take any
+// width.  When the fact table has more columns of its own than they take, x W_f + b_1 is first written to Y by a dense
+// product and the kernels add the gathered rows to it.
+int launch_linear_stage(const PredictArgs& f, hipStream_t s) {
+  int rc = try_rowbatch_wide(f, s);
+  if (rc < 0) rc = try_fused_coltile(f, s);
+  if (rc >= 0) return rc;
+  if (f.c_f > 0 && f.K > 0 && f.x_dtype == f.y_dtype && f.x_dtype == f.p_dtype) {
+    PredictArgs g = f;
+    g.c_f = 0; g.X = nullptr; g.bias[0] = nullptr; g.accumulate_y = 1; g.probe = 1;
+    if (try_rowbatch_wide(g, s) >= 0 || try_fused_coltile(g, s) >= 0) {
+      rc = launch_gemm(f.X, f.ldx, f.W[0], f.ldw[0], f.Y, f.ldy, f.bias[0], f.n, f.wout[0], f.c_f, 0, f.x_dtype, f.y_dtype, s);
+      if (rc) return rc;
+      g.probe = 0;
+      rc = try_rowbatch_wide(g, s);
+      if (rc < 0) rc = try_fused_coltile(g, s);
+      if (rc >= 0) return rc;
+    }
+  }
+  if (!f.relu_linear && !f.accumulate_y) {       // (the per-wavefront tile kernel knows neither)
+    rc = try_fused_tile(f, s);
+    if (rc >= 0) return rc;
+  }
+  return launch_generic(f, s);
+}
+
 // Models that none of the specialised kernels takes (a wide first layer followed by a wide or a third layer, say
 // 1,024 -> 1,024 or 512 -> 64 -> 1): the join stage runs as a linear operator with the ReLU in its store
 // (z = x W_f + sum_k P_k[fk_k] + b_1 written once, in chunks of rows that fit the workspace), the later layers as
@@ -415,9 +449,7 @@ int launch_fused_layered(const PredictArgs& a, void* ws, size_t ws_bytes, hipStr
     f.y_dtype = a.x_dtype;
     int64_t ld = static_cast<int64_t>(round_up(static_cast<size_t>(a.wout[0]) * es, 16) / es);
     f.Y = buf[0]; f.ldy = ld;
-    int rc = try_rowbatch_wide(f, s);
-    if (rc < 0) rc = try_fused_coltile(f, s);
-    if (rc < 0) rc = launch_generic(f, s);
+    int rc = launch_linear_stage(f, s);
     if (rc) return rc;
     int cur = 0;
     for (int j = 1; j < a.n_layers; ++j) {

@@ -171,11 +171,21 @@ __device__ __forceinline__ void compute_group(const PredictArgs& a, int c, bool 
       for (int v = 0; v < COLS; ++v) z[v] = v < nvalid ? z[v] : 0.f;
     }
     if constexpr (NL == 1) {
+      const int64_t row = row0 + group_base + t;
+      if (a.accumulate_y && row < a.n && active) {
+        const T* yo = static_cast<const T*>(a.Y) + row * a.ldy + COLS * c;
+        if (y_piece) {
+          Piece<T>::add(*reinterpret_cast<const v4u*>(yo), z);
+        } else {
+#pragma unroll
+          for (int v = 0; v < COLS; ++v)
+            if (v < nvalid) z[v] += Elem<T>::load(yo + v);
+        }
+      }
       if (a.relu_linear) {
 #pragma unroll
         for (int v = 0; v < COLS; ++v) z[v] = fmaxf(z[v], 0.f);
       }
-      const int64_t row = row0 + group_base + t;
       if (row < a.n && active) {
         T* yr = static_cast<T*>(a.Y) + row * a.ldy + COLS * c;
         if (y_piece) {

@@ -72,6 +72,8 @@ struct PredictArgs {
   int32_t y_dtype;
   int32_t relu_linear;   // a one-layer call stores max(z, 0): the first layer of a model whose later layers run as dense
                          // products (honoured by the wide row-batch, column-tiled and shape-agnostic kernels only)
+  int32_t accumulate_y;  // a one-layer call adds what Y already holds to z (x W_f + b_1 put there by a dense product when the
+                         // fact table has more columns of its own than the kernel takes); same three kernels
   int32_t probe;         // a specialised kernel that would take the shape returns LQ_OK without launching
 };
 

@@ -168,6 +168,11 @@ LAYERED = [
     ("l262_40_3_ragged", 777, 3, (30, 20), 32, (262, 40, 3), torch.float32, True),
     ("l256_300_2_wide_later_layer", 1_111, 4, (100, 200), 32, (256, 300, 2), torch.float32, False),
     ("l2048_256_one_row", 1, 4, (30, 20), 32, (2048, 256), torch.float32, True),
+    # more fact columns than the wide kernels take: x W_f + b_1 by a dense product, the gathered rows added to it
+    ("l512_1_cf12", 3_001, 12, S2_ROWS, 256, (512, 1), torch.float32, True),
+    ("l512_64_1_cf33", 2_049, 33, (300, 200), 97, (512, 64, 1), torch.float32, True),
+    ("l262_5_cf20_ragged", 1_025, 20, (30, 20), 52, (262, 5), torch.float32, False),
+    ("bf16_l1024_1_cf12", 2_049, 12, (100, 200), 44, (1024, 1), torch.bfloat16, True),
     ("bf16_l1024_16", 2_049, 0, (100, 200), 32, (1024, 16), torch.bfloat16, True),
     ("bf16_l1024_64_1", 1_025, 4, (100, 200), 32, (1024, 64, 1), torch.bfloat16, False),
 ]
@@ -200,3 +205,27 @@ def test_wide_models_that_no_fused_kernel_takes(lq, shape):
                                   ws=torch.empty(256, dtype=torch.uint8, device="cuda"))
     torch.cuda.synchronize()
     assert_close(Y0, want, tol, f"{name}: no room for activations, general kernels")
+
+
+@pytest.mark.parametrize("shape", [
+    ("linear_l1024_cf20", 2_049, 20, (300, 200), 84, (1024,), torch.float32, True),
+    ("linear_l300_cf64", 1_025, 64, (30, 20), 96, (300,), torch.float32, False),
+    ("linear_l130_cf17", 4_099, 17, (300, 200, 100), 65, (130,), torch.float32, True),
+    ("bf16_linear_l1024_cf12", 1_025, 12, (100, 200), 44, (1024,), torch.bfloat16, True),
+], ids=lambda s: s[0])
+def test_wide_linear_operators_with_many_fact_columns(lq, shape):
+    """A linear operator whose fact table brings more columns of its own than the wide kernels take: x W_f + b goes to Y
+    by a dense product and the join stage adds the gathered rows to it (Y of the model's type); with Y of another type
+    the general kernels run.  Against the oracle."""
+    name, n, c_f, rows, k, layers, dt, bias = shape
+    cols = _cols(k - c_f, len(rows))
+    w = WL.make_predict(name, n, c_f, rows, cols, layers, seed=WL.SEED0 + 4500 + len(name), dtype=dt,
+                        w_sigma=_sigmas(k, layers), bias=bias)
+    want = _oracle(w)
+    w = to_dev(w)
+    tol = TOL_BF16 if dt == torch.bfloat16 else TOL_F32
+    P = lq.lq_project_dims(w.dims, w.weights[0], w.c_f, p_dtype=dt)
+    for yd in ((dt, torch.float32) if dt == torch.bfloat16 else (dt,)):
+        Y = lq.lq_fused_join_predict(w.X, w.fks, P, w.weights, w.biases, y_dtype=yd)
+        torch.cuda.synchronize()
+        assert_close(Y, want, tol, f"{name}: Y {yd}")
