@@ -326,7 +326,7 @@ def lq_fused_join_predict(X: Optional[torch.Tensor], fks: Sequence[torch.Tensor]
         Y = _empty(stream, (n, weights[-1].shape[1]), dtype=y_dtype or weights[0].dtype, device=dev)
     star = _Star(n, X, None, fks)
     model = _Model(weights, biases)
-    if ws is None and len(weights) >= 2 and max(int(w.shape[1]) for w in weights[:-1]) > 128 and n > 0:
+    if ws is None and len(weights) >= 2 and max(int(w.shape[1]) for w in weights) > 128 and n > 0:
         # a wide model that no fused kernel may take: room for the layered form (activations of a chunk of rows,
         # at most half a gigabyte); the library uses it only if it needs to
         per_row = int(_lib.lq_workspace_bytes(LQ_CALL_FUSED, ctypes.byref(star.c), ctypes.byref(model.c), 256) - 256) // 256

@@ -15,7 +15,7 @@ int try_rowbatch_wide_bf16(const PredictArgs& a, hipStream_t s) {
   // (any hidden width: the last 16-byte piece of a row may end in the padding of the row stride, which is a multiple
   // of eight values; a linear model's Y may have any alignment)
   const int l1 = a.wout[0];
-  if (l1 > 512 || l1 <= 32) return -1;
+  if (l1 > 512 || l1 < 16) return -1;
   if (l1 <= 64) return pick_k<bf16_t, 8, 4>(a, s);      // lanes beyond l_1 / 8 idle
   if (l1 <= 128) return pick_k<bf16_t, 16, 4>(a, s);
   if (l1 <= 256) return pick_k<bf16_t, 32, 4>(a, s);
