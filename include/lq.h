@@ -388,7 +388,8 @@ int lq_fused_join_tree(const lq_star* star, const lq_tree* tree, const void* con
  * tables[k] equals the number of nodes dimension k owns on the path to leaf j"; the sum over the
  * dimensions followed by `== h` is then a bitwise AND of one mask row per dimension, and the join
  * stage gathers l / 8 bytes per dimension instead of l.
- *   lq_tree_mask_words(l)   words (uint64) per mask row: ceil(l / 64); bits past l are 0
+ *   lq_tree_mask_words(l)   words (uint64) per mask row: ceil(l / 64), rounded up to an even number from
+ *                           three words on (rows of 16-byte pieces); bits past l are 0
  *   tables  as written by lq_tree_project_dims;  masks  host array of K device pointers,
  *           r_k * words uint64 each;  star->dims gives r_k and c_k, star->fact.cols the number of
  *           joined columns before the first dimension's (no data is read through star)

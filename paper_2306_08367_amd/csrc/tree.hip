@@ -1201,7 +1201,7 @@ int project_slices(const TreeArgs& t, const DimSlice* sl, int n, hipStream_t s) 
 // Mask rows of the table rows in sl[k].out (sl[k].D is not read).
 int compress_slices(const TreeArgs& t, const DimSlice* sl, u64* const* masks, int n, hipStream_t s) {
   if (n == 0) return LQ_OK;
-  const int32_t words = static_cast<int32_t>((static_cast<int64_t>(t.l) + 63) / 64);
+  const int32_t words = static_cast<int32_t>(lq_tree_mask_words(t.l));
   CompressArgs ca{};
   int64_t max_rows = 0;
   for (int k = 0; k < n; ++k) {
@@ -1422,7 +1422,13 @@ int lq_materialized_join_tree(const lq_star* star, const lq_tree* tree, int32_t*
   return LQ_OK;
 }
 
-int64_t lq_tree_mask_words(int32_t n_leaves) { return n_leaves < 1 ? 0 : (static_cast<int64_t>(n_leaves) + 63) / 64; }
+// ceil(l / 64), rounded up to an even number from three words on: mask rows then start 16 bytes apart and the
+// join reads them two words at a time (129 leaves: four words, the last all zero).
+int64_t lq_tree_mask_words(int32_t n_leaves) {
+  if (n_leaves < 1) return 0;
+  const int64_t w = (static_cast<int64_t>(n_leaves) + 63) / 64;
+  return (w >= 3 && (w & 1)) ? w + 1 : w;
+}
 
 int lq_tree_compress_tables(const lq_star* star, const lq_tree* tree, const void* const* tables,
                             uint64_t* const* masks, void* hip_stream) {
