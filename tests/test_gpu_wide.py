@@ -205,6 +205,11 @@ def test_wide_models_that_no_fused_kernel_takes(lq, shape):
                                   ws=torch.empty(256, dtype=torch.uint8, device="cuda"))
     torch.cuda.synchronize()
     assert_close(Y0, want, tol, f"{name}: no room for activations, general kernels")
+    if dt == torch.bfloat16:
+        Yb = lq.lq_fused_join_predict(w.X, w.fks, P, w.weights, w.biases)          # Y in bf16
+        torch.cuda.synchronize()
+        assert Yb.dtype == torch.bfloat16
+        assert_close(Yb, want, tol, f"{name}: bf16 output")
 
 
 @pytest.mark.parametrize("shape", [
