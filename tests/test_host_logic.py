@@ -347,3 +347,39 @@ def test_keymap64_entry_points_reject_bad_arguments():
     assert lib.lq_keymap64_insert(FAKE, nbytes, FAKE, 10, 2**31, 0, None) == 2
     assert lib.lq_keymap64_lookup(FAKE, nbytes, None, 10, FAKE, None) == 1
     assert lib.lq_keymap64_lookup(FAKE, 8, FAKE, 10, FAKE, None) == 4
+
+
+def test_bucket_workspace_sizes_follow_the_rows_and_the_groups():
+    """lq_groupby_bucket_workspace_bytes: 0 where the bucketed form does not apply, otherwise the small workspace plus
+    two slots of 4 (1 + measures) bytes per fact row (plus 1,024 slots per bucket and the counters)."""
+    b = _binding()
+    rows, card = [300, 280], [250, 240]                       # 60,000 groups
+    small = b.lq_groupby_workspace_bytes(rows, card, 1)
+    for n in (1, 1_000, 2_000_003):
+        big = b.lq_groupby_bucket_workspace_bytes(n, rows, card, 1)
+        assert big > small + 2 * 8 * n
+        assert big < small + 2 * 8 * n + 8_192 * (4 + 1_026 * 8) + 4_096
+    assert b.lq_groupby_bucket_workspace_bytes(1_000, rows, card, 2) > b.lq_groupby_bucket_workspace_bytes(1_000, rows, card, 1)
+    assert b.lq_groupby_bucket_workspace_bytes(1_000, rows, [30, 28], 1) == 0        # 840 groups: LDS accumulators
+    assert b.lq_groupby_bucket_workspace_bytes(1_000, rows, card, 3) == 0            # the specialised scans take two measures
+    assert b.lq_groupby_bucket_workspace_bytes(0, rows, card, 1) == 0
+    assert b.lq_groupby_bucket_workspace_bytes(1 << 31, rows, card, 1) == 0
+    assert b.lq_groupby_bucket_workspace_bytes(1_000, [70_000, 70_000], [65_535, 16_000], 1) == 0   # more than 8,192 buckets
+
+
+def test_fused_workspace_grows_with_the_chunk_only_for_models_of_two_or_more_layers():
+    import torch
+    b = _binding()
+    W1 = [torch.zeros((40, 1_000)), torch.zeros((1_000, 300)), torch.zeros((300, 2))]
+    assert b.lq_workspace_bytes(b.LQ_CALL_FUSED, 40, W1[:1], 4_096) == 256
+    assert b.lq_workspace_bytes(b.LQ_CALL_FUSED, 40, W1, 0) == 256
+    # two activation buffers as wide as the widest hidden layer (1,000 floats), rows rounded up to 256
+    assert b.lq_workspace_bytes(b.LQ_CALL_FUSED, 40, W1, 4_000) == 256 + 2 * 4_096 * 4_000
+    Wb = [w.to(torch.bfloat16) for w in W1]
+    assert b.lq_workspace_bytes(b.LQ_CALL_FUSED, 40, Wb, 256) == 256 + 2 * 256 * 2_000
+
+
+def test_tree_mask_rows_have_an_even_number_of_words_from_three_on():
+    b = _binding()
+    got = [b.lq_tree_mask_words(l) for l in (0, 1, 64, 65, 128, 129, 192, 193, 256, 257, 1_024, 1_025)]
+    assert got == [0, 1, 1, 2, 2, 4, 4, 4, 4, 6, 16, 18]
