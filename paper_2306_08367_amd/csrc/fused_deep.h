@@ -434,7 +434,8 @@ int launch_deep_nl(const PredictArgs& a, const DeepLds& L, size_t lds, int64_t b
     else if (T1 == 2) LQ_DEEP_K(2, 1, TH_); else if (T1 == 4) LQ_DEEP_K(4, 1, TH_);                         \
     else LQ_DEEP_K(8, 1, TH_);                                                                              \
   } while (0)
-  if (TH == 1) LQ_DEEP_T1(1); else if (TH == 2) LQ_DEEP_T1(2); else if (TH == 4) LQ_DEEP_T1(4); else LQ_DEEP_T1(8);
+  if (TH == 1) LQ_DEEP_T1(1); else if (TH == 2) LQ_DEEP_T1(2); else if (TH == 4) LQ_DEEP_T1(4); else if (TH == 8) LQ_DEEP_T1(8);
+  else if (T1 == 2) LQ_DEEP_K(2, 1, 16); else LQ_DEEP_K(4, 1, 16);     // later layers of 129..256 units: first layers up to 64 only
 #undef LQ_DEEP_T1
 #undef LQ_DEEP_K
 #undef LQ_DEEP

@@ -35,8 +35,8 @@ int try_fused_deep(const PredictArgs& a, hipStream_t s) {
   // row-batch -> this kernel: 64->1 with 12 fact columns 0.36 -> 0.28 ms, 64->4 0.55 -> 0.27, 128->4 0.90 -> 0.52,
   // 64->1 with 20 (beyond the row-batch kernels' 16) 1.10 -> 0.34; 32->1 with 8: 0.12 against 0.14, stays there).
   if (NL == 2 && l_out <= 4 && !(a.c_f > 8 || (a.c_f > 4 && l1 >= 64))) return -1;
-  if (wide > 128) return -1;
-  const int TH = wide <= 16 ? 1 : (wide <= 32 ? 2 : (wide <= 64 ? 4 : 8));
+  if (wide > 256 || (wide > 128 && l1 > 64)) return -1;     // (later layers of 129..256 units next to first layers of up to 64)
+  const int TH = wide <= 16 ? 1 : (wide <= 32 ? 2 : (wide <= 64 ? 4 : (wide <= 128 ? 8 : 16)));
 
   DeepLds L{};
   L.kc = (a.c_f + 3) / 4;

@@ -552,3 +552,24 @@ def test_bf16_hidden_widths_that_are_not_multiples_of_eight(lq, shape):
     Yc = lq.lq_fused_join_predict(w.X, w.fks, P, w.weights, w.biases, y_dtype=torch.float32)
     torch.cuda.synchronize()
     assert_close(Yc, want, TOL_BF16, f"{name}: contiguous tables")
+
+
+@pytest.mark.parametrize("shape", [
+    ("w64_200", 4_099, 4, (300, 200, 100), (8, 8, 8), (64, 200), True),
+    ("w64_256_1", 2_049, 0, (300, 200), (8, 8), (64, 256, 1), False),
+    ("w30_130_7_ragged_k6", 1_025, 5, (30, 40, 50, 60, 70, 80), (4, 4, 4, 4, 4, 4), (30, 130, 7), True),
+    ("w64_256_256_3", 777, 20, (100,), (16,), (64, 256, 256, 3), True),
+    ("w16_129", 63, 1, (10, 20), (3, 3), (16, 129), False),
+], ids=lambda s: s[0])
+def test_later_layers_of_129_to_256_units_next_to_narrow_first_layers(lq, shape):
+    """First layers of up to 64 columns followed by layers of 129 .. 256 units: sixteen 16-unit tiles per later layer
+    on the matrix-core kernel.  Against the oracle."""
+    name, n, c_f, rows, cols, layers, bias = shape
+    k = c_f + sum(cols)
+    w = WL.make_predict(name, n, c_f, rows, cols, layers, seed=WL.SEED0 + 900 + len(name), device="cuda",
+                        w_sigma=[1.0 / np.sqrt(k)] + [1.0 / np.sqrt(a) for a in layers[:-1]], bias=bias)
+    want = _oracle(w)
+    P = lq.lq_project_dims(w.dims, w.weights[0], w.c_f)
+    Y = lq.lq_fused_join_predict(w.X, w.fks, P, w.weights, w.biases, ws=torch.empty(256, dtype=torch.uint8, device="cuda"))
+    torch.cuda.synchronize()
+    assert_close(Y, want, TOL_F32, name)

@@ -72,7 +72,7 @@ def test_random_deeper_models(lq):
     matrix-core kernel (one or two column parts, one to four tables prefetched and up to four more gathered inside
     the step, up to 64 fact columns, later layers up to 128 wide)."""
     first = [20, 24, 32, 36, 48, 64, 72, 100, 128, 132, 200, 256]
-    later = [1, 2, 3, 4, 5, 8, 16, 17, 24, 33, 48, 64, 100, 128]
+    later = [1, 2, 3, 4, 5, 8, 16, 17, 24, 33, 48, 64, 100, 128, 130, 200, 256]
     for seed in _seeds(7, 400):
         r = np.random.default_rng(seed)
         K = int(r.integers(1, 9))
