@@ -326,11 +326,13 @@ def lq_fused_join_predict(X: Optional[torch.Tensor], fks: Sequence[torch.Tensor]
         Y = _empty(stream, (n, weights[-1].shape[1]), dtype=y_dtype or weights[0].dtype, device=dev)
     star = _Star(n, X, None, fks)
     model = _Model(weights, biases)
-    if ws is None and len(weights) >= 2 and max(int(w.shape[1]) for w in weights) > 128 and n > 0:
-        # a wide model that no fused kernel may take: room for the layered form (activations of a chunk of rows,
-        # at most half a gigabyte); the library uses it only if it needs to
+    if ws is None and n > 0 and len(weights) >= 2 and (max(int(w.shape[1]) for w in weights) > 128 or
+                                                       (X is not None and X.shape[1] > 16)):
+        # a model that the fused kernels may not take (a layer wider than 128, more than 16 fact columns): room for the
+        # layered form (activations of a chunk of rows, at most a quarter of a gigabyte); the library uses it only if
+        # it needs to
         per_row = int(_lib.lq_workspace_bytes(LQ_CALL_FUSED, ctypes.byref(star.c), ctypes.byref(model.c), 256) - 256) // 256
-        rows = max(4096, min(n, (512 << 20) // max(per_row, 1)))
+        rows = max(4096, min(n, (256 << 20) // max(per_row, 1)))
         ws = _empty(stream, int(_lib.lq_workspace_bytes(LQ_CALL_FUSED, ctypes.byref(star.c), ctypes.byref(model.c), rows)),
                     dtype=torch.uint8, device=dev)
     if ws is None and (flags & LQ_CHECK_FKS):

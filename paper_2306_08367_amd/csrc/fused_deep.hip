@@ -16,7 +16,7 @@ int try_fused_deep(const PredictArgs& a, hipStream_t s) {
   const int NL = a.n_layers;
   if (NL < 2 || NL > LQ_MAX_LAYERS) return -1;
   const int l1 = a.wout[0];
-  if (l1 < 5 || l1 > 256) return -1;        // (any width: a row's last 16-byte piece may end in the padding of the row stride)
+  if (l1 < 1 || l1 > 256) return -1;        // (any width: a row's last 16-byte piece may end in the padding of the row stride)
   if (a.c_f > 64 || a.K < 1 || a.K > LQ_MAX_DIMS) return -1;
   for (int k = 0; k < a.K; ++k) {
     if (!aligned(a.P[k], 16) || a.ldp[k] % 4) return -1;

@@ -385,8 +385,12 @@ int lq_fused_join_predict(const lq_star* star, const lq_model* model, const lq_m
   if (flags & LQ_FORCE_TILE) return launch_fused_tile(a, s);
   // A model of two or more layers that no specialised kernel takes, and a workspace with room for a chunk of
   // activations behind its first 256 bytes: the join stage as a linear operator, then dense products.
-  if (a.n_layers >= 2 && a.n > 0 && ws && aligned(ws, 256) && ws_bytes >= 256 + fused_layered_bytes_per_256(a) &&
-      !fused_kernel_covers(a))
+  // (Only for models with a layer wider than 128 or more than 16 fact columns: narrow models that no specialised
+  // kernel takes are better off in one pass of the per-wavefront tile kernel than in a dense product per layer.)
+  int widest = 0;
+  for (int j = 0; j < a.n_layers; ++j) widest = std::max(widest, a.wout[j]);
+  if (a.n_layers >= 2 && (widest > 128 || a.c_f > 16) && a.n > 0 && ws && aligned(ws, 256) &&
+      ws_bytes >= 256 + fused_layered_bytes_per_256(a) && !fused_kernel_covers(a))
     return launch_fused_layered(a, static_cast<uint8_t*>(ws) + 256, ws_bytes - 256, s);
   return launch_fused(a, s);
 }
