@@ -180,8 +180,9 @@ int lq_fusion_advice(const lq_star* star, const lq_model* model, double queries_
  *       holds with multiples of 8 values when the model is linear or has one more layer of up to 4 outputs
  *   Y   [n x l_out], dtype f32 or bf16 (bf16 only for bf16 models), overwritten
  *   ws  256-byte aligned, may be NULL.  Its first 256 bytes serve LQ_CHECK_FKS.  A model of two or more
- *       layers that none of the specialised kernels takes (a wide first layer followed by a wide or a third
- *       layer, e.g. 1024 -> 1024 or 512 -> 64 -> 1) runs in a layered form when ws holds at least
+ *       layers that none of the specialised kernels takes and that has a layer wider than 128 or more than 16
+ *       fact columns (a wide first layer followed by a wide or a third layer, e.g. 1024 -> 1024 or
+ *       512 -> 64 -> 1) runs in a layered form when ws holds at least
  *       lq_workspace_bytes(LQ_CALL_FUSED, star, model, 256) bytes: the join stage as a linear operator that
  *       stores ReLU(z) for a chunk of rows, then the later layers as dense products on the matrix cores, chunk by
  *       chunk (lq_workspace_bytes(LQ_CALL_FUSED, star, model, chunk_rows) sizes it for a chunk; more rows per
