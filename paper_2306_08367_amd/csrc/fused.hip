@@ -368,6 +368,7 @@ int launch_fused(const PredictArgs& a, hipStream_t s) {
   if (rc >= 0) return rc;
   rc = try_fused_lds(a, s);           // linear models with 1 / 2 / 4 outputs whose small projected tables fit LDS
   if (rc >= 0) return rc;
+  if (a.n_layers == 1 && a.wout[0] > 128) return launch_linear_stage(a, s);   // wide linear operators: in passes if need be
   rc = try_vec(a, s);
   if (rc >= 0) return rc;
   rc = try_fused_coltile(a, s);       // first layers wider than 256 (fp32) / 512 (bf16) columns, one or two layers
@@ -384,8 +385,11 @@ bool fused_kernel_covers(const PredictArgs& a0) {
   PredictArgs a = a0;
   a.probe = 1;
   hipStream_t s = nullptr;
+  // (the lane-group kernel does not count for first layers wider than 128: it is latency-bound there, 10.6 ms per
+  // 1e6 rows at bf16 512 -> 4 with 12 fact columns against 1.5 ms in passes)
   return try_rowbatch64(a, s) >= 0 || try_fused_deep(a, s) >= 0 || try_rowbatch_wide(a, s) >= 0 || try_fused_bf16(a, s) >= 0 ||
-         try_fused_deep_bf16(a, s) >= 0 || try_fused_lds(a, s) >= 0 || try_vec(a, s) >= 0 || try_fused_coltile(a, s) >= 0;
+         try_fused_deep_bf16(a, s) >= 0 || try_fused_lds(a, s) >= 0 || (a.wout[0] <= 128 && try_vec(a, s) >= 0) ||
+         try_fused_coltile(a, s) >= 0;
 }
 
 int launch_gemm(const void* A, int64_t lda, const void* B, int64_t ldb, void* C, int64_t ldc, const void* bias, int64_t M,
@@ -401,26 +405,55 @@ size_t fused_layered_bytes_per_256(const PredictArgs& a) {
 }
 
 // The join stage as a linear operator (one layer, optionally with the ReLU in its store) on the kernels that take any
-// width.  When the fact table has more columns of its own than they take, x W_f + b_1 is first written to Y by a dense
-// product and the kernels add the gathered rows to it.
+// width.  When the fact table has more columns of its own, or the star more tables, than they take in one go, the
+// stage is cut into passes over Y: x W_f + b_1 by a dense product, then up to four tables at a time added to what Y
+// holds (accumulate_y), the ReLU in the last pass only.
 int launch_linear_stage(const PredictArgs& f, hipStream_t s) {
-  int rc = try_rowbatch_wide(f, s);
-  if (rc < 0) rc = try_fused_coltile(f, s);
+  auto wide_kernels = [&](const PredictArgs& g) {
+    int rc = try_rowbatch_wide(g, s);
+    if (rc < 0) rc = try_fused_coltile(g, s);
+    return rc;
+  };
+  int rc = wide_kernels(f);
   if (rc >= 0) return rc;
-  if (f.c_f > 0 && f.K > 0 && f.x_dtype == f.y_dtype && f.x_dtype == f.p_dtype) {
-    PredictArgs g = f;
-    g.c_f = 0; g.X = nullptr; g.bias[0] = nullptr; g.accumulate_y = 1; g.probe = 1;
-    if (try_rowbatch_wide(g, s) >= 0 || try_fused_coltile(g, s) >= 0) {
-      rc = launch_gemm(f.X, f.ldx, f.W[0], f.ldw[0], f.Y, f.ldy, f.bias[0], f.n, f.wout[0], f.c_f, 0, f.x_dtype, f.y_dtype, s);
-      if (rc) return rc;
-      g.probe = 0;
-      rc = try_rowbatch_wide(g, s);
-      if (rc < 0) rc = try_fused_coltile(g, s);
-      if (rc >= 0) return rc;
+  if (f.K > 0 && f.x_dtype == f.y_dtype && f.x_dtype == f.p_dtype) {
+    constexpr int GROUP = 4;
+    const int n_groups = (f.K + GROUP - 1) / GROUP;
+    // pass p takes tables [GROUP p, GROUP p + GROUP); the fact term goes with the first pass if that pass takes it,
+    // else ahead of it as a dense product
+    auto pass = [&](int p, bool fact_here, bool probe) {
+      PredictArgs g = f;
+      g.K = std::min(GROUP, f.K - GROUP * p);
+      for (int k = 0; k < g.K; ++k) {
+        g.P[k] = f.P[GROUP * p + k]; g.ldp[k] = f.ldp[GROUP * p + k]; g.prows[k] = f.prows[GROUP * p + k];
+        g.fk[k] = f.fk[GROUP * p + k];
+      }
+      const bool first = p == 0 && fact_here;
+      if (!first) { g.c_f = 0; g.X = nullptr; g.bias[0] = nullptr; g.accumulate_y = 1; }
+      g.relu_linear = (p == n_groups - 1) ? f.relu_linear : 0;
+      g.probe = probe ? 1 : 0;
+      return g;
+    };
+    bool fact_here = wide_kernels(pass(0, true, true)) >= 0;
+    bool ok = fact_here || wide_kernels(pass(0, false, true)) >= 0;
+    for (int p = 1; p < n_groups && ok; ++p) ok = wide_kernels(pass(p, fact_here, true)) >= 0;
+    if (ok) {
+      if (!fact_here) {
+        if (f.c_f > 0) {
+          rc = launch_gemm(f.X, f.ldx, f.W[0], f.ldw[0], f.Y, f.ldy, f.bias[0], f.n, f.wout[0], f.c_f, 0, f.x_dtype, f.y_dtype, s);
+          if (rc) return rc;
+        } else {
+          fact_here = true;       // (no fact columns: the first pass carries the bias and starts Y)
+        }
+      }
+      for (int p = 0; p < n_groups; ++p)
+        if ((rc = wide_kernels(pass(p, fact_here, false)))) return rc < 0 ? fail(LQ_ERR_UNSUPPORTED, "linear stage: a pass lost its kernel") : rc;
+      return LQ_OK;
     }
   }
-  if (!f.relu_linear && !f.accumulate_y) {       // (the per-wavefront tile kernel knows neither)
-    rc = try_fused_tile(f, s);
+  if (!f.relu_linear && !f.accumulate_y) {       // (the lane-group and the per-wavefront tile kernel know neither)
+    rc = try_vec(f, s);
+    if (rc < 0) rc = try_fused_tile(f, s);
     if (rc >= 0) return rc;
   }
   return launch_generic(f, s);

@@ -173,6 +173,10 @@ LAYERED = [
     ("l512_64_1_cf33", 2_049, 33, (300, 200), 97, (512, 64, 1), torch.float32, True),
     ("l262_5_cf20_ragged", 1_025, 20, (30, 20), 52, (262, 5), torch.float32, False),
     ("bf16_l1024_1_cf12", 2_049, 12, (100, 200), 44, (1024, 1), torch.bfloat16, True),
+    # more tables than the wide kernels take in one go: passes of up to four tables over the activations
+    ("bf16_l2048_8_k5_cf16", 1_025, 16, (30, 40, 50, 60, 70), 76, (2048, 8), torch.bfloat16, True),
+    ("bf16_l256_16_k8_cf40", 2_049, 40, (30, 40, 50, 60, 70, 80, 90, 100), 104, (256, 16), torch.bfloat16, False),
+    ("l1024_64_1_k7_cf12", 1_025, 12, (30, 40, 50, 60, 70, 80, 90), 68, (1024, 64, 1), torch.float32, True),
     ("bf16_l1024_16", 2_049, 0, (100, 200), 32, (1024, 16), torch.bfloat16, True),
     ("bf16_l1024_64_1", 1_025, 4, (100, 200), 32, (1024, 64, 1), torch.bfloat16, False),
 ]
@@ -217,6 +221,8 @@ def test_wide_models_that_no_fused_kernel_takes(lq, shape):
     ("linear_l300_cf64", 1_025, 64, (30, 20), 96, (300,), torch.float32, False),
     ("linear_l130_cf17", 4_099, 17, (300, 200, 100), 65, (130,), torch.float32, True),
     ("bf16_linear_l1024_cf12", 1_025, 12, (100, 200), 44, (1024,), torch.bfloat16, True),
+    ("bf16_linear_l1024_k6", 1_025, 0, (30, 40, 50, 60, 70, 80), 48, (1024,), torch.bfloat16, True),
+    ("linear_l600_k8_cf20", 777, 20, (30, 40, 50, 60, 70, 80, 90, 100), 84, (600,), torch.float32, False),
 ], ids=lambda s: s[0])
 def test_wide_linear_operators_with_many_fact_columns(lq, shape):
     """A linear operator whose fact table brings more columns of its own than the wide kernels take: x W_f + b goes to Y
