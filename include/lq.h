@@ -323,8 +323,9 @@ size_t lq_groupby_workspace_bytes(int32_t n_dims, const int64_t* dim_rows,
                                   const int32_t* group_card, int32_t n_measures);
 /* Workspace with which lq_masked_groupby_sum over n_fact rows and more than 8,192 accumulators takes the
  * bucketed form (see group_card above): the size above plus two slots of 4 (1 + n_measures) bytes per fact
- * row and a little per bucket.  0 when that form does not apply (8,192 accumulators or fewer, more than two
- * measures, 2^31 rows or more, more than 8,192 buckets); the call then works with the smaller workspace. */
+ * row and a little per bucket (three or four measures run as two such calls of two measures and are sized for
+ * those).  0 when that form does not apply (8,192 accumulators or fewer, 2^31 rows or more, more than 8,192
+ * buckets); the call then works with the smaller workspace. */
 size_t lq_groupby_bucket_workspace_bytes(int64_t n_fact, int32_t n_dims, const int64_t* dim_rows,
                                          const int32_t* group_card, int32_t n_measures);
 

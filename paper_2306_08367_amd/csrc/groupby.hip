@@ -622,9 +622,14 @@ bool bucket_plan(int64_t n, int64_t G, int32_t M, BucketArgs* b, size_t* bytes) 
 }
 
 // Workspace that lets a group-by of n rows over more than 8,192 accumulators take the bucketed form (0: it does not apply).
+// (Three or four measures run as two calls of two: sized for those, provided two measures alone pass the LDS limit.)
 size_t groupby_bucket_ws_bytes(int64_t n, int32_t K, const int64_t* rows, int64_t G, int32_t M) {
   BucketArgs b{};
   size_t extra = 0;
+  if (M > 2) {
+    if (M > LQ_MAX_MEASURES || 3 * G <= GROUPBY_LDS_ACCUMULATORS) return 0;
+    M = 2;
+  }
   if (!bucket_plan(n, G, M, &b, &extra)) return 0;
   return round_up(groupby_ws_bytes(K, rows, G * (M + 1)), 256) + extra;
 }

@@ -301,7 +301,53 @@ __global__ __launch_bounds__(SCAN_THREADS) void scan_fast_kernel(FastArgs a, int
   }
   __syncthreads();
 
-  while (v < v_end) {
+  // No grouping dimension (a filtered sum, one group): every survivor would hit the same accumulator, so a lane adds up
+  // its own rows in registers and a wavefront sends one sum per measure to LDS at the end.
+  constexpr bool SINGLE = NBL + NBG == 0;
+  if constexpr (SINGLE) {
+    long long own[MM];
+#pragma unroll
+    for (int m = 0; m < MM; ++m) own[m] = 0;
+    long long own_rows = 0;
+    while (v < v_end) {
+      const int64_t vn = v + SCAN_THREADS;
+      if (vn < v_end) {
+#pragma unroll
+        for (int k = 0; k < ND; ++k) nxt[k] = __builtin_nontemporal_load(reinterpret_cast<const v4i*>(a.fk[k]) + vn);
+      }
+      bool alive[4];
+#pragma unroll
+      for (int q = 0; q < 4; ++q) {
+        int32_t j[ND];
+#pragma unroll
+        for (int k = 0; k < ND; ++k) j[k] = cur[k][q];
+        int32_t g = 0;
+        alive[q] = true;
+        classify_fast<NBL, NML, NMG, NBG, WIDE>(a, tab, j, alive[q], g);
+      }
+      if (alive[0] || alive[1] || alive[2] || alive[3]) {
+#pragma unroll
+        for (int m = 0; m < MM; ++m) {
+          const v4i val = *(reinterpret_cast<const v4i*>(a.meas[m]) + v);
+#pragma unroll
+          for (int q = 0; q < 4; ++q) own[m] += alive[q] ? val[q] : 0;
+        }
+#pragma unroll
+        for (int q = 0; q < 4; ++q) own_rows += alive[q] ? 1 : 0;
+      }
+#pragma unroll
+      for (int k = 0; k < ND; ++k) cur[k] = nxt[k];
+      v = vn;
+    }
+#pragma unroll
+    for (int m = 0; m < MM; ++m) {
+      const long long t = wave_sum64(own[m]);
+      if ((tid & 63) == 0) atomicAdd(&acc[m], static_cast<unsigned long long>(t));
+    }
+    const long long t = wave_sum64(own_rows);
+    if ((tid & 63) == 0) atomicAdd(&acc[MM], static_cast<unsigned long long>(t));
+  }
+  while (!SINGLE && v < v_end) {
     const int64_t vn = v + SCAN_THREADS;
     if (vn < v_end) {
 #pragma unroll
