@@ -421,6 +421,11 @@ int lq_tree_project_dim_rows(const lq_star* star, const lq_tree* tree, void* con
  *   lq_tree_fact_mask_bytes(p, l)   size of the device buffer (16-byte aligned) that holds them
  *   lq_tree_fact_masks              fills it from feature, threshold and H (no fact data is read);
  *                                   valid for any star with this tree and this c_f
+ * The buffer also holds, per leaf, the list of such nodes on its path ({column, wanted outcome,
+ * threshold}, with room for 64 entries per leaf on average).  From four mask words on the join first
+ * ANDs the dimensions' mask rows and then checks each leaf still possible against its own list (a
+ * few comparisons per row for a tree, instead of one AND per fact-side node and mask word); when
+ * the lists do not fit in that room they are left out and the join applies the nodes one by one.
  */
 int64_t lq_tree_fact_mask_bytes(int32_t n_nodes, int32_t n_leaves);
 int lq_tree_fact_masks(int32_t c_f, const lq_tree* tree, void* fact_masks, void* hip_stream);

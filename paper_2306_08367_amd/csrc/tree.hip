@@ -257,6 +257,7 @@ struct FusedTreeArgs {
   int32_t onehot_vec_ok;       // 16-byte stores into onehot rows are legal
   // nodes that test fact-table columns (evaluated per fact row)
   const float* X; int64_t ldx; int32_t c_f; int32_t has_fact_nodes;
+  int32_t pruned;              // fact-side nodes are evaluated for the leaves the tables leave possible only
   TreeArgs t;
 };
 
@@ -269,12 +270,19 @@ __device__ __forceinline__ unsigned int zero_bytes(unsigned int w) {
 // G lanes per fact row; lane c handles 16-leaf chunks c, c + G, ...
 // The nodes that test fact columns are listed once per workgroup (in LDS, in any order), so that the
 // per-row work on them is proportional to their number rather than to the size of the tree.
+// With `pruned` (dynamic LDS of 16 * chunks bytes) the workgroup also works out, once, what the tables
+// alone must add up to for leaf j: target_j minus the number of fact-side nodes on its path (each table's
+// count reaches at most the number of nodes that table owns there).  A row then evaluates fact-side nodes
+// only for the leaves whose table sum equals that number - a few per row instead of all of them - and a
+// workgroup strides over many groups of rows, so that the once-per-workgroup part stays small.
 constexpr int FT_LIST = 1024;           // listed nodes; a tree with more of them walks all nodes instead
+constexpr int FT_NEED_MAX = 48 * 1024;  // leaves (padded) whose table-only targets fit in LDS
 template <int G>
 __global__ __launch_bounds__(256) void fused_tree_kernel(FusedTreeArgs a) {
   constexpr int RPB = 256 / G;
   __shared__ int fact_q[FT_LIST];
   __shared__ int fact_cnt;
+  extern __shared__ __align__(16) uint8_t need[];
   if (a.has_fact_nodes) {
     if (threadIdx.x == 0) fact_cnt = 0;
     __syncthreads();
@@ -291,58 +299,97 @@ __global__ __launch_bounds__(256) void fused_tree_kernel(FusedTreeArgs a) {
     }
   }
   const int n_fact = a.has_fact_nodes ? fact_cnt : 0;
+  const bool listed = n_fact <= FT_LIST;
+  const int n_walk = listed ? n_fact : a.t.p;
+  if (a.pruned) {
+    for (int j = threadIdx.x; j < 16 * a.chunks; j += 256) {
+      int own = 0;
+      if (j < a.t.l)
+        for (int i = 0; i < n_walk; ++i) {
+          const int q = listed ? fact_q[i] : i;
+          if (!listed && static_cast<unsigned int>(a.t.feature[q]) >= static_cast<unsigned int>(a.c_f)) continue;
+          own += a.t.H[static_cast<int64_t>(q) * a.t.l + j] != 0 ? 1 : 0;
+        }
+      need[j] = static_cast<uint8_t>(a.target[j] - own);       // (padding: 0xFF, which no sum of table entries reaches)
+    }
+    __syncthreads();
+  }
   const int sub = threadIdx.x / G, c = threadIdx.x % G;
-  const int64_t row = static_cast<int64_t>(blockIdx.x) * RPB + sub;
-  const bool live = row < a.n;
-  const int64_t rr = live ? row : a.n - 1;
-  int64_t base[LQ_MAX_DIMS];
-#pragma unroll
-  for (int k = 0; k < LQ_MAX_DIMS; ++k)
-    if (k < a.K) base[k] = static_cast<int64_t>(a.fk[k][rr]) * a.t.ld;
-  int first = 0x7fffffff;
-  for (int ch = c; ch < a.chunks; ch += G) {
-    v4u sum = {0u, 0u, 0u, 0u};
+  const int64_t groups = (a.n + RPB - 1) / RPB;
+  for (int64_t grp = blockIdx.x; grp < groups; grp += gridDim.x) {
+    const int64_t row = grp * RPB + sub;
+    const bool live = row < a.n;
+    const int64_t rr = live ? row : a.n - 1;
+    int64_t base[LQ_MAX_DIMS];
 #pragma unroll
     for (int k = 0; k < LQ_MAX_DIMS; ++k)
-      if (k < a.K) sum += *reinterpret_cast<const v4u*>(a.T[k] + base[k] + 16 * ch);
-    if (a.has_fact_nodes) {
-      const float* xr = a.X + rr * a.ldx;
-      const bool listed = n_fact <= FT_LIST;
-      for (int i = 0; i < (listed ? n_fact : a.t.p); ++i) {
-        const int q = listed ? fact_q[i] : i;
-        const int f = a.t.feature[q];
-        if (f < 0 || f >= a.c_f) continue;
-        const bool bit = xr[f] > a.t.thr[q];
+      if (k < a.K) base[k] = static_cast<int64_t>(a.fk[k][rr]) * a.t.ld;
+    const float* xr = a.has_fact_nodes ? a.X + rr * a.ldx : nullptr;
+    int first = 0x7fffffff;
+    for (int ch = c; ch < a.chunks; ch += G) {
+      v4u sum = {0u, 0u, 0u, 0u};
 #pragma unroll
-        for (int b = 0; b < 16; ++b) {
-          const int j = 16 * ch + b;
-          const int hv = j < a.t.l ? a.t.H[static_cast<int64_t>(q) * a.t.l + j] : 0;
-          if (hv != 0 && bit == (hv > 0)) sum[b >> 2] += 1u << (8 * (b & 3));
+      for (int k = 0; k < LQ_MAX_DIMS; ++k)
+        if (k < a.K) sum += *reinterpret_cast<const v4u*>(a.T[k] + base[k] + 16 * ch);
+      v4u hit;
+      if (a.pruned) {
+        const v4u nd = *reinterpret_cast<const v4u*>(need + 16 * ch);
+#pragma unroll
+        for (int d = 0; d < 4; ++d) {
+          hit[d] = 0u;
+          for (unsigned int cand = zero_bytes(sum[d] ^ nd[d]); cand != 0u; cand &= cand - 1u) {
+            const int at = __builtin_ctz(cand) >> 3;             // byte of this word whose tables are all at their maximum
+            const int j = 16 * ch + 4 * d + at;
+            bool ok = true;
+            for (int i = 0; ok && i < n_walk; ++i) {
+              const int q = listed ? fact_q[i] : i;
+              const int hv = a.t.H[static_cast<int64_t>(q) * a.t.l + j];
+              if (hv == 0) continue;
+              const int f = a.t.feature[q];
+              if (static_cast<unsigned int>(f) >= static_cast<unsigned int>(a.c_f)) continue;
+              ok = (xr[f] > a.t.thr[q]) == (hv > 0);
+            }
+            if (ok) hit[d] |= 0x80u << (8 * at);
+          }
+        }
+      } else {
+        if (a.has_fact_nodes) {
+          for (int i = 0; i < n_walk; ++i) {
+            const int q = listed ? fact_q[i] : i;
+            const int f = a.t.feature[q];
+            if (f < 0 || f >= a.c_f) continue;
+            const bool bit = xr[f] > a.t.thr[q];
+#pragma unroll
+            for (int b = 0; b < 16; ++b) {
+              const int j = 16 * ch + b;
+              const int hv = j < a.t.l ? a.t.H[static_cast<int64_t>(q) * a.t.l + j] : 0;
+              if (hv != 0 && bit == (hv > 0)) sum[b >> 2] += 1u << (8 * (b & 3));
+            }
+          }
+        }
+        const v4u tg = *reinterpret_cast<const v4u*>(a.target + 16 * ch);
+#pragma unroll
+        for (int d = 0; d < 4; ++d) hit[d] = zero_bytes(sum[d] ^ tg[d]);
+      }
+#pragma unroll
+      for (int d = 0; d < 4; ++d)
+        if (hit[d] != 0u) first = min(first, 16 * ch + 4 * d + (__builtin_ctz(hit[d]) >> 3));
+      if (a.onehot && live) {
+        uint8_t* o = a.onehot + row * a.t.l + 16 * ch;
+        if (a.onehot_vec_ok && 16 * ch + 16 <= a.t.l) {
+          const v4u ones = {hit[0] >> 7, hit[1] >> 7, hit[2] >> 7, hit[3] >> 7};
+          __builtin_nontemporal_store(ones, reinterpret_cast<v4u*>(o));
+        } else {
+#pragma unroll
+          for (int b = 0; b < 16; ++b)
+            if (16 * ch + b < a.t.l) o[b] = static_cast<uint8_t>((hit[b >> 2] >> (8 * (b & 3) + 7)) & 1u);
         }
       }
     }
-    const v4u tg = *reinterpret_cast<const v4u*>(a.target + 16 * ch);
-    v4u hit;
 #pragma unroll
-    for (int d = 0; d < 4; ++d) {
-      hit[d] = zero_bytes(sum[d] ^ tg[d]);
-      if (hit[d] != 0u) first = min(first, 16 * ch + 4 * d + (__builtin_ctz(hit[d]) >> 3));
-    }
-    if (a.onehot && live) {
-      uint8_t* o = a.onehot + row * a.t.l + 16 * ch;
-      if (a.onehot_vec_ok && 16 * ch + 16 <= a.t.l) {
-        const v4u ones = {hit[0] >> 7, hit[1] >> 7, hit[2] >> 7, hit[3] >> 7};
-        __builtin_nontemporal_store(ones, reinterpret_cast<v4u*>(o));
-      } else {
-#pragma unroll
-        for (int b = 0; b < 16; ++b)
-          if (16 * ch + b < a.t.l) o[b] = static_cast<uint8_t>((hit[b >> 2] >> (8 * (b & 3) + 7)) & 1u);
-      }
-    }
+    for (int m = 1; m < G; m <<= 1) first = min(first, __shfl_xor(first, m, 64));
+    if (a.leaf && live && c == 0) a.leaf[row] = first == 0x7fffffff ? -1 : first;
   }
-#pragma unroll
-  for (int m = 1; m < G; m <<= 1) first = min(first, __shfl_xor(first, m, 64));
-  if (a.leaf && live && c == 0) a.leaf[row] = first == 0x7fffffff ? -1 : first;
 }
 
 // The same join stage for trees of up to 1,024 leaves without fact-table nodes, organised so that a
@@ -561,13 +608,74 @@ struct FactSide {
   const int32_t* feat;
   const float* thr;
   const u64* tf;                // [(node * words + w) * 2 + {0: test true, 1: test false}]
+  // Per leaf, the fact-side nodes on its path (cnt[1] != 0: the lists are there): entries leaf_off[j] .. leaf_off[j + 1),
+  // each {column, 1 when the path wants the test false, threshold bits, position of the node in tf}.
+  const int32_t* leaf_off;
+  const uint4* leaf_ent;
 };
-struct FactBuf { int32_t* cnt; int32_t* feat; float* thr; u64* tf; };
-FactBuf fact_buf(void* p, int32_t n_nodes) {
+struct FactBuf { int32_t* cnt; int32_t* feat; float* thr; u64* tf; int32_t* leaf_off; uint4* leaf_ent; };
+constexpr int FACT_LIST_PER_LEAF = 64;     // list entries the buffer has room for, per leaf on average
+// cnt[0]: fact-side nodes, cnt[1]: the per-leaf lists are complete, cnt[2]: their total length.
+FactBuf fact_buf(void* p, int32_t n_nodes, int32_t n_leaves) {
   char* b = static_cast<char*>(p);
+  const size_t tf = round_up(16 + 8 * static_cast<size_t>(n_nodes), 16);
+  const size_t off = tf + static_cast<size_t>(n_nodes) * lq_tree_mask_words(n_leaves) * 16;
+  const size_t ent = off + round_up(4 * (static_cast<size_t>(n_leaves) + 1), 16);
   return FactBuf{reinterpret_cast<int32_t*>(b), reinterpret_cast<int32_t*>(b + 16),
-                 reinterpret_cast<float*>(b + 16 + 4 * static_cast<size_t>(n_nodes)),
-                 reinterpret_cast<u64*>(b + round_up(16 + 8 * static_cast<size_t>(n_nodes), 16))};
+                 reinterpret_cast<float*>(b + 16 + 4 * static_cast<size_t>(n_nodes)), reinterpret_cast<u64*>(b + tf),
+                 reinterpret_cast<int32_t*>(b + off), reinterpret_cast<uint4*>(b + ent)};
+}
+
+// The per-leaf lists: count, running sum (one workgroup), fill.  A leaf's list has the fact-side nodes with a nonzero
+// entry in its column of H, in node order.
+__global__ __launch_bounds__(256) void tree_fact_list_count_kernel(TreeArgs t, int32_t c_f, int32_t* leaf_off) {
+  const int j = blockIdx.x * 256 + threadIdx.x;
+  if (j == 0) leaf_off[0] = 0;
+  if (j >= t.l) return;
+  int count = 0;
+  for (int q = 0; q < t.p; ++q)
+    count += (static_cast<unsigned int>(t.feature[q]) < static_cast<unsigned int>(c_f) && t.H[static_cast<int64_t>(q) * t.l + j] != 0) ? 1 : 0;
+  leaf_off[j + 1] = count;
+}
+__global__ __launch_bounds__(1024) void tree_fact_list_scan_kernel(int32_t* leaf_off, int32_t l, int32_t* cnt, int64_t capacity) {
+  __shared__ int part[1024];
+  __shared__ long long carry;
+  if (threadIdx.x == 0) carry = 0;
+  __syncthreads();
+  for (int base = 1; base <= l; base += 1024) {
+    const int i = base + threadIdx.x;
+    const int v = i <= l ? leaf_off[i] : 0;
+    part[threadIdx.x] = v;
+    __syncthreads();
+    for (int d = 1; d < 1024; d <<= 1) {
+      const int add = threadIdx.x >= d ? part[threadIdx.x - d] : 0;
+      __syncthreads();
+      part[threadIdx.x] += add;
+      __syncthreads();
+    }
+    const long long total = carry + part[threadIdx.x];
+    if (i <= l) leaf_off[i] = total > 0x7fffffffLL ? 0x7fffffff : static_cast<int32_t>(total);
+    __syncthreads();
+    if (threadIdx.x == 1023) carry = total;
+    __syncthreads();
+  }
+  if (threadIdx.x == 0) {
+    cnt[2] = carry > 0x7fffffffLL ? 0x7fffffff : static_cast<int32_t>(carry);
+    cnt[1] = carry <= capacity ? 1 : 0;
+  }
+}
+__global__ __launch_bounds__(256) void tree_fact_list_fill_kernel(TreeArgs t, int32_t c_f, const int32_t* cnt, const int32_t* leaf_off,
+                                                                  uint4* ent) {
+  const int j = blockIdx.x * 256 + threadIdx.x;
+  if (j >= t.l || cnt[1] == 0) return;
+  int at = leaf_off[j], pos = 0;                 // pos: fact-side nodes before node q = its place in the packed list
+  for (int q = 0; q < t.p; ++q) {
+    const int f = t.feature[q];
+    if (static_cast<unsigned int>(f) >= static_cast<unsigned int>(c_f)) continue;
+    const int h = t.H[static_cast<int64_t>(q) * t.l + j];
+    if (h != 0) ent[at++] = make_uint4(static_cast<unsigned int>(f), h < 0 ? 1u : 0u, __float_as_uint(t.thr[q]), static_cast<unsigned int>(pos));
+    ++pos;
+  }
 }
 
 // Workgroup = 16 consecutive nodes, wavefront = 4 of them, lane = leaf of the current mask word.
@@ -619,6 +727,7 @@ struct MaskJoinArgs {
   int32_t* leaf;
   uint8_t* onehot;
   int32_t onehot_vec;       // whole 16-byte stores of one-hot rows are legal (l % 16 == 0, aligned)
+  int32_t skip_when_lists;  // fused_tree_mask_kernel returns at once when the fact side has its per-leaf lists (the walk ran)
   FactSide f;
 };
 
@@ -704,6 +813,7 @@ __global__ __launch_bounds__(256) void fused_tree_mask_kernel(MaskJoinArgs a) {
   const int64_t wave = static_cast<int64_t>(blockIdx.x) * 4 + (threadIdx.x >> 6);
   const int64_t row0 = wave * (64 * R);
   if (row0 >= a.n) return;
+  if (a.skip_when_lists && a.f.cnt[1] != 0) return;
   int key[R][KK];
 #pragma unroll
   for (int u = 0; u < R; ++u) {
@@ -816,8 +926,9 @@ __global__ __launch_bounds__(256) void fused_tree_mask_kernel(MaskJoinArgs a) {
 // groups through the cross-lane network; in pass t group g works on row (64 / G) t + g.  Each lane
 // ANDs its two words over the tables, finds its lowest set bit, and a minimum over the group gives
 // the leaf.  The gathers of four passes are requested before the first is consumed.
-// OH: the one-hot rows are written as well, every lane the 128 bytes of its two words (l % 16 == 0).
-template <int KT, int G, bool OH>      // dimensions (1..4, 0 = any number); lanes per fact row (2..64)
+// OH = 1: the one-hot rows are written as well, every lane the 128 bytes of its two words (l % 16 == 0 and aligned rows);
+// OH = 2: any l, the rows were cleared beforehand and a lane sets the byte of each leaf reached (one per row for a tree).
+template <int KT, int G, int OH>       // dimensions (1..4, 0 = any number); lanes per fact row (2..64)
 __global__ __launch_bounds__(256) void fused_tree_mask_rows_kernel(MaskJoinArgs a) {
   constexpr int KK = KT > 0 ? KT : LQ_MAX_DIMS;
   constexpr int RPP = 64 / G;                 // rows per pass
@@ -855,7 +966,13 @@ __global__ __launch_bounds__(256) void fused_tree_mask_rows_kernel(MaskJoinArgs 
       for (int d = 1; d < G; d <<= 1) pos = min(pos, __shfl_xor(pos, d, 64));
       const int64_t row = row0 + (t0 + e) * RPP + g;
       if (a.leaf && c == 0 && row < a.n) a.leaf[row] = pos == 0x7fffffff ? -1 : pos;
-      if constexpr (OH) {
+      if constexpr (OH == 2) {
+        if (piece && row < a.n && a.K > 0)
+#pragma unroll
+          for (int half = 0; half < 2; ++half)
+            for (u64 w = m[e][half]; w != 0ull; w &= w - 1ull) a.onehot[row * a.l + 128 * c + 64 * half + __builtin_ctzll(w)] = 1;
+      }
+      if constexpr (OH == 1) {
         if (piece && row < a.n) {
           uint8_t* o = a.onehot + row * a.l + 128 * c;
 #pragma unroll
@@ -877,10 +994,12 @@ __global__ __launch_bounds__(256) void fused_tree_mask_rows_kernel(MaskJoinArgs 
   }
 }
 
-// The same with nodes on fact-table columns (leaf only, any number of dimensions).  A lane applies
-// every such node to its two words of the row: the node's test is evaluated on the fact row of the
-// lane's group, and the mask pair that applies is ANDed in.  The pairs of the first nodes sit in LDS
-// (32 KB: 128 nodes at 1,024 leaves), those of further nodes are read from memory.
+// The same with nodes on fact-table columns (any number of dimensions), for trees whose per-leaf lists
+// of such nodes did not fit (the call returns at once when they are there: the walk kernel below
+// serves those).  A lane applies every such node to its two words of the row: the node's test is
+// evaluated on the fact row of the lane's group, and the mask pair that applies is ANDed in.  The
+// pairs of the first nodes sit in LDS (32 KB: 128 nodes at 1,024 leaves), those of further nodes are
+// read from memory.  One-hot rows are cleared beforehand; a byte is set per leaf reached.
 constexpr int ROWS_FACT_LDS = 32 * 1024;
 template <int G>
 __global__ __launch_bounds__(256) void fused_tree_mask_rows_fact_kernel(MaskJoinArgs a) {
@@ -890,7 +1009,9 @@ __global__ __launch_bounds__(256) void fused_tree_mask_rows_fact_kernel(MaskJoin
   typedef u64 u64x2 __attribute__((ext_vector_type(2)));
   __shared__ __align__(16) u64 tf_lds[ROWS_FACT_LDS / 8];
   __shared__ u64 ft_lds[ROWS_FACT_LDS / 64];      // column and threshold of the nodes in LDS (at least 4 words per row)
+  if (a.f.cnt[1] != 0) return;                   // per-leaf lists of fact-side nodes are there
   const int fact_nodes = *a.f.cnt;
+  const bool every = a.onehot != nullptr;
   const int in_lds = min(fact_nodes, ROWS_FACT_LDS / (16 * a.words));
   for (int i = threadIdx.x; i < in_lds * a.words * 2; i += 256) tf_lds[i] = a.f.tf[i];
   for (int i = threadIdx.x; i < in_lds; i += 256)
@@ -950,16 +1071,160 @@ __global__ __launch_bounds__(256) void fused_tree_mask_rows_fact_kernel(MaskJoin
 #pragma unroll
     for (int e = 0; e < PB; ++e) {
       int pos = 0x7fffffff;
+      const int64_t row = row0 + (t0 + e) * RPP + g;
       if (piece && (a.K > 0 || fact_nodes > 0)) {
         if (m0[e] != 0ull) pos = 128 * c + __builtin_ctzll(m0[e]);
         else if (m1[e] != 0ull) pos = 128 * c + 64 + __builtin_ctzll(m1[e]);
+        if (every && row < a.n)
+#pragma unroll
+          for (int half = 0; half < 2; ++half)
+            for (u64 m = half ? m1[e] : m0[e]; m != 0ull; m &= m - 1ull) {
+              const int j = 128 * c + 64 * half + __builtin_ctzll(m);
+              if (j < a.l) a.onehot[row * a.l + j] = 1;
+            }
       }
 #pragma unroll
       for (int d = 1; d < G; d <<= 1) pos = min(pos, __shfl_xor(pos, d, 64));
-      const int64_t row = row0 + (t0 + e) * RPP + g;
-      if (c == 0 && row < a.n) a.leaf[row] = pos == 0x7fffffff ? -1 : pos;
+      if (c == 0 && row < a.n && a.leaf) a.leaf[row] = pos == 0x7fffffff ? -1 : pos;
     }
   }
+}
+
+// The same from the per-leaf lists of fact-side nodes (the call returns at once when they are not there).
+// The tables have left few leaves possible.  The G lanes of a row take its lowest leaf still possible and
+// check it against the fact-side nodes on its own path; the first test that comes out the other way takes
+// that leaf out, and with it every leaf that wants the same outcome of that node (one AND with the node's
+// mask row: in a tree, the subtree on that side), so a row needs about as many rounds as its path has
+// fact-side nodes instead of one AND per fact-side node and mask word.  For the leaf number the walk stops
+// at the first leaf that passes; for one-hot rows (cleared beforehand) it sets that leaf's byte and goes on:
+// H need not be a tree.  A lane's four rows go through their rounds together, so that the loads of a round
+// (list bounds, list entries, fact value, mask row: each waits for the one before) are in flight for all four.
+constexpr int WALK_ROWS = 1;        // rows of a lane that go through their rounds together
+// WPL: mask words per lane (1: trees of up to 64 leaves, one lane per row, G = 1).
+template <int G, int WPL = 2>
+__global__ __launch_bounds__(256) void fused_tree_mask_rows_walk_kernel(MaskJoinArgs a) {
+  constexpr int KK = LQ_MAX_DIMS;
+  constexpr int RPP = 64 / G;
+  constexpr int PB = G < WALK_ROWS ? G : WALK_ROWS;
+  constexpr int NONE = 0x7fffffff;
+  typedef u64 u64x2 __attribute__((ext_vector_type(2)));
+  if (a.f.cnt[1] == 0) return;
+  const bool every = a.onehot != nullptr;
+  const int lane = threadIdx.x & 63, g = lane / G, c = lane % G;
+  const int64_t wave = static_cast<int64_t>(blockIdx.x) * 4 + (threadIdx.x >> 6);
+  const int64_t row0 = wave * 64;
+  if (row0 >= a.n) return;
+  int key[KK];
+#pragma unroll
+  for (int k = 0; k < KK; ++k) key[k] = k < a.K ? a.fk[k][min(row0 + lane, a.n - 1)] : 0;
+  static_assert(WPL == 2 || G == 1, "one word per lane: one lane per row");
+  const bool piece = WPL * c < a.words;
+  const int wc = piece ? WPL * c : 0;         // (idle lanes follow along on the first words and store nothing)
+  for (int t0 = 0; t0 < G; t0 += PB) {
+    u64 w0[PB], w1[PB];
+    const float* xr[PB];
+    int64_t row[PB];                           // (the same for the G lanes of a row, and so is all control flow below)
+    bool open[PB];
+    int found[PB];
+#pragma unroll
+    for (int e = 0; e < PB; ++e) {
+      row[e] = row0 + (t0 + e) * RPP + g;
+      xr[e] = a.f.X + min(row[e], a.n - 1) * a.f.ldx;
+      u64x2 m = u64x2{~0ull, WPL == 2 ? ~0ull : 0ull};
+      const int src = (t0 + e) * RPP + g;
+#pragma unroll
+      for (int k = 0; k < KK; ++k)
+        if (k < a.K) {
+          const int j = __shfl(key[k], src, 64);
+          if constexpr (WPL == 2) m &= *reinterpret_cast<const u64x2*>(a.M[k] + static_cast<int64_t>(j) * a.words + wc);
+          else m[0] &= a.M[k][static_cast<int64_t>(j) * a.words + wc];
+        }
+      const bool live = piece && row[e] < a.n;
+      w0[e] = live ? m[0] : 0ull; w1[e] = live ? m[1] : 0ull;
+      open[e] = true; found[e] = NONE;
+    }
+    for (;;) {
+      int j[PB], i[PB], end[PB], bad[PB];
+      bool outcome[PB];
+      bool any = false;
+#pragma unroll
+      for (int e = 0; e < PB; ++e) {
+        int lo = w0[e] != 0ull ? 128 * c + __builtin_ctzll(w0[e]) : (w1[e] != 0ull ? 128 * c + 64 + __builtin_ctzll(w1[e]) : NONE);
+#pragma unroll
+        for (int d = 1; d < G; d <<= 1) lo = min(lo, __shfl_xor(lo, d, 64));
+        j[e] = lo;
+        open[e] = open[e] && lo < a.l;          // none left (without tables the bits past the last leaf are still set)
+        any = any || open[e];
+      }
+      if (!any) break;
+#pragma unroll
+      for (int e = 0; e < PB; ++e) {
+        i[e] = open[e] ? a.f.leaf_off[j[e]] : 0;
+        end[e] = open[e] ? a.f.leaf_off[j[e] + 1] : 0;
+        bad[e] = -1; outcome[e] = false;
+      }
+      for (;;) {                                 // the lists of the four leaves, entry by entry
+        uint4 en[PB];
+        bool scan[PB], more = false;
+#pragma unroll
+        for (int e = 0; e < PB; ++e) {
+          scan[e] = bad[e] < 0 && i[e] < end[e];
+          if (scan[e]) en[e] = a.f.leaf_ent[i[e]];
+          more = more || scan[e];
+        }
+        if (!more) break;
+        float x[PB];
+#pragma unroll
+        for (int e = 0; e < PB; ++e) x[e] = scan[e] ? xr[e][en[e].x] : 0.0f;
+#pragma unroll
+        for (int e = 0; e < PB; ++e)
+          if (scan[e]) {
+            const bool test = x[e] > __uint_as_float(en[e].z);
+            if (test == (en[e].y != 0u)) { bad[e] = static_cast<int>(en[e].w); outcome[e] = test; }
+            ++i[e];
+          }
+      }
+      u64x2 p0[PB], p1[PB];                      // {test true, test false} of this lane's two words
+#pragma unroll
+      for (int e = 0; e < PB; ++e)
+        if (open[e] && bad[e] >= 0) {
+          const u64x2* src = reinterpret_cast<const u64x2*>(a.f.tf) + static_cast<int64_t>(bad[e]) * a.words + wc;
+          p0[e] = src[0];
+          if constexpr (WPL == 2) p1[e] = src[1]; else p1[e] = u64x2{0ull, 0ull};
+        }
+#pragma unroll
+      for (int e = 0; e < PB; ++e) {
+        if (!open[e]) continue;
+        if (bad[e] >= 0) {
+          w0[e] &= outcome[e] ? p0[e][0] : p0[e][1];
+          w1[e] &= outcome[e] ? p1[e][0] : p1[e][1];
+        } else {
+          if (found[e] == NONE) found[e] = j[e];
+          if (!every) open[e] = false;
+          else if (c == (j[e] >> 7)) {
+            a.onehot[row[e] * a.l + j[e]] = 1;
+            if (j[e] & 64) w1[e] &= ~(1ull << (j[e] & 63)); else w0[e] &= ~(1ull << (j[e] & 63));
+          }
+        }
+      }
+    }
+#pragma unroll
+    for (int e = 0; e < PB; ++e)
+      if (c == 0 && row[e] < a.n && a.leaf) a.leaf[row[e]] = found[e] == NONE ? -1 : found[e];
+  }
+}
+
+// Clears `bytes` bytes from p on (any alignment): 16-byte stores between the first and the last 16-byte boundary.
+__global__ __launch_bounds__(256) void zero_bytes_kernel(uint8_t* __restrict__ p, int64_t bytes) {
+  typedef unsigned int v4u __attribute__((ext_vector_type(4)));
+  const int64_t head = min(bytes, static_cast<int64_t>((16 - (reinterpret_cast<uintptr_t>(p) & 15)) & 15));
+  const int64_t pieces = (bytes - head) / 16;
+  const int64_t tail = bytes - head - 16 * pieces;
+  const int64_t stride = static_cast<int64_t>(gridDim.x) * 256;
+  for (int64_t i = static_cast<int64_t>(blockIdx.x) * 256 + threadIdx.x; i < pieces; i += stride)
+    *reinterpret_cast<v4u*>(p + head + 16 * i) = v4u{0u, 0u, 0u, 0u};
+  if (blockIdx.x == 0 && threadIdx.x < head) p[threadIdx.x] = 0;
+  if (blockIdx.x == 0 && threadIdx.x < tail) p[head + 16 * pieces + threadIdx.x] = 0;
 }
 
 // The same join for trees of up to 64 leaves (one mask word) and leaf-only output, with the mask
@@ -1333,10 +1598,16 @@ int lq_fused_join_tree(const lq_star* star, const lq_tree* tree, const void* con
     LQ_LAUNCH_CHECK("fused_tree_batch_kernel");
     return LQ_OK;
   }
-  const int64_t blocks = (a.n + 256 / G - 1) / (256 / G);
+  int64_t blocks = (a.n + 256 / G - 1) / (256 / G);
+  size_t lds = 0;
+  if (a.has_fact_nodes && 16 * a.chunks <= FT_NEED_MAX) {
+    a.pruned = 1;
+    lds = 16 * static_cast<size_t>(a.chunks);
+    blocks = std::min<int64_t>(blocks, static_cast<int64_t>(num_cus()) * 8);    // (each workgroup prepares the tree once)
+  }
   if (blocks > 0x7fffffffLL) return fail(LQ_ERR_UNSUPPORTED, "too many rows for one launch");
   switch (G) {
-#define LQ_TREE_CASE(GG) case GG: hipLaunchKernelGGL(fused_tree_kernel<GG>, dim3(static_cast<unsigned>(blocks)), dim3(256), 0, s, a); break;
+#define LQ_TREE_CASE(GG) case GG: hipLaunchKernelGGL(fused_tree_kernel<GG>, dim3(static_cast<unsigned>(blocks)), dim3(256), lds, s, a); break;
     LQ_TREE_CASE(1) LQ_TREE_CASE(2) LQ_TREE_CASE(4) LQ_TREE_CASE(8) LQ_TREE_CASE(16) LQ_TREE_CASE(32) LQ_TREE_CASE(64)
 #undef LQ_TREE_CASE
   }
@@ -1458,7 +1729,9 @@ int lq_tree_compress_tables(const lq_star* star, const lq_tree* tree, const void
 int64_t lq_tree_fact_mask_bytes(int32_t n_nodes, int32_t n_leaves) {
   if (n_nodes < 1 || n_leaves < 1) return 0;
   return static_cast<int64_t>(round_up(16 + 8 * static_cast<size_t>(n_nodes), 16)) +
-         static_cast<int64_t>(n_nodes) * lq_tree_mask_words(n_leaves) * 16;
+         static_cast<int64_t>(n_nodes) * lq_tree_mask_words(n_leaves) * 16 +
+         static_cast<int64_t>(round_up(4 * (static_cast<size_t>(n_leaves) + 1), 16)) +
+         static_cast<int64_t>(FACT_LIST_PER_LEAF) * n_leaves * 16;
 }
 
 int lq_tree_fact_masks(int32_t c_f, const lq_tree* tree, void* fact_masks, void* hip_stream) {
@@ -1469,9 +1742,18 @@ int lq_tree_fact_masks(int32_t c_f, const lq_tree* tree, void* fact_masks, void*
   if (c_f < 0) return fail(LQ_ERR_SHAPE, "c_f < 0");
   if (!fact_masks || !aligned(fact_masks, 16)) return fail(LQ_ERR_NULL, "fact_masks is NULL or misaligned");
   const int32_t words = static_cast<int32_t>(lq_tree_mask_words(t.l));
-  hipLaunchKernelGGL(tree_fact_masks_kernel, dim3(static_cast<unsigned>((t.p + 15) / 16)), dim3(256), 0,
-                     static_cast<hipStream_t>(hip_stream), t, c_f, words, fact_buf(fact_masks, t.p));
+  hipStream_t s = static_cast<hipStream_t>(hip_stream);
+  const FactBuf fb = fact_buf(fact_masks, t.p, t.l);
+  hipLaunchKernelGGL(tree_fact_masks_kernel, dim3(static_cast<unsigned>((t.p + 15) / 16)), dim3(256), 0, s, t, c_f, words, fb);
   LQ_LAUNCH_CHECK("tree_fact_masks_kernel");
+  const unsigned leaf_blocks = static_cast<unsigned>((t.l + 255) / 256);
+  hipLaunchKernelGGL(tree_fact_list_count_kernel, dim3(leaf_blocks), dim3(256), 0, s, t, c_f, fb.leaf_off);
+  LQ_LAUNCH_CHECK("tree_fact_list_count_kernel");
+  hipLaunchKernelGGL(tree_fact_list_scan_kernel, dim3(1), dim3(1024), 0, s, fb.leaf_off, t.l, fb.cnt,
+                     static_cast<int64_t>(FACT_LIST_PER_LEAF) * t.l);
+  LQ_LAUNCH_CHECK("tree_fact_list_scan_kernel");
+  hipLaunchKernelGGL(tree_fact_list_fill_kernel, dim3(leaf_blocks), dim3(256), 0, s, t, c_f, fb.cnt, fb.leaf_off, fb.leaf_ent);
+  LQ_LAUNCH_CHECK("tree_fact_list_fill_kernel");
   return LQ_OK;
 }
 
@@ -1503,14 +1785,38 @@ int lq_fused_join_tree_masks(const lq_star* star, const lq_tree* tree, const uin
     if (!fact_masks || !aligned(fact_masks, 16))
       return fail(LQ_ERR_NULL, "the fact table has columns: fact_masks (from lq_tree_fact_masks) is NULL or misaligned");
     if (x.ld < x.cols || (a.n > 0 && (!x.data || !aligned(x.data, 4)))) return fail(LQ_ERR_SHAPE, "fact is malformed");
-    const FactBuf fb = fact_buf(const_cast<void*>(fact_masks), t.p);
+    const FactBuf fb = fact_buf(const_cast<void*>(fact_masks), t.p, t.l);
     a.f.X = static_cast<const float*>(x.data); a.f.ldx = x.ld; a.f.c_f = x.cols;
     a.f.vec_x = (aligned(x.data, 16) && x.ld % 4 == 0 && x.cols % 4 == 0) ? 1 : 0;
     a.f.cnt = fb.cnt; a.f.feat = fb.feat; a.f.thr = fb.thr; a.f.tf = fb.tf;
+    a.f.leaf_off = fb.leaf_off; a.f.leaf_ent = fb.leaf_ent;
   }
   if (a.n == 0) return LQ_OK;
   hipStream_t s = static_cast<hipStream_t>(hip_stream);
-  if (a.words == 1 && !onehot && star->dims && a.K >= 1 && a.K <= 4 && a.n >= (1 << 20)) {
+  bool wide_loads = a.words % 2 == 0;
+  for (int k = 0; k < a.K; ++k) wide_loads = wide_loads && aligned(masks[k], 16);
+  auto clear_onehot = [&]() {
+    const int64_t pieces = (a.n * a.l + 15) / 16;
+    const int64_t zb = std::max<int64_t>(1, std::min<int64_t>((pieces + 255) / 256, static_cast<int64_t>(num_cus()) * 32));
+    hipLaunchKernelGGL(zero_bytes_kernel, dim3(static_cast<unsigned>(zb)), dim3(256), 0, s, onehot, a.n * a.l);
+  };
+  // Small trees on a fact table of more columns than the kernels below keep in registers: those re-read the row for
+  // every fact-side node, the walk reads the few values the leaves still possible ask for.  (When the per-leaf lists
+  // are not there the walk returns at once and the general kernel at the end of this function does the join.)
+  if (a.f.X && a.f.c_f > FACT_REG_COLS && a.words <= 2 && (a.words == 1 || wide_loads) && aligned(a.f.tf, 16)) {
+    const int64_t rb = (a.n + 255) / 256;
+    if (rb > 0x7fffffffLL) return fail(LQ_ERR_UNSUPPORTED, "too many rows for one launch");
+    if (onehot) {
+      clear_onehot();
+      LQ_LAUNCH_CHECK("zero_bytes_kernel");
+    }
+    const dim3 rgrid(static_cast<unsigned>(rb)), rblock(256);
+    if (a.words == 1) hipLaunchKernelGGL((fused_tree_mask_rows_walk_kernel<1, 1>), rgrid, rblock, 0, s, a);
+    else hipLaunchKernelGGL((fused_tree_mask_rows_walk_kernel<1, 2>), rgrid, rblock, 0, s, a);
+    LQ_LAUNCH_CHECK("fused_tree_mask_rows_walk_kernel");
+    a.skip_when_lists = 1;
+  }
+  if (!a.skip_when_lists && a.words == 1 && !onehot && star->dims && a.K >= 1 && a.K <= 4 && a.n >= (1 << 20)) {
     // small mask tables go to LDS (smallest first) as long as they fit next to each other
     MaskLds L{};
     int order[LQ_MAX_DIMS];
@@ -1557,37 +1863,56 @@ int lq_fused_join_tree_masks(const lq_star* star, const lq_tree* tree, const uin
       }
     }
   }
-  bool wide_loads = a.words % 2 == 0;
-  for (int k = 0; k < a.K; ++k) wide_loads = wide_loads && aligned(masks[k], 16);
-  if (wide_loads && !onehot && a.f.X && a.words >= 4 && a.words <= 128 && aligned(a.f.tf, 16)) {
+  // (with fact-side nodes the one-hot rows are cleared first and the join sets the byte of every leaf reached)
+  if (wide_loads && a.f.X && a.words >= 4 && a.words <= 128 && aligned(a.f.tf, 16)) {
     const int64_t rb = (a.n + 255) / 256;
     if (rb > 0x7fffffffLL) return fail(LQ_ERR_UNSUPPORTED, "too many rows for one launch");
+    if (onehot) {
+      clear_onehot();
+      LQ_LAUNCH_CHECK("zero_bytes_kernel");
+    }
     const dim3 rgrid(static_cast<unsigned>(rb)), rblock(256);
     int G = 2;
     while (2 * G < a.words) G *= 2;
+    // (whether the tree's per-leaf lists are there is known on the device only: both kernels are launched and the one
+    // whose form of the fact side is not there returns at once)
+#define LQ_ROWS_FACT(G_)                                                                        \
+  do {                                                                                          \
+    hipLaunchKernelGGL(fused_tree_mask_rows_walk_kernel<G_>, rgrid, rblock, 0, s, a);           \
+    hipLaunchKernelGGL(fused_tree_mask_rows_fact_kernel<G_>, rgrid, rblock, 0, s, a);           \
+  } while (0)
     switch (G) {
-      case 2: hipLaunchKernelGGL(fused_tree_mask_rows_fact_kernel<2>, rgrid, rblock, 0, s, a); break;
-      case 4: hipLaunchKernelGGL(fused_tree_mask_rows_fact_kernel<4>, rgrid, rblock, 0, s, a); break;
-      case 8: hipLaunchKernelGGL(fused_tree_mask_rows_fact_kernel<8>, rgrid, rblock, 0, s, a); break;
-      case 16: hipLaunchKernelGGL(fused_tree_mask_rows_fact_kernel<16>, rgrid, rblock, 0, s, a); break;
-      case 32: hipLaunchKernelGGL(fused_tree_mask_rows_fact_kernel<32>, rgrid, rblock, 0, s, a); break;
-      default: hipLaunchKernelGGL(fused_tree_mask_rows_fact_kernel<64>, rgrid, rblock, 0, s, a); break;
+      case 2: LQ_ROWS_FACT(2); break;
+      case 4: LQ_ROWS_FACT(4); break;
+      case 8: LQ_ROWS_FACT(8); break;
+      case 16: LQ_ROWS_FACT(16); break;
+      case 32: LQ_ROWS_FACT(32); break;
+      default: LQ_ROWS_FACT(64); break;
     }
+#undef LQ_ROWS_FACT
     LQ_LAUNCH_CHECK("fused_tree_mask_rows_fact_kernel");
     return LQ_OK;
   }
   // (one-hot rows of up to four words are faster from the kernel below, which writes them 16 bytes per
   // lane through the cross-lane network: 0.14 against 0.30 ms per 2.4e6 rows at 256 leaves)
-  if (wide_loads && (!onehot || (a.onehot_vec && a.words > 4)) && !a.f.X && a.words >= 4 && a.words <= 128) {
+  // (one-hot rows that cannot go out in 16-byte pieces: cleared first, then a byte per leaf reached - 1.6 instead of
+  // 15.7 ms per 2.4e6 rows at 3,000 leaves)
+  if (wide_loads && (!onehot || a.words > 4) && !a.f.X && a.words >= 4 && a.words <= 128) {
     const int64_t rb = (a.n + 255) / 256;
     if (rb > 0x7fffffffLL) return fail(LQ_ERR_UNSUPPORTED, "too many rows for one launch");
     const dim3 rgrid(static_cast<unsigned>(rb)), rblock(256);
     int G = 2;
     while (2 * G < a.words) G *= 2;
+    const int oh = !onehot ? 0 : (a.onehot_vec ? 1 : 2);
+    if (oh == 2) {
+      clear_onehot();
+      LQ_LAUNCH_CHECK("zero_bytes_kernel");
+    }
 #define LQ_TR(KT_, G_)                                                                                \
   do {                                                                                                 \
-    if (onehot) hipLaunchKernelGGL((fused_tree_mask_rows_kernel<KT_, G_, true>), rgrid, rblock, 0, s, a);   \
-    else hipLaunchKernelGGL((fused_tree_mask_rows_kernel<KT_, G_, false>), rgrid, rblock, 0, s, a);         \
+    if (oh == 1) hipLaunchKernelGGL((fused_tree_mask_rows_kernel<KT_, G_, 1>), rgrid, rblock, 0, s, a);      \
+    else if (oh == 2) hipLaunchKernelGGL((fused_tree_mask_rows_kernel<KT_, G_, 2>), rgrid, rblock, 0, s, a); \
+    else hipLaunchKernelGGL((fused_tree_mask_rows_kernel<KT_, G_, 0>), rgrid, rblock, 0, s, a);              \
   } while (0)
 #define LQ_TR_G(KT_)                                                                                   \
   do {                                                                                                 \

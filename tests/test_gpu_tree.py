@@ -52,6 +52,8 @@ CASES = [
     ("fact_columns_8_wide_tree", 3_001, 8, (90, 60), (6, 6), 200),
     ("fact_columns_12", 2_777, 12, (50,), (8,), 48),
     ("fact_columns_5_very_wide_tree", 1_333, 5, (70, 30), (10, 10), 700),
+    ("fact_columns_9_two_mask_words", 2_311, 9, (70, 30), (5, 5), 100),
+    ("fact_columns_20_mostly_fact_nodes", 3_100, 20, (40,), (3,), 40),
     ("fact_columns_only", 4_321, 6, (), (), 40),
     ("fact_columns_4_wide_1024", 1_203, 4, (150, 90), (20, 20), 1_024),
     ("fact_columns_12_wide_384", 1_777, 12, (64, 32, 16), (5, 5, 5), 384),
@@ -341,6 +343,95 @@ def test_mask_join_with_more_fact_side_nodes_than_the_lds_list_holds(lq):
     np.testing.assert_array_equal(leaf_l[rows.cuda()].cpu().numpy(), want)
     np.testing.assert_array_equal(oh_k[rows.cuda()].cpu().numpy(), onehot)
     assert (want >= 0).any() and (want == -1).any() and (onehot.sum(axis=1) > 1).any()
+
+
+def _fact_lists(lq, buf, p, leaves):
+    """The per-leaf lists of fact-side nodes at the end of the packed buffer: (complete?, offsets, entries)."""
+    raw = buf.cpu().numpy()
+    words = lq.lq_tree_mask_words(leaves)
+    off = (16 + 8 * p + 15) // 16 * 16 + p * words * 16
+    ent = off + (4 * (leaves + 1) + 15) // 16 * 16
+    head = raw[:16].view(np.int32)
+    offsets = raw[off:off + 4 * (leaves + 1)].view(np.int32)
+    entries = raw[ent:ent + 16 * min(int(head[2]), 64 * leaves)].view(np.uint32).reshape(-1, 4)
+    return int(head[1]), int(head[2]), offsets, entries
+
+
+@pytest.mark.parametrize("kind", ["lists_and_not_a_tree", "chain_past_the_room_for_lists", "small_past_the_room_for_lists"])
+def test_mask_join_walks_the_fact_side_nodes_of_each_candidate_leaf(lq, kind):
+    """From four mask words on, the join with fact columns checks the lowest leaf the tables left possible against
+    the fact-side nodes on its own path, read from per-leaf lists in the packed buffer (64 entries per leaf on
+    average), and takes out all leaves that the first failed test excludes; a tree whose lists do not fit (a chain
+    of 259 tests, all on fact columns) is joined node by node instead.  With an H that is no tree several leaves
+    are reached per row: the one-hot rows hold all of them."""
+    c_f, n = (12 if kind.startswith("small") else 5), 5_003
+    w = WL.make_predict("masks_fact_lists_" + kind, n, c_f, (300,), (2,), (1,), seed=WL.SEED0 + 670)
+    g = np.random.default_rng(WL.SEED0 + 671)
+    if kind == "lists_and_not_a_tree":
+        p, l = 120, 300
+        feature = g.integers(0, c_f + 2, size=p).astype(np.int32)
+        thr = g.normal(0.0, 0.7, size=p).astype(np.float32)
+        Hn = np.zeros((p, l), dtype=np.int8)
+        for j in range(l):
+            Hn[g.choice(p, size=8, replace=False), j] = g.choice([-1, 1], size=8)
+    elif kind == "small_past_the_room_for_lists":
+        # 40 "leaves" that each want 70 of 80 tests that always come out true, and 4 of 20 real ones: on a fact table
+        # of more than 8 columns small trees take the walk too, and fall back to the general kernel here
+        p, l = 100, 40
+        feature = g.integers(0, c_f, size=p).astype(np.int32)
+        thr = g.normal(0.0, 0.7, size=p).astype(np.float32)
+        thr[:80] = -1e30
+        Hn = np.zeros((p, l), dtype=np.int8)
+        for j in range(l):
+            Hn[g.choice(80, size=70, replace=False), j] = 1
+            Hn[80 + g.choice(20, size=4, replace=False), j] = g.choice([-1, 1], size=4)
+    else:
+        p, l = 259, 260
+        feature = g.integers(0, c_f, size=p).astype(np.int32)
+        thr = g.normal(1.8, 0.5, size=p).astype(np.float32)
+        Hn = np.zeros((p, l), dtype=np.int8)
+        for j in range(l):                                   # leaf j: tests 0 .. j - 1 false, test j true (the last: all false)
+            Hn[:min(j, p), j] = -1
+            if j < p:
+                Hn[j, j] = 1
+    feature, thr, H = torch.from_numpy(feature), torch.from_numpy(thr), torch.from_numpy(Hn)
+    _, onehot, want = O.tree_predict(w.X, w.dims, w.fks, feature, thr, H)
+    w = to_dev(w)
+    f, t, Hd = feature.cuda(), thr.cuda(), H.cuda()
+    assert lq.lq_tree_mask_words(l) >= 4 or c_f > 8
+    tables, target = lq.lq_tree_project_dims(w.dims, c_f, f, t, Hd)
+    masks = lq.lq_tree_compress_tables(w.dims, tables, f, t, Hd, c_f=c_f)
+    fmask = lq.lq_tree_fact_masks(c_f, f, t, Hd)
+    leaf_k, oh_k = lq.lq_fused_join_tree_masks(w.fks, masks, f, t, Hd, want_onehot=True, X=w.X, fact_masks=fmask)
+    leaf_l, _ = lq.lq_fused_join_tree_masks(w.fks, masks, f, t, Hd, X=w.X, fact_masks=fmask)
+    none, oh_o = lq.lq_fused_join_tree_masks(w.fks, masks, f, t, Hd, want_onehot=True, want_leaf=False, X=w.X, fact_masks=fmask)
+    torch.cuda.synchronize()
+    complete, total, offsets, entries = _fact_lists(lq, fmask, p, l)
+    on_fact = feature.numpy() < c_f
+    per_leaf = ((Hn != 0) & on_fact[:, None]).sum(axis=0)
+    assert total == per_leaf.sum()
+    np.testing.assert_array_equal(offsets, np.concatenate([[0], np.cumsum(per_leaf)]))
+    if kind == "lists_and_not_a_tree":
+        assert complete == 1
+        for j in (0, 1, 63, 64, 127, 128, l - 1):
+            qs = np.flatnonzero((Hn[:, j] != 0) & on_fact)
+            got = entries[offsets[j]:offsets[j + 1]]
+            np.testing.assert_array_equal(got[:, 0], feature.numpy()[qs])
+            np.testing.assert_array_equal(got[:, 1], (Hn[qs, j] < 0).astype(np.uint32))
+            np.testing.assert_array_equal(got[:, 2], thr.numpy()[qs].view(np.uint32))
+            np.testing.assert_array_equal(got[:, 3], np.cumsum(on_fact)[qs] - 1)         # place among the fact-side nodes
+        assert (onehot.sum(axis=1) > 1).any() and (want == -1).any()
+    elif kind == "small_past_the_room_for_lists":
+        assert complete == 0 and total > 64 * l
+        assert (onehot.sum(axis=1) > 1).any() and (want == -1).any() and len(np.unique(want)) >= 10
+    else:
+        assert complete == 0 and total > 64 * l
+        assert len(np.unique(want)) >= 10 and (onehot.sum(axis=1) == 1).all()
+    assert none is None
+    np.testing.assert_array_equal(leaf_k.cpu().numpy(), want)
+    np.testing.assert_array_equal(leaf_l.cpu().numpy(), want)
+    np.testing.assert_array_equal(oh_k.cpu().numpy(), onehot)
+    np.testing.assert_array_equal(oh_o.cpu().numpy(), onehot)
 
 
 def test_more_than_32767_nodes_most_of_them_on_no_path(lq):
