@@ -926,9 +926,9 @@ __global__ __launch_bounds__(256) void fused_tree_mask_kernel(MaskJoinArgs a) {
 // groups through the cross-lane network; in pass t group g works on row (64 / G) t + g.  Each lane
 // ANDs its two words over the tables, finds its lowest set bit, and a minimum over the group gives
 // the leaf.  The gathers of four passes are requested before the first is consumed.
-// OH = 1: the one-hot rows are written as well, every lane the 128 bytes of its two words (l % 16 == 0 and aligned rows);
-// OH = 2: any l, the rows were cleared beforehand and a lane sets the byte of each leaf reached (one per row for a tree).
-template <int KT, int G, int OH>       // dimensions (1..4, 0 = any number); lanes per fact row (2..64)
+// OH: one-hot rows as well.  They were cleared beforehand and a lane sets the byte of each leaf reached (one per row for
+// a tree): 0.80 ms per 2.4e6 rows at 1,024 leaves, against 1.04 ms when every lane wrote the 128 bytes of its two words.
+template <int KT, int G, bool OH>      // dimensions (1..4, 0 = any number); lanes per fact row (2..64)
 __global__ __launch_bounds__(256) void fused_tree_mask_rows_kernel(MaskJoinArgs a) {
   constexpr int KK = KT > 0 ? KT : LQ_MAX_DIMS;
   constexpr int RPP = 64 / G;                 // rows per pass
@@ -966,29 +966,11 @@ __global__ __launch_bounds__(256) void fused_tree_mask_rows_kernel(MaskJoinArgs 
       for (int d = 1; d < G; d <<= 1) pos = min(pos, __shfl_xor(pos, d, 64));
       const int64_t row = row0 + (t0 + e) * RPP + g;
       if (a.leaf && c == 0 && row < a.n) a.leaf[row] = pos == 0x7fffffff ? -1 : pos;
-      if constexpr (OH == 2) {
+      if constexpr (OH) {
         if (piece && row < a.n && a.K > 0)
 #pragma unroll
           for (int half = 0; half < 2; ++half)
             for (u64 w = m[e][half]; w != 0ull; w &= w - 1ull) a.onehot[row * a.l + 128 * c + 64 * half + __builtin_ctzll(w)] = 1;
-      }
-      if constexpr (OH == 1) {
-        if (piece && row < a.n) {
-          uint8_t* o = a.onehot + row * a.l + 128 * c;
-#pragma unroll
-          for (int i = 0; i < 8; ++i)
-            if (128 * c + 16 * i < a.l) {
-              const u64 word = a.K > 0 ? m[e][i >> 2] : 0ull;
-              const unsigned int bits = static_cast<unsigned int>(word >> (16 * (i & 3))) & 0xffffu;
-              v4u out;
-#pragma unroll
-              for (int d = 0; d < 4; ++d) {
-                const unsigned int b = (bits >> (4 * d)) & 0xfu;
-                out[d] = (b & 1u) | ((b & 2u) << 7) | ((b & 4u) << 14) | ((b & 8u) << 21);
-              }
-              *reinterpret_cast<v4u*>(o + 16 * i) = out;     // (plain stores: the eight pieces of a lane fill one line in L2)
-            }
-        }
       }
     }
   }
@@ -1893,26 +1875,23 @@ int lq_fused_join_tree_masks(const lq_star* star, const lq_tree* tree, const uin
     LQ_LAUNCH_CHECK("fused_tree_mask_rows_fact_kernel");
     return LQ_OK;
   }
-  // (one-hot rows of up to four words are faster from the kernel below, which writes them 16 bytes per
-  // lane through the cross-lane network: 0.14 against 0.30 ms per 2.4e6 rows at 256 leaves)
-  // (one-hot rows that cannot go out in 16-byte pieces: cleared first, then a byte per leaf reached - 1.6 instead of
-  // 15.7 ms per 2.4e6 rows at 3,000 leaves)
+  // (one-hot rows of up to four words are faster from the kernel below, which writes them 16 bytes per lane through the
+  // cross-lane network when l is a multiple of 16: 0.14 ms per 2.4e6 rows at 256 leaves; larger ones are cleared first
+  // and get a byte per leaf reached: 1.7 instead of 15.7 ms at 3,000 leaves)
   if (wide_loads && (!onehot || a.words > 4) && !a.f.X && a.words >= 4 && a.words <= 128) {
     const int64_t rb = (a.n + 255) / 256;
     if (rb > 0x7fffffffLL) return fail(LQ_ERR_UNSUPPORTED, "too many rows for one launch");
     const dim3 rgrid(static_cast<unsigned>(rb)), rblock(256);
     int G = 2;
     while (2 * G < a.words) G *= 2;
-    const int oh = !onehot ? 0 : (a.onehot_vec ? 1 : 2);
-    if (oh == 2) {
+    if (onehot) {
       clear_onehot();
       LQ_LAUNCH_CHECK("zero_bytes_kernel");
     }
 #define LQ_TR(KT_, G_)                                                                                \
   do {                                                                                                 \
-    if (oh == 1) hipLaunchKernelGGL((fused_tree_mask_rows_kernel<KT_, G_, 1>), rgrid, rblock, 0, s, a);      \
-    else if (oh == 2) hipLaunchKernelGGL((fused_tree_mask_rows_kernel<KT_, G_, 2>), rgrid, rblock, 0, s, a); \
-    else hipLaunchKernelGGL((fused_tree_mask_rows_kernel<KT_, G_, 0>), rgrid, rblock, 0, s, a);              \
+    if (onehot) hipLaunchKernelGGL((fused_tree_mask_rows_kernel<KT_, G_, true>), rgrid, rblock, 0, s, a);   \
+    else hipLaunchKernelGGL((fused_tree_mask_rows_kernel<KT_, G_, false>), rgrid, rblock, 0, s, a);         \
   } while (0)
 #define LQ_TR_G(KT_)                                                                                   \
   do {                                                                                                 \
