@@ -182,10 +182,12 @@ def test_tree_entry_points_reject_bad_arguments():
                                          None) == 4
     assert lib.lq_tree_workspace_bytes(ctypes.byref(star), ctypes.byref(tree), 256) >= 256 * 5 * 4
     # leaf masks: word count; size of the fact-side buffer (header 16 B, column + threshold per node,
-    # rounded to 16, then two words per node and mask word); missing or misaligned arguments
+    # rounded to 16, then two words per node and mask word, then the per-leaf lists: l + 1 offsets rounded
+    # to 16 and room for 64 entries of 16 bytes per leaf); missing or misaligned arguments
     assert b.lq_tree_mask_words(1) == 1 and b.lq_tree_mask_words(64) == 1 and b.lq_tree_mask_words(65) == 2
     assert b.lq_tree_mask_words(0) == 0
-    assert b.lq_tree_fact_mask_bytes(3, 4) == 48 + 3 * 16 and b.lq_tree_fact_mask_bytes(63, 65) == 528 + 63 * 32
+    assert b.lq_tree_fact_mask_bytes(3, 4) == 48 + 3 * 16 + 32 + 4 * 1024
+    assert b.lq_tree_fact_mask_bytes(63, 65) == 528 + 63 * 32 + 272 + 65 * 1024
     assert b.lq_tree_fact_mask_bytes(0, 4) == 0
     assert lib.lq_tree_fact_masks(-1, ctypes.byref(tree), FAKE, None) == 2
     assert lib.lq_tree_fact_masks(2, ctypes.byref(tree), None, None) == 1
