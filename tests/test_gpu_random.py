@@ -192,6 +192,59 @@ def test_random_trees(lq):
                 assert torch.equal(tables[k], t2[k]) and torch.equal(masks[k], m2[k]), f"refresh differs, {desc}"
 
 
+def test_random_path_matrices_that_are_no_trees(lq):
+    """H in its matrix form (Section 3.3.1) with any set of wanted outcomes per column, and chains of tests: several
+    leaves or none are reached per row, fact-side lists of any length.  Byte-table join, mask join with leaf and
+    one-hot rows together and each alone, against the oracle."""
+    for seed in _seeds(7, 250):
+        r = np.random.default_rng(seed)
+        K = int(r.choice([0, 1, 1, 2, 3, 5]))
+        c_f = int(r.choice([0, 2, 4, 7, 9, 12, 20]))
+        if K == 0 and c_f == 0:
+            c_f = 3
+        rows = [int(r.integers(1, 400)) for _ in range(K)]
+        cols = [int(r.integers(1, 9)) for _ in range(K)]
+        n = int(r.choice([1, 63, 65, 257, 1000, 4099]))
+        kw = c_f + sum(cols)
+        if r.random() < 0.7:
+            p, l = int(r.integers(1, 150)), int(r.choice([1, 5, 48, 64, 70, 130, 200, 260, 400]))
+            per = int(r.integers(1, min(p, 9) + 1))
+            thr = r.normal(0, 0.7, size=p).astype(np.float32)
+            Hn = np.zeros((p, l), dtype=np.int8)
+            for j in range(l):
+                Hn[r.choice(p, size=per, replace=False), j] = r.choice([-1, 1], size=per)
+        else:
+            p = int(r.choice([5, 70, 130, 200]))
+            l = p + 1
+            thr = r.normal(1.5, 0.6, size=p).astype(np.float32)
+            Hn = np.zeros((p, l), dtype=np.int8)
+            for j in range(l):                           # leaf j: tests before j false, test j true
+                Hn[:min(j, p), j] = -1
+                if j < p:
+                    Hn[j, j] = 1
+        feature = torch.from_numpy(r.integers(0, kw, size=p).astype(np.int32))
+        thr, H = torch.from_numpy(thr), torch.from_numpy(Hn)
+        desc = f"seed={seed} n={n} c_f={c_f} rows={rows} cols={cols} p={p} l={l}"
+        w = WL.make_predict("random_matrix", n, c_f, rows, cols, (1,), seed=seed)
+        _, oh, leaf = O.tree_predict(w.X, w.dims, w.fks, feature, thr, H)
+        w = to_dev(w)
+        f, t, Hd = feature.cuda(), thr.cuda(), H.cuda()
+        tables, target = lq.lq_tree_project_dims(w.dims, c_f, f, t, Hd)
+        masks = lq.lq_tree_compress_tables(w.dims, tables, f, t, Hd, c_f=c_f)
+        fact = {"X": w.X, "fact_masks": lq.lq_tree_fact_masks(c_f, f, t, Hd)} if c_f else {}
+        gl, go = lq.lq_fused_join_tree(w.X, w.fks, tables, target, f, t, Hd, want_onehot=True)
+        kl, ko = lq.lq_fused_join_tree_masks(w.fks, masks, f, t, Hd, want_onehot=True, **fact)
+        kl2, _ = lq.lq_fused_join_tree_masks(w.fks, masks, f, t, Hd, **fact)
+        _, ko2 = lq.lq_fused_join_tree_masks(w.fks, masks, f, t, Hd, want_leaf=False, want_onehot=True, **fact)
+        torch.cuda.synchronize()
+        for got_leaf, got_oh, what in ((gl, go, "byte tables"), (kl, ko, "leaf masks"), (kl2, None, "leaf masks, leaf only"),
+                                       (None, ko2, "leaf masks, one-hot only")):
+            if got_leaf is not None:
+                np.testing.assert_array_equal(got_leaf.cpu().numpy(), leaf, err_msg=f"{what}, {desc}")
+            if got_oh is not None:
+                np.testing.assert_array_equal(got_oh.cpu().numpy(), oh, err_msg=f"{what} one-hot, {desc}")
+
+
 def test_random_key_maps(lq):
     for seed in _seeds(3, 300):
         r = np.random.default_rng(seed)
