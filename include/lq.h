@@ -372,8 +372,8 @@ int lq_tree_project_dims(const lq_star* star, const lq_tree* tree, void* const* 
  *   leaf    device int32 [n] or NULL: the first leaf j with R_j = h_j, -1 if none
  *   onehot  device uint8 [n x l] (row stride l) or NULL: (R == h), the paper's binary encoding
  * star->dims is not used (may be NULL); star->fact is needed only if a node tests a fact column
- * (that case runs a general kernel whose cost grows with nodes x leaves per row: the mask form
- * below is the fast path for it).
+ * (those nodes are then evaluated per fact row, for the leaves whose table sums leave them
+ * possible; the mask form below is several times faster for such trees).
  * flags: LQ_CHECK_FKS checks every key against dims[k].rows first (synchronous; star->dims must then
  * give the row counts, ws a 256-byte aligned buffer of at least 256 bytes) and returns
  * LQ_ERR_FK_RANGE instead of reading outside a table; ws is not used otherwise.

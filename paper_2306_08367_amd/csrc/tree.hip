@@ -258,6 +258,7 @@ struct FusedTreeArgs {
   // nodes that test fact-table columns (evaluated per fact row)
   const float* X; int64_t ldx; int32_t c_f; int32_t has_fact_nodes;
   int32_t pruned;              // fact-side nodes are evaluated for the leaves the tables leave possible only
+  int32_t lists;               // ... from per-leaf lists of those nodes that the workgroup builds in LDS (pruned only)
   TreeArgs t;
 };
 
@@ -275,8 +276,16 @@ __device__ __forceinline__ unsigned int zero_bytes(unsigned int w) {
 // count reaches at most the number of nodes that table owns there).  A row then evaluates fact-side nodes
 // only for the leaves whose table sum equals that number - a few per row instead of all of them - and a
 // workgroup strides over many groups of rows, so that the once-per-workgroup part stays small.
+// With `lists` (trees of up to FT_LISTS_MAX_L leaves) the same pass over H also leaves, per leaf, the list of fact-side
+// nodes on its path in LDS, so that a possible leaf costs a few LDS reads instead of a column of H.
 constexpr int FT_LIST = 1024;           // listed nodes; a tree with more of them walks all nodes instead
 constexpr int FT_NEED_MAX = 48 * 1024;  // leaves (padded) whose table-only targets fit in LDS
+constexpr int FT_LISTS_MAX_L = 8192;    // leaves (padded) up to which per-leaf lists are built
+constexpr int FT_LISTS_CAP = 8192;      // list entries in all (2 bytes each: place in the node list, bit 15 = wants the test false)
+inline size_t ft_lds_bytes(int chunks, bool lists) {
+  return 16 * static_cast<size_t>(chunks) +
+         (lists ? 8 * FT_LIST + round_up(2 * (16 * static_cast<size_t>(chunks) + 1), 16) + 2 * FT_LISTS_CAP : 0);
+}
 template <int G>
 __global__ __launch_bounds__(256) void fused_tree_kernel(FusedTreeArgs a) {
   constexpr int RPB = 256 / G;
@@ -301,8 +310,14 @@ __global__ __launch_bounds__(256) void fused_tree_kernel(FusedTreeArgs a) {
   const int n_fact = a.has_fact_nodes ? fact_cnt : 0;
   const bool listed = n_fact <= FT_LIST;
   const int n_walk = listed ? n_fact : a.t.p;
+  const int padded = 16 * a.chunks;
+  uint2* ft = reinterpret_cast<uint2*>(need + padded);                        // {column, threshold bits} of listed node i
+  unsigned short* off = reinterpret_cast<unsigned short*>(need + padded + 8 * FT_LIST);
+  unsigned short* ent = off + (2 * (padded + 1) + 15) / 16 * 8;
+  __shared__ int seg[257];
+  bool lists = a.lists && listed;
   if (a.pruned) {
-    for (int j = threadIdx.x; j < 16 * a.chunks; j += 256) {
+    for (int j = threadIdx.x; j < padded; j += 256) {
       int own = 0;
       if (j < a.t.l)
         for (int i = 0; i < n_walk; ++i) {
@@ -311,8 +326,43 @@ __global__ __launch_bounds__(256) void fused_tree_kernel(FusedTreeArgs a) {
           own += a.t.H[static_cast<int64_t>(q) * a.t.l + j] != 0 ? 1 : 0;
         }
       need[j] = static_cast<uint8_t>(a.target[j] - own);       // (padding: 0xFF, which no sum of table entries reaches)
+      if (lists) off[j + 1] = static_cast<unsigned short>(own);
     }
     __syncthreads();
+    if (lists) {
+      // running sums of the list lengths: a thread owns a run of consecutive leaves
+      const int per = (padded + 255) / 256, lo = min(padded, per * static_cast<int>(threadIdx.x)), hi = min(padded, lo + per);
+      int sum = 0;
+      for (int j = lo; j < hi; ++j) sum += off[j + 1];
+      seg[threadIdx.x + 1] = sum;
+      __syncthreads();
+      if (threadIdx.x == 0) {
+        seg[0] = 0;
+        for (int i = 1; i <= 256; ++i) seg[i] += seg[i - 1];
+        off[0] = 0;
+      }
+      __syncthreads();
+      lists = seg[256] <= FT_LISTS_CAP;
+      if (lists) {
+        int run = seg[threadIdx.x];
+        for (int j = lo; j < hi; ++j) { run += off[j + 1]; off[j + 1] = static_cast<unsigned short>(run); }
+        for (int i = threadIdx.x; i < n_fact; i += 256) {
+          const int q = fact_q[i];
+          ft[i] = make_uint2(static_cast<unsigned int>(a.t.feature[q]), __float_as_uint(a.t.thr[q]));
+        }
+      }
+      __syncthreads();
+      if (lists) {
+        for (int j = threadIdx.x; j < a.t.l; j += 256) {
+          int at = off[j];
+          for (int i = 0; i < n_fact; ++i) {
+            const int hv = a.t.H[static_cast<int64_t>(fact_q[i]) * a.t.l + j];
+            if (hv != 0) ent[at++] = static_cast<unsigned short>(i | (hv < 0 ? 0x8000 : 0));
+          }
+        }
+        __syncthreads();
+      }
+    }
   }
   const int sub = threadIdx.x / G, c = threadIdx.x % G;
   const int64_t groups = (a.n + RPB - 1) / RPB;
@@ -341,13 +391,21 @@ __global__ __launch_bounds__(256) void fused_tree_kernel(FusedTreeArgs a) {
             const int at = __builtin_ctz(cand) >> 3;             // byte of this word whose tables are all at their maximum
             const int j = 16 * ch + 4 * d + at;
             bool ok = true;
-            for (int i = 0; ok && i < n_walk; ++i) {
-              const int q = listed ? fact_q[i] : i;
-              const int hv = a.t.H[static_cast<int64_t>(q) * a.t.l + j];
-              if (hv == 0) continue;
-              const int f = a.t.feature[q];
-              if (static_cast<unsigned int>(f) >= static_cast<unsigned int>(a.c_f)) continue;
-              ok = (xr[f] > a.t.thr[q]) == (hv > 0);
+            if (lists) {
+              for (int e = off[j]; ok && e < off[j + 1]; ++e) {
+                const unsigned int en = ent[e];
+                const uint2 node = ft[en & 0x7fffu];
+                ok = (xr[node.x] > __uint_as_float(node.y)) == ((en & 0x8000u) == 0u);
+              }
+            } else {
+              for (int i = 0; ok && i < n_walk; ++i) {
+                const int q = listed ? fact_q[i] : i;
+                const int hv = a.t.H[static_cast<int64_t>(q) * a.t.l + j];
+                if (hv == 0) continue;
+                const int f = a.t.feature[q];
+                if (static_cast<unsigned int>(f) >= static_cast<unsigned int>(a.c_f)) continue;
+                ok = (xr[f] > a.t.thr[q]) == (hv > 0);
+              }
             }
             if (ok) hit[d] |= 0x80u << (8 * at);
           }
@@ -1584,7 +1642,8 @@ int lq_fused_join_tree(const lq_star* star, const lq_tree* tree, const void* con
   size_t lds = 0;
   if (a.has_fact_nodes && 16 * a.chunks <= FT_NEED_MAX) {
     a.pruned = 1;
-    lds = 16 * static_cast<size_t>(a.chunks);
+    a.lists = 16 * a.chunks <= FT_LISTS_MAX_L ? 1 : 0;
+    lds = ft_lds_bytes(a.chunks, a.lists != 0);
     blocks = std::min<int64_t>(blocks, static_cast<int64_t>(num_cus()) * 8);    // (each workgroup prepares the tree once)
   }
   if (blocks > 0x7fffffffLL) return fail(LQ_ERR_UNSUPPORTED, "too many rows for one launch");
