@@ -257,8 +257,7 @@ struct FusedTreeArgs {
   int32_t onehot_vec_ok;       // 16-byte stores into onehot rows are legal
   // nodes that test fact-table columns (evaluated per fact row)
   const float* X; int64_t ldx; int32_t c_f; int32_t has_fact_nodes;
-  int32_t pruned;              // fact-side nodes are evaluated for the leaves the tables leave possible only
-  int32_t lists;               // ... from per-leaf lists of those nodes that the workgroup builds in LDS (pruned only)
+  int32_t lists;               // the workgroup builds per-leaf lists of the fact-side nodes in LDS
   TreeArgs t;
 };
 
@@ -271,7 +270,7 @@ __device__ __forceinline__ unsigned int zero_bytes(unsigned int w) {
 // G lanes per fact row; lane c handles 16-leaf chunks c, c + G, ...
 // The nodes that test fact columns are listed once per workgroup (in LDS, in any order), so that the
 // per-row work on them is proportional to their number rather than to the size of the tree.
-// With `pruned` (dynamic LDS of 16 * chunks bytes) the workgroup also works out, once, what the tables
+// With such nodes (dynamic LDS of 16 * chunks bytes and more) the workgroup also works out, once, what the tables
 // alone must add up to for leaf j: target_j minus the number of fact-side nodes on its path (each table's
 // count reaches at most the number of nodes that table owns there).  A row then evaluates fact-side nodes
 // only for the leaves whose table sum equals that number - a few per row instead of all of them - and a
@@ -279,7 +278,7 @@ __device__ __forceinline__ unsigned int zero_bytes(unsigned int w) {
 // With `lists` (trees of up to FT_LISTS_MAX_L leaves) the same pass over H also leaves, per leaf, the list of fact-side
 // nodes on its path in LDS, so that a possible leaf costs a few LDS reads instead of a column of H.
 constexpr int FT_LIST = 1024;           // listed nodes; a tree with more of them walks all nodes instead
-constexpr int FT_NEED_MAX = 48 * 1024;  // leaves (padded) whose table-only targets fit in LDS
+constexpr int FT_NEED_MAX = 48 * 1024;  // leaves (padded) whose table-only targets fit in LDS (trees have at most 16,384)
 constexpr int FT_LISTS_MAX_L = 8192;    // leaves (padded) up to which per-leaf lists are built
 constexpr int FT_LISTS_CAP = 8192;      // list entries in all (2 bytes each: place in the node list, bit 15 = wants the test false)
 inline size_t ft_lds_bytes(int chunks, bool lists) {
@@ -316,7 +315,7 @@ __global__ __launch_bounds__(256) void fused_tree_kernel(FusedTreeArgs a) {
   unsigned short* ent = off + (2 * (padded + 1) + 15) / 16 * 8;
   __shared__ int seg[257];
   bool lists = a.lists && listed;
-  if (a.pruned) {
+  if (a.has_fact_nodes) {
     for (int j = threadIdx.x; j < padded; j += 256) {
       int own = 0;
       if (j < a.t.l)
@@ -382,7 +381,7 @@ __global__ __launch_bounds__(256) void fused_tree_kernel(FusedTreeArgs a) {
       for (int k = 0; k < LQ_MAX_DIMS; ++k)
         if (k < a.K) sum += *reinterpret_cast<const v4u*>(a.T[k] + base[k] + 16 * ch);
       v4u hit;
-      if (a.pruned) {
+      if (a.has_fact_nodes) {
         const v4u nd = *reinterpret_cast<const v4u*>(need + 16 * ch);
 #pragma unroll
         for (int d = 0; d < 4; ++d) {
@@ -411,20 +410,6 @@ __global__ __launch_bounds__(256) void fused_tree_kernel(FusedTreeArgs a) {
           }
         }
       } else {
-        if (a.has_fact_nodes) {
-          for (int i = 0; i < n_walk; ++i) {
-            const int q = listed ? fact_q[i] : i;
-            const int f = a.t.feature[q];
-            if (f < 0 || f >= a.c_f) continue;
-            const bool bit = xr[f] > a.t.thr[q];
-#pragma unroll
-            for (int b = 0; b < 16; ++b) {
-              const int j = 16 * ch + b;
-              const int hv = j < a.t.l ? a.t.H[static_cast<int64_t>(q) * a.t.l + j] : 0;
-              if (hv != 0 && bit == (hv > 0)) sum[b >> 2] += 1u << (8 * (b & 3));
-            }
-          }
-        }
         const v4u tg = *reinterpret_cast<const v4u*>(a.target + 16 * ch);
 #pragma unroll
         for (int d = 0; d < 4; ++d) hit[d] = zero_bytes(sum[d] ^ tg[d]);
@@ -1640,8 +1625,8 @@ int lq_fused_join_tree(const lq_star* star, const lq_tree* tree, const void* con
   }
   int64_t blocks = (a.n + 256 / G - 1) / (256 / G);
   size_t lds = 0;
-  if (a.has_fact_nodes && 16 * a.chunks <= FT_NEED_MAX) {
-    a.pruned = 1;
+  if (a.has_fact_nodes) {
+    static_assert(16384 + 15 <= FT_NEED_MAX, "the table-only targets of the largest tree fit in LDS");
     a.lists = 16 * a.chunks <= FT_LISTS_MAX_L ? 1 : 0;
     lds = ft_lds_bytes(a.chunks, a.lists != 0);
     blocks = std::min<int64_t>(blocks, static_cast<int64_t>(num_cus()) * 8);    // (each workgroup prepares the tree once)

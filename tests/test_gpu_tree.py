@@ -434,6 +434,37 @@ def test_mask_join_walks_the_fact_side_nodes_of_each_candidate_leaf(lq, kind):
     np.testing.assert_array_equal(oh_o.cpu().numpy(), onehot)
 
 
+@pytest.mark.parametrize("l", [8_193, 16_384], ids=["l8193", "l16384"])
+def test_fact_side_nodes_with_more_leaves_than_the_byte_join_lists_in_lds(lq, l):
+    """The byte-table join prepares the fact side of the tree in LDS: the table-only target of every leaf, and per-leaf
+    node lists up to 8,192 leaves; past that it reads a column of H for every leaf the tables leave possible.  Up to the
+    largest tree the calls take (16,384 leaves): 40 nodes on three fact columns and one table, l columns of H that want
+    three nodes each; all joins against the oracle."""
+    c_f, p, n = 3, 40, 301
+    w = WL.make_predict("many_leaves_fact", n, c_f, (50,), (4,), (1,), seed=WL.SEED0 + 680)
+    g = np.random.default_rng(WL.SEED0 + 681 + l)
+    feature = torch.from_numpy(g.integers(0, c_f + 4, size=p).astype(np.int32))
+    thr = torch.from_numpy(g.normal(0.0, 0.7, size=p).astype(np.float32))
+    Hn = np.zeros((p, l), dtype=np.int8)
+    picks = np.argsort(g.random((l, p)), axis=1)[:, :3]
+    Hn[picks, np.arange(l)[:, None]] = g.choice(np.array([-1, 1], dtype=np.int8), size=(l, 3))
+    H = torch.from_numpy(Hn)
+    _, onehot, want = O.tree_predict(w.X, w.dims, w.fks, feature, thr, H)
+    assert (onehot.sum(axis=1) > 1).any()
+    w = to_dev(w)
+    f, t, Hd = feature.cuda(), thr.cuda(), H.cuda()
+    tables, target = lq.lq_tree_project_dims(w.dims, c_f, f, t, Hd)
+    masks = lq.lq_tree_compress_tables(w.dims, tables, f, t, Hd, c_f=c_f)
+    fmask = lq.lq_tree_fact_masks(c_f, f, t, Hd)
+    leaf_b, oh_b = lq.lq_fused_join_tree(w.X, w.fks, tables, target, f, t, Hd, want_onehot=True)
+    leaf_k, oh_k = lq.lq_fused_join_tree_masks(w.fks, masks, f, t, Hd, want_onehot=True, X=w.X, fact_masks=fmask)
+    torch.cuda.synchronize()
+    np.testing.assert_array_equal(leaf_b.cpu().numpy(), want)
+    np.testing.assert_array_equal(oh_b.cpu().numpy(), onehot)
+    np.testing.assert_array_equal(leaf_k.cpu().numpy(), want)
+    np.testing.assert_array_equal(oh_k.cpu().numpy(), onehot)
+
+
 def test_more_than_32767_nodes_most_of_them_on_no_path(lq):
     """The matrix form allows nodes that lie on no leaf's path (all-zero rows of H).  Past 32,767 nodes the
     pre-fusion walks the columns of H directly instead of building per-leaf node lists."""
