@@ -770,6 +770,7 @@ struct MaskJoinArgs {
   int32_t* leaf;
   uint8_t* onehot;
   int32_t onehot_vec;       // whole 16-byte stores of one-hot rows are legal (l % 16 == 0, aligned)
+  int32_t onehot_w4;        // 4-byte stores are (l % 4 == 0, rows start at multiples of 4 bytes)
   int32_t skip_when_lists;  // fused_tree_mask_kernel returns at once when the fact side has its per-leaf lists (the walk ran)
   FactSide f;
 };
@@ -960,6 +961,50 @@ __global__ __launch_bounds__(256) void fused_tree_mask_kernel(MaskJoinArgs a) {
   }
 }
 
+struct __attribute__((packed, aligned(4))) Words4At4 { unsigned int v[4]; };     // 16 bytes at a 4-byte boundary
+
+// One-hot row of a fact row whose mask words are spread over the G lanes of a group (lane c: words 2c, 2c + 1), for l
+// a multiple of 4 and rows aligned likewise (16-byte stores when both are multiples of 16).  The lanes hand their
+// words to each other through LDS (`mine`: this wavefront's 64 x 16 bytes) so that a store instruction writes
+// neighbouring 16-byte pieces of the row, eight instructions for its 128 G bytes.  Every lane of the wavefront calls it.
+template <int G>
+__device__ __forceinline__ void onehot_row_store(const MaskJoinArgs& a, u64* mine, int lane, int c, int64_t row, u64 w0, u64 w1) {
+  typedef u64 u64x2 __attribute__((ext_vector_type(2)));
+  __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");      // (the reads of the previous row are done)
+  __builtin_amdgcn_wave_barrier();
+  *reinterpret_cast<u64x2*>(mine + 2 * lane) = u64x2{w0, w1};
+  __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+  __builtin_amdgcn_wave_barrier();
+  __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
+  // the row's mask now lies in LDS as the 16 G bytes of its lanes, in leaf order; piece P = 16 leaves = 2 of those bytes
+  const unsigned short* bits16 = reinterpret_cast<const unsigned short*>(mine + 2 * (lane - c));
+  const int pieces = (a.l + 15) >> 4;
+  if (row >= a.n) return;
+#pragma unroll
+  for (int i = 0; i < 8; ++i) {
+    const int P = i * G + c;
+    if (P < pieces) {
+      const unsigned int bits = bits16[P];
+      v4u out;
+#pragma unroll
+      for (int d = 0; d < 4; ++d) {
+        const unsigned int b = (bits >> (4 * d)) & 0xfu;
+        out[d] = (b & 1u) | ((b & 2u) << 7) | ((b & 4u) << 14) | ((b & 8u) << 21);
+      }
+      uint8_t* dst = a.onehot + row * a.l + 16 * P;
+      if (a.onehot_vec) {
+        *reinterpret_cast<v4u*>(dst) = out;
+      } else if (16 * P + 16 <= a.l) {                    // rows that start at multiples of 4 bytes only
+        *reinterpret_cast<Words4At4*>(dst) = Words4At4{{out[0], out[1], out[2], out[3]}};
+      } else {                                            // the row's last, partial piece
+#pragma unroll
+        for (int d = 0; d < 4; ++d)
+          if (16 * P + 4 * d < a.l) *reinterpret_cast<unsigned int*>(dst + 4 * d) = out[d];
+      }
+    }
+  }
+}
+
 // Join for trees of more than 192 leaves (an even number of mask words, no fact-side nodes).
 // A mask row of `words` words is contiguous (128 bytes for 1,024 leaves), so G = words / 2 lanes
 // (rounded up to a power of two) read it as neighbouring 16-byte pieces: one load instruction then
@@ -969,14 +1014,19 @@ __global__ __launch_bounds__(256) void fused_tree_mask_kernel(MaskJoinArgs a) {
 // groups through the cross-lane network; in pass t group g works on row (64 / G) t + g.  Each lane
 // ANDs its two words over the tables, finds its lowest set bit, and a minimum over the group gives
 // the leaf.  The gathers of four passes are requested before the first is consumed.
-// OH: one-hot rows as well.  They were cleared beforehand and a lane sets the byte of each leaf reached (one per row for
-// a tree): 0.80 ms per 2.4e6 rows at 1,024 leaves, against 1.04 ms when every lane wrote the 128 bytes of its two words.
-template <int KT, int G, bool OH>      // dimensions (1..4, 0 = any number); lanes per fact row (2..64)
+// OH: one-hot rows as well.
+//   1  (l a multiple of 4, rows aligned likewise) through onehot_row_store, neighbouring 16-byte pieces of a row per
+//      store instruction: 0.50 ms per 2.4e6 rows at 1,024 leaves (4.9 TB/s written); when every lane wrote the 128 bytes
+//      of its own two words a line took eight instructions to fill: 1.04 ms
+//   2  (any l) the rows were cleared beforehand and a lane sets the byte of each leaf reached, one per row for a tree:
+//      0.80 ms at 1,024 leaves
+template <int KT, int G, int OH>       // dimensions (1..4, 0 = any number); lanes per fact row (2..64)
 __global__ __launch_bounds__(256) void fused_tree_mask_rows_kernel(MaskJoinArgs a) {
   constexpr int KK = KT > 0 ? KT : LQ_MAX_DIMS;
   constexpr int RPP = 64 / G;                 // rows per pass
   constexpr int PB = G < 4 ? G : 4;           // passes in flight together (G passes cover the 64 rows)
   typedef u64 u64x2 __attribute__((ext_vector_type(2)));
+  __shared__ __align__(16) u64 swap[OH == 1 ? 4 * 64 * 2 : 2];     // per wavefront: the 16 bytes of every lane
   const int lane = threadIdx.x & 63, g = lane / G, c = lane % G;
   const int64_t wave = static_cast<int64_t>(blockIdx.x) * 4 + (threadIdx.x >> 6);
   const int64_t row0 = wave * 64;
@@ -1009,12 +1059,15 @@ __global__ __launch_bounds__(256) void fused_tree_mask_rows_kernel(MaskJoinArgs 
       for (int d = 1; d < G; d <<= 1) pos = min(pos, __shfl_xor(pos, d, 64));
       const int64_t row = row0 + (t0 + e) * RPP + g;
       if (a.leaf && c == 0 && row < a.n) a.leaf[row] = pos == 0x7fffffff ? -1 : pos;
-      if constexpr (OH) {
+      if constexpr (OH == 2) {
         if (piece && row < a.n && a.K > 0)
 #pragma unroll
           for (int half = 0; half < 2; ++half)
             for (u64 w = m[e][half]; w != 0ull; w &= w - 1ull) a.onehot[row * a.l + 128 * c + 64 * half + __builtin_ctzll(w)] = 1;
       }
+      if constexpr (OH == 1)
+        onehot_row_store<G>(a, swap + (threadIdx.x >> 6) * 128, lane, c, row, (piece && a.K > 0) ? m[e][0] : 0ull,
+                            (piece && a.K > 0) ? m[e][1] : 0ull);
     }
   }
 }
@@ -1034,9 +1087,11 @@ __global__ __launch_bounds__(256) void fused_tree_mask_rows_fact_kernel(MaskJoin
   typedef u64 u64x2 __attribute__((ext_vector_type(2)));
   __shared__ __align__(16) u64 tf_lds[ROWS_FACT_LDS / 8];
   __shared__ u64 ft_lds[ROWS_FACT_LDS / 64];      // column and threshold of the nodes in LDS (at least 4 words per row)
+  __shared__ __align__(16) u64 swap[4 * 64 * 2];  // per wavefront: the 16 bytes of every lane (onehot_row_store)
   if (a.f.cnt[1] != 0) return;                   // per-leaf lists of fact-side nodes are there
   const int fact_nodes = *a.f.cnt;
   const bool every = a.onehot != nullptr;
+  const bool rows_whole = a.onehot_vec || a.onehot_w4;
   const int in_lds = min(fact_nodes, ROWS_FACT_LDS / (16 * a.words));
   for (int i = threadIdx.x; i < in_lds * a.words * 2; i += 256) tf_lds[i] = a.f.tf[i];
   for (int i = threadIdx.x; i < in_lds; i += 256)
@@ -1100,7 +1155,7 @@ __global__ __launch_bounds__(256) void fused_tree_mask_rows_fact_kernel(MaskJoin
       if (piece && (a.K > 0 || fact_nodes > 0)) {
         if (m0[e] != 0ull) pos = 128 * c + __builtin_ctzll(m0[e]);
         else if (m1[e] != 0ull) pos = 128 * c + 64 + __builtin_ctzll(m1[e]);
-        if (every && row < a.n)
+        if (every && !rows_whole && row < a.n)
 #pragma unroll
           for (int half = 0; half < 2; ++half)
             for (u64 m = half ? m1[e] : m0[e]; m != 0ull; m &= m - 1ull) {
@@ -1111,6 +1166,10 @@ __global__ __launch_bounds__(256) void fused_tree_mask_rows_fact_kernel(MaskJoin
 #pragma unroll
       for (int d = 1; d < G; d <<= 1) pos = min(pos, __shfl_xor(pos, d, 64));
       if (c == 0 && row < a.n && a.leaf) a.leaf[row] = pos == 0x7fffffff ? -1 : pos;
+      if (every && rows_whole) {
+        const bool any = piece && (a.K > 0 || fact_nodes > 0);
+        onehot_row_store<G>(a, swap + (threadIdx.x >> 6) * 128, lane, c, row, any ? m0[e] : 0ull, any ? m1[e] : 0ull);
+      }
     }
   }
 }
@@ -1126,15 +1185,18 @@ __global__ __launch_bounds__(256) void fused_tree_mask_rows_fact_kernel(MaskJoin
 // (list bounds, list entries, fact value, mask row: each waits for the one before) are in flight for all four.
 constexpr int WALK_ROWS = 1;        // rows of a lane that go through their rounds together
 // WPL: mask words per lane (1: trees of up to 64 leaves, one lane per row, G = 1).
-template <int G, int WPL = 2>
+// OH: 0 = leaf numbers only, 1 = one-hot rows written whole at the end (onehot_row_store), 2 = byte by byte.
+template <int G, int WPL, int OH>
 __global__ __launch_bounds__(256) void fused_tree_mask_rows_walk_kernel(MaskJoinArgs a) {
   constexpr int KK = LQ_MAX_DIMS;
   constexpr int RPP = 64 / G;
   constexpr int PB = G < WALK_ROWS ? G : WALK_ROWS;
   constexpr int NONE = 0x7fffffff;
   typedef u64 u64x2 __attribute__((ext_vector_type(2)));
+  __shared__ __align__(16) u64 swap[OH == 1 ? 4 * 64 * 2 : 2];   // per wavefront: the 16 bytes of every lane (onehot_row_store)
   if (a.f.cnt[1] == 0) return;
-  const bool every = a.onehot != nullptr;
+  constexpr bool every = OH != 0;
+  constexpr bool rows_whole = OH == 1;
   const int lane = threadIdx.x & 63, g = lane / G, c = lane % G;
   const int64_t wave = static_cast<int64_t>(blockIdx.x) * 4 + (threadIdx.x >> 6);
   const int64_t row0 = wave * 64;
@@ -1151,8 +1213,10 @@ __global__ __launch_bounds__(256) void fused_tree_mask_rows_walk_kernel(MaskJoin
     int64_t row[PB];                           // (the same for the G lanes of a row, and so is all control flow below)
     bool open[PB];
     int found[PB];
+    u64 r0[rows_whole ? PB : 1], r1[rows_whole ? PB : 1];      // leaves reached (one-hot rows written whole)
 #pragma unroll
     for (int e = 0; e < PB; ++e) {
+      if constexpr (rows_whole) { r0[e] = 0ull; r1[e] = 0ull; }
       row[e] = row0 + (t0 + e) * RPP + g;
       xr[e] = a.f.X + min(row[e], a.n - 1) * a.f.ldx;
       u64x2 m = u64x2{~0ull, WPL == 2 ? ~0ull : 0ull};
@@ -1227,15 +1291,19 @@ __global__ __launch_bounds__(256) void fused_tree_mask_rows_walk_kernel(MaskJoin
           if (found[e] == NONE) found[e] = j[e];
           if (!every) open[e] = false;
           else if (c == (j[e] >> 7)) {
-            a.onehot[row[e] * a.l + j[e]] = 1;
-            if (j[e] & 64) w1[e] &= ~(1ull << (j[e] & 63)); else w0[e] &= ~(1ull << (j[e] & 63));
+            const u64 bit = 1ull << (j[e] & 63);
+            if constexpr (!rows_whole) a.onehot[row[e] * a.l + j[e]] = 1;
+            if (j[e] & 64) w1[e] &= ~bit; else w0[e] &= ~bit;
+            if constexpr (rows_whole) { if (j[e] & 64) r1[e] |= bit; else r0[e] |= bit; }
           }
         }
       }
     }
 #pragma unroll
-    for (int e = 0; e < PB; ++e)
+    for (int e = 0; e < PB; ++e) {
       if (c == 0 && row[e] < a.n && a.leaf) a.leaf[row[e]] = found[e] == NONE ? -1 : found[e];
+      if constexpr (rows_whole) onehot_row_store<G>(a, swap + (threadIdx.x >> 6) * 128, lane, c, row[e], r0[e], r1[e]);
+    }
   }
 }
 
@@ -1806,6 +1874,7 @@ int lq_fused_join_tree_masks(const lq_star* star, const lq_tree* tree, const uin
   }
   a.leaf = leaf; a.onehot = onehot;
   a.onehot_vec = onehot && aligned(onehot, 16) && t.l % 16 == 0;
+  a.onehot_w4 = onehot && aligned(onehot, 4) && t.l % 4 == 0;
   if (star->fact.cols > 0) {
     const lq_mat& x = star->fact;
     if (!fact_masks || !aligned(fact_masks, 16))
@@ -1832,13 +1901,20 @@ int lq_fused_join_tree_masks(const lq_star* star, const lq_tree* tree, const uin
   if (a.f.X && a.f.c_f > FACT_REG_COLS && a.words <= 2 && (a.words == 1 || wide_loads) && aligned(a.f.tf, 16)) {
     const int64_t rb = (a.n + 255) / 256;
     if (rb > 0x7fffffffLL) return fail(LQ_ERR_UNSUPPORTED, "too many rows for one launch");
-    if (onehot) {
+    if (onehot && !(a.onehot_vec || a.onehot_w4)) {
       clear_onehot();
       LQ_LAUNCH_CHECK("zero_bytes_kernel");
     }
     const dim3 rgrid(static_cast<unsigned>(rb)), rblock(256);
-    if (a.words == 1) hipLaunchKernelGGL((fused_tree_mask_rows_walk_kernel<1, 1>), rgrid, rblock, 0, s, a);
-    else hipLaunchKernelGGL((fused_tree_mask_rows_walk_kernel<1, 2>), rgrid, rblock, 0, s, a);
+    const int oh = !onehot ? 0 : ((a.onehot_vec || a.onehot_w4) ? 1 : 2);
+#define LQ_WALK1(WPL_)                                                                                          \
+  do {                                                                                                          \
+    if (oh == 0) hipLaunchKernelGGL((fused_tree_mask_rows_walk_kernel<1, WPL_, 0>), rgrid, rblock, 0, s, a);      \
+    else if (oh == 1) hipLaunchKernelGGL((fused_tree_mask_rows_walk_kernel<1, WPL_, 1>), rgrid, rblock, 0, s, a); \
+    else hipLaunchKernelGGL((fused_tree_mask_rows_walk_kernel<1, WPL_, 2>), rgrid, rblock, 0, s, a);              \
+  } while (0)
+    if (a.words == 1) LQ_WALK1(1); else LQ_WALK1(2);
+#undef LQ_WALK1
     LQ_LAUNCH_CHECK("fused_tree_mask_rows_walk_kernel");
     a.skip_when_lists = 1;
   }
@@ -1889,11 +1965,11 @@ int lq_fused_join_tree_masks(const lq_star* star, const lq_tree* tree, const uin
       }
     }
   }
-  // (with fact-side nodes the one-hot rows are cleared first and the join sets the byte of every leaf reached)
+  // (one-hot rows whose length is no multiple of 4 are cleared first and the join sets the byte of every leaf reached)
   if (wide_loads && a.f.X && a.words >= 4 && a.words <= 128 && aligned(a.f.tf, 16)) {
     const int64_t rb = (a.n + 255) / 256;
     if (rb > 0x7fffffffLL) return fail(LQ_ERR_UNSUPPORTED, "too many rows for one launch");
-    if (onehot) {
+    if (onehot && !(a.onehot_vec || a.onehot_w4)) {
       clear_onehot();
       LQ_LAUNCH_CHECK("zero_bytes_kernel");
     }
@@ -1902,10 +1978,13 @@ int lq_fused_join_tree_masks(const lq_star* star, const lq_tree* tree, const uin
     while (2 * G < a.words) G *= 2;
     // (whether the tree's per-leaf lists are there is known on the device only: both kernels are launched and the one
     // whose form of the fact side is not there returns at once)
-#define LQ_ROWS_FACT(G_)                                                                        \
-  do {                                                                                          \
-    hipLaunchKernelGGL(fused_tree_mask_rows_walk_kernel<G_>, rgrid, rblock, 0, s, a);           \
-    hipLaunchKernelGGL(fused_tree_mask_rows_fact_kernel<G_>, rgrid, rblock, 0, s, a);           \
+    const int oh = !onehot ? 0 : ((a.onehot_vec || a.onehot_w4) ? 1 : 2);
+#define LQ_ROWS_FACT(G_)                                                                                         \
+  do {                                                                                                           \
+    if (oh == 0) hipLaunchKernelGGL((fused_tree_mask_rows_walk_kernel<G_, 2, 0>), rgrid, rblock, 0, s, a);        \
+    else if (oh == 1) hipLaunchKernelGGL((fused_tree_mask_rows_walk_kernel<G_, 2, 1>), rgrid, rblock, 0, s, a);   \
+    else hipLaunchKernelGGL((fused_tree_mask_rows_walk_kernel<G_, 2, 2>), rgrid, rblock, 0, s, a);                \
+    hipLaunchKernelGGL(fused_tree_mask_rows_fact_kernel<G_>, rgrid, rblock, 0, s, a);                            \
   } while (0)
     switch (G) {
       case 2: LQ_ROWS_FACT(2); break;
@@ -1928,14 +2007,16 @@ int lq_fused_join_tree_masks(const lq_star* star, const lq_tree* tree, const uin
     const dim3 rgrid(static_cast<unsigned>(rb)), rblock(256);
     int G = 2;
     while (2 * G < a.words) G *= 2;
-    if (onehot) {
+    const int oh = !onehot ? 0 : ((a.onehot_vec || a.onehot_w4) ? 1 : 2);
+    if (oh == 2) {
       clear_onehot();
       LQ_LAUNCH_CHECK("zero_bytes_kernel");
     }
 #define LQ_TR(KT_, G_)                                                                                \
   do {                                                                                                 \
-    if (onehot) hipLaunchKernelGGL((fused_tree_mask_rows_kernel<KT_, G_, true>), rgrid, rblock, 0, s, a);   \
-    else hipLaunchKernelGGL((fused_tree_mask_rows_kernel<KT_, G_, false>), rgrid, rblock, 0, s, a);         \
+    if (oh == 1) hipLaunchKernelGGL((fused_tree_mask_rows_kernel<KT_, G_, 1>), rgrid, rblock, 0, s, a);      \
+    else if (oh == 2) hipLaunchKernelGGL((fused_tree_mask_rows_kernel<KT_, G_, 2>), rgrid, rblock, 0, s, a); \
+    else hipLaunchKernelGGL((fused_tree_mask_rows_kernel<KT_, G_, 0>), rgrid, rblock, 0, s, a);              \
   } while (0)
 #define LQ_TR_G(KT_)                                                                                   \
   do {                                                                                                 \
