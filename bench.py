@@ -405,6 +405,16 @@ def main():
         # the same calls recorded in a HIP graph (12 per graph, two turns over the copies): no gaps between the launches
         gt = graph_time(gb, reps=2 * copies, iters=20, warmup=3)
         grt = graph_time(lambda: gb(lq.LQ_REUSE_SIDE_TABLES), reps=2 * copies, iters=20, warmup=3)
+        # the same query with a selection vector on the fact table itself (one byte per fact row, nine rows in ten kept)
+        fact_masks = [(torch.rand(g.n, device=dev) < 0.9).to(torch.uint8) for _ in range(copies)]
+
+        def gb_fact_mask():
+            fk, me = cols[it[0] % copies]
+            fm = fact_masks[it[0] % copies]
+            it[0] += 1
+            lq.lq_masked_groupby_sum(fk, g.dim_rows, g.dim_mask, g.dim_code, g.group_card, fm, me,
+                                     sums=sums, counts=counts, ws=ws)
+        fmt = graph_time(gb_fact_mask, reps=2 * copies, iters=20, warmup=3)
         # floor of this call shape on this machine: one launch that only reads the 96 MB of key columns
         sink = torch.zeros(4, dtype=torch.int32, device=dev)
         keys = torch.cat([f.view(torch.uint8) for f in cols[0][0]])
@@ -413,6 +423,7 @@ def main():
                              **tstats(t), **tstats(rt, "reuse_side_tables_"),
                              "ms_in_a_graph": gt, "reuse_side_tables_ms_in_a_graph": grt,
                              "launches_per_call": 3, "read_only_sweep_of_the_key_columns_ms": ft[2],
+                             "with_a_fact_mask_ms_in_a_graph": fmt,
                              "roofline": hbm_roofline(20, g.n, t[2], traffic=measured_traffic("groupby_c3"),
                                                       frac_reuse_side_tables=20.0 * g.n / (rt[2] * 1e-3) / 1e9 / HBM_PEAK_GBPS,
                                                       bytes_per_row_keys_only=16,

@@ -229,7 +229,7 @@ int lq_materialized_join_predict(const lq_star* star, const lq_model* model, lq_
  *              the surviving rows are first sorted into buckets of neighbouring groups in the workspace
  *              and each bucket is then added up in LDS by the one workgroup that owns its groups
  *              (several times faster when many rows survive) -- same results every way
- *   fact_mask  uint8 [n] or NULL
+ *   fact_mask  uint8 [n] or NULL (4-byte aligned for the fast scans; any alignment works)
  *   measures   host array of n_measures (1..LQ_MAX_MEASURES) device pointers, int32 [n]
  *   sums       int64 [n_measures x G], overwritten;  counts int64 [G] or NULL
  *   ws         lq_groupby_workspace_bytes(..) bytes, 256-byte aligned; holds the encoded side

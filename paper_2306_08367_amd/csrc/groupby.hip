@@ -762,7 +762,7 @@ int launch_groupby(int64_t n, int32_t K, const int32_t* const* fks, const int64_
   // (their counters are cleared with the outputs), else through atomics
   BucketArgs bucket{};
   bool want_buckets = false;
-  if (gacc && vec_ok && !fact_mask && n > 0) {
+  if (gacc && vec_ok && n > 0) {
     size_t extra = 0;
     const size_t base = round_up(groupby_ws_bytes(K, rows, static_cast<int64_t>(M + 1) * G), 256);
     if (bucket_plan(n, G, M, &bucket, &extra) && ws_bytes >= base + extra &&
@@ -797,7 +797,7 @@ int launch_groupby(int64_t n, int32_t K, const int32_t* const* fks, const int64_
   };
 
   // Common case: compile-time specialised kernel, side tables in LDS as far as they fit.
-  if (vec == 4 && !fact_mask) {
+  if (vec == 4) {
     FastArgs f{};
     FastLaunch L{};
     bool ok = true;
@@ -827,7 +827,9 @@ int launch_groupby(int64_t n, int32_t K, const int32_t* const* fks, const int64_
         L.lds = round_up(lds_prefix, 16) + static_cast<size_t>(bucket.buckets) * 8;
       }
       slices(L.lds, &L.blocks, &L.per_block);
-      bool any_wide = false;
+      // (a fact mask is read by the instantiations that also take 16-bit code tables: calls without either do not pay for the test)
+      f.fact_mask = fact_mask;
+      bool any_wide = fact_mask != nullptr;
       for (int k = 0; k < slot; ++k) any_wide = any_wide || f.wide[k];
       auto run = [&](int mode) {
         if (any_wide) return launch_fast_wide(f, L, mode);

@@ -61,6 +61,7 @@ struct FastArgs {
   unsigned long long* partial;
   unsigned long long* gsums;         // not NULL: more groups than LDS holds, accumulate into the caller's
   unsigned long long* gcounts;       // arrays (gcounts may be NULL) instead of LDS + partial rows
+  const uint8_t* fact_mask;          // NULL or one byte per fact row, 4-byte aligned (WIDE instantiations only)
 };
 
 // The wider aggregate on the specialised scan: one measure (a column, or the product / difference of two),
@@ -261,6 +262,29 @@ __device__ __forceinline__ void lookup(const uint8_t* t, int32_t j, int32_t stri
   }
 }
 
+// The fact table's own selection vector: the four mask bytes of rows 4 v .. 4 v + 3 (all ones without a mask), and the
+// first key of row q with the row's byte applied (a row that is masked out gets the key -1, "no match").  Only the
+// WIDE instantiations look at it, so that calls without a mask and with byte tables do not pay for the test.
+template <bool WIDE>
+__device__ __forceinline__ uint32_t fact_mask_word(const FastArgs& a, int64_t v) {
+  if constexpr (WIDE) {
+    if (a.fact_mask) return __builtin_nontemporal_load(reinterpret_cast<const uint32_t*>(a.fact_mask) + v);
+  }
+  return ~0u;
+}
+template <bool WIDE>
+__device__ __forceinline__ int32_t masked_key(uint32_t word, int q, int32_t key) {
+  if constexpr (WIDE) return ((word >> (8 * q)) & 0xffu) != 0u ? key : -1;
+  return key;
+}
+template <bool WIDE>
+__device__ __forceinline__ int32_t masked_tail_key(const FastArgs& a, int64_t row, int32_t key) {
+  if constexpr (WIDE) {
+    if (a.fact_mask && a.fact_mask[row] == 0) return -1;
+  }
+  return key;
+}
+
 // All dimensions of one fact row.
 template <int NBL, int NML, int NMG, int NBG, bool WIDE = false>
 __device__ __forceinline__ void classify_fast(const FastArgs& a, const uint8_t* tab, const int32_t* j,
@@ -289,9 +313,11 @@ __global__ __launch_bounds__(SCAN_THREADS) void scan_fast_kernel(FastArgs a, int
   const int64_t v_end = min(n_vec, v_begin + per_block);
   int64_t v = v_begin + tid;
   v4i cur[ND], nxt[ND];
+  uint32_t fm_cur = ~0u, fm_nxt = ~0u;
   if (v < v_end) {
 #pragma unroll
     for (int k = 0; k < ND; ++k) cur[k] = __builtin_nontemporal_load(reinterpret_cast<const v4i*>(a.fk[k]) + v);
+    fm_cur = fact_mask_word<WIDE>(a, v);
   }
   for (int i = tid; i < n_acc; i += SCAN_THREADS) acc[i] = 0ull;
   {
@@ -314,6 +340,7 @@ __global__ __launch_bounds__(SCAN_THREADS) void scan_fast_kernel(FastArgs a, int
       if (vn < v_end) {
 #pragma unroll
         for (int k = 0; k < ND; ++k) nxt[k] = __builtin_nontemporal_load(reinterpret_cast<const v4i*>(a.fk[k]) + vn);
+        fm_nxt = fact_mask_word<WIDE>(a, vn);
       }
       bool alive[4];
 #pragma unroll
@@ -321,6 +348,7 @@ __global__ __launch_bounds__(SCAN_THREADS) void scan_fast_kernel(FastArgs a, int
         int32_t j[ND];
 #pragma unroll
         for (int k = 0; k < ND; ++k) j[k] = cur[k][q];
+        j[0] = masked_key<WIDE>(fm_cur, q, j[0]);
         int32_t g = 0;
         alive[q] = true;
         classify_fast<NBL, NML, NMG, NBG, WIDE>(a, tab, j, alive[q], g);
@@ -337,6 +365,7 @@ __global__ __launch_bounds__(SCAN_THREADS) void scan_fast_kernel(FastArgs a, int
       }
 #pragma unroll
       for (int k = 0; k < ND; ++k) cur[k] = nxt[k];
+      fm_cur = fm_nxt;
       v = vn;
     }
 #pragma unroll
@@ -352,6 +381,7 @@ __global__ __launch_bounds__(SCAN_THREADS) void scan_fast_kernel(FastArgs a, int
     if (vn < v_end) {
 #pragma unroll
       for (int k = 0; k < ND; ++k) nxt[k] = __builtin_nontemporal_load(reinterpret_cast<const v4i*>(a.fk[k]) + vn);
+      fm_nxt = fact_mask_word<WIDE>(a, vn);
     }
     int32_t g[4];
     bool alive[4];
@@ -360,6 +390,7 @@ __global__ __launch_bounds__(SCAN_THREADS) void scan_fast_kernel(FastArgs a, int
       int32_t j[ND];
 #pragma unroll
       for (int k = 0; k < ND; ++k) j[k] = cur[k][q];
+      j[0] = masked_key<WIDE>(fm_cur, q, j[0]);
       g[q] = 0;
       alive[q] = true;
       classify_fast<NBL, NML, NMG, NBG, WIDE>(a, tab, j, alive[q], g[q]);
@@ -379,6 +410,7 @@ __global__ __launch_bounds__(SCAN_THREADS) void scan_fast_kernel(FastArgs a, int
     }
 #pragma unroll
     for (int k = 0; k < ND; ++k) cur[k] = nxt[k];
+    fm_cur = fm_nxt;
     v = vn;
   }
   // ragged tail (n % 4 rows)
@@ -388,6 +420,7 @@ __global__ __launch_bounds__(SCAN_THREADS) void scan_fast_kernel(FastArgs a, int
       int32_t j[ND];
 #pragma unroll
       for (int k = 0; k < ND; ++k) j[k] = a.fk[k][i];
+      j[0] = masked_tail_key<WIDE>(a, i, j[0]);
       int32_t g = 0;
       bool alive = true;
       classify_fast<NBL, NML, NMG, NBG, WIDE>(a, tab, j, alive, g);
@@ -424,6 +457,7 @@ __global__ __launch_bounds__(SCAN_THREADS) void scan_fast_mem_kernel(FastArgs a,
 #pragma unroll
   for (int k = 0; k < ND; ++k)
     cur[k] = v < v_end ? __builtin_nontemporal_load(reinterpret_cast<const v4i*>(a.fk[k]) + v) : none;
+  uint32_t fm_cur = v < v_end ? fact_mask_word<WIDE>(a, v) : ~0u, fm_nxt = ~0u;
   {
     const uint4* src = reinterpret_cast<const uint4*>(a.packed);
     uint4* dst = reinterpret_cast<uint4*>(tab);
@@ -438,6 +472,7 @@ __global__ __launch_bounds__(SCAN_THREADS) void scan_fast_mem_kernel(FastArgs a,
 #pragma unroll
     for (int k = 0; k < ND; ++k)
       nxt[k] = vn < v_end ? __builtin_nontemporal_load(reinterpret_cast<const v4i*>(a.fk[k]) + vn) : none;
+    fm_nxt = vn < v_end ? fact_mask_word<WIDE>(a, vn) : ~0u;
     int32_t g[4];
     bool alive[4];
 #pragma unroll
@@ -445,6 +480,7 @@ __global__ __launch_bounds__(SCAN_THREADS) void scan_fast_mem_kernel(FastArgs a,
       int32_t j[ND];
 #pragma unroll
       for (int k = 0; k < ND; ++k) j[k] = cur[k][q];
+      j[0] = masked_key<WIDE>(fm_cur, q, j[0]);
       g[q] = 0;
       alive[q] = true;
       classify_fast<NBL, NML, NMG, NBG, WIDE>(a, tab, j, alive[q], g[q]);
@@ -463,6 +499,7 @@ __global__ __launch_bounds__(SCAN_THREADS) void scan_fast_mem_kernel(FastArgs a,
     }
 #pragma unroll
     for (int k = 0; k < ND; ++k) cur[k] = nxt[k];
+    fm_cur = fm_nxt;
     v = vn;
   }
   // ragged tail (n % 4 rows): one row per lane, straight to memory
@@ -472,6 +509,7 @@ __global__ __launch_bounds__(SCAN_THREADS) void scan_fast_mem_kernel(FastArgs a,
       int32_t j[ND];
 #pragma unroll
       for (int k = 0; k < ND; ++k) j[k] = a.fk[k][i];
+      j[0] = masked_tail_key<WIDE>(a, i, j[0]);
       int32_t g = 0;
       bool alive = true;
       classify_fast<NBL, NML, NMG, NBG, WIDE>(a, tab, j, alive, g);
@@ -510,6 +548,7 @@ __global__ __launch_bounds__(SCAN_THREADS) void scan_fast_bucket_kernel(FastArgs
 #pragma unroll
   for (int k = 0; k < ND; ++k)
     cur[k] = v < v_end ? __builtin_nontemporal_load(reinterpret_cast<const v4i*>(a.fk[k]) + v) : none;
+  uint32_t fm_cur = v < v_end ? fact_mask_word<WIDE>(a, v) : ~0u, fm_nxt = ~0u;
   {
     const uint4* src = reinterpret_cast<const uint4*>(a.packed);
     uint4* dst = reinterpret_cast<uint4*>(tab);
@@ -533,12 +572,14 @@ __global__ __launch_bounds__(SCAN_THREADS) void scan_fast_bucket_kernel(FastArgs
 #pragma unroll
         for (int k = 0; k < ND; ++k)
           nxt[k] = vn < v_end ? __builtin_nontemporal_load(reinterpret_cast<const v4i*>(a.fk[k]) + vn) : none;
+        fm_nxt = vn < v_end ? fact_mask_word<WIDE>(a, vn) : ~0u;
         bool alive[4];
 #pragma unroll
         for (int q = 0; q < 4; ++q) {
           int32_t j[ND];
 #pragma unroll
           for (int k = 0; k < ND; ++k) j[k] = cur[k][q];
+          j[0] = masked_key<WIDE>(fm_cur, q, j[0]);
           g[s][q] = 0;
           alive[q] = true;
           classify_fast<NBL, NML, NMG, NBG, WIDE>(a, tab, j, alive[q], g[s][q]);
@@ -557,6 +598,7 @@ __global__ __launch_bounds__(SCAN_THREADS) void scan_fast_bucket_kernel(FastArgs
         }
 #pragma unroll
         for (int k = 0; k < ND; ++k) cur[k] = nxt[k];
+        fm_cur = fm_nxt;
         v = vn;
       }
     }
@@ -606,6 +648,7 @@ __global__ __launch_bounds__(SCAN_THREADS) void scan_fast_bucket_kernel(FastArgs
       int32_t j[ND];
 #pragma unroll
       for (int k = 0; k < ND; ++k) j[k] = a.fk[k][i];
+      j[0] = masked_tail_key<WIDE>(a, i, j[0]);
       int32_t g = 0;
       bool alive = true;
       classify_fast<NBL, NML, NMG, NBG, WIDE>(a, tab, j, alive, g);

@@ -550,12 +550,12 @@ static int groupby_sum_checked(int64_t n_fact, int32_t n_dims, const int32_t* co
   // workspace that has room for it the call runs as two of them (the counts with the first, the side tables encoded
   // once); far fewer device-wide atomics than one pass of the generic scan.
   const bool reuse = (flags & LQ_REUSE_SIDE_TABLES) != 0;
-  if (n_measures > 2 && G * 3 > 8192 && !fact_mask && n_fact > 0) {
+  if (n_measures > 2 && G * 3 > 8192 && aligned(fact_mask, 4) && n_fact > 0) {
     const size_t big = groupby_bucket_ws_bytes(n_fact, n_dims, dim_rows, G, 2);
     if (big > 0 && ws_bytes >= big) {
       for (int m0 = 0; m0 < n_measures; m0 += 2) {
         const int mm = std::min(2, n_measures - m0);
-        if ((rc = launch_groupby(n_fact, n_dims, fks, dim_rows, dim_mask, dim_code, group_card, nullptr, mm, measures + m0,
+        if ((rc = launch_groupby(n_fact, n_dims, fks, dim_rows, dim_mask, dim_code, group_card, fact_mask, mm, measures + m0,
                                  sums + static_cast<int64_t>(m0) * G, m0 == 0 ? counts : nullptr, static_cast<int32_t>(G), ws,
                                  ws_bytes, reuse || m0 > 0, s)))
           return rc;

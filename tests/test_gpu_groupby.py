@@ -394,6 +394,30 @@ def test_bucketed_many_groups_bucket_geometries(lq, card, n_measures):
     _check(lq, w)
 
 
+@pytest.mark.parametrize("n", [3, 4_098, 600_001])
+@pytest.mark.parametrize("card,n_measures", [
+    ((7, 25), 2),                   # accumulators in LDS
+    ((), 1),                        # no grouping: a filtered sum
+    ((200, 173), 1),                # 34,600 groups: buckets (atomics with the small workspace)
+    ((250, 240), 3),                # three measures over many groups: two bucketed calls
+    ((1_000, 9), 2),                # a 16-bit code table
+], ids=["lds", "one_group", "buckets", "buckets_m3", "wide_codes"])
+def test_fact_mask_on_the_specialised_scan(lq, card, n_measures, n):
+    """The fact table's own selection vector (one byte per fact row, Section 2.2) on the compile-time specialised
+    scans: accumulators in LDS, through buckets and through atomics, ragged sizes, rows dropped by a negative key as
+    well.  (A mask that is not 4-byte aligned takes the generic scan: test_unaligned_columns_take_the_scalar_path.)"""
+    rows = tuple(c + 3 for c in card) + (60,)
+    w = _many_groups(390 + len(card) + n_measures, n, rows, tuple(card) + (1,), n_measures,
+                     sel=(None,) * len(card) + (0.8,), fact_mask=True, neg=True)
+    assert w.fact_mask is not None and (n < 100 or int(w.fact_mask.sum()) < n)
+    w, ws_, wc_ = _check(lq, w)
+    if len(card) == 2 and card[0] * card[1] > 8_192 and n_measures <= 2:
+        small = torch.empty(lq.lq_groupby_workspace_bytes(w.dim_rows, w.group_card, n_measures), dtype=torch.uint8, device="cuda")
+        s, c = _gpu(lq, w, ws=small)
+        np.testing.assert_array_equal(s, ws_)
+        np.testing.assert_array_equal(c, wc_)
+
+
 def test_bucketed_many_groups_all_rows_in_one_group(lq):
     # every row in one group: its bucket fills up and the rest goes through the merged atomics
     w = _many_groups(380, 1_000_003, (300, 300), (300, 300), 1)
