@@ -559,9 +559,12 @@ size_t plan_tables(int32_t K, const int64_t* rows, const uint8_t* const* mask,
     if (has_code) {
       if (card[k] <= 255) { kind = DK_BYTE; b = static_cast<size_t>(r); }
       else { kind = DK_U16; b = static_cast<size_t>(r) * 2; }
-    } else if (has_mask) {
+    } else {
+      // (also for a joined table with neither predicate nor grouping attribute, which can only drop rows through a
+      // negative key: an all-ones bitmap keeps such calls on the specialised scans)
       kind = DK_BITMAP; b = static_cast<size_t>((r + 31) / 32) * 4;
     }
+    (void)has_mask;
     bytes[k] = round_up(b, 16);
     d[k].kind = kind;
     order[k] = k;

@@ -107,7 +107,7 @@ __device__ __forceinline__ void pack_tables(const GbArgs& a, uint8_t* dst, int64
       const int64_t steps = d.bytes / 8;               // 64 rows per step
       for (int64_t q = gwave; q < steps; q += nwave) {
         const int64_t j = q * 64 + lane;
-        const bool on = j < d.rows && d.mask[j] != 0;
+        const bool on = j < d.rows && (!d.mask || d.mask[j] != 0);     // (a table without predicate or code: all rows pass)
         const unsigned long long bits = __ballot(on);
         if (lane == 0) out[q] = bits;
       }
