@@ -746,6 +746,9 @@ int launch_fast_g(const FastArgs& a, const FastLaunch& L) {
   if (L.nmg == 1 && L.nbg == 0) return launch_fast_m<MODE, WIDE, NBL, NML, 1, 0>(a, L);
   if (L.nmg == 0 && L.nbg == 1) return launch_fast_m<MODE, WIDE, NBL, NML, 0, 1>(a, L);
   if (L.nmg == 1 && L.nbg == 1) return launch_fast_m<MODE, WIDE, NBL, NML, 1, 1>(a, L);
+  // (two grouping attributes from tables too large for LDS: customer x supplier cities at large scale factors)
+  if (L.nmg == 0 && L.nbg == 2) return launch_fast_m<MODE, WIDE, NBL, NML, 0, 2>(a, L);
+  if (L.nmg == 1 && L.nbg == 2) return launch_fast_m<MODE, WIDE, NBL, NML, 1, 2>(a, L);
   return -1;
 }
 template <int MODE, bool WIDE, int NBL>

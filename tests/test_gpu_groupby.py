@@ -341,7 +341,9 @@ def test_many_groups_unaligned_columns_counts_optional_and_flags(lq):
     ((2_556, 30_000, 2_000, 200_000), (25, 25, 250, 1), (None, 0.2, None, 0.12), 2),     # all side tables in LDS
     ((400_000, 300, 250, 900_000), (200, 200, 3, 1), (0.5, None, None, 0.3), 1),         # a code table and a bitmap stay in memory
     ((300, 250), (250, 250), (None, 0.9), 2),                                            # two grouping tables only
-], ids=["lds_tables_m2", "tables_in_memory", "two_tables_m2"])
+    ((400_000, 300_000, 900, 700_000), (200, 150, 3, 1), (None, 0.8, None, 0.5), 2),     # two code tables and a bitmap in memory
+    ((400_000, 300_000), (20, 15), (0.9, None), 1),                                      # the same with accumulators in LDS
+], ids=["lds_tables_m2", "tables_in_memory", "two_tables_m2", "two_code_tables_in_memory", "two_code_tables_in_memory_lds_acc"])
 def test_many_groups_on_the_specialised_scan(lq, rows, card, sel, n_measures):
     # aligned columns, no fact mask, byte codes and bitmaps, one or two measures: the compile-time specialised scan
     w = _many_groups(350 + len(rows) + n_measures, 777_777, rows, card, n_measures, sel=sel, neg=True)
