@@ -435,17 +435,19 @@ __global__ __launch_bounds__(256) void fused_tree_kernel(FusedTreeArgs a) {
   }
 }
 
-// The same join stage for trees of up to 1,024 leaves without fact-table nodes, organised so that a
+// The same join stage for trees of up to 4,096 leaves without fact-table nodes, organised so that a
 // wavefront has many gathers in flight: it owns 64 consecutive fact rows, reads their keys once,
 // coalesced (lane = row), and hands them to the G-lane groups through the cross-lane network; in
 // pass t group g works on row (64 / G) t + g.  The gathers of up to four passes are issued before
 // the first is consumed.
 // KT: number of dimensions when it is 1..4 (loops unroll without guards), 0 = any number.
-template <int G, int KT>
+// CPL: 16-leaf chunks per lane (1; 2 or 4 with G = 64, for 1,025 to 4,096 leaves: lane c takes chunks c, c + 64, ...).
+template <int G, int KT, int CPL = 1>
 __global__ __launch_bounds__(256) void fused_tree_batch_kernel(FusedTreeArgs a) {
+  static_assert(CPL == 1 || G == 64, "several chunks per lane: all lanes on one row");
   constexpr int KK = KT > 0 ? KT : LQ_MAX_DIMS;
   constexpr int RPP = 64 / G;                 // rows per pass
-  constexpr int PB = G < 4 ? G : 4;           // passes in flight together (G passes cover the 64 rows)
+  constexpr int PB = (G < 4 ? G : 4) / CPL;   // passes in flight together (G passes cover the 64 rows)
   const int lane = threadIdx.x & 63, g = lane / G, c = lane % G;
   const int64_t wave = static_cast<int64_t>(blockIdx.x) * 4 + (threadIdx.x >> 6);
   const int64_t row0 = wave * 64;
@@ -459,20 +461,28 @@ __global__ __launch_bounds__(256) void fused_tree_batch_kernel(FusedTreeArgs a) 
     key[k] = used ? a.fk[k][myrow] : 0;
     tab[k] = (used ? a.T[k] : a.T[0]) + 16 * c;
   }
-  const bool active = c < a.chunks;
-  v4u tg = {0u, 0u, 0u, 0u};
-  if (active) tg = *reinterpret_cast<const v4u*>(a.target + 16 * c);
+  bool active[CPL];
+  v4u tg[CPL];
+#pragma unroll
+  for (int h = 0; h < CPL; ++h) {
+    active[h] = c + G * h < a.chunks;
+    tg[h] = v4u{0u, 0u, 0u, 0u};
+    if (active[h]) tg[h] = *reinterpret_cast<const v4u*>(a.target + 16 * (c + G * h));
+  }
   for (int pb = 0; pb < G; pb += PB) {
-    v4u sum[PB];
+    v4u sum[PB][CPL];
 #pragma unroll
     for (int u = 0; u < PB; ++u) {
       const int src = RPP * (pb + u) + g;     // the lane that holds this row's keys
-      sum[u] = v4u{0u, 0u, 0u, 0u};
+#pragma unroll
+      for (int h = 0; h < CPL; ++h) sum[u][h] = v4u{0u, 0u, 0u, 0u};
 #pragma unroll
       for (int k = 0; k < KK; ++k)
         if (KT > 0 || k < a.K) {
           const int64_t j = __shfl(key[k], src, 64);
-          if (active) sum[u] += *reinterpret_cast<const v4u*>(tab[k] + j * a.t.ld);
+#pragma unroll
+          for (int h = 0; h < CPL; ++h)
+            if (active[h]) sum[u][h] += *reinterpret_cast<const v4u*>(tab[k] + j * a.t.ld + 16 * G * h);
         }
     }
 #pragma unroll
@@ -480,18 +490,21 @@ __global__ __launch_bounds__(256) void fused_tree_batch_kernel(FusedTreeArgs a) 
       const int64_t row = row0 + RPP * (pb + u) + g;
       const bool live = row < a.n;
       int first = 0x7fffffff;
-      v4u hit = {0u, 0u, 0u, 0u};
-      if (active) {
 #pragma unroll
-        for (int d = 0; d < 4; ++d) {
-          hit[d] = zero_bytes(sum[u][d] ^ tg[d]);
-          // 0x80 marks a matching byte: its position is that of the lowest set bit
-          const int at = 16 * c + 4 * d + ((__builtin_ctz(hit[d] | 0x80000000u)) >> 3);
-          first = min(first, hit[d] != 0u ? at : 0x7fffffff);
-        }
-        if (a.onehot && live) {               // (this kernel is only chosen when whole 16-byte stores fit)
-          const v4u ones = {hit[0] >> 7, hit[1] >> 7, hit[2] >> 7, hit[3] >> 7};
-          __builtin_nontemporal_store(ones, reinterpret_cast<v4u*>(a.onehot + row * a.t.l + 16 * c));
+      for (int h = 0; h < CPL; ++h) {
+        v4u hit = {0u, 0u, 0u, 0u};
+        if (active[h]) {
+#pragma unroll
+          for (int d = 0; d < 4; ++d) {
+            hit[d] = zero_bytes(sum[u][h][d] ^ tg[h][d]);
+            // 0x80 marks a matching byte: its position is that of the lowest set bit
+            const int at = 16 * (c + G * h) + 4 * d + ((__builtin_ctz(hit[d] | 0x80000000u)) >> 3);
+            first = min(first, hit[d] != 0u ? at : 0x7fffffff);
+          }
+          if (a.onehot && live) {               // (this kernel is only chosen when whole 16-byte stores fit)
+            const v4u ones = {hit[0] >> 7, hit[1] >> 7, hit[2] >> 7, hit[3] >> 7};
+            __builtin_nontemporal_store(ones, reinterpret_cast<v4u*>(a.onehot + row * a.t.l + 16 * (c + G * h)));
+          }
         }
       }
 #pragma unroll
@@ -1672,10 +1685,22 @@ int lq_fused_join_tree(const lq_star* star, const lq_tree* tree, const void* con
     if ((rc = tree_check_fks(star, ws, ws_bytes, s))) return rc;
   int G = 1;
   while (G < a.chunks && G < 64) G <<= 1;
-  if (!a.has_fact_nodes && a.chunks <= 64 && (!a.onehot || (a.onehot_vec_ok && a.t.l % 16 == 0))) {
+  if (!a.has_fact_nodes && a.chunks <= 256 && (!a.onehot || (a.onehot_vec_ok && a.t.l % 16 == 0))) {
     const int64_t bblocks = (a.n + 255) / 256;
     if (bblocks > 0x7fffffffLL) return fail(LQ_ERR_UNSUPPORTED, "too many rows for one launch");
     const dim3 grid(static_cast<unsigned>(bblocks)), block(256);
+    if (a.chunks > 64) {                       // 1,025 to 4,096 leaves: two or four chunks per lane
+#define LQ_TREE_C(KT_)                                                                                   \
+  do {                                                                                                   \
+    if (a.chunks <= 128) hipLaunchKernelGGL((fused_tree_batch_kernel<64, KT_, 2>), grid, block, 0, s, a); \
+    else hipLaunchKernelGGL((fused_tree_batch_kernel<64, KT_, 4>), grid, block, 0, s, a);                 \
+  } while (0)
+      if (a.K == 1) LQ_TREE_C(1); else if (a.K == 2) LQ_TREE_C(2); else if (a.K == 3) LQ_TREE_C(3);
+      else if (a.K == 4) LQ_TREE_C(4); else LQ_TREE_C(0);
+#undef LQ_TREE_C
+      LQ_LAUNCH_CHECK("fused_tree_batch_kernel");
+      return LQ_OK;
+    }
 #define LQ_TREE_K(GG, KT_) hipLaunchKernelGGL((fused_tree_batch_kernel<GG, KT_>), grid, block, 0, s, a)
 #define LQ_TREE_CASE(GG)                                                            \
   case GG:                                                                          \

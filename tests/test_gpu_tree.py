@@ -47,6 +47,8 @@ CASES = [
     ("wide_1024_three_tables", 1_101, 0, (150, 90, 60), (20, 20, 20), 1_024),
     ("wide_2048_one_table", 515, 0, (333,), (40,), 2_048),
     ("wide_600_three_tables", 777, 0, (1_000, 37, 300), (20, 30, 10), 600),
+    ("wide_4096_two_tables", 301, 0, (50, 40), (12, 12), 4_096),
+    ("wide_2704_five_tables", 259, 0, (20, 30, 10, 25, 9), (5, 5, 5, 5, 5), 2_704),
     ("fact_columns", 2_500, 3, (40, 60), (4, 4), 24),
     ("fact_columns_4_aligned", 5_111, 4, (40, 60, 25), (4, 4, 3), 64),
     ("fact_columns_8_wide_tree", 3_001, 8, (90, 60), (6, 6), 200),
