@@ -583,10 +583,11 @@ __global__ __launch_bounds__(256) void tree_match_kernel(int32_t l, const float*
 typedef unsigned long long u64;
 
 // Workgroup (blockIdx.y = word w) for up to 1,024 rows.  First the number of nodes this dimension
-// owns on the path to each of the 64 leaves of the word (lane = leaf, the four wavefronts split the
-// nodes, eight loads in flight each); then every thread compares the 64 table bytes of its rows with
-// those counts, four bytes per operation, and packs the 64 outcomes into the mask word of its row.
-constexpr int CMP_ROWS = 4;      // rows per thread
+// owns on the path to each of the 64 leaves of the word (lane = leaf, the wavefronts split the
+// nodes, eight loads in flight each, H only read for nodes the dimension owns); then every thread compares
+// the 64 table bytes of its row with those counts, four bytes per operation, and packs the 64 outcomes
+// into the mask word of its row.
+constexpr int CMP_THREADS = 1024;   // sixteen wavefronts split the nodes (256 threads: 0.117 ms for the three tables at 1,024 leaves)
 // All dimension tables in one launch: blockIdx.z selects the table, workgroups past its rows leave at once.
 struct CompressArgs {
   const uint8_t* table[LQ_MAX_DIMS];
@@ -594,33 +595,36 @@ struct CompressArgs {
   int64_t rows[LQ_MAX_DIMS];
   int32_t col_off[LQ_MAX_DIMS], cols[LQ_MAX_DIMS];
 };
-__global__ __launch_bounds__(256) void tree_compress_kernel(TreeArgs t, CompressArgs ca, int32_t words) {
+__global__ __launch_bounds__(CMP_THREADS) void tree_compress_kernel(TreeArgs t, CompressArgs ca, int32_t words) {
+  constexpr int WAVES = CMP_THREADS / 64;
   const int dim = blockIdx.z;
   const int64_t rows = ca.rows[dim];
-  if (static_cast<int64_t>(blockIdx.x) * CMP_ROWS * 256 >= rows) return;
+  if (static_cast<int64_t>(blockIdx.x) * CMP_THREADS >= rows) return;
   const uint8_t* __restrict__ table = ca.table[dim];
   u64* __restrict__ masks = ca.masks[dim];
   const int32_t col_off = ca.col_off[dim], c = ca.cols[dim];
-  __shared__ int part[4][64];
+  __shared__ int part[WAVES][64];
   __shared__ unsigned int own_dw[16];
   const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6, w = blockIdx.y;
   const int j = 64 * w + lane;
   int own = 0;
-  for (int q0 = wave; q0 < t.p; q0 += 32) {
-    int f[8], h[8];
+  for (int q0 = wave; q0 < t.p; q0 += 8 * WAVES) {
+    int h[8];
 #pragma unroll
     for (int e = 0; e < 8; ++e) {
-      const int q = q0 + 4 * e;
-      f[e] = q < t.p ? t.feature[q] - col_off : -1;
-      h[e] = (q < t.p && j < t.l) ? t.H[static_cast<int64_t>(q) * t.l + j] : 0;
+      const int q = q0 + WAVES * e;                       // (the same for every lane: the test on the column is uniform)
+      const int f = q < t.p ? t.feature[q] - col_off : -1;
+      h[e] = (f >= 0 && f < c && j < t.l) ? t.H[static_cast<int64_t>(q) * t.l + j] : 0;
     }
 #pragma unroll
-    for (int e = 0; e < 8; ++e) own += (f[e] >= 0 && f[e] < c && h[e] != 0) ? 1 : 0;
+    for (int e = 0; e < 8; ++e) own += h[e] != 0 ? 1 : 0;
   }
   part[wave][lane] = own;
   __syncthreads();
   if (threadIdx.x < 64) {
-    int tot = part[0][lane] + part[1][lane] + part[2][lane] + part[3][lane];
+    int tot = 0;
+#pragma unroll
+    for (int i = 0; i < WAVES; ++i) tot += part[i][lane];
     tot = j < t.l ? min(tot, 255) : 0xff;               // leaves past l never match (their table bytes are 0)
     part[0][lane] = tot;
   }
@@ -630,25 +634,23 @@ __global__ __launch_bounds__(256) void tree_compress_kernel(TreeArgs t, Compress
                           (static_cast<unsigned int>(part[0][4 * threadIdx.x + 2]) << 16) | (static_cast<unsigned int>(part[0][4 * threadIdx.x + 3]) << 24);
   __syncthreads();
   const int pieces = static_cast<int>(min<int64_t>(4, (t.ld - 64 * w) / 16));   // 16-byte pieces of a row that exist in this word
+  // (several runs of rows per workgroup, so that fewer workgroups scan H, changed nothing: 0.066 against 0.070 ms)
+  const int64_t r = static_cast<int64_t>(blockIdx.x) * CMP_THREADS + threadIdx.x;
+  if (r >= rows) return;
+  const uint8_t* src = table + r * t.ld + 64 * w;
+  v4u tb[4];
 #pragma unroll
-  for (int i = 0; i < CMP_ROWS; ++i) {
-    const int64_t r = (static_cast<int64_t>(blockIdx.x) * CMP_ROWS + i) * 256 + threadIdx.x;
-    if (r >= rows) continue;
-    const uint8_t* src = table + r * t.ld + 64 * w;
-    v4u tb[4];
+  for (int pc = 0; pc < 4; ++pc) tb[pc] = pc < pieces ? *reinterpret_cast<const v4u*>(src + 16 * pc) : v4u{0u, 0u, 0u, 0u};
+  u64 word = 0ull;
 #pragma unroll
-    for (int pc = 0; pc < 4; ++pc) tb[pc] = pc < pieces ? *reinterpret_cast<const v4u*>(src + 16 * pc) : v4u{0u, 0u, 0u, 0u};
-    u64 word = 0ull;
+  for (int pc = 0; pc < 4; ++pc)
 #pragma unroll
-    for (int pc = 0; pc < 4; ++pc)
-#pragma unroll
-      for (int d = 0; d < 4; ++d) {
-        const unsigned int fl = zero_bytes(tb[pc][d] ^ own_dw[4 * pc + d]) >> 7;     // bit 0, 8, 16, 24: the byte matches
-        const unsigned int nib = (fl & 1u) | ((fl >> 7) & 2u) | ((fl >> 14) & 4u) | ((fl >> 21) & 8u);
-        word |= static_cast<u64>(nib) << (16 * pc + 4 * d);
-      }
-    masks[r * words + w] = word;
-  }
+    for (int d = 0; d < 4; ++d) {
+      const unsigned int fl = zero_bytes(tb[pc][d] ^ own_dw[4 * pc + d]) >> 7;     // bit 0, 8, 16, 24: the byte matches
+      const unsigned int nib = (fl & 1u) | ((fl >> 7) & 2u) | ((fl >> 14) & 4u) | ((fl >> 21) & 8u);
+      word |= static_cast<u64>(nib) << (16 * pc + 4 * d);
+    }
+  masks[r * words + w] = word;
 }
 
 // Nodes that test the fact table's own columns have no table to be folded into: their outcome is
@@ -1580,11 +1582,11 @@ int compress_slices(const TreeArgs& t, const DimSlice* sl, u64* const* masks, in
     ca.rows[k] = sl[k].rows; ca.col_off[k] = sl[k].col_off; ca.cols[k] = sl[k].cols;
     max_rows = std::max<int64_t>(max_rows, sl[k].rows);
   }
-  const int64_t blocks = (max_rows + 256 * CMP_ROWS - 1) / (256 * CMP_ROWS);
+  const int64_t blocks = (max_rows + CMP_THREADS - 1) / CMP_THREADS;
   if (blocks < 1) return LQ_OK;
   if (blocks > 0x7fffffffLL || words > 65535) return fail(LQ_ERR_UNSUPPORTED, "too many rows or leaves for one launch");
   hipLaunchKernelGGL(tree_compress_kernel, dim3(static_cast<unsigned>(blocks), static_cast<unsigned>(words),
-                                                static_cast<unsigned>(n)), dim3(256), 0, s, t, ca, words);
+                                                static_cast<unsigned>(n)), dim3(CMP_THREADS), 0, s, t, ca, words);
   LQ_LAUNCH_CHECK("tree_compress_kernel");
   return LQ_OK;
 }
