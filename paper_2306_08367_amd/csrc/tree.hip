@@ -686,14 +686,30 @@ FactBuf fact_buf(void* p, int32_t n_nodes, int32_t n_leaves) {
 
 // The per-leaf lists: count, running sum (one workgroup), fill.  A leaf's list has the fact-side nodes with a nonzero
 // entry in its column of H, in node order.
-__global__ __launch_bounds__(256) void tree_fact_list_count_kernel(TreeArgs t, int32_t c_f, int32_t* leaf_off) {
-  const int j = blockIdx.x * 256 + threadIdx.x;
-  if (j == 0) leaf_off[0] = 0;
-  if (j >= t.l) return;
+// Count and fill: a workgroup takes 64 leaves (lane = leaf) and its 16 wavefronts take consecutive runs of the nodes,
+// so that a list stays in node order: a wavefront's entries follow those of the wavefronts before it.
+constexpr int FL_WAVES = 16;
+__device__ __forceinline__ int fact_list_count_run(const TreeArgs& t, int32_t c_f, int j, int q_lo, int q_hi) {
   int count = 0;
-  for (int q = 0; q < t.p; ++q)
-    count += (static_cast<unsigned int>(t.feature[q]) < static_cast<unsigned int>(c_f) && t.H[static_cast<int64_t>(q) * t.l + j] != 0) ? 1 : 0;
-  leaf_off[j + 1] = count;
+  for (int q = q_lo; q < q_hi; ++q)
+    if (static_cast<unsigned int>(t.feature[q]) < static_cast<unsigned int>(c_f))       // (the same for every lane)
+      count += (j < t.l && t.H[static_cast<int64_t>(q) * t.l + j] != 0) ? 1 : 0;
+  return count;
+}
+__global__ __launch_bounds__(64 * FL_WAVES) void tree_fact_list_count_kernel(TreeArgs t, int32_t c_f, int32_t* leaf_off) {
+  __shared__ int part[FL_WAVES][64];
+  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+  const int j = blockIdx.x * 64 + lane;
+  const int run = (t.p + FL_WAVES - 1) / FL_WAVES;
+  part[wave][lane] = fact_list_count_run(t, c_f, j, min(t.p, wave * run), min(t.p, (wave + 1) * run));
+  __syncthreads();
+  if (wave == 0) {
+    int count = 0;
+#pragma unroll
+    for (int w = 0; w < FL_WAVES; ++w) count += part[w][lane];
+    if (j == 0) leaf_off[0] = 0;
+    if (j < t.l) leaf_off[j + 1] = count;
+  }
 }
 __global__ __launch_bounds__(1024) void tree_fact_list_scan_kernel(int32_t* leaf_off, int32_t l, int32_t* cnt, int64_t capacity) {
   __shared__ int part[1024];
@@ -722,12 +738,26 @@ __global__ __launch_bounds__(1024) void tree_fact_list_scan_kernel(int32_t* leaf
     cnt[1] = carry <= capacity ? 1 : 0;
   }
 }
-__global__ __launch_bounds__(256) void tree_fact_list_fill_kernel(TreeArgs t, int32_t c_f, const int32_t* cnt, const int32_t* leaf_off,
-                                                                  uint4* ent) {
-  const int j = blockIdx.x * 256 + threadIdx.x;
-  if (j >= t.l || cnt[1] == 0) return;
-  int at = leaf_off[j], pos = 0;                 // pos: fact-side nodes before node q = its place in the packed list
-  for (int q = 0; q < t.p; ++q) {
+__global__ __launch_bounds__(64 * FL_WAVES) void tree_fact_list_fill_kernel(TreeArgs t, int32_t c_f, const int32_t* cnt,
+                                                                            const int32_t* leaf_off, uint4* ent) {
+  __shared__ int part[FL_WAVES][64];      // entries of the leaf in the wavefront's run of nodes
+  __shared__ int before[FL_WAVES];        // fact-side nodes before the wavefront's run (their place in the packed list)
+  if (cnt[1] == 0) return;
+  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+  const int j = blockIdx.x * 64 + lane;
+  const int run = (t.p + FL_WAVES - 1) / FL_WAVES;
+  const int q_lo = min(t.p, wave * run), q_hi = min(t.p, (wave + 1) * run);
+  part[wave][lane] = fact_list_count_run(t, c_f, j, q_lo, q_hi);
+  if (lane == 0) {
+    int nodes = 0;
+    for (int q = q_lo; q < q_hi; ++q) nodes += static_cast<unsigned int>(t.feature[q]) < static_cast<unsigned int>(c_f) ? 1 : 0;
+    before[wave] = nodes;
+  }
+  __syncthreads();
+  if (j >= t.l) return;
+  int at = leaf_off[j], pos = 0;
+  for (int w = 0; w < wave; ++w) { at += part[w][lane]; pos += before[w]; }
+  for (int q = q_lo; q < q_hi; ++q) {
     const int f = t.feature[q];
     if (static_cast<unsigned int>(f) >= static_cast<unsigned int>(c_f)) continue;
     const int h = t.H[static_cast<int64_t>(q) * t.l + j];
@@ -1867,13 +1897,13 @@ int lq_tree_fact_masks(int32_t c_f, const lq_tree* tree, void* fact_masks, void*
   const FactBuf fb = fact_buf(fact_masks, t.p, t.l);
   hipLaunchKernelGGL(tree_fact_masks_kernel, dim3(static_cast<unsigned>((t.p + 15) / 16)), dim3(256), 0, s, t, c_f, words, fb);
   LQ_LAUNCH_CHECK("tree_fact_masks_kernel");
-  const unsigned leaf_blocks = static_cast<unsigned>((t.l + 255) / 256);
-  hipLaunchKernelGGL(tree_fact_list_count_kernel, dim3(leaf_blocks), dim3(256), 0, s, t, c_f, fb.leaf_off);
+  const unsigned leaf_blocks = static_cast<unsigned>((t.l + 63) / 64);
+  hipLaunchKernelGGL(tree_fact_list_count_kernel, dim3(leaf_blocks), dim3(64 * FL_WAVES), 0, s, t, c_f, fb.leaf_off);
   LQ_LAUNCH_CHECK("tree_fact_list_count_kernel");
   hipLaunchKernelGGL(tree_fact_list_scan_kernel, dim3(1), dim3(1024), 0, s, fb.leaf_off, t.l, fb.cnt,
                      static_cast<int64_t>(FACT_LIST_PER_LEAF) * t.l);
   LQ_LAUNCH_CHECK("tree_fact_list_scan_kernel");
-  hipLaunchKernelGGL(tree_fact_list_fill_kernel, dim3(leaf_blocks), dim3(256), 0, s, t, c_f, fb.cnt, fb.leaf_off, fb.leaf_ent);
+  hipLaunchKernelGGL(tree_fact_list_fill_kernel, dim3(leaf_blocks), dim3(64 * FL_WAVES), 0, s, t, c_f, fb.cnt, fb.leaf_off, fb.leaf_ent);
   LQ_LAUNCH_CHECK("tree_fact_list_fill_kernel");
   return LQ_OK;
 }
