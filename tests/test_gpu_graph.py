@@ -115,3 +115,69 @@ def test_raw_keys_to_ordered_aggregate_replays_match_eager(lq):
             assert torch.equal(got, want)
         call()
         torch.cuda.synchronize()
+
+
+@pytest.mark.parametrize("leaves", [300, 257], ids=["rows_written_whole", "rows_cleared_then_set"])
+def test_tree_mask_join_with_fact_columns_replays_match_eager(lq, leaves):
+    """Leaf numbers and one-hot rows of a tree that tests fact columns: the call clears the one-hot rows with a
+    fill kernel where it sets them byte by byte (257 leaves), and launches both forms of the fact side."""
+    c_f = 5
+    w = to_dev(WL.make_predict("graph_tree_fact", 70_001, c_f, (300, 200), (6, 6), (1,), seed=WL.SEED0 + 910))
+    tree = WL.make_tree(c_f + 12, leaves, WL.SEED0 + 911)
+    f, t, H = tree.feature.cuda(), tree.threshold.cuda(), tree.H.cuda()
+    tables, target = lq.lq_tree_project_dims(w.dims, c_f, f, t, H)
+    masks = lq.lq_tree_compress_tables(w.dims, tables, f, t, H, c_f=c_f)
+    fmask = lq.lq_tree_fact_masks(c_f, f, t, H)
+    torch.cuda.synchronize()
+    out = {}
+
+    def call():
+        out["leaf"], out["onehot"] = lq.lq_fused_join_tree_masks(w.fks, masks, f, t, H, want_onehot=True, X=w.X,
+                                                                  fact_masks=fmask)
+    call()
+    torch.cuda.synchronize()
+    ref_leaf, ref_oh = out["leaf"].clone(), out["onehot"].clone()
+    assert int(ref_oh.sum()) == w.n
+    graph = _capture(call)                      # (the outputs of the captured call live in the graph's memory pool)
+    g_leaf, g_oh = out["leaf"], out["onehot"]
+    for _ in range(4):
+        g_leaf.fill_(-7); g_oh.fill_(9)
+        torch.cuda.synchronize()
+        graph.replay()
+        torch.cuda.synchronize()
+        assert torch.equal(g_leaf, ref_leaf) and torch.equal(g_oh, ref_oh)
+        call()                                  # eager work between replays
+        torch.cuda.synchronize()
+
+
+def test_bucketed_group_by_with_a_fact_mask_replays_match_eager(lq):
+    """More groups than LDS accumulators, a fact mask, the bucketed form: outputs and bucket counters are cleared by
+    a kernel of the call."""
+    import numpy as np
+    r = np.random.default_rng(920)
+    n, rows, card = 400_003, (300, 280, 5_000), (250, 240, 1)
+    fks = [torch.from_numpy(r.integers(0, a, size=n).astype(np.int32)).cuda() for a in rows]
+    codes = [torch.from_numpy(r.integers(0, c, size=a).astype(np.int32)).cuda() if c > 1 else None for a, c in zip(rows, card)]
+    masks = [None, None, torch.from_numpy((r.random(rows[2]) < 0.7).astype(np.uint8)).cuda()]
+    meas = [torch.from_numpy(r.integers(-1000, 100_000, size=n).astype(np.int32)).cuda()]
+    fm = torch.from_numpy((r.random(n) < 0.8).astype(np.uint8)).cuda()
+    G = 250 * 240
+    ws = torch.empty(lq.lq_groupby_bucket_workspace_bytes(n, rows, card, 1), dtype=torch.uint8, device="cuda")
+    sums = torch.empty((1, G), dtype=torch.int64, device="cuda")
+    counts = torch.empty((G,), dtype=torch.int64, device="cuda")
+
+    def call():
+        lq.lq_masked_groupby_sum(fks, rows, masks, codes, card, fm, meas, sums=sums, counts=counts, ws=ws)
+    call()
+    torch.cuda.synchronize()
+    ref_s, ref_c = sums.clone(), counts.clone()
+    assert 0 < int(ref_c.sum()) < n
+    graph = _capture(call)
+    for _ in range(4):
+        sums.fill_(-1); counts.fill_(-1)
+        torch.cuda.synchronize()
+        graph.replay()
+        torch.cuda.synchronize()
+        assert torch.equal(sums, ref_s) and torch.equal(counts, ref_c)
+        call()
+        torch.cuda.synchronize()
