@@ -169,3 +169,39 @@ def test_literal_per_dimension_predicate_double_counts_with_negative_thresholds(
             assert (literal != R).any()
         else:
             np.testing.assert_array_equal(literal, R)
+
+
+def test_path_matrices_that_are_no_trees_by_brute_force():
+    """Eq. 2 for any H: column j of the result is 1 exactly when every node with a +1 in the column tests true and
+    every node with a -1 tests false on the joined tuple, whatever the other columns say.  Several columns, or none,
+    may then hold a 1; `leaf` is the first of them, -1 for none.  Checked tuple by tuple with plain Python loops on
+    path matrices in which each column wants a few random nodes."""
+    for seed, p, l, per, c_f in ((21, 6, 9, 2, 0), (22, 9, 20, 3, 2), (23, 4, 5, 1, 1), (24, 12, 30, 4, 0)):
+        X, dims, fks = _star(40 + seed, n=150, c_f=c_f)
+        kw = c_f + 9
+        r = np.random.default_rng(seed)
+        feature = r.integers(0, kw, size=p).astype(np.int32)
+        thr = r.normal(0.0, 0.7, size=p)
+        Hm = np.zeros((p, l), dtype=np.int8)
+        for j in range(l):
+            Hm[r.choice(p, size=per, replace=False), j] = r.choice([-1, 1], size=per)
+        R, onehot, leaf = O.tree_predict(X, dims, fks, feature, thr, Hm)
+        T = O.materialize(X, dims, fks)
+        several = none = 0
+        for i in range(T.shape[0]):
+            hits = []
+            for j in range(l):
+                ok = True
+                for q in range(p):
+                    if Hm[q, j] == 0:
+                        continue
+                    test = T[i][int(feature[q])] > thr[q]
+                    if test != (Hm[q, j] > 0):
+                        ok = False
+                if ok:
+                    hits.append(j)
+            assert onehot[i].tolist() == [1 if j in hits else 0 for j in range(l)]
+            assert leaf[i] == (hits[0] if hits else -1)
+            several += len(hits) > 1
+            none += len(hits) == 0
+        assert several > 0 and (none > 0 or per < 3)
