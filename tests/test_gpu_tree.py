@@ -60,6 +60,7 @@ CASES = [
     ("fact_columns_4_wide_1024", 1_203, 4, (150, 90), (20, 20), 1_024),
     ("fact_columns_12_wide_384", 1_777, 12, (64, 32, 16), (5, 5, 5), 384),
     ("fact_columns_only_wide_256", 2_049, 7, (), (), 256),
+    ("fact_columns_only_1100_leaves", 1_501, 3, (), (), 1_100),      # more fact-side nodes than the byte-table join lists
     ("one_row", 1, 0, (5,), (3,), 4),
 ]
 
