@@ -296,11 +296,13 @@ def _n_of(X, fks) -> int:
 def lq_project_dims(dims: Sequence[torch.Tensor], W0: torch.Tensor, c_f: int,
                     P: Optional[List[torch.Tensor]] = None, p_dtype: Optional[torch.dtype] = None,
                     stream=None) -> List[torch.Tensor]:
-    """P_k = D_k times its rows of W0 (pre-fusion stage).  Allocates P unless given."""
+    """P_k = D_k times its rows of W0 (pre-fusion stage).  Allocates P unless given: in the model's element type
+    unless p_dtype says otherwise (the specialised kernels of the join stage take tables of the model's type;
+    fp32 tables under a bf16 model run on the shape-agnostic kernel, several times slower)."""
     if P is None:
         # rows start 16 bytes apart at the least (the stride is padded to 4 floats / 8 bf16 values): the fast kernels of
         # the join stage then take any hidden width, the padding is never read as data
-        pd = p_dtype or torch.float32
+        pd = p_dtype or W0.dtype
         per16 = 4 if pd == torch.float32 else 8
         l1 = int(W0.shape[1])
         ld = (l1 + per16 - 1) // per16 * per16

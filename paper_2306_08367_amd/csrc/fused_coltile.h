@@ -58,26 +58,6 @@ __device__ __forceinline__ void ct_issue(const T* const (&pb)[K], const int64_t 
 
 // T: element type of the model, the tables and the output.  K dimensions, CFC groups of four fact
 // columns, NL layers (1 or 2), L2P outputs of the second layer rounded up to 1, 4 or 16.
-// Sums of y[0..15] over the 64 lanes of a wavefront, scattered: lane L ends with the total of output L & 15.
-// Each step halves the outputs a lane still carries (it keeps the half its own lane bit selects and adds what its
-// partner sends of that half), so sixteen outputs cost 8 + 4 + 2 + 1 exchanges inside the rows of 16 lanes and two
-// more across them, instead of six per output.  The mirror steps come first: they also flip the lower lane bits, which
-// is harmless only while the lower bits have not selected anything yet.
-__device__ __forceinline__ float reduce_scatter16(const float (&y)[16], int lane) {
-  const bool b3 = (lane & 8) != 0, b2 = (lane & 4) != 0, b1 = (lane & 2) != 0, b0 = (lane & 1) != 0;
-  float a8[8], a4[4], a2[2];
-#pragma unroll
-  for (int i = 0; i < 8; ++i) a8[i] = (b3 ? y[8 + i] : y[i]) + dppw<0x140>(b3 ? y[i] : y[8 + i]);          // row_mirror: i <-> 15 - i
-#pragma unroll
-  for (int i = 0; i < 4; ++i) a4[i] = (b2 ? a8[4 + i] : a8[i]) + dppw<0x141>(b2 ? a8[i] : a8[4 + i]);      // row_half_mirror: i <-> 7 - i
-#pragma unroll
-  for (int i = 0; i < 2; ++i) a2[i] = (b1 ? a4[2 + i] : a4[i]) + dppw<0x4E>(b1 ? a4[i] : a4[2 + i]);       // quad_perm [2,3,0,1]
-  float r = (b0 ? a2[1] : a2[0]) + dppw<0xB1>(b0 ? a2[0] : a2[1]);                                         // quad_perm [1,0,3,2]
-  r += __shfl_xor(r, 16, 64);
-  r += __shfl_xor(r, 32, 64);
-  return r;
-}
-
 template <typename T, int K, int CFC, int NL, int L2P>
 __global__ __launch_bounds__(CT_THREADS) void fused_coltile_kernel(PredictArgs a, int tiles, int RB) {
   constexpr int COLS = Piece<T>::COLS;
@@ -200,7 +180,7 @@ __global__ __launch_bounds__(CT_THREADS) void fused_coltile_kernel(PredictArgs a
             }
             if constexpr (L2P == 16) {
               // (one sum per output, six cross-lane steps each, made wide second layers arithmetic-bound)
-              const float tot = reduce_scatter16(y, lane);
+              const float tot = group_reduce_scatter16<64>(y, lane);
               if (lane < 16) atomicAdd(&ct_red[(w * RB + t) * L2P + lane], tot);     // this wavefront's rows only
             } else {
 #pragma unroll

@@ -72,6 +72,29 @@ template <int LPR> __device__ __forceinline__ float group_sum(float y) {
   if (LPR >= 64) y += __shfl_xor(y, 32, 64);
   return y;
 }
+// Sums of y[0..15] over the 16 lanes of a row of the cross-lane network, scattered: lane L ends with the total of
+// output L & 15.  Each step halves the outputs a lane still carries (it keeps the half its own lane bit selects and adds
+// what its partner sends of that half): 8 + 4 + 2 + 1 exchanges instead of four per output.  The mirror steps come
+// first: they also flip the lower lane bits, which is harmless only while those have not selected anything yet.
+__device__ __forceinline__ float reduce_scatter16_row(const float (&y)[16], int lane) {
+  const bool b3 = (lane & 8) != 0, b2 = (lane & 4) != 0, b1 = (lane & 2) != 0, b0 = (lane & 1) != 0;
+  float a8[8], a4[4], a2[2];
+#pragma unroll
+  for (int i = 0; i < 8; ++i) a8[i] = (b3 ? y[8 + i] : y[i]) + dppw<0x140>(b3 ? y[i] : y[8 + i]);          // row_mirror: i <-> 15 - i
+#pragma unroll
+  for (int i = 0; i < 4; ++i) a4[i] = (b2 ? a8[4 + i] : a8[i]) + dppw<0x141>(b2 ? a8[i] : a8[4 + i]);      // row_half_mirror: i <-> 7 - i
+#pragma unroll
+  for (int i = 0; i < 2; ++i) a2[i] = (b1 ? a4[2 + i] : a4[i]) + dppw<0x4E>(b1 ? a4[i] : a4[2 + i]);       // quad_perm [2,3,0,1]
+  return (b0 ? a2[1] : a2[0]) + dppw<0xB1>(b0 ? a2[0] : a2[1]);                                            // quad_perm [1,0,3,2]
+}
+// The scattered form over a group of LPR = 16, 32 or 64 lanes: every lane L of the group ends with output L & 15.
+template <int LPR> __device__ __forceinline__ float group_reduce_scatter16(const float (&y)[16], int lane) {
+  static_assert(LPR >= 16, "a group of at least one row of 16 lanes");
+  float r = reduce_scatter16_row(y, lane);
+  if (LPR >= 32) r += __shfl_xor(r, 16, 64);
+  if (LPR >= 64) r += __shfl_xor(r, 32, 64);
+  return r;
+}
 // Value that lane (group base + t) holds, for every lane of the group.
 template <int LPR> __device__ __forceinline__ int from_lane(int v, int t, int group_base) {
   if constexpr (LPR == 64) return __builtin_amdgcn_readlane(v, t);
