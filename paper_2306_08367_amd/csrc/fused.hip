@@ -364,7 +364,7 @@ int launch_fused(const PredictArgs& a, hipStream_t s) {
   if (rc >= 0) return rc;
   rc = try_fused_bf16(a, s);
   if (rc >= 0) return rc;
-  rc = try_fused_deep_bf16(a, s);     // bf16: three to eight layers, or a second layer of 17..256 outputs
+  rc = try_fused_deep_bf16(a, s);     // bf16: three to eight layers, a second layer of 17..256 outputs, or what the kernel above left
   if (rc >= 0) return rc;
   rc = try_fused_lds(a, s);           // linear models with 1 / 2 / 4 outputs whose small projected tables fit LDS
   if (rc >= 0) return rc;

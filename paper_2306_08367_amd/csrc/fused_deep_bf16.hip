@@ -30,6 +30,7 @@ constexpr int DBF_THREADS = 256;
 struct DeepBfLds {
   int w[LQ_MAX_LAYERS - 1];       // layer j + 1: [TOUT][chunks of 32 inputs][64 lanes] x 16 bytes
   int b[LQ_MAX_LAYERS - 1];       // fp32 [16 TOUT]
+  int wf;                         // rows of W_0 that belong to the fact columns: bf16 [c_f][32 KB], zeros past l_1
   int total;
 };
 
@@ -132,13 +133,19 @@ __global__ __launch_bounds__(DBF_THREADS, (TH <= 8 ? 2 : 1)) void fused_deep_bf1
   for (int layer = 2; layer < nl; ++layer)
     stage_weights(a, layer, false, M, (layer == nl - 1 && a.wout[nl - 1] <= 16) ? 1 : TH, reinterpret_cast<v4u*>(smem + L.w[layer - 1]),
                   reinterpret_cast<float*>(smem + L.b[layer - 1]));
+  const int l1 = a.wout[0];
+  // (the fact term's weights were read from memory in every pass, through the address path the gathers need:
+  // 256 -> 17 with four fact columns 0.41 ms per 1e6 rows against 0.19 without any)
+  for (int i = threadIdx.x; i < a.c_f * 32 * KB; i += DBF_THREADS) {
+    const int q = i / (32 * KB), u = i - q * (32 * KB);
+    reinterpret_cast<bf16_t*>(smem + L.wf)[i] = u < l1 ? static_cast<const bf16_t*>(a.W[0])[static_cast<int64_t>(q) * a.ldw[0] + u] : bf16_t{0};
+  }
   __syncthreads();
 
   const int64_t wave = static_cast<int64_t>(blockIdx.x) * (DBF_THREADS / 64) + (threadIdx.x >> 6);
   const int64_t nwaves = static_cast<int64_t>(gridDim.x) * (DBF_THREADS / 64);
   const int64_t npass = (a.n + 15) / 16;
-  const int l_out = a.wout[nl - 1], l1 = a.wout[0];
-  const bool w0_vec = (reinterpret_cast<uintptr_t>(a.W[0]) & 15) == 0 && a.ldw[0] % 8 == 0;
+  const int l_out = a.wout[nl - 1];
 
   // Gathers: the row of table k + 1 is requested before the row of table k is added up, so one row is
   // always in flight (lanes whose units lie past l_1 re-read the first piece of the row and add
@@ -188,26 +195,17 @@ __global__ __launch_bounds__(DBF_THREADS, (TH <= 8 ? 2 : 1)) void fused_deep_bf1
     }
     if (a.c_f > 0) {
       const bf16_t* xr = static_cast<const bf16_t*>(a.X) + rr * a.ldx;
-      const bf16_t* W0 = static_cast<const bf16_t*>(a.W[0]) + 8 * g;
+      const bf16_t* wf = reinterpret_cast<const bf16_t*>(smem + L.wf) + 8 * g;
       for (int q = 0; q < a.c_f; ++q) {
         const float x = bf16_to_f32(xr[q]);
-        const bf16_t* wq = W0 + static_cast<int64_t>(q) * a.ldw[0];
 #pragma unroll
         for (int kb = 0; kb < KB; ++kb) {
-          float wv[8];
-          if (32 * kb + 8 * g >= l1) {
+          const v4u t = *reinterpret_cast<const v4u*>(wf + (q * KB + kb) * 32);     // (zeros where the units lie past l_1)
 #pragma unroll
-            for (int e = 0; e < 8; ++e) wv[e] = 0.f;
-          } else if (w0_vec) {
-            const v4u t = *reinterpret_cast<const v4u*>(wq + 32 * kb);
-#pragma unroll
-            for (int e = 0; e < 4; ++e) { wv[2 * e] = __uint_as_float(t[e] << 16); wv[2 * e + 1] = __uint_as_float(t[e] & 0xffff0000u); }
-          } else {
-#pragma unroll
-            for (int e = 0; e < 8; ++e) wv[e] = bf16_to_f32(wq[32 * kb + e]);
+          for (int e = 0; e < 4; ++e) {
+            acc[kb][2 * e] = fmaf(x, __uint_as_float(t[e] << 16), acc[kb][2 * e]);
+            acc[kb][2 * e + 1] = fmaf(x, __uint_as_float(t[e] & 0xffff0000u), acc[kb][2 * e + 1]);
           }
-#pragma unroll
-          for (int e = 0; e < 8; ++e) acc[kb][e] = fmaf(x, wv[e], acc[kb][e]);
         }
       }
     }
@@ -280,7 +278,8 @@ int try_fused_deep_bf16(const PredictArgs& a, hipStream_t s) {
     if (a.prows[k] * (a.ldp[k] / 8) > 0xffffffffLL) return -1;     // the kernel counts 16-byte pieces of a table in 32 bits
   }
   const int l_out = a.wout[NL - 1];
-  if (NL == 2 && l_out <= 16) return -1;              // the one-tile bf16 kernel covers these
+  // (two layers with up to 16 outputs: the one-tile bf16 kernel, tried before this one, takes first layers of 32, 64, 128
+  // and 256 columns without fact columns; other widths that are multiples of 8, and stars with fact columns, end up here)
   int wide = 0;
   for (int j = 1; j < NL; ++j)
     if (j < NL - 1 || NL == 2 || l_out > 16) wide = std::max(wide, a.wout[j]);   // (an output layer of <= 16 is its own tile)
@@ -296,6 +295,7 @@ int try_fused_deep_bf16(const PredictArgs& a, hipStream_t s) {
     L.w[j - 1] = off; off += tout * chunks * 64 * 16;
     L.b[j - 1] = off; off += 16 * tout * 4;
   }
+  L.wf = off; off += a.c_f * KB * 64;
   L.total = off;
   const size_t lds = static_cast<size_t>(off);
   if (lds > 150 * 1024) return -1;
