@@ -332,6 +332,13 @@ BF16_MFMA_SHAPES = [
     ("bf16_linear_128_k4_cf8", 1_301, (50, 60, 70, 80), (6, 6, 6, 6), (128,), False, 8),
     ("bf16_96_1_k2", 2_049, (100, 200), (16, 16), (96, 1), True, 4),
     ("bf16_linear_40", 1_111, (100, 200), (16, 16), (40,), False),
+    # 9 to 16 fact columns on the one-tile kernel (their rows of W_0 staged in LDS); two layers with 5 to 16 outputs and
+    # fact columns, or a first layer of another width than 32 / 64 / 128 / 256, on the kernel for deeper models
+    ("bf16_linear_256_cf12", 2_003, (64, 80, 96), (24, 24, 24), (256,), True, 12),
+    ("bf16_64_3_cf12", 3_001, (100, 200), (16, 16), (64, 3), True, 12),
+    ("bf16_128_9_cf12", 1_999, (100, 200), (16, 16), (128, 9), False, 12),
+    ("bf16_200_16", 2_311, (100, 200, 50), (16, 16, 8), (200, 16), True),
+    ("bf16_72_9_cf5", 1_025, (90, 70), (12, 12), (72, 9), True, 5),
     # deeper / wider bf16 models: later layers chained on the matrix cores
     ("bf16_deep_256_64_16", 3_001, (500, 700, 300, 900), (64, 64, 32, 48), (256, 64, 16), True),
     ("bf16_deep_64_64_1_cf4", 4_099, (1000, 5000, 200), (32, 32, 32), (64, 64, 1), True, 4),
