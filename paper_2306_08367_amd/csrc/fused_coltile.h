@@ -252,7 +252,12 @@ int ct_pick_layers(const PredictArgs& a, hipStream_t s) {
   const int l2 = a.wout[1];
   if (l2 > MAXL2) return -1;
   if constexpr (MAXL2 > 4) {
-    if (l2 > 4) return ct_launch<T, K, CFC, 2, 16>(a, s);
+    if (l2 > 4) {
+      // (bf16, eight columns per lane: with more than four fact columns the weights of sixteen outputs no longer fit
+      // the registers, 32 to 160 bytes per lane would spill; such models take the layered form)
+      if constexpr (sizeof(T) == 2 && CFC > 1) return -1;
+      else return ct_launch<T, K, CFC, 2, 16>(a, s);
+    }
   }
   if (l2 == 1) return ct_launch<T, K, CFC, 2, 1>(a, s);
   return ct_launch<T, K, CFC, 2, 4>(a, s);

@@ -99,7 +99,7 @@ WIDE_BF16 = [
     ("bf16_l520_linear", 4_099, 8, (300, 200), 64, (520,), True),
     ("bf16_l1032_mlp_2_65_rows", 65, 3, (30, 20), 32, (1032, 2), True),
     ("bf16_l4096_linear_k1", 1_025, 0, (100,), 16, (4096,), False),
-    ("bf16_l1024_mlp_16", 2_049, 0, (100, 200), 32, (1024, 16), True),      # general kernels
+    ("bf16_l1024_mlp_16", 2_049, 0, (100, 200), 32, (1024, 16), True),
 ]
 
 
